@@ -1,0 +1,147 @@
+"""CPU oracle for the bit-packed merged-expert MoE FFN.  TEST INFRASTRUCTURE ONLY.
+
+Thin ctypes access to ``puzzle_oracle.c`` (plain C, fp64).  Nothing in the product
+package may import this module; only tests, the smoke check and the benchmark's
+CPU-baseline leg do.  It shares no code with the HIP library.
+
+Paper passages: Sec. 3.3.2 (packed word, exponent rule), Algorithm 1 (decode),
+Eq. 6 (reconstruction).
+"""
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "puzzle_oracle.c")
+_LIB = os.path.join(_HERE, "liboracle.so")
+_lib = None
+
+
+def build(force=False):
+    """Compile the oracle with gcc (no fast-math: fp64 sums stay in source order)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(["gcc", "-O2", "-fopenmp", "-shared", "-fPIC", "-Wall", "-Wextra",
+                               "-o", _LIB, _SRC, "-lm"])
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        lib = ctypes.CDLL(build())
+        u16p = ctypes.POINTER(ctypes.c_uint16)
+        u8p = ctypes.POINTER(ctypes.c_uint8)
+        lib.orc_bf16_to_double.restype = ctypes.c_double
+        lib.orc_bf16_to_double.argtypes = [ctypes.c_uint16]
+        lib.orc_bf16_from_double.restype = ctypes.c_uint16
+        lib.orc_bf16_from_double.argtypes = [ctypes.c_double]
+        lib.orc_pack.restype = ctypes.c_int64
+        lib.orc_pack.argtypes = [u16p, u8p, u8p, u8p, u8p, ctypes.c_int64, u16p]
+        lib.orc_unpack.restype = None
+        lib.orc_unpack.argtypes = [u16p, ctypes.c_int, ctypes.c_int64, u16p]
+        lib.orc_moe_ffn.restype = ctypes.c_int
+        _lib = lib
+    return _lib
+
+
+def _u16(a):
+    a = np.ascontiguousarray(a)
+    assert a.dtype == np.uint16, a.dtype
+    return a
+
+
+def _u8(a):
+    a = np.ascontiguousarray(a)
+    assert a.dtype == np.uint8, a.dtype
+    return a
+
+
+def _ptr(a, ctype):
+    return a.ctypes.data_as(ctypes.POINTER(ctype))
+
+
+def bf16_to_double(bits):
+    return _load().orc_bf16_to_double(int(bits))
+
+
+def bf16_from_double(v):
+    return _load().orc_bf16_from_double(float(v))
+
+
+def pack(merged, mask0, mask1, sign0, sign1):
+    """Sec. 3.3.2 pack.  Returns (packed uint16 array of merged's shape, n_out_of_range)."""
+    merged = _u16(merged)
+    m0, m1, s0, s1 = (_u8(a) for a in (mask0, mask1, sign0, sign1))
+    for a in (m0, m1, s0, s1):
+        assert a.shape == merged.shape
+    out = np.empty_like(merged)
+    bad = _load().orc_pack(_ptr(merged, ctypes.c_uint16), _ptr(m0, ctypes.c_uint8),
+                           _ptr(m1, ctypes.c_uint8), _ptr(s0, ctypes.c_uint8),
+                           _ptr(s1, ctypes.c_uint8), merged.size, _ptr(out, ctypes.c_uint16))
+    return out, int(bad)
+
+
+def unpack(packed, expert_pos):
+    """Algorithm 1 on every element.  Returns bf16 bit patterns (uint16)."""
+    packed = _u16(packed)
+    assert expert_pos in (0, 1)
+    out = np.empty_like(packed)
+    _load().orc_unpack(_ptr(packed, ctypes.c_uint16), int(expert_pos), packed.size,
+                       _ptr(out, ctypes.c_uint16))
+    return out
+
+
+def moe_ffn(x, ids, w, expert_pair, expert_pos, gate, up, down,
+            shared=(), stage_h_bf16=False):
+    """Routed SwiGLU FFN over Eq. 6-decoded experts, fp64.
+
+    x: [T,d] bf16 bits (uint16); ids: [T,k] int32; w: [T,k] float32;
+    gate/up: per pair, packed uint16 [f,d] in logical order; down: per pair [d,f];
+    shared: sequence of (gate [fs,d], up [fs,d], down [d,fs]) dense bf16 bits.
+    Returns (y_f64 [T,d], y_bf16_bits [T,d]).
+    """
+    lib = _load()
+    x = _u16(x)
+    T, d = x.shape
+    ids = np.ascontiguousarray(ids, dtype=np.int32)
+    w = np.ascontiguousarray(w, dtype=np.float32)
+    k = ids.shape[1] if ids.ndim == 2 else 0
+    assert ids.shape == (T, k) and w.shape == (T, k)
+    expert_pair = np.ascontiguousarray(expert_pair, dtype=np.int32)
+    expert_pos = np.ascontiguousarray(expert_pos, dtype=np.uint8)
+    E = expert_pair.size
+    gate = [_u16(a) for a in gate]
+    up = [_u16(a) for a in up]
+    down = [_u16(a) for a in down]
+    P = len(gate)
+    f = gate[0].shape[0] if P else 0
+    for a, b, c in zip(gate, up, down):
+        assert a.shape == (f, d) and b.shape == (f, d) and c.shape == (d, f)
+    sg = [_u16(s[0]) for s in shared]
+    su = [_u16(s[1]) for s in shared]
+    sd = [_u16(s[2]) for s in shared]
+    sf = np.array([a.shape[0] for a in sg], dtype=np.int32)
+    for a, b, c in zip(sg, su, sd):
+        assert a.shape[1] == d and b.shape == a.shape and c.shape == (d, a.shape[0])
+
+    def ptr_array(arrs):
+        arr_t = ctypes.c_void_p * max(len(arrs), 1)
+        return arr_t(*[a.ctypes.data for a in arrs])
+
+    y64 = np.zeros((T, d), dtype=np.float64)
+    ybf = np.zeros((T, d), dtype=np.uint16)
+    rc = lib.orc_moe_ffn(
+        ctypes.c_int(T), ctypes.c_int(k), ctypes.c_int(E), ctypes.c_int(d), ctypes.c_int(f),
+        ctypes.c_void_p(x.ctypes.data), ctypes.c_void_p(ids.ctypes.data),
+        ctypes.c_void_p(w.ctypes.data), ctypes.c_void_p(expert_pair.ctypes.data),
+        ctypes.c_void_p(expert_pos.ctypes.data),
+        ptr_array(gate), ptr_array(up), ptr_array(down),
+        ctypes.c_int(len(sg)), ctypes.c_void_p(sf.ctypes.data),
+        ptr_array(sg), ptr_array(su), ptr_array(sd),
+        ctypes.c_int(1 if stage_h_bf16 else 0),
+        ctypes.c_void_p(y64.ctypes.data), ctypes.c_void_p(ybf.ctypes.data))
+    if rc != 0:
+        raise ValueError("oracle moe_ffn: expert id out of range or allocation failure")
+    return y64, ybf

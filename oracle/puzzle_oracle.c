@@ -1,0 +1,225 @@
+/*
+ * CPU oracle for the bit-packed merged-expert MoE FFN (PuzzleMoE inference path).
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain definition that the
+ * HIP library is checked against.  It shares no code, header, table or helper
+ * with the GPU path, and nothing in the product path may call it.
+ *
+ * What follows the paper, and where:
+ *   - packed 16-bit word and exponent rule ... Sec. 3.3.2 "System Co-design"
+ *   - orc_unpack .............................. Algorithm 1 (weight decoding)
+ *   - reconstruction identity ................. Eq. 6
+ *   - orc_moe_ffn ............................. Eq. 6 weights inside an ordinary
+ *     routed SwiGLU expert FFN ("other modules unchanged", Sec. 4.1); the FFN
+ *     itself (gate/up/down, silu, weighted top-k sum, shared experts added with
+ *     weight 1) is not in the paper and follows the standard definition.
+ *
+ * Readings where the paper is silent (all listed in the design notes):
+ *   - an exponent below 112 is raised to 112 and the mantissa is kept;
+ *   - an exactly-zero magnitude is stored with both mask bits cleared, so
+ *     that Eq. 6 still gives 0;
+ *   - an exponent above 143 (this includes Inf/NaN) cannot be stored in five
+ *     bits: it is counted as out of range and stored as a fully masked word;
+ *   - a masked-out element decodes to +0 (Algorithm 1 assigns 0 before any
+ *     sign handling);
+ *   - sign bits are stored as given even where the mask is 0; the sign bit of
+ *     the merged input is ignored (Eq. 5 makes W_merged non-negative).
+ *
+ * Parity pins (tests, CPU only): exhaustive Algorithm-1 truth table against
+ * the closed form (-1)^s m 2^(e5-15)(1+mant/128); pack->unpack against Eq. 6
+ * over every non-negative bf16 and all 16 flag combinations; a hand-derived
+ * golden example; the FFN against an independent dense numpy evaluation and
+ * against special cases that reduce to a textbook dense SwiGLU FFN.
+ * Unpinned (paper silent, no second source): the three readings above that
+ * concern exponents < 112, zero, and exponents > 143.
+ *
+ * Arithmetic: integer for pack/unpack; fp64 everywhere in the FFN; a single
+ * round-to-nearest-even to bf16 at the very end.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+/* ---------- bf16 helpers (bf16 = 1 sign, 8 exponent, 7 mantissa bits; Sec. 3.3.1) ---------- */
+
+double orc_bf16_to_double(uint16_t b)
+{
+    uint32_t u = (uint32_t)b << 16;
+    float f;
+    memcpy(&f, &u, sizeof f);
+    return (double)f;
+}
+
+/* Round a double to the nearest bf16, ties to even, directly (no float stage). */
+uint16_t orc_bf16_from_double(double v)
+{
+    if (isnan(v)) return 0x7FC0;
+    uint16_t sign = signbit(v) ? 0x8000 : 0;
+    double a = fabs(v);
+    if (a == 0.0) return sign;
+    if (isinf(a)) return sign | 0x7F80;
+    double r;                              /* the rounded magnitude, exactly representable */
+    const double min_normal = ldexp(1.0, -126);
+    if (a < min_normal) {
+        const double quantum = ldexp(1.0, -133);           /* bf16 subnormal spacing */
+        r = nearbyint(a / quantum) * quantum;
+    } else {
+        int e;
+        double m = frexp(a, &e);                           /* a = m 2^e, m in [0.5,1) */
+        double q = nearbyint(m * 256.0);                   /* 8 significant bits, RNE */
+        r = ldexp(q, e - 8);
+    }
+    float f = (float)r;                                    /* exact, or overflow to inf */
+    uint32_t u;
+    memcpy(&u, &f, sizeof u);
+    return sign | (uint16_t)(u >> 16);
+}
+
+/* ---------- pack: Sec. 3.3.2 exponent rule + the bit positions Algorithm 1 reads ---------- */
+
+/*
+ * word = S0<<15 | S1<<14 | M0<<13 | M1<<12 | (exponent-112)<<7 | mantissa
+ * Returns the number of elements whose exponent does not fit (exponent > 143).
+ */
+int64_t orc_pack(const uint16_t *merged, const uint8_t *mask0, const uint8_t *mask1,
+                 const uint8_t *sign0, const uint8_t *sign1, int64_t n, uint16_t *packed)
+{
+    int64_t bad = 0;
+    for (int64_t i = 0; i < n; ++i) {
+        uint16_t mag = merged[i] & 0x7FFF;                 /* input sign ignored */
+        int exponent = mag >> 7;
+        int mantissa = mag & 0x7F;
+        int m0 = mask0[i] ? 1 : 0, m1 = mask1[i] ? 1 : 0;
+        int s0 = sign0[i] ? 1 : 0, s1 = sign1[i] ? 1 : 0;
+        if (exponent > 143) {                              /* not representable in 5 bits */
+            ++bad;
+            packed[i] = (uint16_t)(s0 << 15 | s1 << 14);
+            continue;
+        }
+        if (mag == 0) {                                    /* exact zero: mask it out */
+            packed[i] = (uint16_t)(s0 << 15 | s1 << 14);
+            continue;
+        }
+        if (exponent < 112) exponent = 112;                /* raised to 112, mantissa kept */
+        packed[i] = (uint16_t)(s0 << 15 | s1 << 14 | m0 << 13 | m1 << 12 |
+                               (exponent - 112) << 7 | mantissa);
+    }
+    return bad;
+}
+
+/* ---------- unpack: Algorithm 1 ---------- */
+
+static uint16_t decode_word(uint16_t W, int expert_pos)
+{
+    int mask_bit = (W >> (13 - expert_pos)) & 1;
+    if (mask_bit == 0) return 0;
+    int sign_bit = (W >> (15 - expert_pos)) & 1;
+    int exp_field = (W & 0x0F80) + (112 << 7);
+    return (uint16_t)(sign_bit << 15 | exp_field | (W & 0x007F));
+}
+
+void orc_unpack(const uint16_t *packed, int expert_pos, int64_t n, uint16_t *out)
+{
+    for (int64_t i = 0; i < n; ++i) out[i] = decode_word(packed[i], expert_pos);
+}
+
+/* ---------- routed SwiGLU expert FFN on decoded weights ---------- */
+
+static double silu(double g) { return g / (1.0 + exp(-g)); }
+
+/* out[r] = sum_c decode(Wp[r,c]) * v[c]   (rows x cols, row-major, fp64, left to right) */
+static void matvec_packed(const uint16_t *Wp, int pos, int rows, int cols,
+                          const double *v, double *out)
+{
+#pragma omp parallel for schedule(static)
+    for (int r = 0; r < rows; ++r) {
+        const uint16_t *row = Wp + (int64_t)r * cols;
+        double acc = 0.0;
+        for (int c = 0; c < cols; ++c)
+            acc += orc_bf16_to_double(decode_word(row[c], pos)) * v[c];
+        out[r] = acc;
+    }
+}
+
+static void matvec_dense(const uint16_t *Wd, int rows, int cols, const double *v, double *out)
+{
+#pragma omp parallel for schedule(static)
+    for (int r = 0; r < rows; ++r) {
+        const uint16_t *row = Wd + (int64_t)r * cols;
+        double acc = 0.0;
+        for (int c = 0; c < cols; ++c) acc += orc_bf16_to_double(row[c]) * v[c];
+        out[r] = acc;
+    }
+}
+
+/*
+ * y[t,:] = sum_j w[t,j] * FFN_{ids[t,j]}(x[t,:])  +  sum_s FFN_shared_s(x[t,:])
+ * FFN_e(x) = Wdown_e ( silu(Wgate_e x) * (Wup_e x) ),  W_e = Eq. 6 decode of its pair's
+ * packed tensor at position expert_pos[e].  gate/up are [f,d], down is [d,f], row-major,
+ * in the *logical* element order (the order orc_pack wrote them).
+ *
+ * stage_h_bf16 = 0: the definition (h kept in fp64).
+ * stage_h_bf16 = 1: h rounded to bf16 before the down projection (diagnostic only).
+ * y64 (optional) receives the unrounded sums, ybf16 (optional) their bf16 rounding.
+ * Returns 0, or -1 on an id outside [0,E) or allocation failure.
+ */
+int orc_moe_ffn(int T, int k, int E, int d, int f,
+                const uint16_t *x, const int32_t *ids, const float *w,
+                const int32_t *expert_pair, const uint8_t *expert_pos,
+                const uint16_t *const *gate, const uint16_t *const *up,
+                const uint16_t *const *down,
+                int n_shared, const int32_t *shared_f,
+                const uint16_t *const *sgate, const uint16_t *const *sup,
+                const uint16_t *const *sdown,
+                int stage_h_bf16, double *y64, uint16_t *ybf16)
+{
+    int fmax = f;
+    for (int s = 0; s < n_shared; ++s) if (shared_f[s] > fmax) fmax = shared_f[s];
+    double *xv = malloc(sizeof(double) * d);
+    double *g = malloc(sizeof(double) * fmax);
+    double *u = malloc(sizeof(double) * fmax);
+    double *h = malloc(sizeof(double) * fmax);
+    double *o = malloc(sizeof(double) * d);
+    double *acc = malloc(sizeof(double) * d);
+    int rc = 0;
+    if (!xv || !g || !u || !h || !o || !acc) { rc = -1; goto done; }
+
+    for (int t = 0; t < T; ++t) {
+        for (int c = 0; c < d; ++c) xv[c] = orc_bf16_to_double(x[(int64_t)t * d + c]);
+        for (int c = 0; c < d; ++c) acc[c] = 0.0;
+
+        for (int j = 0; j < k; ++j) {
+            int e = ids[(int64_t)t * k + j];
+            if (e < 0 || e >= E) { rc = -1; goto done; }
+            int p = expert_pair[e], pos = expert_pos[e];
+            matvec_packed(gate[p], pos, f, d, xv, g);
+            matvec_packed(up[p], pos, f, d, xv, u);
+            for (int r = 0; r < f; ++r) {
+                h[r] = silu(g[r]) * u[r];
+                if (stage_h_bf16) h[r] = orc_bf16_to_double(orc_bf16_from_double(h[r]));
+            }
+            matvec_packed(down[p], pos, d, f, h, o);
+            double wt = (double)w[(int64_t)t * k + j];
+            for (int c = 0; c < d; ++c) acc[c] += wt * o[c];
+        }
+        for (int s = 0; s < n_shared; ++s) {
+            int fs = shared_f[s];
+            matvec_dense(sgate[s], fs, d, xv, g);
+            matvec_dense(sup[s], fs, d, xv, u);
+            for (int r = 0; r < fs; ++r) {
+                h[r] = silu(g[r]) * u[r];
+                if (stage_h_bf16) h[r] = orc_bf16_to_double(orc_bf16_from_double(h[r]));
+            }
+            matvec_dense(sdown[s], d, fs, h, o);
+            for (int c = 0; c < d; ++c) acc[c] += o[c];
+        }
+        for (int c = 0; c < d; ++c) {
+            if (y64) y64[(int64_t)t * d + c] = acc[c];
+            if (ybf16) ybf16[(int64_t)t * d + c] = orc_bf16_from_double(acc[c]);
+        }
+    }
+done:
+    free(xv); free(g); free(u); free(h); free(o); free(acc);
+    return rc;
+}

@@ -1,0 +1,147 @@
+"""Seeded synthetic workloads shaped like the paper's MoE layers.
+
+This module only *draws inputs*: merged magnitudes, mask and sign planes, dense
+shared-expert weights, token activations and router decisions.  It contains none
+of the method's arithmetic (no pack, no decode, no FFN) so that the CPU oracle and
+the HIP library can both be fed from it without sharing any code of their own.
+
+The trained Mixtral-8x7B / Qwen1.5-MoE-A2.7B / DeepSeek-MoE-16B weights the paper
+evaluates (Sec. 4.1) are not available offline; these tensors stand in for them:
+expert weights are zero-mean Gaussians with one sigma per layer (paper appendix,
+"Visualization of MoE Expert Weight Distribution"), which keeps bf16 exponents in
+the 112..128 band the paper reports (Sec. 3.3.1).
+"""
+from dataclasses import dataclass, field
+from typing import Tuple
+
+import numpy as np
+import torch
+
+
+@dataclass(frozen=True)
+class LayerConfig:
+    name: str
+    n_experts: int
+    d_model: int
+    d_ffn: int
+    top_k: int
+    n_tokens: Tuple[int, ...]
+    shared_d_ffn: Tuple[int, ...] = ()
+    routing: str = "gaussian"          # "gaussian" | "zipf"
+    seed: int = 1000
+    sigma: float = 0.02
+    mask_density: float = 0.5
+
+    @property
+    def n_pairs(self):
+        return self.n_experts // 2
+
+
+CONFIGS = {
+    "tiny": LayerConfig("tiny", 2, 128, 256, 1, (8,), seed=1000),
+    "mixtral_decode": LayerConfig("mixtral_decode", 8, 4096, 14336, 2, (1, 8, 32, 64), seed=1001),
+    "mixtral_prefill": LayerConfig("mixtral_prefill", 8, 4096, 14336, 2, (4096,), seed=1001),
+    "qwen15_moe": LayerConfig("qwen15_moe", 60, 2048, 1408, 4, (256,), shared_d_ffn=(5632,),
+                              seed=1003),
+    "deepseek_moe": LayerConfig("deepseek_moe", 64, 2048, 1408, 6, (2048,),
+                                shared_d_ffn=(1408, 1408), routing="zipf", seed=1004),
+}
+
+_GATE, _UP, _DOWN = 0, 1, 2
+_PLANES = ("merged", "mask0", "mask1", "sign0", "sign1")
+
+
+def _gen(cfg, *key):
+    """One independent generator per tensor, so any tensor can be redrawn alone."""
+    g = torch.Generator(device="cpu")
+    s = cfg.seed
+    for v in key:
+        s = (s * 1000003 + int(v) + 12345) % (2 ** 62)
+    g.manual_seed(s)
+    return g
+
+
+def _bf16_bits(t):
+    return t.to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+
+
+def matrix_shape(cfg, which, d_ffn=None):
+    f = cfg.d_ffn if d_ffn is None else d_ffn
+    return (cfg.d_model, f) if which == _DOWN else (f, cfg.d_model)
+
+
+def pair_matrix(cfg, pair, which, shape=None):
+    """Inputs of pack for one matrix of one expert pair.
+
+    Returns dict(merged uint16 bf16 bits of |N(0, sigma)|, mask0, mask1, sign0, sign1 uint8).
+    Masks are independent Bernoulli(mask_density) per expert, signs Bernoulli(0.5).
+    """
+    rows, cols = shape if shape is not None else matrix_shape(cfg, which)
+    n = rows * cols
+    out = {}
+    g = _gen(cfg, 1, pair, which, 0)
+    out["merged"] = _bf16_bits((torch.randn(n, generator=g) * cfg.sigma).abs_()).reshape(rows, cols)
+    for i, name in enumerate(_PLANES[1:], start=1):
+        g = _gen(cfg, 1, pair, which, i)
+        p = cfg.mask_density if name.startswith("mask") else 0.5
+        out[name] = (torch.rand(n, generator=g) < p).to(torch.uint8).numpy().reshape(rows, cols)
+    return out
+
+
+def shared_matrix(cfg, s, which):
+    """Dense bf16 bits of one matrix of shared expert ``s`` (signed N(0, sigma))."""
+    rows, cols = matrix_shape(cfg, which, cfg.shared_d_ffn[s])
+    g = _gen(cfg, 2, s, which)
+    return _bf16_bits(torch.randn(rows * cols, generator=g) * cfg.sigma).reshape(rows, cols)
+
+
+def tokens(cfg, T):
+    """x [T, d_model] bf16 bits, N(0,1)."""
+    g = _gen(cfg, 3, T)
+    return _bf16_bits(torch.randn(T * cfg.d_model, generator=g)).reshape(T, cfg.d_model)
+
+
+def routing(cfg, T):
+    """Router decisions (inputs of the path): ids [T,k] int32, weights [T,k] float32.
+
+    gaussian: top-k of N(0,1) logits.  zipf: expert popularity p_r ~ r^-1.1 assigned to
+    experts by a seeded permutation; ids are the top-k of log p + Gumbel noise, i.e. k
+    experts sampled without replacement in proportion to p.  Weights are the softmax of
+    the selected scores.
+    """
+    g = _gen(cfg, 4, T)
+    E, k = cfg.n_experts, cfg.top_k
+    logits = torch.randn(T, E, generator=g)
+    if cfg.routing == "zipf":
+        ranks = torch.arange(1, E + 1, dtype=torch.float64)
+        p = ranks.pow(-1.1)
+        p = (p / p.sum()).to(torch.float32)
+        perm = torch.randperm(E, generator=g)
+        logp = torch.empty(E)
+        logp[perm] = p.log()
+        u = torch.rand(T, E, generator=g).clamp_(1e-9, 1 - 1e-9)
+        scores = logp[None, :] + (-(-u.log()).log())
+        sel, ids = torch.topk(scores, k, dim=1)
+        sel = logits.gather(1, ids)
+    else:
+        sel, ids = torch.topk(logits, k, dim=1)
+    w = torch.softmax(sel.float(), dim=1)
+    return ids.to(torch.int32).numpy(), w.to(torch.float32).numpy()
+
+
+def expert_map(cfg, mode="adjacent"):
+    """expert -> (pair, position).  adjacent: (e//2, e%2); random: seeded random pairing
+    (the paper's default grouping is random, Sec. 3.2 "Pair-wise Experts Grouping")."""
+    E = cfg.n_experts
+    if mode == "adjacent":
+        order = np.arange(E)
+    else:
+        order = torch.randperm(E, generator=_gen(cfg, 5)).numpy()
+    pair = np.empty(E, dtype=np.int32)
+    pos = np.empty(E, dtype=np.uint8)
+    pair[order] = np.arange(E) // 2
+    pos[order] = np.arange(E) % 2
+    return pair, pos
+
+
+GATE, UP, DOWN = _GATE, _UP, _DOWN

@@ -1,0 +1,197 @@
+"""Pins for the oracle's routed SwiGLU FFN over Eq. 6-decoded experts.  CPU only.
+
+The independent side never calls the oracle's decode: expert weights come straight from
+Eq. 6, (-1)^S * M * W_merged evaluated in numpy on the *inputs* of pack, and the FFN is
+dense numpy/torch fp64 matmuls.
+"""
+import numpy as np
+import pytest
+import torch
+
+from paper_2511_04805_amd import synth
+
+
+def bits_to_f64(bits):
+    return torch.from_numpy(np.ascontiguousarray(bits).astype(np.int16)).view(torch.bfloat16).double().numpy()
+
+
+def eq6_weights(planes, pos):
+    """(-1)^S * M * canon(W_merged) as float64, from pack's inputs (Eq. 6)."""
+    mags = planes["merged"] & 0x7FFF
+    exps = mags >> 7
+    canon = np.where(exps < 112, (112 << 7) | (mags & 0x7F), mags).astype(np.uint16)
+    val = np.where(mags == 0, 0.0, bits_to_f64(canon))
+    s = planes["sign%d" % pos].astype(np.float64)
+    return (1.0 - 2.0 * s) * planes["mask%d" % pos] * val
+
+
+def small_layer(oracle, E=4, d=64, f=96, seed=11, shared_f=(), mask_density=0.5):
+    cfg = synth.LayerConfig("unit", E, d, f, 2, (8,), shared_d_ffn=tuple(shared_f), seed=seed,
+                            mask_density=mask_density)
+    planes, packed = {}, {}
+    for p in range(cfg.n_pairs):
+        for which in (synth.GATE, synth.UP, synth.DOWN):
+            pl = synth.pair_matrix(cfg, p, which)
+            planes[p, which] = pl
+            packed[p, which], bad = oracle.pack(pl["merged"], pl["mask0"], pl["mask1"],
+                                                pl["sign0"], pl["sign1"])
+            assert bad == 0
+    shared = [tuple(synth.shared_matrix(cfg, s, w) for w in (synth.GATE, synth.UP, synth.DOWN))
+              for s in range(len(shared_f))]
+    return cfg, planes, packed, shared
+
+
+def run_oracle(oracle, cfg, packed, shared, x, ids, w, emap, **kw):
+    P = cfg.n_pairs
+    return oracle.moe_ffn(x, ids, w, emap[0], emap[1],
+                          [packed[p, synth.GATE] for p in range(P)],
+                          [packed[p, synth.UP] for p in range(P)],
+                          [packed[p, synth.DOWN] for p in range(P)], shared=shared, **kw)
+
+
+def dense_reference(cfg, planes, shared, x, ids, w, emap):
+    """Brute force: materialise every expert's dense fp64 matrices, then plain matmuls."""
+    xs = bits_to_f64(x)
+    T = xs.shape[0]
+    y = np.zeros((T, cfg.d_model))
+    silu = lambda g: g / (1.0 + np.exp(-g))
+    for t in range(T):
+        for j in range(ids.shape[1]):
+            e = int(ids[t, j])
+            p, pos = int(emap[0][e]), int(emap[1][e])
+            Wg = eq6_weights(planes[p, synth.GATE], pos)
+            Wu = eq6_weights(planes[p, synth.UP], pos)
+            Wd = eq6_weights(planes[p, synth.DOWN], pos)
+            h = silu(Wg @ xs[t]) * (Wu @ xs[t])
+            y[t] += float(w[t, j]) * (Wd @ h)
+        for sg, su, sd in shared:
+            h = silu(bits_to_f64(sg) @ xs[t]) * (bits_to_f64(su) @ xs[t])
+            y[t] += bits_to_f64(sd) @ h
+    return y
+
+
+def assert_close(a, b, rel=1e-11):
+    scale = np.abs(b).max() + 1e-300
+    assert np.abs(a - b).max() <= rel * scale, np.abs(a - b).max() / scale
+
+
+@pytest.mark.parametrize("mode", ["adjacent", "random"])
+def test_ffn_matches_brute_force(oracle, mode):
+    cfg, planes, packed, shared = small_layer(oracle, E=6, shared_f=(80, 48))
+    emap = synth.expert_map(cfg, mode)
+    x = synth.tokens(cfg, 8)
+    ids, w = synth.routing(cfg, 8)
+    y64, ybf = run_oracle(oracle, cfg, packed, shared, x, ids, w, emap)
+    ref = dense_reference(cfg, planes, shared, x, ids, w, emap)
+    assert_close(y64, ref)
+    want_bits = torch.from_numpy(y64).to(torch.float32).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    # double -> float -> bf16 may differ from the direct rounding only on near-ties
+    assert (ybf != want_bits).mean() < 1e-3
+    assert np.abs(bits_to_f64(ybf) - y64).max() <= 2.0 ** -8 * np.abs(y64).max()
+
+
+def test_tiny_config_matches_brute_force(oracle):
+    cfg = synth.CONFIGS["tiny"]
+    planes = {(0, w): synth.pair_matrix(cfg, 0, w) for w in (synth.GATE, synth.UP, synth.DOWN)}
+    packed = {k: oracle.pack(v["merged"], v["mask0"], v["mask1"], v["sign0"], v["sign1"])[0]
+              for k, v in planes.items()}
+    emap = synth.expert_map(cfg)
+    x = synth.tokens(cfg, 8)
+    ids, w = synth.routing(cfg, 8)
+    assert set(np.unique(ids)) <= {0, 1} and np.allclose(w, 1.0)
+    y64, _ = run_oracle(oracle, cfg, packed, [], x, ids, w, emap)
+    assert_close(y64, dense_reference(cfg, planes, [], x, ids, w, emap))
+    assert np.abs(y64).max() > 0
+
+
+def test_all_ones_masks_reduce_to_textbook_swiglu(oracle):
+    """masks = 1, signs = 0: both experts of a pair equal W_merged, and the layer is an
+    ordinary dense SwiGLU FFN; checked against torch's own silu and matmul."""
+    cfg = synth.LayerConfig("unit", 2, 64, 96, 1, (4,), seed=5)
+    pl = {w: synth.pair_matrix(cfg, 0, w) for w in (synth.GATE, synth.UP, synth.DOWN)}
+    one = lambda a: np.ones_like(a)
+    zero = lambda a: np.zeros_like(a)
+    packed = {w: oracle.pack(p["merged"], one(p["mask0"]), one(p["mask1"]), zero(p["sign0"]),
+                             zero(p["sign1"]))[0] for w, p in pl.items()}
+    x = synth.tokens(cfg, 4)
+    ids = np.array([[0], [1], [1], [0]], dtype=np.int32)
+    w = np.ones((4, 1), dtype=np.float32)
+    y64, _ = oracle.moe_ffn(x, ids, w, [0, 0], [0, 1], [packed[synth.GATE]], [packed[synth.UP]],
+                            [packed[synth.DOWN]])
+    canon = lambda p: torch.from_numpy(np.where((p["merged"] >> 7) < 112,
+                                                 bits_to_f64(((112 << 7) | (p["merged"] & 0x7F)).astype(np.uint16)),
+                                                 bits_to_f64(p["merged"])))
+    Wg, Wu, Wd = canon(pl[synth.GATE]), canon(pl[synth.UP]), canon(pl[synth.DOWN])
+    xt = torch.from_numpy(bits_to_f64(x))
+    ref = (torch.nn.functional.silu(xt @ Wg.T) * (xt @ Wu.T)) @ Wd.T
+    assert_close(y64, ref.numpy())
+
+
+def test_properties(oracle):
+    cfg, planes, packed, shared = small_layer(oracle, E=4, seed=3)
+    emap = synth.expert_map(cfg)
+    x = synth.tokens(cfg, 6)
+    ids, w = synth.routing(cfg, 6)
+    y, _ = run_oracle(oracle, cfg, packed, shared, x, ids, w, emap)
+    # token-permutation equivariance
+    perm = np.array([3, 0, 5, 1, 4, 2])
+    yp, _ = run_oracle(oracle, cfg, packed, shared, x[perm], ids[perm], w[perm], emap)
+    assert np.array_equal(yp, y[perm])
+    # linear in the routing weights
+    y2, _ = run_oracle(oracle, cfg, packed, shared, x, ids, (2 * w).astype(np.float32), emap)
+    assert_close(y2, 2 * y, rel=1e-14)
+    # zero routing weight removes the expert; duplicate ids add
+    w0 = w.copy(); w0[:, 1] = 0
+    ya, _ = run_oracle(oracle, cfg, packed, shared, x, ids, w0, emap)
+    yb, _ = run_oracle(oracle, cfg, packed, shared, x, ids[:, :1].copy(), w[:, :1].copy(), emap)
+    assert np.array_equal(ya, yb)
+    dup = np.repeat(ids[:, :1], 2, axis=1)
+    half = np.repeat(w[:, :1], 2, axis=1)
+    yc, _ = run_oracle(oracle, cfg, packed, shared, x, dup, half, emap)
+    assert_close(yc, 2 * yb, rel=1e-14)
+    # empty batch and bad ids
+    ye, _ = run_oracle(oracle, cfg, packed, shared, x[:0], ids[:0], w[:0], emap)
+    assert ye.shape == (0, cfg.d_model)
+    bad = ids.copy(); bad[0, 0] = cfg.n_experts
+    with pytest.raises(ValueError):
+        run_oracle(oracle, cfg, packed, shared, x, bad, w, emap)
+
+
+def test_masked_out_expert_contributes_zero(oracle):
+    cfg = synth.LayerConfig("unit", 2, 64, 96, 2, (4,), seed=9)
+    pl = {w: synth.pair_matrix(cfg, 0, w) for w in (synth.GATE, synth.UP, synth.DOWN)}
+    packed = {}
+    for wh, p in pl.items():
+        m0 = np.zeros_like(p["mask0"]) if wh == synth.DOWN else p["mask0"]
+        packed[wh] = oracle.pack(p["merged"], m0, p["mask1"], p["sign0"], p["sign1"])[0]
+    x = synth.tokens(cfg, 4)
+    ids = np.tile(np.array([[0, 1]], dtype=np.int32), (4, 1))
+    w = np.full((4, 2), 0.5, dtype=np.float32)
+    args = ([0, 0], [0, 1], [packed[synth.GATE]], [packed[synth.UP]], [packed[synth.DOWN]])
+    y_both, _ = oracle.moe_ffn(x, ids, w, *args)
+    y_only1, _ = oracle.moe_ffn(x, ids[:, 1:].copy(), w[:, 1:].copy(), *args)
+    assert np.array_equal(y_both, y_only1)
+
+
+def test_shared_expert_adds_with_weight_one(oracle):
+    cfg, planes, packed, shared = small_layer(oracle, E=2, shared_f=(80,), seed=21)
+    emap = synth.expert_map(cfg)
+    x = synth.tokens(cfg, 3)
+    ids = np.zeros((3, 1), dtype=np.int32)
+    w = np.zeros((3, 1), dtype=np.float32)          # routed part switched off
+    y, _ = run_oracle(oracle, cfg, packed, shared, x, ids, w, emap)
+    sg, su, sd = (torch.from_numpy(bits_to_f64(a)) for a in shared[0])
+    xt = torch.from_numpy(bits_to_f64(x))
+    ref = (torch.nn.functional.silu(xt @ sg.T) * (xt @ su.T)) @ sd.T
+    assert_close(y, ref.numpy())
+
+
+def test_staged_variant_is_close(oracle):
+    cfg, planes, packed, shared = small_layer(oracle, E=4, seed=4)
+    emap = synth.expert_map(cfg)
+    x = synth.tokens(cfg, 4)
+    ids, w = synth.routing(cfg, 4)
+    y, _ = run_oracle(oracle, cfg, packed, shared, x, ids, w, emap)
+    ys, _ = run_oracle(oracle, cfg, packed, shared, x, ids, w, emap, stage_h_bf16=True)
+    rms = np.sqrt((y ** 2).mean())
+    assert 0 < np.abs(ys - y).max() < 2.0 ** -7 * rms * 4
