@@ -1,0 +1,151 @@
+/*
+ * puzzle_moe.h — C ABI of the MI355X (gfx950) bit-packed merged-expert MoE FFN library.
+ *
+ * The library implements the inference hot path of PuzzleMoE: two experts of an MoE layer
+ * share one merged, non-negative bf16 tensor whose freed exponent bits and unused sign bit
+ * hold each expert's mask and sign bit (Sec. 3.3.2 "System Co-design"); an activated
+ * expert's weights are rebuilt element by element as (-1)^S * M * W_merged (Eq. 6) by the
+ * bit-level decode of Algorithm 1, inside the expert matmuls, without ever materialising
+ * the decoded matrix and with one read of the packed tensor serving both experts
+ * (Sec. 3.3.2, decode-GEMM).
+ *
+ * Conventions for every call
+ *   - Pointers are DEVICE pointers unless the comment says "host".
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  Calls enqueue
+ *     work and return without synchronising; results are valid after the stream is
+ *     synchronised.
+ *   - No call keeps a reference to caller memory after it returns, except that a
+ *     pzl_layer keeps the weight pointers it was created with (the weights stay
+ *     caller-owned and must outlive the layer).
+ *   - pzl_moe_ffn allocates nothing; everything it needs beyond inputs and outputs is in
+ *     the caller's workspace.
+ *   - Return value: PZL_OK (0) or a negative PZL_E* code; nothing throws across the ABI.
+ *
+ * Packed word (16 bits per element, no side metadata; bit positions are those Algorithm 1
+ * reads):   15: S0   14: S1   13: M0   12: M1   11..7: exponent-112   6..0: mantissa
+ * where S_p / M_p are the sign / mask bit of the expert at position p of the pair.
+ *
+ * Physical order of a packed (or tiled dense) [rows, cols] matrix.  The paper fixes the
+ * word, not the element order in memory; this library stores 16x32 tiles so that one
+ * 64-lane wavefront reads 1 KiB contiguously and receives its matrix-core operand
+ * directly: rows % 16 == 0 and cols % 32 == 0 are required, and logical element (r, c)
+ * lives at 16-bit index
+ *     ((r/16) * (cols/32) + c/32) * 512  +  (((c%32)/8) * 16 + r%16) * 8  +  c%8 .
+ * pzl_unpack returns the logical row-major matrix.
+ */
+#ifndef PUZZLE_MOE_H
+#define PUZZLE_MOE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define PZL_ABI_VERSION 1
+
+#define PZL_OK       0
+#define PZL_EINVAL  -1   /* null pointer, bad shape, position not 0/1, pair map not a 2-to-1 cover */
+#define PZL_ENOSPC  -2   /* workspace too small */
+#define PZL_EHIP    -3   /* a HIP call or kernel launch failed; see pzl_last_hip_error() */
+#define PZL_ENOMEM  -4   /* pzl_layer_create could not allocate its tables */
+
+int pzl_abi_version(void);
+/* Static description of a return code. */
+const char *pzl_strerror(int rc);
+/* Text of the last HIP error seen by this library on the calling thread (static storage). */
+const char *pzl_last_hip_error(void);
+
+/* Size of a packed [rows, cols] tensor: rows*cols*2 bytes, the size of the bf16 tensor it
+ * replaces (Sec. 3.3.2: masks and signs are embedded "without additional storage"). */
+size_t pzl_packed_bytes(int64_t rows, int64_t cols);
+
+/*
+ * pack — Sec. 3.3.2: clamp each exponent to >= 112, subtract 112, and put S0,S1,M0,M1 in the
+ * four freed top bits.  Readings where the paper is silent: the mantissa is kept when the
+ * exponent is raised; an exactly-zero magnitude is stored with both mask bits cleared; an
+ * exponent above 143 (incl. Inf/NaN) is stored as a fully masked word and counted.
+ *   merged      [rows, cols] row-major bf16 bit patterns; the sign bit is ignored (Eq. 5)
+ *   mask0/1     [rows, cols] row-major bytes, non-zero = element kept for position 0 / 1
+ *   sign0/1     [rows, cols] row-major bytes, non-zero = negative (Eq. 1)
+ *   packed_out  pzl_packed_bytes(rows, cols) bytes, caller-owned, tiled order (see above)
+ *   n_out_of_range  optional int32 on the device; the kernel ADDS the number of
+ *               out-of-range elements to it (zero it first).  May be NULL.
+ */
+int pzl_pack(const uint16_t *merged, const uint8_t *mask0, const uint8_t *mask1,
+             const uint8_t *sign0, const uint8_t *sign1, int64_t rows, int64_t cols,
+             uint16_t *packed_out, int32_t *n_out_of_range, void *stream);
+
+/*
+ * unpack — Algorithm 1 on every element: the weights of the expert at `expert_pos` (0 or 1).
+ *   packed  tiled packed tensor written by pzl_pack
+ *   out     [rows, cols] row-major bf16 bit patterns, caller-owned
+ * Masked-out elements are +0.  Bit-exact by definition.
+ */
+int pzl_unpack(const uint16_t *packed, int expert_pos, int64_t rows, int64_t cols,
+               uint16_t *out, void *stream);
+
+/*
+ * Re-order a dense row-major bf16 matrix (an unmerged shared expert, "other modules
+ * unchanged", Sec. 4.1) into the same 16x32 tiled order.  Values are not changed.
+ */
+int pzl_tile_dense(const uint16_t *dense_rowmajor, int64_t rows, int64_t cols,
+                   uint16_t *tiled_out, void *stream);
+
+/*
+ * Description of one MoE layer.  Host struct; the small tables are copied at create time,
+ * the weight tensors are referenced, not copied.
+ */
+typedef struct pzl_layer_desc {
+    int32_t n_experts;              /* E, even */
+    int32_t d_model;                /* d, multiple of 32 */
+    int32_t d_ffn;                  /* f of the routed experts, multiple of 32 */
+    const int32_t *expert_pair;     /* host [E]: pair index in [0, E/2)                  */
+    const uint8_t *expert_pos;      /* host [E]: position 0|1 inside the pair; every pair
+                                       must be covered exactly once at each position
+                                       (pair-wise grouping, Sec. 3.2)                    */
+    const uint16_t *const *gate;    /* host [E/2] of device ptrs, packed [d_ffn, d_model] */
+    const uint16_t *const *up;      /* host [E/2] of device ptrs, packed [d_ffn, d_model] */
+    const uint16_t *const *down;    /* host [E/2] of device ptrs, packed [d_model, d_ffn] */
+    int32_t n_shared;               /* dense experts applied to every token with weight 1 */
+    const int32_t *shared_d_ffn;    /* host [n_shared], each a multiple of 32             */
+    const uint16_t *const *shared_gate;   /* host [n_shared] of device ptrs, tiled dense  */
+    const uint16_t *const *shared_up;     /*   bf16 [fs, d_model] (pzl_tile_dense)        */
+    const uint16_t *const *shared_down;   /*   bf16 [d_model, fs]                         */
+} pzl_layer_desc;
+
+typedef struct pzl_layer pzl_layer;
+
+/* Validates the description and builds the layer's device tables (the only allocation the
+ * library performs).  The device current at the call is the layer's device. */
+int pzl_layer_create(const pzl_layer_desc *desc, pzl_layer **out);
+void pzl_layer_destroy(pzl_layer *layer);
+
+/* Bytes of workspace pzl_moe_ffn needs for any T <= max_tokens at this top_k (0 on bad
+ * arguments).  The workspace must be 256-byte aligned device memory. */
+size_t pzl_moe_ffn_workspace_bytes(const pzl_layer *layer, int32_t max_tokens, int32_t top_k);
+
+/*
+ * moe_ffn — the routed expert FFN over Eq. 6-decoded weights:
+ *   y[t,:] = sum_j topk_w[t,j] * FFN_{topk_ids[t,j]}(x[t,:])  +  sum_s FFN_shared_s(x[t,:])
+ *   FFN_e(x) = Wdown_e ( silu(Wgate_e x) * (Wup_e x) ),   silu(g) = g / (1 + exp(-g))
+ * with every routed W_e decoded on the fly from its pair's packed tensor (Algorithm 1).
+ * Products are bf16 x bf16 accumulated in fp32; the SwiGLU output is rounded to bf16 once
+ * before the down projection; y is rounded to bf16 once at the end.
+ *   x         [T, d_model] bf16 bits, row-major
+ *   topk_ids  [T, k] int32 expert ids in [0, E); duplicates within a token add up; ids
+ *             outside the range are ignored (contribute nothing)
+ *   topk_w    [T, k] fp32 routing weights
+ *   y         [T, d_model] bf16 bits, overwritten
+ *   workspace at least pzl_moe_ffn_workspace_bytes(layer, T, k) bytes; contents are scratch
+ * T == 0 is a no-op.  Concurrent calls must use different workspaces.
+ */
+int pzl_moe_ffn(const pzl_layer *layer, const uint16_t *x, const int32_t *topk_ids,
+                const float *topk_w, int32_t T, int32_t k, uint16_t *y,
+                void *workspace, size_t workspace_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PUZZLE_MOE_H */

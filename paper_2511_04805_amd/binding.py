@@ -1,0 +1,212 @@
+"""ctypes binding of the HIP C-ABI library (include/puzzle_moe.h).
+
+Argument marshalling only: every step of the path runs in the library's kernels.  torch is
+used for device memory and streams.  There is no fallback: if the library is not built, or no
+GPU is present, the calls raise.
+"""
+import ctypes
+import os
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libpuzzle_moe.so")
+_lib = None
+
+PZL_OK, PZL_EINVAL, PZL_ENOSPC, PZL_EHIP, PZL_ENOMEM = 0, -1, -2, -3, -4
+
+EXPORTS = ("pzl_abi_version", "pzl_strerror", "pzl_last_hip_error", "pzl_packed_bytes", "pzl_pack",
+           "pzl_unpack", "pzl_tile_dense", "pzl_layer_create", "pzl_layer_destroy",
+           "pzl_moe_ffn_workspace_bytes", "pzl_moe_ffn")
+
+
+class PzlError(RuntimeError):
+    def __init__(self, rc, where):
+        self.rc = rc
+        lib = load()
+        msg = lib.pzl_strerror(rc).decode()
+        if rc == PZL_EHIP:
+            msg += ": " + lib.pzl_last_hip_error().decode()
+        super().__init__("%s failed: %s (rc=%d)" % (where, msg, rc))
+
+
+class _LayerDesc(ctypes.Structure):
+    _fields_ = [("n_experts", ctypes.c_int32), ("d_model", ctypes.c_int32), ("d_ffn", ctypes.c_int32),
+                ("expert_pair", ctypes.c_void_p), ("expert_pos", ctypes.c_void_p),
+                ("gate", ctypes.c_void_p), ("up", ctypes.c_void_p), ("down", ctypes.c_void_p),
+                ("n_shared", ctypes.c_int32), ("shared_d_ffn", ctypes.c_void_p),
+                ("shared_gate", ctypes.c_void_p), ("shared_up", ctypes.c_void_p),
+                ("shared_down", ctypes.c_void_p)]
+
+
+def load():
+    """Load the built library; raise if it is missing (build with `python -m paper_2511_04805_amd.build`)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError("HIP library not built: %s is missing "
+                               "(run `python -m paper_2511_04805_amd.build`)" % LIB_PATH)
+        lib = ctypes.CDLL(LIB_PATH)
+        vp, i64, i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32
+        lib.pzl_abi_version.restype = ctypes.c_int
+        lib.pzl_strerror.restype = ctypes.c_char_p
+        lib.pzl_strerror.argtypes = [ctypes.c_int]
+        lib.pzl_last_hip_error.restype = ctypes.c_char_p
+        lib.pzl_packed_bytes.restype = ctypes.c_size_t
+        lib.pzl_packed_bytes.argtypes = [i64, i64]
+        lib.pzl_pack.restype = ctypes.c_int
+        lib.pzl_pack.argtypes = [vp, vp, vp, vp, vp, i64, i64, vp, vp, vp]
+        lib.pzl_unpack.restype = ctypes.c_int
+        lib.pzl_unpack.argtypes = [vp, ctypes.c_int, i64, i64, vp, vp]
+        lib.pzl_tile_dense.restype = ctypes.c_int
+        lib.pzl_tile_dense.argtypes = [vp, i64, i64, vp, vp]
+        lib.pzl_layer_create.restype = ctypes.c_int
+        lib.pzl_layer_create.argtypes = [ctypes.POINTER(_LayerDesc), ctypes.POINTER(vp)]
+        lib.pzl_layer_destroy.restype = None
+        lib.pzl_layer_destroy.argtypes = [vp]
+        lib.pzl_moe_ffn_workspace_bytes.restype = ctypes.c_size_t
+        lib.pzl_moe_ffn_workspace_bytes.argtypes = [vp, i32, i32]
+        lib.pzl_moe_ffn.restype = ctypes.c_int
+        lib.pzl_moe_ffn.argtypes = [vp, vp, vp, vp, i32, i32, vp, vp, ctypes.c_size_t, vp]
+        _lib = lib
+    return _lib
+
+
+def _check(rc, where):
+    if rc != PZL_OK:
+        raise PzlError(rc, where)
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _dev(t, dtypes, name):
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.is_contiguous() and t.dtype in dtypes):
+        raise TypeError("%s must be a contiguous CUDA tensor of dtype %s" % (name, dtypes))
+    return ctypes.c_void_p(t.data_ptr())
+
+
+_BITS16 = (torch.int16, torch.bfloat16, torch.uint16)
+
+
+def pzl_packed_bytes(rows, cols):
+    return load().pzl_packed_bytes(rows, cols)
+
+
+def pzl_pack(merged, mask0, mask1, sign0, sign1, out=None, n_out_of_range=None):
+    """pack(merged weights, masks, signs) -> packed tensor (int16, tiled order, rows*cols elements)."""
+    rows, cols = merged.shape
+    if out is None:
+        out = torch.empty(rows * cols, dtype=torch.int16, device=merged.device)
+    for m in (mask0, mask1, sign0, sign1):
+        if tuple(m.shape) != (rows, cols):
+            raise ValueError("mask/sign planes must have the shape of merged")
+    cnt = ctypes.c_void_p(0) if n_out_of_range is None else _dev(n_out_of_range, (torch.int32,), "n_out_of_range")
+    rc = load().pzl_pack(_dev(merged, _BITS16, "merged"), _dev(mask0, (torch.uint8,), "mask0"),
+                         _dev(mask1, (torch.uint8,), "mask1"), _dev(sign0, (torch.uint8,), "sign0"),
+                         _dev(sign1, (torch.uint8,), "sign1"), rows, cols, _dev(out, _BITS16, "out"),
+                         cnt, _stream())
+    _check(rc, "pzl_pack")
+    return out
+
+
+def pzl_unpack(packed, expert_pos, rows, cols, out=None):
+    """Algorithm 1 decode of one expert of the pair -> bfloat16 [rows, cols], row-major."""
+    if packed.numel() != rows * cols:
+        raise ValueError("packed tensor does not hold rows*cols elements")
+    if out is None:
+        out = torch.empty(rows, cols, dtype=torch.bfloat16, device=packed.device)
+    rc = load().pzl_unpack(_dev(packed, _BITS16, "packed"), int(expert_pos), rows, cols,
+                           _dev(out, _BITS16, "out"), _stream())
+    _check(rc, "pzl_unpack")
+    return out
+
+
+def pzl_tile_dense(dense, out=None):
+    rows, cols = dense.shape
+    if out is None:
+        out = torch.empty(rows * cols, dtype=dense.dtype, device=dense.device)
+    rc = load().pzl_tile_dense(_dev(dense, _BITS16, "dense"), rows, cols, _dev(out, _BITS16, "out"), _stream())
+    _check(rc, "pzl_tile_dense")
+    return out
+
+
+def _ptr_table(tensors):
+    return (ctypes.c_void_p * max(len(tensors), 1))(*[t.data_ptr() for t in tensors])
+
+
+class Layer:
+    """Owns a pzl_layer handle and keeps the weight tensors it references alive."""
+
+    def __init__(self, d_model, d_ffn, expert_pair, expert_pos, gate, up, down, shared=()):
+        self.d_model, self.d_ffn = int(d_model), int(d_ffn)
+        self._keep = (list(gate), list(up), list(down), [tuple(s) for s in shared])
+        pair = np.ascontiguousarray(expert_pair, dtype=np.int32)
+        pos = np.ascontiguousarray(expert_pos, dtype=np.uint8)
+        P = len(gate)
+        for name, ws, shape in (("gate", gate, d_ffn * d_model), ("up", up, d_ffn * d_model),
+                                ("down", down, d_model * d_ffn)):
+            if len(ws) != P:
+                raise ValueError("need one %s tensor per pair" % name)
+            for t in ws:
+                _dev(t, _BITS16, name)
+                if t.numel() != shape:
+                    raise ValueError("%s tensor has the wrong size" % name)
+        sf = np.array([int(s[3]) for s in shared], dtype=np.int32)
+        for g, u, dn, fs in shared:
+            for t in (g, u, dn):
+                _dev(t, _BITS16, "shared weight")
+                if t.numel() != fs * d_model:
+                    raise ValueError("shared weight has the wrong size")
+        self._tables = (pair, pos, sf, _ptr_table(gate), _ptr_table(up), _ptr_table(down),
+                        _ptr_table([s[0] for s in shared]), _ptr_table([s[1] for s in shared]),
+                        _ptr_table([s[2] for s in shared]))
+        d = _LayerDesc()
+        d.n_experts, d.d_model, d.d_ffn = int(pair.size), self.d_model, self.d_ffn
+        d.expert_pair, d.expert_pos = pair.ctypes.data, pos.ctypes.data
+        cast = lambda a: ctypes.cast(a, ctypes.c_void_p)
+        d.gate, d.up, d.down = cast(self._tables[3]), cast(self._tables[4]), cast(self._tables[5])
+        d.n_shared = len(shared)
+        d.shared_d_ffn = sf.ctypes.data if len(shared) else None
+        d.shared_gate, d.shared_up, d.shared_down = (cast(self._tables[6]), cast(self._tables[7]),
+                                                     cast(self._tables[8]))
+        self._h = ctypes.c_void_p()
+        _check(load().pzl_layer_create(ctypes.byref(d), ctypes.byref(self._h)), "pzl_layer_create")
+        self._ws = None
+
+    def close(self):
+        if getattr(self, "_h", None) is not None and self._h:
+            load().pzl_layer_destroy(self._h)
+            self._h = None
+
+    __del__ = close
+
+    def pzl_moe_ffn_workspace_bytes(self, max_tokens, top_k):
+        return load().pzl_moe_ffn_workspace_bytes(self._h, int(max_tokens), int(top_k))
+
+    def pzl_moe_ffn(self, x, topk_ids, topk_w, y=None, workspace=None):
+        """moe_ffn(x, router top-k ids/weights, packed experts) -> y (bfloat16 [T, d_model])."""
+        T = x.shape[0]
+        k = topk_ids.shape[1] if topk_ids.dim() == 2 else 0
+        if y is None:
+            y = torch.empty(T, self.d_model, dtype=torch.bfloat16, device=x.device)
+        if T == 0:
+            return y
+        if workspace is None:
+            need = self.pzl_moe_ffn_workspace_bytes(T, k)
+            if self._ws is None or self._ws.numel() < need:
+                self._ws = torch.empty(need, dtype=torch.uint8, device=x.device)
+            workspace = self._ws
+        rc = load().pzl_moe_ffn(self._h, _dev(x, _BITS16, "x"), _dev(topk_ids, (torch.int32,), "topk_ids"),
+                                _dev(topk_w, (torch.float32,), "topk_w"), T, k, _dev(y, _BITS16, "y"),
+                                _dev(workspace, (torch.uint8,), "workspace"), workspace.numel(), _stream())
+        _check(rc, "pzl_moe_ffn")
+        return y
+
+
+def tiled_to_logical(tiled, rows, cols):
+    """Undo the 16x32 tiled order of a packed / tiled tensor (numpy, layout only)."""
+    a = np.asarray(tiled).reshape(rows // 16, cols // 32, 4, 16, 8)       # [rt, kb, kgroup, r, j]
+    return np.ascontiguousarray(a.transpose(0, 3, 1, 2, 4)).reshape(rows, cols)

@@ -1,0 +1,273 @@
+// C ABI of the library (see include/puzzle_moe.h): argument checks, the layer object, workspace
+// carving and the launch sequence of pzl_moe_ffn.  No kernel lives here.
+#include "pzl_common.h"
+
+#include <new>
+#include <string.h>
+#include <vector>
+
+namespace pzl {
+
+static thread_local char g_hip_error[256] = "no HIP error recorded";
+
+void set_hip_error(hipError_t e)
+{
+    const char *s = hipGetErrorString(e);
+    strncpy(g_hip_error, s ? s : "unknown HIP error", sizeof(g_hip_error) - 1);
+    g_hip_error[sizeof(g_hip_error) - 1] = 0;
+}
+
+static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+}  // namespace pzl
+
+struct pzl_layer {
+    int32_t n_experts, n_pairs, d_model, d_ffn, n_shared;
+    int32_t ksplit;                        // k-splits of the down projection (layer constant)
+    std::vector<int32_t> shared_f;
+    // device tables
+    int32_t *d_q_of_expert;                // [E] expert -> 2*pair + pos
+    const uint16_t **d_gate, **d_up, **d_down;            // [P]
+    const uint16_t **d_sgate, **d_sup, **d_sdown;         // [n_shared]
+    void *d_block;                         // the one allocation holding all of the above
+};
+
+namespace pzl {
+
+struct WorkspaceLayout {
+    size_t cnt, off, slot_tok, slot_of, h_routed, h_shared, opart, total;
+    int64_t o_ks_stride;      // elements between k-splits of the partial-sum buffer
+    size_t h_shared_each(const pzl_layer *L, int32_t T, int s) const
+    {
+        return align_up((size_t)T * L->shared_f[s] * 2, 256);
+    }
+};
+
+static WorkspaceLayout carve(const pzl_layer *L, int32_t T, int32_t k)
+{
+    WorkspaceLayout w;
+    const size_t N = (size_t)T * k;
+    const size_t slots = N + (size_t)L->n_shared * T;
+    size_t p = 0;
+    w.cnt = p;       p += align_up((size_t)L->n_experts * 4, 256);
+    w.off = p;       p += align_up(((size_t)L->n_experts + 1) * 4, 256);
+    w.slot_tok = p;  p += align_up(N * 4, 256);
+    w.slot_of = p;   p += align_up(N * 4, 256);
+    w.h_routed = p;  p += align_up(N * L->d_ffn * 2, 256);
+    w.h_shared = p;
+    for (int s = 0; s < L->n_shared; ++s) p += w.h_shared_each(L, T, s);
+    w.o_ks_stride = (int64_t)slots * L->d_model;
+    w.opart = p;     p += align_up((size_t)L->ksplit * slots * L->d_model * 4, 256);
+    w.total = p;
+    return w;
+}
+
+static int choose_ksplit(int n_groups, int rows)
+{
+    // The down projection has only rows/64 workgroups per pair; split its long K so that a
+    // launch has at least ~4 workgroups per compute unit (256 CUs).
+    int row_groups = (rows / TILE_ROWS + 3) / 4;
+    int64_t wgs = (int64_t)n_groups * row_groups;
+    int ks = (int)((1024 + wgs - 1) / wgs);
+    if (ks < 1) ks = 1;
+    if (ks > 8) ks = 8;
+    return ks;
+}
+
+}  // namespace pzl
+
+using namespace pzl;
+
+extern "C" {
+
+int pzl_abi_version(void) { return PZL_ABI_VERSION; }
+
+const char *pzl_strerror(int rc)
+{
+    switch (rc) {
+        case PZL_OK: return "ok";
+        case PZL_EINVAL: return "invalid argument (null pointer, bad shape, bad position or pair map)";
+        case PZL_ENOSPC: return "workspace too small";
+        case PZL_EHIP: return "HIP call or kernel launch failed (see pzl_last_hip_error)";
+        case PZL_ENOMEM: return "device allocation failed";
+        default: return "unknown error code";
+    }
+}
+
+const char *pzl_last_hip_error(void) { return g_hip_error; }
+
+size_t pzl_packed_bytes(int64_t rows, int64_t cols)
+{
+    if (rows <= 0 || cols <= 0) return 0;
+    return (size_t)rows * (size_t)cols * 2;
+}
+
+int pzl_pack(const uint16_t *merged, const uint8_t *mask0, const uint8_t *mask1, const uint8_t *sign0,
+             const uint8_t *sign1, int64_t rows, int64_t cols, uint16_t *packed_out,
+             int32_t *n_out_of_range, void *stream)
+{
+    return launch_pack(merged, mask0, mask1, sign0, sign1, rows, cols, packed_out, n_out_of_range,
+                       (hipStream_t)stream);
+}
+
+int pzl_unpack(const uint16_t *packed, int expert_pos, int64_t rows, int64_t cols, uint16_t *out,
+               void *stream)
+{
+    return launch_unpack(packed, expert_pos, rows, cols, out, (hipStream_t)stream);
+}
+
+int pzl_tile_dense(const uint16_t *dense_rowmajor, int64_t rows, int64_t cols, uint16_t *tiled_out,
+                   void *stream)
+{
+    return launch_tile_dense(dense_rowmajor, rows, cols, tiled_out, (hipStream_t)stream);
+}
+
+int pzl_layer_create(const pzl_layer_desc *desc, pzl_layer **out)
+{
+    if (!desc || !out) return PZL_EINVAL;
+    *out = nullptr;
+    const int E = desc->n_experts, d = desc->d_model, f = desc->d_ffn, S = desc->n_shared;
+    if (E < 2 || (E & 1) || E > 512 || d <= 0 || f <= 0 || d % TILE_COLS || f % TILE_COLS) return PZL_EINVAL;
+    if (!desc->expert_pair || !desc->expert_pos || !desc->gate || !desc->up || !desc->down) return PZL_EINVAL;
+    if (S < 0 || S > 16) return PZL_EINVAL;
+    if (S > 0 && (!desc->shared_d_ffn || !desc->shared_gate || !desc->shared_up || !desc->shared_down))
+        return PZL_EINVAL;
+    const int P = E / 2;
+    // the pair map must cover every (pair, position) exactly once
+    std::vector<int32_t> q_of(E);
+    std::vector<char> seen(E, 0);
+    for (int e = 0; e < E; ++e) {
+        int p = desc->expert_pair[e], pos = desc->expert_pos[e];
+        if (p < 0 || p >= P || pos < 0 || pos > 1 || seen[2 * p + pos]) return PZL_EINVAL;
+        seen[2 * p + pos] = 1;
+        q_of[e] = 2 * p + pos;
+    }
+    for (int p = 0; p < P; ++p)
+        if (!desc->gate[p] || !desc->up[p] || !desc->down[p]) return PZL_EINVAL;
+    for (int s = 0; s < S; ++s) {
+        int fs = desc->shared_d_ffn[s];
+        if (fs <= 0 || fs % TILE_COLS || !desc->shared_gate[s] || !desc->shared_up[s] || !desc->shared_down[s])
+            return PZL_EINVAL;
+    }
+
+    pzl_layer *L = new (std::nothrow) pzl_layer();
+    if (!L) return PZL_ENOMEM;
+    L->n_experts = E; L->n_pairs = P; L->d_model = d; L->d_ffn = f; L->n_shared = S;
+    L->shared_f.assign(desc->shared_d_ffn, desc->shared_d_ffn + S);
+    L->ksplit = choose_ksplit(P, d);
+
+    const size_t sz_q = align_up((size_t)E * 4, 256);
+    const size_t sz_p = align_up((size_t)P * sizeof(void *), 256);
+    const size_t sz_s = align_up((size_t)(S > 0 ? S : 1) * sizeof(void *), 256);
+    const size_t total = sz_q + 3 * sz_p + 3 * sz_s;
+    std::vector<unsigned char> host(total, 0);
+    size_t o = 0;
+    memcpy(&host[o], q_of.data(), (size_t)E * 4);                     size_t o_q = o;  o += sz_q;
+    memcpy(&host[o], desc->gate, (size_t)P * sizeof(void *));         size_t o_g = o;  o += sz_p;
+    memcpy(&host[o], desc->up, (size_t)P * sizeof(void *));           size_t o_u = o;  o += sz_p;
+    memcpy(&host[o], desc->down, (size_t)P * sizeof(void *));         size_t o_d = o;  o += sz_p;
+    size_t o_sg = o; if (S) memcpy(&host[o], desc->shared_gate, (size_t)S * sizeof(void *)); o += sz_s;
+    size_t o_su = o; if (S) memcpy(&host[o], desc->shared_up, (size_t)S * sizeof(void *));   o += sz_s;
+    size_t o_sd = o; if (S) memcpy(&host[o], desc->shared_down, (size_t)S * sizeof(void *)); o += sz_s;
+
+    hipError_t e = hipMalloc(&L->d_block, total);
+    if (e != hipSuccess) { set_hip_error(e); delete L; return PZL_ENOMEM; }
+    e = hipMemcpy(L->d_block, host.data(), total, hipMemcpyHostToDevice);
+    if (e != hipSuccess) { set_hip_error(e); (void)hipFree(L->d_block); delete L; return PZL_EHIP; }
+    unsigned char *base = (unsigned char *)L->d_block;
+    L->d_q_of_expert = (int32_t *)(base + o_q);
+    L->d_gate = (const uint16_t **)(base + o_g);
+    L->d_up = (const uint16_t **)(base + o_u);
+    L->d_down = (const uint16_t **)(base + o_d);
+    L->d_sgate = (const uint16_t **)(base + o_sg);
+    L->d_sup = (const uint16_t **)(base + o_su);
+    L->d_sdown = (const uint16_t **)(base + o_sd);
+    *out = L;
+    return PZL_OK;
+}
+
+void pzl_layer_destroy(pzl_layer *layer)
+{
+    if (!layer) return;
+    if (layer->d_block) (void)hipFree(layer->d_block);
+    delete layer;
+}
+
+size_t pzl_moe_ffn_workspace_bytes(const pzl_layer *layer, int32_t max_tokens, int32_t top_k)
+{
+    if (!layer || max_tokens < 0 || top_k < 0) return 0;
+    if ((int64_t)max_tokens * top_k > 0x3FFFFFFF) return 0;
+    // every buffer grows with T, so the layout at max_tokens bounds all smaller batches
+    return carve(layer, max_tokens, top_k).total;
+}
+
+int pzl_moe_ffn(const pzl_layer *L, const uint16_t *x, const int32_t *topk_ids, const float *topk_w,
+                int32_t T, int32_t k, uint16_t *y, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!L || T < 0 || k < 0) return PZL_EINVAL;
+    if (T == 0) return PZL_OK;
+    if (!x || !y || (k > 0 && (!topk_ids || !topk_w)) || !workspace) return PZL_EINVAL;
+    if ((int64_t)T * k > 0x3FFFFFFF || ((uintptr_t)workspace & 255)) return PZL_EINVAL;
+    const WorkspaceLayout w = carve(L, T, k);
+    if (workspace_bytes < w.total) return PZL_ENOSPC;
+    hipStream_t st = (hipStream_t)stream;
+    unsigned char *ws = (unsigned char *)workspace;
+    const int32_t N = T * k;
+
+    RouteTables rt;
+    rt.cnt = (int32_t *)(ws + w.cnt);
+    rt.off = (int32_t *)(ws + w.off);
+    rt.slot_tok = (int32_t *)(ws + w.slot_tok);
+    rt.slot_of = (int32_t *)(ws + w.slot_of);
+    uint16_t *h_routed = (uint16_t *)(ws + w.h_routed);
+    float *opart = (float *)(ws + w.opart);
+
+    int rc = launch_route(topk_ids, N, k, L->n_experts, L->d_q_of_expert, rt, st);
+    if (rc) return rc;
+
+    if (N > 0) {
+        StreamGroupArgs a = {};
+        a.n_groups = L->n_pairs;
+        a.cnt = rt.cnt; a.off = rt.off; a.slot_tok = rt.slot_tok;
+        // gate/up + SwiGLU -> H
+        a.w_a = L->d_gate; a.w_b = L->d_up;
+        a.rows = L->d_ffn; a.kdim = L->d_model; a.ksplit = 1;
+        a.act = x; a.act_is_x = 1; a.act_slot_base = 0;
+        a.h_out = h_routed; a.h_slot_base = 0;
+        rc = launch_stream_gateup(a, false, st);
+        if (rc) return rc;
+        // down -> partial sums
+        a.w_a = L->d_down; a.w_b = nullptr;
+        a.rows = L->d_model; a.kdim = L->d_ffn; a.ksplit = L->ksplit;
+        a.act = h_routed; a.act_is_x = 0; a.act_slot_base = 0;
+        a.h_out = nullptr; a.o_out = opart; a.o_ks_stride = w.o_ks_stride;
+        rc = launch_stream_down(a, false, st);
+        if (rc) return rc;
+    }
+
+    size_t h_off = w.h_shared;
+    for (int s = 0; s < L->n_shared; ++s) {
+        uint16_t *h_s = (uint16_t *)(ws + h_off);
+        h_off += w.h_shared_each(L, T, s);
+        const int32_t slot_base = N + s * T;
+        StreamGroupArgs a = {};
+        a.n_groups = 1;
+        a.dense_tokens = T; a.dense_slot_base = slot_base;
+        a.w_a = L->d_sgate + s; a.w_b = L->d_sup + s;
+        a.rows = L->shared_f[s]; a.kdim = L->d_model; a.ksplit = 1;
+        a.act = x; a.act_is_x = 1; a.act_slot_base = 0;
+        a.h_out = h_s; a.h_slot_base = slot_base;
+        rc = launch_stream_gateup(a, true, st);
+        if (rc) return rc;
+        a.w_a = L->d_sdown + s; a.w_b = nullptr;
+        a.rows = L->d_model; a.kdim = L->shared_f[s]; a.ksplit = L->ksplit;
+        a.act = h_s; a.act_is_x = 0; a.act_slot_base = slot_base;
+        a.h_out = nullptr; a.o_out = opart; a.o_ks_stride = w.o_ks_stride;
+        rc = launch_stream_down(a, true, st);
+        if (rc) return rc;
+    }
+
+    return launch_combine(opart, L->ksplit, w.o_ks_stride, rt, topk_w, T, k, L->d_model, L->n_shared, y, st);
+}
+
+}  // extern "C"

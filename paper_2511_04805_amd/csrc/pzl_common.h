@@ -1,0 +1,70 @@
+// Internal declarations shared by the library's HIP translation units (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "../../include/puzzle_moe.h"
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef short s16x2 __attribute__((ext_vector_type(2)));
+
+namespace pzl {
+
+// 16x32 tiled order: one tile is 512 elements = 64 lanes x 8 elements; lane = (c%32)/8*16 + r%16.
+constexpr int TILE_ROWS = 16;
+constexpr int TILE_COLS = 32;
+constexpr int TILE_ELEMS = TILE_ROWS * TILE_COLS;
+
+// Routing tables in the workspace (all int32).  Experts are renumbered q = 2*pair + pos so
+// that the two experts of a pair own adjacent slot ranges.
+struct RouteTables {
+    int32_t *cnt;        // [Q]    tokens routed to expert q
+    int32_t *off;        // [Q+1]  first slot of expert q
+    int32_t *slot_tok;   // [N]    token index of each slot (slots sorted by q, then by flat index)
+    int32_t *slot_of;    // [N]    slot of flat index t*k+j, or -1 for an id outside [0,E)
+};
+
+void set_hip_error(hipError_t e);
+
+// codec.hip
+int launch_pack(const uint16_t *merged, const uint8_t *m0, const uint8_t *m1, const uint8_t *s0,
+                const uint8_t *s1, int64_t rows, int64_t cols, uint16_t *out, int32_t *n_bad,
+                hipStream_t st);
+int launch_unpack(const uint16_t *packed, int pos, int64_t rows, int64_t cols, uint16_t *out,
+                  hipStream_t st);
+int launch_tile_dense(const uint16_t *in, int64_t rows, int64_t cols, uint16_t *out, hipStream_t st);
+
+// route.hip
+int launch_route(const int32_t *ids, int32_t n_flat, int32_t k, int32_t n_experts, const int32_t *q_of_expert,
+                 RouteTables rt, hipStream_t st);
+int launch_combine(const float *opart, int32_t ksplit, int64_t ks_stride, const RouteTables &rt,
+                   const float *topk_w, int32_t T, int32_t k, int32_t d, int32_t n_shared,
+                   uint16_t *y, hipStream_t st);
+
+// stream_gemm.hip: weight-streaming decode-GEMM for small token counts per pair.
+struct StreamGroupArgs {
+    const uint16_t *const *w_a;   // device array [n_groups]: gate (gate/up stage) or down (down stage)
+    const uint16_t *const *w_b;   // device array [n_groups]: up, or nullptr in the down stage
+    int32_t n_groups;
+    int32_t rows;                 // output features of the stage (f or d)
+    int32_t kdim;                 // contracted dimension (d or f)
+    const uint16_t *act;          // activations [*, kdim] bf16 row-major (x or H)
+    int32_t act_is_x;             // 1: row = slot_tok[slot] (or the token itself if dense); 0: row = slot - act_slot_base
+    int32_t act_slot_base;
+    const int32_t *cnt;           // routed: RouteTables.cnt, dense: nullptr
+    const int32_t *off;
+    const int32_t *slot_tok;
+    int32_t dense_tokens;         // dense groups: every group sees tokens 0..dense_tokens-1
+    int32_t dense_slot_base;      // dense groups: slot of (group g, token t) = base + g*dense_tokens + t
+    uint16_t *h_out;              // gate/up stage: H [slots, rows] bf16, row index = slot - h_slot_base
+    int32_t h_slot_base;
+    float *o_out;                 // down stage: partial sums [ksplit][slots][rows] fp32
+    int64_t o_ks_stride;          // elements between k-splits
+    int32_t ksplit;
+};
+int launch_stream_gateup(const StreamGroupArgs &a, bool dense, hipStream_t st);
+int launch_stream_down(const StreamGroupArgs &a, bool dense, hipStream_t st);
+
+}  // namespace pzl

@@ -1,0 +1,150 @@
+// Token-to-expert grouping and the weighted top-k combine.
+// Neither is in the paper (it leaves routing to the host framework, Sec. 4.1 "other modules
+// unchanged"); they are the glue that lets one packed-pair read serve both experts'
+// token blocks, as the decode-GEMM of Sec. 3.3.2 requires.
+#include "pzl_common.h"
+
+namespace pzl {
+
+constexpr int ROUTE_THREADS = 1024;
+constexpr int ROUTE_WAVES = ROUTE_THREADS / 64;
+constexpr int ROUTE_QMAX = 512;
+
+// Stable counting sort of the flat (token, choice) list by q = 2*pair + pos, one workgroup.
+// Wave w owns the contiguous index range [w*chunk, (w+1)*chunk); slots are ordered by
+// (q, wave, iteration, lane) = (q, flat index), so the result does not depend on timing.
+__global__ void __launch_bounds__(ROUTE_THREADS)
+route_kernel(const int32_t *__restrict__ ids, int32_t n_flat, int32_t k, int32_t n_experts,
+             const int32_t *__restrict__ q_of_expert, int32_t Q, int32_t *__restrict__ cnt,
+             int32_t *__restrict__ off, int32_t *__restrict__ slot_tok, int32_t *__restrict__ slot_of)
+{
+    __shared__ int32_t hist[ROUTE_WAVES][ROUTE_QMAX];
+    __shared__ int32_t total[ROUTE_QMAX];
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    for (int i = tid; i < ROUTE_WAVES * ROUTE_QMAX; i += ROUTE_THREADS) (&hist[0][0])[i] = 0;
+    __syncthreads();
+
+    int chunk = (n_flat + ROUTE_WAVES - 1) / ROUTE_WAVES;
+    chunk = (chunk + 63) & ~63;
+    const int lo = wave * chunk;
+    const int hi = min(n_flat, lo + chunk);
+
+    for (int i = lo; i < hi; i += 64) {
+        int idx = i + lane;
+        if (idx < hi) {
+            int e = ids[idx];
+            if (e >= 0 && e < n_experts) atomicAdd(&hist[wave][q_of_expert[e]], 1);
+        }
+    }
+    __syncthreads();
+    // per-q totals, then turn hist[w][q] into the first slot of (q, wave w)
+    for (int q = tid; q < Q; q += ROUTE_THREADS) {
+        int s = 0;
+        for (int w = 0; w < ROUTE_WAVES; ++w) s += hist[w][q];
+        total[q] = s;
+        cnt[q] = s;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        int run = 0;
+        for (int q = 0; q < Q; ++q) { int c = total[q]; total[q] = run; off[q] = run; run += c; }
+        off[Q] = run;
+    }
+    __syncthreads();
+    for (int q = tid; q < Q; q += ROUTE_THREADS) {
+        int run = total[q];
+        for (int w = 0; w < ROUTE_WAVES; ++w) { int c = hist[w][q]; hist[w][q] = run; run += c; }
+    }
+    __syncthreads();
+
+    for (int i = lo; i < hi; i += 64) {
+        int idx = i + lane;
+        int q = -1;
+        if (idx < hi) {
+            int e = ids[idx];
+            if (e >= 0 && e < n_experts) q = q_of_expert[e]; else slot_of[idx] = -1;
+        }
+        unsigned long long remaining = __ballot(q >= 0);
+        while (remaining) {
+            int leader = __ffsll((long long)remaining) - 1;
+            int qq = __shfl(q, leader);
+            unsigned long long same = __ballot(q == qq);
+            int first = hist[wave][qq];
+            if (q == qq) {
+                int rank = __popcll(same & ((1ull << lane) - 1ull));
+                int slot = first + rank;
+                slot_tok[slot] = idx / k;
+                slot_of[idx] = slot;
+            }
+            if (lane == leader) hist[wave][qq] = first + __popcll(same);
+            remaining &= ~same;
+        }
+    }
+}
+
+__device__ __forceinline__ uint32_t f32_to_bf16_rne(float v)
+{
+    uint32_t u = __float_as_uint(v);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return 0x7FC0u;          // NaN
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+
+// y[t, c] = bf16( sum_j w[t,j] * sum_ks O[ks][slot_of(t,j)][c]  +  sum_s sum_ks O[ks][N + s*T + t][c] )
+// Fixed summation order (j ascending, k-splits ascending inside), so results are reproducible.
+__global__ void __launch_bounds__(256)
+combine_kernel(const float *__restrict__ opart, int32_t ksplit, int64_t ks_stride,
+               const int32_t *__restrict__ slot_of, const float *__restrict__ topk_w, int32_t T,
+               int32_t k, int32_t d, int32_t n_shared, uint16_t *__restrict__ y)
+{
+    const int t = blockIdx.x;
+    const int c = (blockIdx.y * 256 + threadIdx.x) * 4;
+    if (c >= d) return;
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    const int n_flat = T * k;
+    for (int j = 0; j < k; ++j) {
+        int slot = slot_of[t * k + j];
+        if (slot < 0) continue;
+        float w = topk_w[t * k + j];
+        const float *p = opart + (int64_t)slot * d + c;
+        f32x4 s = *(const f32x4 *)p;
+        for (int ks = 1; ks < ksplit; ++ks) s += *(const f32x4 *)(p + ks * ks_stride);
+        acc += w * s;
+    }
+    for (int sh = 0; sh < n_shared; ++sh) {
+        const float *p = opart + (int64_t)(n_flat + sh * T + t) * d + c;
+        f32x4 s = *(const f32x4 *)p;
+        for (int ks = 1; ks < ksplit; ++ks) s += *(const f32x4 *)(p + ks * ks_stride);
+        acc += s;
+    }
+    u32x2 o;
+    o.x = f32_to_bf16_rne(acc.x) | (f32_to_bf16_rne(acc.y) << 16);
+    o.y = f32_to_bf16_rne(acc.z) | (f32_to_bf16_rne(acc.w) << 16);
+    *(u32x2 *)(y + (int64_t)t * d + c) = o;
+}
+
+int launch_route(const int32_t *ids, int32_t n_flat, int32_t k, int32_t n_experts,
+                 const int32_t *q_of_expert, RouteTables rt, hipStream_t st)
+{
+    int Q = n_experts;
+    if (Q > ROUTE_QMAX) return PZL_EINVAL;
+    hipLaunchKernelGGL(route_kernel, dim3(1), dim3(ROUTE_THREADS), 0, st, ids, n_flat, k, n_experts,
+                       q_of_expert, Q, rt.cnt, rt.off, rt.slot_tok, rt.slot_of);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) { set_hip_error(e); return PZL_EHIP; }
+    return PZL_OK;
+}
+
+int launch_combine(const float *opart, int32_t ksplit, int64_t ks_stride, const RouteTables &rt,
+                   const float *topk_w, int32_t T, int32_t k, int32_t d, int32_t n_shared,
+                   uint16_t *y, hipStream_t st)
+{
+    dim3 grid((unsigned)T, (unsigned)((d / 4 + 255) / 256));
+    hipLaunchKernelGGL(combine_kernel, grid, dim3(256), 0, st, opart, ksplit, ks_stride, rt.slot_of,
+                       topk_w, T, k, d, n_shared, y);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) { set_hip_error(e); return PZL_EHIP; }
+    return PZL_OK;
+}
+
+}  // namespace pzl

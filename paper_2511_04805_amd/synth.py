@@ -51,9 +51,9 @@ _GATE, _UP, _DOWN = 0, 1, 2
 _PLANES = ("merged", "mask0", "mask1", "sign0", "sign1")
 
 
-def _gen(cfg, *key):
+def _gen(cfg, device, *key):
     """One independent generator per tensor, so any tensor can be redrawn alone."""
-    g = torch.Generator(device="cpu")
+    g = torch.Generator(device=device)
     s = cfg.seed
     for v in key:
         s = (s * 1000003 + int(v) + 12345) % (2 ** 62)
@@ -61,8 +61,10 @@ def _gen(cfg, *key):
     return g
 
 
-def _bf16_bits(t):
-    return t.to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+def _np_bits(t):
+    """torch int16/uint8 tensor -> numpy (uint16 view for 16-bit patterns)."""
+    a = t.cpu().numpy()
+    return a.view(np.uint16) if a.dtype == np.int16 else a
 
 
 def matrix_shape(cfg, which, d_ffn=None):
@@ -70,35 +72,48 @@ def matrix_shape(cfg, which, d_ffn=None):
     return (cfg.d_model, f) if which == _DOWN else (f, cfg.d_model)
 
 
-def pair_matrix(cfg, pair, which, shape=None):
-    """Inputs of pack for one matrix of one expert pair.
+def pair_matrix_t(cfg, pair, which, shape=None, device="cpu"):
+    """Inputs of pack for one matrix of one expert pair, as torch tensors on ``device``.
 
-    Returns dict(merged uint16 bf16 bits of |N(0, sigma)|, mask0, mask1, sign0, sign1 uint8).
-    Masks are independent Bernoulli(mask_density) per expert, signs Bernoulli(0.5).
+    dict(merged: int16 view of the bf16 bits of |N(0, sigma)|, mask0, mask1, sign0, sign1: uint8).
+    Masks are independent Bernoulli(mask_density) per expert, signs Bernoulli(0.5).  The stream
+    of a CPU generator and of a GPU generator differ; each is reproducible on its own device.
     """
     rows, cols = shape if shape is not None else matrix_shape(cfg, which)
     n = rows * cols
     out = {}
-    g = _gen(cfg, 1, pair, which, 0)
-    out["merged"] = _bf16_bits((torch.randn(n, generator=g) * cfg.sigma).abs_()).reshape(rows, cols)
+    g = _gen(cfg, device, 1, pair, which, 0)
+    mag = (torch.randn(n, generator=g, device=device) * cfg.sigma).abs_()
+    out["merged"] = mag.to(torch.bfloat16).view(torch.int16).reshape(rows, cols)
     for i, name in enumerate(_PLANES[1:], start=1):
-        g = _gen(cfg, 1, pair, which, i)
+        g = _gen(cfg, device, 1, pair, which, i)
         p = cfg.mask_density if name.startswith("mask") else 0.5
-        out[name] = (torch.rand(n, generator=g) < p).to(torch.uint8).numpy().reshape(rows, cols)
+        out[name] = (torch.rand(n, generator=g, device=device) < p).to(torch.uint8).reshape(rows, cols)
     return out
 
 
-def shared_matrix(cfg, s, which):
-    """Dense bf16 bits of one matrix of shared expert ``s`` (signed N(0, sigma))."""
+def pair_matrix(cfg, pair, which, shape=None):
+    """numpy form of pair_matrix_t on the CPU (merged as uint16)."""
+    return {k: _np_bits(v) for k, v in pair_matrix_t(cfg, pair, which, shape).items()}
+
+
+def shared_matrix_t(cfg, s, which, device="cpu"):
+    """Dense bf16 bits (int16 view) of one matrix of shared expert ``s`` (signed N(0, sigma))."""
     rows, cols = matrix_shape(cfg, which, cfg.shared_d_ffn[s])
-    g = _gen(cfg, 2, s, which)
-    return _bf16_bits(torch.randn(rows * cols, generator=g) * cfg.sigma).reshape(rows, cols)
+    g = _gen(cfg, device, 2, s, which)
+    w = torch.randn(rows * cols, generator=g, device=device) * cfg.sigma
+    return w.to(torch.bfloat16).view(torch.int16).reshape(rows, cols)
+
+
+def shared_matrix(cfg, s, which):
+    return _np_bits(shared_matrix_t(cfg, s, which))
 
 
 def tokens(cfg, T):
     """x [T, d_model] bf16 bits, N(0,1)."""
-    g = _gen(cfg, 3, T)
-    return _bf16_bits(torch.randn(T * cfg.d_model, generator=g)).reshape(T, cfg.d_model)
+    g = _gen(cfg, "cpu", 3, T)
+    x = torch.randn(T * cfg.d_model, generator=g).to(torch.bfloat16).view(torch.int16)
+    return _np_bits(x).reshape(T, cfg.d_model)
 
 
 def routing(cfg, T):
@@ -109,7 +124,7 @@ def routing(cfg, T):
     experts sampled without replacement in proportion to p.  Weights are the softmax of
     the selected scores.
     """
-    g = _gen(cfg, 4, T)
+    g = _gen(cfg, "cpu", 4, T)
     E, k = cfg.n_experts, cfg.top_k
     logits = torch.randn(T, E, generator=g)
     if cfg.routing == "zipf":
@@ -136,7 +151,7 @@ def expert_map(cfg, mode="adjacent"):
     if mode == "adjacent":
         order = np.arange(E)
     else:
-        order = torch.randperm(E, generator=_gen(cfg, 5)).numpy()
+        order = torch.randperm(E, generator=_gen(cfg, "cpu", 5)).numpy()
     pair = np.empty(E, dtype=np.int32)
     pos = np.empty(E, dtype=np.uint8)
     pair[order] = np.arange(E) // 2

@@ -1,0 +1,163 @@
+"""GPU parity: the HIP library through its C ABI against the CPU oracle.
+
+Bit-exact for pack / unpack (integer work); |y - y_ref| <= 1e-2 * max(|y_ref|, rms(y_ref)) for
+the FFN (bf16 products, fp32 accumulation, bf16 H and y against the oracle's fp64).
+"""
+import numpy as np
+import pytest
+import torch
+
+from paper_2511_04805_amd import synth
+from helpers import Case, bits_to_f64, tolerance_ok
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def binding():
+    from paper_2511_04805_amd import binding as b
+    b.load()
+    assert torch.cuda.is_available()
+    return b
+
+
+def say(msg):
+    print(msg, flush=True)
+
+
+@pytest.mark.parametrize("shape", [(16, 32), (48, 96), (256, 128), (1408, 2048)])
+def test_pack_unpack_bit_exact(oracle, binding, shape):
+    say("pack/unpack shape=%s" % (shape,))
+    cfg = synth.LayerConfig("codec", 2, 32, 32, 1, (1,), seed=77)
+    pl = synth.pair_matrix(cfg, 0, synth.GATE, shape=shape)
+    # sprinkle the corner cases: zero, below the band, top of the band, out of range, negative input
+    flat = pl["merged"].reshape(-1)
+    flat[:8] = np.array([0x0000, 0x0001, 0x3581, 0x37FF, 0x47FF, 0x4800, 0x7F80, 0xBCA4], dtype=np.uint16)
+    dev = {k: torch.from_numpy(v.view(np.int16) if v.dtype == np.uint16 else v).cuda() for k, v in pl.items()}
+    n_bad = torch.zeros(1, dtype=torch.int32, device="cuda")
+    packed = binding.pzl_pack(dev["merged"], dev["mask0"], dev["mask1"], dev["sign0"], dev["sign1"],
+                              n_out_of_range=n_bad)
+    torch.cuda.synchronize()
+    want, bad = oracle.pack(pl["merged"], pl["mask0"], pl["mask1"], pl["sign0"], pl["sign1"])
+    assert int(n_bad.item()) == bad == 2
+    assert packed.numel() * 2 == binding.pzl_packed_bytes(*shape)
+    got = binding.tiled_to_logical(packed.cpu().numpy().view(np.uint16), *shape)
+    assert np.array_equal(got, want)
+    for pos in (0, 1):
+        out = binding.pzl_unpack(packed, pos, *shape)
+        torch.cuda.synchronize()
+        assert np.array_equal(out.view(torch.int16).cpu().numpy().view(np.uint16), oracle.unpack(want, pos))
+
+
+def test_unpack_all_words(oracle, binding):
+    """Every 16-bit word through the GPU decode, both positions (Algorithm 1 is total)."""
+    words = np.arange(65536, dtype=np.uint16).reshape(64, 1024)
+    # lay the words out so that logical order == value order
+    tiled = np.empty(65536, dtype=np.uint16)
+    r, c = np.divmod(np.arange(65536), 1024)
+    tiled[((r // 16) * 32 + c // 32) * 512 + (((c % 32) // 8) * 16 + r % 16) * 8 + c % 8] = words.reshape(-1)
+    t = torch.from_numpy(tiled.view(np.int16)).cuda()
+    for pos in (0, 1):
+        out = binding.pzl_unpack(t, pos, 64, 1024)
+        torch.cuda.synchronize()
+        assert np.array_equal(out.view(torch.int16).cpu().numpy().view(np.uint16), oracle.unpack(words, pos))
+
+
+def test_tile_dense_roundtrip(binding):
+    a = torch.arange(64 * 96, dtype=torch.int16, device="cuda").reshape(64, 96)
+    t = binding.pzl_tile_dense(a)
+    torch.cuda.synchronize()
+    assert np.array_equal(binding.tiled_to_logical(t.cpu().numpy(), 64, 96), a.cpu().numpy())
+
+
+def check(case, T, label, ids=None, w=None, x=None, ref_rows=None):
+    cfg = case.cfg
+    say("moe_ffn %s T=%d" % (label, T))
+    x = synth.tokens(cfg, T) if x is None else x
+    if ids is None:
+        ids, w = synth.routing(cfg, T)
+    y = case.gpu(x, ids, w)
+    rows = np.arange(T) if ref_rows is None else np.asarray(ref_rows)
+    y64, _ = case.ref(x[rows], ids[rows], w[rows])
+    ok, worst = tolerance_ok(y[rows], y64)
+    say("  worst err / bound = %.3f" % worst)
+    assert ok, worst
+    return y, y64
+
+
+def test_tiny_config(oracle, binding):
+    case = Case(synth.CONFIGS["tiny"], oracle, binding)
+    y, y64 = check(case, 8, "tiny")
+    assert np.abs(y64).max() > 0
+
+
+SMALL = synth.LayerConfig("small", 6, 192, 352, 2, (40,), shared_d_ffn=(96, 160), seed=31)
+
+
+@pytest.fixture(scope="module")
+def small_case(oracle, binding):
+    return Case(SMALL, oracle, binding, emap_mode="random")
+
+
+@pytest.mark.parametrize("T", [1, 2, 7, 16, 17, 40, 100, 300])
+def test_small_layer_token_counts(small_case, T):
+    """Ragged tails, one/several token tiles per expert, several passes, shared experts."""
+    check(small_case, T, "small")
+
+
+def test_edge_cases(small_case, binding):
+    cfg, case = SMALL, small_case
+    T = 24
+    x = synth.tokens(cfg, T)
+    ids, w = synth.routing(cfg, T)
+    # an expert with no tokens, a pair with no tokens
+    ids0 = ids.copy(); ids0[ids0 == 3] = 0
+    check(case, T, "expert-empty", ids=ids0, w=w, x=x)
+    emap = case.emap
+    only = np.array([e for e in range(cfg.n_experts) if emap[0][e] == 0], dtype=np.int32)
+    ids1 = np.tile(only[None, :], (T, 1)).astype(np.int32)
+    check(case, T, "single-pair", ids=ids1, w=w, x=x)
+    # duplicate ids within a token add up
+    ids2 = np.repeat(ids[:, :1], 2, axis=1).copy()
+    check(case, T, "duplicates", ids=ids2, w=w, x=x)
+    # ids outside [0,E) are ignored
+    ids3 = ids.copy(); ids3[::3, 1] = cfg.n_experts + 5; ids3[1::3, 1] = -1
+    y = case.gpu(x, ids3, w)
+    w3 = w.copy(); w3[::3, 1] = 0; w3[1::3, 1] = 0
+    y64, _ = case.ref(x, np.where((ids3 < 0) | (ids3 >= cfg.n_experts), 0, ids3).astype(np.int32), w3)
+    assert tolerance_ok(y, y64)[0]
+    # T = 0 is a no-op, and results are reproducible bit for bit
+    empty = case.layer.pzl_moe_ffn(torch.empty(0, cfg.d_model, dtype=torch.bfloat16, device="cuda"),
+                                   torch.empty(0, 2, dtype=torch.int32, device="cuda"),
+                                   torch.empty(0, 2, dtype=torch.float32, device="cuda"))
+    assert empty.shape == (0, cfg.d_model)
+    ya = case.gpu(x, ids, w); yb = case.gpu(x, ids, w)
+    assert np.array_equal(ya, yb)
+    # token-permutation equivariance, exactly
+    perm = np.random.RandomState(0).permutation(T)
+    yp = case.gpu(x[perm], ids[perm], w[perm])
+    assert np.array_equal(yp, ya[perm])
+
+
+def test_error_codes(small_case, binding):
+    cfg, case = SMALL, small_case
+    lib = binding.load()
+    x = torch.zeros(4, cfg.d_model, dtype=torch.bfloat16, device="cuda")
+    ids = torch.zeros(4, 2, dtype=torch.int32, device="cuda")
+    w = torch.zeros(4, 2, dtype=torch.float32, device="cuda")
+    small_ws = torch.empty(256, dtype=torch.uint8, device="cuda")
+    with pytest.raises(binding.PzlError) as ei:
+        case.layer.pzl_moe_ffn(x, ids, w, workspace=small_ws)
+    assert ei.value.rc == binding.PZL_ENOSPC
+    with pytest.raises(binding.PzlError) as ei:
+        binding.pzl_unpack(torch.zeros(16 * 32, dtype=torch.int16, device="cuda"), 2, 16, 32)
+    assert ei.value.rc == binding.PZL_EINVAL
+    with pytest.raises(binding.PzlError) as ei:
+        binding.pzl_unpack(torch.zeros(15 * 32, dtype=torch.int16, device="cuda"), 0, 15, 32)
+    assert ei.value.rc == binding.PZL_EINVAL
+    with pytest.raises(binding.PzlError):      # pair map that is not a 2-to-1 cover
+        binding.Layer(cfg.d_model, cfg.d_ffn, [0, 0, 0, 1, 2, 2], [0, 1, 0, 1, 0, 1],
+                      [case.packed_gpu[p, synth.GATE] for p in range(3)],
+                      [case.packed_gpu[p, synth.UP] for p in range(3)],
+                      [case.packed_gpu[p, synth.DOWN] for p in range(3)])
+    assert lib.pzl_moe_ffn_workspace_bytes(case.layer._h, -1, 2) == 0
