@@ -1,0 +1,210 @@
+#!/usr/bin/env python3
+"""Benchmark of the bit-packed merged-expert MoE FFN on one MI355X.
+
+A step is one pzl_moe_ffn call (route -> gate/up decode-GEMM + SwiGLU -> down decode-GEMM ->
+combine) over one batch of synthetic tokens on a Mixtral-8x7B-shaped layer whose 8 experts are
+merged into 4 packed pairs (the decode-time configuration the metric is quoted on).  Inputs
+and weights are resident in HBM before the timed region.  Prints one JSON line.
+"""
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+import numpy as np
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+from paper_2511_04805_amd import binding, synth  # noqa: E402
+
+HBM_PEAK_GBS = 8000.0
+W3 = (synth.GATE, synth.UP, synth.DOWN)
+
+
+class Hip:
+    """The few HIP runtime calls the benchmark needs for its own event timing."""
+
+    def __init__(self):
+        self.lib = ctypes.CDLL("libamdhip64.so")
+        self.lib.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+        self.lib.hipEventRecord.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
+        self.lib.hipEventSynchronize.argtypes = [ctypes.c_void_p]
+        self.lib.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+        self.lib.hipEventDestroy.argtypes = [ctypes.c_void_p]
+
+    def event(self):
+        e = ctypes.c_void_p()
+        assert self.lib.hipEventCreate(ctypes.byref(e)) == 0
+        return e
+
+    def record(self, e, stream):
+        assert self.lib.hipEventRecord(e, ctypes.c_void_p(stream)) == 0
+
+    def elapsed_ms(self, a, b):
+        assert self.lib.hipEventSynchronize(b) == 0
+        ms = ctypes.c_float()
+        assert self.lib.hipEventElapsedTime(ctypes.byref(ms), a, b) == 0
+        return ms.value
+
+
+def build_layer(cfg, keep_planes_for=None):
+    """Generate on the GPU, pack with the library.  Optionally hand each matrix's pack inputs
+    (host copies) to ``keep_planes_for(pair, which, planes)`` for the CPU baseline."""
+    packed = {}
+    n_bad = torch.zeros(1, dtype=torch.int32, device="cuda")
+    for p in range(cfg.n_pairs):
+        for which in W3:
+            pl = synth.pair_matrix_t(cfg, p, which, device="cuda")
+            packed[p, which] = binding.pzl_pack(pl["merged"], pl["mask0"], pl["mask1"], pl["sign0"],
+                                                pl["sign1"], n_out_of_range=n_bad)
+            if keep_planes_for is not None:
+                keep_planes_for(p, which, {k: synth._np_bits(v) for k, v in pl.items()})
+            del pl
+    shared = []
+    for s, fs in enumerate(cfg.shared_d_ffn):
+        shared.append(tuple(binding.pzl_tile_dense(synth.shared_matrix_t(cfg, s, w, device="cuda"))
+                            for w in W3) + (fs,))
+    emap = synth.expert_map(cfg)
+    P = cfg.n_pairs
+    layer = binding.Layer(cfg.d_model, cfg.d_ffn, emap[0], emap[1],
+                          [packed[p, synth.GATE] for p in range(P)], [packed[p, synth.UP] for p in range(P)],
+                          [packed[p, synth.DOWN] for p in range(P)], shared=shared)
+    torch.cuda.synchronize()
+    assert int(n_bad.item()) == 0
+    return layer, emap
+
+
+def batch(cfg, T):
+    x = synth.tokens(cfg, T)
+    ids, w = synth.routing(cfg, T)
+    return (x, ids, w, torch.from_numpy(x.view(np.int16)).cuda(), torch.from_numpy(ids).cuda(),
+            torch.from_numpy(w).cuda())
+
+
+def touched_pairs(ids, emap):
+    return len(set(int(emap[0][e]) for e in np.unique(ids)))
+
+
+def time_steps(hip, layer, xt, idt, wt, steps, warmup, stage="gateup"):
+    """K timed steps bracketed by synchronisation; events around one stage of every step."""
+    y = torch.empty(xt.shape[0], layer.d_model, dtype=torch.bfloat16, device="cuda")
+    stream = torch.cuda.current_stream().cuda_stream
+    si = binding.STAGES.index(stage)
+    evs = []
+    for _ in range(steps):
+        arr = (ctypes.c_void_p * (2 * len(binding.STAGES)))()
+        a, b = hip.event(), hip.event()
+        arr[2 * si], arr[2 * si + 1] = a, b
+        evs.append((arr, a, b))
+    for _ in range(warmup):
+        layer.pzl_moe_ffn(xt, idt, wt, y=y)
+    t0, t1 = hip.event(), hip.event()
+    torch.cuda.synchronize()
+    wall0 = time.perf_counter()
+    hip.record(t0, stream)
+    for arr, _, _ in evs:
+        layer.pzl_moe_ffn(xt, idt, wt, y=y, stage_events=arr)
+    hip.record(t1, stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - wall0
+    total_ms = hip.elapsed_ms(t0, t1)
+    stage_ms = [hip.elapsed_ms(a, b) for _, a, b in evs]
+    for _, a, b in evs:
+        hip.lib.hipEventDestroy(a); hip.lib.hipEventDestroy(b)
+    return total_ms / steps, float(np.mean(stage_ms)), wall * 1e3 / steps, y
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--tokens", type=int, default=64, help="decode batch size (1, 8, 32 or 64)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-sweep", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (--gpus must be 1)", file=sys.stderr)
+        sys.exit(2)
+    if not torch.cuda.is_available():
+        print("bench.py needs an MI355X; no GPU is visible", file=sys.stderr)
+        sys.exit(2)
+    binding.load()
+    hip = Hip()
+    cfg = synth.CONFIGS["mixtral_decode"]
+    T = args.tokens
+
+    want_cpu = not args.no_cpu_baseline
+    cpu_packed = {}
+    if want_cpu:
+        import oracle  # CPU-baseline leg only
+
+        def keep(p, which, planes):
+            cpu_packed[p, which] = oracle.pack(planes["merged"], planes["mask0"], planes["mask1"],
+                                               planes["sign0"], planes["sign1"])[0]
+    layer, emap = build_layer(cfg, keep if want_cpu else None)
+
+    x, ids, w, xt, idt, wt = batch(cfg, T)
+    ms_step, ms_gateup, ms_wall, y = time_steps(hip, layer, xt, idt, wt, args.steps, args.warmup)
+    n_touched = touched_pairs(ids, emap)
+    d, f, k = cfg.d_model, cfg.d_ffn, cfg.top_k
+    pair_bytes_gateup = 2 * f * d * 2
+    alg_bytes = n_touched * pair_bytes_gateup + T * d * 2 + T * k * f * 2   # packed gate+up once, x, H
+    achieved = alg_bytes / (ms_gateup * 1e-3) / 1e9
+
+    out = {
+        "metric": "MoE-FFN tokens/sec at 1 MI355X; achieved HBM GB/s (decode)",
+        "value": T / (ms_step * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "mixtral_decode_T%d" % T, "layer": "Mixtral-8x7B-shaped, 8 experts -> 4 packed pairs",
+                   "d_model": d, "d_ffn": f, "top_k": k, "tokens": T, "touched_pairs": n_touched},
+        "roofline": {"bound": "hbm", "kernel": "stream_kernel<gate/up + SwiGLU>", "achieved": achieved,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": None, "algorithmic_bytes": alg_bytes, "avg_launch_ms": ms_gateup},
+        "ms_per_step_host_wall": ms_wall,
+    }
+    path_bytes = n_touched * 3 * f * d * 2
+    out["path_hbm_frac"] = path_bytes / (ms_step * 1e-3) / 1e9 / HBM_PEAK_GBS
+
+    if not args.no_sweep:
+        sweep = {}
+        for Ts in (1, 8, 32, 64):
+            if Ts == T:
+                sweep[str(Ts)] = {"tokens_per_s": out["value"], "ms_per_step": ms_step,
+                                  "gateup_GBs": achieved}
+                continue
+            xs, ids_s, ws, xts, idts, wts = batch(cfg, Ts)
+            ms, msg, _, _ = time_steps(hip, layer, xts, idts, wts, max(20, args.steps // 4), 5)
+            nt = touched_pairs(ids_s, emap)
+            sweep[str(Ts)] = {"tokens_per_s": Ts / (ms * 1e-3), "ms_per_step": ms, "touched_pairs": nt,
+                              "gateup_GBs": (nt * pair_bytes_gateup) / (msg * 1e-3) / 1e9}
+        out["sweep"] = sweep
+
+    if want_cpu:
+        import oracle
+        P = cfg.n_pairs
+        n_sample = min(T, 64)
+        t0 = time.perf_counter()
+        y64, _ = oracle.moe_ffn(x[:n_sample], ids[:n_sample], w[:n_sample], emap[0], emap[1],
+                                [cpu_packed[p, synth.GATE] for p in range(P)],
+                                [cpu_packed[p, synth.UP] for p in range(P)],
+                                [cpu_packed[p, synth.DOWN] for p in range(P)])
+        dt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": n_sample / dt, "unit": "tokens/s",
+                               "cores": int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1)),
+                               "kind": "oracle",
+                               "sample": "first %d tokens of the same batch, fp64 oracle, %.1f s" % (n_sample, dt)}
+        yg = y[:n_sample].float().cpu().numpy().astype(np.float64)
+        rms = float(np.sqrt(np.mean(y64 ** 2)))
+        out["parity_sample"] = {"worst_err_over_bound":
+                                float((np.abs(yg - y64) / (1e-2 * np.maximum(np.abs(y64), rms))).max())}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -145,6 +145,29 @@ int pzl_moe_ffn(const pzl_layer *layer, const uint16_t *x, const int32_t *topk_i
                 const float *topk_w, int32_t T, int32_t k, uint16_t *y,
                 void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * Measurement variant of pzl_moe_ffn: the same launches on the same stream, and in addition the
+ * caller's hipEvent_t handles are recorded around each stage, so that a benchmark can time one
+ * kernel of the path with events on the stream the kernel really runs on.
+ *   stage_events  host array of 2*PZL_N_STAGES hipEvent_t (as void*), created by the caller
+ *                 with timing enabled; [2*s] is recorded before and [2*s+1] after stage s.
+ *                 NULL entries are skipped; a NULL array makes the call identical to
+ *                 pzl_moe_ffn.
+ * Stages: the token grouping, the routed gate/up decode-GEMM with SwiGLU (the kernel the
+ * decode-time roofline is quoted on), the routed down decode-GEMM, all shared-expert work,
+ * and the weighted combine.
+ */
+#define PZL_STAGE_ROUTE   0
+#define PZL_STAGE_GATEUP  1
+#define PZL_STAGE_DOWN    2
+#define PZL_STAGE_SHARED  3
+#define PZL_STAGE_COMBINE 4
+#define PZL_N_STAGES      5
+int pzl_moe_ffn_staged(const pzl_layer *layer, const uint16_t *x, const int32_t *topk_ids,
+                       const float *topk_w, int32_t T, int32_t k, uint16_t *y,
+                       void *workspace, size_t workspace_bytes, void *stream,
+                       void *const *stage_events);
+
 #ifdef __cplusplus
 }
 #endif

@@ -18,7 +18,9 @@ PZL_OK, PZL_EINVAL, PZL_ENOSPC, PZL_EHIP, PZL_ENOMEM = 0, -1, -2, -3, -4
 
 EXPORTS = ("pzl_abi_version", "pzl_strerror", "pzl_last_hip_error", "pzl_packed_bytes", "pzl_pack",
            "pzl_unpack", "pzl_tile_dense", "pzl_layer_create", "pzl_layer_destroy",
-           "pzl_moe_ffn_workspace_bytes", "pzl_moe_ffn")
+           "pzl_moe_ffn_workspace_bytes", "pzl_moe_ffn", "pzl_moe_ffn_staged")
+
+STAGES = ("route", "gateup", "down", "shared", "combine")
 
 
 class PzlError(RuntimeError):
@@ -69,6 +71,8 @@ def load():
         lib.pzl_moe_ffn_workspace_bytes.argtypes = [vp, i32, i32]
         lib.pzl_moe_ffn.restype = ctypes.c_int
         lib.pzl_moe_ffn.argtypes = [vp, vp, vp, vp, i32, i32, vp, vp, ctypes.c_size_t, vp]
+        lib.pzl_moe_ffn_staged.restype = ctypes.c_int
+        lib.pzl_moe_ffn_staged.argtypes = [vp, vp, vp, vp, i32, i32, vp, vp, ctypes.c_size_t, vp, vp]
         _lib = lib
     return _lib
 
@@ -186,8 +190,11 @@ class Layer:
     def pzl_moe_ffn_workspace_bytes(self, max_tokens, top_k):
         return load().pzl_moe_ffn_workspace_bytes(self._h, int(max_tokens), int(top_k))
 
-    def pzl_moe_ffn(self, x, topk_ids, topk_w, y=None, workspace=None):
-        """moe_ffn(x, router top-k ids/weights, packed experts) -> y (bfloat16 [T, d_model])."""
+    def pzl_moe_ffn(self, x, topk_ids, topk_w, y=None, workspace=None, stage_events=None):
+        """moe_ffn(x, router top-k ids/weights, packed experts) -> y (bfloat16 [T, d_model]).
+
+        stage_events: optional ctypes array of 2*len(STAGES) hipEvent_t handles (0 = skip); when
+        given, the call goes through pzl_moe_ffn_staged."""
         T = x.shape[0]
         k = topk_ids.shape[1] if topk_ids.dim() == 2 else 0
         if y is None:
@@ -199,10 +206,14 @@ class Layer:
             if self._ws is None or self._ws.numel() < need:
                 self._ws = torch.empty(need, dtype=torch.uint8, device=x.device)
             workspace = self._ws
-        rc = load().pzl_moe_ffn(self._h, _dev(x, _BITS16, "x"), _dev(topk_ids, (torch.int32,), "topk_ids"),
-                                _dev(topk_w, (torch.float32,), "topk_w"), T, k, _dev(y, _BITS16, "y"),
-                                _dev(workspace, (torch.uint8,), "workspace"), workspace.numel(), _stream())
-        _check(rc, "pzl_moe_ffn")
+        args = (self._h, _dev(x, _BITS16, "x"), _dev(topk_ids, (torch.int32,), "topk_ids"),
+                _dev(topk_w, (torch.float32,), "topk_w"), T, k, _dev(y, _BITS16, "y"),
+                _dev(workspace, (torch.uint8,), "workspace"), workspace.numel(), _stream())
+        if stage_events is None:
+            _check(load().pzl_moe_ffn(*args), "pzl_moe_ffn")
+        else:
+            _check(load().pzl_moe_ffn_staged(*args, ctypes.cast(stage_events, ctypes.c_void_p)),
+                   "pzl_moe_ffn_staged")
         return y
 
 

@@ -204,6 +204,20 @@ size_t pzl_moe_ffn_workspace_bytes(const pzl_layer *layer, int32_t max_tokens, i
 int pzl_moe_ffn(const pzl_layer *L, const uint16_t *x, const int32_t *topk_ids, const float *topk_w,
                 int32_t T, int32_t k, uint16_t *y, void *workspace, size_t workspace_bytes, void *stream)
 {
+    return pzl_moe_ffn_staged(L, x, topk_ids, topk_w, T, k, y, workspace, workspace_bytes, stream, nullptr);
+}
+
+int pzl_moe_ffn_staged(const pzl_layer *L, const uint16_t *x, const int32_t *topk_ids, const float *topk_w,
+                       int32_t T, int32_t k, uint16_t *y, void *workspace, size_t workspace_bytes,
+                       void *stream, void *const *stage_events)
+{
+    // records the caller's events around a stage; a failed record is reported like a failed launch
+    auto mark = [&](int stage, int end) -> int {
+        if (!stage_events || !stage_events[2 * stage + end]) return PZL_OK;
+        hipError_t e = hipEventRecord((hipEvent_t)stage_events[2 * stage + end], (hipStream_t)stream);
+        if (e != hipSuccess) { set_hip_error(e); return PZL_EHIP; }
+        return PZL_OK;
+    };
     if (!L || T < 0 || k < 0) return PZL_EINVAL;
     if (T == 0) return PZL_OK;
     if (!x || !y || (k > 0 && (!topk_ids || !topk_w)) || !workspace) return PZL_EINVAL;
@@ -222,8 +236,11 @@ int pzl_moe_ffn(const pzl_layer *L, const uint16_t *x, const int32_t *topk_ids, 
     uint16_t *h_routed = (uint16_t *)(ws + w.h_routed);
     float *opart = (float *)(ws + w.opart);
 
-    int rc = launch_route(topk_ids, N, k, L->n_experts, L->d_q_of_expert, rt, st);
+    int rc = mark(PZL_STAGE_ROUTE, 0);
     if (rc) return rc;
+    rc = launch_route(topk_ids, N, k, L->n_experts, L->d_q_of_expert, rt, st);
+    if (rc) return rc;
+    if ((rc = mark(PZL_STAGE_ROUTE, 1))) return rc;
 
     if (N > 0) {
         StreamGroupArgs a = {};
@@ -234,17 +251,22 @@ int pzl_moe_ffn(const pzl_layer *L, const uint16_t *x, const int32_t *topk_ids, 
         a.rows = L->d_ffn; a.kdim = L->d_model; a.ksplit = 1;
         a.act = x; a.act_is_x = 1; a.act_slot_base = 0;
         a.h_out = h_routed; a.h_slot_base = 0;
+        if ((rc = mark(PZL_STAGE_GATEUP, 0))) return rc;
         rc = launch_stream_gateup(a, false, st);
         if (rc) return rc;
+        if ((rc = mark(PZL_STAGE_GATEUP, 1))) return rc;
         // down -> partial sums
         a.w_a = L->d_down; a.w_b = nullptr;
         a.rows = L->d_model; a.kdim = L->d_ffn; a.ksplit = L->ksplit;
         a.act = h_routed; a.act_is_x = 0; a.act_slot_base = 0;
         a.h_out = nullptr; a.o_out = opart; a.o_ks_stride = w.o_ks_stride;
+        if ((rc = mark(PZL_STAGE_DOWN, 0))) return rc;
         rc = launch_stream_down(a, false, st);
         if (rc) return rc;
+        if ((rc = mark(PZL_STAGE_DOWN, 1))) return rc;
     }
 
+    if ((rc = mark(PZL_STAGE_SHARED, 0))) return rc;
     size_t h_off = w.h_shared;
     for (int s = 0; s < L->n_shared; ++s) {
         uint16_t *h_s = (uint16_t *)(ws + h_off);
@@ -267,7 +289,11 @@ int pzl_moe_ffn(const pzl_layer *L, const uint16_t *x, const int32_t *topk_ids, 
         if (rc) return rc;
     }
 
-    return launch_combine(opart, L->ksplit, w.o_ks_stride, rt, topk_w, T, k, L->d_model, L->n_shared, y, st);
+    if ((rc = mark(PZL_STAGE_SHARED, 1))) return rc;
+    if ((rc = mark(PZL_STAGE_COMBINE, 0))) return rc;
+    rc = launch_combine(opart, L->ksplit, w.o_ks_stride, rt, topk_w, T, k, L->d_model, L->n_shared, y, st);
+    if (rc) return rc;
+    return mark(PZL_STAGE_COMBINE, 1);
 }
 
 }  // extern "C"
