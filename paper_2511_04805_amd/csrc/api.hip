@@ -37,9 +37,10 @@ namespace pzl {
 struct WorkspaceLayout {
     size_t cnt, off, slot_tok, slot_of, h_routed, h_shared, opart, total;
     int64_t o_ks_stride;      // elements between k-splits of the partial-sum buffer
+    // H is held as two bf16 planes (hi, lo), the lo plane right after the hi plane
     size_t h_shared_each(const pzl_layer *L, int32_t T, int s) const
     {
-        return align_up((size_t)T * L->shared_f[s] * 2, 256);
+        return align_up((size_t)2 * T * L->shared_f[s] * 2, 256);
     }
 };
 
@@ -53,7 +54,7 @@ static WorkspaceLayout carve(const pzl_layer *L, int32_t T, int32_t k)
     w.off = p;       p += align_up(((size_t)L->n_experts + 1) * 4, 256);
     w.slot_tok = p;  p += align_up(N * 4, 256);
     w.slot_of = p;   p += align_up(N * 4, 256);
-    w.h_routed = p;  p += align_up(N * L->d_ffn * 2, 256);
+    w.h_routed = p;  p += align_up(2 * N * L->d_ffn * 2, 256);
     w.h_shared = p;
     for (int s = 0; s < L->n_shared; ++s) p += w.h_shared_each(L, T, s);
     w.o_ks_stride = (int64_t)slots * L->d_model;
@@ -64,10 +65,9 @@ static WorkspaceLayout carve(const pzl_layer *L, int32_t T, int32_t k)
 
 static int choose_ksplit(int n_groups, int rows)
 {
-    // The down projection has only rows/64 workgroups per pair; split its long K so that a
+    // The down projection has only rows/128 workgroups per pair; split its long K so that a
     // launch has at least ~4 workgroups per compute unit (256 CUs).
-    int row_groups = (rows / TILE_ROWS + 3) / 4;
-    int64_t wgs = (int64_t)n_groups * row_groups;
+    int64_t wgs = (int64_t)n_groups * stream_row_groups(rows, true);
     int ks = (int)((1024 + wgs - 1) / wgs);
     if (ks < 1) ks = 1;
     if (ks > 8) ks = 8;
@@ -250,7 +250,7 @@ int pzl_moe_ffn_staged(const pzl_layer *L, const uint16_t *x, const int32_t *top
         a.w_a = L->d_gate; a.w_b = L->d_up;
         a.rows = L->d_ffn; a.kdim = L->d_model; a.ksplit = 1;
         a.act = x; a.act_is_x = 1; a.act_slot_base = 0;
-        a.h_out = h_routed; a.h_slot_base = 0;
+        a.h_out = h_routed; a.h_slot_base = 0; a.h_plane_stride = (int64_t)N * L->d_ffn;
         if ((rc = mark(PZL_STAGE_GATEUP, 0))) return rc;
         rc = launch_stream_gateup(a, false, st);
         if (rc) return rc;
@@ -258,7 +258,7 @@ int pzl_moe_ffn_staged(const pzl_layer *L, const uint16_t *x, const int32_t *top
         // down -> partial sums
         a.w_a = L->d_down; a.w_b = nullptr;
         a.rows = L->d_model; a.kdim = L->d_ffn; a.ksplit = L->ksplit;
-        a.act = h_routed; a.act_is_x = 0; a.act_slot_base = 0;
+        a.act = h_routed; a.act_is_x = 0; a.act_slot_base = 0; a.act_plane_stride = (int64_t)N * L->d_ffn;
         a.h_out = nullptr; a.o_out = opart; a.o_ks_stride = w.o_ks_stride;
         if ((rc = mark(PZL_STAGE_DOWN, 0))) return rc;
         rc = launch_stream_down(a, false, st);
@@ -278,12 +278,12 @@ int pzl_moe_ffn_staged(const pzl_layer *L, const uint16_t *x, const int32_t *top
         a.w_a = L->d_sgate + s; a.w_b = L->d_sup + s;
         a.rows = L->shared_f[s]; a.kdim = L->d_model; a.ksplit = 1;
         a.act = x; a.act_is_x = 1; a.act_slot_base = 0;
-        a.h_out = h_s; a.h_slot_base = slot_base;
+        a.h_out = h_s; a.h_slot_base = slot_base; a.h_plane_stride = (int64_t)T * L->shared_f[s];
         rc = launch_stream_gateup(a, true, st);
         if (rc) return rc;
         a.w_a = L->d_sdown + s; a.w_b = nullptr;
         a.rows = L->d_model; a.kdim = L->shared_f[s]; a.ksplit = L->ksplit;
-        a.act = h_s; a.act_is_x = 0; a.act_slot_base = slot_base;
+        a.act = h_s; a.act_is_x = 0; a.act_slot_base = slot_base; a.act_plane_stride = (int64_t)T * L->shared_f[s];
         a.h_out = nullptr; a.o_out = opart; a.o_ks_stride = w.o_ks_stride;
         rc = launch_stream_down(a, true, st);
         if (rc) return rc;

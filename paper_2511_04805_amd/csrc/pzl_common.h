@@ -50,7 +50,8 @@ struct StreamGroupArgs {
     int32_t n_groups;
     int32_t rows;                 // output features of the stage (f or d)
     int32_t kdim;                 // contracted dimension (d or f)
-    const uint16_t *act;          // activations [*, kdim] bf16 row-major (x or H)
+    const uint16_t *act;          // activations [*, kdim] bf16 row-major (x, or the hi plane of H)
+    int64_t act_plane_stride;     // down stage: elements from the hi plane of H to its lo plane
     int32_t act_is_x;             // 1: row = slot_tok[slot] (or the token itself if dense); 0: row = slot - act_slot_base
     int32_t act_slot_base;
     const int32_t *cnt;           // routed: RouteTables.cnt, dense: nullptr
@@ -58,12 +59,14 @@ struct StreamGroupArgs {
     const int32_t *slot_tok;
     int32_t dense_tokens;         // dense groups: every group sees tokens 0..dense_tokens-1
     int32_t dense_slot_base;      // dense groups: slot of (group g, token t) = base + g*dense_tokens + t
-    uint16_t *h_out;              // gate/up stage: H [slots, rows] bf16, row index = slot - h_slot_base
+    uint16_t *h_out;              // gate/up stage: H hi plane [slots, rows] bf16, row index = slot - h_slot_base
+    int64_t h_plane_stride;       // elements from the hi plane to the lo plane
     int32_t h_slot_base;
     float *o_out;                 // down stage: partial sums [ksplit][slots][rows] fp32
     int64_t o_ks_stride;          // elements between k-splits
     int32_t ksplit;
 };
+int stream_row_groups(int rows, bool down_stage);   // workgroups along the output rows
 int launch_stream_gateup(const StreamGroupArgs &a, bool dense, hipStream_t st);
 int launch_stream_down(const StreamGroupArgs &a, bool dense, hipStream_t st);
 

@@ -6,33 +6,47 @@
 // packed tiles (1 KiB contiguous, one 128-bit load per lane) straight into registers in
 // matrix-core operand order, decodes them for position 0 and position 1 with packed 16-bit
 // integer ops, and feeds v_mfma_f32_16x16x32_bf16 with the tokens of each expert as the
-// other operand.  The kernel is HBM-bound: its job is to keep enough loads in flight and
-// to keep the decode under the VALU budget.
+// other operand.  The kernels are HBM-bound: their job is to keep the load queue full and
+// the decode under the VALU budget.
 //
-// Workgroup = 4 waves = 4 adjacent row tiles sharing the staged activations in LDS
-// (double-buffered chunks of 8 k-blocks).  Token tiles: up to MAX_TILES tiles of 16 tokens per
-// pass, the tiles of position 0 first; longer token lists take further passes (re-streaming
-// the weights), which is only the fallback — large batches belong to the tiled GEMM path.
+// Every wave owns two weight streams: in the gate/up stage the same row tile of the gate and
+// of the up matrix (SwiGLU needs both), in the down stage two adjacent row tiles of the down
+// matrix.  A workgroup is 4 waves sharing the staged activations in LDS (double-buffered
+// chunks of k-blocks).  Token tiles: up to SG_MAX_TILES tiles of 16 tokens per pass, the tiles
+// of position 0 first; longer token lists take further passes (re-streaming the weights) —
+// only a fallback, large batches belong to the tiled GEMM path.
+//
+// The SwiGLU output H is kept as two bf16 planes, hi = bf16(h) and lo = bf16(h - hi), and the
+// down stage multiplies both (the matrix cores idle in this kernel anyway).  One bf16 plane
+// alone would put the rounding of H (2^-9 relative per element) straight into y and leave no
+// margin under the 1e-2 output tolerance.
 #include "pzl_common.h"
 
 namespace pzl {
 
+#ifndef SG_DEPTH_N
+#define SG_DEPTH_N 4
+#endif
 constexpr int SG_WAVES = 4;
 constexpr int SG_THREADS = SG_WAVES * 64;
-constexpr int SG_KCB = 8;            // k-blocks of 32 per staged chunk == weight prefetch depth
-constexpr int SG_MAX_TILES = 4;      // token tiles per pass (both positions together)
-constexpr int SG_POS_TILES = 2;      // token tiles per pass per position (routed groups)
-constexpr int SG_LDS_BYTES = 2 * SG_MAX_TILES * SG_KCB * 64 * 16;   // 64 KiB
+constexpr int SG_DEPTH = SG_DEPTH_N;   // weight k-blocks in flight per stream
+constexpr int SG_MAX_TILES = 4;        // token tiles per pass (both positions together)
+constexpr int SG_POS_TILES = 2;        // token tiles per pass per position (routed groups)
+constexpr int SG_FRAGS = 32;           // staged 1 KiB fragments per LDS buffer
+constexpr int SG_LDS_BYTES = 2 * SG_FRAGS * 64 * 16;   // 64 KiB, two buffers
+constexpr int STAGE_GATEUP = 0, STAGE_DOWN = 1;
 
 struct SgArgs {
     const uint16_t *const *w_a;
     const uint16_t *const *w_b;
     int32_t rows, kdim, ksplit;
     const uint16_t *act;
+    int64_t act_plane_stride;
     int32_t act_is_x, act_slot_base;
     const int32_t *cnt, *off, *slot_tok;
     int32_t dense_tokens, dense_slot_base;
     uint16_t *h_out;
+    int64_t h_plane_stride;
     int32_t h_slot_base;
     float *o_out;
     int64_t o_ks_stride;
@@ -74,15 +88,28 @@ __device__ __forceinline__ uint32_t f32_to_bf16_rne_sg(float v)
 
 __device__ __forceinline__ float silu_f32(float g) { return g / (1.0f + __expf(-g)); }
 
+// h = silu(g) * u  ->  hi = bf16(h), lo = bf16(h - hi)
+__device__ __forceinline__ void swiglu_split(float g, float u, uint32_t &hi, uint32_t &lo)
+{
+    float h = silu_f32(g) * u;
+    hi = f32_to_bf16_rne_sg(h);
+    lo = f32_to_bf16_rne_sg(h - __uint_as_float(hi << 16));
+}
+
 // One pass: NT0 token tiles of position 0 followed by NT1 tiles of position 1.
-// NM = 2: gate and up with the SwiGLU epilogue (H, bf16); NM = 1: down (fp32 partial sums).
-template <int NM, bool DENSE, int NT0, int NT1>
+template <int STAGE, bool DENSE, int NT0, int NT1>
 __device__ __forceinline__ void stream_pass(const SgArgs &a, const uint16_t *wa, const uint16_t *wb,
-                                            int rt, bool active, int kb0, int kb1, int ks,
+                                            int rt0, int rt1, bool active0, bool active1,
+                                            int kb0, int kb1, int ks,
                                             int base0, int n0, int tile0, int base1, int n1, int tile1,
                                             u32x4 *xs, int32_t *rowidx)
 {
     constexpr int NT = NT0 + NT1;
+    constexpr int PARTS = (STAGE == STAGE_DOWN) ? 2 : 1;    // activation planes (hi, lo)
+    constexpr int VT = NT * PARTS;                          // staged fragment columns per k-block
+    constexpr int KCB = (STAGE == STAGE_DOWN) ? 4 : 8;      // k-blocks per staged chunk
+    static_assert(VT * KCB <= SG_FRAGS, "staged chunk does not fit its LDS buffer");
+    static_assert(KCB % SG_DEPTH == 0, "prefetch slots must line up with chunk steps");
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int kb_total = a.kdim / TILE_COLS;
 
@@ -100,46 +127,48 @@ __device__ __forceinline__ void stream_pass(const SgArgs &a, const uint16_t *wa,
     }
     __syncthreads();
 
-    f32x4 acc[NM][NT];
+    f32x4 acc[2][NT];
 #pragma unroll
-    for (int m = 0; m < NM; ++m)
+    for (int m = 0; m < 2; ++m)
 #pragma unroll
         for (int n = 0; n < NT; ++n) acc[m][n] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
     // The weight pointers come out of a device-side table, so the compiler cannot see that they
     // are global; say so, or it emits flat loads, which also tick the LDS counter.
     typedef const u32x4 __attribute__((address_space(1))) *gvec_ptr;
-    gvec_ptr wp[NM];
-    wp[0] = (gvec_ptr)(uintptr_t)wa + ((int64_t)rt * kb_total + kb0) * 64 + lane;
-    if (NM == 2) wp[NM - 1] = (gvec_ptr)(uintptr_t)wb + ((int64_t)rt * kb_total + kb0) * 64 + lane;
+    gvec_ptr wp[2];
+    wp[0] = (gvec_ptr)(uintptr_t)wa + ((int64_t)rt0 * kb_total + kb0) * 64 + lane;
+    wp[1] = (gvec_ptr)(uintptr_t)wb + ((int64_t)rt1 * kb_total + kb0) * 64 + lane;
 
     // Weight loads are never predicated (a branch per load would make the compiler drain the
     // whole load queue at every barrier): a k-block past the end re-reads the last valid one,
     // and contributes nothing because its staged activations are zero.
     const u32x4 zero4 = {0u, 0u, 0u, 0u};
     const int kb_last = kb1 - 1 - kb0;
-    u32x4 wbuf[NM][SG_KCB];
+    u32x4 wbuf[2][SG_DEPTH];
 #pragma unroll
-    for (int s = 0; s < SG_KCB; ++s)
+    for (int s = 0; s < SG_DEPTH; ++s)
 #pragma unroll
-        for (int m = 0; m < NM; ++m)
+        for (int m = 0; m < 2; ++m)
             wbuf[m][s] = __builtin_nontemporal_load(wp[m] + (int64_t)min(s, kb_last) * 64);
 
-    // activation fragments this thread stages per chunk: fragment f = wave + 4*i, (tile, k-block) = (f / KCB, f % KCB)
-    constexpr int XPT = NT * SG_KCB / SG_WAVES;
+    // activation fragments this thread stages per chunk: fragment f = wave + 4*i,
+    // (column, k-block) = (f / KCB, f % KCB), column = tile * PARTS + plane
+    constexpr int XPT = VT * KCB / SG_WAVES;
     u32x4 xr[XPT];
     const uint16_t *xrow[XPT];
 #pragma unroll
     for (int i = 0; i < XPT; ++i) {
-        int f = wave + SG_WAVES * i;
-        xrow[i] = a.act + (int64_t)rowidx[(f / SG_KCB) * 16 + (lane & 15)] * a.kdim + (lane >> 4) * 8;
+        int col = (wave + SG_WAVES * i) / KCB;
+        xrow[i] = a.act + (col % PARTS) * a.act_plane_stride +
+                  (int64_t)rowidx[(col / PARTS) * 16 + (lane & 15)] * a.kdim + (lane >> 4) * 8;
     }
     // The loaded registers are only touched again in stage_store, a whole chunk later, so the
     // loads stay in flight behind the weight stream; k-blocks past the end are stored as zeros.
     auto stage_load = [&](int kbc) {
 #pragma unroll
         for (int i = 0; i < XPT; ++i) {
-            int kb = kbc + (wave + SG_WAVES * i) % SG_KCB;
+            int kb = kbc + (wave + SG_WAVES * i) % KCB;
             xr[i] = *(const u32x4 *)(xrow[i] + min(kb, kb1 - 1) * TILE_COLS);
         }
     };
@@ -147,7 +176,7 @@ __device__ __forceinline__ void stream_pass(const SgArgs &a, const uint16_t *wa,
 #pragma unroll
         for (int i = 0; i < XPT; ++i) {
             int f = wave + SG_WAVES * i;
-            xs[(buf * SG_MAX_TILES * SG_KCB + f) * 64 + lane] = (kbc + f % SG_KCB < kb1) ? xr[i] : zero4;
+            xs[(buf * SG_FRAGS + f) * 64 + lane] = (kbc + f % KCB < kb1) ? xr[i] : zero4;
         }
     };
 
@@ -156,52 +185,55 @@ __device__ __forceinline__ void stream_pass(const SgArgs &a, const uint16_t *wa,
     __syncthreads();
 
     int buf = 0;
-    for (int kb = kb0; kb < kb1; kb += SG_KCB) {
-        const bool has_next = kb + SG_KCB < kb1;
-        if (has_next) stage_load(kb + SG_KCB);
+    for (int kb = kb0; kb < kb1; kb += KCB) {
+        const bool has_next = kb + KCB < kb1;
+        if (has_next) stage_load(kb + KCB);
 #pragma unroll
-        for (int s = 0; s < SG_KCB; ++s) {
-            u32x4 wv[NM];
+        for (int s = 0; s < KCB; ++s) {
+            u32x4 wv[2];
 #pragma unroll
-            for (int m = 0; m < NM; ++m) {
-                wv[m] = wbuf[m][s];
-                int kbn = min(kb + SG_KCB + s - kb0, kb_last);
-                wbuf[m][s] = __builtin_nontemporal_load(wp[m] + (int64_t)kbn * 64);
-            }
-            const u32x4 *xf = xs + (buf * SG_MAX_TILES * SG_KCB + s) * 64 + lane;
+            for (int m = 0; m < 2; ++m) wv[m] = wbuf[m][s % SG_DEPTH];
+            const u32x4 *xf = xs + (buf * SG_FRAGS + s) * 64 + lane;
             if (NT0 > 0) {
-                bf16x8 wd[NM];
+                bf16x8 wd[2];
 #pragma unroll
-                for (int m = 0; m < NM; ++m) wd[m] = decode_frag<0, DENSE>(wv[m]);
+                for (int m = 0; m < 2; ++m) wd[m] = decode_frag<0, DENSE>(wv[m]);
 #pragma unroll
-                for (int n = 0; n < NT0; ++n) {
-                    bf16x8 b = __builtin_bit_cast(bf16x8, xf[n * SG_KCB * 64]);
+                for (int c = 0; c < NT0 * PARTS; ++c) {
+                    bf16x8 b = __builtin_bit_cast(bf16x8, xf[c * KCB * 64]);
 #pragma unroll
-                    for (int m = 0; m < NM; ++m)
-                        acc[m][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wd[m], b, acc[m][n], 0, 0, 0);
+                    for (int m = 0; m < 2; ++m)
+                        acc[m][c / PARTS] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wd[m], b, acc[m][c / PARTS], 0, 0, 0);
                 }
             }
             if (NT1 > 0) {
-                bf16x8 wd[NM];
+                bf16x8 wd[2];
 #pragma unroll
-                for (int m = 0; m < NM; ++m) wd[m] = decode_frag<1, DENSE>(wv[m]);
+                for (int m = 0; m < 2; ++m) wd[m] = decode_frag<1, DENSE>(wv[m]);
 #pragma unroll
-                for (int n = NT0; n < NT; ++n) {
-                    bf16x8 b = __builtin_bit_cast(bf16x8, xf[n * SG_KCB * 64]);
+                for (int c = NT0 * PARTS; c < VT; ++c) {
+                    bf16x8 b = __builtin_bit_cast(bf16x8, xf[c * KCB * 64]);
 #pragma unroll
-                    for (int m = 0; m < NM; ++m)
-                        acc[m][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wd[m], b, acc[m][n], 0, 0, 0);
+                    for (int m = 0; m < 2; ++m)
+                        acc[m][c / PARTS] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wd[m], b, acc[m][c / PARTS], 0, 0, 0);
                 }
             }
+            // refill the slot just consumed
+#pragma unroll
+            for (int m = 0; m < 2; ++m) {
+                int kbn = min(kb + SG_DEPTH + s - kb0, kb_last);
+                wbuf[m][s % SG_DEPTH] = __builtin_nontemporal_load(wp[m] + (int64_t)kbn * 64);
+            }
+            // keep each step's refill inside the step: the scheduler otherwise sinks all loads
+            // of a chunk to its end, which exposes the memory latency once per chunk
+            __builtin_amdgcn_sched_barrier(0);
         }
-        if (has_next) stage_store(buf ^ 1, kb + SG_KCB);
+        if (has_next) stage_store(buf ^ 1, kb + KCB);
         __syncthreads();
         buf ^= 1;
     }
 
-    if (!active) return;
     // D layout of the 16x16 MFMA: lane holds rows 4*(lane/16)..+3 of column lane%16.
-    const int r0 = rt * 16 + (lane >> 4) * 4;
     const int j = lane & 15;
 #pragma unroll
     for (int n = 0; n < NT; ++n) {
@@ -209,19 +241,26 @@ __device__ __forceinline__ void stream_pass(const SgArgs &a, const uint16_t *wa,
         int cnt = (n < NT0) ? n0 : n1;
         if (within >= cnt) continue;
         int slot = ((n < NT0) ? base0 : base1) + within;
-        if (NM == 2) {
-            f32x4 g = acc[0][n], u = acc[NM - 1][n];
-            u32x2 o;
-            o.x = f32_to_bf16_rne_sg(silu_f32(g.x) * u.x) | (f32_to_bf16_rne_sg(silu_f32(g.y) * u.y) << 16);
-            o.y = f32_to_bf16_rne_sg(silu_f32(g.z) * u.z) | (f32_to_bf16_rne_sg(silu_f32(g.w) * u.w) << 16);
-            *(u32x2 *)(a.h_out + (int64_t)(slot - a.h_slot_base) * a.rows + r0) = o;
+        if (STAGE == STAGE_GATEUP) {
+            if (!active0) continue;
+            f32x4 g = acc[0][n], u = acc[1][n];
+            uint32_t hi[4], lo[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) swiglu_split(g[r], u[r], hi[r], lo[r]);
+            u32x2 ohi = {hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16)};
+            u32x2 olo = {lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16)};
+            uint16_t *dst = a.h_out + (int64_t)(slot - a.h_slot_base) * a.rows + rt0 * 16 + (lane >> 4) * 4;
+            *(u32x2 *)dst = ohi;
+            *(u32x2 *)(dst + a.h_plane_stride) = olo;
         } else {
-            *(f32x4 *)(a.o_out + (int64_t)ks * a.o_ks_stride + (int64_t)slot * a.rows + r0) = acc[0][n];
+            float *dst = a.o_out + (int64_t)ks * a.o_ks_stride + (int64_t)slot * a.rows + (lane >> 4) * 4;
+            if (active0) *(f32x4 *)(dst + rt0 * 16) = acc[0][n];
+            if (active1) *(f32x4 *)(dst + rt1 * 16) = acc[1][n];
         }
     }
 }
 
-template <int NM, bool DENSE>
+template <int STAGE, bool DENSE>
 __global__ void __launch_bounds__(SG_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2)))
 stream_kernel(SgArgs a)
 {
@@ -229,8 +268,9 @@ stream_kernel(SgArgs a)
     u32x4 *xs = (u32x4 *)lds_raw;
     int32_t *rowidx = (int32_t *)(lds_raw + SG_LDS_BYTES);
 
+    constexpr int RT_PER_WAVE = (STAGE == STAGE_DOWN) ? 2 : 1;
     const int row_tiles = a.rows / TILE_ROWS;
-    const int row_groups = (row_tiles + SG_WAVES - 1) / SG_WAVES;
+    const int row_groups = (row_tiles + SG_WAVES * RT_PER_WAVE - 1) / (SG_WAVES * RT_PER_WAVE);
     int b = blockIdx.x;
     const int ks = b % a.ksplit; b /= a.ksplit;
     const int rg = b % row_groups;
@@ -247,23 +287,25 @@ stream_kernel(SgArgs a)
     if (n0 + n1 == 0) return;
 
     const int wave = threadIdx.x >> 6;
-    int rt = rg * SG_WAVES + wave;
-    const bool active = rt < row_tiles;
-    if (!active) rt = row_tiles - 1;
+    int rt0 = (rg * SG_WAVES + wave) * RT_PER_WAVE;
+    int rt1 = (STAGE == STAGE_DOWN) ? rt0 + 1 : rt0;
+    const bool active0 = rt0 < row_tiles, active1 = rt1 < row_tiles;
+    rt0 = min(rt0, row_tiles - 1);      // inactive streams re-read a valid tile and store nothing
+    rt1 = min(rt1, row_tiles - 1);
     const int kb_total = a.kdim / TILE_COLS;
     const int kb0 = (int)((int64_t)ks * kb_total / a.ksplit);
     const int kb1 = (int)((int64_t)(ks + 1) * kb_total / a.ksplit);
     const uint16_t *wa = a.w_a[g];
-    const uint16_t *wb = (NM == 2) ? a.w_b[g] : nullptr;
+    const uint16_t *wb = (STAGE == STAGE_GATEUP) ? a.w_b[g] : wa;
 
     constexpr int PT = DENSE ? SG_MAX_TILES : SG_POS_TILES;
     const int tiles0 = (n0 + 15) >> 4, tiles1 = (n1 + 15) >> 4;
     for (int t0 = 0, t1 = 0; t0 < tiles0 || t1 < tiles1; t0 += PT, t1 += PT) {
         int c0 = min(PT, max(tiles0 - t0, 0));
         int c1 = min(PT, max(tiles1 - t1, 0));
-#define PZL_PASS(A, B)                                                                               \
-    stream_pass<NM, DENSE, A, B>(a, wa, wb, rt, active, kb0, kb1, ks, base0, n0, t0, base1, n1, t1, \
-                                 xs, rowidx)
+#define PZL_PASS(A, B)                                                                              \
+    stream_pass<STAGE, DENSE, A, B>(a, wa, wb, rt0, rt1, active0, active1, kb0, kb1, ks, base0, n0, \
+                                    t0, base1, n1, t1, xs, rowidx)
         if (DENSE) {
             switch (c0) {
                 case 1: PZL_PASS(1, 0); break;
@@ -287,30 +329,36 @@ stream_kernel(SgArgs a)
     }
 }
 
-template <int NM, bool DENSE>
+int stream_row_groups(int rows, bool down_stage)
+{
+    const int per_wg = SG_WAVES * (down_stage ? 2 : 1);
+    return (rows / TILE_ROWS + per_wg - 1) / per_wg;
+}
+
+template <int STAGE, bool DENSE>
 static int launch(const StreamGroupArgs &g, hipStream_t st)
 {
     if (g.n_groups <= 0) return PZL_OK;
     if (g.rows % TILE_ROWS || g.kdim % TILE_COLS || g.ksplit < 1) return PZL_EINVAL;
     SgArgs a;
     a.w_a = g.w_a; a.w_b = g.w_b; a.rows = g.rows; a.kdim = g.kdim; a.ksplit = g.ksplit;
-    a.act = g.act; a.act_is_x = g.act_is_x; a.act_slot_base = g.act_slot_base;
+    a.act = g.act; a.act_plane_stride = g.act_plane_stride;
+    a.act_is_x = g.act_is_x; a.act_slot_base = g.act_slot_base;
     a.cnt = g.cnt; a.off = g.off; a.slot_tok = g.slot_tok;
     a.dense_tokens = g.dense_tokens; a.dense_slot_base = g.dense_slot_base;
-    a.h_out = g.h_out; a.h_slot_base = g.h_slot_base; a.o_out = g.o_out; a.o_ks_stride = g.o_ks_stride;
-    const int row_tiles = g.rows / TILE_ROWS;
-    const int row_groups = (row_tiles + SG_WAVES - 1) / SG_WAVES;
-    const int64_t blocks = (int64_t)g.n_groups * row_groups * g.ksplit;
+    a.h_out = g.h_out; a.h_plane_stride = g.h_plane_stride; a.h_slot_base = g.h_slot_base;
+    a.o_out = g.o_out; a.o_ks_stride = g.o_ks_stride;
+    const int64_t blocks = (int64_t)g.n_groups * stream_row_groups(g.rows, STAGE == STAGE_DOWN) * g.ksplit;
     if (blocks > 0x7FFFFFFFLL) return PZL_EINVAL;
     const size_t lds = SG_LDS_BYTES + SG_MAX_TILES * 16 * sizeof(int32_t);
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)stream_kernel<NM, DENSE>,
+        hipError_t e = hipFuncSetAttribute((const void *)stream_kernel<STAGE, DENSE>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) { set_hip_error(e); return PZL_EHIP; }
         attr_set = true;
     }
-    hipLaunchKernelGGL((stream_kernel<NM, DENSE>), dim3((unsigned)blocks), dim3(SG_THREADS), lds, st, a);
+    hipLaunchKernelGGL((stream_kernel<STAGE, DENSE>), dim3((unsigned)blocks), dim3(SG_THREADS), lds, st, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) { set_hip_error(e); return PZL_EHIP; }
     return PZL_OK;
@@ -318,12 +366,12 @@ static int launch(const StreamGroupArgs &g, hipStream_t st)
 
 int launch_stream_gateup(const StreamGroupArgs &a, bool dense, hipStream_t st)
 {
-    return dense ? launch<2, true>(a, st) : launch<2, false>(a, st);
+    return dense ? launch<STAGE_GATEUP, true>(a, st) : launch<STAGE_GATEUP, false>(a, st);
 }
 
 int launch_stream_down(const StreamGroupArgs &a, bool dense, hipStream_t st)
 {
-    return dense ? launch<1, true>(a, st) : launch<1, false>(a, st);
+    return dense ? launch<STAGE_DOWN, true>(a, st) : launch<STAGE_DOWN, false>(a, st);
 }
 
 }  // namespace pzl

@@ -1,7 +1,9 @@
 """GPU parity: the HIP library through its C ABI against the CPU oracle.
 
-Bit-exact for pack / unpack (integer work); |y - y_ref| <= 1e-2 * max(|y_ref|, rms(y_ref)) for
-the FFN (bf16 products, fp32 accumulation, bf16 H and y against the oracle's fp64).
+Bit-exact for pack / unpack (integer work); |y - y_ref| <= 1e-2 * max(|y_ref|, rms of the row)
+for the FFN (bf16 x bf16 products, fp32 accumulation, H kept as hi+lo bf16, y rounded to bf16
+once, against the oracle's fp64).  The rounding of y alone is up to 2^-8 relative, i.e. 0.39 of
+the bound.
 """
 import numpy as np
 import pytest
@@ -80,13 +82,8 @@ def check(case, T, label, ids=None, w=None, x=None, ref_rows=None):
     rows = np.arange(T) if ref_rows is None else np.asarray(ref_rows)
     y64, _ = case.ref(x[rows], ids[rows], w[rows])
     ok, worst = tolerance_ok(y[rows], y64)
-    # diagnostic: against the oracle variant that also rounds H to bf16, what is left is the
-    # fp32 accumulation order and the final rounding, i.e. about one bf16 ulp of y
-    ys64, _ = case.ref(x[rows], ids[rows], w[rows], stage_h_bf16=True)
-    _, worst_staged = tolerance_ok(y[rows], ys64)
-    say("  worst err / bound = %.3f   (vs bf16-H oracle variant: %.3f)" % (worst, worst_staged))
+    say("  worst err / bound = %.3f" % worst)
     assert ok, worst
-    assert worst_staged < 0.5, worst_staged
     return y, y64
 
 
