@@ -148,6 +148,13 @@ def main():
                                                planes["sign0"], planes["sign1"])[0]
     layer, emap = build_layer(cfg, keep if want_cpu else None)
 
+    # A plain copy of known size (256 MiB in, 256 MiB out), outside the timed region: under
+    # `rocprofv3 --pmc FETCH_SIZE|WRITE_SIZE` its reading calibrates the HBM byte counters.
+    cal = torch.zeros(16384, 8192, dtype=torch.int16, device="cuda")
+    binding.pzl_tile_dense(cal)
+    torch.cuda.synchronize()
+    del cal
+
     x, ids, w, xt, idt, wt = batch(cfg, T)
     ms_step, ms_gateup, ms_wall, y = time_steps(hip, layer, xt, idt, wt, args.steps, args.warmup)
     n_touched = touched_pairs(ids, emap)
