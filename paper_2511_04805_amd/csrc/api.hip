@@ -23,7 +23,6 @@ static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 struct pzl_layer {
     int32_t n_experts, n_pairs, d_model, d_ffn, n_shared;
-    int32_t ksplit;                        // k-splits of the down projection (layer constant)
     std::vector<int32_t> shared_f;
     // device tables
     int32_t *d_q_of_expert;                // [E] expert -> 2*pair + pos
@@ -33,6 +32,8 @@ struct pzl_layer {
 };
 
 namespace pzl {
+
+constexpr int MAX_KSPLIT = 8;   // upper bound on the k-splits of the down stage (sizes the workspace)
 
 struct WorkspaceLayout {
     size_t cnt, off, slot_tok, slot_of, h_routed, h_shared, opart, total;
@@ -58,19 +59,19 @@ static WorkspaceLayout carve(const pzl_layer *L, int32_t T, int32_t k)
     w.h_shared = p;
     for (int s = 0; s < L->n_shared; ++s) p += w.h_shared_each(L, T, s);
     w.o_ks_stride = (int64_t)slots * L->d_model;
-    w.opart = p;     p += align_up((size_t)L->ksplit * slots * L->d_model * 4, 256);
+    w.opart = p;     p += align_up((size_t)MAX_KSPLIT * slots * L->d_model * 4, 256);
     w.total = p;
     return w;
 }
 
-static int choose_ksplit(int n_groups, int rows)
+static int choose_ksplit(int groups_touched_max, int rows)
 {
-    // The down projection has only rows/128 workgroups per pair; split its long K so that a
-    // launch has at least ~4 workgroups per compute unit (256 CUs).
-    int64_t wgs = (int64_t)n_groups * stream_row_groups(rows, true);
-    int ks = (int)((1024 + wgs - 1) / wgs);
+    // The down projection has only rows/128 workgroups per pair; split its long K so that the
+    // launch fills the chip once (about one resident round of workgroups).
+    int64_t wgs = (int64_t)groups_touched_max * stream_row_groups(rows, true);
+    int ks = (int)(STREAM_RESIDENT_WGS / (wgs > 0 ? wgs : 1));
     if (ks < 1) ks = 1;
-    if (ks > 8) ks = 8;
+    if (ks > MAX_KSPLIT) ks = MAX_KSPLIT;
     return ks;
 }
 
@@ -154,7 +155,6 @@ int pzl_layer_create(const pzl_layer_desc *desc, pzl_layer **out)
     if (!L) return PZL_ENOMEM;
     L->n_experts = E; L->n_pairs = P; L->d_model = d; L->d_ffn = f; L->n_shared = S;
     L->shared_f.assign(desc->shared_d_ffn, desc->shared_d_ffn + S);
-    L->ksplit = choose_ksplit(P, d);
 
     const size_t sz_q = align_up((size_t)E * 4, 256);
     const size_t sz_p = align_up((size_t)P * sizeof(void *), 256);
@@ -242,9 +242,11 @@ int pzl_moe_ffn_staged(const pzl_layer *L, const uint16_t *x, const int32_t *top
     if (rc) return rc;
     if ((rc = mark(PZL_STAGE_ROUTE, 1))) return rc;
 
+    const int pairs_max = (int)((int64_t)N < L->n_pairs ? N : L->n_pairs);   // pairs that can have tokens
+    const int ksplit = choose_ksplit(pairs_max > 0 ? pairs_max : 1, L->d_model);
     if (N > 0) {
         StreamGroupArgs a = {};
-        a.n_groups = L->n_pairs;
+        a.n_groups = L->n_pairs; a.groups_touched_max = pairs_max;
         a.cnt = rt.cnt; a.off = rt.off; a.slot_tok = rt.slot_tok;
         // gate/up + SwiGLU -> H
         a.w_a = L->d_gate; a.w_b = L->d_up;
@@ -257,7 +259,7 @@ int pzl_moe_ffn_staged(const pzl_layer *L, const uint16_t *x, const int32_t *top
         if ((rc = mark(PZL_STAGE_GATEUP, 1))) return rc;
         // down -> partial sums
         a.w_a = L->d_down; a.w_b = nullptr;
-        a.rows = L->d_model; a.kdim = L->d_ffn; a.ksplit = L->ksplit;
+        a.rows = L->d_model; a.kdim = L->d_ffn; a.ksplit = ksplit;
         a.act = h_routed; a.act_is_x = 0; a.act_slot_base = 0; a.act_plane_stride = (int64_t)N * L->d_ffn;
         a.h_out = nullptr; a.o_out = opart; a.o_ks_stride = w.o_ks_stride;
         if ((rc = mark(PZL_STAGE_DOWN, 0))) return rc;
@@ -282,7 +284,7 @@ int pzl_moe_ffn_staged(const pzl_layer *L, const uint16_t *x, const int32_t *top
         rc = launch_stream_gateup(a, true, st);
         if (rc) return rc;
         a.w_a = L->d_sdown + s; a.w_b = nullptr;
-        a.rows = L->d_model; a.kdim = L->shared_f[s]; a.ksplit = L->ksplit;
+        a.rows = L->d_model; a.kdim = L->shared_f[s]; a.ksplit = ksplit;
         a.act = h_s; a.act_is_x = 0; a.act_slot_base = slot_base; a.act_plane_stride = (int64_t)T * L->shared_f[s];
         a.h_out = nullptr; a.o_out = opart; a.o_ks_stride = w.o_ks_stride;
         rc = launch_stream_down(a, true, st);
@@ -291,7 +293,7 @@ int pzl_moe_ffn_staged(const pzl_layer *L, const uint16_t *x, const int32_t *top
 
     if ((rc = mark(PZL_STAGE_SHARED, 1))) return rc;
     if ((rc = mark(PZL_STAGE_COMBINE, 0))) return rc;
-    rc = launch_combine(opart, L->ksplit, w.o_ks_stride, rt, topk_w, T, k, L->d_model, L->n_shared, y, st);
+    rc = launch_combine(opart, ksplit, w.o_ks_stride, rt, topk_w, T, k, L->d_model, L->n_shared, y, st);
     if (rc) return rc;
     return mark(PZL_STAGE_COMBINE, 1);
 }

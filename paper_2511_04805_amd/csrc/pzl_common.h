@@ -48,6 +48,7 @@ struct StreamGroupArgs {
     const uint16_t *const *w_a;   // device array [n_groups]: gate (gate/up stage) or down (down stage)
     const uint16_t *const *w_b;   // device array [n_groups]: up, or nullptr in the down stage
     int32_t n_groups;
+    int32_t groups_touched_max;   // upper bound on groups that can have tokens (0 = all)
     int32_t rows;                 // output features of the stage (f or d)
     int32_t kdim;                 // contracted dimension (d or f)
     const uint16_t *act;          // activations [*, kdim] bf16 row-major (x, or the hi plane of H)
@@ -66,7 +67,8 @@ struct StreamGroupArgs {
     int64_t o_ks_stride;          // elements between k-splits
     int32_t ksplit;
 };
-int stream_row_groups(int rows, bool down_stage);   // workgroups along the output rows
+int stream_row_groups(int rows, bool down_stage);   // row groups (workgroup units) along the output rows
+constexpr int STREAM_RESIDENT_WGS = 512;             // workgroups the chip holds at once (256 CUs x 2)
 int launch_stream_gateup(const StreamGroupArgs &a, bool dense, hipStream_t st);
 int launch_stream_down(const StreamGroupArgs &a, bool dense, hipStream_t st);
 

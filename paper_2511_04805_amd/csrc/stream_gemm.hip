@@ -27,6 +27,12 @@ namespace pzl {
 #ifndef SG_DEPTH_N
 #define SG_DEPTH_N 4
 #endif
+#ifndef SG_SCHED_BARRIER
+#define SG_SCHED_BARRIER 1
+#endif
+#ifndef SG_DEPTH_GATEUP
+#define SG_DEPTH_GATEUP SG_DEPTH_N
+#endif
 constexpr int SG_WAVES = 4;
 constexpr int SG_THREADS = SG_WAVES * 64;
 constexpr int SG_DEPTH = SG_DEPTH_N;   // weight k-blocks in flight per stream
@@ -35,11 +41,12 @@ constexpr int SG_POS_TILES = 2;        // token tiles per pass per position (rou
 constexpr int SG_FRAGS = 32;           // staged 1 KiB fragments per LDS buffer
 constexpr int SG_LDS_BYTES = 2 * SG_FRAGS * 64 * 16;   // 64 KiB, two buffers
 constexpr int STAGE_GATEUP = 0, STAGE_DOWN = 1;
+constexpr int SG_RESIDENT_WGS = 512;   // 256 CUs x 2 workgroups
 
 struct SgArgs {
     const uint16_t *const *w_a;
     const uint16_t *const *w_b;
-    int32_t rows, kdim, ksplit;
+    int32_t rows, kdim, ksplit, rg_per_wg;
     const uint16_t *act;
     int64_t act_plane_stride;
     int32_t act_is_x, act_slot_base;
@@ -108,8 +115,9 @@ __device__ __forceinline__ void stream_pass(const SgArgs &a, const uint16_t *wa,
     constexpr int PARTS = (STAGE == STAGE_DOWN) ? 2 : 1;    // activation planes (hi, lo)
     constexpr int VT = NT * PARTS;                          // staged fragment columns per k-block
     constexpr int KCB = (STAGE == STAGE_DOWN) ? 4 : 8;      // k-blocks per staged chunk
+    constexpr int DEPTH = (STAGE == STAGE_DOWN) ? SG_DEPTH : SG_DEPTH_GATEUP;
     static_assert(VT * KCB <= SG_FRAGS, "staged chunk does not fit its LDS buffer");
-    static_assert(KCB % SG_DEPTH == 0, "prefetch slots must line up with chunk steps");
+    static_assert(KCB % DEPTH == 0, "prefetch slots must line up with chunk steps");
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int kb_total = a.kdim / TILE_COLS;
 
@@ -145,9 +153,9 @@ __device__ __forceinline__ void stream_pass(const SgArgs &a, const uint16_t *wa,
     // and contributes nothing because its staged activations are zero.
     const u32x4 zero4 = {0u, 0u, 0u, 0u};
     const int kb_last = kb1 - 1 - kb0;
-    u32x4 wbuf[2][SG_DEPTH];
+    u32x4 wbuf[2][DEPTH];
 #pragma unroll
-    for (int s = 0; s < SG_DEPTH; ++s)
+    for (int s = 0; s < DEPTH; ++s)
 #pragma unroll
         for (int m = 0; m < 2; ++m)
             wbuf[m][s] = __builtin_nontemporal_load(wp[m] + (int64_t)min(s, kb_last) * 64);
@@ -192,7 +200,7 @@ __device__ __forceinline__ void stream_pass(const SgArgs &a, const uint16_t *wa,
         for (int s = 0; s < KCB; ++s) {
             u32x4 wv[2];
 #pragma unroll
-            for (int m = 0; m < 2; ++m) wv[m] = wbuf[m][s % SG_DEPTH];
+            for (int m = 0; m < 2; ++m) wv[m] = wbuf[m][s % DEPTH];
             const u32x4 *xf = xs + (buf * SG_FRAGS + s) * 64 + lane;
             if (NT0 > 0) {
                 bf16x8 wd[2];
@@ -221,12 +229,14 @@ __device__ __forceinline__ void stream_pass(const SgArgs &a, const uint16_t *wa,
             // refill the slot just consumed
 #pragma unroll
             for (int m = 0; m < 2; ++m) {
-                int kbn = min(kb + SG_DEPTH + s - kb0, kb_last);
-                wbuf[m][s % SG_DEPTH] = __builtin_nontemporal_load(wp[m] + (int64_t)kbn * 64);
+                int kbn = min(kb + DEPTH + s - kb0, kb_last);
+                wbuf[m][s % DEPTH] = __builtin_nontemporal_load(wp[m] + (int64_t)kbn * 64);
             }
+#if SG_SCHED_BARRIER
             // keep each step's refill inside the step: the scheduler otherwise sinks all loads
             // of a chunk to its end, which exposes the memory latency once per chunk
             __builtin_amdgcn_sched_barrier(0);
+#endif
         }
         if (has_next) stage_store(buf ^ 1, kb + KCB);
         __syncthreads();
@@ -271,10 +281,11 @@ stream_kernel(SgArgs a)
     constexpr int RT_PER_WAVE = (STAGE == STAGE_DOWN) ? 2 : 1;
     const int row_tiles = a.rows / TILE_ROWS;
     const int row_groups = (row_tiles + SG_WAVES * RT_PER_WAVE - 1) / (SG_WAVES * RT_PER_WAVE);
+    const int rg_blocks = (row_groups + a.rg_per_wg - 1) / a.rg_per_wg;
     int b = blockIdx.x;
     const int ks = b % a.ksplit; b /= a.ksplit;
-    const int rg = b % row_groups;
-    const int g = b / row_groups;
+    const int rgb = b % rg_blocks;
+    const int g = b / rg_blocks;
 
     int base0, n0, base1, n1;
     if (DENSE) {
@@ -287,19 +298,20 @@ stream_kernel(SgArgs a)
     if (n0 + n1 == 0) return;
 
     const int wave = threadIdx.x >> 6;
-    int rt0 = (rg * SG_WAVES + wave) * RT_PER_WAVE;
-    int rt1 = (STAGE == STAGE_DOWN) ? rt0 + 1 : rt0;
-    const bool active0 = rt0 < row_tiles, active1 = rt1 < row_tiles;
-    rt0 = min(rt0, row_tiles - 1);      // inactive streams re-read a valid tile and store nothing
-    rt1 = min(rt1, row_tiles - 1);
     const int kb_total = a.kdim / TILE_COLS;
     const int kb0 = (int)((int64_t)ks * kb_total / a.ksplit);
     const int kb1 = (int)((int64_t)(ks + 1) * kb_total / a.ksplit);
     const uint16_t *wa = a.w_a[g];
     const uint16_t *wb = (STAGE == STAGE_GATEUP) ? a.w_b[g] : wa;
-
     constexpr int PT = DENSE ? SG_MAX_TILES : SG_POS_TILES;
     const int tiles0 = (n0 + 15) >> 4, tiles1 = (n1 + 15) >> 4;
+
+    for (int rg = rgb * a.rg_per_wg; rg < min(row_groups, (rgb + 1) * a.rg_per_wg); ++rg) {
+    int rt0 = (rg * SG_WAVES + wave) * RT_PER_WAVE;
+    int rt1 = (STAGE == STAGE_DOWN) ? rt0 + 1 : rt0;
+    const bool active0 = rt0 < row_tiles, active1 = rt1 < row_tiles;
+    rt0 = min(rt0, row_tiles - 1);      // inactive streams re-read a valid tile and store nothing
+    rt1 = min(rt1, row_tiles - 1);
     for (int t0 = 0, t1 = 0; t0 < tiles0 || t1 < tiles1; t0 += PT, t1 += PT) {
         int c0 = min(PT, max(tiles0 - t0, 0));
         int c1 = min(PT, max(tiles1 - t1, 0));
@@ -327,6 +339,7 @@ stream_kernel(SgArgs a)
         }
 #undef PZL_PASS
     }
+    }
 }
 
 int stream_row_groups(int rows, bool down_stage)
@@ -348,7 +361,17 @@ static int launch(const StreamGroupArgs &g, hipStream_t st)
     a.dense_tokens = g.dense_tokens; a.dense_slot_base = g.dense_slot_base;
     a.h_out = g.h_out; a.h_plane_stride = g.h_plane_stride; a.h_slot_base = g.h_slot_base;
     a.o_out = g.o_out; a.o_ks_stride = g.o_ks_stride;
-    const int64_t blocks = (int64_t)g.n_groups * stream_row_groups(g.rows, STAGE == STAGE_DOWN) * g.ksplit;
+    // Two workgroups fit a compute unit (registers, LDS), 512 on the chip.  A launch a little
+    // larger than that runs a second, partly empty round; giving each workgroup several row
+    // groups instead keeps the launch to one round.
+    const int row_groups = stream_row_groups(g.rows, STAGE == STAGE_DOWN);
+    const int64_t units = (int64_t)(g.groups_touched_max > 0 ? g.groups_touched_max : g.n_groups) * row_groups * g.ksplit;
+    int rg_per_wg = (int)((units + SG_RESIDENT_WGS - 1) / SG_RESIDENT_WGS);
+    if (rg_per_wg < 1) rg_per_wg = 1;
+    if (rg_per_wg > 4) rg_per_wg = 1;            // many rounds anyway: keep the units small
+    if (rg_per_wg > row_groups) rg_per_wg = row_groups;
+    a.rg_per_wg = rg_per_wg;
+    const int64_t blocks = (int64_t)g.n_groups * ((row_groups + rg_per_wg - 1) / rg_per_wg) * g.ksplit;
     if (blocks > 0x7FFFFFFFLL) return PZL_EINVAL;
     const size_t lds = SG_LDS_BYTES + SG_MAX_TILES * 16 * sizeof(int32_t);
     static bool attr_set = false;
