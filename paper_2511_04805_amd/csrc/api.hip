@@ -33,10 +33,11 @@ struct pzl_layer {
 
 namespace pzl {
 
+constexpr int TILED_MIN_TOKENS_PER_EXPERT = 96;   // average tokens per expert from which the tiled path pays
 constexpr int MAX_KSPLIT = 8;   // upper bound on the k-splits of the down stage (sizes the workspace)
 
 struct WorkspaceLayout {
-    size_t cnt, off, slot_tok, slot_of, h_routed, h_shared, opart, total;
+    size_t cnt, off, slot_tok, slot_of, tile_q, tile_slot0, tile_n, n_tiles, h_routed, h_shared, opart, total;
     int64_t o_ks_stride;      // elements between k-splits of the partial-sum buffer
     // H is held as two bf16 planes (hi, lo), the lo plane right after the hi plane
     size_t h_shared_each(const pzl_layer *L, int32_t T, int s) const
@@ -55,6 +56,11 @@ static WorkspaceLayout carve(const pzl_layer *L, int32_t T, int32_t k)
     w.off = p;       p += align_up(((size_t)L->n_experts + 1) * 4, 256);
     w.slot_tok = p;  p += align_up(N * 4, 256);
     w.slot_of = p;   p += align_up(N * 4, 256);
+    const size_t mt = (size_t)max_token_tiles((int64_t)N, L->n_experts);
+    w.tile_q = p;     p += align_up(mt * 4, 256);
+    w.tile_slot0 = p; p += align_up(mt * 4, 256);
+    w.tile_n = p;     p += align_up(mt * 4, 256);
+    w.n_tiles = p;    p += 256;
     w.h_routed = p;  p += align_up(2 * N * L->d_ffn * 2, 256);
     w.h_shared = p;
     for (int s = 0; s < L->n_shared; ++s) p += w.h_shared_each(L, T, s);
@@ -233,6 +239,10 @@ int pzl_moe_ffn_staged(const pzl_layer *L, const uint16_t *x, const int32_t *top
     rt.off = (int32_t *)(ws + w.off);
     rt.slot_tok = (int32_t *)(ws + w.slot_tok);
     rt.slot_of = (int32_t *)(ws + w.slot_of);
+    rt.tile_q = (int32_t *)(ws + w.tile_q);
+    rt.tile_slot0 = (int32_t *)(ws + w.tile_slot0);
+    rt.tile_n = (int32_t *)(ws + w.tile_n);
+    rt.n_tiles = (int32_t *)(ws + w.n_tiles);
     uint16_t *h_routed = (uint16_t *)(ws + w.h_routed);
     float *opart = (float *)(ws + w.opart);
 
@@ -242,9 +252,37 @@ int pzl_moe_ffn_staged(const pzl_layer *L, const uint16_t *x, const int32_t *top
     if (rc) return rc;
     if ((rc = mark(PZL_STAGE_ROUTE, 1))) return rc;
 
+    // Path choice (host side, from the batch shape only): with few tokens per expert the layer
+    // is bound by streaming the packed weights once (streaming kernels); with many it is a
+    // dense contraction (tiled kernels on the matrix cores).
+    const bool tiled = (int64_t)N >= (int64_t)TILED_MIN_TOKENS_PER_EXPERT * L->n_experts;
+    const bool tiled_shared = T >= TILED_MIN_TOKENS_PER_EXPERT;
     const int pairs_max = (int)((int64_t)N < L->n_pairs ? N : L->n_pairs);   // pairs that can have tokens
-    const int ksplit = choose_ksplit(pairs_max > 0 ? pairs_max : 1, L->d_model);
-    if (N > 0) {
+    const int ksplit = tiled ? 1 : choose_ksplit(pairs_max > 0 ? pairs_max : 1, L->d_model);
+    const int ksplit_shared = tiled_shared ? 1 : choose_ksplit(1, L->d_model);
+    const int64_t h_plane = (int64_t)N * L->d_ffn;
+    if (N > 0 && tiled) {
+        TileGemmArgs a = {};
+        a.slot_tok = rt.slot_tok;
+        a.tile_q = rt.tile_q; a.tile_slot0 = rt.tile_slot0; a.tile_n = rt.tile_n; a.n_tiles = rt.n_tiles;
+        a.max_mtiles = max_token_tiles(N, L->n_experts);
+        a.w_a = L->d_gate; a.w_b = L->d_up;
+        a.rows = L->d_ffn; a.kdim = L->d_model;
+        a.act = x; a.act_is_x = 1;
+        a.h_out = h_routed; a.h_slot_base = 0; a.h_plane_stride = h_plane;
+        if ((rc = mark(PZL_STAGE_GATEUP, 0))) return rc;
+        rc = launch_tile_gateup(a, false, st);
+        if (rc) return rc;
+        if ((rc = mark(PZL_STAGE_GATEUP, 1))) return rc;
+        a.w_a = L->d_down; a.w_b = nullptr;
+        a.rows = L->d_model; a.kdim = L->d_ffn;
+        a.act = h_routed; a.act_is_x = 0; a.act_slot_base = 0; a.act_plane_stride = h_plane;
+        a.h_out = nullptr; a.o_out = opart;
+        if ((rc = mark(PZL_STAGE_DOWN, 0))) return rc;
+        rc = launch_tile_down(a, false, st);
+        if (rc) return rc;
+        if ((rc = mark(PZL_STAGE_DOWN, 1))) return rc;
+    } else if (N > 0) {
         StreamGroupArgs a = {};
         a.n_groups = L->n_pairs; a.groups_touched_max = pairs_max;
         a.cnt = rt.cnt; a.off = rt.off; a.slot_tok = rt.slot_tok;
@@ -252,7 +290,7 @@ int pzl_moe_ffn_staged(const pzl_layer *L, const uint16_t *x, const int32_t *top
         a.w_a = L->d_gate; a.w_b = L->d_up;
         a.rows = L->d_ffn; a.kdim = L->d_model; a.ksplit = 1;
         a.act = x; a.act_is_x = 1; a.act_slot_base = 0;
-        a.h_out = h_routed; a.h_slot_base = 0; a.h_plane_stride = (int64_t)N * L->d_ffn;
+        a.h_out = h_routed; a.h_slot_base = 0; a.h_plane_stride = h_plane;
         if ((rc = mark(PZL_STAGE_GATEUP, 0))) return rc;
         rc = launch_stream_gateup(a, false, st);
         if (rc) return rc;
@@ -260,7 +298,7 @@ int pzl_moe_ffn_staged(const pzl_layer *L, const uint16_t *x, const int32_t *top
         // down -> partial sums
         a.w_a = L->d_down; a.w_b = nullptr;
         a.rows = L->d_model; a.kdim = L->d_ffn; a.ksplit = ksplit;
-        a.act = h_routed; a.act_is_x = 0; a.act_slot_base = 0; a.act_plane_stride = (int64_t)N * L->d_ffn;
+        a.act = h_routed; a.act_is_x = 0; a.act_slot_base = 0; a.act_plane_stride = h_plane;
         a.h_out = nullptr; a.o_out = opart; a.o_ks_stride = w.o_ks_stride;
         if ((rc = mark(PZL_STAGE_DOWN, 0))) return rc;
         rc = launch_stream_down(a, false, st);
@@ -274,18 +312,40 @@ int pzl_moe_ffn_staged(const pzl_layer *L, const uint16_t *x, const int32_t *top
         uint16_t *h_s = (uint16_t *)(ws + h_off);
         h_off += w.h_shared_each(L, T, s);
         const int32_t slot_base = N + s * T;
+        const int64_t hs_plane = (int64_t)T * L->shared_f[s];
+        if (tiled_shared) {
+            TileGemmArgs a = {};
+            const int parts = (T + TILE_MAX_TOKENS - 1) / TILE_MAX_TOKENS;
+            a.dense_tokens = T; a.dense_slot_base = slot_base;
+            a.dense_tile_tokens = ((T + parts - 1) / parts + 15) & ~15;
+            a.dense_tiles = (T + a.dense_tile_tokens - 1) / a.dense_tile_tokens;
+            a.max_mtiles = a.dense_tiles;
+            a.w_a = L->d_sgate + s; a.w_b = L->d_sup + s;
+            a.rows = L->shared_f[s]; a.kdim = L->d_model;
+            a.act = x; a.act_is_x = 1;
+            a.h_out = h_s; a.h_slot_base = slot_base; a.h_plane_stride = hs_plane;
+            rc = launch_tile_gateup(a, true, st);
+            if (rc) return rc;
+            a.w_a = L->d_sdown + s; a.w_b = nullptr;
+            a.rows = L->d_model; a.kdim = L->shared_f[s];
+            a.act = h_s; a.act_is_x = 0; a.act_slot_base = slot_base; a.act_plane_stride = hs_plane;
+            a.h_out = nullptr; a.o_out = opart;
+            rc = launch_tile_down(a, true, st);
+            if (rc) return rc;
+            continue;
+        }
         StreamGroupArgs a = {};
         a.n_groups = 1;
         a.dense_tokens = T; a.dense_slot_base = slot_base;
         a.w_a = L->d_sgate + s; a.w_b = L->d_sup + s;
         a.rows = L->shared_f[s]; a.kdim = L->d_model; a.ksplit = 1;
         a.act = x; a.act_is_x = 1; a.act_slot_base = 0;
-        a.h_out = h_s; a.h_slot_base = slot_base; a.h_plane_stride = (int64_t)T * L->shared_f[s];
+        a.h_out = h_s; a.h_slot_base = slot_base; a.h_plane_stride = hs_plane;
         rc = launch_stream_gateup(a, true, st);
         if (rc) return rc;
         a.w_a = L->d_sdown + s; a.w_b = nullptr;
-        a.rows = L->d_model; a.kdim = L->shared_f[s]; a.ksplit = ksplit;
-        a.act = h_s; a.act_is_x = 0; a.act_slot_base = slot_base; a.act_plane_stride = (int64_t)T * L->shared_f[s];
+        a.rows = L->d_model; a.kdim = L->shared_f[s]; a.ksplit = ksplit_shared;
+        a.act = h_s; a.act_is_x = 0; a.act_slot_base = slot_base; a.act_plane_stride = hs_plane;
         a.h_out = nullptr; a.o_out = opart; a.o_ks_stride = w.o_ks_stride;
         rc = launch_stream_down(a, true, st);
         if (rc) return rc;
@@ -293,7 +353,7 @@ int pzl_moe_ffn_staged(const pzl_layer *L, const uint16_t *x, const int32_t *top
 
     if ((rc = mark(PZL_STAGE_SHARED, 1))) return rc;
     if ((rc = mark(PZL_STAGE_COMBINE, 0))) return rc;
-    rc = launch_combine(opart, ksplit, w.o_ks_stride, rt, topk_w, T, k, L->d_model, L->n_shared, y, st);
+    rc = launch_combine(opart, ksplit, ksplit_shared, w.o_ks_stride, rt, topk_w, T, k, L->d_model, L->n_shared, y, st);
     if (rc) return rc;
     return mark(PZL_STAGE_COMBINE, 1);
 }

@@ -24,7 +24,14 @@ struct RouteTables {
     int32_t *off;        // [Q+1]  first slot of expert q
     int32_t *slot_tok;   // [N]    token index of each slot (slots sorted by q, then by flat index)
     int32_t *slot_of;    // [N]    slot of flat index t*k+j, or -1 for an id outside [0,E)
+    // token tiles of the tiled GEMM path: each expert's slots cut into equal parts of <= 256
+    int32_t *tile_q;     // [max_tiles] expert q of the tile
+    int32_t *tile_slot0; // [max_tiles] first slot
+    int32_t *tile_n;     // [max_tiles] tokens in the tile
+    int32_t *n_tiles;    // [1]
 };
+constexpr int TILE_MAX_TOKENS = 256;
+inline int max_token_tiles(int64_t n_flat, int n_experts) { return (int)(n_flat / TILE_MAX_TOKENS) + n_experts; }
 
 void set_hip_error(hipError_t e);
 
@@ -39,7 +46,7 @@ int launch_tile_dense(const uint16_t *in, int64_t rows, int64_t cols, uint16_t *
 // route.hip
 int launch_route(const int32_t *ids, int32_t n_flat, int32_t k, int32_t n_experts, const int32_t *q_of_expert,
                  RouteTables rt, hipStream_t st);
-int launch_combine(const float *opart, int32_t ksplit, int64_t ks_stride, const RouteTables &rt,
+int launch_combine(const float *opart, int32_t ksplit, int32_t ksplit_shared, int64_t ks_stride, const RouteTables &rt,
                    const float *topk_w, int32_t T, int32_t k, int32_t d, int32_t n_shared,
                    uint16_t *y, hipStream_t st);
 
@@ -71,5 +78,25 @@ int stream_row_groups(int rows, bool down_stage);   // row groups (workgroup uni
 constexpr int STREAM_RESIDENT_WGS = 512;             // workgroups the chip holds at once (256 CUs x 2)
 int launch_stream_gateup(const StreamGroupArgs &a, bool dense, hipStream_t st);
 int launch_stream_down(const StreamGroupArgs &a, bool dense, hipStream_t st);
+
+// tile_gemm.hip: LDS-staged decode-GEMM on the matrix cores for large token counts per expert.
+struct TileGemmArgs {
+    const uint16_t *const *w_a;   // device array: gate (gate/up stage) or down (down stage)
+    const uint16_t *const *w_b;   // device array: up, or nullptr
+    int32_t rows, kdim;
+    const uint16_t *act;          // x, or the hi plane of H
+    int64_t act_plane_stride;
+    int32_t act_is_x, act_slot_base;
+    const int32_t *slot_tok;
+    const int32_t *tile_q, *tile_slot0, *tile_n, *n_tiles;   // routed groups: RouteTables tile list
+    int32_t dense_tokens, dense_slot_base, dense_tiles, dense_tile_tokens;   // dense group: uniform tiles
+    uint16_t *h_out;
+    int64_t h_plane_stride;
+    int32_t h_slot_base;
+    float *o_out;                 // down stage: [slots][rows] fp32
+    int32_t max_mtiles;           // upper bound on token tiles (grid size)
+};
+int launch_tile_gateup(const TileGemmArgs &a, bool dense, hipStream_t st);
+int launch_tile_down(const TileGemmArgs &a, bool dense, hipStream_t st);
 
 }  // namespace pzl

@@ -16,7 +16,9 @@ constexpr int ROUTE_QMAX = 512;
 __global__ void __launch_bounds__(ROUTE_THREADS)
 route_kernel(const int32_t *__restrict__ ids, int32_t n_flat, int32_t k, int32_t n_experts,
              const int32_t *__restrict__ q_of_expert, int32_t Q, int32_t *__restrict__ cnt,
-             int32_t *__restrict__ off, int32_t *__restrict__ slot_tok, int32_t *__restrict__ slot_of)
+             int32_t *__restrict__ off, int32_t *__restrict__ slot_tok, int32_t *__restrict__ slot_of,
+             int32_t *__restrict__ tile_q, int32_t *__restrict__ tile_slot0, int32_t *__restrict__ tile_n,
+             int32_t *__restrict__ n_tiles)
 {
     __shared__ int32_t hist[ROUTE_WAVES][ROUTE_QMAX];
     __shared__ int32_t total[ROUTE_QMAX];
@@ -46,9 +48,21 @@ route_kernel(const int32_t *__restrict__ ids, int32_t n_flat, int32_t k, int32_t
     }
     __syncthreads();
     if (tid == 0) {
-        int run = 0;
-        for (int q = 0; q < Q; ++q) { int c = total[q]; total[q] = run; off[q] = run; run += c; }
+        int run = 0, nt = 0;
+        for (int q = 0; q < Q; ++q) {
+            int c = total[q];
+            total[q] = run; off[q] = run;
+            // token tiles: equal parts of at most TILE_MAX_TOKENS, rounded up to whole fragments of 16
+            int parts = (c + TILE_MAX_TOKENS - 1) / TILE_MAX_TOKENS;
+            int size = parts ? (((c + parts - 1) / parts + 15) & ~15) : 0;
+            for (int s0 = 0; s0 < c; s0 += size) {
+                tile_q[nt] = q; tile_slot0[nt] = run + s0; tile_n[nt] = min(size, c - s0);
+                ++nt;
+            }
+            run += c;
+        }
         off[Q] = run;
+        *n_tiles = nt;
     }
     __syncthreads();
     for (int q = tid; q < Q; q += ROUTE_THREADS) {
@@ -93,7 +107,7 @@ __device__ __forceinline__ uint32_t f32_to_bf16_rne(float v)
 // y[t, c] = bf16( sum_j w[t,j] * sum_ks O[ks][slot_of(t,j)][c]  +  sum_s sum_ks O[ks][N + s*T + t][c] )
 // Fixed summation order (j ascending, k-splits ascending inside), so results are reproducible.
 __global__ void __launch_bounds__(256)
-combine_kernel(const float *__restrict__ opart, int32_t ksplit, int64_t ks_stride,
+combine_kernel(const float *__restrict__ opart, int32_t ksplit, int32_t ksplit_shared, int64_t ks_stride,
                const int32_t *__restrict__ slot_of, const float *__restrict__ topk_w, int32_t T,
                int32_t k, int32_t d, int32_t n_shared, uint16_t *__restrict__ y)
 {
@@ -114,7 +128,7 @@ combine_kernel(const float *__restrict__ opart, int32_t ksplit, int64_t ks_strid
     for (int sh = 0; sh < n_shared; ++sh) {
         const float *p = opart + (int64_t)(n_flat + sh * T + t) * d + c;
         f32x4 s = *(const f32x4 *)p;
-        for (int ks = 1; ks < ksplit; ++ks) s += *(const f32x4 *)(p + ks * ks_stride);
+        for (int ks = 1; ks < ksplit_shared; ++ks) s += *(const f32x4 *)(p + ks * ks_stride);
         acc += s;
     }
     u32x2 o;
@@ -129,18 +143,19 @@ int launch_route(const int32_t *ids, int32_t n_flat, int32_t k, int32_t n_expert
     int Q = n_experts;
     if (Q > ROUTE_QMAX) return PZL_EINVAL;
     hipLaunchKernelGGL(route_kernel, dim3(1), dim3(ROUTE_THREADS), 0, st, ids, n_flat, k, n_experts,
-                       q_of_expert, Q, rt.cnt, rt.off, rt.slot_tok, rt.slot_of);
+                       q_of_expert, Q, rt.cnt, rt.off, rt.slot_tok, rt.slot_of, rt.tile_q, rt.tile_slot0,
+                       rt.tile_n, rt.n_tiles);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) { set_hip_error(e); return PZL_EHIP; }
     return PZL_OK;
 }
 
-int launch_combine(const float *opart, int32_t ksplit, int64_t ks_stride, const RouteTables &rt,
+int launch_combine(const float *opart, int32_t ksplit, int32_t ksplit_shared, int64_t ks_stride, const RouteTables &rt,
                    const float *topk_w, int32_t T, int32_t k, int32_t d, int32_t n_shared,
                    uint16_t *y, hipStream_t st)
 {
     dim3 grid((unsigned)T, (unsigned)((d / 4 + 255) / 256));
-    hipLaunchKernelGGL(combine_kernel, grid, dim3(256), 0, st, opart, ksplit, ks_stride, rt.slot_of,
+    hipLaunchKernelGGL(combine_kernel, grid, dim3(256), 0, st, opart, ksplit, ksplit_shared, ks_stride, rt.slot_of,
                        topk_w, T, k, d, n_shared, y);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) { set_hip_error(e); return PZL_EHIP; }

@@ -1,0 +1,353 @@
+// Tiled decode-GEMM for large token counts per expert (prefill-sized batches): a dense
+// contraction on the matrix cores.
+//
+// Sec. 3.3.2 asks that every packed weight be decoded (Algorithm 1) right before it is
+// multiplied and that the decoded matrix never be materialised in memory.  With hundreds of
+// tokens per expert the work is MFMA-bound, so here a workgroup decodes each packed 16x32
+// tile ONCE into LDS (as bf16, already in matrix-core operand order) and all four waves
+// multiply it with up to 256 tokens: the decode cost is amortised over the token tile, and
+// the decoded weights live only in LDS.
+//
+// Workgroup tile: up to 256 tokens of one expert x 256 weight rows (gate/up stage: the same
+// 128 feature rows of the gate and of the up matrix, so SwiGLU runs on the accumulators; down
+// stage: 256 rows of the down matrix).  4 waves as 2 (tokens) x 2 (rows); a wave accumulates
+// up to 8 token fragments x 8 row tiles of v_mfma_f32_16x16x32_bf16 (256 accumulator
+// registers).  K advances in steps of 64 (gate/up) or 32 (down, whose token operand is the
+// hi and the lo plane of H); global loads for step k+1 are in flight while step k is
+// multiplied, LDS is double-buffered, one barrier per step.
+//
+// Token tiles are cut per expert into equal parts of at most 256 tokens (rounded up to 16),
+// so a 1030-token expert costs 5 x 208 rows rather than 5 x 256.
+#include "pzl_common.h"
+
+namespace pzl {
+
+constexpr int TG_THREADS = 256;
+constexpr int TG_MAX_TOK = 256;          // tokens per tile (16 fragments of 16)
+constexpr int TG_ROW_TILES = 16;         // 16-row weight tiles per workgroup (256 rows)
+constexpr int TG_STAGE_UNITS = 4096;     // 16-byte units per LDS stage (64 KiB)
+constexpr int TG_LDS_BYTES = 2 * TG_STAGE_UNITS * 16 + TG_MAX_TOK * 4;
+constexpr int TSTAGE_GATEUP = 0, TSTAGE_DOWN = 1;
+
+struct TgArgs {
+    const uint16_t *const *w_a;
+    const uint16_t *const *w_b;
+    int32_t rows, kdim;
+    const uint16_t *act;
+    int64_t act_plane_stride;
+    int32_t act_is_x, act_slot_base;
+    const int32_t *slot_tok;
+    const int32_t *tile_q, *tile_slot0, *tile_n, *n_tiles;   // routed: device tile list
+    int32_t dense_tokens, dense_slot_base, dense_tiles, dense_tile_tokens;   // dense: uniform tiles
+    uint16_t *h_out;
+    int64_t h_plane_stride;
+    int32_t h_slot_base;
+    float *o_out;
+    int32_t max_mtiles, n_ntiles;
+};
+
+__device__ __forceinline__ uint32_t tg_decode_body(uint32_t x) { return (x & 0x0FFF0FFFu) + 0x38003800u; }
+
+template <int POS>
+__device__ __forceinline__ uint32_t tg_decode_pair(uint32_t x)
+{
+    uint32_t body = tg_decode_body(x);
+    uint32_t xs = POS ? (x << 1) : x;
+    s16x2 t = __builtin_bit_cast(s16x2, x << (2 + POS));
+    t = t >> 15;
+    uint32_t m = __builtin_bit_cast(uint32_t, t);
+    return ((xs & 0x80008000u) | body) & m;
+}
+
+template <int POS, bool DENSE>
+__device__ __forceinline__ u32x4 tg_decode(u32x4 w)
+{
+    if (DENSE) return w;
+    u32x4 o;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) o[i] = tg_decode_pair<POS>(w[i]);
+    return o;
+}
+
+__device__ __forceinline__ uint32_t tg_bf16_rne(float v)
+{
+    uint32_t u = __float_as_uint(v);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return 0x7FC0u;
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+
+__device__ __forceinline__ void tg_swiglu_split(float g, float u, uint32_t &hi, uint32_t &lo)
+{
+    float h = (g / (1.0f + __expf(-g))) * u;
+    hi = tg_bf16_rne(h);
+    lo = tg_bf16_rne(h - __uint_as_float(hi << 16));
+}
+
+// The whole tile for one expert position (POS is the position of the expert inside its pair).
+// CNT = token fragments per wave: both token-side waves take ceil(n_frags / 2) fragments, so the
+// K loop has no data-dependent branch (a guard per fragment makes the register allocator move
+// accumulators between register files); an odd tile costs one padded fragment.
+template <int STAGE, bool DENSE, int POS, int CNT>
+__device__ __forceinline__ void tile_body(const TgArgs &a, const uint16_t *wa, const uint16_t *wb,
+                                          int slot0, int n_tok, int ntile, u32x4 *lds, int32_t *rowidx)
+{
+    constexpr int KBS = (STAGE == TSTAGE_DOWN) ? 1 : 2;      // k-blocks (of 32) per K step
+    constexpr int PARTS = (STAGE == TSTAGE_DOWN) ? 2 : 1;    // activation planes (hi, lo)
+    constexpr int W_UNITS = TG_ROW_TILES * KBS * 64;         // 16-byte units of decoded weights per stage
+    constexpr int X_UNITS = PARTS * 16 * KBS * 64;
+    static_assert(W_UNITS + X_UNITS <= TG_STAGE_UNITS, "stage does not fit");
+    constexpr int WPT = TG_ROW_TILES * KBS / 4;              // weight tiles each wave loads per step
+    constexpr int XPT = PARTS * 16 * KBS / 4;                // activation fragments each wave loads per step
+
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int wm = __builtin_amdgcn_readfirstlane(wave & 1);  // wave position along tokens
+    const int wn = __builtin_amdgcn_readfirstlane(wave >> 1); // wave position along rows
+    const int kb_total = a.kdim / TILE_COLS;
+    const int n_steps = (kb_total + KBS - 1) / KBS;
+    const int frag0 = wm * CNT;                              // fragments frag0 .. frag0+CNT-1 (< 16)
+    const int row_tiles = a.rows / TILE_ROWS;
+
+    // activation row behind each token column of the tile (clamped to the last valid token)
+    {
+        int slot = slot0 + min(tid, n_tok - 1);
+        int row;
+        if (a.act_is_x) row = DENSE ? (slot - a.dense_slot_base) % a.dense_tokens : a.slot_tok[slot];
+        else            row = slot - a.act_slot_base;
+        rowidx[tid] = row;
+    }
+    __syncthreads();
+
+    // ---- what this wave loads each step --------------------------------------------------
+    // weights: tile t = wave*WPT + i  ->  (local row tile t / KBS, k-block t % KBS)
+    typedef const u32x4 __attribute__((address_space(1))) *gvec_ptr;
+    gvec_ptr wsrc[WPT];
+#pragma unroll
+    for (int i = 0; i < WPT; ++i) {
+        int t = wave * WPT + i;
+        int lrt = t / KBS, kbo = t % KBS;
+        int grt;                                              // global row tile, clamped to the matrix
+        const uint16_t *base;
+        if (STAGE == TSTAGE_GATEUP) {
+            base = (lrt < 8) ? wa : wb;                       // local tiles 0..7 gate, 8..15 up
+            grt = min(ntile * 8 + (lrt & 7), row_tiles - 1);
+        } else {
+            base = wa;
+            grt = min(ntile * TG_ROW_TILES + lrt, row_tiles - 1);
+        }
+        wsrc[i] = (gvec_ptr)(uintptr_t)base + ((int64_t)grt * kb_total + kbo) * 64 + lane;
+    }
+    // activations: fragment column c = wave*XPT + i -> (plane, token fragment, k-block)
+    const uint16_t *xsrc[XPT];
+#pragma unroll
+    for (int i = 0; i < XPT; ++i) {
+        int c = wave * XPT + i;
+        int kbo = c % KBS, fr = (c / KBS) % 16, part = c / (KBS * 16);
+        xsrc[i] = a.act + part * a.act_plane_stride +
+                  (int64_t)rowidx[fr * 16 + (lane & 15)] * a.kdim + kbo * TILE_COLS + (lane >> 4) * 8;
+    }
+
+    u32x4 wreg[WPT], xreg[XPT];
+    const u32x4 zero4 = {0u, 0u, 0u, 0u};
+    auto issue_loads = [&](int step) {
+        // a k-block past the end re-reads the last valid one; its activations are stored as zero
+#pragma unroll
+        for (int i = 0; i < WPT; ++i) {
+            int kbo = (wave * WPT + i) % KBS;
+            int kb = min(step * KBS + kbo, kb_total - 1) - kbo;
+            wreg[i] = __builtin_nontemporal_load(wsrc[i] + (int64_t)kb * 64);
+        }
+#pragma unroll
+        for (int i = 0; i < XPT; ++i) {
+            int kbo = (wave * XPT + i) % KBS;
+            int kb = min(step * KBS + kbo, kb_total - 1) - kbo;
+            xreg[i] = *(const u32x4 *)(xsrc[i] + kb * TILE_COLS);
+        }
+    };
+    auto store_stage = [&](int stage, int step) {
+        u32x4 *ws = lds + stage * TG_STAGE_UNITS;
+        u32x4 *xs = ws + W_UNITS;
+#pragma unroll
+        for (int i = 0; i < WPT; ++i)
+            ws[(wave * WPT + i) * 64 + lane] = tg_decode<POS, DENSE>(wreg[i]);
+#pragma unroll
+        for (int i = 0; i < XPT; ++i) {
+            int c = wave * XPT + i;
+            bool valid = step * KBS + c % KBS < kb_total;
+            xs[c * 64 + lane] = valid ? xreg[i] : zero4;
+        }
+    };
+
+    f32x4 acc[8][CNT];
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+#pragma unroll
+        for (int i = 0; i < CNT; ++i) acc[j][i] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+    issue_loads(0);
+    store_stage(0, 0);
+    __syncthreads();
+
+    for (int step = 0; step < n_steps; ++step) {
+        const bool has_next = step + 1 < n_steps;
+        if (has_next) issue_loads(step + 1);
+
+        const u32x4 *ws = lds + (step & 1) * TG_STAGE_UNITS;
+        const u32x4 *xs = ws + W_UNITS;
+#pragma unroll
+        for (int kbo = 0; kbo < KBS; ++kbo) {
+            // this wave's 8 weight row tiles: gate/up stage -> gate tiles wn*4..+3 and up tiles
+            // 8+wn*4..+3 (same feature rows); down stage -> tiles wn*8..+7
+            bf16x8 af[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                int lrt = (STAGE == TSTAGE_GATEUP) ? ((j < 4) ? wn * 4 + j : 8 + wn * 4 + (j - 4)) : wn * 8 + j;
+                af[j] = __builtin_bit_cast(bf16x8, ws[(lrt * KBS + kbo) * 64 + lane]);
+            }
+#pragma unroll
+            for (int i = 0; i < CNT; ++i) {
+#pragma unroll
+                for (int part = 0; part < PARTS; ++part) {
+                    bf16x8 b = __builtin_bit_cast(bf16x8, xs[((part * 16 + frag0 + i) * KBS + kbo) * 64 + lane]);
+#pragma unroll
+                    for (int j = 0; j < 8; ++j)
+                        acc[j][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[j], b, acc[j][i], 0, 0, 0);
+                }
+            }
+        }
+        if (has_next) store_stage((step + 1) & 1, step + 1);
+        __syncthreads();
+    }
+
+    // ---- epilogue: lane holds rows 4*(lane/16)..+3 of its row tile for token column lane%16 ----
+    const int col = lane & 15, rsub = (lane >> 4) * 4;
+#pragma unroll
+    for (int i = 0; i < CNT; ++i) {
+        int within = (frag0 + i) * 16 + col;
+        if (within >= n_tok) continue;
+        int slot = slot0 + within;
+        if (STAGE == TSTAGE_GATEUP) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                int grt = ntile * 8 + wn * 4 + j;
+                if (grt >= row_tiles) continue;
+                f32x4 g = acc[j][i], u = acc[j + 4][i];
+                uint32_t hi[4], lo[4];
+#pragma unroll
+                for (int r = 0; r < 4; ++r) tg_swiglu_split(g[r], u[r], hi[r], lo[r]);
+                u32x2 ohi = {hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16)};
+                u32x2 olo = {lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16)};
+                uint16_t *dst = a.h_out + (int64_t)(slot - a.h_slot_base) * a.rows + grt * 16 + rsub;
+                *(u32x2 *)dst = ohi;
+                *(u32x2 *)(dst + a.h_plane_stride) = olo;
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                int grt = ntile * TG_ROW_TILES + wn * 8 + j;
+                if (grt >= row_tiles) continue;
+                *(f32x4 *)(a.o_out + (int64_t)slot * a.rows + grt * 16 + rsub) = acc[j][i];
+            }
+        }
+    }
+}
+
+template <int STAGE, bool DENSE>
+__global__ void __launch_bounds__(TG_THREADS) __attribute__((amdgpu_waves_per_eu(1, 1)))
+tile_kernel(TgArgs a)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+    u32x4 *lds = (u32x4 *)lds_raw;
+    int32_t *rowidx = (int32_t *)(lds_raw + 2 * TG_STAGE_UNITS * 16);
+
+    // XCD-aware order: consecutive workgroup ids go to different XCDs (8 of them, each with its
+    // own L2), so give each XCD a contiguous range of logical tiles, token tiles fastest: the
+    // token tiles that share a weight tile then run on the same XCD at about the same time.
+    const int total = gridDim.x;
+    const int per_xcd = (total + 7) / 8;
+    const int logical = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+    if (logical >= a.max_mtiles * a.n_ntiles) return;
+    const int mt = logical % a.max_mtiles;
+    const int ntile = logical / a.max_mtiles;
+
+    int g, pos, slot0, n_tok;
+    if (DENSE) {
+        if (mt >= a.dense_tiles) return;
+        g = mt / ((a.dense_tokens + a.dense_tile_tokens - 1) / a.dense_tile_tokens);
+        int t_in = mt % ((a.dense_tokens + a.dense_tile_tokens - 1) / a.dense_tile_tokens);
+        pos = 0;
+        slot0 = a.dense_slot_base + g * a.dense_tokens + t_in * a.dense_tile_tokens;
+        n_tok = min(a.dense_tile_tokens, a.dense_tokens - t_in * a.dense_tile_tokens);
+    } else {
+        if (mt >= *a.n_tiles) return;
+        int q = a.tile_q[mt];
+        g = q >> 1; pos = q & 1;
+        slot0 = a.tile_slot0[mt];
+        n_tok = a.tile_n[mt];
+    }
+    // these are the same for the whole workgroup; say so, or the per-fragment guards below become
+    // exec-masked branches and the accumulators get shuffled between register files
+    g = __builtin_amdgcn_readfirstlane(g);
+    pos = __builtin_amdgcn_readfirstlane(pos);
+    slot0 = __builtin_amdgcn_readfirstlane(slot0);
+    n_tok = __builtin_amdgcn_readfirstlane(n_tok);
+    const uint16_t *wa = a.w_a[g];
+    const uint16_t *wb = (STAGE == TSTAGE_GATEUP) ? a.w_b[g] : wa;
+    const int cnt = (((n_tok + 15) >> 4) + 1) >> 1;          // 1..8 fragments per wave
+#define PZL_TILE(P, C) tile_body<STAGE, DENSE, P, C>(a, wa, wb, slot0, n_tok, ntile, lds, rowidx)
+#define PZL_TILE_CNT(P)                                                         \
+    switch (cnt) {                                                              \
+        case 1: PZL_TILE(P, 1); break; case 2: PZL_TILE(P, 2); break;           \
+        case 3: PZL_TILE(P, 3); break; case 4: PZL_TILE(P, 4); break;           \
+        case 5: PZL_TILE(P, 5); break; case 6: PZL_TILE(P, 6); break;           \
+        case 7: PZL_TILE(P, 7); break; default: PZL_TILE(P, 8); break;          \
+    }
+    if (DENSE || pos == 0) { PZL_TILE_CNT(0) } else { PZL_TILE_CNT(1) }
+#undef PZL_TILE_CNT
+#undef PZL_TILE
+}
+
+template <int STAGE, bool DENSE>
+static int launch(const TileGemmArgs &t, hipStream_t st)
+{
+    if (t.max_mtiles <= 0) return PZL_OK;
+    if (t.rows % TILE_ROWS || t.kdim % TILE_COLS) return PZL_EINVAL;
+    TgArgs a;
+    a.w_a = t.w_a; a.w_b = t.w_b; a.rows = t.rows; a.kdim = t.kdim;
+    a.act = t.act; a.act_plane_stride = t.act_plane_stride; a.act_is_x = t.act_is_x;
+    a.act_slot_base = t.act_slot_base; a.slot_tok = t.slot_tok;
+    a.tile_q = t.tile_q; a.tile_slot0 = t.tile_slot0; a.tile_n = t.tile_n; a.n_tiles = t.n_tiles;
+    a.dense_tokens = t.dense_tokens; a.dense_slot_base = t.dense_slot_base;
+    a.dense_tiles = t.dense_tiles; a.dense_tile_tokens = t.dense_tile_tokens;
+    a.h_out = t.h_out; a.h_plane_stride = t.h_plane_stride; a.h_slot_base = t.h_slot_base;
+    a.o_out = t.o_out;
+    a.max_mtiles = t.max_mtiles;
+    const int rows_per_wg = (STAGE == TSTAGE_GATEUP) ? 128 : 256;
+    a.n_ntiles = (t.rows + rows_per_wg - 1) / rows_per_wg;
+    int64_t blocks = (int64_t)a.max_mtiles * a.n_ntiles;
+    blocks = (blocks + 7) / 8 * 8;
+    if (blocks > 0x7FFFFFFFLL) return PZL_EINVAL;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void *)tile_kernel<STAGE, DENSE>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, TG_LDS_BYTES);
+        if (e != hipSuccess) { set_hip_error(e); return PZL_EHIP; }
+        attr_set = true;
+    }
+    hipLaunchKernelGGL((tile_kernel<STAGE, DENSE>), dim3((unsigned)blocks), dim3(TG_THREADS), TG_LDS_BYTES, st, a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) { set_hip_error(e); return PZL_EHIP; }
+    return PZL_OK;
+}
+
+int launch_tile_gateup(const TileGemmArgs &a, bool dense, hipStream_t st)
+{
+    return dense ? launch<TSTAGE_GATEUP, true>(a, st) : launch<TSTAGE_GATEUP, false>(a, st);
+}
+
+int launch_tile_down(const TileGemmArgs &a, bool dense, hipStream_t st)
+{
+    return dense ? launch<TSTAGE_DOWN, true>(a, st) : launch<TSTAGE_DOWN, false>(a, st);
+}
+
+}  // namespace pzl
