@@ -10,9 +10,10 @@
 //
 // Workgroup tile: up to 256 tokens of one expert x 256 weight rows (gate/up stage: the same
 // 128 feature rows of the gate and of the up matrix, so SwiGLU runs on the accumulators; down
-// stage: 256 rows of the down matrix).  4 waves as 2 (tokens) x 2 (rows); a wave accumulates
-// up to 8 token fragments x 8 row tiles of v_mfma_f32_16x16x32_bf16 (256 accumulator
-// registers).  K advances in steps of 64 (gate/up) or 32 (down, whose token operand is the
+// stage: 256 rows of the down matrix).  8 waves as 2 (tokens) x 4 (rows), two per SIMD so that
+// one wave's LDS and memory waits are covered by the other; a wave accumulates up to 8 token
+// fragments x 4 row tiles of v_mfma_f32_16x16x32_bf16 (128 accumulator registers, which keeps
+// the whole wave inside the 256 registers it gets at two waves per SIMD).  K advances in steps of 64 (gate/up) or 32 (down, whose token operand is the
 // hi and the lo plane of H); global loads for step k+1 are in flight while step k is
 // multiplied, LDS is double-buffered, one barrier per step.
 //
@@ -22,7 +23,8 @@
 
 namespace pzl {
 
-constexpr int TG_THREADS = 256;
+constexpr int TG_THREADS = 512;
+constexpr int TG_WAVES = 8;
 constexpr int TG_MAX_TOK = 256;          // tokens per tile (16 fragments of 16)
 constexpr int TG_ROW_TILES = 16;         // 16-row weight tiles per workgroup (256 rows)
 constexpr int TG_STAGE_UNITS = 4096;     // 16-byte units per LDS stage (64 KiB)
@@ -97,19 +99,20 @@ __device__ __forceinline__ void tile_body(const TgArgs &a, const uint16_t *wa, c
     constexpr int W_UNITS = TG_ROW_TILES * KBS * 64;         // 16-byte units of decoded weights per stage
     constexpr int X_UNITS = PARTS * 16 * KBS * 64;
     static_assert(W_UNITS + X_UNITS <= TG_STAGE_UNITS, "stage does not fit");
-    constexpr int WPT = TG_ROW_TILES * KBS / 4;              // weight tiles each wave loads per step
-    constexpr int XPT = PARTS * 16 * KBS / 4;                // activation fragments each wave loads per step
+    constexpr int WPT = TG_ROW_TILES * KBS / TG_WAVES;       // weight tiles each wave loads per step
+    constexpr int XPT = PARTS * 16 * KBS / TG_WAVES;         // activation fragments each wave loads per step
+    constexpr int RT = 4;                                    // row tiles per wave
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int wm = __builtin_amdgcn_readfirstlane(wave & 1);  // wave position along tokens
-    const int wn = __builtin_amdgcn_readfirstlane(wave >> 1); // wave position along rows
+    const int wn = __builtin_amdgcn_readfirstlane(wave >> 1); // wave position along rows (0..3)
     const int kb_total = a.kdim / TILE_COLS;
     const int n_steps = (kb_total + KBS - 1) / KBS;
     const int frag0 = wm * CNT;                              // fragments frag0 .. frag0+CNT-1 (< 16)
     const int row_tiles = a.rows / TILE_ROWS;
 
     // activation row behind each token column of the tile (clamped to the last valid token)
-    {
+    if (tid < TG_MAX_TOK) {
         int slot = slot0 + min(tid, n_tok - 1);
         int row;
         if (a.act_is_x) row = DENSE ? (slot - a.dense_slot_base) % a.dense_tokens : a.slot_tok[slot];
@@ -120,8 +123,9 @@ __device__ __forceinline__ void tile_body(const TgArgs &a, const uint16_t *wa, c
 
     // ---- what this wave loads each step --------------------------------------------------
     // weights: tile t = wave*WPT + i  ->  (local row tile t / KBS, k-block t % KBS)
+    // (the tile base is the same for all lanes: keep it in scalar registers and add the lane)
     typedef const u32x4 __attribute__((address_space(1))) *gvec_ptr;
-    gvec_ptr wsrc[WPT];
+    uint64_t wbase[WPT];
 #pragma unroll
     for (int i = 0; i < WPT; ++i) {
         int t = wave * WPT + i;
@@ -135,16 +139,20 @@ __device__ __forceinline__ void tile_body(const TgArgs &a, const uint16_t *wa, c
             base = wa;
             grt = min(ntile * TG_ROW_TILES + lrt, row_tiles - 1);
         }
-        wsrc[i] = (gvec_ptr)(uintptr_t)base + ((int64_t)grt * kb_total + kbo) * 64 + lane;
+        uint64_t p = (uint64_t)(uintptr_t)base + (((int64_t)grt * kb_total + kbo) * 64) * 16;
+        uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)p);
+        uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(p >> 32));
+        wbase[i] = ((uint64_t)hi << 32) | lo;
     }
-    // activations: fragment column c = wave*XPT + i -> (plane, token fragment, k-block)
-    const uint16_t *xsrc[XPT];
+    // activations: fragment column c = wave*XPT + i -> (plane, token fragment, k-block);
+    // 32-bit element offsets from the activation base (every activation buffer is < 2^31 elements)
+    uint32_t xoff[XPT];
 #pragma unroll
     for (int i = 0; i < XPT; ++i) {
         int c = wave * XPT + i;
         int kbo = c % KBS, fr = (c / KBS) % 16, part = c / (KBS * 16);
-        xsrc[i] = a.act + part * a.act_plane_stride +
-                  (int64_t)rowidx[fr * 16 + (lane & 15)] * a.kdim + kbo * TILE_COLS + (lane >> 4) * 8;
+        xoff[i] = (uint32_t)(part * a.act_plane_stride) +
+                  (uint32_t)rowidx[fr * 16 + (lane & 15)] * (uint32_t)a.kdim + kbo * TILE_COLS + (lane >> 4) * 8;
     }
 
     u32x4 wreg[WPT], xreg[XPT];
@@ -155,13 +163,13 @@ __device__ __forceinline__ void tile_body(const TgArgs &a, const uint16_t *wa, c
         for (int i = 0; i < WPT; ++i) {
             int kbo = (wave * WPT + i) % KBS;
             int kb = min(step * KBS + kbo, kb_total - 1) - kbo;
-            wreg[i] = __builtin_nontemporal_load(wsrc[i] + (int64_t)kb * 64);
+            wreg[i] = __builtin_nontemporal_load((gvec_ptr)wbase[i] + (int64_t)kb * 64 + lane);
         }
 #pragma unroll
         for (int i = 0; i < XPT; ++i) {
             int kbo = (wave * XPT + i) % KBS;
             int kb = min(step * KBS + kbo, kb_total - 1) - kbo;
-            xreg[i] = *(const u32x4 *)(xsrc[i] + kb * TILE_COLS);
+            xreg[i] = *(const u32x4 *)(a.act + (xoff[i] + (uint32_t)(kb * TILE_COLS)));
         }
     };
     auto store_stage = [&](int stage, int step) {
@@ -178,9 +186,9 @@ __device__ __forceinline__ void tile_body(const TgArgs &a, const uint16_t *wa, c
         }
     };
 
-    f32x4 acc[8][CNT];
+    f32x4 acc[RT][CNT];
 #pragma unroll
-    for (int j = 0; j < 8; ++j)
+    for (int j = 0; j < RT; ++j)
 #pragma unroll
         for (int i = 0; i < CNT; ++i) acc[j][i] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
@@ -196,12 +204,12 @@ __device__ __forceinline__ void tile_body(const TgArgs &a, const uint16_t *wa, c
         const u32x4 *xs = ws + W_UNITS;
 #pragma unroll
         for (int kbo = 0; kbo < KBS; ++kbo) {
-            // this wave's 8 weight row tiles: gate/up stage -> gate tiles wn*4..+3 and up tiles
-            // 8+wn*4..+3 (same feature rows); down stage -> tiles wn*8..+7
-            bf16x8 af[8];
+            // this wave's 4 weight row tiles: gate/up stage -> gate tiles wn*2, wn*2+1 and up tiles
+            // 8+wn*2, 8+wn*2+1 (same feature rows); down stage -> tiles wn*4..+3
+            bf16x8 af[RT];
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                int lrt = (STAGE == TSTAGE_GATEUP) ? ((j < 4) ? wn * 4 + j : 8 + wn * 4 + (j - 4)) : wn * 8 + j;
+            for (int j = 0; j < RT; ++j) {
+                int lrt = (STAGE == TSTAGE_GATEUP) ? ((j < 2) ? wn * 2 + j : 8 + wn * 2 + (j - 2)) : wn * 4 + j;
                 af[j] = __builtin_bit_cast(bf16x8, ws[(lrt * KBS + kbo) * 64 + lane]);
             }
 #pragma unroll
@@ -210,7 +218,7 @@ __device__ __forceinline__ void tile_body(const TgArgs &a, const uint16_t *wa, c
                 for (int part = 0; part < PARTS; ++part) {
                     bf16x8 b = __builtin_bit_cast(bf16x8, xs[((part * 16 + frag0 + i) * KBS + kbo) * 64 + lane]);
 #pragma unroll
-                    for (int j = 0; j < 8; ++j)
+                    for (int j = 0; j < RT; ++j)
                         acc[j][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[j], b, acc[j][i], 0, 0, 0);
                 }
             }
@@ -228,10 +236,10 @@ __device__ __forceinline__ void tile_body(const TgArgs &a, const uint16_t *wa, c
         int slot = slot0 + within;
         if (STAGE == TSTAGE_GATEUP) {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                int grt = ntile * 8 + wn * 4 + j;
+            for (int j = 0; j < 2; ++j) {
+                int grt = ntile * 8 + wn * 2 + j;
                 if (grt >= row_tiles) continue;
-                f32x4 g = acc[j][i], u = acc[j + 4][i];
+                f32x4 g = acc[j][i], u = acc[j + 2][i];
                 uint32_t hi[4], lo[4];
 #pragma unroll
                 for (int r = 0; r < 4; ++r) tg_swiglu_split(g[r], u[r], hi[r], lo[r]);
@@ -243,8 +251,8 @@ __device__ __forceinline__ void tile_body(const TgArgs &a, const uint16_t *wa, c
             }
         } else {
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                int grt = ntile * TG_ROW_TILES + wn * 8 + j;
+            for (int j = 0; j < RT; ++j) {
+                int grt = ntile * TG_ROW_TILES + wn * 4 + j;
                 if (grt >= row_tiles) continue;
                 *(f32x4 *)(a.o_out + (int64_t)slot * a.rows + grt * 16 + rsub) = acc[j][i];
             }
@@ -253,7 +261,7 @@ __device__ __forceinline__ void tile_body(const TgArgs &a, const uint16_t *wa, c
 }
 
 template <int STAGE, bool DENSE>
-__global__ void __launch_bounds__(TG_THREADS) __attribute__((amdgpu_waves_per_eu(1, 1)))
+__global__ void __launch_bounds__(TG_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2)))
 tile_kernel(TgArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
@@ -295,6 +303,9 @@ tile_kernel(TgArgs a)
     const uint16_t *wb = (STAGE == TSTAGE_GATEUP) ? a.w_b[g] : wa;
     const int cnt = (((n_tok + 15) >> 4) + 1) >> 1;          // 1..8 fragments per wave
 #define PZL_TILE(P, C) tile_body<STAGE, DENSE, P, C>(a, wa, wb, slot0, n_tok, ntile, lds, rowidx)
+#ifdef TG_ONLY_CNT8
+#define PZL_TILE_CNT(P) PZL_TILE(P, 8);
+#else
 #define PZL_TILE_CNT(P)                                                         \
     switch (cnt) {                                                              \
         case 1: PZL_TILE(P, 1); break; case 2: PZL_TILE(P, 2); break;           \
@@ -302,6 +313,7 @@ tile_kernel(TgArgs a)
         case 5: PZL_TILE(P, 5); break; case 6: PZL_TILE(P, 6); break;           \
         case 7: PZL_TILE(P, 7); break; default: PZL_TILE(P, 8); break;          \
     }
+#endif
     if (DENSE || pos == 0) { PZL_TILE_CNT(0) } else { PZL_TILE_CNT(1) }
 #undef PZL_TILE_CNT
 #undef PZL_TILE
