@@ -8,28 +8,54 @@
 // multiply it with up to 256 tokens: the decode cost is amortised over the token tile, and
 // the decoded weights live only in LDS.
 //
-// Workgroup tile: up to 256 tokens of one expert x 256 weight rows (gate/up stage: the same
-// 128 feature rows of the gate and of the up matrix, so SwiGLU runs on the accumulators; down
-// stage: 256 rows of the down matrix).  8 waves as 2 (tokens) x 4 (rows), two per SIMD so that
-// one wave's LDS and memory waits are covered by the other; a wave accumulates up to 8 token
-// fragments x 4 row tiles of v_mfma_f32_16x16x32_bf16 (128 accumulator registers, which keeps
-// the whole wave inside the 256 registers it gets at two waves per SIMD).  K advances in steps of 64 (gate/up) or 32 (down, whose token operand is the
-// hi and the lo plane of H); global loads for step k+1 are in flight while step k is
-// multiplied, LDS is double-buffered, one barrier per step.
+// Workgroup tile: gate/up stage up to 256 tokens x 128 weight rows (the same 64 feature rows of
+// the gate and of the up matrix, so SwiGLU runs on the accumulators); down stage up to 128
+// tokens x 128 rows of the down matrix with both planes (hi, lo) of H as the token operand.
+// 4 waves as 2 (tokens) x 2 (rows), each accumulating up to 8 token fragments x 4 row tiles of
+// v_mfma_f32_16x16x32_bf16.  K advances 32 at a time; the global loads of step k+1 are in flight
+// while step k is multiplied; LDS is double-buffered (24 KiB per stage), one barrier per step.
+// The tile is deliberately small enough (48 KiB of LDS, 256 registers per wave) for TWO
+// workgroups per compute unit: the store / barrier / first-read bubble of one workgroup is
+// filled by the other's MFMAs.  A single 512-thread workgroup with 256 x 256 tiles was measured
+// slower: its eight waves hit the same barrier, so nothing covered the bubble.
 //
 // Token tiles are cut per expert into equal parts of at most 256 tokens (rounded up to 16),
-// so a 1030-token expert costs 5 x 208 rows rather than 5 x 256.
+// so a 1030-token expert costs 5 x 208 rows rather than 5 x 256; the down stage takes each
+// such tile in two halves.
 #include "pzl_common.h"
 
 namespace pzl {
 
-constexpr int TG_THREADS = 512;
-constexpr int TG_WAVES = 8;
-constexpr int TG_MAX_TOK = 256;          // tokens per tile (16 fragments of 16)
-constexpr int TG_ROW_TILES = 16;         // 16-row weight tiles per workgroup (256 rows)
-constexpr int TG_STAGE_UNITS = 4096;     // 16-byte units per LDS stage (64 KiB)
+#ifndef TG_WN
+#define TG_WN 4            // waves along the weight rows (2 more along the tokens)
+#endif
+#ifndef TG_RT
+#define TG_RT 4            // 16-row weight tiles per wave
+#endif
+#ifndef TG_KBS_GATEUP
+#define TG_KBS_GATEUP 2    // k-blocks of 32 per K step, gate/up stage
+#endif
+#ifndef TG_DOWN_TOK
+#define TG_DOWN_TOK 256    // tokens per down tile (256, or 128: half a gate/up tile)
+#endif
+#ifndef TG_WPE
+#define TG_WPE 2
+#endif
+constexpr int TG_WAVES = 2 * TG_WN;
+constexpr int TG_THREADS = TG_WAVES * 64;
+constexpr int TG_MAX_TOK = 256;          // tokens per gate/up tile (16 fragments of 16)
+constexpr int TG_ROW_TILES = TG_WN * TG_RT;   // 16-row weight tiles per workgroup
+constexpr int TG_STAGE_UNITS = (TG_ROW_TILES + 16) * TG_KBS_GATEUP * 64 > (TG_ROW_TILES + 2 * TG_DOWN_TOK / 16) * 64
+                                   ? (TG_ROW_TILES + 16) * TG_KBS_GATEUP * 64
+                                   : (TG_ROW_TILES + 2 * TG_DOWN_TOK / 16) * 64;   // 16-byte units per LDS stage
 constexpr int TG_LDS_BYTES = 2 * TG_STAGE_UNITS * 16 + TG_MAX_TOK * 4;
 constexpr int TSTAGE_GATEUP = 0, TSTAGE_DOWN = 1;
+#ifndef TG_BLOCK_M
+#define TG_BLOCK_M 8
+#endif
+#ifndef TG_BLOCK_N
+#define TG_BLOCK_N 4
+#endif
 
 struct TgArgs {
     const uint16_t *const *w_a;
@@ -94,18 +120,19 @@ template <int STAGE, bool DENSE, int POS, int CNT>
 __device__ __forceinline__ void tile_body(const TgArgs &a, const uint16_t *wa, const uint16_t *wb,
                                           int slot0, int n_tok, int ntile, u32x4 *lds, int32_t *rowidx)
 {
-    constexpr int KBS = (STAGE == TSTAGE_DOWN) ? 1 : 2;      // k-blocks (of 32) per K step
+    constexpr int KBS = (STAGE == TSTAGE_DOWN) ? 1 : TG_KBS_GATEUP;   // k-blocks (of 32) per K step
+    constexpr int FR = (STAGE == TSTAGE_DOWN) ? TG_DOWN_TOK / 16 : TG_MAX_TOK / 16;   // token fragment slots
     constexpr int PARTS = (STAGE == TSTAGE_DOWN) ? 2 : 1;    // activation planes (hi, lo)
     constexpr int W_UNITS = TG_ROW_TILES * KBS * 64;         // 16-byte units of decoded weights per stage
-    constexpr int X_UNITS = PARTS * 16 * KBS * 64;
+    constexpr int X_UNITS = PARTS * FR * KBS * 64;
     static_assert(W_UNITS + X_UNITS <= TG_STAGE_UNITS, "stage does not fit");
     constexpr int WPT = TG_ROW_TILES * KBS / TG_WAVES;       // weight tiles each wave loads per step
-    constexpr int XPT = PARTS * 16 * KBS / TG_WAVES;         // activation fragments each wave loads per step
-    constexpr int RT = 4;                                    // row tiles per wave
+    constexpr int XPT = PARTS * FR * KBS / TG_WAVES;         // activation fragments each wave loads per step
+    constexpr int RT = TG_RT;                                // row tiles per wave
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int wm = __builtin_amdgcn_readfirstlane(wave & 1);  // wave position along tokens
-    const int wn = __builtin_amdgcn_readfirstlane(wave >> 1); // wave position along rows (0..3)
+    const int wn = __builtin_amdgcn_readfirstlane(wave >> 1); // wave position along rows
     const int kb_total = a.kdim / TILE_COLS;
     const int n_steps = (kb_total + KBS - 1) / KBS;
     const int frag0 = wm * CNT;                              // fragments frag0 .. frag0+CNT-1 (< 16)
@@ -133,8 +160,9 @@ __device__ __forceinline__ void tile_body(const TgArgs &a, const uint16_t *wa, c
         int grt;                                              // global row tile, clamped to the matrix
         const uint16_t *base;
         if (STAGE == TSTAGE_GATEUP) {
-            base = (lrt < 8) ? wa : wb;                       // local tiles 0..7 gate, 8..15 up
-            grt = min(ntile * 8 + (lrt & 7), row_tiles - 1);
+            constexpr int HALF = TG_ROW_TILES / 2;            // local tiles [0,HALF) gate, [HALF,2*HALF) up
+            base = (lrt < HALF) ? wa : wb;
+            grt = min(ntile * HALF + (lrt % HALF), row_tiles - 1);
         } else {
             base = wa;
             grt = min(ntile * TG_ROW_TILES + lrt, row_tiles - 1);
@@ -150,7 +178,7 @@ __device__ __forceinline__ void tile_body(const TgArgs &a, const uint16_t *wa, c
 #pragma unroll
     for (int i = 0; i < XPT; ++i) {
         int c = wave * XPT + i;
-        int kbo = c % KBS, fr = (c / KBS) % 16, part = c / (KBS * 16);
+        int kbo = c % KBS, fr = (c / KBS) % FR, part = c / (KBS * FR);
         xoff[i] = (uint32_t)(part * a.act_plane_stride) +
                   (uint32_t)rowidx[fr * 16 + (lane & 15)] * (uint32_t)a.kdim + kbo * TILE_COLS + (lane >> 4) * 8;
     }
@@ -205,18 +233,18 @@ __device__ __forceinline__ void tile_body(const TgArgs &a, const uint16_t *wa, c
 #pragma unroll
         for (int kbo = 0; kbo < KBS; ++kbo) {
             // this wave's 4 weight row tiles: gate/up stage -> gate tiles wn*2, wn*2+1 and up tiles
-            // 8+wn*2, 8+wn*2+1 (same feature rows); down stage -> tiles wn*4..+3
+            // 4+wn*2, 4+wn*2+1 (same feature rows); down stage -> tiles wn*4..+3
             bf16x8 af[RT];
 #pragma unroll
             for (int j = 0; j < RT; ++j) {
-                int lrt = (STAGE == TSTAGE_GATEUP) ? ((j < 2) ? wn * 2 + j : 8 + wn * 2 + (j - 2)) : wn * 4 + j;
+                int lrt = (STAGE == TSTAGE_GATEUP) ? ((j < RT / 2) ? wn * (RT / 2) + j : TG_ROW_TILES / 2 + wn * (RT / 2) + (j - RT / 2)) : wn * RT + j;
                 af[j] = __builtin_bit_cast(bf16x8, ws[(lrt * KBS + kbo) * 64 + lane]);
             }
 #pragma unroll
             for (int i = 0; i < CNT; ++i) {
 #pragma unroll
                 for (int part = 0; part < PARTS; ++part) {
-                    bf16x8 b = __builtin_bit_cast(bf16x8, xs[((part * 16 + frag0 + i) * KBS + kbo) * 64 + lane]);
+                    bf16x8 b = __builtin_bit_cast(bf16x8, xs[((part * FR + frag0 + i) * KBS + kbo) * 64 + lane]);
 #pragma unroll
                     for (int j = 0; j < RT; ++j)
                         acc[j][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[j], b, acc[j][i], 0, 0, 0);
@@ -236,10 +264,10 @@ __device__ __forceinline__ void tile_body(const TgArgs &a, const uint16_t *wa, c
         int slot = slot0 + within;
         if (STAGE == TSTAGE_GATEUP) {
 #pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                int grt = ntile * 8 + wn * 2 + j;
+            for (int j = 0; j < RT / 2; ++j) {
+                int grt = ntile * (TG_ROW_TILES / 2) + wn * (RT / 2) + j;
                 if (grt >= row_tiles) continue;
-                f32x4 g = acc[j][i], u = acc[j + 2][i];
+                f32x4 g = acc[j][i], u = acc[j + RT / 2][i];
                 uint32_t hi[4], lo[4];
 #pragma unroll
                 for (int r = 0; r < 4; ++r) tg_swiglu_split(g[r], u[r], hi[r], lo[r]);
@@ -252,7 +280,7 @@ __device__ __forceinline__ void tile_body(const TgArgs &a, const uint16_t *wa, c
         } else {
 #pragma unroll
             for (int j = 0; j < RT; ++j) {
-                int grt = ntile * TG_ROW_TILES + wn * 4 + j;
+                int grt = ntile * TG_ROW_TILES + wn * RT + j;
                 if (grt >= row_tiles) continue;
                 *(f32x4 *)(a.o_out + (int64_t)slot * a.rows + grt * 16 + rsub) = acc[j][i];
             }
@@ -261,23 +289,31 @@ __device__ __forceinline__ void tile_body(const TgArgs &a, const uint16_t *wa, c
 }
 
 template <int STAGE, bool DENSE>
-__global__ void __launch_bounds__(TG_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2)))
+__global__ void __launch_bounds__(TG_THREADS) __attribute__((amdgpu_waves_per_eu(TG_WPE, TG_WPE)))
 tile_kernel(TgArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
     u32x4 *lds = (u32x4 *)lds_raw;
     int32_t *rowidx = (int32_t *)(lds_raw + 2 * TG_STAGE_UNITS * 16);
 
-    // XCD-aware order: consecutive workgroup ids go to different XCDs (8 of them, each with its
-    // own L2), so give each XCD a contiguous range of logical tiles, token tiles fastest: the
-    // token tiles that share a weight tile then run on the same XCD at about the same time.
+    // XCD-aware order.  Consecutive workgroup ids go to different XCDs (8 of them, each with its
+    // own L2), so give each XCD a contiguous range of logical ids.  The 32 workgroups an XCD runs
+    // at a time form a block of 4 token tiles x 8 row tiles that march through K together: each
+    // K slice of activations is shared by 8 of them and each slice of weights by 4, instead of
+    // 32 workgroups streaming 32 different activation tiles through one L2.
     const int total = gridDim.x;
-    const int per_xcd = (total + 7) / 8;
+    const int per_xcd = total / 8;
     const int logical = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
-    if (logical >= a.max_mtiles * a.n_ntiles) return;
-    const int mt = logical % a.max_mtiles;
-    const int ntile = logical / a.max_mtiles;
+    const int gm_count = (a.max_mtiles + TG_BLOCK_M - 1) / TG_BLOCK_M;
+    const int blk = logical / (TG_BLOCK_M * TG_BLOCK_N), r = logical % (TG_BLOCK_M * TG_BLOCK_N);
+    const int mt_raw = (blk % gm_count) * TG_BLOCK_M + r % TG_BLOCK_M;
+    const int ntile = (blk / gm_count) * TG_BLOCK_N + r / TG_BLOCK_M;
+    if (mt_raw >= a.max_mtiles || ntile >= a.n_ntiles) return;
 
+    // the down stage takes a gate/up token tile in two halves of at most TG_DOWN_TOK tokens
+    constexpr int HALVES = (STAGE == TSTAGE_DOWN) ? TG_MAX_TOK / TG_DOWN_TOK : 1;
+    const int half = mt_raw % HALVES;
+    const int mt = mt_raw / HALVES;
     int g, pos, slot0, n_tok;
     if (DENSE) {
         if (mt >= a.dense_tiles) return;
@@ -292,6 +328,11 @@ tile_kernel(TgArgs a)
         g = q >> 1; pos = q & 1;
         slot0 = a.tile_slot0[mt];
         n_tok = a.tile_n[mt];
+    }
+    if (STAGE == TSTAGE_DOWN) {
+        slot0 += half * TG_DOWN_TOK;
+        n_tok = min(n_tok - half * TG_DOWN_TOK, TG_DOWN_TOK);
+        if (n_tok <= 0) return;
     }
     // these are the same for the whole workgroup; say so, or the per-fragment guards below become
     // exec-masked branches and the accumulators get shuffled between register files
@@ -333,10 +374,11 @@ static int launch(const TileGemmArgs &t, hipStream_t st)
     a.dense_tiles = t.dense_tiles; a.dense_tile_tokens = t.dense_tile_tokens;
     a.h_out = t.h_out; a.h_plane_stride = t.h_plane_stride; a.h_slot_base = t.h_slot_base;
     a.o_out = t.o_out;
-    a.max_mtiles = t.max_mtiles;
-    const int rows_per_wg = (STAGE == TSTAGE_GATEUP) ? 128 : 256;
+    a.max_mtiles = t.max_mtiles * ((STAGE == TSTAGE_DOWN) ? TG_MAX_TOK / TG_DOWN_TOK : 1);
+    const int rows_per_wg = (STAGE == TSTAGE_GATEUP) ? TG_ROW_TILES * 8 : TG_ROW_TILES * 16;
     a.n_ntiles = (t.rows + rows_per_wg - 1) / rows_per_wg;
-    int64_t blocks = (int64_t)a.max_mtiles * a.n_ntiles;
+    int64_t blocks = (int64_t)((a.max_mtiles + TG_BLOCK_M - 1) / TG_BLOCK_M) *
+                     ((a.n_ntiles + TG_BLOCK_N - 1) / TG_BLOCK_N) * (TG_BLOCK_M * TG_BLOCK_N);
     blocks = (blocks + 7) / 8 * 8;
     if (blocks > 0x7FFFFFFFLL) return PZL_EINVAL;
     static bool attr_set = false;
