@@ -126,6 +126,7 @@ def main():
     ap.add_argument("--tokens", type=int, default=64, help="decode batch size (1, 8, 32 or 64)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sweep", action="store_true")
+    ap.add_argument("--no-prefill", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (--gpus must be 1)", file=sys.stderr)
@@ -191,6 +192,24 @@ def main():
             sweep[str(Ts)] = {"tokens_per_s": Ts / (ms * 1e-3), "ms_per_step": ms, "touched_pairs": nt,
                               "gateup_GBs": (nt * pair_bytes_gateup) / (msg * 1e-3) / 1e9}
         out["sweep"] = sweep
+
+    if not args.no_prefill:
+        # Same layer, prefill-sized batch (4096 tokens): the tiled decode-GEMM path on the matrix
+        # cores.  Useful flops only: 3 projections x 2*d*f per (token, choice); the second MFMA
+        # pass over the lo plane of H is not counted.
+        Tp = 4096
+        xs, ids_p, ws, xtp, idtp, wtp = batch(cfg, Tp)
+        ms_p, ms_gu, _, _ = time_steps(hip, layer, xtp, idtp, wtp, 10, 3, stage="gateup")
+        _, ms_dn, _, _ = time_steps(hip, layer, xtp, idtp, wtp, 10, 3, stage="down")
+        fl_proj = 2.0 * Tp * k * d * f
+        out["prefill"] = {
+            "workload": "mixtral_prefill_T4096", "tokens_per_s": Tp / (ms_p * 1e-3), "ms_per_step": ms_p,
+            "roofline": {"bound": "mfma", "kernel": "tile_kernel<gate/up + SwiGLU>",
+                         "achieved": 2 * fl_proj / (ms_gu * 1e-3) / 1e12, "peak": 2500.0, "unit": "TFLOP/s",
+                         "frac": 2 * fl_proj / (ms_gu * 1e-3) / 2.5e15, "traffic": None, "avg_launch_ms": ms_gu},
+            "down_kernel": {"avg_launch_ms": ms_dn, "useful_TFLOPs": fl_proj / (ms_dn * 1e-3) / 1e12,
+                            "executed_TFLOPs": 2 * fl_proj / (ms_dn * 1e-3) / 1e12},
+            "path_useful_mfma_frac": 3 * fl_proj / (ms_p * 1e-3) / 2.5e15}
 
     if want_cpu:
         import oracle

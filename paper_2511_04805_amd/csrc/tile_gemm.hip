@@ -8,20 +8,22 @@
 // multiply it with up to 256 tokens: the decode cost is amortised over the token tile, and
 // the decoded weights live only in LDS.
 //
-// Workgroup tile: gate/up stage up to 256 tokens x 128 weight rows (the same 64 feature rows of
-// the gate and of the up matrix, so SwiGLU runs on the accumulators); down stage up to 128
-// tokens x 128 rows of the down matrix with both planes (hi, lo) of H as the token operand.
-// 4 waves as 2 (tokens) x 2 (rows), each accumulating up to 8 token fragments x 4 row tiles of
-// v_mfma_f32_16x16x32_bf16.  K advances 32 at a time; the global loads of step k+1 are in flight
-// while step k is multiplied; LDS is double-buffered (24 KiB per stage), one barrier per step.
-// The tile is deliberately small enough (48 KiB of LDS, 256 registers per wave) for TWO
-// workgroups per compute unit: the store / barrier / first-read bubble of one workgroup is
-// filled by the other's MFMAs.  A single 512-thread workgroup with 256 x 256 tiles was measured
-// slower: its eight waves hit the same barrier, so nothing covered the bubble.
+// Workgroup tile (defaults): up to 256 tokens of one expert x 256 weight rows (gate/up stage: the
+// same 128 feature rows of the gate and of the up matrix, so SwiGLU runs on the accumulators;
+// down stage: 256 rows of the down matrix, with both planes (hi, lo) of H as the token operand).
+// 8 waves as 2 (tokens) x 4 (rows), two per SIMD; a wave accumulates up to 8 token fragments x
+// 4 row tiles of v_mfma_f32_16x16x32_bf16 (128 accumulator registers, which keeps the wave inside
+// the 256 registers it gets at two waves per SIMD).  K advances 64 (gate/up) or 32 (down) per
+// step; the global loads of step k+1 are in flight while step k is multiplied; LDS is
+// double-buffered, one barrier per step.
+//
+// Measured alternatives on the Mixtral-shaped prefill (T = 4096), all slower than the default:
+// 4 waves with 256 accumulators each (1 wave per SIMD), 4-wave 256x128 / 128x128 tiles with two
+// workgroups per compute unit, weights loaded two steps ahead, three LDS stages with fragment
+// read-ahead across the barrier.  The shape macros below are kept so they can be re-measured.
 //
 // Token tiles are cut per expert into equal parts of at most 256 tokens (rounded up to 16),
-// so a 1030-token expert costs 5 x 208 rows rather than 5 x 256; the down stage takes each
-// such tile in two halves.
+// so a 1030-token expert costs 5 x 208 rows rather than 5 x 256.
 #include "pzl_common.h"
 
 namespace pzl {
@@ -344,9 +346,6 @@ tile_kernel(TgArgs a)
     const uint16_t *wb = (STAGE == TSTAGE_GATEUP) ? a.w_b[g] : wa;
     const int cnt = (((n_tok + 15) >> 4) + 1) >> 1;          // 1..8 fragments per wave
 #define PZL_TILE(P, C) tile_body<STAGE, DENSE, P, C>(a, wa, wb, slot0, n_tok, ntile, lds, rowidx)
-#ifdef TG_ONLY_CNT8
-#define PZL_TILE_CNT(P) PZL_TILE(P, 8);
-#else
 #define PZL_TILE_CNT(P)                                                         \
     switch (cnt) {                                                              \
         case 1: PZL_TILE(P, 1); break; case 2: PZL_TILE(P, 2); break;           \
@@ -354,7 +353,6 @@ tile_kernel(TgArgs a)
         case 5: PZL_TILE(P, 5); break; case 6: PZL_TILE(P, 6); break;           \
         case 7: PZL_TILE(P, 7); break; default: PZL_TILE(P, 8); break;          \
     }
-#endif
     if (DENSE || pos == 0) { PZL_TILE_CNT(0) } else { PZL_TILE_CNT(1) }
 #undef PZL_TILE_CNT
 #undef PZL_TILE
