@@ -34,6 +34,7 @@ struct pzl_layer {
 namespace pzl {
 
 constexpr int TILED_MIN_TOKENS_PER_EXPERT = 96;   // average tokens per expert from which the tiled path pays
+constexpr int TILED_MIN_TOKENS_SHARED = 1024;     // a dense expert sees every token but has few row tiles: the tiled path needs >= 4 token tiles
 constexpr int MAX_KSPLIT = 8;   // upper bound on the k-splits of the down stage (sizes the workspace)
 
 struct WorkspaceLayout {
@@ -256,7 +257,7 @@ int pzl_moe_ffn_staged(const pzl_layer *L, const uint16_t *x, const int32_t *top
     // is bound by streaming the packed weights once (streaming kernels); with many it is a
     // dense contraction (tiled kernels on the matrix cores).
     const bool tiled = (int64_t)N >= (int64_t)TILED_MIN_TOKENS_PER_EXPERT * L->n_experts;
-    const bool tiled_shared = T >= TILED_MIN_TOKENS_PER_EXPERT;
+    const bool tiled_shared = T >= TILED_MIN_TOKENS_SHARED;
     const int pairs_max = (int)((int64_t)N < L->n_pairs ? N : L->n_pairs);   // pairs that can have tokens
     const int ksplit = tiled ? 1 : choose_ksplit(pairs_max > 0 ? pairs_max : 1, L->d_model);
     const int ksplit_shared = tiled_shared ? 1 : choose_ksplit(1, L->d_model);

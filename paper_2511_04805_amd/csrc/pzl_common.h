@@ -22,7 +22,7 @@ constexpr int TILE_ELEMS = TILE_ROWS * TILE_COLS;
 struct RouteTables {
     int32_t *cnt;        // [Q]    tokens routed to expert q
     int32_t *off;        // [Q+1]  first slot of expert q
-    int32_t *slot_tok;   // [N]    token index of each slot (slots sorted by q, then by flat index)
+    int32_t *slot_tok;   // [N]    token index of each slot (slots grouped by q; order inside a group is arbitrary)
     int32_t *slot_of;    // [N]    slot of flat index t*k+j, or -1 for an id outside [0,E)
     // token tiles of the tiled GEMM path: each expert's slots cut into equal parts of <= 256
     int32_t *tile_q;     // [max_tiles] expert q of the tile

@@ -10,9 +10,9 @@ constexpr int ROUTE_THREADS = 1024;
 constexpr int ROUTE_WAVES = ROUTE_THREADS / 64;
 constexpr int ROUTE_QMAX = 512;
 
-// Stable counting sort of the flat (token, choice) list by q = 2*pair + pos, one workgroup.
-// Wave w owns the contiguous index range [w*chunk, (w+1)*chunk); slots are ordered by
-// (q, wave, iteration, lane) = (q, flat index), so the result does not depend on timing.
+// Counting sort of the flat (token, choice) list by q = 2*pair + pos, one workgroup.
+// Wave w owns the contiguous index range [w*chunk, (w+1)*chunk) and its own histogram row, so
+// the only contended atomics are LDS atomics inside one wave.
 __global__ void __launch_bounds__(ROUTE_THREADS)
 route_kernel(const int32_t *__restrict__ ids, int32_t n_flat, int32_t k, int32_t n_experts,
              const int32_t *__restrict__ q_of_expert, int32_t Q, int32_t *__restrict__ cnt,
@@ -71,27 +71,21 @@ route_kernel(const int32_t *__restrict__ ids, int32_t n_flat, int32_t k, int32_t
     }
     __syncthreads();
 
+    // scatter: the rank inside (q, wave) comes from an LDS atomic.  Which lane gets which rank is
+    // up to the hardware, so the order of slots inside one expert is not fixed; nothing
+    // downstream depends on it (every slot is computed on its own and the combine adds a
+    // token's choices in choice order).
     for (int i = lo; i < hi; i += 64) {
         int idx = i + lane;
-        int q = -1;
         if (idx < hi) {
             int e = ids[idx];
-            if (e >= 0 && e < n_experts) q = q_of_expert[e]; else slot_of[idx] = -1;
-        }
-        unsigned long long remaining = __ballot(q >= 0);
-        while (remaining) {
-            int leader = __ffsll((long long)remaining) - 1;
-            int qq = __shfl(q, leader);
-            unsigned long long same = __ballot(q == qq);
-            int first = hist[wave][qq];
-            if (q == qq) {
-                int rank = __popcll(same & ((1ull << lane) - 1ull));
-                int slot = first + rank;
+            if (e >= 0 && e < n_experts) {
+                int slot = atomicAdd(&hist[wave][q_of_expert[e]], 1);
                 slot_tok[slot] = idx / k;
                 slot_of[idx] = slot;
+            } else {
+                slot_of[idx] = -1;
             }
-            if (lane == leader) hist[wave][qq] = first + __popcll(same);
-            remaining &= ~same;
         }
     }
 }
