@@ -94,6 +94,25 @@ int pzl_tile_dense(const uint16_t *dense_rowmajor, int64_t rows, int64_t cols,
                    uint16_t *tiled_out, void *stream);
 
 /*
+ * merge_pack — the offline dual-mask merge of two experts (Sec. 3.2, Eqs. 1-5) fused with pack:
+ * from the two experts' bf16 matrices straight to the packed pair, position 0 = expert i.
+ *   similarity mask   | |wi|-|wj| | / (|wi|+|wj|) <= tau_sim  (evaluated without the division, in
+ *                     fp32 with one rounding per operation; 0/0 is "not similar")
+ *   sign bits (Eq. 1) w < 0
+ *   saliency (Eqs. 2-3)  |wi| * norm_i[c] >= |wj| * norm_j[c] keeps expert i on dissimilar elements
+ *   masks (Eq. 4)     saliency OR similarity;   merged (Eq. 5) mean magnitude where similar (fp32
+ *                     mean rounded to bf16, nearest even), else the kept expert's magnitude
+ *   w_i, w_j    [rows, cols] row-major bf16 bit patterns
+ *   norm_i/j    [cols] fp32, the l2 norm of each input channel's calibration activations
+ *   tau_sim     in [0, 1] (the paper uses 0.4)
+ *   packed_out  pzl_packed_bytes(rows, cols) bytes, tiled order
+ *   n_similar, n_out_of_range  optional int32 counters on the device, ADDED to (zero them first)
+ */
+int pzl_merge_pack(const uint16_t *w_i, const uint16_t *w_j, const float *norm_i, const float *norm_j,
+                   int64_t rows, int64_t cols, float tau_sim, uint16_t *packed_out,
+                   int32_t *n_similar, int32_t *n_out_of_range, void *stream);
+
+/*
  * Description of one MoE layer.  Host struct; the small tables are copied at create time,
  * the weight tensors are referenced, not copied.
  */

@@ -42,6 +42,10 @@ def _load():
         lib.orc_unpack.restype = None
         lib.orc_unpack.argtypes = [u16p, ctypes.c_int, ctypes.c_int64, u16p]
         lib.orc_moe_ffn.restype = ctypes.c_int
+        f32p = ctypes.POINTER(ctypes.c_float)
+        lib.orc_merge.restype = ctypes.c_int64
+        lib.orc_merge.argtypes = [u16p, u16p, f32p, f32p, ctypes.c_int64, ctypes.c_int64, ctypes.c_float,
+                                  u16p, u8p, u8p, u8p, u8p]
         _lib = lib
     return _lib
 
@@ -91,6 +95,29 @@ def unpack(packed, expert_pos):
     _load().orc_unpack(_ptr(packed, ctypes.c_uint16), int(expert_pos), packed.size,
                        _ptr(out, ctypes.c_uint16))
     return out
+
+
+def merge(wi, wj, norm_i, norm_j, tau):
+    """Offline dual-mask merge of two expert matrices (Sec. 3.2, Eqs. 1-5).
+
+    wi, wj: [rows, cols] bf16 bits; norm_i, norm_j: [cols] float32 activation norms.
+    Returns dict(merged, mask0, mask1, sign0, sign1, n_similar); position 0 is expert i.
+    """
+    wi, wj = _u16(wi), _u16(wj)
+    assert wi.shape == wj.shape and wi.ndim == 2
+    rows, cols = wi.shape
+    ni = np.ascontiguousarray(norm_i, dtype=np.float32)
+    nj = np.ascontiguousarray(norm_j, dtype=np.float32)
+    assert ni.shape == (cols,) and nj.shape == (cols,)
+    merged = np.empty_like(wi)
+    planes = [np.empty(wi.shape, dtype=np.uint8) for _ in range(4)]
+    f32p = ctypes.POINTER(ctypes.c_float)
+    n_sim = _load().orc_merge(_ptr(wi, ctypes.c_uint16), _ptr(wj, ctypes.c_uint16),
+                              ni.ctypes.data_as(f32p), nj.ctypes.data_as(f32p), rows, cols,
+                              ctypes.c_float(tau), _ptr(merged, ctypes.c_uint16),
+                              *[_ptr(p, ctypes.c_uint8) for p in planes])
+    return {"merged": merged, "mask0": planes[0], "mask1": planes[1], "sign0": planes[2],
+            "sign1": planes[3], "n_similar": int(n_sim)}
 
 
 def moe_ffn(x, ids, w, expert_pair, expert_pos, gate, up, down,

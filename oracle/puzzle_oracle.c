@@ -35,6 +35,14 @@
  *
  * Arithmetic: integer for pack/unpack; fp64 everywhere in the FFN; a single
  * round-to-nearest-even to bf16 at the very end.
+ *
+ * orc_merge (the offline dual-mask merge, Sec. 3.2, Eqs. 1-5) decides two masks by
+ * floating-point comparisons.  Those decisions are taken in fp32, one rounding per
+ * operation and no fused multiply-add, which is the precision the GPU kernel uses:
+ * a mask bit is an integer result and both sides must take it the same way.
+ * Pinned by Lemma 3.1's closed form on Gaussian inputs, the structure Eq. 4 implies
+ * (never both masks clear), the reconstruction error bound, and special cases.
+ * Unpinned: 0/0 in the similarity measure is read as "not similar".
  */
 #include <math.h>
 #include <stdint.h>
@@ -222,4 +230,59 @@ int orc_moe_ffn(int T, int k, int E, int d, int f,
 done:
     free(xv); free(g); free(u); free(h); free(o); free(acc);
     return rc;
+}
+
+/* ---------- offline dual-mask merge of two experts: Sec. 3.2, Eqs. 1-5 ---------- */
+
+static float bf16_to_float(uint16_t b)
+{
+    uint32_t u = (uint32_t)b << 16;
+    float f;
+    memcpy(&f, &u, sizeof f);
+    return f;
+}
+
+/*
+ * wi, wj: [rows, cols] bf16 bit patterns of the two experts' matrices (row-major, the
+ * contracted/input dimension along cols).  norm_i, norm_j: [cols] the l2 norm of each input
+ * channel's calibration activations (Eq. 2 multiplies |W| by it, channel-wise).
+ * Outputs, all [rows, cols]: merged (bf16 bits, >= 0), mask_i, mask_j, sign_i, sign_j (0/1).
+ *
+ *   similarity (unnumbered display before Eq. 1):  | |wi|-|wj| | / (|wi|+|wj|) <= tau,
+ *       evaluated division-free as  | |wi|-|wj| |  <=  tau * (|wi|+|wj|)  in fp32;
+ *       both magnitudes zero (0/0) counts as not similar;
+ *   signs (Eq. 1): w < 0;  saliency (Eqs. 2, 3): |wi|*norm_i >= |wj|*norm_j picks i, ties to i;
+ *   masks (Eq. 4): saliency mask OR similarity mask;
+ *   merged (Eq. 5): mean magnitude where similar, else the salient expert's magnitude;
+ *       the mean is formed in fp32 and rounded to bf16 to nearest even.
+ * Returns the number of similar elements.
+ */
+int64_t orc_merge(const uint16_t *wi, const uint16_t *wj, const float *norm_i, const float *norm_j,
+                  int64_t rows, int64_t cols, float tau,
+                  uint16_t *merged, uint8_t *mask_i, uint8_t *mask_j, uint8_t *sign_i, uint8_t *sign_j)
+{
+    int64_t n_sim = 0;
+    for (int64_t r = 0; r < rows; ++r) {
+        for (int64_t c = 0; c < cols; ++c) {
+            int64_t k = r * cols + c;
+            float a = fabsf(bf16_to_float(wi[k])), b = fabsf(bf16_to_float(wj[k]));
+            volatile float diff = fabsf(a - b);            /* volatile: one rounding per operation, */
+            volatile float sum = a + b;                    /* never contracted into an fma          */
+            volatile float thr = tau * sum;
+            int sim = (sum > 0.0f) && (diff <= thr);
+            volatile float sal_i = a * norm_i[c];
+            volatile float sal_j = b * norm_j[c];
+            int pick_i = sal_i >= sal_j;
+            float mag;
+            if (sim) { volatile float half = sum * 0.5f; mag = half; }
+            else     mag = pick_i ? a : b;
+            merged[k] = orc_bf16_from_double((double)mag);
+            mask_i[k] = (uint8_t)(sim || pick_i);
+            mask_j[k] = (uint8_t)(sim || !pick_i);
+            sign_i[k] = (uint8_t)((wi[k] & 0x8000) && (wi[k] & 0x7FFF));   /* w < 0: -0 is not negative */
+            sign_j[k] = (uint8_t)((wj[k] & 0x8000) && (wj[k] & 0x7FFF));
+            n_sim += sim;
+        }
+    }
+    return n_sim;
 }

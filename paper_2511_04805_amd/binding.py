@@ -17,7 +17,7 @@ _lib = None
 PZL_OK, PZL_EINVAL, PZL_ENOSPC, PZL_EHIP, PZL_ENOMEM = 0, -1, -2, -3, -4
 
 EXPORTS = ("pzl_abi_version", "pzl_strerror", "pzl_last_hip_error", "pzl_packed_bytes", "pzl_pack",
-           "pzl_unpack", "pzl_tile_dense", "pzl_layer_create", "pzl_layer_destroy",
+           "pzl_unpack", "pzl_tile_dense", "pzl_merge_pack", "pzl_layer_create", "pzl_layer_destroy",
            "pzl_moe_ffn_workspace_bytes", "pzl_moe_ffn", "pzl_moe_ffn_staged")
 
 STAGES = ("route", "gateup", "down", "shared", "combine")
@@ -63,6 +63,8 @@ def load():
         lib.pzl_unpack.argtypes = [vp, ctypes.c_int, i64, i64, vp, vp]
         lib.pzl_tile_dense.restype = ctypes.c_int
         lib.pzl_tile_dense.argtypes = [vp, i64, i64, vp, vp]
+        lib.pzl_merge_pack.restype = ctypes.c_int
+        lib.pzl_merge_pack.argtypes = [vp, vp, vp, vp, i64, i64, ctypes.c_float, vp, vp, vp, vp]
         lib.pzl_layer_create.restype = ctypes.c_int
         lib.pzl_layer_create.argtypes = [ctypes.POINTER(_LayerDesc), ctypes.POINTER(vp)]
         lib.pzl_layer_destroy.restype = None
@@ -134,6 +136,22 @@ def pzl_tile_dense(dense, out=None):
         out = torch.empty(rows * cols, dtype=dense.dtype, device=dense.device)
     rc = load().pzl_tile_dense(_dev(dense, _BITS16, "dense"), rows, cols, _dev(out, _BITS16, "out"), _stream())
     _check(rc, "pzl_tile_dense")
+    return out
+
+
+def pzl_merge_pack(w_i, w_j, norm_i, norm_j, tau_sim, out=None, n_similar=None, n_out_of_range=None):
+    """Offline dual-mask merge of two expert matrices fused with pack -> packed pair (tiled order)."""
+    rows, cols = w_i.shape
+    if tuple(w_j.shape) != (rows, cols) or norm_i.numel() != cols or norm_j.numel() != cols:
+        raise ValueError("w_i, w_j must share a shape and the norms must have one entry per column")
+    if out is None:
+        out = torch.empty(rows * cols, dtype=torch.int16, device=w_i.device)
+    opt = lambda t, name: ctypes.c_void_p(0) if t is None else _dev(t, (torch.int32,), name)
+    rc = load().pzl_merge_pack(_dev(w_i, _BITS16, "w_i"), _dev(w_j, _BITS16, "w_j"),
+                               _dev(norm_i, (torch.float32,), "norm_i"), _dev(norm_j, (torch.float32,), "norm_j"),
+                               rows, cols, ctypes.c_float(tau_sim), _dev(out, _BITS16, "out"),
+                               opt(n_similar, "n_similar"), opt(n_out_of_range, "n_out_of_range"), _stream())
+    _check(rc, "pzl_merge_pack")
     return out
 
 

@@ -130,6 +130,14 @@ int pzl_tile_dense(const uint16_t *dense_rowmajor, int64_t rows, int64_t cols, u
     return launch_tile_dense(dense_rowmajor, rows, cols, tiled_out, (hipStream_t)stream);
 }
 
+int pzl_merge_pack(const uint16_t *w_i, const uint16_t *w_j, const float *norm_i, const float *norm_j,
+                   int64_t rows, int64_t cols, float tau_sim, uint16_t *packed_out, int32_t *n_similar,
+                   int32_t *n_out_of_range, void *stream)
+{
+    return launch_merge_pack(w_i, w_j, norm_i, norm_j, rows, cols, tau_sim, packed_out, n_similar,
+                             n_out_of_range, (hipStream_t)stream);
+}
+
 int pzl_layer_create(const pzl_layer_desc *desc, pzl_layer **out)
 {
     if (!desc || !out) return PZL_EINVAL;

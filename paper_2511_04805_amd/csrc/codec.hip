@@ -14,6 +14,17 @@ __device__ __forceinline__ void chunk_coords(int64_t chunk, int64_t col_tiles, i
     col = kb * TILE_COLS + (lane >> 4) * 8;
 }
 
+// Sec. 3.3.2 word for one element: exponent raised to >= 112 and shifted by -112, flags on top.
+__device__ __forceinline__ uint32_t pack_word(uint32_t mag, uint32_t m0, uint32_t m1, uint32_t s0, uint32_t s1, int &bad)
+{
+    uint32_t exponent = mag >> 7, mantissa = mag & 0x7Fu;
+    uint32_t flags = (s0 ? 0x8000u : 0u) | (s1 ? 0x4000u : 0u);
+    if (exponent > 143u) { ++bad; return flags; }      // does not fit five bits: fully masked, counted
+    if (mag == 0u) return flags;                        // exact zero: fully masked so that Eq. 6 gives 0
+    if (exponent < 112u) exponent = 112u;               // raised, mantissa kept
+    return flags | (m0 ? 0x2000u : 0u) | (m1 ? 0x1000u : 0u) | ((exponent - 112u) << 7) | mantissa;
+}
+
 __global__ void __launch_bounds__(256)
 pack_kernel(const uint16_t *__restrict__ merged, const uint8_t *__restrict__ m0,
             const uint8_t *__restrict__ m1, const uint8_t *__restrict__ s0,
@@ -36,22 +47,67 @@ pack_kernel(const uint16_t *__restrict__ merged, const uint8_t *__restrict__ m0,
         uint32_t mag = (w[i >> 1] >> ((i & 1) * 16)) & 0x7FFFu;     // input sign ignored
         uint32_t fm0 = (vm0[i >> 2] >> ((i & 3) * 8)) & 0xFFu, fm1 = (vm1[i >> 2] >> ((i & 3) * 8)) & 0xFFu;
         uint32_t fs0 = (vs0[i >> 2] >> ((i & 3) * 8)) & 0xFFu, fs1 = (vs1[i >> 2] >> ((i & 3) * 8)) & 0xFFu;
-        uint32_t exponent = mag >> 7, mantissa = mag & 0x7Fu;
-        uint32_t flags = (fs0 ? 0x8000u : 0u) | (fs1 ? 0x4000u : 0u);
-        uint32_t word;
-        if (exponent > 143u) {            // does not fit five bits: fully masked, counted
-            ++bad;
-            word = flags;
-        } else if (mag == 0u) {           // exact zero: fully masked so that Eq. 6 gives 0
-            word = flags;
-        } else {
-            if (exponent < 112u) exponent = 112u;                   // raised, mantissa kept
-            word = flags | (fm0 ? 0x2000u : 0u) | (fm1 ? 0x1000u : 0u) | ((exponent - 112u) << 7) | mantissa;
-        }
+        uint32_t word = pack_word(mag, fm0, fm1, fs0, fs1, bad);
         if (i & 1) res[i >> 1] |= word << 16; else res[i >> 1] = word;
     }
     u32x4 o = {res[0], res[1], res[2], res[3]};
     *(u32x4 *)(out + chunk * 8) = o;
+    if (bad && n_bad) atomicAdd(n_bad, bad);
+}
+
+__device__ __forceinline__ uint32_t f32_to_bf16_rne_codec(float v)
+{
+    uint32_t u = __float_as_uint(v);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+
+// Offline dual-mask merge of two experts (Sec. 3.2, Eqs. 1-5) fused with pack: reads the two bf16
+// matrices and the per-input-channel activation norms, writes the packed pair (tiled order).
+// Mask decisions are fp32 comparisons, one rounding per operation:
+//   similar:  | |wi|-|wj| | <= tau * (|wi|+|wj|), and not both zero   (the paper's ratio test,
+//             written without the division);
+//   salient:  |wi| * norm_i[c] >= |wj| * norm_j[c] keeps expert i (ties to i, Eq. 3).
+__global__ void __launch_bounds__(256)
+merge_pack_kernel(const uint16_t *__restrict__ wi, const uint16_t *__restrict__ wj,
+                  const float *__restrict__ norm_i, const float *__restrict__ norm_j, int64_t rows,
+                  int64_t cols, float tau, uint16_t *__restrict__ out, int32_t *__restrict__ n_similar,
+                  int32_t *__restrict__ n_bad)
+{
+    int64_t n_chunks = rows * cols / 8;
+    int64_t chunk = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (chunk >= n_chunks) return;
+    int64_t row, col;
+    chunk_coords(chunk, cols / TILE_COLS, row, col);
+    int64_t src = row * cols + col;
+    u32x4 vi = *(const u32x4 *)(wi + src), vj = *(const u32x4 *)(wj + src);
+    f32x4 ni0 = *(const f32x4 *)(norm_i + col), ni1 = *(const f32x4 *)(norm_i + col + 4);
+    f32x4 nj0 = *(const f32x4 *)(norm_j + col), nj1 = *(const f32x4 *)(norm_j + col + 4);
+    uint32_t res[4];
+    int bad = 0, sim_count = 0;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        uint32_t bi = (vi[i >> 1] >> ((i & 1) * 16)) & 0xFFFFu, bj = (vj[i >> 1] >> ((i & 1) * 16)) & 0xFFFFu;
+        float a = __uint_as_float((bi & 0x7FFFu) << 16), b = __uint_as_float((bj & 0x7FFFu) << 16);
+        float cn_i = (i < 4) ? ni0[i & 3] : ni1[i & 3], cn_j = (i < 4) ? nj0[i & 3] : nj1[i & 3];
+        float diff = fabsf(__fsub_rn(a, b));
+        float sum = __fadd_rn(a, b);
+        float thr = __fmul_rn(tau, sum);
+        bool sim = (sum > 0.0f) && (diff <= thr);
+        bool pick_i = __fmul_rn(a, cn_i) >= __fmul_rn(b, cn_j);
+        float mag = sim ? __fmul_rn(sum, 0.5f) : (pick_i ? a : b);
+        uint32_t s_i = (bi & 0x8000u) && (bi & 0x7FFFu), s_j = (bj & 0x8000u) && (bj & 0x7FFFu);
+        uint32_t word = pack_word(f32_to_bf16_rne_codec(mag), sim || pick_i, sim || !pick_i, s_i, s_j, bad);
+        sim_count += sim;
+        if (i & 1) res[i >> 1] |= word << 16; else res[i >> 1] = word;
+    }
+    u32x4 o = {res[0], res[1], res[2], res[3]};
+    *(u32x4 *)(out + chunk * 8) = o;
+    if (n_similar) {
+        // one atomic per wavefront
+        for (int off = 32; off > 0; off >>= 1) sim_count += __shfl_down(sim_count, off);
+        if ((threadIdx.x & 63) == 0 && sim_count) atomicAdd(n_similar, sim_count);
+    }
     if (bad && n_bad) atomicAdd(n_bad, bad);
 }
 
@@ -132,6 +188,19 @@ int launch_tile_dense(const uint16_t *in, int64_t rows, int64_t cols, uint16_t *
     int64_t n_chunks = rows * cols / 8;
     unsigned blocks = (unsigned)((n_chunks + 255) / 256);
     hipLaunchKernelGGL(tile_dense_kernel, dim3(blocks), dim3(256), 0, st, in, rows, cols, out);
+    return finish_launch();
+}
+
+int launch_merge_pack(const uint16_t *wi, const uint16_t *wj, const float *norm_i, const float *norm_j,
+                      int64_t rows, int64_t cols, float tau, uint16_t *out, int32_t *n_similar,
+                      int32_t *n_bad, hipStream_t st)
+{
+    if (!wi || !wj || !norm_i || !norm_j || !out || !shape_ok(rows, cols) || !(tau >= 0.0f && tau <= 1.0f))
+        return PZL_EINVAL;
+    int64_t n_chunks = rows * cols / 8;
+    unsigned blocks = (unsigned)((n_chunks + 255) / 256);
+    hipLaunchKernelGGL(merge_pack_kernel, dim3(blocks), dim3(256), 0, st, wi, wj, norm_i, norm_j, rows, cols,
+                       tau, out, n_similar, n_bad);
     return finish_launch();
 }
 

@@ -42,6 +42,9 @@ int launch_pack(const uint16_t *merged, const uint8_t *m0, const uint8_t *m1, co
 int launch_unpack(const uint16_t *packed, int pos, int64_t rows, int64_t cols, uint16_t *out,
                   hipStream_t st);
 int launch_tile_dense(const uint16_t *in, int64_t rows, int64_t cols, uint16_t *out, hipStream_t st);
+int launch_merge_pack(const uint16_t *wi, const uint16_t *wj, const float *norm_i, const float *norm_j,
+                      int64_t rows, int64_t cols, float tau, uint16_t *out, int32_t *n_similar,
+                      int32_t *n_bad, hipStream_t st);
 
 // route.hip
 int launch_route(const int32_t *ids, int32_t n_flat, int32_t k, int32_t n_experts, const int32_t *q_of_expert,

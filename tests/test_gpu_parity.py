@@ -163,3 +163,34 @@ def test_error_codes(small_case, binding):
                       [case.packed_gpu[p, synth.UP] for p in range(3)],
                       [case.packed_gpu[p, synth.DOWN] for p in range(3)])
     assert lib.pzl_moe_ffn_workspace_bytes(case.layer._h, -1, 2) == 0
+
+
+@pytest.mark.parametrize("shape,tau", [((64, 96), 0.4), ((256, 512), 0.4), ((1408, 2048), 0.25)])
+def test_merge_pack_bit_exact(oracle, binding, shape, tau):
+    """Offline dual-mask merge fused with pack (Eqs. 1-5 -> packed word) against oracle merge + pack."""
+    say("merge_pack shape=%s tau=%s" % (shape, tau))
+    rows, cols = shape
+    g = torch.Generator().manual_seed(rows + cols)
+    to_bits = lambda t: t.to(torch.bfloat16).view(torch.int16)
+    wi = to_bits(torch.randn(rows, cols, generator=g) * 0.02)
+    wj = to_bits(torch.randn(rows, cols, generator=g) * 0.02)
+    # corner cases: both zero, equal magnitudes with opposite sign, one zero, -0
+    wi.view(-1)[:6] = torch.tensor([0, 0x3CA4, 0x3CA4, 0, -32768, 0x0001], dtype=torch.int16)
+    wj.view(-1)[:6] = torch.tensor([0, -17244, 0x3CA5, 0x3CA4, 0x3CA4, 0x0001], dtype=torch.int16)   # -17244 = 0xBCA4
+    ni = (torch.rand(cols, generator=g) + 0.5).float()
+    nj = (torch.rand(cols, generator=g) + 0.5).float()
+    ref = oracle.merge(wi.numpy().view(np.uint16), wj.numpy().view(np.uint16), ni.numpy(), nj.numpy(), tau)
+    want, bad = oracle.pack(ref["merged"], ref["mask0"], ref["mask1"], ref["sign0"], ref["sign1"])
+    n_sim = torch.zeros(1, dtype=torch.int32, device="cuda")
+    n_bad = torch.zeros(1, dtype=torch.int32, device="cuda")
+    packed = binding.pzl_merge_pack(wi.cuda(), wj.cuda(), ni.cuda(), nj.cuda(), tau, n_similar=n_sim,
+                                    n_out_of_range=n_bad)
+    torch.cuda.synchronize()
+    got = binding.tiled_to_logical(packed.cpu().numpy().view(np.uint16), rows, cols)
+    assert np.array_equal(got, want)
+    assert int(n_sim.item()) == ref["n_similar"] and int(n_bad.item()) == bad == 0
+    # and the packed pair decodes to each expert's reconstruction (Eq. 6)
+    for pos in (0, 1):
+        out = binding.pzl_unpack(packed, pos, rows, cols)
+        torch.cuda.synchronize()
+        assert np.array_equal(out.view(torch.int16).cpu().numpy().view(np.uint16), oracle.unpack(want, pos))
