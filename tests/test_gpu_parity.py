@@ -194,3 +194,31 @@ def test_merge_pack_bit_exact(oracle, binding, shape, tau):
         out = binding.pzl_unpack(packed, pos, rows, cols)
         torch.cuda.synchronize()
         assert np.array_equal(out.view(torch.int16).cpu().numpy().view(np.uint16), oracle.unpack(want, pos))
+
+
+# A layer whose sizes allow the tiled (MFMA) path: d and f multiples of 64.
+TILED = synth.LayerConfig("tiled", 4, 256, 384, 2, (600,), shared_d_ffn=(128,), seed=41)
+
+
+@pytest.fixture(scope="module")
+def tiled_case(oracle, binding):
+    return Case(TILED, oracle, binding, emap_mode="random")
+
+
+@pytest.mark.parametrize("T", [192, 200, 333, 600, 1100])
+def test_tiled_path_token_counts(tiled_case, T):
+    """>= 96 slots per expert: tiled kernels; ragged token tiles, several tiles per expert, and from
+    1024 tokens the dense shared expert on the tiled kernels too."""
+    check(tiled_case, T, "tiled")
+
+
+def test_tiled_path_skewed_routing(tiled_case):
+    """One hot expert (several full token tiles), one expert with a single token, one with none."""
+    cfg = TILED
+    T = 700
+    x = synth.tokens(cfg, T)
+    ids, w = synth.routing(cfg, T)
+    ids[:, 0] = 2
+    ids[:, 1] = 0
+    ids[5, 1] = 1                    # expert 1: one token; expert 3: none
+    check(tiled_case, T, "tiled-skewed", ids=ids.astype(np.int32), w=w, x=x)
