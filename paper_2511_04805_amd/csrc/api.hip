@@ -71,6 +71,19 @@ static WorkspaceLayout carve(const pzl_layer *L, int32_t T, int32_t k)
     return w;
 }
 
+// Tiled down stage: workgroups = token tiles x rows/256; split K until the launch has about three
+// rounds of workgroups (256 CUs, one workgroup each), keeping at least 8 K steps per workgroup.
+static int choose_tile_ksplit(int64_t token_tiles, int rows, int kdim)
+{
+    int64_t wgs = token_tiles * ((rows + 255) / 256);
+    int ks = (int)((768 + wgs - 1) / (wgs > 0 ? wgs : 1));
+    int cap = kdim / TILE_COLS / 8;
+    if (ks > cap) ks = cap;
+    if (ks > MAX_KSPLIT) ks = MAX_KSPLIT;
+    if (ks < 1) ks = 1;
+    return ks;
+}
+
 static int choose_ksplit(int groups_touched_max, int rows)
 {
     // The down projection has only rows/128 workgroups per pair; split its long K so that the
@@ -267,8 +280,16 @@ int pzl_moe_ffn_staged(const pzl_layer *L, const uint16_t *x, const int32_t *top
     const bool tiled = (int64_t)N >= (int64_t)TILED_MIN_TOKENS_PER_EXPERT * L->n_experts;
     const bool tiled_shared = T >= TILED_MIN_TOKENS_SHARED;
     const int pairs_max = (int)((int64_t)N < L->n_pairs ? N : L->n_pairs);   // pairs that can have tokens
-    const int ksplit = tiled ? 1 : choose_ksplit(pairs_max > 0 ? pairs_max : 1, L->d_model);
-    const int ksplit_shared = tiled_shared ? 1 : choose_ksplit(1, L->d_model);
+    const int ksplit = tiled ? choose_tile_ksplit(N / TILE_MAX_TOKENS + L->n_experts / 2, L->d_model, L->d_ffn)
+                             : choose_ksplit(pairs_max > 0 ? pairs_max : 1, L->d_model);
+    int ksplit_shared = choose_ksplit(1, L->d_model);
+    if (tiled_shared) {
+        ksplit_shared = MAX_KSPLIT;
+        for (int s = 0; s < L->n_shared; ++s) {
+            int ks = choose_tile_ksplit((T + TILE_MAX_TOKENS - 1) / TILE_MAX_TOKENS, L->d_model, L->shared_f[s]);
+            if (ks < ksplit_shared) ksplit_shared = ks;
+        }
+    }
     const int64_t h_plane = (int64_t)N * L->d_ffn;
     if (N > 0 && tiled) {
         TileGemmArgs a = {};
@@ -286,7 +307,7 @@ int pzl_moe_ffn_staged(const pzl_layer *L, const uint16_t *x, const int32_t *top
         a.w_a = L->d_down; a.w_b = nullptr;
         a.rows = L->d_model; a.kdim = L->d_ffn;
         a.act = h_routed; a.act_is_x = 0; a.act_slot_base = 0; a.act_plane_stride = h_plane;
-        a.h_out = nullptr; a.o_out = opart;
+        a.h_out = nullptr; a.o_out = opart; a.o_ks_stride = w.o_ks_stride; a.ksplit = ksplit;
         if ((rc = mark(PZL_STAGE_DOWN, 0))) return rc;
         rc = launch_tile_down(a, false, st);
         if (rc) return rc;
@@ -338,7 +359,7 @@ int pzl_moe_ffn_staged(const pzl_layer *L, const uint16_t *x, const int32_t *top
             a.w_a = L->d_sdown + s; a.w_b = nullptr;
             a.rows = L->d_model; a.kdim = L->shared_f[s];
             a.act = h_s; a.act_is_x = 0; a.act_slot_base = slot_base; a.act_plane_stride = hs_plane;
-            a.h_out = nullptr; a.o_out = opart;
+            a.h_out = nullptr; a.o_out = opart; a.o_ks_stride = w.o_ks_stride; a.ksplit = ksplit_shared;
             rc = launch_tile_down(a, true, st);
             if (rc) return rc;
             continue;

@@ -96,7 +96,9 @@ struct TileGemmArgs {
     uint16_t *h_out;
     int64_t h_plane_stride;
     int32_t h_slot_base;
-    float *o_out;                 // down stage: [slots][rows] fp32
+    float *o_out;                 // down stage: [ksplit][slots][rows] fp32
+    int64_t o_ks_stride;
+    int32_t ksplit;               // down stage only: workgroups sharing one output tile along K
     int32_t max_mtiles;           // upper bound on token tiles (grid size)
 };
 int launch_tile_gateup(const TileGemmArgs &a, bool dense, hipStream_t st);

@@ -73,7 +73,8 @@ struct TgArgs {
     int64_t h_plane_stride;
     int32_t h_slot_base;
     float *o_out;
-    int32_t max_mtiles, n_ntiles;
+    int64_t o_ks_stride;
+    int32_t max_mtiles, n_ntiles, ksplit;
 };
 
 __device__ __forceinline__ uint32_t tg_decode_body(uint32_t x) { return (x & 0x0FFF0FFFu) + 0x38003800u; }
@@ -120,7 +121,7 @@ __device__ __forceinline__ void tg_swiglu_split(float g, float u, uint32_t &hi, 
 // accumulators between register files); an odd tile costs one padded fragment.
 template <int STAGE, bool DENSE, int POS, int CNT>
 __device__ __forceinline__ void tile_body(const TgArgs &a, const uint16_t *wa, const uint16_t *wb,
-                                          int slot0, int n_tok, int ntile, u32x4 *lds, int32_t *rowidx)
+                                          int slot0, int n_tok, int ntile, int ks, u32x4 *lds, int32_t *rowidx)
 {
     constexpr int KBS = (STAGE == TSTAGE_DOWN) ? 1 : TG_KBS_GATEUP;   // k-blocks (of 32) per K step
     constexpr int FR = (STAGE == TSTAGE_DOWN) ? TG_DOWN_TOK / 16 : TG_MAX_TOK / 16;   // token fragment slots
@@ -136,7 +137,10 @@ __device__ __forceinline__ void tile_body(const TgArgs &a, const uint16_t *wa, c
     const int wm = __builtin_amdgcn_readfirstlane(wave & 1);  // wave position along tokens
     const int wn = __builtin_amdgcn_readfirstlane(wave >> 1); // wave position along rows
     const int kb_total = a.kdim / TILE_COLS;
-    const int n_steps = (kb_total + KBS - 1) / KBS;
+    // this workgroup's share of K (the down stage may be split over several workgroups)
+    const int kb0 = (int)((int64_t)ks * kb_total / a.ksplit);
+    const int kb1 = (int)((int64_t)(ks + 1) * kb_total / a.ksplit);
+    const int n_steps = (kb1 - kb0 + KBS - 1) / KBS;
     const int frag0 = wm * CNT;                              // fragments frag0 .. frag0+CNT-1 (< 16)
     const int row_tiles = a.rows / TILE_ROWS;
 
@@ -192,13 +196,13 @@ __device__ __forceinline__ void tile_body(const TgArgs &a, const uint16_t *wa, c
 #pragma unroll
         for (int i = 0; i < WPT; ++i) {
             int kbo = (wave * WPT + i) % KBS;
-            int kb = min(step * KBS + kbo, kb_total - 1) - kbo;
+            int kb = min(kb0 + step * KBS + kbo, kb1 - 1) - kbo;
             wreg[i] = __builtin_nontemporal_load((gvec_ptr)wbase[i] + (int64_t)kb * 64 + lane);
         }
 #pragma unroll
         for (int i = 0; i < XPT; ++i) {
             int kbo = (wave * XPT + i) % KBS;
-            int kb = min(step * KBS + kbo, kb_total - 1) - kbo;
+            int kb = min(kb0 + step * KBS + kbo, kb1 - 1) - kbo;
             xreg[i] = *(const u32x4 *)(a.act + (xoff[i] + (uint32_t)(kb * TILE_COLS)));
         }
     };
@@ -211,7 +215,7 @@ __device__ __forceinline__ void tile_body(const TgArgs &a, const uint16_t *wa, c
 #pragma unroll
         for (int i = 0; i < XPT; ++i) {
             int c = wave * XPT + i;
-            bool valid = step * KBS + c % KBS < kb_total;
+            bool valid = kb0 + step * KBS + c % KBS < kb1;
             xs[c * 64 + lane] = valid ? xreg[i] : zero4;
         }
     };
@@ -284,7 +288,7 @@ __device__ __forceinline__ void tile_body(const TgArgs &a, const uint16_t *wa, c
             for (int j = 0; j < RT; ++j) {
                 int grt = ntile * TG_ROW_TILES + wn * RT + j;
                 if (grt >= row_tiles) continue;
-                *(f32x4 *)(a.o_out + (int64_t)slot * a.rows + grt * 16 + rsub) = acc[j][i];
+                *(f32x4 *)(a.o_out + (int64_t)ks * a.o_ks_stride + (int64_t)slot * a.rows + grt * 16 + rsub) = acc[j][i];
             }
         }
     }
@@ -305,7 +309,10 @@ tile_kernel(TgArgs a)
     // 32 workgroups streaming 32 different activation tiles through one L2.
     const int total = gridDim.x;
     const int per_xcd = total / 8;
-    const int logical = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+    int logical = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+    const int per_ks = total / a.ksplit;                     // K splits are the slowest index
+    const int ks = logical / per_ks;
+    logical -= ks * per_ks;
     const int gm_count = (a.max_mtiles + TG_BLOCK_M - 1) / TG_BLOCK_M;
     const int blk = logical / (TG_BLOCK_M * TG_BLOCK_N), r = logical % (TG_BLOCK_M * TG_BLOCK_N);
     const int mt_raw = (blk % gm_count) * TG_BLOCK_M + r % TG_BLOCK_M;
@@ -345,7 +352,7 @@ tile_kernel(TgArgs a)
     const uint16_t *wa = a.w_a[g];
     const uint16_t *wb = (STAGE == TSTAGE_GATEUP) ? a.w_b[g] : wa;
     const int cnt = (((n_tok + 15) >> 4) + 1) >> 1;          // 1..8 fragments per wave
-#define PZL_TILE(P, C) tile_body<STAGE, DENSE, P, C>(a, wa, wb, slot0, n_tok, ntile, lds, rowidx)
+#define PZL_TILE(P, C) tile_body<STAGE, DENSE, P, C>(a, wa, wb, slot0, n_tok, ntile, ks, lds, rowidx)
 #define PZL_TILE_CNT(P)                                                         \
     switch (cnt) {                                                              \
         case 1: PZL_TILE(P, 1); break; case 2: PZL_TILE(P, 2); break;           \
@@ -371,13 +378,14 @@ static int launch(const TileGemmArgs &t, hipStream_t st)
     a.dense_tokens = t.dense_tokens; a.dense_slot_base = t.dense_slot_base;
     a.dense_tiles = t.dense_tiles; a.dense_tile_tokens = t.dense_tile_tokens;
     a.h_out = t.h_out; a.h_plane_stride = t.h_plane_stride; a.h_slot_base = t.h_slot_base;
-    a.o_out = t.o_out;
+    a.o_out = t.o_out; a.o_ks_stride = t.o_ks_stride;
+    a.ksplit = (STAGE == TSTAGE_DOWN && t.ksplit > 1) ? t.ksplit : 1;
     a.max_mtiles = t.max_mtiles * ((STAGE == TSTAGE_DOWN) ? TG_MAX_TOK / TG_DOWN_TOK : 1);
     const int rows_per_wg = (STAGE == TSTAGE_GATEUP) ? TG_ROW_TILES * 8 : TG_ROW_TILES * 16;
     a.n_ntiles = (t.rows + rows_per_wg - 1) / rows_per_wg;
     int64_t blocks = (int64_t)((a.max_mtiles + TG_BLOCK_M - 1) / TG_BLOCK_M) *
                      ((a.n_ntiles + TG_BLOCK_N - 1) / TG_BLOCK_N) * (TG_BLOCK_M * TG_BLOCK_N);
-    blocks = (blocks + 7) / 8 * 8;
+    blocks = (blocks + 7) / 8 * 8 * a.ksplit;
     if (blocks > 0x7FFFFFFFLL) return PZL_EINVAL;
     static bool attr_set = false;
     if (!attr_set) {
