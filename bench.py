@@ -22,6 +22,10 @@ sys.path.insert(0, ROOT)
 from paper_2511_04805_amd import binding, synth  # noqa: E402
 
 HBM_PEAK_GBS = 8000.0
+# HBM bytes per launch of the gate/up streaming kernel at T = 64, from the two rocprofv3 --pmc runs
+# (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, calibrated on the copy below) summarised in
+# profiles/stream_kernels_mixtral_decode_T64.md.  Counters cannot be read inside this process.
+MEASURED_TRAFFIC_BYTES = {"mixtral_decode_T64": 956.2e6}
 W3 = (synth.GATE, synth.UP, synth.DOWN)
 
 
@@ -173,7 +177,8 @@ def main():
                    "d_model": d, "d_ffn": f, "top_k": k, "tokens": T, "touched_pairs": n_touched},
         "roofline": {"bound": "hbm", "kernel": "stream_kernel<gate/up + SwiGLU>", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": None, "algorithmic_bytes": alg_bytes, "avg_launch_ms": ms_gateup},
+                     "traffic": MEASURED_TRAFFIC_BYTES.get("mixtral_decode_T%d" % T),
+                     "algorithmic_bytes": alg_bytes, "avg_launch_ms": ms_gateup},
         "ms_per_step_host_wall": ms_wall,
     }
     path_bytes = n_touched * 3 * f * d * 2
