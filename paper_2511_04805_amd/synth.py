@@ -109,6 +109,23 @@ def shared_matrix(cfg, s, which):
     return _np_bits(shared_matrix_t(cfg, s, which))
 
 
+def unmerged_pair_t(cfg, pair, which, shape=None, device="cpu"):
+    """Inputs of the offline merge for one matrix of one expert pair: two dense experts drawn as
+    signed N(0, sigma) bf16 (int16 views) and one positive activation-norm vector per expert
+    (uniform in [0.5, 1.5]; stands in for the calibration norms of Eq. 2, which need real data).
+    Returns (w_i, w_j, norm_i, norm_j)."""
+    rows, cols = shape if shape is not None else matrix_shape(cfg, which)
+    out = []
+    for e in (0, 1):
+        g = _gen(cfg, device, 6, pair, which, e)
+        w = torch.randn(rows * cols, generator=g, device=device) * cfg.sigma
+        out.append(w.to(torch.bfloat16).view(torch.int16).reshape(rows, cols))
+    for e in (0, 1):
+        g = _gen(cfg, device, 7, pair, which, e)
+        out.append(torch.rand(cols, generator=g, device=device) + 0.5)
+    return tuple(out)
+
+
 def tokens(cfg, T):
     """x [T, d_model] bf16 bits, N(0,1)."""
     g = _gen(cfg, "cpu", 3, T)

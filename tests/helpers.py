@@ -31,15 +31,34 @@ class Case:
     """One layer: oracle-side packed tensors (numpy, logical order) + the library's Layer."""
 
     def __init__(self, cfg, oracle, binding, device="cuda", emap_mode="adjacent", gen_device=None,
-                 check_pack=True):
+                 check_pack=True, from_merge=None):
         self.cfg, self.oracle, self.binding = cfg, oracle, binding
         gen_device = gen_device or device
         self.emap = synth.expert_map(cfg, emap_mode)
         self.packed_cpu = {}
         self.packed_gpu = {}
         self.n_bad = torch.zeros(1, dtype=torch.int32, device=device)
+        self.n_similar = 0
         for p in range(cfg.n_pairs):
             for which in W3:
+                if from_merge is not None:
+                    # the paper's own pipeline: two dense experts -> dual-mask merge -> packed pair
+                    wi, wj, ni, nj = synth.unmerged_pair_t(cfg, p, which, device=gen_device)
+                    self.packed_gpu[p, which] = binding.pzl_merge_pack(wi.to(device), wj.to(device), ni.to(device),
+                                                                       nj.to(device), from_merge,
+                                                                       n_out_of_range=self.n_bad)
+                    ref = oracle.merge(synth._np_bits(wi), synth._np_bits(wj), ni.cpu().numpy(),
+                                       nj.cpu().numpy(), from_merge)
+                    packed, bad = oracle.pack(ref["merged"], ref["mask0"], ref["mask1"], ref["sign0"],
+                                              ref["sign1"])
+                    assert bad == 0
+                    self.packed_cpu[p, which] = packed
+                    self.n_similar += ref["n_similar"]
+                    rows, cols = packed.shape
+                    got = binding.tiled_to_logical(
+                        self.packed_gpu[p, which].cpu().numpy().view(np.uint16), rows, cols)
+                    assert np.array_equal(got, packed), "merge_pack mismatch pair %d matrix %d" % (p, which)
+                    continue
                 pl = synth.pair_matrix_t(cfg, p, which, device=gen_device)
                 pl_dev = {k: v.to(device) for k, v in pl.items()}
                 self.packed_gpu[p, which] = binding.pzl_pack(pl_dev["merged"], pl_dev["mask0"], pl_dev["mask1"],

@@ -222,3 +222,17 @@ def test_tiled_path_skewed_routing(tiled_case):
     ids[:, 1] = 0
     ids[5, 1] = 1                    # expert 1: one token; expert 3: none
     check(tiled_case, T, "tiled-skewed", ids=ids.astype(np.int32), w=w, x=x)
+
+
+def test_merged_layer_end_to_end(oracle, binding):
+    """The paper's pipeline on synthetic experts: dense pair -> dual-mask merge (tau = 0.4) -> packed
+    pair -> routed FFN.  Masks have the paper's structure: never both clear, density ~0.74."""
+    cfg = synth.LayerConfig("merged", 8, 256, 448, 2, (300,), seed=53)
+    case = Case(cfg, oracle, binding, emap_mode="random", from_merge=0.4)
+    n_elems = cfg.n_pairs * 3 * cfg.d_model * cfg.d_ffn
+    assert abs(case.n_similar / n_elems - 0.4845) < 0.005            # Lemma 3.1 at tau = 0.4
+    words = case.packed_cpu[0, synth.GATE]
+    m0, m1 = (words >> 13) & 1, (words >> 12) & 1
+    assert np.all((m0 | m1) == 1) and abs(float(m0.mean()) - 0.742) < 0.01
+    for T in (5, 40, 500):                                           # streaming and tiled kernels
+        check(case, T, "merged-layer")
