@@ -43,7 +43,7 @@
 extern "C" {
 #endif
 
-#define PZL_ABI_VERSION 1
+#define PZL_ABI_VERSION 2
 
 #define PZL_OK       0
 #define PZL_EINVAL  -1   /* null pointer, bad shape, position not 0/1, pair map not a 2-to-1 cover */
@@ -117,21 +117,28 @@ int pzl_merge_pack(const uint16_t *w_i, const uint16_t *w_j, const float *norm_i
  * the weight tensors are referenced, not copied.
  */
 typedef struct pzl_layer_desc {
-    int32_t n_experts;              /* E, even */
+    int32_t n_experts;              /* E routed experts = 2 * n_pairs + n_dense */
     int32_t d_model;                /* d, multiple of 32 */
     int32_t d_ffn;                  /* f of the routed experts, multiple of 32 */
-    const int32_t *expert_pair;     /* host [E]: pair index in [0, E/2)                  */
-    const uint8_t *expert_pos;      /* host [E]: position 0|1 inside the pair; every pair
-                                       must be covered exactly once at each position
-                                       (pair-wise grouping, Sec. 3.2)                    */
-    const uint16_t *const *gate;    /* host [E/2] of device ptrs, packed [d_ffn, d_model] */
-    const uint16_t *const *up;      /* host [E/2] of device ptrs, packed [d_ffn, d_model] */
-    const uint16_t *const *down;    /* host [E/2] of device ptrs, packed [d_model, d_ffn] */
+    const int32_t *expert_pair;     /* host [E]: pair index in [0, n_pairs) for a merged expert,
+                                       or -1-j for routed expert j kept unmerged (the paper's
+                                       25 % compression setting merges only half of the experts,
+                                       Sec. 4.1)                                              */
+    const uint8_t *expert_pos;      /* host [E]: position 0|1 inside the pair (0 for unmerged);
+                                       every (pair, position) and every unmerged index must be
+                                       named exactly once (pair-wise grouping, Sec. 3.2)      */
+    const uint16_t *const *gate;    /* host [n_pairs] of device ptrs, packed [d_ffn, d_model] */
+    const uint16_t *const *up;      /* host [n_pairs] of device ptrs, packed [d_ffn, d_model] */
+    const uint16_t *const *down;    /* host [n_pairs] of device ptrs, packed [d_model, d_ffn] */
     int32_t n_shared;               /* dense experts applied to every token with weight 1 */
     const int32_t *shared_d_ffn;    /* host [n_shared], each a multiple of 32             */
     const uint16_t *const *shared_gate;   /* host [n_shared] of device ptrs, tiled dense  */
     const uint16_t *const *shared_up;     /*   bf16 [fs, d_model] (pzl_tile_dense)        */
     const uint16_t *const *shared_down;   /*   bf16 [d_model, fs]                         */
+    int32_t n_dense;                /* routed experts kept unmerged (0 at 50 % compression) */
+    const uint16_t *const *dense_gate;    /* host [n_dense] of device ptrs, tiled dense   */
+    const uint16_t *const *dense_up;      /*   bf16 [d_ffn, d_model] (pzl_tile_dense)     */
+    const uint16_t *const *dense_down;    /*   bf16 [d_model, d_ffn]                      */
 } pzl_layer_desc;
 
 typedef struct pzl_layer pzl_layer;

@@ -121,12 +121,14 @@ def merge(wi, wj, norm_i, norm_j, tau):
 
 
 def moe_ffn(x, ids, w, expert_pair, expert_pos, gate, up, down,
-            shared=(), stage_h_bf16=False):
+            shared=(), stage_h_bf16=False, dense=()):
     """Routed SwiGLU FFN over Eq. 6-decoded experts, fp64.
 
     x: [T,d] bf16 bits (uint16); ids: [T,k] int32; w: [T,k] float32;
     gate/up: per pair, packed uint16 [f,d] in logical order; down: per pair [d,f];
     shared: sequence of (gate [fs,d], up [fs,d], down [d,fs]) dense bf16 bits.
+    dense: routed experts kept unmerged, sequence of (gate [f,d], up [f,d], down [d,f]) dense bf16
+    bits; expert e with expert_pair[e] = -1-j uses dense[j].
     Returns (y_f64 [T,d], y_bf16_bits [T,d]).
     """
     lib = _load()
@@ -143,7 +145,12 @@ def moe_ffn(x, ids, w, expert_pair, expert_pos, gate, up, down,
     up = [_u16(a) for a in up]
     down = [_u16(a) for a in down]
     P = len(gate)
-    f = gate[0].shape[0] if P else 0
+    dg = [_u16(s_[0]) for s_ in dense]
+    du = [_u16(s_[1]) for s_ in dense]
+    dd = [_u16(s_[2]) for s_ in dense]
+    f = gate[0].shape[0] if P else (dg[0].shape[0] if dg else 0)
+    for a, b, c in zip(dg, du, dd):
+        assert a.shape == (f, d) and b.shape == (f, d) and c.shape == (d, f)
     for a, b, c in zip(gate, up, down):
         assert a.shape == (f, d) and b.shape == (f, d) and c.shape == (d, f)
     sg = [_u16(s[0]) for s in shared]
@@ -165,6 +172,7 @@ def moe_ffn(x, ids, w, expert_pair, expert_pos, gate, up, down,
         ctypes.c_void_p(w.ctypes.data), ctypes.c_void_p(expert_pair.ctypes.data),
         ctypes.c_void_p(expert_pos.ctypes.data),
         ptr_array(gate), ptr_array(up), ptr_array(down),
+        ctypes.c_int(len(dg)), ptr_array(dg), ptr_array(du), ptr_array(dd),
         ctypes.c_int(len(sg)), ctypes.c_void_p(sf.ctypes.data),
         ptr_array(sg), ptr_array(su), ptr_array(sd),
         ctypes.c_int(1 if stage_h_bf16 else 0),

@@ -163,9 +163,11 @@ static void matvec_dense(const uint16_t *Wd, int rows, int cols, const double *v
 
 /*
  * y[t,:] = sum_j w[t,j] * FFN_{ids[t,j]}(x[t,:])  +  sum_s FFN_shared_s(x[t,:])
- * FFN_e(x) = Wdown_e ( silu(Wgate_e x) * (Wup_e x) ),  W_e = Eq. 6 decode of its pair's
- * packed tensor at position expert_pos[e].  gate/up are [f,d], down is [d,f], row-major,
- * in the *logical* element order (the order orc_pack wrote them).
+ * FFN_e(x) = Wdown_e ( silu(Wgate_e x) * (Wup_e x) ).
+ * Expert e with expert_pair[e] = p >= 0 is merged: W_e = Eq. 6 decode of pair p's packed tensor at
+ * position expert_pos[e].  Expert e with expert_pair[e] = -1-j is routed dense expert j, kept
+ * unmerged (the 25 % compression setting of Sec. 4.1 leaves half of the experts as they are).
+ * gate/up are [f,d], down is [d,f], row-major, in the *logical* element order.
  *
  * stage_h_bf16 = 0: the definition (h kept in fp64).
  * stage_h_bf16 = 1: h rounded to bf16 before the down projection (diagnostic only).
@@ -177,6 +179,8 @@ int orc_moe_ffn(int T, int k, int E, int d, int f,
                 const int32_t *expert_pair, const uint8_t *expert_pos,
                 const uint16_t *const *gate, const uint16_t *const *up,
                 const uint16_t *const *down,
+                int n_dense, const uint16_t *const *dgate, const uint16_t *const *dup,
+                const uint16_t *const *ddown,
                 int n_shared, const int32_t *shared_f,
                 const uint16_t *const *sgate, const uint16_t *const *sup,
                 const uint16_t *const *sdown,
@@ -201,13 +205,21 @@ int orc_moe_ffn(int T, int k, int E, int d, int f,
             int e = ids[(int64_t)t * k + j];
             if (e < 0 || e >= E) { rc = -1; goto done; }
             int p = expert_pair[e], pos = expert_pos[e];
-            matvec_packed(gate[p], pos, f, d, xv, g);
-            matvec_packed(up[p], pos, f, d, xv, u);
+            if (p >= 0) {
+                matvec_packed(gate[p], pos, f, d, xv, g);
+                matvec_packed(up[p], pos, f, d, xv, u);
+            } else {
+                int dj = -1 - p;
+                if (dj >= n_dense) { rc = -1; goto done; }
+                matvec_dense(dgate[dj], f, d, xv, g);
+                matvec_dense(dup[dj], f, d, xv, u);
+            }
             for (int r = 0; r < f; ++r) {
                 h[r] = silu(g[r]) * u[r];
                 if (stage_h_bf16) h[r] = orc_bf16_to_double(orc_bf16_from_double(h[r]));
             }
-            matvec_packed(down[p], pos, d, f, h, o);
+            if (p >= 0) matvec_packed(down[p], pos, d, f, h, o);
+            else        matvec_dense(ddown[-1 - p], d, f, h, o);
             double wt = (double)w[(int64_t)t * k + j];
             for (int c = 0; c < d; ++c) acc[c] += wt * o[c];
         }

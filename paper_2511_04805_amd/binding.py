@@ -39,7 +39,9 @@ class _LayerDesc(ctypes.Structure):
                 ("gate", ctypes.c_void_p), ("up", ctypes.c_void_p), ("down", ctypes.c_void_p),
                 ("n_shared", ctypes.c_int32), ("shared_d_ffn", ctypes.c_void_p),
                 ("shared_gate", ctypes.c_void_p), ("shared_up", ctypes.c_void_p),
-                ("shared_down", ctypes.c_void_p)]
+                ("shared_down", ctypes.c_void_p),
+                ("n_dense", ctypes.c_int32), ("dense_gate", ctypes.c_void_p),
+                ("dense_up", ctypes.c_void_p), ("dense_down", ctypes.c_void_p)]
 
 
 def load():
@@ -162,9 +164,11 @@ def _ptr_table(tensors):
 class Layer:
     """Owns a pzl_layer handle and keeps the weight tensors it references alive."""
 
-    def __init__(self, d_model, d_ffn, expert_pair, expert_pos, gate, up, down, shared=()):
+    def __init__(self, d_model, d_ffn, expert_pair, expert_pos, gate, up, down, shared=(), dense=()):
+        """gate/up/down: one packed tensor per pair; shared: (gate, up, down, f) tiled dense per shared
+        expert; dense: (gate, up, down) tiled dense per routed expert kept unmerged."""
         self.d_model, self.d_ffn = int(d_model), int(d_ffn)
-        self._keep = (list(gate), list(up), list(down), [tuple(s) for s in shared])
+        self._keep = (list(gate), list(up), list(down), [tuple(s) for s in shared], [tuple(s) for s in dense])
         pair = np.ascontiguousarray(expert_pair, dtype=np.int32)
         pos = np.ascontiguousarray(expert_pos, dtype=np.uint8)
         P = len(gate)
@@ -182,9 +186,16 @@ class Layer:
                 _dev(t, _BITS16, "shared weight")
                 if t.numel() != fs * d_model:
                     raise ValueError("shared weight has the wrong size")
+        for g, u, dn in dense:
+            for t in (g, u, dn):
+                _dev(t, _BITS16, "unmerged expert weight")
+                if t.numel() != d_ffn * d_model:
+                    raise ValueError("unmerged expert weight has the wrong size")
         self._tables = (pair, pos, sf, _ptr_table(gate), _ptr_table(up), _ptr_table(down),
                         _ptr_table([s[0] for s in shared]), _ptr_table([s[1] for s in shared]),
-                        _ptr_table([s[2] for s in shared]))
+                        _ptr_table([s[2] for s in shared]),
+                        _ptr_table([s[0] for s in dense]), _ptr_table([s[1] for s in dense]),
+                        _ptr_table([s[2] for s in dense]))
         d = _LayerDesc()
         d.n_experts, d.d_model, d.d_ffn = int(pair.size), self.d_model, self.d_ffn
         d.expert_pair, d.expert_pos = pair.ctypes.data, pos.ctypes.data
@@ -194,6 +205,9 @@ class Layer:
         d.shared_d_ffn = sf.ctypes.data if len(shared) else None
         d.shared_gate, d.shared_up, d.shared_down = (cast(self._tables[6]), cast(self._tables[7]),
                                                      cast(self._tables[8]))
+        d.n_dense = len(dense)
+        d.dense_gate, d.dense_up, d.dense_down = (cast(self._tables[9]), cast(self._tables[10]),
+                                                  cast(self._tables[11]))
         self._h = ctypes.c_void_p()
         _check(load().pzl_layer_create(ctypes.byref(d), ctypes.byref(self._h)), "pzl_layer_create")
         self._ws = None

@@ -22,11 +22,13 @@ static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 }  // namespace pzl
 
 struct pzl_layer {
-    int32_t n_experts, n_pairs, d_model, d_ffn, n_shared;
+    int32_t n_experts, n_pairs, n_dense, d_model, d_ffn, n_shared;
+    int32_t n_q;                           // routing keys: 2 per pair, then 2 per unmerged expert (its position 1 stays empty)
     std::vector<int32_t> shared_f;
     // device tables
     int32_t *d_q_of_expert;                // [E] expert -> 2*pair + pos
     const uint16_t **d_gate, **d_up, **d_down;            // [P]
+    const uint16_t **d_dgate, **d_dup, **d_ddown;         // [n_dense] routed experts kept unmerged
     const uint16_t **d_sgate, **d_sup, **d_sdown;         // [n_shared]
     void *d_block;                         // the one allocation holding all of the above
 };
@@ -53,11 +55,11 @@ static WorkspaceLayout carve(const pzl_layer *L, int32_t T, int32_t k)
     const size_t N = (size_t)T * k;
     const size_t slots = N + (size_t)L->n_shared * T;
     size_t p = 0;
-    w.cnt = p;       p += align_up((size_t)L->n_experts * 4, 256);
-    w.off = p;       p += align_up(((size_t)L->n_experts + 1) * 4, 256);
+    w.cnt = p;       p += align_up((size_t)L->n_q * 4, 256);
+    w.off = p;       p += align_up(((size_t)L->n_q + 1) * 4, 256);
     w.slot_tok = p;  p += align_up(N * 4, 256);
     w.slot_of = p;   p += align_up(N * 4, 256);
-    const size_t mt = (size_t)max_token_tiles((int64_t)N, L->n_experts);
+    const size_t mt = (size_t)max_token_tiles((int64_t)N, L->n_q);
     w.tile_q = p;     p += align_up(mt * 4, 256);
     w.tile_slot0 = p; p += align_up(mt * 4, 256);
     w.tile_n = p;     p += align_up(mt * 4, 256);
@@ -155,24 +157,38 @@ int pzl_layer_create(const pzl_layer_desc *desc, pzl_layer **out)
 {
     if (!desc || !out) return PZL_EINVAL;
     *out = nullptr;
-    const int E = desc->n_experts, d = desc->d_model, f = desc->d_ffn, S = desc->n_shared;
-    if (E < 2 || (E & 1) || E > 512 || d <= 0 || f <= 0 || d % TILE_COLS || f % TILE_COLS) return PZL_EINVAL;
-    if (!desc->expert_pair || !desc->expert_pos || !desc->gate || !desc->up || !desc->down) return PZL_EINVAL;
+    const int E = desc->n_experts, d = desc->d_model, f = desc->d_ffn, S = desc->n_shared, D = desc->n_dense;
+    if (E < 1 || E > 256 || D < 0 || D > E || ((E - D) & 1) || d <= 0 || f <= 0 || d % TILE_COLS || f % TILE_COLS)
+        return PZL_EINVAL;
+    const int P = (E - D) / 2;
+    if (!desc->expert_pair || !desc->expert_pos) return PZL_EINVAL;
+    if (P > 0 && (!desc->gate || !desc->up || !desc->down)) return PZL_EINVAL;
+    if (D > 0 && (!desc->dense_gate || !desc->dense_up || !desc->dense_down)) return PZL_EINVAL;
     if (S < 0 || S > 16) return PZL_EINVAL;
     if (S > 0 && (!desc->shared_d_ffn || !desc->shared_gate || !desc->shared_up || !desc->shared_down))
         return PZL_EINVAL;
-    const int P = E / 2;
-    // the pair map must cover every (pair, position) exactly once
+    // every (pair, position) and every unmerged expert must be named exactly once
     std::vector<int32_t> q_of(E);
-    std::vector<char> seen(E, 0);
+    std::vector<char> seen(2 * (P + D), 0);
     for (int e = 0; e < E; ++e) {
         int p = desc->expert_pair[e], pos = desc->expert_pos[e];
-        if (p < 0 || p >= P || pos < 0 || pos > 1 || seen[2 * p + pos]) return PZL_EINVAL;
-        seen[2 * p + pos] = 1;
-        q_of[e] = 2 * p + pos;
+        int q;
+        if (p >= 0) {
+            if (p >= P || pos < 0 || pos > 1) return PZL_EINVAL;
+            q = 2 * p + pos;
+        } else {
+            int j = -1 - p;
+            if (j >= D) return PZL_EINVAL;
+            q = 2 * (P + j);
+        }
+        if (seen[q]) return PZL_EINVAL;
+        seen[q] = 1;
+        q_of[e] = q;
     }
     for (int p = 0; p < P; ++p)
         if (!desc->gate[p] || !desc->up[p] || !desc->down[p]) return PZL_EINVAL;
+    for (int j = 0; j < D; ++j)
+        if (!desc->dense_gate[j] || !desc->dense_up[j] || !desc->dense_down[j]) return PZL_EINVAL;
     for (int s = 0; s < S; ++s) {
         int fs = desc->shared_d_ffn[s];
         if (fs <= 0 || fs % TILE_COLS || !desc->shared_gate[s] || !desc->shared_up[s] || !desc->shared_down[s])
@@ -181,19 +197,24 @@ int pzl_layer_create(const pzl_layer_desc *desc, pzl_layer **out)
 
     pzl_layer *L = new (std::nothrow) pzl_layer();
     if (!L) return PZL_ENOMEM;
-    L->n_experts = E; L->n_pairs = P; L->d_model = d; L->d_ffn = f; L->n_shared = S;
+    L->n_experts = E; L->n_pairs = P; L->n_dense = D; L->d_model = d; L->d_ffn = f; L->n_shared = S;
+    L->n_q = 2 * (P + D);
     L->shared_f.assign(desc->shared_d_ffn, desc->shared_d_ffn + S);
 
     const size_t sz_q = align_up((size_t)E * 4, 256);
-    const size_t sz_p = align_up((size_t)P * sizeof(void *), 256);
+    const size_t sz_p = align_up((size_t)(P > 0 ? P : 1) * sizeof(void *), 256);
     const size_t sz_s = align_up((size_t)(S > 0 ? S : 1) * sizeof(void *), 256);
-    const size_t total = sz_q + 3 * sz_p + 3 * sz_s;
+    const size_t sz_d = align_up((size_t)(D > 0 ? D : 1) * sizeof(void *), 256);
+    const size_t total = sz_q + 3 * sz_p + 3 * sz_s + 3 * sz_d;
     std::vector<unsigned char> host(total, 0);
     size_t o = 0;
     memcpy(&host[o], q_of.data(), (size_t)E * 4);                     size_t o_q = o;  o += sz_q;
-    memcpy(&host[o], desc->gate, (size_t)P * sizeof(void *));         size_t o_g = o;  o += sz_p;
-    memcpy(&host[o], desc->up, (size_t)P * sizeof(void *));           size_t o_u = o;  o += sz_p;
-    memcpy(&host[o], desc->down, (size_t)P * sizeof(void *));         size_t o_d = o;  o += sz_p;
+    size_t o_g = o; if (P) memcpy(&host[o], desc->gate, (size_t)P * sizeof(void *)); o += sz_p;
+    size_t o_u = o; if (P) memcpy(&host[o], desc->up, (size_t)P * sizeof(void *));   o += sz_p;
+    size_t o_d = o; if (P) memcpy(&host[o], desc->down, (size_t)P * sizeof(void *)); o += sz_p;
+    size_t o_dg = o; if (D) memcpy(&host[o], desc->dense_gate, (size_t)D * sizeof(void *)); o += sz_d;
+    size_t o_du = o; if (D) memcpy(&host[o], desc->dense_up, (size_t)D * sizeof(void *));   o += sz_d;
+    size_t o_dd = o; if (D) memcpy(&host[o], desc->dense_down, (size_t)D * sizeof(void *)); o += sz_d;
     size_t o_sg = o; if (S) memcpy(&host[o], desc->shared_gate, (size_t)S * sizeof(void *)); o += sz_s;
     size_t o_su = o; if (S) memcpy(&host[o], desc->shared_up, (size_t)S * sizeof(void *));   o += sz_s;
     size_t o_sd = o; if (S) memcpy(&host[o], desc->shared_down, (size_t)S * sizeof(void *)); o += sz_s;
@@ -207,6 +228,9 @@ int pzl_layer_create(const pzl_layer_desc *desc, pzl_layer **out)
     L->d_gate = (const uint16_t **)(base + o_g);
     L->d_up = (const uint16_t **)(base + o_u);
     L->d_down = (const uint16_t **)(base + o_d);
+    L->d_dgate = (const uint16_t **)(base + o_dg);
+    L->d_dup = (const uint16_t **)(base + o_du);
+    L->d_ddown = (const uint16_t **)(base + o_dd);
     L->d_sgate = (const uint16_t **)(base + o_sg);
     L->d_sup = (const uint16_t **)(base + o_su);
     L->d_sdown = (const uint16_t **)(base + o_sd);
@@ -270,7 +294,7 @@ int pzl_moe_ffn_staged(const pzl_layer *L, const uint16_t *x, const int32_t *top
 
     int rc = mark(PZL_STAGE_ROUTE, 0);
     if (rc) return rc;
-    rc = launch_route(topk_ids, N, k, L->n_experts, L->d_q_of_expert, rt, st);
+    rc = launch_route(topk_ids, N, k, L->n_experts, L->n_q, L->d_q_of_expert, rt, st);
     if (rc) return rc;
     if ((rc = mark(PZL_STAGE_ROUTE, 1))) return rc;
 
@@ -279,9 +303,10 @@ int pzl_moe_ffn_staged(const pzl_layer *L, const uint16_t *x, const int32_t *top
     // dense contraction (tiled kernels on the matrix cores).
     const bool tiled = (int64_t)N >= (int64_t)TILED_MIN_TOKENS_PER_EXPERT * L->n_experts;
     const bool tiled_shared = T >= TILED_MIN_TOKENS_SHARED;
-    const int pairs_max = (int)((int64_t)N < L->n_pairs ? N : L->n_pairs);   // pairs that can have tokens
+    const int routed_groups = L->n_pairs + L->n_dense;
+    const int groups_max = (int)((int64_t)N < routed_groups ? N : routed_groups);   // groups that can have tokens
     const int ksplit = tiled ? choose_tile_ksplit(N / TILE_MAX_TOKENS + L->n_experts / 2, L->d_model, L->d_ffn)
-                             : choose_ksplit(pairs_max > 0 ? pairs_max : 1, L->d_model);
+                             : choose_ksplit(groups_max > 0 ? groups_max : 1, L->d_model);
     int ksplit_shared = choose_ksplit(1, L->d_model);
     if (tiled_shared) {
         ksplit_shared = MAX_KSPLIT;
@@ -291,49 +316,66 @@ int pzl_moe_ffn_staged(const pzl_layer *L, const uint16_t *x, const int32_t *top
         }
     }
     const int64_t h_plane = (int64_t)N * L->d_ffn;
-    if (N > 0 && tiled) {
-        TileGemmArgs a = {};
-        a.slot_tok = rt.slot_tok;
-        a.tile_q = rt.tile_q; a.tile_slot0 = rt.tile_slot0; a.tile_n = rt.tile_n; a.n_tiles = rt.n_tiles;
-        a.max_mtiles = max_token_tiles(N, L->n_experts);
-        a.w_a = L->d_gate; a.w_b = L->d_up;
-        a.rows = L->d_ffn; a.kdim = L->d_model;
-        a.act = x; a.act_is_x = 1;
-        a.h_out = h_routed; a.h_slot_base = 0; a.h_plane_stride = h_plane;
-        if ((rc = mark(PZL_STAGE_GATEUP, 0))) return rc;
-        rc = launch_tile_gateup(a, false, st);
-        if (rc) return rc;
-        if ((rc = mark(PZL_STAGE_GATEUP, 1))) return rc;
-        a.w_a = L->d_down; a.w_b = nullptr;
-        a.rows = L->d_model; a.kdim = L->d_ffn;
-        a.act = h_routed; a.act_is_x = 0; a.act_slot_base = 0; a.act_plane_stride = h_plane;
-        a.h_out = nullptr; a.o_out = opart; a.o_ks_stride = w.o_ks_stride; a.ksplit = ksplit;
-        if ((rc = mark(PZL_STAGE_DOWN, 0))) return rc;
-        rc = launch_tile_down(a, false, st);
-        if (rc) return rc;
-        if ((rc = mark(PZL_STAGE_DOWN, 1))) return rc;
-    } else if (N > 0) {
-        StreamGroupArgs a = {};
-        a.n_groups = L->n_pairs; a.groups_touched_max = pairs_max;
-        a.cnt = rt.cnt; a.off = rt.off; a.slot_tok = rt.slot_tok;
-        // gate/up + SwiGLU -> H
-        a.w_a = L->d_gate; a.w_b = L->d_up;
-        a.rows = L->d_ffn; a.kdim = L->d_model; a.ksplit = 1;
-        a.act = x; a.act_is_x = 1; a.act_slot_base = 0;
-        a.h_out = h_routed; a.h_slot_base = 0; a.h_plane_stride = h_plane;
-        if ((rc = mark(PZL_STAGE_GATEUP, 0))) return rc;
-        rc = launch_stream_gateup(a, false, st);
-        if (rc) return rc;
-        if ((rc = mark(PZL_STAGE_GATEUP, 1))) return rc;
-        // down -> partial sums
-        a.w_a = L->d_down; a.w_b = nullptr;
-        a.rows = L->d_model; a.kdim = L->d_ffn; a.ksplit = ksplit;
-        a.act = h_routed; a.act_is_x = 0; a.act_slot_base = 0; a.act_plane_stride = h_plane;
-        a.h_out = nullptr; a.o_out = opart; a.o_ks_stride = w.o_ks_stride;
-        if ((rc = mark(PZL_STAGE_DOWN, 0))) return rc;
-        rc = launch_stream_down(a, false, st);
-        if (rc) return rc;
-        if ((rc = mark(PZL_STAGE_DOWN, 1))) return rc;
+    // Routed experts come in two kinds that differ only in the decode: packed pairs (groups
+    // [0, P)) and experts kept unmerged (dense bf16, groups [P, P + D), position 0 only).  Both
+    // kinds write disjoint slots of the same H and partial-sum buffers.
+    for (int pass = 0; pass < 2 && N > 0; ++pass) {
+        const bool unmerged = pass == 1;
+        const int n_groups = unmerged ? L->n_dense : L->n_pairs;
+        if (n_groups == 0) continue;
+        const int kind = unmerged ? KIND_UNMERGED : KIND_PACKED;
+        const uint16_t *const *wg = unmerged ? L->d_dgate : L->d_gate;
+        const uint16_t *const *wu = unmerged ? L->d_dup : L->d_up;
+        const uint16_t *const *wd = unmerged ? L->d_ddown : L->d_down;
+        const int group_base = unmerged ? L->n_pairs : 0;
+        // the stage events bracket the packed kind when the layer has one, else the unmerged kind
+        const bool timed = !unmerged || L->n_pairs == 0;
+        if (tiled) {
+            TileGemmArgs a = {};
+            a.slot_tok = rt.slot_tok;
+            a.tile_q = rt.tile_q; a.tile_slot0 = rt.tile_slot0; a.tile_n = rt.tile_n; a.n_tiles = rt.n_tiles;
+            a.group_lo = group_base; a.group_hi = group_base + n_groups;
+            a.max_mtiles = max_token_tiles(N, L->n_q);
+            a.w_a = wg; a.w_b = wu;
+            a.rows = L->d_ffn; a.kdim = L->d_model;
+            a.act = x; a.act_is_x = 1;
+            a.h_out = h_routed; a.h_slot_base = 0; a.h_plane_stride = h_plane;
+            if (timed && (rc = mark(PZL_STAGE_GATEUP, 0))) return rc;
+            rc = launch_tile_gateup(a, kind, st);
+            if (rc) return rc;
+            if (timed && (rc = mark(PZL_STAGE_GATEUP, 1))) return rc;
+            a.w_a = wd; a.w_b = nullptr;
+            a.rows = L->d_model; a.kdim = L->d_ffn;
+            a.act = h_routed; a.act_is_x = 0; a.act_slot_base = 0; a.act_plane_stride = h_plane;
+            a.h_out = nullptr; a.o_out = opart; a.o_ks_stride = w.o_ks_stride; a.ksplit = ksplit;
+            if (timed && (rc = mark(PZL_STAGE_DOWN, 0))) return rc;
+            rc = launch_tile_down(a, kind, st);
+            if (rc) return rc;
+            if (timed && (rc = mark(PZL_STAGE_DOWN, 1))) return rc;
+        } else {
+            StreamGroupArgs a = {};
+            a.n_groups = n_groups; a.group_base = group_base;
+            a.groups_touched_max = (int)((int64_t)N < n_groups ? N : n_groups);
+            a.cnt = rt.cnt; a.off = rt.off; a.slot_tok = rt.slot_tok;
+            // gate/up + SwiGLU -> H
+            a.w_a = wg; a.w_b = wu;
+            a.rows = L->d_ffn; a.kdim = L->d_model; a.ksplit = 1;
+            a.act = x; a.act_is_x = 1; a.act_slot_base = 0;
+            a.h_out = h_routed; a.h_slot_base = 0; a.h_plane_stride = h_plane;
+            if (timed && (rc = mark(PZL_STAGE_GATEUP, 0))) return rc;
+            rc = launch_stream_gateup(a, kind, st);
+            if (rc) return rc;
+            if (timed && (rc = mark(PZL_STAGE_GATEUP, 1))) return rc;
+            // down -> partial sums
+            a.w_a = wd; a.w_b = nullptr;
+            a.rows = L->d_model; a.kdim = L->d_ffn; a.ksplit = ksplit;
+            a.act = h_routed; a.act_is_x = 0; a.act_slot_base = 0; a.act_plane_stride = h_plane;
+            a.h_out = nullptr; a.o_out = opart; a.o_ks_stride = w.o_ks_stride;
+            if (timed && (rc = mark(PZL_STAGE_DOWN, 0))) return rc;
+            rc = launch_stream_down(a, kind, st);
+            if (rc) return rc;
+            if (timed && (rc = mark(PZL_STAGE_DOWN, 1))) return rc;
+        }
     }
 
     if ((rc = mark(PZL_STAGE_SHARED, 0))) return rc;
@@ -354,13 +396,13 @@ int pzl_moe_ffn_staged(const pzl_layer *L, const uint16_t *x, const int32_t *top
             a.rows = L->shared_f[s]; a.kdim = L->d_model;
             a.act = x; a.act_is_x = 1;
             a.h_out = h_s; a.h_slot_base = slot_base; a.h_plane_stride = hs_plane;
-            rc = launch_tile_gateup(a, true, st);
+            rc = launch_tile_gateup(a, KIND_SHARED, st);
             if (rc) return rc;
             a.w_a = L->d_sdown + s; a.w_b = nullptr;
             a.rows = L->d_model; a.kdim = L->shared_f[s];
             a.act = h_s; a.act_is_x = 0; a.act_slot_base = slot_base; a.act_plane_stride = hs_plane;
             a.h_out = nullptr; a.o_out = opart; a.o_ks_stride = w.o_ks_stride; a.ksplit = ksplit_shared;
-            rc = launch_tile_down(a, true, st);
+            rc = launch_tile_down(a, KIND_SHARED, st);
             if (rc) return rc;
             continue;
         }
@@ -371,13 +413,13 @@ int pzl_moe_ffn_staged(const pzl_layer *L, const uint16_t *x, const int32_t *top
         a.rows = L->shared_f[s]; a.kdim = L->d_model; a.ksplit = 1;
         a.act = x; a.act_is_x = 1; a.act_slot_base = 0;
         a.h_out = h_s; a.h_slot_base = slot_base; a.h_plane_stride = hs_plane;
-        rc = launch_stream_gateup(a, true, st);
+        rc = launch_stream_gateup(a, KIND_SHARED, st);
         if (rc) return rc;
         a.w_a = L->d_sdown + s; a.w_b = nullptr;
         a.rows = L->d_model; a.kdim = L->shared_f[s]; a.ksplit = ksplit_shared;
         a.act = h_s; a.act_is_x = 0; a.act_slot_base = slot_base; a.act_plane_stride = hs_plane;
         a.h_out = nullptr; a.o_out = opart; a.o_ks_stride = w.o_ks_stride;
-        rc = launch_stream_down(a, true, st);
+        rc = launch_stream_down(a, KIND_SHARED, st);
         if (rc) return rc;
     }
 

@@ -47,7 +47,7 @@ int launch_merge_pack(const uint16_t *wi, const uint16_t *wj, const float *norm_
                       int32_t *n_bad, hipStream_t st);
 
 // route.hip
-int launch_route(const int32_t *ids, int32_t n_flat, int32_t k, int32_t n_experts, const int32_t *q_of_expert,
+int launch_route(const int32_t *ids, int32_t n_flat, int32_t k, int32_t n_experts, int32_t n_slots_q, const int32_t *q_of_expert,
                  RouteTables rt, hipStream_t st);
 int launch_combine(const float *opart, int32_t ksplit, int32_t ksplit_shared, int64_t ks_stride, const RouteTables &rt,
                    const float *topk_w, int32_t T, int32_t k, int32_t d, int32_t n_shared,
@@ -66,6 +66,7 @@ struct StreamGroupArgs {
     int32_t act_is_x;             // 1: row = slot_tok[slot] (or the token itself if dense); 0: row = slot - act_slot_base
     int32_t act_slot_base;
     const int32_t *cnt;           // routed: RouteTables.cnt, dense: nullptr
+    int32_t group_base;           // routed: index of the first group (q = 2 * (group_base + g) + pos)
     const int32_t *off;
     const int32_t *slot_tok;
     int32_t dense_tokens;         // dense groups: every group sees tokens 0..dense_tokens-1
@@ -79,8 +80,10 @@ struct StreamGroupArgs {
 };
 int stream_row_groups(int rows, bool down_stage);   // row groups (workgroup units) along the output rows
 constexpr int STREAM_RESIDENT_WGS = 512;             // workgroups the chip holds at once (256 CUs x 2)
-int launch_stream_gateup(const StreamGroupArgs &a, bool dense, hipStream_t st);
-int launch_stream_down(const StreamGroupArgs &a, bool dense, hipStream_t st);
+// kind: 0 packed pairs, 1 dense experts seeing every token (shared), 2 dense routed experts
+constexpr int KIND_PACKED = 0, KIND_SHARED = 1, KIND_UNMERGED = 2;
+int launch_stream_gateup(const StreamGroupArgs &a, int kind, hipStream_t st);
+int launch_stream_down(const StreamGroupArgs &a, int kind, hipStream_t st);
 
 // tile_gemm.hip: LDS-staged decode-GEMM on the matrix cores for large token counts per expert.
 struct TileGemmArgs {
@@ -92,6 +95,7 @@ struct TileGemmArgs {
     int32_t act_is_x, act_slot_base;
     const int32_t *slot_tok;
     const int32_t *tile_q, *tile_slot0, *tile_n, *n_tiles;   // routed groups: RouteTables tile list
+    int32_t group_lo, group_hi;                              // routed: groups [lo, hi) belong to this launch
     int32_t dense_tokens, dense_slot_base, dense_tiles, dense_tile_tokens;   // dense group: uniform tiles
     uint16_t *h_out;
     int64_t h_plane_stride;
@@ -101,7 +105,7 @@ struct TileGemmArgs {
     int32_t ksplit;               // down stage only: workgroups sharing one output tile along K
     int32_t max_mtiles;           // upper bound on token tiles (grid size)
 };
-int launch_tile_gateup(const TileGemmArgs &a, bool dense, hipStream_t st);
-int launch_tile_down(const TileGemmArgs &a, bool dense, hipStream_t st);
+int launch_tile_gateup(const TileGemmArgs &a, int kind, hipStream_t st);
+int launch_tile_down(const TileGemmArgs &a, int kind, hipStream_t st);
 
 }  // namespace pzl

@@ -131,10 +131,10 @@ combine_kernel(const float *__restrict__ opart, int32_t ksplit, int32_t ksplit_s
     *(u32x2 *)(y + (int64_t)t * d + c) = o;
 }
 
-int launch_route(const int32_t *ids, int32_t n_flat, int32_t k, int32_t n_experts,
+int launch_route(const int32_t *ids, int32_t n_flat, int32_t k, int32_t n_experts, int32_t n_slots_q,
                  const int32_t *q_of_expert, RouteTables rt, hipStream_t st)
 {
-    int Q = n_experts;
+    int Q = n_slots_q;
     if (Q > ROUTE_QMAX) return PZL_EINVAL;
     hipLaunchKernelGGL(route_kernel, dim3(1), dim3(ROUTE_THREADS), 0, st, ids, n_flat, k, n_experts,
                        q_of_expert, Q, rt.cnt, rt.off, rt.slot_tok, rt.slot_of, rt.tile_q, rt.tile_slot0,

@@ -51,6 +51,7 @@ struct SgArgs {
     int64_t act_plane_stride;
     int32_t act_is_x, act_slot_base;
     const int32_t *cnt, *off, *slot_tok;
+    int32_t group_base;          // routed groups: first group index (q = 2 * (group_base + g) + pos)
     int32_t dense_tokens, dense_slot_base;
     uint16_t *h_out;
     int64_t h_plane_stride;
@@ -104,7 +105,9 @@ __device__ __forceinline__ void swiglu_split(float g, float u, uint32_t &hi, uin
 }
 
 // One pass: NT0 token tiles of position 0 followed by NT1 tiles of position 1.
-template <int STAGE, bool DENSE, int NT0, int NT1>
+// DENSE: the weights are plain bf16 (identity decode).  ALLTOK: the group sees every token
+// (a shared expert) instead of a routed slot range.
+template <int STAGE, bool DENSE, bool ALLTOK, int NT0, int NT1>
 __device__ __forceinline__ void stream_pass(const SgArgs &a, const uint16_t *wa, const uint16_t *wb,
                                             int rt0, int rt1, bool active0, bool active1,
                                             int kb0, int kb1, int ks,
@@ -129,7 +132,7 @@ __device__ __forceinline__ void stream_pass(const SgArgs &a, const uint16_t *wa,
         if (nt < NT0) slot = base0 + min((tile0 + nt) * 16 + j, n0 - 1);
         else          slot = base1 + min((tile1 + nt - NT0) * 16 + j, n1 - 1);
         int row;
-        if (a.act_is_x) row = DENSE ? (slot - base0) : a.slot_tok[slot];
+        if (a.act_is_x) row = ALLTOK ? (slot - base0) : a.slot_tok[slot];
         else            row = slot - a.act_slot_base;
         rowidx[tid] = row;
     }
@@ -270,7 +273,7 @@ __device__ __forceinline__ void stream_pass(const SgArgs &a, const uint16_t *wa,
     }
 }
 
-template <int STAGE, bool DENSE>
+template <int STAGE, bool DENSE, bool ALLTOK>
 __global__ void __launch_bounds__(SG_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2)))
 stream_kernel(SgArgs a)
 {
@@ -288,12 +291,13 @@ stream_kernel(SgArgs a)
     const int g = b / rg_blocks;
 
     int base0, n0, base1, n1;
-    if (DENSE) {
+    if (ALLTOK) {
         n0 = a.dense_tokens; n1 = 0;
         base0 = a.dense_slot_base + g * a.dense_tokens; base1 = 0;
     } else {
-        n0 = a.cnt[2 * g]; n1 = a.cnt[2 * g + 1];
-        base0 = a.off[2 * g]; base1 = a.off[2 * g + 1];
+        const int q0 = 2 * (a.group_base + g);
+        n0 = a.cnt[q0]; n1 = a.cnt[q0 + 1];
+        base0 = a.off[q0]; base1 = a.off[q0 + 1];
     }
     if (n0 + n1 == 0) return;
 
@@ -303,7 +307,7 @@ stream_kernel(SgArgs a)
     const int kb1 = (int)((int64_t)(ks + 1) * kb_total / a.ksplit);
     const uint16_t *wa = a.w_a[g];
     const uint16_t *wb = (STAGE == STAGE_GATEUP) ? a.w_b[g] : wa;
-    constexpr int PT = DENSE ? SG_MAX_TILES : SG_POS_TILES;
+    constexpr int PT = DENSE ? SG_MAX_TILES : SG_POS_TILES;   // a dense group has one position only
     const int tiles0 = (n0 + 15) >> 4, tiles1 = (n1 + 15) >> 4;
 
     for (int rg = rgb * a.rg_per_wg; rg < min(row_groups, (rgb + 1) * a.rg_per_wg); ++rg) {
@@ -316,7 +320,7 @@ stream_kernel(SgArgs a)
         int c0 = min(PT, max(tiles0 - t0, 0));
         int c1 = min(PT, max(tiles1 - t1, 0));
 #define PZL_PASS(A, B)                                                                              \
-    stream_pass<STAGE, DENSE, A, B>(a, wa, wb, rt0, rt1, active0, active1, kb0, kb1, ks, base0, n0, \
+    stream_pass<STAGE, DENSE, ALLTOK, A, B>(a, wa, wb, rt0, rt1, active0, active1, kb0, kb1, ks, base0, n0, \
                                     t0, base1, n1, t1, xs, rowidx)
         if (DENSE) {
             switch (c0) {
@@ -348,7 +352,7 @@ int stream_row_groups(int rows, bool down_stage)
     return (rows / TILE_ROWS + per_wg - 1) / per_wg;
 }
 
-template <int STAGE, bool DENSE>
+template <int STAGE, bool DENSE, bool ALLTOK>
 static int launch(const StreamGroupArgs &g, hipStream_t st)
 {
     if (g.n_groups <= 0) return PZL_OK;
@@ -357,7 +361,7 @@ static int launch(const StreamGroupArgs &g, hipStream_t st)
     a.w_a = g.w_a; a.w_b = g.w_b; a.rows = g.rows; a.kdim = g.kdim; a.ksplit = g.ksplit;
     a.act = g.act; a.act_plane_stride = g.act_plane_stride;
     a.act_is_x = g.act_is_x; a.act_slot_base = g.act_slot_base;
-    a.cnt = g.cnt; a.off = g.off; a.slot_tok = g.slot_tok;
+    a.cnt = g.cnt; a.off = g.off; a.slot_tok = g.slot_tok; a.group_base = g.group_base;
     a.dense_tokens = g.dense_tokens; a.dense_slot_base = g.dense_slot_base;
     a.h_out = g.h_out; a.h_plane_stride = g.h_plane_stride; a.h_slot_base = g.h_slot_base;
     a.o_out = g.o_out; a.o_ks_stride = g.o_ks_stride;
@@ -376,25 +380,31 @@ static int launch(const StreamGroupArgs &g, hipStream_t st)
     const size_t lds = SG_LDS_BYTES + SG_MAX_TILES * 16 * sizeof(int32_t);
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)stream_kernel<STAGE, DENSE>,
+        hipError_t e = hipFuncSetAttribute((const void *)stream_kernel<STAGE, DENSE, ALLTOK>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) { set_hip_error(e); return PZL_EHIP; }
         attr_set = true;
     }
-    hipLaunchKernelGGL((stream_kernel<STAGE, DENSE>), dim3((unsigned)blocks), dim3(SG_THREADS), lds, st, a);
+    hipLaunchKernelGGL((stream_kernel<STAGE, DENSE, ALLTOK>), dim3((unsigned)blocks), dim3(SG_THREADS), lds, st, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) { set_hip_error(e); return PZL_EHIP; }
     return PZL_OK;
 }
 
-int launch_stream_gateup(const StreamGroupArgs &a, bool dense, hipStream_t st)
+// kind: 0 = packed pairs (routed), 1 = dense experts that see every token (shared),
+//       2 = dense routed experts (kept unmerged)
+int launch_stream_gateup(const StreamGroupArgs &a, int kind, hipStream_t st)
 {
-    return dense ? launch<STAGE_GATEUP, true>(a, st) : launch<STAGE_GATEUP, false>(a, st);
+    if (kind == 0) return launch<STAGE_GATEUP, false, false>(a, st);
+    if (kind == 1) return launch<STAGE_GATEUP, true, true>(a, st);
+    return launch<STAGE_GATEUP, true, false>(a, st);
 }
 
-int launch_stream_down(const StreamGroupArgs &a, bool dense, hipStream_t st)
+int launch_stream_down(const StreamGroupArgs &a, int kind, hipStream_t st)
 {
-    return dense ? launch<STAGE_DOWN, true>(a, st) : launch<STAGE_DOWN, false>(a, st);
+    if (kind == 0) return launch<STAGE_DOWN, false, false>(a, st);
+    if (kind == 1) return launch<STAGE_DOWN, true, true>(a, st);
+    return launch<STAGE_DOWN, true, false>(a, st);
 }
 
 }  // namespace pzl

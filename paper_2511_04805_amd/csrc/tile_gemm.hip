@@ -68,6 +68,7 @@ struct TgArgs {
     int32_t act_is_x, act_slot_base;
     const int32_t *slot_tok;
     const int32_t *tile_q, *tile_slot0, *tile_n, *n_tiles;   // routed: device tile list
+    int32_t group_lo, group_hi;                              // routed: this launch owns groups [lo, hi)
     int32_t dense_tokens, dense_slot_base, dense_tiles, dense_tile_tokens;   // dense: uniform tiles
     uint16_t *h_out;
     int64_t h_plane_stride;
@@ -119,7 +120,9 @@ __device__ __forceinline__ void tg_swiglu_split(float g, float u, uint32_t &hi, 
 // CNT = token fragments per wave: both token-side waves take ceil(n_frags / 2) fragments, so the
 // K loop has no data-dependent branch (a guard per fragment makes the register allocator move
 // accumulators between register files); an odd tile costs one padded fragment.
-template <int STAGE, bool DENSE, int POS, int CNT>
+// DENSE: plain bf16 weights (identity decode).  ALLTOK: a shared expert, uniform token tiles
+// over every token instead of the routed tile list.
+template <int STAGE, bool DENSE, bool ALLTOK, int POS, int CNT>
 __device__ __forceinline__ void tile_body(const TgArgs &a, const uint16_t *wa, const uint16_t *wb,
                                           int slot0, int n_tok, int ntile, int ks, u32x4 *lds, int32_t *rowidx)
 {
@@ -148,7 +151,7 @@ __device__ __forceinline__ void tile_body(const TgArgs &a, const uint16_t *wa, c
     if (tid < TG_MAX_TOK) {
         int slot = slot0 + min(tid, n_tok - 1);
         int row;
-        if (a.act_is_x) row = DENSE ? (slot - a.dense_slot_base) % a.dense_tokens : a.slot_tok[slot];
+        if (a.act_is_x) row = ALLTOK ? (slot - a.dense_slot_base) % a.dense_tokens : a.slot_tok[slot];
         else            row = slot - a.act_slot_base;
         rowidx[tid] = row;
     }
@@ -294,7 +297,7 @@ __device__ __forceinline__ void tile_body(const TgArgs &a, const uint16_t *wa, c
     }
 }
 
-template <int STAGE, bool DENSE>
+template <int STAGE, bool DENSE, bool ALLTOK>
 __global__ void __launch_bounds__(TG_THREADS) __attribute__((amdgpu_waves_per_eu(TG_WPE, TG_WPE)))
 tile_kernel(TgArgs a)
 {
@@ -324,7 +327,7 @@ tile_kernel(TgArgs a)
     const int half = mt_raw % HALVES;
     const int mt = mt_raw / HALVES;
     int g, pos, slot0, n_tok;
-    if (DENSE) {
+    if (ALLTOK) {
         if (mt >= a.dense_tiles) return;
         g = mt / ((a.dense_tokens + a.dense_tile_tokens - 1) / a.dense_tile_tokens);
         int t_in = mt % ((a.dense_tokens + a.dense_tile_tokens - 1) / a.dense_tile_tokens);
@@ -335,6 +338,8 @@ tile_kernel(TgArgs a)
         if (mt >= *a.n_tiles) return;
         int q = a.tile_q[mt];
         g = q >> 1; pos = q & 1;
+        if (g < a.group_lo || g >= a.group_hi) return;       // another launch's kind of expert
+        g -= a.group_lo;
         slot0 = a.tile_slot0[mt];
         n_tok = a.tile_n[mt];
     }
@@ -352,7 +357,7 @@ tile_kernel(TgArgs a)
     const uint16_t *wa = a.w_a[g];
     const uint16_t *wb = (STAGE == TSTAGE_GATEUP) ? a.w_b[g] : wa;
     const int cnt = (((n_tok + 15) >> 4) + 1) >> 1;          // 1..8 fragments per wave
-#define PZL_TILE(P, C) tile_body<STAGE, DENSE, P, C>(a, wa, wb, slot0, n_tok, ntile, ks, lds, rowidx)
+#define PZL_TILE(P, C) tile_body<STAGE, DENSE, ALLTOK, P, C>(a, wa, wb, slot0, n_tok, ntile, ks, lds, rowidx)
 #define PZL_TILE_CNT(P)                                                         \
     switch (cnt) {                                                              \
         case 1: PZL_TILE(P, 1); break; case 2: PZL_TILE(P, 2); break;           \
@@ -365,7 +370,7 @@ tile_kernel(TgArgs a)
 #undef PZL_TILE
 }
 
-template <int STAGE, bool DENSE>
+template <int STAGE, bool DENSE, bool ALLTOK>
 static int launch(const TileGemmArgs &t, hipStream_t st)
 {
     if (t.max_mtiles <= 0) return PZL_OK;
@@ -375,6 +380,7 @@ static int launch(const TileGemmArgs &t, hipStream_t st)
     a.act = t.act; a.act_plane_stride = t.act_plane_stride; a.act_is_x = t.act_is_x;
     a.act_slot_base = t.act_slot_base; a.slot_tok = t.slot_tok;
     a.tile_q = t.tile_q; a.tile_slot0 = t.tile_slot0; a.tile_n = t.tile_n; a.n_tiles = t.n_tiles;
+    a.group_lo = t.group_lo; a.group_hi = t.group_hi;
     a.dense_tokens = t.dense_tokens; a.dense_slot_base = t.dense_slot_base;
     a.dense_tiles = t.dense_tiles; a.dense_tile_tokens = t.dense_tile_tokens;
     a.h_out = t.h_out; a.h_plane_stride = t.h_plane_stride; a.h_slot_base = t.h_slot_base;
@@ -389,25 +395,31 @@ static int launch(const TileGemmArgs &t, hipStream_t st)
     if (blocks > 0x7FFFFFFFLL) return PZL_EINVAL;
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)tile_kernel<STAGE, DENSE>,
+        hipError_t e = hipFuncSetAttribute((const void *)tile_kernel<STAGE, DENSE, ALLTOK>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, TG_LDS_BYTES);
         if (e != hipSuccess) { set_hip_error(e); return PZL_EHIP; }
         attr_set = true;
     }
-    hipLaunchKernelGGL((tile_kernel<STAGE, DENSE>), dim3((unsigned)blocks), dim3(TG_THREADS), TG_LDS_BYTES, st, a);
+    hipLaunchKernelGGL((tile_kernel<STAGE, DENSE, ALLTOK>), dim3((unsigned)blocks), dim3(TG_THREADS), TG_LDS_BYTES, st, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) { set_hip_error(e); return PZL_EHIP; }
     return PZL_OK;
 }
 
-int launch_tile_gateup(const TileGemmArgs &a, bool dense, hipStream_t st)
+// kind: 0 = packed pairs (routed), 1 = dense experts that see every token (shared),
+//       2 = dense routed experts (kept unmerged)
+int launch_tile_gateup(const TileGemmArgs &a, int kind, hipStream_t st)
 {
-    return dense ? launch<TSTAGE_GATEUP, true>(a, st) : launch<TSTAGE_GATEUP, false>(a, st);
+    if (kind == 0) return launch<TSTAGE_GATEUP, false, false>(a, st);
+    if (kind == 1) return launch<TSTAGE_GATEUP, true, true>(a, st);
+    return launch<TSTAGE_GATEUP, true, false>(a, st);
 }
 
-int launch_tile_down(const TileGemmArgs &a, bool dense, hipStream_t st)
+int launch_tile_down(const TileGemmArgs &a, int kind, hipStream_t st)
 {
-    return dense ? launch<TSTAGE_DOWN, true>(a, st) : launch<TSTAGE_DOWN, false>(a, st);
+    if (kind == 0) return launch<TSTAGE_DOWN, false, false>(a, st);
+    if (kind == 1) return launch<TSTAGE_DOWN, true, true>(a, st);
+    return launch<TSTAGE_DOWN, true, false>(a, st);
 }
 
 }  // namespace pzl

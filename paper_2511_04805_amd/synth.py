@@ -31,10 +31,11 @@ class LayerConfig:
     seed: int = 1000
     sigma: float = 0.02
     mask_density: float = 0.5
+    n_unmerged: int = 0                # routed experts kept dense (25 % compression leaves half of them)
 
     @property
     def n_pairs(self):
-        return self.n_experts // 2
+        return (self.n_experts - self.n_unmerged) // 2
 
 
 CONFIGS = {
@@ -109,6 +110,14 @@ def shared_matrix(cfg, s, which):
     return _np_bits(shared_matrix_t(cfg, s, which))
 
 
+def unmerged_matrix_t(cfg, j, which, device="cpu"):
+    """Dense bf16 bits (int16 view) of one matrix of routed expert j that is kept unmerged."""
+    rows, cols = matrix_shape(cfg, which)
+    g = _gen(cfg, device, 8, j, which)
+    w = torch.randn(rows * cols, generator=g, device=device) * cfg.sigma
+    return w.to(torch.bfloat16).view(torch.int16).reshape(rows, cols)
+
+
 def unmerged_pair_t(cfg, pair, which, shape=None, device="cpu"):
     """Inputs of the offline merge for one matrix of one expert pair: two dense experts drawn as
     signed N(0, sigma) bf16 (int16 views) and one positive activation-norm vector per expert
@@ -163,7 +172,8 @@ def routing(cfg, T):
 
 def expert_map(cfg, mode="adjacent"):
     """expert -> (pair, position).  adjacent: (e//2, e%2); random: seeded random pairing
-    (the paper's default grouping is random, Sec. 3.2 "Pair-wise Experts Grouping")."""
+    (the paper's default grouping is random, Sec. 3.2 "Pair-wise Experts Grouping").
+    Experts kept unmerged get pair = -1 - j (j-th dense routed expert)."""
     E = cfg.n_experts
     if mode == "adjacent":
         order = np.arange(E)
@@ -173,6 +183,11 @@ def expert_map(cfg, mode="adjacent"):
     pos = np.empty(E, dtype=np.uint8)
     pair[order] = np.arange(E) // 2
     pos[order] = np.arange(E) % 2
+    # the last n_unmerged experts of the order stay dense: pair = -1 - j, position 0
+    D = cfg.n_unmerged
+    if D:
+        pair[order[E - D:]] = -1 - np.arange(D)
+        pos[order[E - D:]] = 0
     return pair, pos
 
 

@@ -80,11 +80,17 @@ class Case:
             mats = [synth.shared_matrix_t(cfg, s, w, device=gen_device) for w in W3]
             self.shared_cpu.append(tuple(synth._np_bits(m) for m in mats))
             shared_gpu.append(tuple(binding.pzl_tile_dense(m.to(device)) for m in mats) + (fs,))
+        self.dense_cpu, dense_gpu = [], []
+        for j in range(cfg.n_unmerged):                       # routed experts kept unmerged
+            mats = [synth.unmerged_matrix_t(cfg, j, w, device=gen_device) for w in W3]
+            self.dense_cpu.append(tuple(synth._np_bits(m) for m in mats))
+            dense_gpu.append(tuple(binding.pzl_tile_dense(m.to(device)) for m in mats))
         P = cfg.n_pairs
         self.layer = binding.Layer(cfg.d_model, cfg.d_ffn, self.emap[0], self.emap[1],
                                    [self.packed_gpu[p, synth.GATE] for p in range(P)],
                                    [self.packed_gpu[p, synth.UP] for p in range(P)],
-                                   [self.packed_gpu[p, synth.DOWN] for p in range(P)], shared=shared_gpu)
+                                   [self.packed_gpu[p, synth.DOWN] for p in range(P)], shared=shared_gpu,
+                                   dense=dense_gpu)
         assert int(self.n_bad.item()) == 0
         self.device = device
 
@@ -101,4 +107,4 @@ class Case:
                                    [self.packed_cpu[p, synth.GATE] for p in range(P)],
                                    [self.packed_cpu[p, synth.UP] for p in range(P)],
                                    [self.packed_cpu[p, synth.DOWN] for p in range(P)],
-                                   shared=self.shared_cpu, **kw)
+                                   shared=self.shared_cpu, dense=self.dense_cpu, **kw)

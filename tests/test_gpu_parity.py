@@ -236,3 +236,28 @@ def test_merged_layer_end_to_end(oracle, binding):
     assert np.all((m0 | m1) == 1) and abs(float(m0.mean()) - 0.742) < 0.01
     for T in (5, 40, 500):                                           # streaming and tiled kernels
         check(case, T, "merged-layer")
+
+
+# 25 % compression (Sec. 4.1): only half of the routed experts are merged, the rest stay dense.
+MIXED = synth.LayerConfig("mixed", 8, 256, 384, 2, (64,), shared_d_ffn=(128,), seed=61, n_unmerged=4)
+
+
+@pytest.fixture(scope="module")
+def mixed_case(oracle, binding):
+    assert MIXED.n_pairs == 2
+    return Case(MIXED, oracle, binding, emap_mode="random")
+
+
+@pytest.mark.parametrize("T", [1, 9, 64, 150, 800, 1100])
+def test_mixed_layer_unmerged_experts(mixed_case, T):
+    """Packed pairs and unmerged dense experts in one layer, on the streaming kernels (T <= 150)
+    and on the tiled kernels (T >= 800)."""
+    check(mixed_case, T, "mixed")
+
+
+def test_all_experts_unmerged(oracle, binding):
+    """No pair at all: every routed expert dense (the degenerate end of the compression range)."""
+    cfg = synth.LayerConfig("unmerged", 3, 128, 192, 2, (40,), seed=67, n_unmerged=3)
+    case = Case(cfg, oracle, binding)
+    for T in (3, 40, 400):
+        check(case, T, "all-unmerged")

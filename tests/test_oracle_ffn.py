@@ -195,3 +195,38 @@ def test_staged_variant_is_close(oracle):
     ys, _ = run_oracle(oracle, cfg, packed, shared, x, ids, w, emap, stage_h_bf16=True)
     rms = np.sqrt((y ** 2).mean())
     assert 0 < np.abs(ys - y).max() < 2.0 ** -7 * rms * 4
+
+
+def test_unmerged_routed_experts(oracle):
+    """25 % compression: some routed experts stay dense.  Brute force with plain matmuls."""
+    cfg = synth.LayerConfig("mixed", 6, 64, 96, 2, (8,), seed=17, n_unmerged=2)
+    assert cfg.n_pairs == 2
+    planes, packed = {}, {}
+    for p in range(cfg.n_pairs):
+        for which in (synth.GATE, synth.UP, synth.DOWN):
+            pl = synth.pair_matrix(cfg, p, which)
+            planes[p, which] = pl
+            packed[p, which] = oracle.pack(pl["merged"], pl["mask0"], pl["mask1"], pl["sign0"], pl["sign1"])[0]
+    dense = [tuple(synth._np_bits(synth.unmerged_matrix_t(cfg, j, w)) for w in (synth.GATE, synth.UP, synth.DOWN))
+             for j in range(cfg.n_unmerged)]
+    emap = synth.expert_map(cfg, "random")
+    assert sorted(int(p) for p in emap[0] if p < 0) == [-2, -1]
+    x = synth.tokens(cfg, 8)
+    ids, w = synth.routing(cfg, 8)
+    ids[0] = [np.where(emap[0] == -1)[0][0], np.where(emap[0] == -2)[0][0]]     # make sure both are hit
+    P = cfg.n_pairs
+    y64, _ = oracle.moe_ffn(x, ids, w, emap[0], emap[1], [packed[p, synth.GATE] for p in range(P)],
+                            [packed[p, synth.UP] for p in range(P)], [packed[p, synth.DOWN] for p in range(P)],
+                            dense=dense)
+    xs = bits_to_f64(x)
+    ref = np.zeros_like(y64)
+    silu = lambda g: g / (1.0 + np.exp(-g))
+    for t in range(8):
+        for j in range(2):
+            e = int(ids[t, j]); p = int(emap[0][e])
+            if p >= 0:
+                Wg, Wu, Wd = (eq6_weights(planes[p, wh], int(emap[1][e])) for wh in (synth.GATE, synth.UP, synth.DOWN))
+            else:
+                Wg, Wu, Wd = (bits_to_f64(m) for m in dense[-1 - p])
+            ref[t] += float(w[t, j]) * (Wd @ (silu(Wg @ xs[t]) * (Wu @ xs[t])))
+    assert_close(y64, ref)
