@@ -79,7 +79,10 @@ struct StreamGroupArgs {
     int32_t ksplit;
 };
 int stream_row_groups(int rows, bool down_stage);   // row groups (workgroup units) along the output rows
-constexpr int STREAM_RESIDENT_WGS = 512;             // workgroups the chip holds at once (256 CUs x 2)
+#ifndef SG_WAVES_N
+#define SG_WAVES_N 8
+#endif
+constexpr int STREAM_RESIDENT_WGS = 2048 / SG_WAVES_N;             // workgroups the chip holds at once (256 CUs x 2)
 // kind: 0 packed pairs, 1 dense experts seeing every token (shared), 2 dense routed experts
 constexpr int KIND_PACKED = 0, KIND_SHARED = 1, KIND_UNMERGED = 2;
 int launch_stream_gateup(const StreamGroupArgs &a, int kind, hipStream_t st);
