@@ -172,6 +172,20 @@ int pzl_moe_ffn(const pzl_layer *layer, const uint16_t *x, const int32_t *topk_i
                 void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * router_topk — the step in front of pzl_moe_ffn, so that a whole MoE block runs on the device.
+ * The paper keeps the router as it is in the model ("the other modules unchanged", Sec. 4.1); this
+ * is the usual linear router: logits = x W_r^T, the k largest logits per token in descending order
+ * (ties: lower expert index first), weights = softmax over those k logits.
+ * Each logit is one fp32 fused-multiply-add chain over the channels in order, which makes the
+ * chosen experts exactly reproducible.
+ *   x         [T, d_model] bf16 bits;  w_router  [n_experts, d_model] bf16 bits, row-major
+ *   topk_ids  [T, k] int32 out;        topk_w    [T, k] fp32 out
+ * d_model % 8 == 0, n_experts <= 256, k <= min(n_experts, 64).
+ */
+int pzl_router_topk(const uint16_t *x, const uint16_t *w_router, int32_t T, int32_t d_model,
+                    int32_t n_experts, int32_t k, int32_t *topk_ids, float *topk_w, void *stream);
+
+/*
  * Measurement variant of pzl_moe_ffn: the same launches on the same stream, and in addition the
  * caller's hipEvent_t handles are recorded around each stage, so that a benchmark can time one
  * kernel of the path with events on the stream the kernel really runs on.

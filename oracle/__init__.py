@@ -120,6 +120,27 @@ def merge(wi, wj, norm_i, norm_j, tau):
             "sign1": planes[3], "n_similar": int(n_sim)}
 
 
+def router_topk(x, w_router, k):
+    """Linear router + top-k + softmax over the selected logits.  x [T,d], w_router [E,d] bf16 bits.
+    Returns (ids int32 [T,k], weights float32 [T,k], logits float32 [T,E])."""
+    x, wr = _u16(x), _u16(w_router)
+    T, d = x.shape
+    E = wr.shape[0]
+    assert wr.shape == (E, d) and 1 <= k <= min(E, 64)
+    ids = np.empty((T, k), dtype=np.int32)
+    wts = np.empty((T, k), dtype=np.float32)
+    logits = np.empty((T, E), dtype=np.float32)
+    lib = _load()
+    lib.orc_router_topk.restype = ctypes.c_int
+    rc = lib.orc_router_topk(ctypes.c_int(T), ctypes.c_int(d), ctypes.c_int(E), ctypes.c_int(k),
+                             ctypes.c_void_p(x.ctypes.data), ctypes.c_void_p(wr.ctypes.data),
+                             ctypes.c_void_p(ids.ctypes.data), ctypes.c_void_p(wts.ctypes.data),
+                             ctypes.c_void_p(logits.ctypes.data))
+    if rc != 0:
+        raise ValueError("oracle router_topk: bad k")
+    return ids, wts, logits
+
+
 def moe_ffn(x, ids, w, expert_pair, expert_pos, gate, up, down,
             shared=(), stage_h_bf16=False, dense=()):
     """Routed SwiGLU FFN over Eq. 6-decoded experts, fp64.

@@ -33,6 +33,13 @@
  * Unpinned (paper silent, no second source): the three readings above that
  * concern exponents < 112, zero, and exponents > 143.
  *
+ * orc_router_topk (the router in front of the experts; not in the paper, which keeps
+ * "the other modules unchanged", Sec. 4.1): a textbook linear router, top-k, softmax over
+ * the selected logits.  The logits decide integers (which experts), so they are computed
+ * in fp32 as one fused multiply-add chain over the channels in order, exactly as the GPU
+ * kernel does; ties go to the lower expert index.  Pinned by brute force against numpy on
+ * inputs whose products and sums are exact in fp32, and by permutation / tie cases.
+ *
  * Arithmetic: integer for pack/unpack; fp64 everywhere in the FFN; a single
  * round-to-nearest-even to bf16 at the very end.
  *
@@ -297,4 +304,45 @@ int64_t orc_merge(const uint16_t *wi, const uint16_t *wj, const float *norm_i, c
         }
     }
     return n_sim;
+}
+
+/* ---------- router: logits, top-k, softmax over the selected logits ---------- */
+
+/*
+ * x [T,d] bf16 bits, w_router [E,d] bf16 bits (row-major).  logits[t,e] = sum_c x[t,c]*w[e,c]
+ * as acc = fmaf(x, w, acc) for c = 0..d-1 in fp32.  ids[t,0..k) are the k largest logits in
+ * descending order (ties: lower expert first); weights[t,:] = softmax of those k logits,
+ * computed in fp64 from the fp32 logits and returned as fp32.  Optionally returns the logits.
+ */
+int orc_router_topk(int T, int d, int E, int k, const uint16_t *x, const uint16_t *w_router,
+                    int32_t *ids, float *weights, float *logits_out)
+{
+    if (k > E || k < 1) return -1;
+    float *logit = malloc(sizeof(float) * E);
+    char *taken = malloc(E);
+    if (!logit || !taken) { free(logit); free(taken); return -1; }
+    for (int t = 0; t < T; ++t) {
+        for (int e = 0; e < E; ++e) {
+            float acc = 0.0f;
+            for (int c = 0; c < d; ++c)
+                acc = fmaf(bf16_to_float(x[(int64_t)t * d + c]), bf16_to_float(w_router[(int64_t)e * d + c]), acc);
+            logit[e] = acc;
+            if (logits_out) logits_out[(int64_t)t * E + e] = acc;
+        }
+        memset(taken, 0, E);
+        double sel[64];
+        for (int j = 0; j < k; ++j) {
+            int best = -1;
+            for (int e = 0; e < E; ++e)
+                if (!taken[e] && (best < 0 || logit[e] > logit[best])) best = e;   /* strict >: lower index wins ties */
+            taken[best] = 1;
+            ids[(int64_t)t * k + j] = best;
+            if (j < 64) sel[j] = (double)logit[best];
+        }
+        double mx = sel[0], sum = 0.0;
+        for (int j = 0; j < k && j < 64; ++j) sum += exp(sel[j] - mx);
+        for (int j = 0; j < k && j < 64; ++j) weights[(int64_t)t * k + j] = (float)(exp(sel[j] - mx) / sum);
+    }
+    free(logit); free(taken);
+    return 0;
 }

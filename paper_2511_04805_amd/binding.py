@@ -17,7 +17,7 @@ _lib = None
 PZL_OK, PZL_EINVAL, PZL_ENOSPC, PZL_EHIP, PZL_ENOMEM = 0, -1, -2, -3, -4
 
 EXPORTS = ("pzl_abi_version", "pzl_strerror", "pzl_last_hip_error", "pzl_packed_bytes", "pzl_pack",
-           "pzl_unpack", "pzl_tile_dense", "pzl_merge_pack", "pzl_layer_create", "pzl_layer_destroy",
+           "pzl_unpack", "pzl_tile_dense", "pzl_merge_pack", "pzl_router_topk", "pzl_layer_create", "pzl_layer_destroy",
            "pzl_moe_ffn_workspace_bytes", "pzl_moe_ffn", "pzl_moe_ffn_staged")
 
 STAGES = ("route", "gateup", "down", "shared", "combine")
@@ -67,6 +67,8 @@ def load():
         lib.pzl_tile_dense.argtypes = [vp, i64, i64, vp, vp]
         lib.pzl_merge_pack.restype = ctypes.c_int
         lib.pzl_merge_pack.argtypes = [vp, vp, vp, vp, i64, i64, ctypes.c_float, vp, vp, vp, vp]
+        lib.pzl_router_topk.restype = ctypes.c_int
+        lib.pzl_router_topk.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp, vp]
         lib.pzl_layer_create.restype = ctypes.c_int
         lib.pzl_layer_create.argtypes = [ctypes.POINTER(_LayerDesc), ctypes.POINTER(vp)]
         lib.pzl_layer_destroy.restype = None
@@ -155,6 +157,18 @@ def pzl_merge_pack(w_i, w_j, norm_i, norm_j, tau_sim, out=None, n_similar=None, 
                                opt(n_similar, "n_similar"), opt(n_out_of_range, "n_out_of_range"), _stream())
     _check(rc, "pzl_merge_pack")
     return out
+
+
+def pzl_router_topk(x, w_router, k):
+    """Linear router + top-k + softmax over the selected logits -> (ids int32 [T,k], weights fp32 [T,k])."""
+    T, d = x.shape
+    E = w_router.shape[0]
+    ids = torch.empty(T, k, dtype=torch.int32, device=x.device)
+    w = torch.empty(T, k, dtype=torch.float32, device=x.device)
+    rc = load().pzl_router_topk(_dev(x, _BITS16, "x"), _dev(w_router, _BITS16, "w_router"), T, d, E, k,
+                                _dev(ids, (torch.int32,), "ids"), _dev(w, (torch.float32,), "w"), _stream())
+    _check(rc, "pzl_router_topk")
+    return ids, w
 
 
 def _ptr_table(tensors):

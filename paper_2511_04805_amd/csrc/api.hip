@@ -153,6 +153,12 @@ int pzl_merge_pack(const uint16_t *w_i, const uint16_t *w_j, const float *norm_i
                              n_out_of_range, (hipStream_t)stream);
 }
 
+int pzl_router_topk(const uint16_t *x, const uint16_t *w_router, int32_t T, int32_t d_model, int32_t n_experts,
+                    int32_t k, int32_t *topk_ids, float *topk_w, void *stream)
+{
+    return launch_router_topk(x, w_router, T, d_model, n_experts, k, topk_ids, topk_w, (hipStream_t)stream);
+}
+
 int pzl_layer_create(const pzl_layer_desc *desc, pzl_layer **out)
 {
     if (!desc || !out) return PZL_EINVAL;

@@ -49,6 +49,8 @@ int launch_merge_pack(const uint16_t *wi, const uint16_t *wj, const float *norm_
 // route.hip
 int launch_route(const int32_t *ids, int32_t n_flat, int32_t k, int32_t n_experts, int32_t n_slots_q, const int32_t *q_of_expert,
                  RouteTables rt, hipStream_t st);
+int launch_router_topk(const uint16_t *x, const uint16_t *w_router, int32_t T, int32_t d, int32_t E, int32_t k,
+                       int32_t *ids_out, float *w_out, hipStream_t st);
 int launch_combine(const float *opart, int32_t ksplit, int32_t ksplit_shared, int64_t ks_stride, const RouteTables &rt,
                    const float *topk_w, int32_t T, int32_t k, int32_t d, int32_t n_shared,
                    uint16_t *y, hipStream_t st);

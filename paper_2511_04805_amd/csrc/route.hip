@@ -131,6 +131,70 @@ combine_kernel(const float *__restrict__ opart, int32_t ksplit, int32_t ksplit_s
     *(u32x2 *)(y + (int64_t)t * d + c) = o;
 }
 
+// Router in front of the experts (not in the paper, which leaves the rest of the model unchanged,
+// Sec. 4.1): logits = x W_r^T, top-k, softmax over the selected logits.  One workgroup per token;
+// thread e owns expert e and accumulates its logit as ONE fused-multiply-add chain over the
+// channels in order, so the logits, and with them the chosen experts, are reproducible bit for bit
+// by a CPU that does the same.  Ties go to the lower expert index.
+constexpr int ROUTER_MAX_E = 256;
+constexpr int ROUTER_MAX_K = 64;
+
+__global__ void __launch_bounds__(ROUTER_MAX_E)
+router_topk_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ w_router, int32_t d,
+                   int32_t E, int32_t k, int32_t *__restrict__ ids_out, float *__restrict__ w_out)
+{
+    __shared__ float logit[ROUTER_MAX_E];
+    __shared__ float sel[ROUTER_MAX_K];
+    const int t = blockIdx.x, e = threadIdx.x;
+    if (e < E) {
+        const u32x4 *xr = (const u32x4 *)(x + (int64_t)t * d);
+        const u32x4 *wr = (const u32x4 *)(w_router + (int64_t)e * d);
+        float acc = 0.0f;
+        for (int c = 0; c < d / 8; ++c) {
+            u32x4 xv = xr[c], wv = wr[c];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                acc = __fmaf_rn(__uint_as_float(xv[i] << 16), __uint_as_float(wv[i] << 16), acc);
+                acc = __fmaf_rn(__uint_as_float(xv[i] & 0xFFFF0000u), __uint_as_float(wv[i] & 0xFFFF0000u), acc);
+            }
+        }
+        logit[e] = acc;
+    }
+    __syncthreads();
+    if (e == 0) {
+        // k selection passes; a taken expert is marked by clearing its slot to -inf after the
+        // pass has recorded it (a NaN logit never wins, as on the CPU side)
+        for (int j = 0; j < k; ++j) {
+            int best = -1;
+            float bv = 0.0f;
+            for (int i = 0; i < E; ++i) {
+                float v = logit[i];
+                bool free_slot = !(__float_as_uint(v) == 0xFF800001u);      // marker, see below
+                if (free_slot && (best < 0 || v > bv)) { best = i; bv = v; }
+            }
+            ids_out[(int64_t)t * k + j] = best;
+            sel[j] = bv;
+            logit[best] = __uint_as_float(0xFF800001u);                     // a NaN pattern no fma chain of finite bf16 yields
+        }
+        float mx = sel[0], sum = 0.0f;
+        for (int j = 0; j < k; ++j) sum += expf(sel[j] - mx);
+        for (int j = 0; j < k; ++j) w_out[(int64_t)t * k + j] = expf(sel[j] - mx) / sum;
+    }
+}
+
+int launch_router_topk(const uint16_t *x, const uint16_t *w_router, int32_t T, int32_t d, int32_t E, int32_t k,
+                       int32_t *ids_out, float *w_out, hipStream_t st)
+{
+    if (T < 0 || d <= 0 || d % 8 || E < 1 || E > ROUTER_MAX_E || k < 1 || k > E || k > ROUTER_MAX_K) return PZL_EINVAL;
+    if (T == 0) return PZL_OK;
+    if (!x || !w_router || !ids_out || !w_out) return PZL_EINVAL;
+    hipLaunchKernelGGL(router_topk_kernel, dim3((unsigned)T), dim3(ROUTER_MAX_E), 0, st, x, w_router, d, E, k,
+                       ids_out, w_out);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) { set_hip_error(e); return PZL_EHIP; }
+    return PZL_OK;
+}
+
 int launch_route(const int32_t *ids, int32_t n_flat, int32_t k, int32_t n_experts, int32_t n_slots_q,
                  const int32_t *q_of_expert, RouteTables rt, hipStream_t st)
 {

@@ -261,3 +261,23 @@ def test_all_experts_unmerged(oracle, binding):
     case = Case(cfg, oracle, binding)
     for T in (3, 40, 400):
         check(case, T, "all-unmerged")
+
+
+@pytest.mark.parametrize("T,d,E,k", [(1, 4096, 8, 2), (64, 4096, 8, 2), (300, 2048, 60, 4), (2048, 2048, 64, 6)])
+def test_router_topk(oracle, binding, T, d, E, k):
+    """Router logits as one fp32 fma chain: expert ids must equal the oracle's exactly."""
+    say("router T=%d d=%d E=%d k=%d" % (T, d, E, k))
+    g = torch.Generator().manual_seed(T + E)
+    x = torch.randn(T, d, generator=g).to(torch.bfloat16)
+    wr = (torch.randn(E, d, generator=g) * 0.05).to(torch.bfloat16)
+    if T > 1:
+        x[1] = x[0]                                    # duplicate token: identical decision
+    wr[E - 1] = wr[0]                                  # duplicate expert: a tie on every token
+    ids, w = binding.pzl_router_topk(x.cuda(), wr.cuda(), k)
+    torch.cuda.synchronize()
+    ids_ref, w_ref, _ = oracle.router_topk(x.view(torch.int16).numpy().view(np.uint16),
+                                           wr.view(torch.int16).numpy().view(np.uint16), k)
+    assert np.array_equal(ids.cpu().numpy(), ids_ref)
+    assert np.allclose(w.cpu().numpy(), w_ref, rtol=2e-6, atol=1e-9)
+    # the router's output feeds moe_ffn as is
+    assert ids.dtype == torch.int32 and w.dtype == torch.float32 and ids.shape == (T, k)
