@@ -56,6 +56,7 @@ struct SgArgs {
     const int32_t *cnt, *off, *slot_tok;
     int32_t group_base;          // routed groups: first group index (q = 2 * (group_base + g) + pos)
     int32_t dense_tokens, dense_slot_base;
+    int32_t n_passes;            // ALLTOK groups: token passes, each taken by its own workgroup
     uint16_t *h_out;
     int64_t h_plane_stride;
     int32_t h_slot_base;
@@ -289,6 +290,11 @@ stream_kernel(SgArgs a)
     const int row_groups = (row_tiles + SG_WAVES * RT_PER_WAVE - 1) / (SG_WAVES * RT_PER_WAVE);
     const int rg_blocks = (row_groups + a.rg_per_wg - 1) / a.rg_per_wg;
     int b = blockIdx.x;
+    // A shared expert has few row groups (few workgroups) but sees every token: its token passes
+    // go to different workgroups (pass index fastest, so the workgroups that read the same
+    // weights run at the same time and share them through L2 / the memory-side cache).
+    const int my_pass = ALLTOK ? b % a.n_passes : 0;
+    if (ALLTOK) b /= a.n_passes;
     const int ks = b % a.ksplit; b /= a.ksplit;
     const int rgb = b % rg_blocks;
     const int g = b / rg_blocks;
@@ -319,7 +325,7 @@ stream_kernel(SgArgs a)
     const bool active0 = rt0 < row_tiles, active1 = rt1 < row_tiles;
     rt0 = min(rt0, row_tiles - 1);      // inactive streams re-read a valid tile and store nothing
     rt1 = min(rt1, row_tiles - 1);
-    for (int t0 = 0, t1 = 0; t0 < tiles0 || t1 < tiles1; t0 += PT, t1 += PT) {
+    for (int t0 = my_pass * PT, t1 = 0; t0 < tiles0 || t1 < tiles1; t0 += PT, t1 += PT) {
         int c0 = min(PT, max(tiles0 - t0, 0));
         int c1 = min(PT, max(tiles1 - t1, 0));
 #define PZL_PASS(A, B)                                                                              \
@@ -345,6 +351,7 @@ stream_kernel(SgArgs a)
             }
         }
 #undef PZL_PASS
+        if (ALLTOK) break;           // the other passes belong to other workgroups
     }
     }
 }
@@ -372,13 +379,16 @@ static int launch(const StreamGroupArgs &g, hipStream_t st)
     // larger than that runs a second, partly empty round; giving each workgroup several row
     // groups instead keeps the launch to one round.
     const int row_groups = stream_row_groups(g.rows, STAGE == STAGE_DOWN);
-    const int64_t units = (int64_t)(g.groups_touched_max > 0 ? g.groups_touched_max : g.n_groups) * row_groups * g.ksplit;
+    const int pass_tokens = SG_MAX_TILES * 16;
+    a.n_passes = ALLTOK ? (g.dense_tokens + pass_tokens - 1) / pass_tokens : 1;
+    if (a.n_passes < 1) a.n_passes = 1;
+    const int64_t units = (int64_t)(g.groups_touched_max > 0 ? g.groups_touched_max : g.n_groups) * row_groups * g.ksplit * a.n_passes;
     int rg_per_wg = (int)((units + SG_RESIDENT_WGS - 1) / SG_RESIDENT_WGS);
     if (rg_per_wg < 1) rg_per_wg = 1;
     if (rg_per_wg > 4) rg_per_wg = 1;            // many rounds anyway: keep the units small
     if (rg_per_wg > row_groups) rg_per_wg = row_groups;
     a.rg_per_wg = rg_per_wg;
-    const int64_t blocks = (int64_t)g.n_groups * ((row_groups + rg_per_wg - 1) / rg_per_wg) * g.ksplit;
+    const int64_t blocks = (int64_t)g.n_groups * ((row_groups + rg_per_wg - 1) / rg_per_wg) * g.ksplit * a.n_passes;
     if (blocks > 0x7FFFFFFFLL) return PZL_EINVAL;
     const size_t lds = SG_LDS_BYTES + SG_MAX_TILES * 16 * sizeof(int32_t);
     static bool attr_set = false;
