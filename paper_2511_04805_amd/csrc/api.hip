@@ -35,8 +35,14 @@ struct pzl_layer {
 
 namespace pzl {
 
-constexpr int TILED_MIN_TOKENS_PER_EXPERT = 96;   // average tokens per expert from which the tiled path pays
-constexpr int TILED_MIN_TOKENS_SHARED = 1024;     // a dense expert sees every token but has few row tiles: the tiled path needs >= 4 token tiles
+#ifndef PZL_TILED_MIN_TPE
+#define PZL_TILED_MIN_TPE 96
+#endif
+#ifndef PZL_TILED_MIN_SHARED
+#define PZL_TILED_MIN_SHARED 1024
+#endif
+constexpr int TILED_MIN_TOKENS_PER_EXPERT = PZL_TILED_MIN_TPE;   // average tokens per expert from which the tiled path pays
+constexpr int TILED_MIN_TOKENS_SHARED = PZL_TILED_MIN_SHARED;     // a dense expert sees every token but has few row tiles: the tiled path needs >= 4 token tiles
 constexpr int MAX_KSPLIT = 8;   // upper bound on the k-splits of the down stage (sizes the workspace)
 
 struct WorkspaceLayout {
@@ -313,11 +319,14 @@ int pzl_moe_ffn_staged(const pzl_layer *L, const uint16_t *x, const int32_t *top
     const int groups_max = (int)((int64_t)N < routed_groups ? N : routed_groups);   // groups that can have tokens
     const int ksplit = tiled ? choose_tile_ksplit(N / TILE_MAX_TOKENS + L->n_experts / 2, L->d_model, L->d_ffn)
                              : choose_ksplit(groups_max > 0 ? groups_max : 1, L->d_model);
-    int ksplit_shared = choose_ksplit(1, L->d_model);
+    // one k-split count for all shared experts (the combine step sums that many partials); sized
+    // for the usual case, all of them of one width and hence in one launch per stage
+    const int ns = L->n_shared > 0 ? L->n_shared : 1;
+    int ksplit_shared = choose_ksplit(ns * ((T + 63) / 64), L->d_model);
     if (tiled_shared) {
         ksplit_shared = MAX_KSPLIT;
         for (int s = 0; s < L->n_shared; ++s) {
-            int ks = choose_tile_ksplit((T + TILE_MAX_TOKENS - 1) / TILE_MAX_TOKENS, L->d_model, L->shared_f[s]);
+            int ks = choose_tile_ksplit((int64_t)ns * ((T + TILE_MAX_TOKENS - 1) / TILE_MAX_TOKENS), L->d_model, L->shared_f[s]);
             if (ks < ksplit_shared) ksplit_shared = ks;
         }
     }
@@ -385,18 +394,22 @@ int pzl_moe_ffn_staged(const pzl_layer *L, const uint16_t *x, const int32_t *top
     }
 
     if ((rc = mark(PZL_STAGE_SHARED, 0))) return rc;
+    // Shared experts of equal width go into one launch per stage (group index = expert), so that
+    // the launch has enough workgroups; their H rows sit back to back, slot = N + s*T + t.
     size_t h_off = w.h_shared;
-    for (int s = 0; s < L->n_shared; ++s) {
+    for (int s = 0; s < L->n_shared;) {
+        int nb = 1;
+        while (s + nb < L->n_shared && L->shared_f[s + nb] == L->shared_f[s]) ++nb;
         uint16_t *h_s = (uint16_t *)(ws + h_off);
-        h_off += w.h_shared_each(L, T, s);
+        for (int j = 0; j < nb; ++j) h_off += w.h_shared_each(L, T, s + j);
         const int32_t slot_base = N + s * T;
-        const int64_t hs_plane = (int64_t)T * L->shared_f[s];
+        const int64_t hs_plane = (int64_t)nb * T * L->shared_f[s];
         if (tiled_shared) {
             TileGemmArgs a = {};
             const int parts = (T + TILE_MAX_TOKENS - 1) / TILE_MAX_TOKENS;
             a.dense_tokens = T; a.dense_slot_base = slot_base;
             a.dense_tile_tokens = ((T + parts - 1) / parts + 15) & ~15;
-            a.dense_tiles = (T + a.dense_tile_tokens - 1) / a.dense_tile_tokens;
+            a.dense_tiles = nb * ((T + a.dense_tile_tokens - 1) / a.dense_tile_tokens);
             a.max_mtiles = a.dense_tiles;
             a.w_a = L->d_sgate + s; a.w_b = L->d_sup + s;
             a.rows = L->shared_f[s]; a.kdim = L->d_model;
@@ -410,10 +423,11 @@ int pzl_moe_ffn_staged(const pzl_layer *L, const uint16_t *x, const int32_t *top
             a.h_out = nullptr; a.o_out = opart; a.o_ks_stride = w.o_ks_stride; a.ksplit = ksplit_shared;
             rc = launch_tile_down(a, KIND_SHARED, st);
             if (rc) return rc;
+            s += nb;
             continue;
         }
         StreamGroupArgs a = {};
-        a.n_groups = 1;
+        a.n_groups = nb;
         a.dense_tokens = T; a.dense_slot_base = slot_base;
         a.w_a = L->d_sgate + s; a.w_b = L->d_sup + s;
         a.rows = L->shared_f[s]; a.kdim = L->d_model; a.ksplit = 1;
@@ -427,6 +441,7 @@ int pzl_moe_ffn_staged(const pzl_layer *L, const uint16_t *x, const int32_t *top
         a.h_out = nullptr; a.o_out = opart; a.o_ks_stride = w.o_ks_stride;
         rc = launch_stream_down(a, KIND_SHARED, st);
         if (rc) return rc;
+        s += nb;
     }
 
     if ((rc = mark(PZL_STAGE_SHARED, 1))) return rc;
