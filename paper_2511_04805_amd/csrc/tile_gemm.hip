@@ -2,25 +2,31 @@
 // contraction on the matrix cores.
 //
 // Sec. 3.3.2 asks that every packed weight be decoded (Algorithm 1) right before it is
-// multiplied and that the decoded matrix never be materialised in memory.  With hundreds of
-// tokens per expert the work is MFMA-bound, so here a workgroup decodes each packed 16x32
-// tile ONCE into LDS (as bf16, already in matrix-core operand order) and all four waves
-// multiply it with up to 256 tokens: the decode cost is amortised over the token tile, and
-// the decoded weights live only in LDS.
+// multiplied and that the decoded matrix never be materialised in memory.  Here the decoded
+// weights do not even reach LDS: each wave loads the packed 16x32 tiles of its own weight rows
+// straight into registers (the tiled layout is already the A operand of
+// v_mfma_f32_16x16x32_bf16), decodes them there and multiplies them with every token of the
+// tile, so each packed word is decoded once per 256 tokens.
 //
-// Workgroup tile (defaults): up to 256 tokens of one expert x 256 weight rows (gate/up stage: the
-// same 128 feature rows of the gate and of the up matrix, so SwiGLU runs on the accumulators;
-// down stage: 256 rows of the down matrix, with both planes (hi, lo) of H as the token operand).
-// 8 waves as 2 (tokens) x 4 (rows), two per SIMD; a wave accumulates up to 8 token fragments x
-// 4 row tiles of v_mfma_f32_16x16x32_bf16 (128 accumulator registers, which keeps the wave inside
-// the 256 registers it gets at two waves per SIMD).  K advances 64 (gate/up) or 32 (down) per
-// step; the global loads of step k+1 are in flight while step k is multiplied; LDS is
-// double-buffered, one barrier per step.
+// Workgroup tile: up to 256 tokens of one expert x 256 weight rows (gate/up stage: the same 128
+// feature rows of the gate and of the up matrix, so SwiGLU runs on the accumulators; down stage:
+// 256 rows of the down matrix, with both planes (hi, lo) of H as the token operand).  8 waves,
+// all along the weight rows: a wave owns 2 row tiles (gate + up of 16 features, or 2 down tiles)
+// and all 16 token fragments, 128 accumulator registers, two waves per SIMD.
 //
-// Measured alternatives on the Mixtral-shaped prefill (T = 4096), all slower than the default:
-// 4 waves with 256 accumulators each (1 wave per SIMD), 4-wave 256x128 / 128x128 tiles with two
-// workgroups per compute unit, weights loaded two steps ahead, three LDS stages with fragment
-// read-ahead across the barrier.  The shape macros below are kept so they can be re-measured.
+// Token operand: activation rows are gathered by `global_load_lds_dwordx4`, which writes a whole
+// fragment (64 lanes x 16 bytes, already in B operand order) into LDS without passing through
+// registers.  LDS holds a ring of 4 such stages (32 KiB each: 64 K elements of 256 tokens, or 32
+// of both H planes), filled three steps ahead; the weights are loaded two steps ahead into two
+// register sets.  One barrier per K step publishes the stage written two steps earlier; no wave
+// writes LDS with ds_write at all.  (Measured on this chip: ds_write_b128 sustains about
+// 70 B/clk per compute unit against 210 B/clk for ds_read_b128, which is why the earlier design,
+// decoded weights staged through LDS by all waves, stalled.)
+//
+// Memory operations complete in issue order, and every step issues [activation stage s+3,
+// weights s+2] in that order; waiting for the weights of step s (which the decode does) therefore
+// also covers the activation stage s+1 issued before them, which the barrier at the end of step
+// s then makes visible to the other waves.
 //
 // Token tiles are cut per expert into equal parts of at most 256 tokens (rounded up to 16),
 // so a 1030-token expert costs 5 x 208 rows rather than 5 x 256.
@@ -28,30 +34,20 @@
 
 namespace pzl {
 
-#ifndef TG_WN
-#define TG_WN 4            // waves along the weight rows (2 more along the tokens)
-#endif
-#ifndef TG_RT
-#define TG_RT 4            // 16-row weight tiles per wave
-#endif
-#ifndef TG_KBS_GATEUP
-#define TG_KBS_GATEUP 2    // k-blocks of 32 per K step, gate/up stage
-#endif
-#ifndef TG_DOWN_TOK
-#define TG_DOWN_TOK 256    // tokens per down tile (256, or 128: half a gate/up tile)
-#endif
 #ifndef TG_WPE
 #define TG_WPE 2
 #endif
-constexpr int TG_WAVES = 2 * TG_WN;
+constexpr int TG_WAVES = 8;
 constexpr int TG_THREADS = TG_WAVES * 64;
-constexpr int TG_MAX_TOK = 256;          // tokens per gate/up tile (16 fragments of 16)
-constexpr int TG_ROW_TILES = TG_WN * TG_RT;   // 16-row weight tiles per workgroup
-constexpr int TG_STAGE_UNITS = (TG_ROW_TILES + 16) * TG_KBS_GATEUP * 64 > (TG_ROW_TILES + 2 * TG_DOWN_TOK / 16) * 64
-                                   ? (TG_ROW_TILES + 16) * TG_KBS_GATEUP * 64
-                                   : (TG_ROW_TILES + 2 * TG_DOWN_TOK / 16) * 64;   // 16-byte units per LDS stage
-constexpr int TG_LDS_BYTES = 2 * TG_STAGE_UNITS * 16 + TG_MAX_TOK * 4;
+constexpr int TG_MAX_TOK = 256;          // tokens per tile (16 fragments of 16)
+constexpr int TG_FRAGS = TG_MAX_TOK / 16;
+constexpr int TG_ROW_TILES = 2 * TG_WAVES;    // 16-row weight tiles per workgroup
+constexpr int TG_XSTAGES = 4;
+constexpr int TG_XSTAGE_UNITS = TG_FRAGS * 2 * 64;   // 16-byte units per stage (16 fragments x 2 k-blocks or planes)
 constexpr int TSTAGE_GATEUP = 0, TSTAGE_DOWN = 1;
+#ifndef TG_READ_AHEAD
+#define TG_READ_AHEAD 3     // fragment reads kept in flight ahead of the matrix instructions
+#endif
 #ifndef TG_BLOCK_M
 #define TG_BLOCK_M 8
 #endif
@@ -92,13 +88,22 @@ __device__ __forceinline__ uint32_t tg_decode_pair(uint32_t x)
 }
 
 template <int POS, bool DENSE>
-__device__ __forceinline__ u32x4 tg_decode(u32x4 w)
+__device__ __forceinline__ bf16x8 tg_decode(u32x4 w)
 {
-    if (DENSE) return w;
     u32x4 o;
+    if (DENSE) {
+        // An identity "decode" still has to produce NEW registers (an opaque copy): if the operand
+        // were the load's own registers, the compiler would keep them alive past the refill,
+        // rename the refill and copy it back at the loop edge while it is still in flight.
+        uint32_t o0, o1, o2, o3;
+        asm("v_mov_b32 %0, %4\n\tv_mov_b32 %1, %5\n\tv_mov_b32 %2, %6\n\tv_mov_b32 %3, %7"
+            : "=&v"(o0), "=&v"(o1), "=&v"(o2), "=&v"(o3) : "v"(w[0]), "v"(w[1]), "v"(w[2]), "v"(w[3]));
+        o = (u32x4){o0, o1, o2, o3};
+        return __builtin_bit_cast(bf16x8, o);
+    }
 #pragma unroll
     for (int i = 0; i < 4; ++i) o[i] = tg_decode_pair<POS>(w[i]);
-    return o;
+    return __builtin_bit_cast(bf16x8, o);
 }
 
 __device__ __forceinline__ uint32_t tg_bf16_rne(float v)
@@ -116,35 +121,35 @@ __device__ __forceinline__ void tg_swiglu_split(float g, float u, uint32_t &hi, 
     lo = tg_bf16_rne(h - __uint_as_float(hi << 16));
 }
 
+typedef const u32x4 __attribute__((address_space(1))) *tg_gvec_ptr;
+typedef __attribute__((address_space(3))) void *tg_lds_ptr;
+
 // The whole tile for one expert position (POS is the position of the expert inside its pair).
-// CNT = token fragments per wave: both token-side waves take ceil(n_frags / 2) fragments, so the
-// K loop has no data-dependent branch (a guard per fragment makes the register allocator move
-// accumulators between register files); an odd tile costs one padded fragment.
+// CNT = pairs of token fragments (the tile has at most 32*CNT tokens): a template parameter so
+// that the K loop has no data-dependent branch; an odd tile costs one padded fragment.
 // DENSE: plain bf16 weights (identity decode).  ALLTOK: a shared expert, uniform token tiles
 // over every token instead of the routed tile list.
 template <int STAGE, bool DENSE, bool ALLTOK, int POS, int CNT>
 __device__ __forceinline__ void tile_body(const TgArgs &a, const uint16_t *wa, const uint16_t *wb,
-                                          int slot0, int n_tok, int ntile, int ks, u32x4 *lds, int32_t *rowidx)
+                                          int slot0, int n_tok, int ntile, int ks,
+                                          u32x4 *ring, int32_t *rowidx)
 {
-    constexpr int KBS = (STAGE == TSTAGE_DOWN) ? 1 : TG_KBS_GATEUP;   // k-blocks (of 32) per K step
-    constexpr int FR = (STAGE == TSTAGE_DOWN) ? TG_DOWN_TOK / 16 : TG_MAX_TOK / 16;   // token fragment slots
+    constexpr int KBS = (STAGE == TSTAGE_DOWN) ? 1 : 2;      // k-blocks (of 32) per K step
     constexpr int PARTS = (STAGE == TSTAGE_DOWN) ? 2 : 1;    // activation planes (hi, lo)
-    constexpr int W_UNITS = TG_ROW_TILES * KBS * 64;         // 16-byte units of decoded weights per stage
-    constexpr int X_UNITS = PARTS * FR * KBS * 64;
-    static_assert(W_UNITS + X_UNITS <= TG_STAGE_UNITS, "stage does not fit");
-    constexpr int WPT = TG_ROW_TILES * KBS / TG_WAVES;       // weight tiles each wave loads per step
-    constexpr int XPT = PARTS * FR * KBS / TG_WAVES;         // activation fragments each wave loads per step
-    constexpr int RT = TG_RT;                                // row tiles per wave
+    constexpr int NF = 2 * CNT;                              // token fragments in use
+    constexpr int RT = 2;                                    // row tiles per wave
+    constexpr int XTOTAL = PARTS * NF * KBS;                 // activation fragments per stage
+    constexpr int XPT = (XTOTAL + TG_WAVES - 1) / TG_WAVES;  // ... of which each wave fetches this many
+    static_assert(PARTS * TG_FRAGS * KBS * 64 == TG_XSTAGE_UNITS, "stage size");
 
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    const int wm = __builtin_amdgcn_readfirstlane(wave & 1);  // wave position along tokens
-    const int wn = __builtin_amdgcn_readfirstlane(wave >> 1); // wave position along rows
+    const int tid = threadIdx.x, lane = tid & 63;
+    const uint32_t lane16 = lane * 16u;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int kb_total = a.kdim / TILE_COLS;
     // this workgroup's share of K (the down stage may be split over several workgroups)
     const int kb0 = (int)((int64_t)ks * kb_total / a.ksplit);
     const int kb1 = (int)((int64_t)(ks + 1) * kb_total / a.ksplit);
     const int n_steps = (kb1 - kb0 + KBS - 1) / KBS;
-    const int frag0 = wm * CNT;                              // fragments frag0 .. frag0+CNT-1 (< 16)
     const int row_tiles = a.rows / TILE_ROWS;
 
     // activation row behind each token column of the tile (clamped to the last valid token)
@@ -157,139 +162,183 @@ __device__ __forceinline__ void tile_body(const TgArgs &a, const uint16_t *wa, c
     }
     __syncthreads();
 
-    // ---- what this wave loads each step --------------------------------------------------
-    // weights: tile t = wave*WPT + i  ->  (local row tile t / KBS, k-block t % KBS)
-    // (the tile base is the same for all lanes: keep it in scalar registers and add the lane)
-    typedef const u32x4 __attribute__((address_space(1))) *gvec_ptr;
-    uint64_t wbase[WPT];
+    // ---- this wave's weight rows: gate/up -> tile `wave` of the gate and of the up rows of this
+    // workgroup (same 16 features); down -> tiles 2*wave, 2*wave+1.  The tile base is the same for
+    // all lanes: keep it in scalar registers and add the lane.
+    uint64_t wbase[RT];
 #pragma unroll
-    for (int i = 0; i < WPT; ++i) {
-        int t = wave * WPT + i;
-        int lrt = t / KBS, kbo = t % KBS;
-        int grt;                                              // global row tile, clamped to the matrix
-        const uint16_t *base;
-        if (STAGE == TSTAGE_GATEUP) {
-            constexpr int HALF = TG_ROW_TILES / 2;            // local tiles [0,HALF) gate, [HALF,2*HALF) up
-            base = (lrt < HALF) ? wa : wb;
-            grt = min(ntile * HALF + (lrt % HALF), row_tiles - 1);
-        } else {
-            base = wa;
-            grt = min(ntile * TG_ROW_TILES + lrt, row_tiles - 1);
-        }
-        uint64_t p = (uint64_t)(uintptr_t)base + (((int64_t)grt * kb_total + kbo) * 64) * 16;
+    for (int j = 0; j < RT; ++j) {
+        const uint16_t *base = (STAGE == TSTAGE_GATEUP && j == 1) ? wb : wa;
+        int grt = (STAGE == TSTAGE_GATEUP) ? ntile * TG_WAVES + wave : ntile * TG_ROW_TILES + wave * RT + j;
+        grt = min(grt, row_tiles - 1);                        // clamped to the matrix; never stored
+        uint64_t p = (uint64_t)(uintptr_t)base + ((int64_t)grt * kb_total * 64) * 16;
         uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)p);
         uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(p >> 32));
-        wbase[i] = ((uint64_t)hi << 32) | lo;
+        wbase[j] = ((uint64_t)hi << 32) | lo;
     }
-    // activations: fragment column c = wave*XPT + i -> (plane, token fragment, k-block);
-    // 32-bit element offsets from the activation base (every activation buffer is < 2^31 elements)
+    // ---- the activation fragments this wave fetches each step: fragment c = wave*XPT + i (the
+    // last one repeated if the count does not divide) -> (plane, token fragment, k-block);
+    // 32-bit byte offsets from the activation base (every activation buffer is < 2^31 elements):
+    // uniform base + 32-bit lane offset is the addressing form that needs no 64-bit vector math
     uint32_t xoff[XPT];
+    int xunit[XPT], xkbo[XPT];
 #pragma unroll
     for (int i = 0; i < XPT; ++i) {
-        int c = wave * XPT + i;
-        int kbo = c % KBS, fr = (c / KBS) % FR, part = c / (KBS * FR);
-        xoff[i] = (uint32_t)(part * a.act_plane_stride) +
-                  (uint32_t)rowidx[fr * 16 + (lane & 15)] * (uint32_t)a.kdim + kbo * TILE_COLS + (lane >> 4) * 8;
+        int c = min(wave * XPT + i, XTOTAL - 1);
+        int kbo = c % KBS, fr = (c / KBS) % NF, part = c / (KBS * NF);
+        xkbo[i] = kbo;
+        xunit[i] = ((part * TG_FRAGS + fr) * KBS + kbo) * 64;
+        xoff[i] = 2u * ((uint32_t)(part * a.act_plane_stride) +
+                        (uint32_t)rowidx[fr * 16 + (lane & 15)] * (uint32_t)a.kdim + (lane >> 4) * 8);
     }
 
-    u32x4 wreg[WPT], xreg[XPT];
-    const u32x4 zero4 = {0u, 0u, 0u, 0u};
-    auto issue_loads = [&](int step) {
-        // a k-block past the end re-reads the last valid one; its activations are stored as zero
-#pragma unroll
-        for (int i = 0; i < WPT; ++i) {
-            int kbo = (wave * WPT + i) % KBS;
-            int kb = min(kb0 + step * KBS + kbo, kb1 - 1) - kbo;
-            wreg[i] = __builtin_nontemporal_load((gvec_ptr)wbase[i] + (int64_t)kb * 64 + lane);
-        }
+    // a k-block past the end re-reads the last valid one; the last step skips its products
+    // Both kinds of load are issued from inline assembly, and waited for by hand (wait_w below):
+    // the compiler, seeing a direct-to-LDS load, waits for ALL outstanding loads before the next
+    // LDS read, which would undo the prefetch.
+    const uint64_t act_base = (uint64_t)(uintptr_t)a.act;
+    auto fetch_x = [&](int step, u32x4 *stage) {
 #pragma unroll
         for (int i = 0; i < XPT; ++i) {
-            int kbo = (wave * XPT + i) % KBS;
-            int kb = min(kb0 + step * KBS + kbo, kb1 - 1) - kbo;
-            xreg[i] = *(const u32x4 *)(a.act + (xoff[i] + (uint32_t)(kb * TILE_COLS)));
+            int kb = min(kb0 + step * KBS + xkbo[i], kb1 - 1);
+            uint32_t voff = xoff[i] + (uint32_t)(kb * TILE_COLS * 2);
+            uint32_t lds_addr = (uint32_t)(uintptr_t)(tg_lds_ptr)(stage + xunit[i]);
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                         :: "s"(lds_addr), "v"(voff), "s"(act_base) : "memory");
         }
     };
-    auto store_stage = [&](int stage, int step) {
-        u32x4 *ws = lds + stage * TG_STAGE_UNITS;
-        u32x4 *xs = ws + W_UNITS;
+    auto fetch_w = [&](int step, u32x4 (&raw)[KBS][RT], int kbo) {
+        int kb = min(kb0 + step * KBS + kbo, kb1 - 1);
 #pragma unroll
-        for (int i = 0; i < WPT; ++i)
-            ws[(wave * WPT + i) * 64 + lane] = tg_decode<POS, DENSE>(wreg[i]);
-#pragma unroll
-        for (int i = 0; i < XPT; ++i) {
-            int c = wave * XPT + i;
-            bool valid = kb0 + step * KBS + c % KBS < kb1;
-            xs[c * 64 + lane] = valid ? xreg[i] : zero4;
+        for (int j = 0; j < RT; ++j) {
+            uint64_t base = wbase[j] + (uint64_t)kb * 1024u;
+            // in/out operand: the load must land in the registers that the wait and the decode of
+            // step + 2 will name; as a plain output the compiler may pick other registers and
+            // copy them over at the loop edge, while the load is still in flight
+            asm volatile("global_load_dwordx4 %0, %1, %2" : "+v"(raw[kbo][j]) : "v"(lane16), "s"(base));
         }
+    };
+    // Loads complete in issue order.  A step issues: activation stage s+3, then per k-block
+    // [wait for its weights, decode, refill the registers with the weights of step s+2].  Younger
+    // than the weights of (s, k-block) are then: the remaining k-blocks of s, activation stage
+    // s+2, the weights of s+1, activation stage s+3 and the refills already issued in this step:
+    // 2*XPT + (2*KBS-1)*RT loads in all.  Waiting until only that many are outstanding makes the
+    // weights usable and, being older, the activation stage s+1 complete.  The asm takes the
+    // registers as in/out operands so that nothing that uses them can be scheduled above the wait.
+    auto wait_w = [&](u32x4 (&raw)[KBS][RT], int kbo, bool all) {
+        if (all) asm volatile("s_waitcnt vmcnt(0)" : "+v"(raw[kbo][0]), "+v"(raw[kbo][1]));
+        else     asm volatile("s_waitcnt vmcnt(%2)" : "+v"(raw[kbo][0]), "+v"(raw[kbo][1]) : "n"(2 * XPT + (2 * KBS - 1) * RT));
     };
 
-    f32x4 acc[RT][CNT];
+    f32x4 acc[RT][NF];
 #pragma unroll
     for (int j = 0; j < RT; ++j)
 #pragma unroll
-        for (int i = 0; i < CNT; ++i) acc[j][i] = (f32x4){0.f, 0.f, 0.f, 0.f};
+        for (int i = 0; i < NF; ++i) acc[j][i] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
-    issue_loads(0);
-    store_stage(0, 0);
-    __syncthreads();
-
-    for (int step = 0; step < n_steps; ++step) {
-        const bool has_next = step + 1 < n_steps;
-        if (has_next) issue_loads(step + 1);
-
-        const u32x4 *ws = lds + (step & 1) * TG_STAGE_UNITS;
-        const u32x4 *xs = ws + W_UNITS;
+    auto multiply = [&](const u32x4 *xs, const bf16x8 (&af)[RT], int kbo) {
 #pragma unroll
-        for (int kbo = 0; kbo < KBS; ++kbo) {
-            // this wave's 4 weight row tiles: gate/up stage -> gate tiles wn*2, wn*2+1 and up tiles
-            // 4+wn*2, 4+wn*2+1 (same feature rows); down stage -> tiles wn*4..+3
-            bf16x8 af[RT];
+        for (int i = 0; i < NF; ++i) {
 #pragma unroll
-            for (int j = 0; j < RT; ++j) {
-                int lrt = (STAGE == TSTAGE_GATEUP) ? ((j < RT / 2) ? wn * (RT / 2) + j : TG_ROW_TILES / 2 + wn * (RT / 2) + (j - RT / 2)) : wn * RT + j;
-                af[j] = __builtin_bit_cast(bf16x8, ws[(lrt * KBS + kbo) * 64 + lane]);
-            }
+            for (int part = 0; part < PARTS; ++part) {
+                bf16x8 b = __builtin_bit_cast(bf16x8, xs[((part * TG_FRAGS + i) * KBS + kbo) * 64 + lane]);
 #pragma unroll
-            for (int i = 0; i < CNT; ++i) {
-#pragma unroll
-                for (int part = 0; part < PARTS; ++part) {
-                    bf16x8 b = __builtin_bit_cast(bf16x8, xs[((part * FR + frag0 + i) * KBS + kbo) * 64 + lane]);
-#pragma unroll
-                    for (int j = 0; j < RT; ++j)
-                        acc[j][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[j], b, acc[j][i], 0, 0, 0);
-                }
+                for (int j = 0; j < RT; ++j)
+                    acc[j][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[j], b, acc[j][i], 0, 0, 0);
             }
         }
-        if (has_next) store_stage((step + 1) & 1, step + 1);
-        __syncthreads();
+    };
+    // One K step.  `cur` holds the activations of this step, `fill` is the stage read three steps
+    // ago (free since the last barrier); `raw` holds this step's packed weights and is refilled
+    // with those of step + 2 once they are decoded.
+    auto full_step = [&](const u32x4 *cur, u32x4 *fill, u32x4 (&raw)[KBS][RT], int step) {
+        fetch_x(step + 3, fill);
+#pragma unroll
+        for (int kbo = 0; kbo < KBS; ++kbo) {
+            wait_w(raw, kbo, false);
+            bf16x8 af[RT];
+#pragma unroll
+            for (int j = 0; j < RT; ++j) af[j] = tg_decode<POS, DENSE>(raw[kbo][j]);
+            if (kbo > 0) {                 // a k-block past the end (odd count): multiply by zero
+                const bool valid = kb0 + step * KBS + kbo < kb1;
+                const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+                for (int j = 0; j < RT; ++j) af[j] = valid ? af[j] : zero;
+            }
+            fetch_w(step + 2, raw, kbo);
+            multiply(cur, af, kbo);
+            // order of issue: a few fragment reads ahead, then one more read per pair of matrix
+            // instructions, so that the LDS latency is covered by the products of earlier fragments
+            __builtin_amdgcn_sched_group_barrier(0x100, TG_READ_AHEAD, 0);
+#pragma unroll
+            for (int f = 0; f < NF * PARTS; ++f) {
+                __builtin_amdgcn_sched_group_barrier(0x008, RT, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            }
+        }
+        // A bare barrier (no fence): the only LDS writes are the direct loads, whose completion
+        // the wait above covers.  Nothing may be scheduled across it.
+        __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    // stage of step s: ring + (s % 4) * TG_XSTAGE_UNITS
+    auto stage = [&](int step) { return ring + (step & (TG_XSTAGES - 1)) * TG_XSTAGE_UNITS; };
+    u32x4 raw0[KBS][RT] = {}, raw1[KBS][RT] = {};      // weights of the even / of the odd steps
+    fetch_x(0, stage(0));
+    fetch_x(1, stage(1));
+    fetch_x(2, stage(2));
+#pragma unroll
+    for (int kbo = 0; kbo < KBS; ++kbo) fetch_w(0, raw0, kbo);
+#pragma unroll
+    for (int kbo = 0; kbo < KBS; ++kbo) fetch_w(1, raw1, kbo);
+#pragma unroll
+    for (int kbo = 0; kbo < KBS; ++kbo) {  // everything landed (this wave's share of the stages too)
+        wait_w(raw0, kbo, true);
+        wait_w(raw1, kbo, true);
     }
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+
+    // Every step is the same code, the last ones included: their refills are clamped re-reads
+    // that nobody uses, their barrier is harmless.
+    for (int step = 0;; step += 2) {
+        full_step(stage(step), stage(step + 3), raw0, step);
+        if (step + 1 >= n_steps) break;
+        full_step(stage(step + 1), stage(step + 4), raw1, step + 1);
+        if (step + 2 >= n_steps) break;
+    }
+    // No load of this wave is in flight past this point: the refills of the last steps still
+    // write the (now dead) weight registers, so nothing may be scheduled above this wait that
+    // could be given one of them.
+    __builtin_amdgcn_sched_barrier(0);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
 
     // ---- epilogue: lane holds rows 4*(lane/16)..+3 of its row tile for token column lane%16 ----
     const int col = lane & 15, rsub = (lane >> 4) * 4;
 #pragma unroll
-    for (int i = 0; i < CNT; ++i) {
-        int within = (frag0 + i) * 16 + col;
+    for (int i = 0; i < NF; ++i) {
+        int within = i * 16 + col;
         if (within >= n_tok) continue;
         int slot = slot0 + within;
         if (STAGE == TSTAGE_GATEUP) {
+            int grt = ntile * TG_WAVES + wave;
+            if (grt >= row_tiles) continue;
+            f32x4 g = acc[0][i], u = acc[1][i];
+            uint32_t hi[4], lo[4];
 #pragma unroll
-            for (int j = 0; j < RT / 2; ++j) {
-                int grt = ntile * (TG_ROW_TILES / 2) + wn * (RT / 2) + j;
-                if (grt >= row_tiles) continue;
-                f32x4 g = acc[j][i], u = acc[j + RT / 2][i];
-                uint32_t hi[4], lo[4];
-#pragma unroll
-                for (int r = 0; r < 4; ++r) tg_swiglu_split(g[r], u[r], hi[r], lo[r]);
-                u32x2 ohi = {hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16)};
-                u32x2 olo = {lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16)};
-                uint16_t *dst = a.h_out + (int64_t)(slot - a.h_slot_base) * a.rows + grt * 16 + rsub;
-                *(u32x2 *)dst = ohi;
-                *(u32x2 *)(dst + a.h_plane_stride) = olo;
-            }
+            for (int r = 0; r < 4; ++r) tg_swiglu_split(g[r], u[r], hi[r], lo[r]);
+            u32x2 ohi = {hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16)};
+            u32x2 olo = {lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16)};
+            uint16_t *dst = a.h_out + (int64_t)(slot - a.h_slot_base) * a.rows + grt * 16 + rsub;
+            *(u32x2 *)dst = ohi;
+            *(u32x2 *)(dst + a.h_plane_stride) = olo;
         } else {
 #pragma unroll
             for (int j = 0; j < RT; ++j) {
-                int grt = ntile * TG_ROW_TILES + wn * RT + j;
+                int grt = ntile * TG_ROW_TILES + wave * RT + j;
                 if (grt >= row_tiles) continue;
                 *(f32x4 *)(a.o_out + (int64_t)ks * a.o_ks_stride + (int64_t)slot * a.rows + grt * 16 + rsub) = acc[j][i];
             }
@@ -301,9 +350,8 @@ template <int STAGE, bool DENSE, bool ALLTOK>
 __global__ void __launch_bounds__(TG_THREADS) __attribute__((amdgpu_waves_per_eu(TG_WPE, TG_WPE)))
 tile_kernel(TgArgs a)
 {
-    extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
-    u32x4 *lds = (u32x4 *)lds_raw;
-    int32_t *rowidx = (int32_t *)(lds_raw + 2 * TG_STAGE_UNITS * 16);
+    __shared__ u32x4 ring[TG_XSTAGES * TG_XSTAGE_UNITS];
+    __shared__ int32_t rowidx[TG_MAX_TOK];
 
     // XCD-aware order.  Consecutive workgroup ids go to different XCDs (8 of them, each with its
     // own L2), so give each XCD a contiguous range of logical ids.  The 32 workgroups an XCD runs
@@ -322,10 +370,7 @@ tile_kernel(TgArgs a)
     const int ntile = (blk / gm_count) * TG_BLOCK_N + r / TG_BLOCK_M;
     if (mt_raw >= a.max_mtiles || ntile >= a.n_ntiles) return;
 
-    // the down stage takes a gate/up token tile in two halves of at most TG_DOWN_TOK tokens
-    constexpr int HALVES = (STAGE == TSTAGE_DOWN) ? TG_MAX_TOK / TG_DOWN_TOK : 1;
-    const int half = mt_raw % HALVES;
-    const int mt = mt_raw / HALVES;
+    const int mt = mt_raw;
     int g, pos, slot0, n_tok;
     if (ALLTOK) {
         if (mt >= a.dense_tiles) return;
@@ -343,11 +388,6 @@ tile_kernel(TgArgs a)
         slot0 = a.tile_slot0[mt];
         n_tok = a.tile_n[mt];
     }
-    if (STAGE == TSTAGE_DOWN) {
-        slot0 += half * TG_DOWN_TOK;
-        n_tok = min(n_tok - half * TG_DOWN_TOK, TG_DOWN_TOK);
-        if (n_tok <= 0) return;
-    }
     // these are the same for the whole workgroup; say so, or the per-fragment guards below become
     // exec-masked branches and the accumulators get shuffled between register files
     g = __builtin_amdgcn_readfirstlane(g);
@@ -357,7 +397,7 @@ tile_kernel(TgArgs a)
     const uint16_t *wa = a.w_a[g];
     const uint16_t *wb = (STAGE == TSTAGE_GATEUP) ? a.w_b[g] : wa;
     const int cnt = (((n_tok + 15) >> 4) + 1) >> 1;          // 1..8 fragments per wave
-#define PZL_TILE(P, C) tile_body<STAGE, DENSE, ALLTOK, P, C>(a, wa, wb, slot0, n_tok, ntile, ks, lds, rowidx)
+#define PZL_TILE(P, C) tile_body<STAGE, DENSE, ALLTOK, P, C>(a, wa, wb, slot0, n_tok, ntile, ks, ring, rowidx)
 #define PZL_TILE_CNT(P)                                                         \
     switch (cnt) {                                                              \
         case 1: PZL_TILE(P, 1); break; case 2: PZL_TILE(P, 2); break;           \
@@ -386,21 +426,14 @@ static int launch(const TileGemmArgs &t, hipStream_t st)
     a.h_out = t.h_out; a.h_plane_stride = t.h_plane_stride; a.h_slot_base = t.h_slot_base;
     a.o_out = t.o_out; a.o_ks_stride = t.o_ks_stride;
     a.ksplit = (STAGE == TSTAGE_DOWN && t.ksplit > 1) ? t.ksplit : 1;
-    a.max_mtiles = t.max_mtiles * ((STAGE == TSTAGE_DOWN) ? TG_MAX_TOK / TG_DOWN_TOK : 1);
-    const int rows_per_wg = (STAGE == TSTAGE_GATEUP) ? TG_ROW_TILES * 8 : TG_ROW_TILES * 16;
+    a.max_mtiles = t.max_mtiles;
+    const int rows_per_wg = (STAGE == TSTAGE_GATEUP) ? TG_ROW_TILES * 8 : TG_ROW_TILES * 16;   // feature rows / down rows
     a.n_ntiles = (t.rows + rows_per_wg - 1) / rows_per_wg;
     int64_t blocks = (int64_t)((a.max_mtiles + TG_BLOCK_M - 1) / TG_BLOCK_M) *
                      ((a.n_ntiles + TG_BLOCK_N - 1) / TG_BLOCK_N) * (TG_BLOCK_M * TG_BLOCK_N);
     blocks = (blocks + 7) / 8 * 8 * a.ksplit;
     if (blocks > 0x7FFFFFFFLL) return PZL_EINVAL;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)tile_kernel<STAGE, DENSE, ALLTOK>,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, TG_LDS_BYTES);
-        if (e != hipSuccess) { set_hip_error(e); return PZL_EHIP; }
-        attr_set = true;
-    }
-    hipLaunchKernelGGL((tile_kernel<STAGE, DENSE, ALLTOK>), dim3((unsigned)blocks), dim3(TG_THREADS), TG_LDS_BYTES, st, a);
+    hipLaunchKernelGGL((tile_kernel<STAGE, DENSE, ALLTOK>), dim3((unsigned)blocks), dim3(TG_THREADS), 0, st, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) { set_hip_error(e); return PZL_EHIP; }
     return PZL_OK;
