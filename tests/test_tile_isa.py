@@ -1,0 +1,33 @@
+"""Host-side check of the tiled kernels' machine code (no GPU needed: hipcc cross-compiles).
+
+The tiled decode-GEMM waits by hand for loads it issues from inline assembly; this test compiles
+it and verifies that the compiler left the in-flight registers alone (see
+paper_2511_04805_amd/check_tile_isa.py for the reasoning)."""
+import shutil
+
+import pytest
+
+from paper_2511_04805_amd import check_tile_isa
+
+
+@pytest.mark.skipif(shutil.which("hipcc") is None, reason="hipcc not installed")
+def test_tile_kernel_in_flight_registers(tmp_path):
+    asm = tmp_path / "tile_gemm.s"
+    check_tile_isa.compile_to_asm(str(asm))
+    n_loops, n_exits, problems = check_tile_isa.check(asm.read_text())
+    assert not problems, problems[:5]
+    # 6 kernels x 2 positions (packed) or 1 (dense) x 8 tile sizes
+    assert n_loops == 64 and n_exits == 64, (n_loops, n_exits)
+
+
+def test_checker_flags_a_planted_copy():
+    """The checker itself: a copy of a register that an asm load has just written is reported."""
+    body = ["\tv_mfma_f32_16x16x32_bf16 v[0:3], v[4:7], v[8:11], v[0:3]"] * 8
+    text = "\n".join([".LBB0_1:"] + body + [
+        "\t;;#ASMSTART", "\tglobal_load_dwordx4 v[20:23], v1, s[2:3]", "\t;;#ASMEND",
+        "\ts_barrier", "\tv_mov_b32_e32 v30, v21", "\ts_barrier",
+        "\ts_cbranch_scc1 .LBB0_1"])
+    n_loops, _, problems = check_tile_isa.check(text)
+    assert n_loops == 1 and len(problems) == 1 and "v_mov_b32" in problems[0]
+    clean = text.replace("v_mov_b32_e32 v30, v21", "v_mov_b32_e32 v30, v31")
+    assert check_tile_isa.check(clean)[2] == []
