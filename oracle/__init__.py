@@ -15,15 +15,17 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "puzzle_oracle.c")
+_SRC_Q = os.path.join(_HERE, "quant_oracle.c")
 _LIB = os.path.join(_HERE, "liboracle.so")
 _lib = None
 
 
 def build(force=False):
     """Compile the oracle with gcc (no fast-math: fp64 sums stay in source order)."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+    newest = max(os.path.getmtime(_SRC), os.path.getmtime(_SRC_Q))
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < newest:
         subprocess.check_call(["gcc", "-O2", "-fopenmp", "-shared", "-fPIC", "-Wall", "-Wextra",
-                               "-o", _LIB, _SRC, "-lm"])
+                               "-o", _LIB, _SRC, _SRC_Q, "-lm"])
     return _LIB
 
 
@@ -201,3 +203,84 @@ def moe_ffn(x, ids, w, expert_pair, expert_pos, gate, up, down,
     if rc != 0:
         raise ValueError("oracle moe_ffn: expert id out of range or allocation failure")
     return y64, ybf
+
+
+# ---------- quantised variant (appendix "Combining PuzzleMoE with Quantization") ----------
+
+def q_quantise(merged, mask0, mask1, sign0, sign1):
+    """3-bit group-128 quantisation of a merged matrix with its masks and signs.
+
+    Returns dict(code, trit, s0, s1 (uint8 [rows, cols]), scale (uint16 bf16 bits [rows, cols/128]),
+    n_bad)."""
+    merged = _u16(merged)
+    rows, cols = merged.shape
+    assert cols % 128 == 0
+    m0, m1, s0, s1 = (_u8(a) for a in (mask0, mask1, sign0, sign1))
+    out = {k: np.empty(merged.shape, dtype=np.uint8) for k in ("code", "trit", "s0", "s1")}
+    scale = np.empty((rows, cols // 128), dtype=np.uint16)
+    lib = _load()
+    lib.orc_q_quantise.restype = ctypes.c_int64
+    bad = lib.orc_q_quantise(*[ctypes.c_void_p(a.ctypes.data) for a in (merged, m0, m1, s0, s1)],
+                             ctypes.c_int64(rows), ctypes.c_int64(cols),
+                             *[ctypes.c_void_p(out[k].ctypes.data) for k in ("code", "trit", "s0", "s1")],
+                             ctypes.c_void_p(scale.ctypes.data))
+    out["scale"] = scale
+    out["n_bad"] = int(bad)
+    return out
+
+
+def q_dequantise(q, pos):
+    """Reconstructed weights of expert `pos` of the pair, fp64 [rows, cols] (exact code * scale)."""
+    rows, cols = q["code"].shape
+    out = np.empty((rows, cols), dtype=np.float64)
+    lib = _load()
+    lib.orc_q_dequantise.restype = None
+    lib.orc_q_dequantise(*[ctypes.c_void_p(q[k].ctypes.data) for k in ("code", "trit", "s0", "s1", "scale")],
+                         ctypes.c_int(pos), ctypes.c_int64(rows), ctypes.c_int64(cols),
+                         ctypes.c_void_p(out.ctypes.data))
+    return out
+
+
+def q_records(q):
+    """The stored 53-bit records, uint64 [rows, cols/8], in plain row-major record order."""
+    rows, cols = q["code"].shape
+    out = np.empty((rows, cols // 8), dtype=np.uint64)
+    lib = _load()
+    lib.orc_q_records.restype = None
+    lib.orc_q_records(*[ctypes.c_void_p(q[k].ctypes.data) for k in ("code", "trit", "s0", "s1")],
+                      ctypes.c_int64(rows), ctypes.c_int64(cols), ctypes.c_void_p(out.ctypes.data))
+    return out
+
+
+def q_bits_per_weight():
+    lib = _load()
+    lib.orc_q_bits_per_weight.restype = ctypes.c_double
+    return lib.orc_q_bits_per_weight()
+
+
+def ffn_dense64(x, ids, w, gate, up, down):
+    """Routed SwiGLU FFN with per-expert fp64 weight matrices (gate/up [f,d], down [d,f])."""
+    x = _u16(x)
+    T, d = x.shape
+    ids = np.ascontiguousarray(ids, dtype=np.int32)
+    w = np.ascontiguousarray(w, dtype=np.float32)
+    k = ids.shape[1]
+    gate = [np.ascontiguousarray(a, dtype=np.float64) for a in gate]
+    up = [np.ascontiguousarray(a, dtype=np.float64) for a in up]
+    down = [np.ascontiguousarray(a, dtype=np.float64) for a in down]
+    E = len(gate)
+    f = gate[0].shape[0]
+    for a, b, c in zip(gate, up, down):
+        assert a.shape == (f, d) and b.shape == (f, d) and c.shape == (d, f)
+    arr_t = ctypes.c_void_p * E
+    y64 = np.zeros((T, d), dtype=np.float64)
+    lib = _load()
+    lib.orc_ffn_dense64.restype = ctypes.c_int
+    rc = lib.orc_ffn_dense64(ctypes.c_int(T), ctypes.c_int(k), ctypes.c_int(E), ctypes.c_int(d), ctypes.c_int(f),
+                             ctypes.c_void_p(x.ctypes.data), ctypes.c_void_p(ids.ctypes.data),
+                             ctypes.c_void_p(w.ctypes.data), arr_t(*[a.ctypes.data for a in gate]),
+                             arr_t(*[a.ctypes.data for a in up]), arr_t(*[a.ctypes.data for a in down]),
+                             ctypes.c_void_p(y64.ctypes.data))
+    if rc != 0:
+        raise ValueError("oracle ffn_dense64: expert id out of range or allocation failure")
+    return y64
