@@ -43,7 +43,7 @@
 extern "C" {
 #endif
 
-#define PZL_ABI_VERSION 2
+#define PZL_ABI_VERSION 3
 
 #define PZL_OK       0
 #define PZL_EINVAL  -1   /* null pointer, bad shape, position not 0/1, pair map not a 2-to-1 cover */
@@ -184,6 +184,44 @@ int pzl_moe_ffn(const pzl_layer *layer, const uint16_t *x, const int32_t *topk_i
  */
 int pzl_router_topk(const uint16_t *x, const uint16_t *w_router, int32_t T, int32_t d_model,
                     int32_t n_experts, int32_t k, int32_t *topk_ids, float *topk_w, void *stream);
+
+/*
+ * Quantised variant of the packed pair (appendix "Combining PuzzleMoE with Quantization": the
+ * merged weights quantised uniformly to 3 bits in groups of 128 with a symmetric scheme, stored
+ * with the two sign bits and the mask, whose three possible values cost log2(3) bits; the
+ * appendix's accounting is (2 + 1.58 + 3 + 0.125) / 2 = 3.35 bits per original weight).
+ *
+ * The appendix fixes neither a rounding rule nor a storage layout.  This library's readings:
+ * codes are unsigned magnitudes 0..7; groups are 128 consecutive columns of one row;
+ * scale = bf16(max / 7) over the magnitudes some expert uses, code = min(7, round-to-nearest-even
+ * (magnitude / scale)), both divisions correctly rounded in fp32; an element no expert uses is
+ * stored as code 0; reconstruction is (-1)^S * M * code * scale with no further rounding.
+ * Stored form: per 16x32 tile (same element order as the 16-bit format) 64 records of 53 bits,
+ * packed back to back (424 bytes): codes (3 bits x 8 elements), S0 x 8, S1 x 8, and the 8 masks
+ * as one base-3 number in 13 bits (digit 0: position 0 only, 1: position 1 only, 2: both); the
+ * scales in a separate array [rows/16][cols/128][16] of bf16.  3.375 bits per original weight.
+ * rows % 16 == 0 and cols % 128 == 0 are required.
+ */
+/* Bytes of the record array (includes 8 bytes of padding that the last record's 8-byte load may
+ * touch) and of the scale array; 0 for a bad shape. */
+size_t pzl_q_record_bytes(int64_t rows, int64_t cols);
+size_t pzl_q_scale_bytes(int64_t rows, int64_t cols);
+/*
+ * q_pack: quantise and store.  Inputs as for pzl_pack (row-major, logical order).
+ *   records_out  pzl_q_record_bytes(rows, cols) bytes, 8-byte aligned, caller-owned
+ *   scales_out   pzl_q_scale_bytes(rows, cols) bytes, caller-owned
+ *   n_non_finite optional int32 on the device; the kernel ADDS the number of used elements whose
+ *                magnitude is Inf/NaN (stored as code 0).  May be NULL.
+ */
+int pzl_q_pack(const uint16_t *merged, const uint8_t *mask0, const uint8_t *mask1,
+               const uint8_t *sign0, const uint8_t *sign1, int64_t rows, int64_t cols,
+               uint8_t *records_out, uint16_t *scales_out, int32_t *n_non_finite, void *stream);
+/*
+ * q_unpack: the reconstructed weights of the expert at `expert_pos` (0 or 1) as fp32, row-major
+ * [rows, cols]; code * scale is exact in fp32, so this is bit-exact by definition.
+ */
+int pzl_q_unpack(const uint8_t *records, const uint16_t *scales, int expert_pos, int64_t rows,
+                 int64_t cols, float *out, void *stream);
 
 /*
  * Measurement variant of pzl_moe_ffn: the same launches on the same stream, and in addition the

@@ -17,7 +17,8 @@ _lib = None
 PZL_OK, PZL_EINVAL, PZL_ENOSPC, PZL_EHIP, PZL_ENOMEM = 0, -1, -2, -3, -4
 
 EXPORTS = ("pzl_abi_version", "pzl_strerror", "pzl_last_hip_error", "pzl_packed_bytes", "pzl_pack",
-           "pzl_unpack", "pzl_tile_dense", "pzl_merge_pack", "pzl_router_topk", "pzl_layer_create", "pzl_layer_destroy",
+           "pzl_unpack", "pzl_tile_dense", "pzl_merge_pack", "pzl_router_topk",
+           "pzl_q_record_bytes", "pzl_q_scale_bytes", "pzl_q_pack", "pzl_q_unpack", "pzl_layer_create", "pzl_layer_destroy",
            "pzl_moe_ffn_workspace_bytes", "pzl_moe_ffn", "pzl_moe_ffn_staged")
 
 STAGES = ("route", "gateup", "down", "shared", "combine")
@@ -132,6 +133,66 @@ def pzl_unpack(packed, expert_pos, rows, cols, out=None):
                            _dev(out, _BITS16, "out"), _stream())
     _check(rc, "pzl_unpack")
     return out
+
+
+def pzl_q_pack(merged, mask0, mask1, sign0, sign1, n_non_finite=None):
+    """Quantised pack -> (records uint8 [pzl_q_record_bytes], scales int16 bf16 bits [rows/16, cols/128, 16])."""
+    rows, cols = merged.shape
+    lib = load()
+    lib.pzl_q_record_bytes.restype = ctypes.c_size_t
+    lib.pzl_q_scale_bytes.restype = ctypes.c_size_t
+    nrec = lib.pzl_q_record_bytes(ctypes.c_int64(rows), ctypes.c_int64(cols))
+    nsc = lib.pzl_q_scale_bytes(ctypes.c_int64(rows), ctypes.c_int64(cols))
+    if nrec == 0:
+        raise ValueError("quantised format needs rows % 16 == 0 and cols % 128 == 0")
+    records = torch.zeros(nrec, dtype=torch.uint8, device=merged.device)
+    scales = torch.empty(nsc // 2, dtype=torch.int16, device=merged.device)
+    cnt = ctypes.c_void_p(0) if n_non_finite is None else _dev(n_non_finite, (torch.int32,), "n_non_finite")
+    rc = lib.pzl_q_pack(_dev(merged, _BITS16, "merged"), _dev(mask0, (torch.uint8,), "mask0"),
+                        _dev(mask1, (torch.uint8,), "mask1"), _dev(sign0, (torch.uint8,), "sign0"),
+                        _dev(sign1, (torch.uint8,), "sign1"), ctypes.c_int64(rows), ctypes.c_int64(cols),
+                        _dev(records, (torch.uint8,), "records"), _dev(scales, _BITS16, "scales"), cnt, _stream())
+    _check(rc, "pzl_q_pack")
+    return records, scales
+
+
+def pzl_q_unpack(records, scales, expert_pos, rows, cols):
+    """Reconstructed weights of one expert of a quantised pair -> float32 [rows, cols], row-major."""
+    out = torch.empty(rows, cols, dtype=torch.float32, device=records.device)
+    rc = load().pzl_q_unpack(_dev(records, (torch.uint8,), "records"), _dev(scales, _BITS16, "scales"),
+                             int(expert_pos), ctypes.c_int64(rows), ctypes.c_int64(cols),
+                             _dev(out, (torch.float32,), "out"), _stream())
+    _check(rc, "pzl_q_unpack")
+    return out
+
+
+def q_records_to_logical(records, rows, cols):
+    """Host view of a record array (numpy uint8, as written by pzl_q_pack): the 53-bit records as
+    uint64 [rows, cols/8] in plain row-major record order (a layout change only)."""
+    import numpy as np
+    rec = np.asarray(records, dtype=np.uint8)
+    kb_total = cols // 32
+    n_tiles = (rows // 16) * kb_total
+    out = np.zeros((rows, cols // 8), dtype=np.uint64)
+    lanes = np.arange(64)
+    byte0 = (53 * lanes) >> 3
+    shift = ((53 * lanes) & 7).astype(np.uint64)
+    pow8 = (np.uint64(8) * np.arange(8, dtype=np.uint64))
+    for t in range(n_tiles):
+        base = t * 424
+        idx = base + byte0[:, None] + np.arange(8)[None, :]
+        v = (rec[idx].astype(np.uint64) << pow8[None, :]).sum(axis=1, dtype=np.uint64)
+        v = (v >> shift) & np.uint64((1 << 53) - 1)
+        rt, kb = divmod(t, kb_total)
+        out[rt * 16 + (lanes & 15), kb * 4 + (lanes >> 4)] = v
+    return out
+
+
+def q_scales_to_logical(scales, rows, cols):
+    """Scale array [rows/16, cols/128, 16] -> [rows, cols/128] (a layout change only)."""
+    import numpy as np
+    s = np.asarray(scales).reshape(rows // 16, cols // 128, 16)
+    return np.ascontiguousarray(s.transpose(0, 2, 1)).reshape(rows, cols // 128)
 
 
 def pzl_tile_dense(dense, out=None):

@@ -6,7 +6,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpuzzle_moe.so")
-SOURCES = ["api.hip", "codec.hip", "route.hip", "stream_gemm.hip", "tile_gemm.hip"]
+SOURCES = ["api.hip", "codec.hip", "quant_codec.hip", "route.hip", "stream_gemm.hip", "tile_gemm.hip"]
 # -packed-fp32-ops off: the compiler must not form packed fp32 arithmetic on this target
 FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

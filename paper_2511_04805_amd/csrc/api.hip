@@ -145,6 +145,24 @@ int pzl_unpack(const uint16_t *packed, int expert_pos, int64_t rows, int64_t col
     return launch_unpack(packed, expert_pos, rows, cols, out, (hipStream_t)stream);
 }
 
+size_t pzl_q_record_bytes(int64_t rows, int64_t cols) { return q_record_bytes(rows, cols); }
+size_t pzl_q_scale_bytes(int64_t rows, int64_t cols) { return q_scale_bytes(rows, cols); }
+
+int pzl_q_pack(const uint16_t *merged, const uint8_t *mask0, const uint8_t *mask1, const uint8_t *sign0,
+               const uint8_t *sign1, int64_t rows, int64_t cols, uint8_t *records_out,
+               uint16_t *scales_out, int32_t *n_non_finite, void *stream)
+{
+    if ((uintptr_t)records_out & 7) return PZL_EINVAL;
+    return launch_q_pack(merged, mask0, mask1, sign0, sign1, rows, cols, records_out, scales_out,
+                         n_non_finite, (hipStream_t)stream);
+}
+
+int pzl_q_unpack(const uint8_t *records, const uint16_t *scales, int expert_pos, int64_t rows,
+                 int64_t cols, float *out, void *stream)
+{
+    return launch_q_unpack(records, scales, expert_pos, rows, cols, out, (hipStream_t)stream);
+}
+
 int pzl_tile_dense(const uint16_t *dense_rowmajor, int64_t rows, int64_t cols, uint16_t *tiled_out,
                    void *stream)
 {

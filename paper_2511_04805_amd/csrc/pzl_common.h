@@ -46,6 +46,15 @@ int launch_merge_pack(const uint16_t *wi, const uint16_t *wj, const float *norm_
                       int64_t rows, int64_t cols, float tau, uint16_t *out, int32_t *n_similar,
                       int32_t *n_bad, hipStream_t st);
 
+// quant_codec.hip
+size_t q_record_bytes(int64_t rows, int64_t cols);
+size_t q_scale_bytes(int64_t rows, int64_t cols);
+int launch_q_pack(const uint16_t *merged, const uint8_t *m0, const uint8_t *m1, const uint8_t *s0,
+                  const uint8_t *s1, int64_t rows, int64_t cols, uint8_t *records, uint16_t *scales,
+                  int32_t *n_bad, hipStream_t st);
+int launch_q_unpack(const uint8_t *records, const uint16_t *scales, int pos, int64_t rows, int64_t cols,
+                    float *out, hipStream_t st);
+
 // route.hip
 int launch_route(const int32_t *ids, int32_t n_flat, int32_t k, int32_t n_experts, int32_t n_slots_q, const int32_t *q_of_expert,
                  RouteTables rt, hipStream_t st);

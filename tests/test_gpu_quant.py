@@ -1,0 +1,81 @@
+"""GPU parity of the quantised variant (appendix "Combining PuzzleMoE with Quantization"):
+the HIP codec through its C ABI against the CPU oracle, bit-exact (codes, scales, signs and the
+base-3 mask numbers are integers; code * scale is exact in fp32)."""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def binding():
+    from paper_2511_04805_amd import binding as b
+    b.load()
+    assert torch.cuda.is_available()
+    return b
+
+
+def say(msg):
+    print(msg, flush=True)
+
+
+def make_case(rows, cols, seed, paper_masks):
+    rng = np.random.RandomState(seed)
+    mag = np.abs(rng.randn(rows, cols)).astype(np.float32) * 0.02
+    merged = (mag.view(np.uint32) >> 16).astype(np.uint16)
+    if paper_masks:
+        t = rng.randint(0, 3, size=(rows, cols))
+        m0 = ((t == 0) | (t == 2)).astype(np.uint8)
+        m1 = ((t == 1) | (t == 2)).astype(np.uint8)
+    else:
+        m0 = rng.randint(0, 2, size=(rows, cols)).astype(np.uint8)
+        m1 = rng.randint(0, 2, size=(rows, cols)).astype(np.uint8)
+    s0 = rng.randint(0, 2, size=(rows, cols)).astype(np.uint8)
+    s1 = rng.randint(0, 2, size=(rows, cols)).astype(np.uint8)
+    return merged, m0, m1, s0, s1
+
+
+@pytest.mark.parametrize("shape,paper_masks", [((16, 128), True), ((48, 384), False), ((256, 1024), True),
+                                               ((1408, 2048), False)])
+def test_q_pack_unpack_bit_exact(oracle, binding, shape, paper_masks):
+    say("q_pack/q_unpack shape=%s paper_masks=%s" % (shape, paper_masks))
+    rows, cols = shape
+    merged, m0, m1, s0, s1 = make_case(rows, cols, seed=rows + cols, paper_masks=paper_masks)
+    # corner cases in the first group: an all-zero second row group, Inf and NaN magnitudes, a
+    # negative input sign (ignored), exact ties of the quotient
+    flat = merged.reshape(-1)
+    flat[:6] = np.array([0x0000, 0x7F80, 0x7FC1, 0xBCA4, 0x3C00, 0x0001], dtype=np.uint16)
+    m0.reshape(-1)[:6] = 1
+    if cols >= 256:
+        merged[0, 128:256] = 0
+    dev = [torch.from_numpy(a.view(np.int16) if a.dtype == np.uint16 else a).cuda() for a in (merged, m0, m1, s0, s1)]
+    n_bad = torch.zeros(1, dtype=torch.int32, device="cuda")
+    records, scales = binding.pzl_q_pack(*dev, n_non_finite=n_bad)
+    torch.cuda.synchronize()
+    q = oracle.q_quantise(merged, m0, m1, s0, s1)
+    assert int(n_bad.item()) == q["n_bad"] == 2
+    assert records.numel() == (rows // 16) * (cols // 32) * 424 + 8
+    got_rec = binding.q_records_to_logical(records.cpu().numpy(), rows, cols)
+    assert np.array_equal(got_rec, oracle.q_records(q))
+    got_sc = binding.q_scales_to_logical(scales.cpu().numpy().view(np.uint16), rows, cols)
+    assert np.array_equal(got_sc, q["scale"])
+    for pos in (0, 1):
+        out = binding.pzl_q_unpack(records, scales, pos, rows, cols)
+        torch.cuda.synchronize()
+        want = oracle.q_dequantise(q, pos)
+        got = out.cpu().numpy().astype(np.float64)
+        assert np.array_equal(got, want)
+    # size of the stored pair against the 16-bit format: (424*8/512 + 16/128) / 16 bits
+    stored = (records.numel() - 8) + scales.numel() * 2
+    assert stored * 8 / (rows * cols) == pytest.approx(2 * oracle.q_bits_per_weight())
+
+
+def test_q_pack_rejects_bad_shapes(binding):
+    for rows, cols in ((16, 96), (8, 128), (0, 128)):
+        merged = torch.zeros(max(rows, 1), max(cols, 1), dtype=torch.int16, device="cuda")
+        planes = [torch.zeros(max(rows, 1), max(cols, 1), dtype=torch.uint8, device="cuda") for _ in range(4)]
+        merged = merged[:rows, :cols].contiguous() if rows and cols else merged
+        with pytest.raises((ValueError, binding.PzlError)):
+            binding.pzl_q_pack(merged.reshape(rows, cols) if rows and cols else merged[:0].reshape(0, 128), *[
+                p[:rows, :cols].contiguous() if rows and cols else p[:0].reshape(0, 128) for p in planes])
