@@ -139,6 +139,13 @@ typedef struct pzl_layer_desc {
     const uint16_t *const *dense_gate;    /* host [n_dense] of device ptrs, tiled dense   */
     const uint16_t *const *dense_up;      /*   bf16 [d_ffn, d_model] (pzl_tile_dense)     */
     const uint16_t *const *dense_down;    /*   bf16 [d_model, d_ffn]                      */
+    int32_t pair_format;            /* 0: 16-bit packed words (pzl_pack / pzl_merge_pack);
+                                       1: quantised records (pzl_q_pack): gate/up/down then point
+                                       to the record arrays and the three tables below to the
+                                       scale arrays; d_model and d_ffn must be multiples of 128 */
+    const uint16_t *const *gate_scale;    /* host [n_pairs] of device ptrs, or NULL (format 0) */
+    const uint16_t *const *up_scale;
+    const uint16_t *const *down_scale;
 } pzl_layer_desc;
 
 typedef struct pzl_layer pzl_layer;
@@ -156,7 +163,10 @@ size_t pzl_moe_ffn_workspace_bytes(const pzl_layer *layer, int32_t max_tokens, i
  * moe_ffn — the routed expert FFN over Eq. 6-decoded weights:
  *   y[t,:] = sum_j topk_w[t,j] * FFN_{topk_ids[t,j]}(x[t,:])  +  sum_s FFN_shared_s(x[t,:])
  *   FFN_e(x) = Wdown_e ( silu(Wgate_e x) * (Wup_e x) ),   silu(g) = g / (1 + exp(-g))
- * with every routed W_e decoded on the fly from its pair's packed tensor (Algorithm 1).
+ * with every routed W_e decoded on the fly from its pair's packed tensor (Algorithm 1), or, for a
+ * layer in the quantised format, reconstructed on the fly as (-1)^S * M * code * scale (the group
+ * scale is applied to the fp32 partial sums of each 128-column group, so code * scale is never
+ * rounded).  Quantised layers always take the weight-streaming kernels.
  * Products are bf16 x bf16 accumulated in fp32; the SwiGLU output is rounded to bf16 once
  * before the down projection; y is rounded to bf16 once at the end.
  *   x         [T, d_model] bf16 bits, row-major

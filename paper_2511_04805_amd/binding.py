@@ -42,7 +42,9 @@ class _LayerDesc(ctypes.Structure):
                 ("shared_gate", ctypes.c_void_p), ("shared_up", ctypes.c_void_p),
                 ("shared_down", ctypes.c_void_p),
                 ("n_dense", ctypes.c_int32), ("dense_gate", ctypes.c_void_p),
-                ("dense_up", ctypes.c_void_p), ("dense_down", ctypes.c_void_p)]
+                ("dense_up", ctypes.c_void_p), ("dense_down", ctypes.c_void_p),
+                ("pair_format", ctypes.c_int32), ("gate_scale", ctypes.c_void_p),
+                ("up_scale", ctypes.c_void_p), ("down_scale", ctypes.c_void_p)]
 
 
 def load():
@@ -239,11 +241,17 @@ def _ptr_table(tensors):
 class Layer:
     """Owns a pzl_layer handle and keeps the weight tensors it references alive."""
 
-    def __init__(self, d_model, d_ffn, expert_pair, expert_pos, gate, up, down, shared=(), dense=()):
-        """gate/up/down: one packed tensor per pair; shared: (gate, up, down, f) tiled dense per shared
-        expert; dense: (gate, up, down) tiled dense per routed expert kept unmerged."""
+    def __init__(self, d_model, d_ffn, expert_pair, expert_pos, gate, up, down, shared=(), dense=(),
+                 quantised=False):
+        """gate/up/down: one packed tensor per pair -- or, with quantised=True, one (records, scales)
+        pair of tensors per pair as returned by pzl_q_pack; shared: (gate, up, down, f) tiled dense
+        per shared expert; dense: (gate, up, down) tiled dense per routed expert kept unmerged."""
         self.d_model, self.d_ffn = int(d_model), int(d_ffn)
-        self._keep = (list(gate), list(up), list(down), [tuple(s) for s in shared], [tuple(s) for s in dense])
+        scales = None
+        if quantised:
+            scales = [[t[1] for t in ws] for ws in (gate, up, down)]
+            gate, up, down = ([t[0] for t in ws] for ws in (gate, up, down))
+        self._keep = (list(gate), list(up), list(down), [tuple(s) for s in shared], [tuple(s) for s in dense], scales)
         pair = np.ascontiguousarray(expert_pair, dtype=np.int32)
         pos = np.ascontiguousarray(expert_pos, dtype=np.uint8)
         P = len(gate)
@@ -252,6 +260,11 @@ class Layer:
             if len(ws) != P:
                 raise ValueError("need one %s tensor per pair" % name)
             for t in ws:
+                if quantised:
+                    _dev(t, (torch.uint8,), name)
+                    if t.numel() != shape // 512 * 424 + 8:
+                        raise ValueError("%s record array has the wrong size" % name)
+                    continue
                 _dev(t, _BITS16, name)
                 if t.numel() != shape:
                     raise ValueError("%s tensor has the wrong size" % name)
@@ -283,6 +296,15 @@ class Layer:
         d.n_dense = len(dense)
         d.dense_gate, d.dense_up, d.dense_down = (cast(self._tables[9]), cast(self._tables[10]),
                                                   cast(self._tables[11]))
+        if quantised:
+            for ws in scales:
+                for t in ws:
+                    _dev(t, _BITS16, "scale array")
+                    if t.numel() != d_ffn * d_model // 128:
+                        raise ValueError("scale array has the wrong size")
+            self._scale_tables = tuple(_ptr_table(ws) for ws in scales)
+            d.pair_format = 1
+            d.gate_scale, d.up_scale, d.down_scale = (cast(t) for t in self._scale_tables)
         self._h = ctypes.c_void_p()
         _check(load().pzl_layer_create(ctypes.byref(d), ctypes.byref(self._h)), "pzl_layer_create")
         self._ws = None

@@ -28,6 +28,8 @@ struct pzl_layer {
     // device tables
     int32_t *d_q_of_expert;                // [E] expert -> 2*pair + pos
     const uint16_t **d_gate, **d_up, **d_down;            // [P]
+    int32_t pair_format;                   // 0: 16-bit packed words, 1: quantised records
+    const uint16_t **d_gscale, **d_uscale, **d_dscale;    // [P] scale arrays (quantised format)
     const uint16_t **d_dgate, **d_dup, **d_ddown;         // [n_dense] routed experts kept unmerged
     const uint16_t **d_sgate, **d_sup, **d_sdown;         // [n_shared]
     void *d_block;                         // the one allocation holding all of the above
@@ -194,6 +196,10 @@ int pzl_layer_create(const pzl_layer_desc *desc, pzl_layer **out)
     if (!desc->expert_pair || !desc->expert_pos) return PZL_EINVAL;
     if (P > 0 && (!desc->gate || !desc->up || !desc->down)) return PZL_EINVAL;
     if (D > 0 && (!desc->dense_gate || !desc->dense_up || !desc->dense_down)) return PZL_EINVAL;
+    const int fmt = desc->pair_format;
+    if (fmt != 0 && fmt != 1) return PZL_EINVAL;
+    if (fmt == 1 && P > 0 && (d % 128 || f % 128 || !desc->gate_scale || !desc->up_scale || !desc->down_scale))
+        return PZL_EINVAL;
     if (S < 0 || S > 16) return PZL_EINVAL;
     if (S > 0 && (!desc->shared_d_ffn || !desc->shared_gate || !desc->shared_up || !desc->shared_down))
         return PZL_EINVAL;
@@ -215,8 +221,10 @@ int pzl_layer_create(const pzl_layer_desc *desc, pzl_layer **out)
         seen[q] = 1;
         q_of[e] = q;
     }
-    for (int p = 0; p < P; ++p)
+    for (int p = 0; p < P; ++p) {
         if (!desc->gate[p] || !desc->up[p] || !desc->down[p]) return PZL_EINVAL;
+        if (fmt == 1 && (!desc->gate_scale[p] || !desc->up_scale[p] || !desc->down_scale[p])) return PZL_EINVAL;
+    }
     for (int j = 0; j < D; ++j)
         if (!desc->dense_gate[j] || !desc->dense_up[j] || !desc->dense_down[j]) return PZL_EINVAL;
     for (int s = 0; s < S; ++s) {
@@ -229,19 +237,24 @@ int pzl_layer_create(const pzl_layer_desc *desc, pzl_layer **out)
     if (!L) return PZL_ENOMEM;
     L->n_experts = E; L->n_pairs = P; L->n_dense = D; L->d_model = d; L->d_ffn = f; L->n_shared = S;
     L->n_q = 2 * (P + D);
+    L->pair_format = fmt;
     L->shared_f.assign(desc->shared_d_ffn, desc->shared_d_ffn + S);
 
     const size_t sz_q = align_up((size_t)E * 4, 256);
     const size_t sz_p = align_up((size_t)(P > 0 ? P : 1) * sizeof(void *), 256);
     const size_t sz_s = align_up((size_t)(S > 0 ? S : 1) * sizeof(void *), 256);
     const size_t sz_d = align_up((size_t)(D > 0 ? D : 1) * sizeof(void *), 256);
-    const size_t total = sz_q + 3 * sz_p + 3 * sz_s + 3 * sz_d;
+    const size_t total = sz_q + 6 * sz_p + 3 * sz_s + 3 * sz_d;
     std::vector<unsigned char> host(total, 0);
     size_t o = 0;
     memcpy(&host[o], q_of.data(), (size_t)E * 4);                     size_t o_q = o;  o += sz_q;
     size_t o_g = o; if (P) memcpy(&host[o], desc->gate, (size_t)P * sizeof(void *)); o += sz_p;
     size_t o_u = o; if (P) memcpy(&host[o], desc->up, (size_t)P * sizeof(void *));   o += sz_p;
     size_t o_d = o; if (P) memcpy(&host[o], desc->down, (size_t)P * sizeof(void *)); o += sz_p;
+    const bool q = fmt == 1 && P > 0;
+    size_t o_gs = o; if (q) memcpy(&host[o], desc->gate_scale, (size_t)P * sizeof(void *)); o += sz_p;
+    size_t o_us = o; if (q) memcpy(&host[o], desc->up_scale, (size_t)P * sizeof(void *));   o += sz_p;
+    size_t o_ds = o; if (q) memcpy(&host[o], desc->down_scale, (size_t)P * sizeof(void *)); o += sz_p;
     size_t o_dg = o; if (D) memcpy(&host[o], desc->dense_gate, (size_t)D * sizeof(void *)); o += sz_d;
     size_t o_du = o; if (D) memcpy(&host[o], desc->dense_up, (size_t)D * sizeof(void *));   o += sz_d;
     size_t o_dd = o; if (D) memcpy(&host[o], desc->dense_down, (size_t)D * sizeof(void *)); o += sz_d;
@@ -258,6 +271,9 @@ int pzl_layer_create(const pzl_layer_desc *desc, pzl_layer **out)
     L->d_gate = (const uint16_t **)(base + o_g);
     L->d_up = (const uint16_t **)(base + o_u);
     L->d_down = (const uint16_t **)(base + o_d);
+    L->d_gscale = (const uint16_t **)(base + o_gs);
+    L->d_uscale = (const uint16_t **)(base + o_us);
+    L->d_dscale = (const uint16_t **)(base + o_ds);
     L->d_dgate = (const uint16_t **)(base + o_dg);
     L->d_dup = (const uint16_t **)(base + o_du);
     L->d_ddown = (const uint16_t **)(base + o_dd);
@@ -331,12 +347,14 @@ int pzl_moe_ffn_staged(const pzl_layer *L, const uint16_t *x, const int32_t *top
     // Path choice (host side, from the batch shape only): with few tokens per expert the layer
     // is bound by streaming the packed weights once (streaming kernels); with many it is a
     // dense contraction (tiled kernels on the matrix cores).
-    const bool tiled = (int64_t)N >= (int64_t)TILED_MIN_TOKENS_PER_EXPERT * L->n_experts;
+    // (quantised pairs have no tiled kernel: they always stream)
+    const bool tiled = L->pair_format == 0 && (int64_t)N >= (int64_t)TILED_MIN_TOKENS_PER_EXPERT * L->n_experts;
     const bool tiled_shared = T >= TILED_MIN_TOKENS_SHARED;
     const int routed_groups = L->n_pairs + L->n_dense;
     const int groups_max = (int)((int64_t)N < routed_groups ? N : routed_groups);   // groups that can have tokens
-    const int ksplit = tiled ? choose_tile_ksplit(N / TILE_MAX_TOKENS + L->n_experts / 2, L->d_model, L->d_ffn)
-                             : choose_ksplit(groups_max > 0 ? groups_max : 1, L->d_model);
+    int ksplit = tiled ? choose_tile_ksplit(N / TILE_MAX_TOKENS + L->n_experts / 2, L->d_model, L->d_ffn)
+                       : choose_ksplit(groups_max > 0 ? groups_max : 1, L->d_model);
+    if (L->pair_format == 1 && ksplit > L->d_ffn / 128) ksplit = L->d_ffn / 128;   // whole 128-column groups per split
     // one k-split count for all shared experts (the combine step sums that many partials); sized
     // for the usual case, all of them of one width and hence in one launch per stage
     const int ns = L->n_shared > 0 ? L->n_shared : 1;
@@ -356,7 +374,7 @@ int pzl_moe_ffn_staged(const pzl_layer *L, const uint16_t *x, const int32_t *top
         const bool unmerged = pass == 1;
         const int n_groups = unmerged ? L->n_dense : L->n_pairs;
         if (n_groups == 0) continue;
-        const int kind = unmerged ? KIND_UNMERGED : KIND_PACKED;
+        const int kind = unmerged ? KIND_UNMERGED : (L->pair_format == 1 ? KIND_QUANT : KIND_PACKED);
         const uint16_t *const *wg = unmerged ? L->d_dgate : L->d_gate;
         const uint16_t *const *wu = unmerged ? L->d_dup : L->d_up;
         const uint16_t *const *wd = unmerged ? L->d_ddown : L->d_down;
@@ -392,6 +410,7 @@ int pzl_moe_ffn_staged(const pzl_layer *L, const uint16_t *x, const int32_t *top
             a.cnt = rt.cnt; a.off = rt.off; a.slot_tok = rt.slot_tok;
             // gate/up + SwiGLU -> H
             a.w_a = wg; a.w_b = wu;
+            if (kind == KIND_QUANT) { a.s_a = L->d_gscale; a.s_b = L->d_uscale; }
             a.rows = L->d_ffn; a.kdim = L->d_model; a.ksplit = 1;
             a.act = x; a.act_is_x = 1; a.act_slot_base = 0;
             a.h_out = h_routed; a.h_slot_base = 0; a.h_plane_stride = h_plane;
@@ -401,6 +420,7 @@ int pzl_moe_ffn_staged(const pzl_layer *L, const uint16_t *x, const int32_t *top
             if (timed && (rc = mark(PZL_STAGE_GATEUP, 1))) return rc;
             // down -> partial sums
             a.w_a = wd; a.w_b = nullptr;
+            if (kind == KIND_QUANT) { a.s_a = L->d_dscale; a.s_b = nullptr; }
             a.rows = L->d_model; a.kdim = L->d_ffn; a.ksplit = ksplit;
             a.act = h_routed; a.act_is_x = 0; a.act_slot_base = 0; a.act_plane_stride = h_plane;
             a.h_out = nullptr; a.o_out = opart; a.o_ks_stride = w.o_ks_stride;

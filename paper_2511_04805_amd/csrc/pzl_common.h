@@ -68,6 +68,8 @@ int launch_combine(const float *opart, int32_t ksplit, int32_t ksplit_shared, in
 struct StreamGroupArgs {
     const uint16_t *const *w_a;   // device array [n_groups]: gate (gate/up stage) or down (down stage)
     const uint16_t *const *w_b;   // device array [n_groups]: up, or nullptr in the down stage
+    const uint16_t *const *s_a;   // quantised pairs only: the scale arrays of w_a / w_b
+    const uint16_t *const *s_b;
     int32_t n_groups;
     int32_t groups_touched_max;   // upper bound on groups that can have tokens (0 = all)
     int32_t rows;                 // output features of the stage (f or d)
@@ -95,7 +97,7 @@ int stream_row_groups(int rows, bool down_stage);   // row groups (workgroup uni
 #endif
 constexpr int STREAM_RESIDENT_WGS = 2048 / SG_WAVES_N;             // workgroups the chip holds at once (256 CUs x 2)
 // kind: 0 packed pairs, 1 dense experts seeing every token (shared), 2 dense routed experts
-constexpr int KIND_PACKED = 0, KIND_SHARED = 1, KIND_UNMERGED = 2;
+constexpr int KIND_PACKED = 0, KIND_SHARED = 1, KIND_UNMERGED = 2, KIND_QUANT = 3;
 int launch_stream_gateup(const StreamGroupArgs &a, int kind, hipStream_t st);
 int launch_stream_down(const StreamGroupArgs &a, int kind, hipStream_t st);
 

@@ -49,6 +49,8 @@ constexpr int SG_RESIDENT_WGS = 2048 / SG_WAVES;   // 256 CUs x 8 waves
 struct SgArgs {
     const uint16_t *const *w_a;
     const uint16_t *const *w_b;
+    const uint16_t *const *s_a;  // quantised pairs: scale arrays of w_a / w_b
+    const uint16_t *const *s_b;
     int32_t rows, kdim, ksplit, rg_per_wg;
     const uint16_t *act;
     int64_t act_plane_stride;
@@ -108,11 +110,102 @@ __device__ __forceinline__ void swiglu_split(float g, float u, uint32_t &hi, uin
     lo = f32_to_bf16_rne_sg(h - __uint_as_float(hi << 16));
 }
 
+
+// ---- quantised pairs (3-bit codes, group scales, base-3 masks) --------------------------------
+// The appendix on combining the method with quantisation stores, per element, a 3-bit magnitude
+// code, two sign bits and which expert(s) use it; here 8 elements make one 53-bit record (layout
+// in quant_codec.hip).  Decoding with arithmetic would cost more vector instructions than the
+// packed bytes leave time for, so it is table-driven; the tables live in LDS, built by every
+// workgroup at start:
+//   lut_t[13-bit mask number] -> the 8 mask bits of position 0 (low byte) and of position 1
+//   lut_mask[byte]  -> 4 dwords, 0xFFFF in each half whose bit is set
+//   lut_sign[byte]  -> 4 dwords, bit 15 / bit 31 set where the bit is set
+//   lut_mag[6 bits: two codes] -> the two codes as bf16 (0..7 are exact)
+// A decoded fragment holds +-code (or 0); the group scale multiplies the accumulated products
+// of each 128-column group afterwards, in fp32, so nothing is rounded that the definition
+// (code * scale, exactly) does not round.
+constexpr int Q_TILE_BYTES = 424;
+constexpr int Q_LUT_T = 8192;
+constexpr int Q_LUT_BYTES = Q_LUT_T * 2 + 256 * 16 * 2 + 64 * 4;
+
+struct QLuts {
+    const uint16_t *t;
+    const u32x4 *mask, *sign;
+    const uint32_t *mag;
+};
+
+__device__ __forceinline__ void q_build_luts(unsigned char *base, QLuts &l)
+{
+    uint16_t *t = (uint16_t *)base;
+    u32x4 *mask = (u32x4 *)(base + Q_LUT_T * 2);
+    u32x4 *sign = mask + 256;
+    uint32_t *mag = (uint32_t *)(sign + 256);
+    for (int v = threadIdx.x; v < Q_LUT_T; v += SG_THREADS) {
+        uint32_t r = v, m0 = 0, m1 = 0;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            uint32_t d = r % 3u;
+            r /= 3u;
+            m0 |= (d != 1u ? 1u : 0u) << e;          // digit 0 or 2: position 0 uses the element
+            m1 |= (d != 0u ? 1u : 0u) << e;          // digit 1 or 2: position 1 uses it
+        }
+        t[v] = (uint16_t)(v < 6561 ? (m0 | m1 << 8) : 0u);
+    }
+    if (threadIdx.x < 256) {
+        uint32_t b = threadIdx.x;
+        u32x4 mk, sg;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            uint32_t lo = (b >> (2 * i)) & 1u, hi = (b >> (2 * i + 1)) & 1u;
+            mk[i] = (lo ? 0x0000FFFFu : 0u) | (hi ? 0xFFFF0000u : 0u);
+            sg[i] = lo << 15 | hi << 31;
+        }
+        mask[b] = mk;
+        sign[b] = sg;
+    }
+    if (threadIdx.x < 64) {
+        uint32_t ca = threadIdx.x & 7u, cb = threadIdx.x >> 3;
+        mag[threadIdx.x] = (__float_as_uint((float)ca) >> 16) | (__float_as_uint((float)cb) & 0xFFFF0000u);
+    }
+    l.t = t; l.mask = mask; l.sign = sign; l.mag = mag;
+}
+
+struct QRecord {
+    u32x4 mag;
+    uint32_t s0, s1, mm;
+};
+
+__device__ __forceinline__ QRecord q_split(uint64_t raw, int shift, const QLuts &l)
+{
+    uint64_t r = raw >> shift;
+    uint32_t lo = (uint32_t)r, hi = (uint32_t)(r >> 32);
+    QRecord q;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) q.mag[i] = l.mag[(lo >> (6 * i)) & 63u];
+    q.s0 = lo >> 24;
+    q.s1 = hi & 0xFFu;
+    q.mm = l.t[(hi >> 8) & 0x1FFFu];
+    return q;
+}
+
+template <int POS>
+__device__ __forceinline__ bf16x8 q_frag(const QRecord &q, const QLuts &l)
+{
+    u32x4 sg = l.sign[POS ? q.s1 : q.s0];
+    u32x4 mk = l.mask[POS ? (q.mm >> 8) : (q.mm & 0xFFu)];
+    u32x4 o;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) o[i] = (q.mag[i] | sg[i]) & mk[i];
+    return __builtin_bit_cast(bf16x8, o);
+}
+
 // One pass: NT0 token tiles of position 0 followed by NT1 tiles of position 1.
 // DENSE: the weights are plain bf16 (identity decode).  ALLTOK: the group sees every token
 // (a shared expert) instead of a routed slot range.
-template <int STAGE, bool DENSE, bool ALLTOK, int NT0, int NT1>
+// QUANT: the weights are quantised records (see above) instead of 16-bit words.
+template <int STAGE, bool DENSE, bool ALLTOK, bool QUANT, int NT0, int NT1>
 __device__ __forceinline__ void stream_pass(const SgArgs &a, const uint16_t *wa, const uint16_t *wb,
+                                            const uint16_t *sa, const uint16_t *sb, const QLuts &luts,
                                             int rt0, int rt1, bool active0, bool active1,
                                             int kb0, int kb1, int ks,
                                             int base0, int n0, int tile0, int base1, int n1, int tile1,
@@ -143,10 +236,14 @@ __device__ __forceinline__ void stream_pass(const SgArgs &a, const uint16_t *wa,
     __syncthreads();
 
     f32x4 acc[2][NT];
+    f32x4 accg[2][QUANT ? NT : 1];      // QUANT: products of the current 128-column group, unscaled
 #pragma unroll
     for (int m = 0; m < 2; ++m)
 #pragma unroll
-        for (int n = 0; n < NT; ++n) acc[m][n] = (f32x4){0.f, 0.f, 0.f, 0.f};
+        for (int n = 0; n < NT; ++n) {
+            acc[m][n] = (f32x4){0.f, 0.f, 0.f, 0.f};
+            if (QUANT) accg[m][n] = (f32x4){0.f, 0.f, 0.f, 0.f};
+        }
 
     // The weight pointers come out of a device-side table, so the compiler cannot see that they
     // are global; say so, or it emits flat loads, which also tick the LDS counter.
@@ -154,18 +251,45 @@ __device__ __forceinline__ void stream_pass(const SgArgs &a, const uint16_t *wa,
     gvec_ptr wp[2];
     wp[0] = (gvec_ptr)(uintptr_t)wa + ((int64_t)rt0 * kb_total + kb0) * 64 + lane;
     wp[1] = (gvec_ptr)(uintptr_t)wb + ((int64_t)rt1 * kb_total + kb0) * 64 + lane;
+    // QUANT: a tile is 424 bytes; lane l's 53-bit record starts at bit 53*l: one unaligned
+    // 8-byte load at byte 53*l/8, shifted right by 53*l%8
+    typedef uint64_t __attribute__((aligned(1))) u64_unaligned;
+    typedef const u64_unaligned __attribute__((address_space(1))) *gq_ptr;
+    typedef const unsigned char __attribute__((address_space(1))) *gbyte_ptr;
+    gbyte_ptr qp[2];
+    qp[0] = (gbyte_ptr)(uintptr_t)wa + ((int64_t)rt0 * kb_total + kb0) * Q_TILE_BYTES + ((53 * lane) >> 3);
+    qp[1] = (gbyte_ptr)(uintptr_t)wb + ((int64_t)rt1 * kb_total + kb0) * Q_TILE_BYTES + ((53 * lane) >> 3);
+    const int qshift = (53 * lane) & 7;
+    // ... and the scales of the 4 accumulator rows of this lane, one 128-column group ahead
+    typedef const u32x2 __attribute__((address_space(1))) *gsc_ptr;
+    const int n_qgroups = kb_total / 4;
+    gsc_ptr sp[2];
+    sp[0] = (gsc_ptr)(uintptr_t)(sa + ((int64_t)rt0 * n_qgroups) * TILE_ROWS + (lane >> 4) * 4);
+    sp[1] = (gsc_ptr)(uintptr_t)(sb + ((int64_t)rt1 * n_qgroups) * TILE_ROWS + (lane >> 4) * 4);
+    auto load_scale = [&](int m, int kb_abs) {
+        int gi = min(kb_abs / 4, n_qgroups - 1);
+        return sp[m][gi * (TILE_ROWS * 2 / 8)];                  // 16 bf16 = 4 x 8 bytes per group
+    };
+    u32x2 sc_cur[2] = {{0u, 0u}, {0u, 0u}}, sc_nxt[2] = {{0u, 0u}, {0u, 0u}};
+    if (QUANT) {
+#pragma unroll
+        for (int m = 0; m < 2; ++m) { sc_cur[m] = load_scale(m, kb0); sc_nxt[m] = load_scale(m, kb0 + 4); }
+    }
 
     // Weight loads are never predicated (a branch per load would make the compiler drain the
     // whole load queue at every barrier): a k-block past the end re-reads the last valid one,
     // and contributes nothing because its staged activations are zero.
     const u32x4 zero4 = {0u, 0u, 0u, 0u};
     const int kb_last = kb1 - 1 - kb0;
-    u32x4 wbuf[2][DEPTH];
+    u32x4 wbuf[2][QUANT ? 1 : DEPTH];
+    uint64_t qbuf[2][QUANT ? DEPTH : 1];
 #pragma unroll
     for (int s = 0; s < DEPTH; ++s)
 #pragma unroll
-        for (int m = 0; m < 2; ++m)
-            wbuf[m][s] = __builtin_nontemporal_load(wp[m] + (int64_t)min(s, kb_last) * 64);
+        for (int m = 0; m < 2; ++m) {
+            if (QUANT) qbuf[m][s] = *(gq_ptr)(qp[m] + (int64_t)min(s, kb_last) * Q_TILE_BYTES);
+            else       wbuf[m][s] = __builtin_nontemporal_load(wp[m] + (int64_t)min(s, kb_last) * 64);
+        }
 
     // activation fragments this thread stages per chunk: fragment f = wave + 4*i,
     // (column, k-block) = (f / KCB, f % KCB), column = tile * PARTS + plane
@@ -206,38 +330,66 @@ __device__ __forceinline__ void stream_pass(const SgArgs &a, const uint16_t *wa,
 #pragma unroll
         for (int s = 0; s < KCB; ++s) {
             u32x4 wv[2];
+            QRecord qr[2];
 #pragma unroll
-            for (int m = 0; m < 2; ++m) wv[m] = wbuf[m][s % DEPTH];
+            for (int m = 0; m < 2; ++m) {
+                if (QUANT) qr[m] = q_split(qbuf[m][s % DEPTH], qshift, luts);
+                else       wv[m] = wbuf[m][s % DEPTH];
+            }
             const u32x4 *xf = xs + (buf * SG_FRAGS + s) * 64 + lane;
             if (NT0 > 0) {
                 bf16x8 wd[2];
 #pragma unroll
-                for (int m = 0; m < 2; ++m) wd[m] = decode_frag<0, DENSE>(wv[m]);
+                for (int m = 0; m < 2; ++m) wd[m] = QUANT ? q_frag<0>(qr[m], luts) : decode_frag<0, DENSE>(wv[m]);
 #pragma unroll
                 for (int c = 0; c < NT0 * PARTS; ++c) {
                     bf16x8 b = __builtin_bit_cast(bf16x8, xf[c * KCB * 64]);
 #pragma unroll
-                    for (int m = 0; m < 2; ++m)
-                        acc[m][c / PARTS] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wd[m], b, acc[m][c / PARTS], 0, 0, 0);
+                    for (int m = 0; m < 2; ++m) {
+                        f32x4 &dst = QUANT ? accg[m][QUANT ? c / PARTS : 0] : acc[m][c / PARTS];
+                        dst = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wd[m], b, dst, 0, 0, 0);
+                    }
                 }
             }
             if (NT1 > 0) {
                 bf16x8 wd[2];
 #pragma unroll
-                for (int m = 0; m < 2; ++m) wd[m] = decode_frag<1, DENSE>(wv[m]);
+                for (int m = 0; m < 2; ++m) wd[m] = QUANT ? q_frag<1>(qr[m], luts) : decode_frag<1, DENSE>(wv[m]);
 #pragma unroll
                 for (int c = NT0 * PARTS; c < VT; ++c) {
                     bf16x8 b = __builtin_bit_cast(bf16x8, xf[c * KCB * 64]);
 #pragma unroll
-                    for (int m = 0; m < 2; ++m)
-                        acc[m][c / PARTS] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wd[m], b, acc[m][c / PARTS], 0, 0, 0);
+                    for (int m = 0; m < 2; ++m) {
+                        f32x4 &dst = QUANT ? accg[m][QUANT ? c / PARTS : 0] : acc[m][c / PARTS];
+                        dst = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wd[m], b, dst, 0, 0, 0);
+                    }
+                }
+            }
+            if (QUANT && s % 4 == 3) {
+                // end of a 128-column group: scale its products (rows 4*(lane/16)..+3 of the tile)
+#pragma unroll
+                for (int m = 0; m < 2; ++m) {
+                    float f0 = __uint_as_float(sc_cur[m][0] << 16), f1 = __uint_as_float(sc_cur[m][0] & 0xFFFF0000u);
+                    float f2 = __uint_as_float(sc_cur[m][1] << 16), f3 = __uint_as_float(sc_cur[m][1] & 0xFFFF0000u);
+#pragma unroll
+                    for (int n = 0; n < NT; ++n) {
+                        f32x4 &g = accg[m][QUANT ? n : 0];
+                        acc[m][n][0] = fmaf(f0, g[0], acc[m][n][0]);
+                        acc[m][n][1] = fmaf(f1, g[1], acc[m][n][1]);
+                        acc[m][n][2] = fmaf(f2, g[2], acc[m][n][2]);
+                        acc[m][n][3] = fmaf(f3, g[3], acc[m][n][3]);
+                        g = (f32x4){0.f, 0.f, 0.f, 0.f};
+                    }
+                    sc_cur[m] = sc_nxt[m];
+                    sc_nxt[m] = load_scale(m, kb + s + 5);       // the group after the next one
                 }
             }
             // refill the slot just consumed
 #pragma unroll
             for (int m = 0; m < 2; ++m) {
                 int kbn = min(kb + DEPTH + s - kb0, kb_last);
-                wbuf[m][s % DEPTH] = __builtin_nontemporal_load(wp[m] + (int64_t)kbn * 64);
+                if (QUANT) qbuf[m][s % DEPTH] = *(gq_ptr)(qp[m] + (int64_t)kbn * Q_TILE_BYTES);
+                else       wbuf[m][s % DEPTH] = __builtin_nontemporal_load(wp[m] + (int64_t)kbn * 64);
             }
 #if SG_SCHED_BARRIER
             // keep each step's refill inside the step: the scheduler otherwise sinks all loads
@@ -277,13 +429,15 @@ __device__ __forceinline__ void stream_pass(const SgArgs &a, const uint16_t *wa,
     }
 }
 
-template <int STAGE, bool DENSE, bool ALLTOK>
+template <int STAGE, bool DENSE, bool ALLTOK, bool QUANT>
 __global__ void __launch_bounds__(SG_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2)))
 stream_kernel(SgArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
     u32x4 *xs = (u32x4 *)lds_raw;
     int32_t *rowidx = (int32_t *)(lds_raw + SG_LDS_BYTES);
+    QLuts luts = {nullptr, nullptr, nullptr, nullptr};
+    if (QUANT) q_build_luts(lds_raw + SG_LDS_BYTES + SG_MAX_TILES * 16 * sizeof(int32_t), luts);   // visible after the pass's first barrier
 
     constexpr int RT_PER_WAVE = (STAGE == STAGE_DOWN) ? 2 : 1;
     const int row_tiles = a.rows / TILE_ROWS;
@@ -312,10 +466,14 @@ stream_kernel(SgArgs a)
 
     const int wave = threadIdx.x >> 6;
     const int kb_total = a.kdim / TILE_COLS;
-    const int kb0 = (int)((int64_t)ks * kb_total / a.ksplit);
-    const int kb1 = (int)((int64_t)(ks + 1) * kb_total / a.ksplit);
+    // K splits: whole k-blocks; for quantised weights whole 128-column groups (4 k-blocks)
+    const int kq = QUANT ? 4 : 1;
+    const int kb0 = (int)((int64_t)ks * (kb_total / kq) / a.ksplit) * kq;
+    const int kb1 = (int)((int64_t)(ks + 1) * (kb_total / kq) / a.ksplit) * kq;
     const uint16_t *wa = a.w_a[g];
     const uint16_t *wb = (STAGE == STAGE_GATEUP) ? a.w_b[g] : wa;
+    const uint16_t *sa = QUANT ? a.s_a[g] : nullptr;
+    const uint16_t *sb = QUANT ? ((STAGE == STAGE_GATEUP) ? a.s_b[g] : sa) : nullptr;
     constexpr int PT = DENSE ? SG_MAX_TILES : SG_POS_TILES;   // a dense group has one position only
     const int tiles0 = (n0 + 15) >> 4, tiles1 = (n1 + 15) >> 4;
 
@@ -329,8 +487,8 @@ stream_kernel(SgArgs a)
         int c0 = min(PT, max(tiles0 - t0, 0));
         int c1 = min(PT, max(tiles1 - t1, 0));
 #define PZL_PASS(A, B)                                                                              \
-    stream_pass<STAGE, DENSE, ALLTOK, A, B>(a, wa, wb, rt0, rt1, active0, active1, kb0, kb1, ks, base0, n0, \
-                                    t0, base1, n1, t1, xs, rowidx)
+    stream_pass<STAGE, DENSE, ALLTOK, QUANT, A, B>(a, wa, wb, sa, sb, luts, rt0, rt1, active0, active1, kb0, kb1, ks, \
+                                                   base0, n0, t0, base1, n1, t1, xs, rowidx)
         if (DENSE) {
             switch (c0) {
                 case 1: PZL_PASS(1, 0); break;
@@ -362,13 +520,16 @@ int stream_row_groups(int rows, bool down_stage)
     return (rows / TILE_ROWS + per_wg - 1) / per_wg;
 }
 
-template <int STAGE, bool DENSE, bool ALLTOK>
+template <int STAGE, bool DENSE, bool ALLTOK, bool QUANT>
 static int launch(const StreamGroupArgs &g, hipStream_t st)
 {
     if (g.n_groups <= 0) return PZL_OK;
     if (g.rows % TILE_ROWS || g.kdim % TILE_COLS || g.ksplit < 1) return PZL_EINVAL;
+    if (QUANT && (g.kdim % 128 || !g.s_a || (STAGE == STAGE_GATEUP && !g.s_b))) return PZL_EINVAL;
     SgArgs a;
     a.w_a = g.w_a; a.w_b = g.w_b; a.rows = g.rows; a.kdim = g.kdim; a.ksplit = g.ksplit;
+    a.s_a = g.s_a; a.s_b = g.s_b;
+    if (QUANT && a.ksplit > g.kdim / 128) return PZL_EINVAL;    // a K split holds whole 128-column groups
     a.act = g.act; a.act_plane_stride = g.act_plane_stride;
     a.act_is_x = g.act_is_x; a.act_slot_base = g.act_slot_base;
     a.cnt = g.cnt; a.off = g.off; a.slot_tok = g.slot_tok; a.group_base = g.group_base;
@@ -390,34 +551,36 @@ static int launch(const StreamGroupArgs &g, hipStream_t st)
     a.rg_per_wg = rg_per_wg;
     const int64_t blocks = (int64_t)g.n_groups * ((row_groups + rg_per_wg - 1) / rg_per_wg) * g.ksplit * a.n_passes;
     if (blocks > 0x7FFFFFFFLL) return PZL_EINVAL;
-    const size_t lds = SG_LDS_BYTES + SG_MAX_TILES * 16 * sizeof(int32_t);
+    const size_t lds = SG_LDS_BYTES + SG_MAX_TILES * 16 * sizeof(int32_t) + (QUANT ? Q_LUT_BYTES : 0);
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)stream_kernel<STAGE, DENSE, ALLTOK>,
+        hipError_t e = hipFuncSetAttribute((const void *)stream_kernel<STAGE, DENSE, ALLTOK, QUANT>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) { set_hip_error(e); return PZL_EHIP; }
         attr_set = true;
     }
-    hipLaunchKernelGGL((stream_kernel<STAGE, DENSE, ALLTOK>), dim3((unsigned)blocks), dim3(SG_THREADS), lds, st, a);
+    hipLaunchKernelGGL((stream_kernel<STAGE, DENSE, ALLTOK, QUANT>), dim3((unsigned)blocks), dim3(SG_THREADS), lds, st, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) { set_hip_error(e); return PZL_EHIP; }
     return PZL_OK;
 }
 
 // kind: 0 = packed pairs (routed), 1 = dense experts that see every token (shared),
-//       2 = dense routed experts (kept unmerged)
+//       2 = dense routed experts (kept unmerged), 3 = quantised pairs (routed)
 int launch_stream_gateup(const StreamGroupArgs &a, int kind, hipStream_t st)
 {
-    if (kind == 0) return launch<STAGE_GATEUP, false, false>(a, st);
-    if (kind == 1) return launch<STAGE_GATEUP, true, true>(a, st);
-    return launch<STAGE_GATEUP, true, false>(a, st);
+    if (kind == 0) return launch<STAGE_GATEUP, false, false, false>(a, st);
+    if (kind == 1) return launch<STAGE_GATEUP, true, true, false>(a, st);
+    if (kind == 3) return launch<STAGE_GATEUP, false, false, true>(a, st);
+    return launch<STAGE_GATEUP, true, false, false>(a, st);
 }
 
 int launch_stream_down(const StreamGroupArgs &a, int kind, hipStream_t st)
 {
-    if (kind == 0) return launch<STAGE_DOWN, false, false>(a, st);
-    if (kind == 1) return launch<STAGE_DOWN, true, true>(a, st);
-    return launch<STAGE_DOWN, true, false>(a, st);
+    if (kind == 0) return launch<STAGE_DOWN, false, false, false>(a, st);
+    if (kind == 1) return launch<STAGE_DOWN, true, true, false>(a, st);
+    if (kind == 3) return launch<STAGE_DOWN, false, false, true>(a, st);
+    return launch<STAGE_DOWN, true, false, false>(a, st);
 }
 
 }  // namespace pzl

@@ -79,3 +79,91 @@ def test_q_pack_rejects_bad_shapes(binding):
         with pytest.raises((ValueError, binding.PzlError)):
             binding.pzl_q_pack(merged.reshape(rows, cols) if rows and cols else merged[:0].reshape(0, 128), *[
                 p[:rows, :cols].contiguous() if rows and cols else p[:0].reshape(0, 128) for p in planes])
+
+
+# ---------- the expert FFN over quantised pairs ----------
+
+from paper_2511_04805_amd import synth                      # noqa: E402
+from helpers import tolerance_ok                             # noqa: E402
+
+W3 = (synth.GATE, synth.UP, synth.DOWN)
+
+
+class QCase:
+    """One quantised layer: the oracle's reconstructed fp64 experts and the library's Layer."""
+
+    def __init__(self, cfg, oracle, binding, needed_experts=None):
+        self.cfg, self.oracle, self.binding = cfg, oracle, binding
+        self.emap = synth.expert_map(cfg, "adjacent")
+        pair_of, pos_of = self.emap
+        needed = set(range(cfg.n_experts)) if needed_experts is None else set(needed_experts)
+        dev = {}
+        self.w64 = {}                                        # (expert, which) -> fp64 matrix
+        for p in range(cfg.n_pairs):
+            for which in W3:
+                pl = synth.pair_matrix(cfg, p, which)
+                t = {k: torch.from_numpy(v.view(np.int16) if v.dtype == np.uint16 else v).cuda() for k, v in pl.items()}
+                dev[p, which] = binding.pzl_q_pack(t["merged"], t["mask0"], t["mask1"], t["sign0"], t["sign1"])
+                experts = [e for e in range(cfg.n_experts) if pair_of[e] == p and e in needed]
+                if experts:
+                    q = oracle.q_quantise(pl["merged"], pl["mask0"], pl["mask1"], pl["sign0"], pl["sign1"])
+                    for e in experts:
+                        self.w64[e, which] = oracle.q_dequantise(q, int(pos_of[e]))
+        P = cfg.n_pairs
+        self.layer = binding.Layer(cfg.d_model, cfg.d_ffn, pair_of, pos_of,
+                                   [dev[p, synth.GATE] for p in range(P)], [dev[p, synth.UP] for p in range(P)],
+                                   [dev[p, synth.DOWN] for p in range(P)], quantised=True)
+
+    def gpu(self, x, ids, w):
+        xt = torch.from_numpy(x.view(np.int16)).cuda()
+        y = self.layer.pzl_moe_ffn(xt, torch.from_numpy(ids).cuda(), torch.from_numpy(w).cuda())
+        torch.cuda.synchronize()
+        return y.view(torch.int16).cpu().numpy().view(np.uint16)
+
+    def ref(self, x, ids, w):
+        any_e = next(iter(self.w64))[0]
+        mats = [[self.w64.get((e, which), self.w64[any_e, which]) for e in range(self.cfg.n_experts)] for which in W3]
+        return self.oracle.ffn_dense64(x, ids, w, *mats)
+
+
+@pytest.fixture(scope="module")
+def small_q(oracle, binding):
+    cfg = synth.LayerConfig("quant_small", 8, 256, 512, 2, (64,), seed=4242)
+    return QCase(cfg, oracle, binding)
+
+
+@pytest.mark.parametrize("T", [1, 7, 33, 64, 150])
+def test_q_ffn_small(small_q, T):
+    """Element-wise parity over several token tiles, a ragged tail and (T = 150) several passes."""
+    say("quantised FFN, small layer, T=%d" % T)
+    cfg = small_q.cfg
+    x = synth.tokens(cfg, T)
+    ids, w = synth.routing(cfg, T)
+    y = small_q.gpu(x, ids, w)
+    y64 = small_q.ref(x, ids, w)
+    ok, worst = tolerance_ok(y, y64)
+    say("  worst err / bound = %.3f" % worst)
+    assert ok, worst
+
+
+def test_q_ffn_skewed_and_empty(small_q):
+    """All tokens on one expert (many passes for one pair, none for the others); zero tokens."""
+    cfg = small_q.cfg
+    T = 70
+    x = synth.tokens(cfg, T)
+    ids = np.tile(np.array([[3, 3]], dtype=np.int32), (T, 1))            # duplicate ids add up
+    w = np.full((T, 2), 0.5, dtype=np.float32)
+    y = small_q.gpu(x, ids, w)
+    ok, worst = tolerance_ok(y, small_q.ref(x, ids, w))
+    assert ok, worst
+    y0 = small_q.layer.pzl_moe_ffn(torch.empty(0, cfg.d_model, dtype=torch.bfloat16, device="cuda"),
+                                   torch.empty(0, 2, dtype=torch.int32, device="cuda"),
+                                   torch.empty(0, 2, dtype=torch.float32, device="cuda"))
+    assert y0.shape == (0, cfg.d_model)
+
+
+def test_q_layer_rejects_bad_shapes(binding):
+    """d_model / d_ffn must be multiples of 128 for the quantised format."""
+    dummy = (torch.zeros(8, dtype=torch.uint8, device="cuda"), torch.zeros(8, dtype=torch.int16, device="cuda"))
+    with pytest.raises((ValueError, binding.PzlError)):
+        binding.Layer(96, 256, [0, 0], [0, 1], [dummy], [dummy], [dummy], quantised=True)
