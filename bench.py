@@ -82,6 +82,23 @@ def build_layer(cfg, keep_planes_for=None):
     return layer, emap
 
 
+def build_quantised_layer(cfg):
+    """The same synthetic pairs in the quantised format (3-bit codes, group scales, base-3 masks)."""
+    q = {}
+    for p in range(cfg.n_pairs):
+        for which in W3:
+            pl = synth.pair_matrix_t(cfg, p, which, device="cuda")
+            q[p, which] = binding.pzl_q_pack(pl["merged"], pl["mask0"], pl["mask1"], pl["sign0"], pl["sign1"])
+            del pl
+    emap = synth.expert_map(cfg)
+    P = cfg.n_pairs
+    layer = binding.Layer(cfg.d_model, cfg.d_ffn, emap[0], emap[1],
+                          [q[p, synth.GATE] for p in range(P)], [q[p, synth.UP] for p in range(P)],
+                          [q[p, synth.DOWN] for p in range(P)], quantised=True)
+    torch.cuda.synchronize()
+    return layer
+
+
 def batch(cfg, T):
     x = synth.tokens(cfg, T)
     ids, w = synth.routing(cfg, T)
@@ -131,6 +148,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sweep", action="store_true")
     ap.add_argument("--no-prefill", action="store_true")
+    ap.add_argument("--no-quant", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (--gpus must be 1)", file=sys.stderr)
@@ -215,6 +233,23 @@ def main():
             "down_kernel": {"avg_launch_ms": ms_dn, "useful_TFLOPs": fl_proj / (ms_dn * 1e-3) / 1e12,
                             "executed_TFLOPs": 2 * fl_proj / (ms_dn * 1e-3) / 1e12},
             "path_useful_mfma_frac": 3 * fl_proj / (ms_p * 1e-3) / 2.5e15}
+
+    if not args.no_quant:
+        # Same layer and batch with the pairs in the quantised format (the paper's appendix on
+        # combining the method with quantisation): 424 bytes per 16x32 tile plus the group scales.
+        qlayer = build_quantised_layer(cfg)
+        ms_q, ms_qgu, _, _ = time_steps(hip, qlayer, xt, idt, wt, max(20, args.steps // 2), 5)
+        q_pair_bytes_gateup = 2 * (f * d // 512 * 424 + f * d // 128 * 2)
+        q_alg = n_touched * q_pair_bytes_gateup + T * d * 2 + T * k * f * 2
+        out["quantised"] = {
+            "workload": "mixtral_decode_T%d, quantised pairs (3.375 bits per weight)" % T,
+            "tokens_per_s": T / (ms_q * 1e-3), "ms_per_step": ms_q,
+            "roofline": {"bound": "hbm", "kernel": "stream_kernel<gate/up + SwiGLU, quantised>",
+                         "achieved": q_alg / (ms_qgu * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                         "frac": q_alg / (ms_qgu * 1e-3) / 1e9 / HBM_PEAK_GBS, "traffic": None,
+                         "algorithmic_bytes": q_alg, "avg_launch_ms": ms_qgu},
+            "weight_bytes_vs_16bit": q_pair_bytes_gateup / pair_bytes_gateup}
+        del qlayer
 
     if want_cpu:
         import oracle

@@ -167,3 +167,22 @@ def test_q_layer_rejects_bad_shapes(binding):
     dummy = (torch.zeros(8, dtype=torch.uint8, device="cuda"), torch.zeros(8, dtype=torch.int16, device="cuda"))
     with pytest.raises((ValueError, binding.PzlError)):
         binding.Layer(96, 256, [0, 0], [0, 1], [dummy], [dummy], [dummy], quantised=True)
+
+
+def test_q_ffn_mixtral_shaped_decode(oracle, binding):
+    """The benchmark's layer shape and batch (Mixtral-8x7B-shaped, T = 64) in the quantised format,
+    in the launch configuration bench.py times; the oracle on sampled token rows (only the experts
+    those rows use are reconstructed in fp64: 0.47 GB per matrix)."""
+    cfg = synth.CONFIGS["mixtral_decode"]
+    T = 64
+    x = synth.tokens(cfg, T)
+    ids, w = synth.routing(cfg, T)
+    rows = np.array([0, 31, 63])
+    say("quantised FFN, %s T=%d, oracle on rows %s" % (cfg.name, T, rows.tolist()))
+    case = QCase(cfg, oracle, binding, needed_experts=np.unique(ids[rows]).tolist())
+    y = case.gpu(x, ids, w)
+    y64 = case.ref(x[rows], ids[rows], w[rows])
+    ok, worst = tolerance_ok(y[rows], y64)
+    say("  worst err / bound = %.3f" % worst)
+    assert ok, worst
+    assert np.isfinite((y.astype(np.uint32) << 16).view(np.float32)).all()
