@@ -33,6 +33,9 @@ namespace pzl {
 #ifndef SG_DEPTH_GATEUP
 #define SG_DEPTH_GATEUP SG_DEPTH_N
 #endif
+#ifndef SG_DEPTH_QUANT_GATEUP
+#define SG_DEPTH_QUANT_GATEUP 4
+#endif
 #ifndef SG_WAVES_N
 #define SG_WAVES_N 8
 #endif
@@ -118,28 +121,31 @@ __device__ __forceinline__ void swiglu_split(float g, float u, uint32_t &hi, uin
 // packed bytes leave time for, so it is table-driven; the tables live in LDS, built by every
 // workgroup at start:
 //   lut_t[13-bit mask number] -> the 8 mask bits of position 0 (low byte) and of position 1
-//   lut_mask[byte]  -> 4 dwords, 0xFFFF in each half whose bit is set
-//   lut_sign[byte]  -> 4 dwords, bit 15 / bit 31 set where the bit is set
+//   lut_mask[nibble] -> 2 dwords, 0xFFFF in each half whose bit is set
+//   lut_sign[nibble] -> 2 dwords, bit 15 / bit 31 set where the bit is set
 //   lut_mag[6 bits: two codes] -> the two codes as bf16 (0..7 are exact)
+// The nibble tables are 128 bytes each and the code table 256: every entry has its own LDS banks,
+// so 64 lanes reading arbitrary entries do not conflict (a 256-entry table of 16-byte rows did,
+// and was the bottleneck of a first version).
 // A decoded fragment holds +-code (or 0); the group scale multiplies the accumulated products
 // of each 128-column group afterwards, in fp32, so nothing is rounded that the definition
 // (code * scale, exactly) does not round.
 constexpr int Q_TILE_BYTES = 424;
 constexpr int Q_LUT_T = 8192;
-constexpr int Q_LUT_BYTES = Q_LUT_T * 2 + 256 * 16 * 2 + 64 * 4;
+constexpr int Q_LUT_BYTES = Q_LUT_T * 2 + 16 * 8 * 2 + 64 * 4;
 
 struct QLuts {
     const uint16_t *t;
-    const u32x4 *mask, *sign;
+    const u32x2 *mask, *sign;
     const uint32_t *mag;
 };
 
 __device__ __forceinline__ void q_build_luts(unsigned char *base, QLuts &l)
 {
     uint16_t *t = (uint16_t *)base;
-    u32x4 *mask = (u32x4 *)(base + Q_LUT_T * 2);
-    u32x4 *sign = mask + 256;
-    uint32_t *mag = (uint32_t *)(sign + 256);
+    u32x2 *mask = (u32x2 *)(base + Q_LUT_T * 2);
+    u32x2 *sign = mask + 16;
+    uint32_t *mag = (uint32_t *)(sign + 16);
     for (int v = threadIdx.x; v < Q_LUT_T; v += SG_THREADS) {
         uint32_t r = v, m0 = 0, m1 = 0;
 #pragma unroll
@@ -151,11 +157,11 @@ __device__ __forceinline__ void q_build_luts(unsigned char *base, QLuts &l)
         }
         t[v] = (uint16_t)(v < 6561 ? (m0 | m1 << 8) : 0u);
     }
-    if (threadIdx.x < 256) {
+    if (threadIdx.x < 16) {
         uint32_t b = threadIdx.x;
-        u32x4 mk, sg;
+        u32x2 mk, sg;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
+        for (int i = 0; i < 2; ++i) {
             uint32_t lo = (b >> (2 * i)) & 1u, hi = (b >> (2 * i + 1)) & 1u;
             mk[i] = (lo ? 0x0000FFFFu : 0u) | (hi ? 0xFFFF0000u : 0u);
             sg[i] = lo << 15 | hi << 31;
@@ -191,11 +197,15 @@ __device__ __forceinline__ QRecord q_split(uint64_t raw, int shift, const QLuts 
 template <int POS>
 __device__ __forceinline__ bf16x8 q_frag(const QRecord &q, const QLuts &l)
 {
-    u32x4 sg = l.sign[POS ? q.s1 : q.s0];
-    u32x4 mk = l.mask[POS ? (q.mm >> 8) : (q.mm & 0xFFu)];
+    const uint32_t sb = POS ? q.s1 : q.s0;
+    const uint32_t mb = POS ? (q.mm >> 8) : q.mm;
+    u32x2 sl = l.sign[sb & 15u], sh = l.sign[(sb >> 4) & 15u];
+    u32x2 ml = l.mask[mb & 15u], mh = l.mask[(mb >> 4) & 15u];
     u32x4 o;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) o[i] = (q.mag[i] | sg[i]) & mk[i];
+    o[0] = (q.mag[0] | sl[0]) & ml[0];
+    o[1] = (q.mag[1] | sl[1]) & ml[1];
+    o[2] = (q.mag[2] | sh[0]) & mh[0];
+    o[3] = (q.mag[3] | sh[1]) & mh[1];
     return __builtin_bit_cast(bf16x8, o);
 }
 
@@ -215,7 +225,8 @@ __device__ __forceinline__ void stream_pass(const SgArgs &a, const uint16_t *wa,
     constexpr int PARTS = (STAGE == STAGE_DOWN) ? 2 : 1;    // activation planes (hi, lo)
     constexpr int VT = NT * PARTS;                          // staged fragment columns per k-block
     constexpr int KCB = (STAGE == STAGE_DOWN) ? 4 : 8;      // k-blocks per staged chunk
-    constexpr int DEPTH = (STAGE == STAGE_DOWN) ? SG_DEPTH : SG_DEPTH_GATEUP;
+    // (a depth of 8 for the 8-byte quantised records measured 7 % slower than 4)
+    constexpr int DEPTH = (STAGE == STAGE_DOWN) ? SG_DEPTH : (QUANT ? SG_DEPTH_QUANT_GATEUP : SG_DEPTH_GATEUP);
     static_assert(VT * KCB <= SG_FRAGS, "staged chunk does not fit its LDS buffer");
     static_assert(KCB % DEPTH == 0, "prefetch slots must line up with chunk steps");
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
