@@ -186,3 +186,50 @@ def test_q_ffn_mixtral_shaped_decode(oracle, binding):
     say("  worst err / bound = %.3f" % worst)
     assert ok, worst
     assert np.isfinite((y.astype(np.uint32) << 16).view(np.float32)).all()
+
+
+def test_q_ffn_mixed_layer_with_unmerged_and_shared_experts(oracle, binding):
+    """Quantised pairs next to routed experts kept unmerged (25 % compression, Sec. 4.1) and a
+    dense shared expert: the routed part against the fp64-weights oracle, the shared part
+    against the bf16 oracle's dense path, summed."""
+    cfg = synth.LayerConfig("quant_mixed", 6, 256, 384, 2, (40,), shared_d_ffn=(256,), seed=77, n_unmerged=2)
+    pair_of, pos_of = synth.expert_map(cfg, "adjacent")
+    T = 40
+    x = synth.tokens(cfg, T)
+    ids, w = synth.routing(cfg, T)
+    qdev, w64 = {}, {}
+    for p in range(cfg.n_pairs):
+        for which in W3:
+            pl = synth.pair_matrix(cfg, p, which)
+            t = {k: torch.from_numpy(v.view(np.int16) if v.dtype == np.uint16 else v).cuda() for k, v in pl.items()}
+            qdev[p, which] = binding.pzl_q_pack(t["merged"], t["mask0"], t["mask1"], t["sign0"], t["sign1"])
+            q = oracle.q_quantise(pl["merged"], pl["mask0"], pl["mask1"], pl["sign0"], pl["sign1"])
+            for e in range(cfg.n_experts):
+                if pair_of[e] == p:
+                    w64[e, which] = oracle.q_dequantise(q, int(pos_of[e]))
+    dense_gpu = []
+    for j in range(cfg.n_unmerged):
+        mats = [synth.unmerged_matrix_t(cfg, j, which) for which in W3]
+        dense_gpu.append(tuple(binding.pzl_tile_dense(m.cuda()) for m in mats))
+        e = [e for e in range(cfg.n_experts) if pair_of[e] == -1 - j][0]
+        for which, m in zip(W3, mats):
+            w64[e, which] = (synth._np_bits(m).astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    shared_mats = [synth.shared_matrix_t(cfg, 0, which) for which in W3]
+    shared_gpu = [tuple(binding.pzl_tile_dense(m.cuda()) for m in shared_mats) + (cfg.shared_d_ffn[0],)]
+    P = cfg.n_pairs
+    layer = binding.Layer(cfg.d_model, cfg.d_ffn, pair_of, pos_of,
+                          [qdev[p, synth.GATE] for p in range(P)], [qdev[p, synth.UP] for p in range(P)],
+                          [qdev[p, synth.DOWN] for p in range(P)], shared=shared_gpu, dense=dense_gpu,
+                          quantised=True)
+    y = layer.pzl_moe_ffn(torch.from_numpy(x.view(np.int16)).cuda(), torch.from_numpy(ids).cuda(),
+                          torch.from_numpy(w).cuda())
+    torch.cuda.synchronize()
+    y = y.view(torch.int16).cpu().numpy().view(np.uint16)
+    y_routed = oracle.ffn_dense64(x, ids, w, *[[w64[e, which] for e in range(cfg.n_experts)] for which in W3])
+    no_ids = np.zeros((T, 0), dtype=np.int32)
+    y_shared, _ = oracle.moe_ffn(x, no_ids, np.zeros((T, 0), dtype=np.float32),
+                                 np.full(cfg.n_experts, -1, dtype=np.int32), np.zeros(cfg.n_experts, np.uint8),
+                                 [], [], [], shared=[tuple(synth._np_bits(m) for m in shared_mats)])
+    ok, worst = tolerance_ok(y, y_routed + y_shared)
+    say("mixed quantised layer: worst err / bound = %.3f" % worst)
+    assert ok, worst
