@@ -43,7 +43,15 @@ namespace pzl {
 #ifndef PZL_TILED_MIN_SHARED
 #define PZL_TILED_MIN_SHARED 1024
 #endif
-constexpr int TILED_MIN_TOKENS_PER_EXPERT = PZL_TILED_MIN_TPE;   // average tokens per expert from which the tiled path pays
+constexpr int TILED_MIN_TOKENS_PER_EXPERT = PZL_TILED_MIN_TPE;   // average tokens per expert from which the K split is sized for the tiled kernels
+#ifndef PZL_HYBRID_MIN_TPE
+#define PZL_HYBRID_MIN_TPE 20
+#endif
+#ifndef PZL_HYBRID_TILE_MIN
+#define PZL_HYBRID_TILE_MIN 33
+#endif
+constexpr int HYBRID_MIN_TOKENS_PER_EXPERT = PZL_HYBRID_MIN_TPE;  // average from which both paths are launched
+constexpr int HYBRID_TILE_MIN_TOKENS = PZL_HYBRID_TILE_MIN;       // ... and a pair with an expert of this many tokens is tiled
 constexpr int TILED_MIN_TOKENS_SHARED = PZL_TILED_MIN_SHARED;     // a dense expert sees every token but has few row tiles: the tiled path needs >= 4 token tiles
 constexpr int MAX_KSPLIT = 8;   // upper bound on the k-splits of the down stage (sizes the workspace)
 
@@ -338,22 +346,34 @@ int pzl_moe_ffn_staged(const pzl_layer *L, const uint16_t *x, const int32_t *top
     uint16_t *h_routed = (uint16_t *)(ws + w.h_routed);
     float *opart = (float *)(ws + w.opart);
 
+    // Path choice.  With few tokens per expert the layer is bound by streaming the packed weights
+    // once (streaming kernels); with many it is a dense contraction (tiled kernels on the matrix
+    // cores).  The streaming kernels take 32 tokens per expert in one sweep of a pair's weights
+    // and need another sweep, in sequence, for every 32 more; measured over the Mixtral-, Qwen-
+    // and DeepSeek-shaped layers the tiled kernels win as soon as a second sweep would be needed.
+    // The host only knows the batch shape, not how the router spread the tokens: from an average
+    // of HYBRID_MIN_TOKENS_PER_EXPERT both paths are launched and the grouping kernel decides
+    // per pair (tile_min).  Below that average only the streaming kernels are launched (two
+    // empty tiled launches would cost the decode step 3 %).
+    // (quantised pairs have no tiled kernel: they always stream)
+    const int64_t E64 = L->n_experts;
+    const bool hybrid = L->pair_format == 0 && (int64_t)N >= (int64_t)HYBRID_MIN_TOKENS_PER_EXPERT * E64;
+    const int tile_min = hybrid ? HYBRID_TILE_MIN_TOKENS : 0x7FFFFFFF;
+    const bool tiled = hybrid, streamed = true;
+    const bool mostly_tiled = hybrid && (int64_t)N >= (int64_t)TILED_MIN_TOKENS_PER_EXPERT * E64;
+    const bool tiled_shared = T >= TILED_MIN_TOKENS_SHARED;
+
     int rc = mark(PZL_STAGE_ROUTE, 0);
     if (rc) return rc;
-    rc = launch_route(topk_ids, N, k, L->n_experts, L->n_q, L->d_q_of_expert, rt, st);
+    rc = launch_route(topk_ids, N, k, L->n_experts, L->n_q, L->d_q_of_expert, rt, tile_min, st);
     if (rc) return rc;
     if ((rc = mark(PZL_STAGE_ROUTE, 1))) return rc;
 
-    // Path choice (host side, from the batch shape only): with few tokens per expert the layer
-    // is bound by streaming the packed weights once (streaming kernels); with many it is a
-    // dense contraction (tiled kernels on the matrix cores).
-    // (quantised pairs have no tiled kernel: they always stream)
-    const bool tiled = L->pair_format == 0 && (int64_t)N >= (int64_t)TILED_MIN_TOKENS_PER_EXPERT * L->n_experts;
-    const bool tiled_shared = T >= TILED_MIN_TOKENS_SHARED;
     const int routed_groups = L->n_pairs + L->n_dense;
     const int groups_max = (int)((int64_t)N < routed_groups ? N : routed_groups);   // groups that can have tokens
-    int ksplit = tiled ? choose_tile_ksplit(N / TILE_MAX_TOKENS + L->n_experts / 2, L->d_model, L->d_ffn)
-                       : choose_ksplit(groups_max > 0 ? groups_max : 1, L->d_model);
+    // one k-split count for all routed slots (the combine step sums that many partials)
+    int ksplit = mostly_tiled ? choose_tile_ksplit(N / TILE_MAX_TOKENS + L->n_experts / 2, L->d_model, L->d_ffn)
+                           : choose_ksplit(groups_max > 0 ? groups_max : 1, L->d_model);
     if (L->pair_format == 1 && ksplit > L->d_ffn / 128) ksplit = L->d_ffn / 128;   // whole 128-column groups per split
     // one k-split count for all shared experts (the combine step sums that many partials); sized
     // for the usual case, all of them of one width and hence in one launch per stage
@@ -369,66 +389,64 @@ int pzl_moe_ffn_staged(const pzl_layer *L, const uint16_t *x, const int32_t *top
     const int64_t h_plane = (int64_t)N * L->d_ffn;
     // Routed experts come in two kinds that differ only in the decode: packed pairs (groups
     // [0, P)) and experts kept unmerged (dense bf16, groups [P, P + D), position 0 only).  Both
-    // kinds write disjoint slots of the same H and partial-sum buffers.
-    for (int pass = 0; pass < 2 && N > 0; ++pass) {
-        const bool unmerged = pass == 1;
-        const int n_groups = unmerged ? L->n_dense : L->n_pairs;
-        if (n_groups == 0) continue;
-        const int kind = unmerged ? KIND_UNMERGED : (L->pair_format == 1 ? KIND_QUANT : KIND_PACKED);
-        const uint16_t *const *wg = unmerged ? L->d_dgate : L->d_gate;
-        const uint16_t *const *wu = unmerged ? L->d_dup : L->d_up;
-        const uint16_t *const *wd = unmerged ? L->d_ddown : L->d_down;
-        const int group_base = unmerged ? L->n_pairs : 0;
-        // the stage events bracket the packed kind when the layer has one, else the unmerged kind
-        const bool timed = !unmerged || L->n_pairs == 0;
-        if (tiled) {
-            TileGemmArgs a = {};
-            a.slot_tok = rt.slot_tok;
-            a.tile_q = rt.tile_q; a.tile_slot0 = rt.tile_slot0; a.tile_n = rt.tile_n; a.n_tiles = rt.n_tiles;
-            a.group_lo = group_base; a.group_hi = group_base + n_groups;
-            a.max_mtiles = max_token_tiles(N, L->n_q);
-            a.w_a = wg; a.w_b = wu;
-            a.rows = L->d_ffn; a.kdim = L->d_model;
-            a.act = x; a.act_is_x = 1;
-            a.h_out = h_routed; a.h_slot_base = 0; a.h_plane_stride = h_plane;
-            if (timed && (rc = mark(PZL_STAGE_GATEUP, 0))) return rc;
-            rc = launch_tile_gateup(a, kind, st);
-            if (rc) return rc;
-            if (timed && (rc = mark(PZL_STAGE_GATEUP, 1))) return rc;
-            a.w_a = wd; a.w_b = nullptr;
-            a.rows = L->d_model; a.kdim = L->d_ffn;
-            a.act = h_routed; a.act_is_x = 0; a.act_slot_base = 0; a.act_plane_stride = h_plane;
-            a.h_out = nullptr; a.o_out = opart; a.o_ks_stride = w.o_ks_stride; a.ksplit = ksplit;
-            if (timed && (rc = mark(PZL_STAGE_DOWN, 0))) return rc;
-            rc = launch_tile_down(a, kind, st);
-            if (rc) return rc;
-            if (timed && (rc = mark(PZL_STAGE_DOWN, 1))) return rc;
-        } else {
-            StreamGroupArgs a = {};
-            a.n_groups = n_groups; a.group_base = group_base;
-            a.groups_touched_max = (int)((int64_t)N < n_groups ? N : n_groups);
-            a.cnt = rt.cnt; a.off = rt.off; a.slot_tok = rt.slot_tok;
-            // gate/up + SwiGLU -> H
-            a.w_a = wg; a.w_b = wu;
-            if (kind == KIND_QUANT) { a.s_a = L->d_gscale; a.s_b = L->d_uscale; }
-            a.rows = L->d_ffn; a.kdim = L->d_model; a.ksplit = 1;
-            a.act = x; a.act_is_x = 1; a.act_slot_base = 0;
-            a.h_out = h_routed; a.h_slot_base = 0; a.h_plane_stride = h_plane;
-            if (timed && (rc = mark(PZL_STAGE_GATEUP, 0))) return rc;
-            rc = launch_stream_gateup(a, kind, st);
-            if (rc) return rc;
-            if (timed && (rc = mark(PZL_STAGE_GATEUP, 1))) return rc;
-            // down -> partial sums
-            a.w_a = wd; a.w_b = nullptr;
-            if (kind == KIND_QUANT) { a.s_a = L->d_dscale; a.s_b = nullptr; }
-            a.rows = L->d_model; a.kdim = L->d_ffn; a.ksplit = ksplit;
-            a.act = h_routed; a.act_is_x = 0; a.act_slot_base = 0; a.act_plane_stride = h_plane;
-            a.h_out = nullptr; a.o_out = opart; a.o_ks_stride = w.o_ks_stride;
-            if (timed && (rc = mark(PZL_STAGE_DOWN, 0))) return rc;
-            rc = launch_stream_down(a, kind, st);
-            if (rc) return rc;
-            if (timed && (rc = mark(PZL_STAGE_DOWN, 1))) return rc;
+    // kinds, and both paths, write disjoint slots of the same H and partial-sum buffers.
+    for (int stage = 0; stage < 2 && N > 0; ++stage) {
+        const int stage_id = stage == 0 ? PZL_STAGE_GATEUP : PZL_STAGE_DOWN;
+        if ((rc = mark(stage_id, 0))) return rc;
+        for (int pass = 0; pass < 2; ++pass) {
+            const bool unmerged = pass == 1;
+            const int n_groups = unmerged ? L->n_dense : L->n_pairs;
+            if (n_groups == 0) continue;
+            const int kind = unmerged ? KIND_UNMERGED : (L->pair_format == 1 ? KIND_QUANT : KIND_PACKED);
+            const uint16_t *const *wg = unmerged ? L->d_dgate : L->d_gate;
+            const uint16_t *const *wu = unmerged ? L->d_dup : L->d_up;
+            const uint16_t *const *wd = unmerged ? L->d_ddown : L->d_down;
+            const int group_base = unmerged ? L->n_pairs : 0;
+            if (tiled) {
+                TileGemmArgs a = {};
+                a.slot_tok = rt.slot_tok;
+                a.tile_q = rt.tile_q; a.tile_slot0 = rt.tile_slot0; a.tile_n = rt.tile_n; a.n_tiles = rt.n_tiles;
+                a.group_lo = group_base; a.group_hi = group_base + n_groups;
+                a.max_mtiles = max_token_tiles(N, L->n_q);
+                if (stage == 0) {
+                    a.w_a = wg; a.w_b = wu;
+                    a.rows = L->d_ffn; a.kdim = L->d_model;
+                    a.act = x; a.act_is_x = 1;
+                    a.h_out = h_routed; a.h_slot_base = 0; a.h_plane_stride = h_plane;
+                    rc = launch_tile_gateup(a, kind, st);
+                } else {
+                    a.w_a = wd; a.w_b = nullptr;
+                    a.rows = L->d_model; a.kdim = L->d_ffn;
+                    a.act = h_routed; a.act_is_x = 0; a.act_slot_base = 0; a.act_plane_stride = h_plane;
+                    a.o_out = opart; a.o_ks_stride = w.o_ks_stride; a.ksplit = ksplit;
+                    rc = launch_tile_down(a, kind, st);
+                }
+                if (rc) return rc;
+            }
+            if (streamed) {
+                StreamGroupArgs a = {};
+                a.n_groups = n_groups; a.group_base = group_base;
+                a.groups_touched_max = (int)((int64_t)N < n_groups ? N : n_groups);
+                a.cnt = rt.cnt; a.off = rt.off; a.slot_tok = rt.slot_tok;
+                if (stage == 0) {                        // gate/up + SwiGLU -> H
+                    a.w_a = wg; a.w_b = wu;
+                    if (kind == KIND_QUANT) { a.s_a = L->d_gscale; a.s_b = L->d_uscale; }
+                    a.rows = L->d_ffn; a.kdim = L->d_model; a.ksplit = 1;
+                    a.act = x; a.act_is_x = 1; a.act_slot_base = 0;
+                    a.h_out = h_routed; a.h_slot_base = 0; a.h_plane_stride = h_plane;
+                    rc = launch_stream_gateup(a, kind, st);
+                } else {                                 // down -> partial sums
+                    a.w_a = wd; a.w_b = nullptr;
+                    if (kind == KIND_QUANT) { a.s_a = L->d_dscale; a.s_b = nullptr; }
+                    a.rows = L->d_model; a.kdim = L->d_ffn; a.ksplit = ksplit;
+                    a.act = h_routed; a.act_is_x = 0; a.act_slot_base = 0; a.act_plane_stride = h_plane;
+                    a.o_out = opart; a.o_ks_stride = w.o_ks_stride;
+                    rc = launch_stream_down(a, kind, st);
+                }
+                if (rc) return rc;
+            }
         }
+        if ((rc = mark(stage_id, 1))) return rc;
     }
 
     if ((rc = mark(PZL_STAGE_SHARED, 0))) return rc;

@@ -20,7 +20,7 @@ constexpr int TILE_ELEMS = TILE_ROWS * TILE_COLS;
 // Routing tables in the workspace (all int32).  Experts are renumbered q = 2*pair + pos so
 // that the two experts of a pair own adjacent slot ranges.
 struct RouteTables {
-    int32_t *cnt;        // [Q]    tokens routed to expert q
+    int32_t *cnt;        // [Q]    tokens routed to expert q that the streaming kernels handle (0 if the expert is tiled)
     int32_t *off;        // [Q+1]  first slot of expert q
     int32_t *slot_tok;   // [N]    token index of each slot (slots grouped by q; order inside a group is arbitrary)
     int32_t *slot_of;    // [N]    slot of flat index t*k+j, or -1 for an id outside [0,E)
@@ -56,8 +56,10 @@ int launch_q_unpack(const uint8_t *records, const uint16_t *scales, int pos, int
                     float *out, hipStream_t st);
 
 // route.hip
+// tile_min: a pair one of whose experts has at least that many tokens gets token tiles (tiled
+// kernels) and counts as empty for the streaming kernels; the other pairs the other way round
 int launch_route(const int32_t *ids, int32_t n_flat, int32_t k, int32_t n_experts, int32_t n_slots_q, const int32_t *q_of_expert,
-                 RouteTables rt, hipStream_t st);
+                 RouteTables rt, int32_t tile_min, hipStream_t st);
 int launch_router_topk(const uint16_t *x, const uint16_t *w_router, int32_t T, int32_t d, int32_t E, int32_t k,
                        int32_t *ids_out, float *w_out, hipStream_t st);
 int launch_combine(const float *opart, int32_t ksplit, int32_t ksplit_shared, int64_t ks_stride, const RouteTables &rt,

@@ -18,10 +18,11 @@ route_kernel(const int32_t *__restrict__ ids, int32_t n_flat, int32_t k, int32_t
              const int32_t *__restrict__ q_of_expert, int32_t Q, int32_t *__restrict__ cnt,
              int32_t *__restrict__ off, int32_t *__restrict__ slot_tok, int32_t *__restrict__ slot_of,
              int32_t *__restrict__ tile_q, int32_t *__restrict__ tile_slot0, int32_t *__restrict__ tile_n,
-             int32_t *__restrict__ n_tiles)
+             int32_t *__restrict__ n_tiles, int32_t tile_min)
 {
     __shared__ int32_t hist[ROUTE_WAVES][ROUTE_QMAX];
     __shared__ int32_t total[ROUTE_QMAX];
+    __shared__ bool tiled_pair[ROUTE_QMAX];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     for (int i = tid; i < ROUTE_WAVES * ROUTE_QMAX; i += ROUTE_THREADS) (&hist[0][0])[i] = 0;
     __syncthreads();
@@ -44,7 +45,28 @@ route_kernel(const int32_t *__restrict__ ids, int32_t n_flat, int32_t k, int32_t
         int s = 0;
         for (int w = 0; w < ROUTE_WAVES; ++w) s += hist[w][q];
         total[q] = s;
-        cnt[q] = s;
+    }
+    __syncthreads();
+    // A pair one of whose experts has at least tile_min tokens belongs to the tiled kernels (token
+    // tiles below) and is empty for the streaming kernels; the decision is per pair so that a
+    // pair's weights are swept by one path only.  If at least half of the pairs that have tokens
+    // are such pairs, all of them go to the tiled kernels: two half-empty launches one after the
+    // other are slower than either path alone.
+    __shared__ int32_t all_tiled;
+    if (tid == 0) {
+        int active = 0, big = 0;
+        for (int g = 0; g < Q / 2; ++g) {
+            int m = max(total[2 * g], total[2 * g + 1]);
+            active += m > 0;
+            big += m >= tile_min;
+        }
+        all_tiled = big > 0 && 2 * big >= active;
+    }
+    __syncthreads();
+    for (int q = tid; q < Q; q += ROUTE_THREADS) {
+        const bool t = all_tiled || max(total[q & ~1], total[q | 1]) >= tile_min;     // Q is even: q | 1 < Q
+        tiled_pair[q] = t;
+        cnt[q] = t ? 0 : total[q];
     }
     __syncthreads();
     if (tid == 0) {
@@ -55,7 +77,7 @@ route_kernel(const int32_t *__restrict__ ids, int32_t n_flat, int32_t k, int32_t
             // token tiles: equal parts of at most TILE_MAX_TOKENS, rounded up to whole fragments of 16
             int parts = (c + TILE_MAX_TOKENS - 1) / TILE_MAX_TOKENS;
             int size = parts ? (((c + parts - 1) / parts + 15) & ~15) : 0;
-            for (int s0 = 0; s0 < c; s0 += size) {
+            for (int s0 = 0; s0 < c && tiled_pair[q]; s0 += size) {
                 tile_q[nt] = q; tile_slot0[nt] = run + s0; tile_n[nt] = min(size, c - s0);
                 ++nt;
             }
@@ -196,13 +218,13 @@ int launch_router_topk(const uint16_t *x, const uint16_t *w_router, int32_t T, i
 }
 
 int launch_route(const int32_t *ids, int32_t n_flat, int32_t k, int32_t n_experts, int32_t n_slots_q,
-                 const int32_t *q_of_expert, RouteTables rt, hipStream_t st)
+                 const int32_t *q_of_expert, RouteTables rt, int32_t tile_min, hipStream_t st)
 {
     int Q = n_slots_q;
     if (Q > ROUTE_QMAX) return PZL_EINVAL;
     hipLaunchKernelGGL(route_kernel, dim3(1), dim3(ROUTE_THREADS), 0, st, ids, n_flat, k, n_experts,
                        q_of_expert, Q, rt.cnt, rt.off, rt.slot_tok, rt.slot_of, rt.tile_q, rt.tile_slot0,
-                       rt.tile_n, rt.n_tiles);
+                       rt.tile_n, rt.n_tiles, tile_min);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) { set_hip_error(e); return PZL_EHIP; }
     return PZL_OK;

@@ -212,6 +212,28 @@ def test_tiled_path_token_counts(tiled_case, T):
     check(tiled_case, T, "tiled")
 
 
+@pytest.mark.parametrize("T", [70, 100, 180])
+def test_hybrid_path_mixed_pair_sizes(tiled_case, T):
+    """From 20 slots per expert on average both paths are launched and the grouping kernel assigns
+    each PAIR to one of them (tiled kernels if one of its experts has more than 32 tokens).
+    Routing is set by hand: one pair holds a hot expert (T tokens, several token tiles) and a
+    partner with a few tokens (a small tile); the other pair holds an expert with T/8 tokens and an
+    empty one and stays with the streaming kernels."""
+    cfg = TILED
+    pair_of = np.asarray(tiled_case.emap[0])
+    a, b = np.where(pair_of == 0)[0]
+    c, d = np.where(pair_of == 1)[0]
+    x = synth.tokens(cfg, T)
+    _, w = synth.routing(cfg, T)
+    ids = np.empty((T, 2), dtype=np.int32)
+    ids[:, 0] = a                                                # hot expert
+    ids[:, 1] = np.where(np.arange(T) % 8 == 0, c, np.where(np.arange(T) % 8 == 1, b, a))
+    counts = np.bincount(ids.ravel(), minlength=cfg.n_experts)
+    assert T * cfg.top_k >= 20 * cfg.n_experts
+    assert counts[a] > 64 and 0 < counts[b] < 33 and 0 < counts[c] < 33 and counts[d] == 0
+    check(tiled_case, T, "hybrid", ids=ids, w=w, x=x)
+
+
 def test_tiled_path_skewed_routing(tiled_case):
     """One hot expert (several full token tiles), one expert with a single token, one with none."""
     cfg = TILED
