@@ -151,7 +151,11 @@ typedef struct pzl_layer_desc {
 typedef struct pzl_layer pzl_layer;
 
 /* Validates the description and builds the layer's device tables (the only allocation the
- * library performs).  The device current at the call is the layer's device. */
+ * library performs).  The device current at the call is the layer's device.  A layer with
+ * shared experts also owns a second stream (default priority) and two events: pzl_moe_ffn runs
+ * the shared experts there, next to the routed experts, forked from and joined back into the
+ * caller's stream inside the call.  Calls on one layer must therefore not overlap in time on
+ * different streams (calls queued on one stream are fine). */
 int pzl_layer_create(const pzl_layer_desc *desc, pzl_layer **out);
 void pzl_layer_destroy(pzl_layer *layer);
 

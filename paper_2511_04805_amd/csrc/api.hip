@@ -33,6 +33,10 @@ struct pzl_layer {
     const uint16_t **d_dgate, **d_dup, **d_ddown;         // [n_dense] routed experts kept unmerged
     const uint16_t **d_sgate, **d_sup, **d_sdown;         // [n_shared]
     void *d_block;                         // the one allocation holding all of the above
+    // Shared experts do not depend on the routing: they run on a second stream next to the routed
+    // kernels (fork after the caller's stream reaches the call, join before the combine).
+    hipStream_t aux_stream;
+    hipEvent_t ev_fork, ev_join;
 };
 
 namespace pzl {
@@ -288,6 +292,13 @@ int pzl_layer_create(const pzl_layer_desc *desc, pzl_layer **out)
     L->d_sgate = (const uint16_t **)(base + o_sg);
     L->d_sup = (const uint16_t **)(base + o_su);
     L->d_sdown = (const uint16_t **)(base + o_sd);
+    L->aux_stream = nullptr; L->ev_fork = nullptr; L->ev_join = nullptr;
+    if (S > 0) {                                               // default priority, as every stream here
+        e = hipStreamCreateWithFlags(&L->aux_stream, hipStreamNonBlocking);
+        if (e == hipSuccess) e = hipEventCreateWithFlags(&L->ev_fork, hipEventDisableTiming);
+        if (e == hipSuccess) e = hipEventCreateWithFlags(&L->ev_join, hipEventDisableTiming);
+        if (e != hipSuccess) { set_hip_error(e); pzl_layer_destroy(L); return PZL_EHIP; }
+    }
     *out = L;
     return PZL_OK;
 }
@@ -295,6 +306,9 @@ int pzl_layer_create(const pzl_layer_desc *desc, pzl_layer **out)
 void pzl_layer_destroy(pzl_layer *layer)
 {
     if (!layer) return;
+    if (layer->ev_fork) (void)hipEventDestroy(layer->ev_fork);
+    if (layer->ev_join) (void)hipEventDestroy(layer->ev_join);
+    if (layer->aux_stream) (void)hipStreamDestroy(layer->aux_stream);
     if (layer->d_block) (void)hipFree(layer->d_block);
     delete layer;
 }
@@ -333,6 +347,15 @@ int pzl_moe_ffn_staged(const pzl_layer *L, const uint16_t *x, const int32_t *top
     hipStream_t st = (hipStream_t)stream;
     unsigned char *ws = (unsigned char *)workspace;
     const int32_t N = T * k;
+    // Shared experts on the layer's second stream, unless the caller times stages (then every
+    // stage runs alone on the caller's stream) or there is nothing to run next to.
+    const bool overlap = L->n_shared > 0 && !stage_events && N > 0;
+    hipStream_t sst = overlap ? L->aux_stream : st;
+    if (overlap) {
+        hipError_t e = hipEventRecord(L->ev_fork, st);
+        if (e == hipSuccess) e = hipStreamWaitEvent(L->aux_stream, L->ev_fork, 0);
+        if (e != hipSuccess) { set_hip_error(e); return PZL_EHIP; }
+    }
 
     RouteTables rt;
     rt.cnt = (int32_t *)(ws + w.cnt);
@@ -471,13 +494,13 @@ int pzl_moe_ffn_staged(const pzl_layer *L, const uint16_t *x, const int32_t *top
             a.rows = L->shared_f[s]; a.kdim = L->d_model;
             a.act = x; a.act_is_x = 1;
             a.h_out = h_s; a.h_slot_base = slot_base; a.h_plane_stride = hs_plane;
-            rc = launch_tile_gateup(a, KIND_SHARED, st);
+            rc = launch_tile_gateup(a, KIND_SHARED, sst);
             if (rc) return rc;
             a.w_a = L->d_sdown + s; a.w_b = nullptr;
             a.rows = L->d_model; a.kdim = L->shared_f[s];
             a.act = h_s; a.act_is_x = 0; a.act_slot_base = slot_base; a.act_plane_stride = hs_plane;
             a.h_out = nullptr; a.o_out = opart; a.o_ks_stride = w.o_ks_stride; a.ksplit = ksplit_shared;
-            rc = launch_tile_down(a, KIND_SHARED, st);
+            rc = launch_tile_down(a, KIND_SHARED, sst);
             if (rc) return rc;
             s += nb;
             continue;
@@ -489,17 +512,22 @@ int pzl_moe_ffn_staged(const pzl_layer *L, const uint16_t *x, const int32_t *top
         a.rows = L->shared_f[s]; a.kdim = L->d_model; a.ksplit = 1;
         a.act = x; a.act_is_x = 1; a.act_slot_base = 0;
         a.h_out = h_s; a.h_slot_base = slot_base; a.h_plane_stride = hs_plane;
-        rc = launch_stream_gateup(a, KIND_SHARED, st);
+        rc = launch_stream_gateup(a, KIND_SHARED, sst);
         if (rc) return rc;
         a.w_a = L->d_sdown + s; a.w_b = nullptr;
         a.rows = L->d_model; a.kdim = L->shared_f[s]; a.ksplit = ksplit_shared;
         a.act = h_s; a.act_is_x = 0; a.act_slot_base = slot_base; a.act_plane_stride = hs_plane;
         a.h_out = nullptr; a.o_out = opart; a.o_ks_stride = w.o_ks_stride;
-        rc = launch_stream_down(a, KIND_SHARED, st);
+        rc = launch_stream_down(a, KIND_SHARED, sst);
         if (rc) return rc;
         s += nb;
     }
 
+    if (overlap) {
+        hipError_t e = hipEventRecord(L->ev_join, L->aux_stream);
+        if (e == hipSuccess) e = hipStreamWaitEvent(st, L->ev_join, 0);
+        if (e != hipSuccess) { set_hip_error(e); return PZL_EHIP; }
+    }
     if ((rc = mark(PZL_STAGE_SHARED, 1))) return rc;
     if ((rc = mark(PZL_STAGE_COMBINE, 0))) return rc;
     rc = launch_combine(opart, ksplit, ksplit_shared, w.o_ks_stride, rt, topk_w, T, k, L->d_model, L->n_shared, y, st);
