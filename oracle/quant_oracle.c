@@ -36,6 +36,8 @@
  * is below 7, and the group maximum gets code 7; exact reconstruction when the magnitudes are
  * integer multiples of a power-of-two step; the FFN against the bf16 oracle's dense-expert path
  * on such exactly representable weights.
+ * Parity unpinned (paper silent, no second source): that the codes are unsigned, the rounding
+ * rule of scale and code, and the treatment of an element that no expert uses.
  */
 #include <math.h>
 #include <stdint.h>
