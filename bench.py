@@ -25,7 +25,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of the gate/up streaming kernel at T = 64, from the two rocprofv3 --pmc runs
 # (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, calibrated on the copy below) summarised in
 # profiles/stream_kernels_mixtral_decode_T64.md.  Counters cannot be read inside this process.
-MEASURED_TRAFFIC_BYTES = {"mixtral_decode_T64": 955.0e6}
+MEASURED_TRAFFIC_BYTES = {"mixtral_decode_T64": 955.0e6, "mixtral_decode_T64_quantised": 413.7e6}
 W3 = (synth.GATE, synth.UP, synth.DOWN)
 
 
@@ -246,7 +246,8 @@ def main():
             "tokens_per_s": T / (ms_q * 1e-3), "ms_per_step": ms_q,
             "roofline": {"bound": "hbm", "kernel": "stream_kernel<gate/up + SwiGLU, quantised>",
                          "achieved": q_alg / (ms_qgu * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                         "frac": q_alg / (ms_qgu * 1e-3) / 1e9 / HBM_PEAK_GBS, "traffic": None,
+                         "frac": q_alg / (ms_qgu * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                         "traffic": MEASURED_TRAFFIC_BYTES.get("mixtral_decode_T%d_quantised" % T),
                          "algorithmic_bytes": q_alg, "avg_launch_ms": ms_qgu},
             "weight_bytes_vs_16bit": q_pair_bytes_gateup / pair_bytes_gateup}
         del qlayer
