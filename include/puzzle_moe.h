@@ -171,15 +171,18 @@ size_t pzl_moe_ffn_workspace_bytes(const pzl_layer *layer, int32_t max_tokens, i
  * layer in the quantised format, reconstructed on the fly as (-1)^S * M * code * scale (the group
  * scale is applied to the fp32 partial sums of each 128-column group, so code * scale is never
  * rounded).  Quantised layers always take the weight-streaming kernels.
- * Products are bf16 x bf16 accumulated in fp32; the SwiGLU output is rounded to bf16 once
- * before the down projection; y is rounded to bf16 once at the end.
+ * Products are bf16 x bf16 accumulated in fp32; the SwiGLU output is kept as two bf16 numbers
+ * (hi = bf16(h), lo = bf16(h - hi)) and the down projection multiplies both; y is rounded to
+ * bf16 once at the end.
  *   x         [T, d_model] bf16 bits, row-major
  *   topk_ids  [T, k] int32 expert ids in [0, E); duplicates within a token add up; ids
  *             outside the range are ignored (contribute nothing)
  *   topk_w    [T, k] fp32 routing weights
  *   y         [T, d_model] bf16 bits, overwritten
  *   workspace at least pzl_moe_ffn_workspace_bytes(layer, T, k) bytes; contents are scratch
- * T == 0 is a no-op.  Concurrent calls must use different workspaces.
+ * T == 0 is a no-op.  Calls on one layer that overlap in time (different streams) are not
+ * supported when the layer has shared experts (see pzl_layer_create); otherwise they must use
+ * different workspaces.
  */
 int pzl_moe_ffn(const pzl_layer *layer, const uint16_t *x, const int32_t *topk_ids,
                 const float *topk_w, int32_t T, int32_t k, uint16_t *y,
