@@ -36,8 +36,16 @@ namespace pzl {
 #ifndef SG_DEPTH_QUANT_GATEUP
 #define SG_DEPTH_QUANT_GATEUP 4
 #endif
+#ifndef SG_PLAIN_LOADS
+#define SG_PLAIN_LOADS 0
+#endif
 #ifndef SG_WAVES_N
 #define SG_WAVES_N 8
+#endif
+#if SG_PLAIN_LOADS
+#define SG_WLOAD(p) (*(p))
+#else
+#define SG_WLOAD(p) __builtin_nontemporal_load(p)
 #endif
 constexpr int SG_WAVES = SG_WAVES_N;
 constexpr int SG_THREADS = SG_WAVES * 64;
@@ -298,8 +306,8 @@ __device__ __forceinline__ void stream_pass(const SgArgs &a, const uint16_t *wa,
     for (int s = 0; s < DEPTH; ++s)
 #pragma unroll
         for (int m = 0; m < 2; ++m) {
-            if (QUANT) qbuf[m][s] = *(gq_ptr)(qp[m] + (int64_t)min(s, kb_last) * Q_TILE_BYTES);
-            else       wbuf[m][s] = __builtin_nontemporal_load(wp[m] + (int64_t)min(s, kb_last) * 64);
+            if (QUANT) qbuf[m][s] = SG_WLOAD((gq_ptr)(qp[m] + (int64_t)min(s, kb_last) * Q_TILE_BYTES));
+            else       wbuf[m][s] = SG_WLOAD(wp[m] + (int64_t)min(s, kb_last) * 64);
         }
 
     // activation fragments this thread stages per chunk: fragment f = wave + 4*i,
@@ -399,8 +407,8 @@ __device__ __forceinline__ void stream_pass(const SgArgs &a, const uint16_t *wa,
 #pragma unroll
             for (int m = 0; m < 2; ++m) {
                 int kbn = min(kb + DEPTH + s - kb0, kb_last);
-                if (QUANT) qbuf[m][s % DEPTH] = *(gq_ptr)(qp[m] + (int64_t)kbn * Q_TILE_BYTES);
-                else       wbuf[m][s % DEPTH] = __builtin_nontemporal_load(wp[m] + (int64_t)kbn * 64);
+                if (QUANT) qbuf[m][s % DEPTH] = SG_WLOAD((gq_ptr)(qp[m] + (int64_t)kbn * Q_TILE_BYTES));
+                else       wbuf[m][s % DEPTH] = SG_WLOAD(wp[m] + (int64_t)kbn * 64);
             }
 #if SG_SCHED_BARRIER
             // keep each step's refill inside the step: the scheduler otherwise sinks all loads
