@@ -311,7 +311,8 @@ class Layer:
 
     def close(self):
         if getattr(self, "_h", None) is not None and self._h:
-            load().pzl_layer_destroy(self._h)
+            if _lib is not None:                 # (None again while the interpreter shuts down)
+                _lib.pzl_layer_destroy(self._h)
             self._h = None
 
     __del__ = close

@@ -52,40 +52,67 @@ route_kernel(const int32_t *__restrict__ ids, int32_t n_flat, int32_t k, int32_t
     // pair's weights are swept by one path only.  If at least half of the pairs that have tokens
     // are such pairs, all of them go to the tiled kernels: two half-empty launches one after the
     // other are slower than either path alone.
-    __shared__ int32_t all_tiled;
-    if (tid == 0) {
-        int active = 0, big = 0;
-        for (int g = 0; g < Q / 2; ++g) {
-            int m = max(total[2 * g], total[2 * g + 1]);
-            active += m > 0;
-            big += m >= tile_min;
+    __shared__ int32_t n_active, n_big, scan_c[ROUTE_QMAX], scan_t[ROUTE_QMAX];
+    if (tid == 0) { n_active = 0; n_big = 0; }
+    __syncthreads();
+    for (int g = tid; g < Q / 2; g += ROUTE_THREADS) {
+        int m = max(total[2 * g], total[2 * g + 1]);
+        if (m > 0) atomicAdd(&n_active, 1);
+        if (m >= tile_min) atomicAdd(&n_big, 1);
+    }
+    __syncthreads();
+    const bool all_tiled = n_big > 0 && 2 * n_big >= n_active;
+    // per expert: its count and its number of token tiles (equal parts of at most TILE_MAX_TOKENS,
+    // rounded up to whole fragments of 16) ...
+    for (int q = tid; q < ROUTE_QMAX; q += ROUTE_THREADS) {
+        int c = q < Q ? total[q] : 0;
+        bool t = q < Q && (all_tiled || max(total[q & ~1], total[q | 1]) >= tile_min);   // Q is even: q | 1 < Q
+        int parts = (c + TILE_MAX_TOKENS - 1) / TILE_MAX_TOKENS;
+        int size = parts ? (((c + parts - 1) / parts + 15) & ~15) : 0;
+        scan_c[q] = c;
+        scan_t[q] = t && c ? (c + size - 1) / size : 0;
+        if (q < Q) { tiled_pair[q] = t; cnt[q] = t ? 0 : c; }
+    }
+    __syncthreads();
+    // ... turned into first slot and first tile by an inclusive scan over the ROUTE_QMAX entries
+    // (wave 0: every lane sums its 8 consecutive entries, a shuffle scan over the lanes, then the
+    // lane walks its entries again)
+    if (wave == 0) {
+        constexpr int PER = ROUTE_QMAX / 64;
+        int sc = 0, st = 0;
+#pragma unroll
+        for (int i = 0; i < PER; ++i) { sc += scan_c[lane * PER + i]; st += scan_t[lane * PER + i]; }
+        int ic = sc, it = st;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            int uc = __shfl_up(ic, d), ut = __shfl_up(it, d);
+            if (lane >= d) { ic += uc; it += ut; }
         }
-        all_tiled = big > 0 && 2 * big >= active;
+        int run_c = ic - sc, run_t = it - st;                        // exclusive prefix of this lane
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+            int q = lane * PER + i;
+            int c = scan_c[q], t = scan_t[q];
+            scan_c[q] = run_c; scan_t[q] = run_t;
+            run_c += c; run_t += t;
+        }
+        if (lane == 63) { off[Q] = run_c; *n_tiles = run_t; }
     }
     __syncthreads();
     for (int q = tid; q < Q; q += ROUTE_THREADS) {
-        const bool t = all_tiled || max(total[q & ~1], total[q | 1]) >= tile_min;     // Q is even: q | 1 < Q
-        tiled_pair[q] = t;
-        cnt[q] = t ? 0 : total[q];
+        const int c = total[q], first = scan_c[q];
+        off[q] = first;
+        if (tiled_pair[q] && c > 0) {
+            int parts = (c + TILE_MAX_TOKENS - 1) / TILE_MAX_TOKENS;
+            int size = ((c + parts - 1) / parts + 15) & ~15;
+            int nt = scan_t[q];
+            for (int s0 = 0; s0 < c; s0 += size, ++nt) {
+                tile_q[nt] = q; tile_slot0[nt] = first + s0; tile_n[nt] = min(size, c - s0);
+            }
+        }
     }
     __syncthreads();
-    if (tid == 0) {
-        int run = 0, nt = 0;
-        for (int q = 0; q < Q; ++q) {
-            int c = total[q];
-            total[q] = run; off[q] = run;
-            // token tiles: equal parts of at most TILE_MAX_TOKENS, rounded up to whole fragments of 16
-            int parts = (c + TILE_MAX_TOKENS - 1) / TILE_MAX_TOKENS;
-            int size = parts ? (((c + parts - 1) / parts + 15) & ~15) : 0;
-            for (int s0 = 0; s0 < c && tiled_pair[q]; s0 += size) {
-                tile_q[nt] = q; tile_slot0[nt] = run + s0; tile_n[nt] = min(size, c - s0);
-                ++nt;
-            }
-            run += c;
-        }
-        off[Q] = run;
-        *n_tiles = nt;
-    }
+    for (int q = tid; q < Q; q += ROUTE_THREADS) total[q] = scan_c[q];
     __syncthreads();
     for (int q = tid; q < Q; q += ROUTE_THREADS) {
         int run = total[q];
