@@ -24,13 +24,13 @@ struct RouteTables {
     int32_t *off;        // [Q+1]  first slot of expert q
     int32_t *slot_tok;   // [N]    token index of each slot (slots grouped by q; order inside a group is arbitrary)
     int32_t *slot_of;    // [N]    slot of flat index t*k+j, or -1 for an id outside [0,E)
-    // token tiles of the tiled GEMM path: each expert's slots cut into equal parts of <= 256
+    // token tiles of the tiled GEMM path: each expert's slots cut into equal parts of <= TILE_MAX_TOKENS
     int32_t *tile_q;     // [max_tiles] expert q of the tile
     int32_t *tile_slot0; // [max_tiles] first slot
     int32_t *tile_n;     // [max_tiles] tokens in the tile
     int32_t *n_tiles;    // [1]
 };
-constexpr int TILE_MAX_TOKENS = 256;
+constexpr int TILE_MAX_TOKENS = 288;
 inline int max_token_tiles(int64_t n_flat, int n_experts) { return (int)(n_flat / TILE_MAX_TOKENS) + n_experts; }
 
 void set_hip_error(hipError_t e);

@@ -6,17 +6,17 @@
 // weights do not even reach LDS: each wave loads the packed 16x32 tiles of its own weight rows
 // straight into registers (the tiled layout is already the A operand of
 // v_mfma_f32_16x16x32_bf16), decodes them there and multiplies them with every token of the
-// tile, so each packed word is decoded once per 256 tokens.
+// tile, so each packed word is decoded once per up to 288 tokens.
 //
-// Workgroup tile: up to 256 tokens of one expert x 256 weight rows (gate/up stage: the same 128
+// Workgroup tile: up to 288 tokens of one expert x 256 weight rows (gate/up stage: the same 128
 // feature rows of the gate and of the up matrix, so SwiGLU runs on the accumulators; down stage:
 // 256 rows of the down matrix, with both planes (hi, lo) of H as the token operand).  8 waves,
 // all along the weight rows: a wave owns 2 row tiles (gate + up of 16 features, or 2 down tiles)
-// and all 16 token fragments, 128 accumulator registers, two waves per SIMD.
+// and all (up to 18) token fragments, up to 144 accumulator registers, two waves per SIMD.
 //
 // Token operand: activation rows are gathered by `global_load_lds_dwordx4`, which writes a whole
 // fragment (64 lanes x 16 bytes, already in B operand order) into LDS without passing through
-// registers.  LDS holds a ring of 4 such stages (32 KiB each: 64 K elements of 256 tokens, or 32
+// registers.  LDS holds a ring of 4 such stages (36 KiB each: 64 K elements of 288 tokens, or 32
 // of both H planes), filled three steps ahead; the weights are loaded two steps ahead into two
 // register sets.  One barrier per K step publishes the stage written two steps earlier; no wave
 // writes LDS with ds_write at all.  (Measured on this chip: ds_write_b128 sustains about
@@ -28,8 +28,10 @@
 // also covers the activation stage s+1 issued before them, which the barrier at the end of step
 // s then makes visible to the other waves.
 //
-// Token tiles are cut per expert into equal parts of at most 256 tokens (rounded up to 16),
-// so a 1030-token expert costs 5 x 208 rows rather than 5 x 256.
+// Token tiles are cut per expert into equal parts of at most 288 tokens (rounded up to 16).  The
+// limit is what registers and LDS allow, not a power of two: a tile with few tokens streams the
+// same weights as a full one and costs about half as much (measured), so an expert with 1030
+// tokens is far better served by 4 tiles of 272 than by 4 of 256 and one of 6, or by 5 of 208.
 #include "pzl_common.h"
 
 namespace pzl {
@@ -39,7 +41,7 @@ namespace pzl {
 #endif
 constexpr int TG_WAVES = 8;
 constexpr int TG_THREADS = TG_WAVES * 64;
-constexpr int TG_MAX_TOK = 256;          // tokens per tile (16 fragments of 16)
+constexpr int TG_MAX_TOK = TILE_MAX_TOKENS;   // tokens per tile (18 fragments of 16)
 constexpr int TG_FRAGS = TG_MAX_TOK / 16;
 constexpr int TG_ROW_TILES = 2 * TG_WAVES;    // 16-row weight tiles per workgroup
 constexpr int TG_XSTAGES = 4;
@@ -396,14 +398,15 @@ tile_kernel(TgArgs a)
     n_tok = __builtin_amdgcn_readfirstlane(n_tok);
     const uint16_t *wa = a.w_a[g];
     const uint16_t *wb = (STAGE == TSTAGE_GATEUP) ? a.w_b[g] : wa;
-    const int cnt = (((n_tok + 15) >> 4) + 1) >> 1;          // 1..8 fragments per wave
+    const int cnt = (((n_tok + 15) >> 4) + 1) >> 1;          // 1..9 pairs of token fragments
 #define PZL_TILE(P, C) tile_body<STAGE, DENSE, ALLTOK, P, C>(a, wa, wb, slot0, n_tok, ntile, ks, ring, rowidx)
 #define PZL_TILE_CNT(P)                                                         \
     switch (cnt) {                                                              \
         case 1: PZL_TILE(P, 1); break; case 2: PZL_TILE(P, 2); break;           \
         case 3: PZL_TILE(P, 3); break; case 4: PZL_TILE(P, 4); break;           \
         case 5: PZL_TILE(P, 5); break; case 6: PZL_TILE(P, 6); break;           \
-        case 7: PZL_TILE(P, 7); break; default: PZL_TILE(P, 8); break;          \
+        case 7: PZL_TILE(P, 7); break; case 8: PZL_TILE(P, 8); break;           \
+        default: PZL_TILE(P, 9); break;                                         \
     }
     if (DENSE || pos == 0) { PZL_TILE_CNT(0) } else { PZL_TILE_CNT(1) }
 #undef PZL_TILE_CNT
