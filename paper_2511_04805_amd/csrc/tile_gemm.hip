@@ -108,19 +108,21 @@ __device__ __forceinline__ bf16x8 tg_decode(u32x4 w)
     return __builtin_bit_cast(bf16x8, o);
 }
 
-__device__ __forceinline__ uint32_t tg_bf16_rne(float v)
-{
-    uint32_t u = __float_as_uint(v);
-    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return 0x7FC0u;
-    u += 0x7FFFu + ((u >> 16) & 1u);
-    return u >> 16;
-}
+typedef __bf16 tg_bf16x2 __attribute__((ext_vector_type(2)));
+typedef float tg_f32x2 __attribute__((ext_vector_type(2)));
 
-__device__ __forceinline__ void tg_swiglu_split(float g, float u, uint32_t &hi, uint32_t &lo)
+// silu(g) * u for two elements, split into a bf16 pair of leading parts and a bf16 pair of
+// remainders (low half = first element).  Reciprocal and exponential are the hardware's
+// approximations (1 ulp), far inside the error budget; the conversions are the hardware's
+// round-to-nearest-even.  The tile's epilogue is pure vector arithmetic with no matrix work to
+// hide behind, so its instruction count is wall time.
+__device__ __forceinline__ void tg_swiglu_split2(float g0, float u0, float g1, float u1, uint32_t &hi, uint32_t &lo)
 {
-    float h = (g / (1.0f + __expf(-g))) * u;
-    hi = tg_bf16_rne(h);
-    lo = tg_bf16_rne(h - __uint_as_float(hi << 16));
+    float h0 = g0 * __builtin_amdgcn_rcpf(1.0f + __expf(-g0)) * u0;
+    float h1 = g1 * __builtin_amdgcn_rcpf(1.0f + __expf(-g1)) * u1;
+    hi = __builtin_bit_cast(uint32_t, __builtin_convertvector((tg_f32x2){h0, h1}, tg_bf16x2));
+    float r0 = h0 - __uint_as_float(hi << 16), r1 = h1 - __uint_as_float(hi & 0xFFFF0000u);
+    lo = __builtin_bit_cast(uint32_t, __builtin_convertvector((tg_f32x2){r0, r1}, tg_bf16x2));
 }
 
 typedef const u32x4 __attribute__((address_space(1))) *tg_gvec_ptr;
@@ -329,11 +331,10 @@ __device__ __forceinline__ void tile_body(const TgArgs &a, const uint16_t *wa, c
             int grt = ntile * TG_WAVES + wave;
             if (grt >= row_tiles) continue;
             f32x4 g = acc[0][i], u = acc[1][i];
-            uint32_t hi[4], lo[4];
-#pragma unroll
-            for (int r = 0; r < 4; ++r) tg_swiglu_split(g[r], u[r], hi[r], lo[r]);
-            u32x2 ohi = {hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16)};
-            u32x2 olo = {lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16)};
+            uint32_t hi01, lo01, hi23, lo23;
+            tg_swiglu_split2(g[0], u[0], g[1], u[1], hi01, lo01);
+            tg_swiglu_split2(g[2], u[2], g[3], u[3], hi23, lo23);
+            u32x2 ohi = {hi01, hi23}, olo = {lo01, lo23};
             uint16_t *dst = a.h_out + (int64_t)(slot - a.h_slot_base) * a.rows + grt * 16 + rsub;
             *(u32x2 *)dst = ohi;
             *(u32x2 *)(dst + a.h_plane_stride) = olo;
@@ -459,3 +460,4 @@ int launch_tile_down(const TileGemmArgs &a, int kind, hipStream_t st)
 }
 
 }  // namespace pzl
+
