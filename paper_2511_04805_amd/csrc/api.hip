@@ -93,17 +93,33 @@ static WorkspaceLayout carve(const pzl_layer *L, int32_t T, int32_t k)
     return w;
 }
 
-// Tiled down stage: workgroups = token tiles x rows/256; split K until the launch has about three
-// rounds of workgroups (256 CUs, one workgroup each), keeping at least 8 K steps per workgroup.
-static int choose_tile_ksplit(int64_t token_tiles, int rows, int kdim)
+// Tiled down stage: workgroups = token tiles x rows/256, one per compute unit at a time.  Splitting
+// K over `ks` workgroups fills idle compute units when there are few tiles, but every split writes
+// its own fp32 partial sums, which the combine step then reads back.  Pick the split with the
+// lowest estimated time: rounds of 256 workgroups x (K steps x time per step + fixed cost per
+// tile) + traffic of the partial sums.  The constants are measured on the Mixtral-shaped layer
+// (1.8 us per K step for a full 288-token tile, about half of that for a nearly empty one, 10 us
+// of prologue and epilogue, 5 TB/s for the partial sums); only their ratios matter.
+static int choose_tile_ksplit(int64_t token_tiles, int64_t slots, int rows, int kdim)
 {
-    int64_t wgs = token_tiles * ((rows + 255) / 256);
-    int ks = (int)((768 + wgs - 1) / (wgs > 0 ? wgs : 1));
-    int cap = kdim / TILE_COLS / 8;
-    if (ks > cap) ks = cap;
-    if (ks > MAX_KSPLIT) ks = MAX_KSPLIT;
-    if (ks < 1) ks = 1;
-    return ks;
+    if (token_tiles < 1) token_tiles = 1;
+    const double wgs = (double)token_tiles * ((rows + 255) / 256);
+    const double steps = kdim / TILE_COLS;
+    double fill = (double)slots / ((double)token_tiles * TILE_MAX_TOKENS);
+    if (fill > 1.0) fill = 1.0;
+    const double us_per_step = 1.8 * (0.5 + 0.5 * fill);
+    const double us_partials = (double)slots * rows * 8.0 / 5.0e6;      // written once, read once
+    int best = 1;
+    double best_us = 0.0;
+    for (int ks = 1; ks <= MAX_KSPLIT; ++ks) {
+        if (ks > 1 && steps / ks < 8.0) break;
+        // the tile count is an estimate and tiles differ in length: 10 % more before rounding up,
+        // so that a launch is never planned as an exact number of long rounds
+        const double rounds = (double)(int64_t)((1.1 * wgs * ks + 255.0) / 256.0);
+        const double us = rounds * (steps / ks * us_per_step + 10.0) + ks * us_partials;
+        if (ks == 1 || us < best_us) { best_us = us; best = ks; }
+    }
+    return best;
 }
 
 static int choose_ksplit(int groups_touched_max, int rows)
@@ -395,7 +411,7 @@ int pzl_moe_ffn_staged(const pzl_layer *L, const uint16_t *x, const int32_t *top
     const int routed_groups = L->n_pairs + L->n_dense;
     const int groups_max = (int)((int64_t)N < routed_groups ? N : routed_groups);   // groups that can have tokens
     // one k-split count for all routed slots (the combine step sums that many partials)
-    int ksplit = mostly_tiled ? choose_tile_ksplit(N / TILE_MAX_TOKENS + L->n_experts / 2, L->d_model, L->d_ffn)
+    int ksplit = mostly_tiled ? choose_tile_ksplit(N / TILE_MAX_TOKENS + L->n_experts / 2, N, L->d_model, L->d_ffn)
                            : choose_ksplit(groups_max > 0 ? groups_max : 1, L->d_model);
     if (L->pair_format == 1 && ksplit > L->d_ffn / 128) ksplit = L->d_ffn / 128;   // whole 128-column groups per split
     // one k-split count for all shared experts (the combine step sums that many partials); sized
@@ -405,7 +421,7 @@ int pzl_moe_ffn_staged(const pzl_layer *L, const uint16_t *x, const int32_t *top
     if (tiled_shared) {
         ksplit_shared = MAX_KSPLIT;
         for (int s = 0; s < L->n_shared; ++s) {
-            int ks = choose_tile_ksplit((int64_t)ns * ((T + TILE_MAX_TOKENS - 1) / TILE_MAX_TOKENS), L->d_model, L->shared_f[s]);
+            int ks = choose_tile_ksplit((int64_t)ns * ((T + TILE_MAX_TOKENS - 1) / TILE_MAX_TOKENS), (int64_t)ns * T, L->d_model, L->shared_f[s]);
             if (ks < ksplit_shared) ksplit_shared = ks;
         }
     }

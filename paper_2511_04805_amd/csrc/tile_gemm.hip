@@ -361,29 +361,34 @@ tile_kernel(TgArgs a)
     // at a time form a block of 4 token tiles x 8 row tiles that march through K together: each
     // K slice of activations is shared by 8 of them and each slice of weights by 4, instead of
     // 32 workgroups streaming 32 different activation tiles through one L2.
-    const int total = gridDim.x;
-    const int per_xcd = total / 8;
+    // The grid is sized for the most token tiles the routing could produce; the logical ids are
+    // laid out over the tiles that exist, so that every XCD gets the same share of real work
+    // (ids laid out over the upper bound leave some XCDs a whole round of workgroups short).
+    const int n_mt = ALLTOK ? a.dense_tiles : min(*a.n_tiles, a.max_mtiles);
+    const int gm_count = (n_mt + TG_BLOCK_M - 1) / TG_BLOCK_M;
+    const int gn_count = (a.n_ntiles + TG_BLOCK_N - 1) / TG_BLOCK_N;
+    const int per_ks = gm_count * gn_count * (TG_BLOCK_M * TG_BLOCK_N);   // K splits are the slowest index
+    const int total = per_ks * a.ksplit;
+    const int per_xcd = (total + 7) / 8;
+    if ((int)(blockIdx.x / 8) >= per_xcd) return;
     int logical = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
-    const int per_ks = total / a.ksplit;                     // K splits are the slowest index
+    if (logical >= total) return;
     const int ks = logical / per_ks;
     logical -= ks * per_ks;
-    const int gm_count = (a.max_mtiles + TG_BLOCK_M - 1) / TG_BLOCK_M;
     const int blk = logical / (TG_BLOCK_M * TG_BLOCK_N), r = logical % (TG_BLOCK_M * TG_BLOCK_N);
     const int mt_raw = (blk % gm_count) * TG_BLOCK_M + r % TG_BLOCK_M;
     const int ntile = (blk / gm_count) * TG_BLOCK_N + r / TG_BLOCK_M;
-    if (mt_raw >= a.max_mtiles || ntile >= a.n_ntiles) return;
+    if (mt_raw >= n_mt || ntile >= a.n_ntiles) return;
 
     const int mt = mt_raw;
     int g, pos, slot0, n_tok;
     if (ALLTOK) {
-        if (mt >= a.dense_tiles) return;
         g = mt / ((a.dense_tokens + a.dense_tile_tokens - 1) / a.dense_tile_tokens);
         int t_in = mt % ((a.dense_tokens + a.dense_tile_tokens - 1) / a.dense_tile_tokens);
         pos = 0;
         slot0 = a.dense_slot_base + g * a.dense_tokens + t_in * a.dense_tile_tokens;
         n_tok = min(a.dense_tile_tokens, a.dense_tokens - t_in * a.dense_tile_tokens);
     } else {
-        if (mt >= *a.n_tiles) return;
         int q = a.tile_q[mt];
         g = q >> 1; pos = q & 1;
         if (g < a.group_lo || g >= a.group_hi) return;       // another launch's kind of expert
