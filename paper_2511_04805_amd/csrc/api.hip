@@ -96,10 +96,12 @@ static WorkspaceLayout carve(const pzl_layer *L, int32_t T, int32_t k)
 // Tiled down stage: workgroups = token tiles x rows/256, one per compute unit at a time.  Splitting
 // K over `ks` workgroups fills idle compute units when there are few tiles, but every split writes
 // its own fp32 partial sums, which the combine step then reads back.  Pick the split with the
-// lowest estimated time: rounds of 256 workgroups x (K steps x time per step + fixed cost per
-// tile) + traffic of the partial sums.  The constants are measured on the Mixtral-shaped layer
-// (1.8 us per K step for a full 288-token tile, about half of that for a nearly empty one, 10 us
-// of prologue and epilogue, 5 TB/s for the partial sums); only their ratios matter.
+// lowest estimated time: rounds of 256 workgroups (at least one) x (K steps x time per step +
+// fixed cost per tile) + traffic of the partial sums.  In effect: split only until the launch
+// fills the chip once (measured on the Mixtral-shaped layer at 1024-8192 tokens, every further
+// split lost 3-10 %).  Constants: 1.8 us per K step for a full 288-token tile, about half of
+// that for a nearly empty one, 10 us of prologue and epilogue, 5 TB/s for the partial sums; only
+// their ratios matter.
 static int choose_tile_ksplit(int64_t token_tiles, int64_t slots, int rows, int kdim)
 {
     if (token_tiles < 1) token_tiles = 1;
@@ -113,9 +115,8 @@ static int choose_tile_ksplit(int64_t token_tiles, int64_t slots, int rows, int 
     double best_us = 0.0;
     for (int ks = 1; ks <= MAX_KSPLIT; ++ks) {
         if (ks > 1 && steps / ks < 8.0) break;
-        // the tile count is an estimate and tiles differ in length: 10 % more before rounding up,
-        // so that a launch is never planned as an exact number of long rounds
-        const double rounds = (double)(int64_t)((1.1 * wgs * ks + 255.0) / 256.0);
+        double rounds = wgs * ks / 256.0;          // workgroups are handed out as compute units free up:
+        if (rounds < 1.0) rounds = 1.0;            // measured, whole rounds are not the right granularity
         const double us = rounds * (steps / ks * us_per_step + 10.0) + ks * us_partials;
         if (ks == 1 || us < best_us) { best_us = us; best = ks; }
     }
