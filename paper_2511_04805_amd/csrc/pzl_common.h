@@ -28,7 +28,7 @@ struct RouteTables {
     int32_t *tile_q;     // [max_tiles] expert q of the tile
     int32_t *tile_slot0; // [max_tiles] first slot
     int32_t *tile_n;     // [max_tiles] tokens in the tile
-    int32_t *n_tiles;    // [1]
+    int32_t *n_tiles;    // [64]: [0] number of tiles; [8..39] work counters of the tiled launches, zeroed by the grouping kernel
 };
 constexpr int TILE_MAX_TOKENS = 288;
 inline int max_token_tiles(int64_t n_flat, int n_experts) { return (int)(n_flat / TILE_MAX_TOKENS) + n_experts; }
@@ -122,6 +122,7 @@ struct TileGemmArgs {
     int64_t o_ks_stride;
     int32_t ksplit;               // down stage only: workgroups sharing one output tile along K
     int32_t max_mtiles;           // upper bound on token tiles (grid size)
+    int32_t *tile_ctr;            // routed groups: 8 zeroed counters (one per XCD) for a persistent launch that draws its tiles, or nullptr
 };
 int launch_tile_gateup(const TileGemmArgs &a, int kind, hipStream_t st);
 int launch_tile_down(const TileGemmArgs &a, int kind, hipStream_t st);

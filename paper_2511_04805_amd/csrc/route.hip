@@ -97,6 +97,7 @@ route_kernel(const int32_t *__restrict__ ids, int32_t n_flat, int32_t k, int32_t
             run_c += c; run_t += t;
         }
         if (lane == 63) { off[Q] = run_c; *n_tiles = run_t; }
+        if (lane >= 8 && lane < 40) n_tiles[lane] = 0;               // work counters of the tiled launches
     }
     __syncthreads();
     for (int q = tid; q < Q; q += ROUTE_THREADS) {

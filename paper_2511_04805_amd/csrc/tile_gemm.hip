@@ -47,6 +47,7 @@ constexpr int TG_ROW_TILES = 2 * TG_WAVES;    // 16-row weight tiles per workgro
 constexpr int TG_XSTAGES = 4;
 constexpr int TG_XSTAGE_UNITS = TG_FRAGS * 2 * 64;   // 16-byte units per stage (16 fragments x 2 k-blocks or planes)
 constexpr int TSTAGE_GATEUP = 0, TSTAGE_DOWN = 1;
+constexpr int TG_PERSISTENT_WGS = 256;   // workgroups of a persistent launch: one per compute unit (8 XCDs x 32)
 #ifndef TG_READ_AHEAD
 #define TG_READ_AHEAD 3     // fragment reads kept in flight ahead of the matrix instructions
 #endif
@@ -74,6 +75,7 @@ struct TgArgs {
     float *o_out;
     int64_t o_ks_stride;
     int32_t max_mtiles, n_ntiles, ksplit;
+    int32_t *tile_ctr;
 };
 
 __device__ __forceinline__ uint32_t tg_decode_body(uint32_t x) { return (x & 0x0FFF0FFFu) + 0x38003800u; }
@@ -136,7 +138,7 @@ typedef __attribute__((address_space(3))) void *tg_lds_ptr;
 template <int STAGE, bool DENSE, bool ALLTOK, int POS, int CNT>
 __device__ __forceinline__ void tile_body(const TgArgs &a, const uint16_t *wa, const uint16_t *wb,
                                           int slot0, int n_tok, int ntile, int ks,
-                                          u32x4 *ring, int32_t *rowidx)
+                                          u32x4 *ring, int32_t *rowidx, int32_t *draw_ctr, int32_t *drawn)
 {
     constexpr int KBS = (STAGE == TSTAGE_DOWN) ? 1 : 2;      // k-blocks (of 32) per K step
     constexpr int PARTS = (STAGE == TSTAGE_DOWN) ? 2 : 1;    // activation planes (hi, lo)
@@ -320,6 +322,11 @@ __device__ __forceinline__ void tile_body(const TgArgs &a, const uint16_t *wa, c
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __builtin_amdgcn_sched_barrier(0);
 
+    // Draw this workgroup's next tile now (see tile_kernel): the counter's answer travels while
+    // the epilogue computes, and is waited for before the epilogue's stores pile up behind it.
+    int next_draw = 0;
+    if (draw_ctr && tid == 0) next_draw = atomicAdd(draw_ctr, 1);
+
     // ---- epilogue: lane holds rows 4*(lane/16)..+3 of its row tile for token column lane%16 ----
     const int col = lane & 15, rsub = (lane >> 4) * 4;
 #pragma unroll
@@ -347,40 +354,22 @@ __device__ __forceinline__ void tile_body(const TgArgs &a, const uint16_t *wa, c
             }
         }
     }
+    if (draw_ctr && tid == 0) *drawn = next_draw;
 }
 
+// One token tile x one block of weight rows, given its logical id (see tile_kernel for the order).
+// Returns whether the tile ran (and, if asked to, drew the workgroup's next id into *drawn).
 template <int STAGE, bool DENSE, bool ALLTOK>
-__global__ void __launch_bounds__(TG_THREADS) __attribute__((amdgpu_waves_per_eu(TG_WPE, TG_WPE)))
-tile_kernel(TgArgs a)
+__device__ __forceinline__ bool tile_run(const TgArgs &a, int logical, int n_mt, int gm_count, int per_ks,
+                                         u32x4 *ring, int32_t *rowidx, int32_t *draw_ctr, int32_t *drawn)
 {
-    __shared__ u32x4 ring[TG_XSTAGES * TG_XSTAGE_UNITS];
-    __shared__ int32_t rowidx[TG_MAX_TOK];
-
-    // XCD-aware order.  Consecutive workgroup ids go to different XCDs (8 of them, each with its
-    // own L2), so give each XCD a contiguous range of logical ids.  The 32 workgroups an XCD runs
-    // at a time form a block of 4 token tiles x 8 row tiles that march through K together: each
-    // K slice of activations is shared by 8 of them and each slice of weights by 4, instead of
-    // 32 workgroups streaming 32 different activation tiles through one L2.
-    // The grid is sized for the most token tiles the routing could produce; the logical ids are
-    // laid out over the tiles that exist, so that every XCD gets the same share of real work
-    // (ids laid out over the upper bound leave some XCDs a whole round of workgroups short).
-    const int n_mt = ALLTOK ? a.dense_tiles : min(*a.n_tiles, a.max_mtiles);
-    const int gm_count = (n_mt + TG_BLOCK_M - 1) / TG_BLOCK_M;
-    const int gn_count = (a.n_ntiles + TG_BLOCK_N - 1) / TG_BLOCK_N;
-    const int per_ks = gm_count * gn_count * (TG_BLOCK_M * TG_BLOCK_N);   // K splits are the slowest index
-    const int total = per_ks * a.ksplit;
-    const int per_xcd = (total + 7) / 8;
-    if ((int)(blockIdx.x / 8) >= per_xcd) return;
-    int logical = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
-    if (logical >= total) return;
     const int ks = logical / per_ks;
     logical -= ks * per_ks;
     const int blk = logical / (TG_BLOCK_M * TG_BLOCK_N), r = logical % (TG_BLOCK_M * TG_BLOCK_N);
-    const int mt_raw = (blk % gm_count) * TG_BLOCK_M + r % TG_BLOCK_M;
+    const int mt = (blk % gm_count) * TG_BLOCK_M + r % TG_BLOCK_M;
     const int ntile = (blk / gm_count) * TG_BLOCK_N + r / TG_BLOCK_M;
-    if (mt_raw >= n_mt || ntile >= a.n_ntiles) return;
+    if (mt >= n_mt || ntile >= a.n_ntiles) return false;
 
-    const int mt = mt_raw;
     int g, pos, slot0, n_tok;
     if (ALLTOK) {
         g = mt / ((a.dense_tokens + a.dense_tile_tokens - 1) / a.dense_tile_tokens);
@@ -391,7 +380,7 @@ tile_kernel(TgArgs a)
     } else {
         int q = a.tile_q[mt];
         g = q >> 1; pos = q & 1;
-        if (g < a.group_lo || g >= a.group_hi) return;       // another launch's kind of expert
+        if (g < a.group_lo || g >= a.group_hi) return false;  // another launch's kind of expert
         g -= a.group_lo;
         slot0 = a.tile_slot0[mt];
         n_tok = a.tile_n[mt];
@@ -405,7 +394,7 @@ tile_kernel(TgArgs a)
     const uint16_t *wa = a.w_a[g];
     const uint16_t *wb = (STAGE == TSTAGE_GATEUP) ? a.w_b[g] : wa;
     const int cnt = (((n_tok + 15) >> 4) + 1) >> 1;          // 1..9 pairs of token fragments
-#define PZL_TILE(P, C) tile_body<STAGE, DENSE, ALLTOK, P, C>(a, wa, wb, slot0, n_tok, ntile, ks, ring, rowidx)
+#define PZL_TILE(P, C) tile_body<STAGE, DENSE, ALLTOK, P, C>(a, wa, wb, slot0, n_tok, ntile, ks, ring, rowidx, draw_ctr, drawn)
 #define PZL_TILE_CNT(P)                                                         \
     switch (cnt) {                                                              \
         case 1: PZL_TILE(P, 1); break; case 2: PZL_TILE(P, 2); break;           \
@@ -417,6 +406,71 @@ tile_kernel(TgArgs a)
     if (DENSE || pos == 0) { PZL_TILE_CNT(0) } else { PZL_TILE_CNT(1) }
 #undef PZL_TILE_CNT
 #undef PZL_TILE
+    return true;
+}
+
+template <int STAGE, bool DENSE, bool ALLTOK, bool PERSIST>
+__global__ void __launch_bounds__(TG_THREADS) __attribute__((amdgpu_waves_per_eu(TG_WPE, TG_WPE)))
+tile_kernel(TgArgs a)
+{
+    __shared__ u32x4 ring[TG_XSTAGES * TG_XSTAGE_UNITS];
+    __shared__ int32_t rowidx[TG_MAX_TOK];
+    __shared__ int32_t drawn;
+
+    // XCD-aware order.  Consecutive workgroup ids go to different XCDs (8 of them, each with its
+    // own L2), so give each XCD a contiguous range of logical ids.  The 32 workgroups an XCD runs
+    // at a time form a block of 4 token tiles x 8 row tiles that march through K together: each
+    // K slice of activations is shared by 8 of them and each slice of weights by 4, instead of
+    // 32 workgroups streaming 32 different activation tiles through one L2.
+    // The logical ids are laid out over the tiles that exist, so that every XCD gets the same
+    // share of real work (laid out over the upper bound, some XCDs end a whole round of
+    // workgroups short).
+    // Routed experts: the number of tiles is only known on the device.  Where the upper bound is
+    // close (few experts, many tokens each) the grid is the upper bound, one tile per workgroup.
+    // Where it can be many times too large (many experts: one more tile per expert than the token
+    // count alone would give; a launch of workgroups that find nothing to do still costs 5-10 us,
+    // and tiles of very different sizes want to be handed out one by one) the launch is
+    // persistent: one workgroup per compute unit, each working through its XCD's range of ids.
+    // Shared experts: the host knows the tiles, one workgroup each.
+    const int xcd = blockIdx.x % 8;
+    const int n_mt = ALLTOK ? a.dense_tiles : min(*a.n_tiles, a.max_mtiles);
+    const int gm_count = (n_mt + TG_BLOCK_M - 1) / TG_BLOCK_M;
+    const int gn_count = (a.n_ntiles + TG_BLOCK_N - 1) / TG_BLOCK_N;
+    const int per_ks = gm_count * gn_count * (TG_BLOCK_M * TG_BLOCK_N);   // K splits are the slowest index
+    const int total = per_ks * a.ksplit;
+    const int per_xcd = (total + 7) / 8;
+    // A persistent workgroup takes its first tiles by fixed stride (three quarters of an even
+    // share: the workgroups of an XCD then stay in step on one block of tiles) and draws the rest
+    // from its XCD's counter, which evens out what tiles of different sizes left uneven.  A tile
+    // draws its successor between its K loop and its epilogue, so that the counter's answer
+    // travels while the epilogue computes.
+    constexpr bool persistent = PERSIST;        // a template parameter: the one-shot kernel compiles without the loop
+    const int wg = blockIdx.x / 8, wgs = gridDim.x / 8;
+    const int fixed_rounds = per_xcd / wgs * 3 / 4;
+    int32_t *ctr = persistent ? a.tile_ctr + xcd : nullptr;
+    bool have_draw = false;
+    for (int round = 0;; ++round) {
+        int i;
+        if (!persistent) {
+            if (round > 0) return;
+            i = wg;
+        } else if (round < fixed_rounds) {
+            // every wave is past the previous tile here (its loads have landed, its LDS reads
+            // are done), so the next tile may overwrite the ring and the row indices
+            __syncthreads();
+            i = round * wgs + wg;
+        } else {
+            if (!have_draw && threadIdx.x == 0) drawn = atomicAdd(ctr, 1);
+            __syncthreads();
+            i = fixed_rounds * wgs + __builtin_amdgcn_readfirstlane(drawn);
+        }
+        if (i >= per_xcd || xcd * per_xcd + i >= total) return;
+        // the tile after this one is drawn by this one unless it is a fixed one
+        const bool draw = persistent && round + 1 >= fixed_rounds;
+        have_draw = tile_run<STAGE, DENSE, ALLTOK>(a, xcd * per_xcd + i, n_mt, gm_count, per_ks, ring, rowidx,
+                                                   draw ? ctr : nullptr, &drawn) && draw;
+        if (persistent && !have_draw) __syncthreads();     // everyone has read `drawn` before it is written again
+    }
 }
 
 template <int STAGE, bool DENSE, bool ALLTOK>
@@ -442,7 +496,13 @@ static int launch(const TileGemmArgs &t, hipStream_t st)
                      ((a.n_ntiles + TG_BLOCK_N - 1) / TG_BLOCK_N) * (TG_BLOCK_M * TG_BLOCK_N);
     blocks = (blocks + 7) / 8 * 8 * a.ksplit;
     if (blocks > 0x7FFFFFFFLL) return PZL_EINVAL;
-    hipLaunchKernelGGL((tile_kernel<STAGE, DENSE, ALLTOK>), dim3((unsigned)blocks), dim3(TG_THREADS), 0, st, a);
+    a.tile_ctr = nullptr;
+    if (!ALLTOK && t.tile_ctr) {                  // persistent: one workgroup per compute unit, tiles are drawn
+        a.tile_ctr = t.tile_ctr;
+        if (blocks > TG_PERSISTENT_WGS) blocks = TG_PERSISTENT_WGS;
+    }
+    if (a.tile_ctr) hipLaunchKernelGGL((tile_kernel<STAGE, DENSE, ALLTOK, !ALLTOK>), dim3((unsigned)blocks), dim3(TG_THREADS), 0, st, a);
+    else            hipLaunchKernelGGL((tile_kernel<STAGE, DENSE, ALLTOK, false>), dim3((unsigned)blocks), dim3(TG_THREADS), 0, st, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) { set_hip_error(e); return PZL_EHIP; }
     return PZL_OK;

@@ -17,7 +17,7 @@ def test_tile_kernel_in_flight_registers(tmp_path):
     n_loops, n_exits, problems = check_tile_isa.check(asm.read_text())
     assert not problems, problems[:5]
     # 6 kernels x 2 positions (packed) or 1 (dense) x 8 tile sizes
-    assert n_loops == 72 and n_exits == 72, (n_loops, n_exits)
+    assert n_loops == 126 and n_exits == 126, (n_loops, n_exits)
 
 
 def test_checker_flags_a_planted_copy():
