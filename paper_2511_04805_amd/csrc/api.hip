@@ -49,7 +49,7 @@ namespace pzl {
 #endif
 constexpr int TILED_MIN_TOKENS_PER_EXPERT = PZL_TILED_MIN_TPE;   // average tokens per expert from which the K split is sized for the tiled kernels
 #ifndef PZL_HYBRID_MIN_TPE
-#define PZL_HYBRID_MIN_TPE 20
+#define PZL_HYBRID_MIN_TPE 8
 #endif
 #ifndef PZL_HYBRID_TILE_MIN
 #define PZL_HYBRID_TILE_MIN 33
@@ -394,7 +394,11 @@ int pzl_moe_ffn_staged(const pzl_layer *L, const uint16_t *x, const int32_t *top
     // The host only knows the batch shape, not how the router spread the tokens: from an average
     // of HYBRID_MIN_TOKENS_PER_EXPERT both paths are launched and the grouping kernel decides
     // per pair (tile_min).  Below that average only the streaming kernels are launched (two
-    // empty tiled launches would cost the decode step 3 %).
+    // empty tiled launches would cost the decode step 3 %).  The average is set low: a router
+    // that favours some experts gives them several sweeps' worth of tokens long before the
+    // average says so (64 experts, top-6, skewed: 96-192 tokens 272-464 us streamed, 201-246 us
+    // with the busy pairs tiled), while two launches that find no tile cost 10-20 us (60
+    // experts, top-4, even routing, 128-192 tokens: 155-171 -> 178-182 us).
     // (quantised pairs have no tiled kernel: they always stream)
     const int64_t E64 = L->n_experts;
     const bool hybrid = L->pair_format == 0 && (int64_t)N >= (int64_t)HYBRID_MIN_TOKENS_PER_EXPERT * E64;
