@@ -49,12 +49,16 @@ namespace pzl {
 #endif
 constexpr int TILED_MIN_TOKENS_PER_EXPERT = PZL_TILED_MIN_TPE;   // average tokens per expert from which the K split is sized for the tiled kernels
 #ifndef PZL_HYBRID_MIN_TPE
-#define PZL_HYBRID_MIN_TPE 8
+#define PZL_HYBRID_MIN_TPE 20
+#endif
+#ifndef PZL_HYBRID_MIN_TPE_MANY
+#define PZL_HYBRID_MIN_TPE_MANY 8
 #endif
 #ifndef PZL_HYBRID_TILE_MIN
 #define PZL_HYBRID_TILE_MIN 33
 #endif
 constexpr int HYBRID_MIN_TOKENS_PER_EXPERT = PZL_HYBRID_MIN_TPE;  // average from which both paths are launched
+constexpr int HYBRID_MIN_TOKENS_PER_EXPERT_MANY = PZL_HYBRID_MIN_TPE_MANY;   // ... in a layer with 32 experts or more
 constexpr int HYBRID_TILE_MIN_TOKENS = PZL_HYBRID_TILE_MIN;       // ... and a pair with an expert of this many tokens is tiled
 constexpr int TILED_MIN_TOKENS_SHARED = PZL_TILED_MIN_SHARED;     // a dense expert sees every token but has few row tiles: the tiled path needs >= 4 token tiles
 constexpr int MAX_KSPLIT = 8;   // upper bound on the k-splits of the down stage (sizes the workspace)
@@ -394,14 +398,16 @@ int pzl_moe_ffn_staged(const pzl_layer *L, const uint16_t *x, const int32_t *top
     // The host only knows the batch shape, not how the router spread the tokens: from an average
     // of HYBRID_MIN_TOKENS_PER_EXPERT both paths are launched and the grouping kernel decides
     // per pair (tile_min).  Below that average only the streaming kernels are launched (two
-    // empty tiled launches would cost the decode step 3 %).  The average is set low: a router
-    // that favours some experts gives them several sweeps' worth of tokens long before the
-    // average says so (64 experts, top-6, skewed: 96-192 tokens 272-464 us streamed, 201-246 us
-    // with the busy pairs tiled), while two launches that find no tile cost 10-20 us (60
-    // experts, top-4, even routing, 128-192 tokens: 155-171 -> 178-182 us).
+    // empty tiled launches would cost the decode step 3 %).  With many experts the average is
+    // set low: a router that favours some experts gives them several sweeps' worth of tokens
+    // long before the average says so (64 experts, top-6, skewed: 96-192 tokens 272-464 us
+    // streamed, 201-246 us with the busy pairs tiled), while two launches that find no tile cost
+    // 10-20 us (60 experts, top-4, even routing, 128-192 tokens: 155-171 -> 178-182 us).  With
+    // few experts the counts stay near their average.
     // (quantised pairs have no tiled kernel: they always stream)
     const int64_t E64 = L->n_experts;
-    const bool hybrid = L->pair_format == 0 && (int64_t)N >= (int64_t)HYBRID_MIN_TOKENS_PER_EXPERT * E64;
+    const bool hybrid = L->pair_format == 0 &&
+        (int64_t)N >= (int64_t)(E64 >= 32 ? HYBRID_MIN_TOKENS_PER_EXPERT_MANY : HYBRID_MIN_TOKENS_PER_EXPERT) * E64;
     const int tile_min = hybrid ? HYBRID_TILE_MIN_TOKENS : 0x7FFFFFFF;
     const bool tiled = hybrid, streamed = true;
     const bool mostly_tiled = hybrid && (int64_t)N >= (int64_t)TILED_MIN_TOKENS_PER_EXPERT * E64;
