@@ -25,7 +25,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of the gate/up streaming kernel at T = 64, from the two rocprofv3 --pmc runs
 # (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, calibrated on the copy below) summarised in
 # profiles/stream_kernels_mixtral_decode_T64.md.  Counters cannot be read inside this process.
-MEASURED_TRAFFIC_BYTES = {"mixtral_decode_T64": 955.0e6, "mixtral_decode_T64_quantised": 413.7e6}
+MEASURED_TRAFFIC_BYTES = {"mixtral_decode_T64": 954.9e6, "mixtral_decode_T64_quantised": 429.8e6}
 W3 = (synth.GATE, synth.UP, synth.DOWN)
 
 
