@@ -89,3 +89,23 @@ def test_deepseek_moe_shaped(oracle, binding):
     ids = check_rows(case, 2048, 192)
     counts = np.sort(np.bincount(ids.ravel(), minlength=cfg.n_experts))
     assert counts[-1] > 10 * counts[0]                         # Zipf-skewed expert popularity
+    # Calls in a row on one workspace: the persistent tiled launches draw their tiles from
+    # counters that every call must find at zero, whatever the call before left there.  The same
+    # batch gives the same bits before and after a different batch (and after a small one that
+    # takes the streaming path only).
+    xa, (ida, wa) = synth.tokens(cfg, 1024), synth.routing(cfg, 1024)
+    xb, (idb, wb) = synth.tokens(cfg, 1536), synth.routing(cfg, 1536)
+    xc, (idc, wc) = synth.tokens(cfg, 8), synth.routing(cfg, 8)
+    y1 = case.gpu(xa, ida, wa)
+    case.gpu(xb, idb, wb)
+    y2 = case.gpu(xa, ida, wa)
+    case.gpu(xc, idc, wc)
+    y3 = case.gpu(xa, ida, wa)
+    assert np.array_equal(y1.view(np.uint16), y2.view(np.uint16))
+    assert np.array_equal(y1.view(np.uint16), y3.view(np.uint16))
+    rows = np.sort(np.random.RandomState(5).choice(1024, 16, replace=False))
+    y64, _ = case.ref(xa[rows], ida[rows], wa[rows])
+    ok, worst = tolerance_ok(y1[rows], y64)
+    say("  T=1024 after other batches: worst err / bound = %.3f" % worst)
+    assert ok, worst
+
