@@ -439,14 +439,14 @@ tile_kernel(TgArgs a)
     const int per_ks = gm_count * gn_count * (TG_BLOCK_M * TG_BLOCK_N);   // K splits are the slowest index
     const int total = per_ks * a.ksplit;
     const int per_xcd = (total + 7) / 8;
-    // A persistent workgroup takes its first tiles by fixed stride (three quarters of an even
+    // A persistent workgroup takes its first tiles by fixed stride (half of an even
     // share: the workgroups of an XCD then stay in step on one block of tiles) and draws the rest
     // from its XCD's counter, which evens out what tiles of different sizes left uneven.  A tile
     // draws its successor between its K loop and its epilogue, so that the counter's answer
     // travels while the epilogue computes.
     constexpr bool persistent = PERSIST;        // a template parameter: the one-shot kernel compiles without the loop
     const int wg = blockIdx.x / 8, wgs = gridDim.x / 8;
-    const int fixed_rounds = per_xcd / wgs * 3 / 4;
+    const int fixed_rounds = per_xcd / wgs / 2;
     int32_t *ctr = persistent ? a.tile_ctr + xcd : nullptr;
     bool have_draw = false;
     for (int round = 0;; ++round) {
