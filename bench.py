@@ -22,10 +22,11 @@ sys.path.insert(0, ROOT)
 from paper_2511_04805_amd import binding, synth  # noqa: E402
 
 HBM_PEAK_GBS = 8000.0
-# HBM bytes per launch of the gate/up streaming kernel at T = 64, from the two rocprofv3 --pmc runs
-# (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, calibrated on the copy below) summarised in
-# profiles/stream_kernels_mixtral_decode_T64.md.  Counters cannot be read inside this process.
-MEASURED_TRAFFIC_BYTES = {"mixtral_decode_T64": 954.9e6, "mixtral_decode_T64_quantised": 429.8e6}
+# Bytes between L2 and memory per launch of the gate/up kernels (streaming at T = 64, tiled at
+# T = 4096), from rocprofv3 --pmc runs (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, calibrated on the
+# copy below) summarised under profiles/.  Counters cannot be read inside this process.
+MEASURED_TRAFFIC_BYTES = {"mixtral_decode_T64": 954.9e6, "mixtral_decode_T64_quantised": 429.8e6,
+                          "mixtral_prefill_T4096": 8.368e9}
 W3 = (synth.GATE, synth.UP, synth.DOWN)
 
 
@@ -229,7 +230,8 @@ def main():
             "workload": "mixtral_prefill_T4096", "tokens_per_s": Tp / (ms_p * 1e-3), "ms_per_step": ms_p,
             "roofline": {"bound": "mfma", "kernel": "tile_kernel<gate/up + SwiGLU>",
                          "achieved": 2 * fl_proj / (ms_gu * 1e-3) / 1e12, "peak": 2500.0, "unit": "TFLOP/s",
-                         "frac": 2 * fl_proj / (ms_gu * 1e-3) / 2.5e15, "traffic": None, "avg_launch_ms": ms_gu},
+                         "frac": 2 * fl_proj / (ms_gu * 1e-3) / 2.5e15,
+                         "traffic": MEASURED_TRAFFIC_BYTES.get("mixtral_prefill_T%d" % Tp), "avg_launch_ms": ms_gu},
             "down_kernel": {"avg_launch_ms": ms_dn, "useful_TFLOPs": fl_proj / (ms_dn * 1e-3) / 1e12,
                             "executed_TFLOPs": 2 * fl_proj / (ms_dn * 1e-3) / 1e12},
             "path_useful_mfma_frac": 3 * fl_proj / (ms_p * 1e-3) / 2.5e15}
