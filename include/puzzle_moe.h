@@ -180,6 +180,9 @@ size_t pzl_moe_ffn_workspace_bytes(const pzl_layer *layer, int32_t max_tokens, i
  *   topk_w    [T, k] fp32 routing weights
  *   y         [T, d_model] bf16 bits, overwritten
  *   workspace at least pzl_moe_ffn_workspace_bytes(layer, T, k) bytes; contents are scratch
+ * Size limits of one call (the kernels address activations with 32-bit byte offsets; larger
+ * batches are to be split by the caller): T * d_model < 2^31, T * k * d_ffn < 2^30, and for the
+ * shared experts n_shared * T * f_shared < 2^30; PZL_EINVAL beyond them.
  * T == 0 is a no-op.  Calls on one layer that overlap in time (different streams) are not
  * supported when the layer has shared experts (see pzl_layer_create); otherwise they must use
  * different workspaces.

@@ -334,10 +334,19 @@ void pzl_layer_destroy(pzl_layer *layer)
     delete layer;
 }
 
+// The kernels address x, H (two planes) and the shared experts' H with 32-bit byte offsets.
+static bool batch_fits(const pzl_layer *L, int64_t T, int64_t k)
+{
+    if (T * L->d_model >= (1LL << 31) || T * k * L->d_ffn >= (1LL << 30)) return false;
+    for (int s = 0; s < L->n_shared; ++s)
+        if ((int64_t)L->n_shared * T * L->shared_f[s] >= (1LL << 30)) return false;
+    return true;
+}
+
 size_t pzl_moe_ffn_workspace_bytes(const pzl_layer *layer, int32_t max_tokens, int32_t top_k)
 {
     if (!layer || max_tokens < 0 || top_k < 0) return 0;
-    if ((int64_t)max_tokens * top_k > 0x3FFFFFFF) return 0;
+    if ((int64_t)max_tokens * top_k > 0x3FFFFFFF || !batch_fits(layer, max_tokens, top_k)) return 0;
     // every buffer grows with T, so the layout at max_tokens bounds all smaller batches
     return carve(layer, max_tokens, top_k).total;
 }
@@ -363,6 +372,7 @@ int pzl_moe_ffn_staged(const pzl_layer *L, const uint16_t *x, const int32_t *top
     if (T == 0) return PZL_OK;
     if (!x || !y || (k > 0 && (!topk_ids || !topk_w)) || !workspace) return PZL_EINVAL;
     if ((int64_t)T * k > 0x3FFFFFFF || ((uintptr_t)workspace & 255)) return PZL_EINVAL;
+    if (!batch_fits(L, T, k)) return PZL_EINVAL;
     const WorkspaceLayout w = carve(L, T, k);
     if (workspace_bytes < w.total) return PZL_ENOSPC;
     hipStream_t st = (hipStream_t)stream;

@@ -163,6 +163,13 @@ def test_error_codes(small_case, binding):
                       [case.packed_gpu[p, synth.UP] for p in range(3)],
                       [case.packed_gpu[p, synth.DOWN] for p in range(3)])
     assert lib.pzl_moe_ffn_workspace_bytes(case.layer._h, -1, 2) == 0
+    # a batch beyond the documented size limits (T * k * d_ffn < 2^30) is refused, not mis-addressed
+    too_many = (1 << 30) // (2 * cfg.d_ffn) + 1
+    assert lib.pzl_moe_ffn_workspace_bytes(case.layer._h, too_many, 2) == 0
+    assert lib.pzl_moe_ffn_workspace_bytes(case.layer._h, too_many - 2, 2) > 0
+    rc = lib.pzl_moe_ffn(case.layer._h, x.data_ptr(), ids.data_ptr(), w.data_ptr(), too_many, 2,
+                         x.data_ptr(), small_ws.data_ptr(), 256, None)
+    assert rc == binding.PZL_EINVAL
 
 
 @pytest.mark.parametrize("shape,tau", [((64, 96), 0.4), ((256, 512), 0.4), ((1408, 2048), 0.25)])
