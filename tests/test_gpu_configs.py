@@ -76,6 +76,11 @@ def test_mixtral_prefill(mixtral):
     assert counts.min() > 850 and counts.max() < 1200          # near-uniform expert load
 
 
+def test_mixtral_large_batch(mixtral):
+    # four times the prefill batch: ~57 token tiles per expert, several rounds of workgroups
+    check_rows(mixtral, 16384, 8, seed=3)
+
+
 def test_qwen15_moe_shaped(oracle, binding):
     case = Case(synth.CONFIGS["qwen15_moe"], oracle, binding)
     check_unpack_everywhere(case)
