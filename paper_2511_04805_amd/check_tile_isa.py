@@ -10,8 +10,10 @@ overwrite an unrelated value such as an address.
 
 This module compiles `csrc/tile_gemm.hip` to gfx950 assembly and verifies, for every K loop, that
 no instruction after an inline-asm `global_load_dwordx4` names one of its destination registers
-before the loop wraps around, that every loop exit waits for all loads before any vector
-instruction, and that nothing spills.  Run it after any change to the kernel or the compiler:
+before the loop wraps around (one exception: a lane-0 read into a scalar register that is
+overwritten before it is read on every path, which is how the compiler materialises an undefined
+value), that every loop exit waits for all loads before any vector instruction, and that nothing
+spills.  Run it after any change to the kernel or the compiler:
 
     python -m paper_2511_04805_amd.check_tile_isa
 """
@@ -40,6 +42,103 @@ def _regs(text):
         else:
             out.add(int(m.group(3)))
     return out
+
+
+_SREG = re.compile(r"s\[(\d+):(\d+)\]|\bs(\d+)\b")
+
+
+def _sregs(text):
+    out = set()
+    for m in _SREG.finditer(text):
+        if m.group(1):
+            out.update(range(int(m.group(1)), int(m.group(2)) + 1))
+        else:
+            out.add(int(m.group(3)))
+    return out
+
+
+def _scalar_dead(lines, labels, i, reg, seen, budget, ones=frozenset(), vcc_zero=False):
+    """True if scalar register `reg` is overwritten before it is read on every feasible path from
+    line i (a plain copy into another scalar register is followed: the copy must be dead too).
+    `ones`: scalar registers known to hold all ones on the current straight-line path, which is
+    how the compiler flags "this is the exit path": vcc = exec & ~ones is then zero and a branch
+    on vcc non-zero is not taken."""
+    ones = set(ones)
+    while i < len(lines):
+        budget[0] -= 1
+        if budget[0] <= 0:
+            return False
+        t = lines[i].split(";")[0].strip()
+        i += 1
+        if not t or (t.startswith(".") and not t.endswith(":")):
+            continue
+        if t.endswith(":"):                      # a join point: forget what was known
+            ones.clear()
+            vcc_zero = False
+            continue
+        parts = t.replace(",", " ").split()
+        op, ops = parts[0], parts[1:]
+        if op == "s_endpgm":
+            return True
+        if op in ("s_setpc_b64", "s_swappc_b64"):
+            return False
+        if re.match(r"(s_cbranch_\w+|s_branch)$", op):
+            if op == "s_cbranch_vccnz" and vcc_zero:
+                continue                          # not taken
+            tgt = labels.get(ops[0])
+            if tgt is None:
+                return False
+            key = (tgt, reg)
+            if key not in seen:
+                seen.add(key)
+                if not _scalar_dead(lines, labels, tgt, reg, seen, budget):
+                    return False
+            if op == "s_branch" or (op == "s_cbranch_vccz" and vcc_zero):
+                return True
+            continue
+        writes_first = not re.match(r"(s_cmp|s_bitcmp|s_waitcnt|s_nop|s_barrier|s_sleep|s_setprio|v_cmp|v_cmpx|global_|ds_|buffer_|scratch_|flat_)", op)
+        read_text = " ".join(ops[1:]) if (writes_first and ops) else " ".join(ops)
+        if reg in _sregs(read_text):
+            if op == "s_mov_b32" and len(ops) == 2 and _sregs(ops[1]) == {reg} and len(_sregs(ops[0])) == 1:
+                if not _scalar_dead(lines, labels, i, next(iter(_sregs(ops[0]))), seen, budget, frozenset(ones), vcc_zero):
+                    return False
+                continue
+            return False
+        if op == "s_andn2_b64" and len(ops) == 3 and ops[0] == "vcc" and ops[1] == "exec" and _sregs(ops[2]) and _sregs(ops[2]) <= ones:
+            vcc_zero = True
+        elif writes_first and ops and ops[0] == "vcc" or op.startswith("v_cmp"):
+            vcc_zero = False
+        if writes_first and ops:
+            w = _sregs(ops[0])
+            if op == "s_mov_b64" and len(ops) == 2 and ops[1] == "-1":
+                ones |= w
+            else:
+                ones -= w
+            if reg in w:
+                return True
+    return False
+
+
+def _known_ones(lines, i):
+    """Scalar registers set to all ones by an s_mov_b64 in the straight-line code just above line i
+    and not written since."""
+    ones, written = set(), set()
+    j = i - 1
+    while j >= 0:
+        t = lines[j].split(";")[0].strip()
+        j -= 1
+        if not t:
+            continue
+        if t.endswith(":") or re.match(r"s_c?branch", t):
+            break
+        parts = t.replace(",", " ").split()
+        if parts[0].startswith(("s_cmp", "s_bitcmp", "s_waitcnt", "s_nop", "v_cmp", "global_", "ds_")) or len(parts) < 2:
+            continue
+        w = _sregs(parts[1])
+        if parts[0] == "s_mov_b64" and len(parts) == 3 and parts[2] == "-1":
+            ones |= (w - written)
+        written |= w
+    return frozenset(ones)
 
 
 def check(asm_text):
@@ -81,6 +180,13 @@ def check(asm_text):
             is_load = in_asm and "global_load_dwordx4" in t
             hit = _regs(t) & inflight
             if hit and not is_load:
+                # The compiler materialises an undefined scalar (a loop-carried value on an exit
+                # path) by reading lane 0 of any vector register.  Reading an in-flight register
+                # does not disturb the load; it is accepted only if the scalar is provably dead.
+                mrf = re.match(r"\s*v_readfirstlane_b32\s+s(\d+),\s*v\d+\s*$", t)
+                if mrf and _scalar_dead(lines, labels, start + k + 1, int(mrf.group(1)), set(), [4000],
+                                        _known_ones(lines, start + k)):
+                    continue
                 problems.append("line %d touches in-flight v%s: %s" % (start + k + 1, sorted(hit)[:4], t.strip()))
             if is_load:
                 m2 = re.search(r"global_load_dwordx4\s+v\[(\d+):(\d+)\]", t)

@@ -425,7 +425,16 @@ int pzl_moe_ffn_staged(const pzl_layer *L, const uint16_t *x, const int32_t *top
 
     int rc = mark(PZL_STAGE_ROUTE, 0);
     if (rc) return rc;
-    rc = launch_route(topk_ids, N, k, L->n_experts, L->n_q, L->d_q_of_expert, rt, tile_min, st);
+    // Many experts with at most about one full tile each: the tile list is far shorter than its
+    // bound and its tiles are uneven, so the tiled launches are persistent and draw their tiles
+    // (counters zeroed by the grouping kernel).  Otherwise one workgroup per tile of the bound.
+    // Measured (whole step, persistent vs not): 64 experts top-6 at 512-2048 tokens -9 %, at 4096
+    // +4 %; 60 experts top-4 at 2048 -3 %, at 4096 +3 %; 8 experts top-2 at 2048-4096 +5-7 %.
+    const bool persistent = L->n_q >= 32 && (int64_t)N <= (int64_t)256 * L->n_q;
+    // one-shot launches may give both experts of a pair one tile (row groups of gate/up tell the
+    // grouping kernel how long the launch is); persistent launches do not have those kernels
+    rc = launch_route(topk_ids, N, k, L->n_experts, L->n_q, L->d_q_of_expert, rt, tile_min,
+                      persistent ? 0 : (L->d_ffn + 127) / 128, st);
     if (rc) return rc;
     if ((rc = mark(PZL_STAGE_ROUTE, 1))) return rc;
 
@@ -468,13 +477,6 @@ int pzl_moe_ffn_staged(const pzl_layer *L, const uint16_t *x, const int32_t *top
                 a.tile_q = rt.tile_q; a.tile_slot0 = rt.tile_slot0; a.tile_n = rt.tile_n; a.n_tiles = rt.n_tiles;
                 a.group_lo = group_base; a.group_hi = group_base + n_groups;
                 a.max_mtiles = max_token_tiles(N, L->n_q);
-                // Many experts with at most about one full tile each: the tile list is far shorter
-                // than its bound and its tiles are uneven, so the launch is persistent and draws
-                // its tiles (counters zeroed by the grouping kernel).  Otherwise one workgroup per
-                // tile of the bound.  Measured (whole step, persistent vs not): 64 experts top-6
-                // at 512-2048 tokens -9 %, at 4096 +4 %; 60 experts top-4 at 2048 -3 %, at 4096
-                // +3 %; 8 experts top-2 at 2048-4096 +5-7 %.
-                const bool persistent = L->n_q >= 32 && (int64_t)N <= (int64_t)256 * L->n_q;
                 a.tile_ctr = persistent ? rt.n_tiles + 8 + (pass * 2 + stage) * 8 : nullptr;
                 if (stage == 0) {
                     a.w_a = wg; a.w_b = wu;

@@ -31,6 +31,15 @@ struct RouteTables {
     int32_t *n_tiles;    // [64]: [0] number of tiles; [8..39] work counters of the tiled launches, zeroed by the grouping kernel
 };
 constexpr int TILE_MAX_TOKENS = 288;
+// A pair both of whose experts have between 1 and TILE_FUSED_MAX_TOKENS tokens gets ONE tile that
+// covers both (tile_q = 2*pair | TILE_FUSED_FLAG, tile_slot0 = first slot of the pair,
+// tile_n = n0 | n1 << 16; the two experts' slots are adjacent): the packed weights are then read
+// once for both, as in the streaming kernels, instead of once per expert.
+constexpr int TILE_FUSED_FLAG = 1 << 30;
+#ifndef PZL_FUSED_MAX
+#define PZL_FUSED_MAX 96
+#endif
+constexpr int TILE_FUSED_MAX_TOKENS = PZL_FUSED_MAX;
 inline int max_token_tiles(int64_t n_flat, int n_experts) { return (int)(n_flat / TILE_MAX_TOKENS) + n_experts; }
 
 void set_hip_error(hipError_t e);
@@ -57,9 +66,11 @@ int launch_q_unpack(const uint8_t *records, const uint16_t *scales, int pos, int
 
 // route.hip
 // tile_min: a pair one of whose experts has at least that many tokens gets token tiles (tiled
-// kernels) and counts as empty for the streaming kernels; the other pairs the other way round
+// kernels) and counts as empty for the streaming kernels; the other pairs the other way round.
+// row_groups: workgroups per token tile in the gate/up stage (decides whether pairs share tiles;
+// 0: never)
 int launch_route(const int32_t *ids, int32_t n_flat, int32_t k, int32_t n_experts, int32_t n_slots_q, const int32_t *q_of_expert,
-                 RouteTables rt, int32_t tile_min, hipStream_t st);
+                 RouteTables rt, int32_t tile_min, int32_t row_groups, hipStream_t st);
 int launch_router_topk(const uint16_t *x, const uint16_t *w_router, int32_t T, int32_t d, int32_t E, int32_t k,
                        int32_t *ids_out, float *w_out, hipStream_t st);
 int launch_combine(const float *opart, int32_t ksplit, int32_t ksplit_shared, int64_t ks_stride, const RouteTables &rt,

@@ -10,6 +10,11 @@ constexpr int ROUTE_THREADS = 1024;
 constexpr int ROUTE_WAVES = ROUTE_THREADS / 64;
 constexpr int ROUTE_QMAX = 512;
 
+__device__ __forceinline__ bool pair_is_fused(int c0, int c1)
+{
+    return c0 >= 1 && c1 >= 1 && c0 <= TILE_FUSED_MAX_TOKENS && c1 <= TILE_FUSED_MAX_TOKENS;
+}
+
 // Counting sort of the flat (token, choice) list by q = 2*pair + pos, one workgroup.
 // Wave w owns the contiguous index range [w*chunk, (w+1)*chunk) and its own histogram row, so
 // the only contended atomics are LDS atomics inside one wave.
@@ -18,7 +23,7 @@ route_kernel(const int32_t *__restrict__ ids, int32_t n_flat, int32_t k, int32_t
              const int32_t *__restrict__ q_of_expert, int32_t Q, int32_t *__restrict__ cnt,
              int32_t *__restrict__ off, int32_t *__restrict__ slot_tok, int32_t *__restrict__ slot_of,
              int32_t *__restrict__ tile_q, int32_t *__restrict__ tile_slot0, int32_t *__restrict__ tile_n,
-             int32_t *__restrict__ n_tiles, int32_t tile_min)
+             int32_t *__restrict__ n_tiles, int32_t tile_min, int32_t row_groups)
 {
     __shared__ int32_t hist[ROUTE_WAVES][ROUTE_QMAX];
     __shared__ int32_t total[ROUTE_QMAX];
@@ -62,6 +67,25 @@ route_kernel(const int32_t *__restrict__ ids, int32_t n_flat, int32_t k, int32_t
     }
     __syncthreads();
     const bool all_tiled = n_big > 0 && 2 * n_big >= n_active;
+    // One tile for both experts of a pair (see pair_is_fused) saves a second pass over the pair's
+    // weights but does the work of two tiles in one workgroup.  Measured on the three layer shapes
+    // it pays when the launch (tiles x row_groups workgroups, 256 at a time) gets shorter by well
+    // over a third, counting a launch that does not fill the chip as one that just does; it costs
+    // when it only thins out a launch that was already short.
+    __shared__ int32_t tiles_plain, pairs_fusable;
+    if (tid == 0) { tiles_plain = 0; pairs_fusable = 0; }
+    __syncthreads();
+    for (int g = tid; g < Q / 2; g += ROUTE_THREADS) {
+        const int c0 = total[2 * g], c1 = total[2 * g + 1];
+        if (all_tiled || max(c0, c1) >= tile_min) {
+            atomicAdd(&tiles_plain, (c0 + TILE_MAX_TOKENS - 1) / TILE_MAX_TOKENS + (c1 + TILE_MAX_TOKENS - 1) / TILE_MAX_TOKENS);
+            if (pair_is_fused(c0, c1)) atomicAdd(&pairs_fusable, 1);
+        }
+    }
+    __syncthreads();
+    const int64_t wgs_plain = max((int64_t)tiles_plain * row_groups, (int64_t)256);
+    const int64_t wgs_fused = max((int64_t)(tiles_plain - pairs_fusable) * row_groups, (int64_t)256);
+    const bool fuse = row_groups > 0 && pairs_fusable > 0 && 17 * wgs_fused < 10 * wgs_plain;
     // per expert: its count and its number of token tiles (equal parts of at most TILE_MAX_TOKENS,
     // rounded up to whole fragments of 16) ...
     for (int q = tid; q < ROUTE_QMAX; q += ROUTE_THREADS) {
@@ -71,6 +95,9 @@ route_kernel(const int32_t *__restrict__ ids, int32_t n_flat, int32_t k, int32_t
         int size = parts ? (((c + parts - 1) / parts + 15) & ~15) : 0;
         scan_c[q] = c;
         scan_t[q] = t && c ? (c + size - 1) / size : 0;
+        // a tiled pair whose experts both have a few tokens gets one tile for both (counted for the
+        // even expert), so that its weights are read once
+        if (t && fuse && pair_is_fused(total[q & ~1], total[q | 1])) scan_t[q] = (q & 1) ? 0 : 1;
         if (q < Q) { tiled_pair[q] = t; cnt[q] = t ? 0 : c; }
     }
     __syncthreads();
@@ -103,7 +130,12 @@ route_kernel(const int32_t *__restrict__ ids, int32_t n_flat, int32_t k, int32_t
     for (int q = tid; q < Q; q += ROUTE_THREADS) {
         const int c = total[q], first = scan_c[q];
         off[q] = first;
-        if (tiled_pair[q] && c > 0) {
+        if (tiled_pair[q] && fuse && pair_is_fused(total[q & ~1], total[q | 1])) {
+            if (!(q & 1)) {
+                const int nt = scan_t[q];
+                tile_q[nt] = q | TILE_FUSED_FLAG; tile_slot0[nt] = first; tile_n[nt] = c | (total[q | 1] << 16);
+            }
+        } else if (tiled_pair[q] && c > 0) {
             int parts = (c + TILE_MAX_TOKENS - 1) / TILE_MAX_TOKENS;
             int size = ((c + parts - 1) / parts + 15) & ~15;
             int nt = scan_t[q];
@@ -246,13 +278,13 @@ int launch_router_topk(const uint16_t *x, const uint16_t *w_router, int32_t T, i
 }
 
 int launch_route(const int32_t *ids, int32_t n_flat, int32_t k, int32_t n_experts, int32_t n_slots_q,
-                 const int32_t *q_of_expert, RouteTables rt, int32_t tile_min, hipStream_t st)
+                 const int32_t *q_of_expert, RouteTables rt, int32_t tile_min, int32_t row_groups, hipStream_t st)
 {
     int Q = n_slots_q;
     if (Q > ROUTE_QMAX) return PZL_EINVAL;
     hipLaunchKernelGGL(route_kernel, dim3(1), dim3(ROUTE_THREADS), 0, st, ids, n_flat, k, n_experts,
                        q_of_expert, Q, rt.cnt, rt.off, rt.slot_tok, rt.slot_of, rt.tile_q, rt.tile_slot0,
-                       rt.tile_n, rt.n_tiles, tile_min);
+                       rt.tile_n, rt.n_tiles, tile_min, row_groups);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) { set_hip_error(e); return PZL_EHIP; }
     return PZL_OK;

@@ -135,14 +135,20 @@ typedef __attribute__((address_space(3))) void *tg_lds_ptr;
 // that the K loop has no data-dependent branch; an odd tile costs one padded fragment.
 // DENSE: plain bf16 weights (identity decode).  ALLTOK: a shared expert, uniform token tiles
 // over every token instead of the routed tile list.
+// POS = 2: a tile for BOTH experts of a pair (n_tok tokens of position 0 in the first half of the
+// fragments, n_tok1 tokens of position 1, whose slots follow, in the second half; CNT pairs of
+// fragments each): every packed word is loaded once and decoded for both positions.
 template <int STAGE, bool DENSE, bool ALLTOK, int POS, int CNT>
 __device__ __forceinline__ void tile_body(const TgArgs &a, const uint16_t *wa, const uint16_t *wb,
-                                          int slot0, int n_tok, int ntile, int ks,
+                                          int slot0, int n_tok, int n_tok1, int ntile, int ks,
                                           u32x4 *ring, int32_t *rowidx, int32_t *draw_ctr, int32_t *drawn)
 {
+    constexpr bool FUSED = POS == 2;
     constexpr int KBS = (STAGE == TSTAGE_DOWN) ? 1 : 2;      // k-blocks (of 32) per K step
     constexpr int PARTS = (STAGE == TSTAGE_DOWN) ? 2 : 1;    // activation planes (hi, lo)
-    constexpr int NF = 2 * CNT;                              // token fragments in use
+    constexpr int NF = (FUSED ? 4 : 2) * CNT;                // token fragments in use
+    constexpr int NFH = FUSED ? NF / 2 : NF;                 // ... of which the first expert's
+    static_assert(NF <= TG_FRAGS, "fragments");
     constexpr int RT = 2;                                    // row tiles per wave
     constexpr int XTOTAL = PARTS * NF * KBS;                 // activation fragments per stage
     constexpr int XPT = (XTOTAL + TG_WAVES - 1) / TG_WAVES;  // ... of which each wave fetches this many
@@ -161,6 +167,7 @@ __device__ __forceinline__ void tile_body(const TgArgs &a, const uint16_t *wa, c
     // activation row behind each token column of the tile (clamped to the last valid token)
     if (tid < TG_MAX_TOK) {
         int slot = slot0 + min(tid, n_tok - 1);
+        if (FUSED && tid >= NFH * 16) slot = slot0 + n_tok + min(tid - NFH * 16, n_tok1 - 1);
         int row;
         if (a.act_is_x) row = ALLTOK ? (slot - a.dense_slot_base) % a.dense_tokens : a.slot_tok[slot];
         else            row = slot - a.act_slot_base;
@@ -242,7 +249,7 @@ __device__ __forceinline__ void tile_body(const TgArgs &a, const uint16_t *wa, c
 #pragma unroll
         for (int i = 0; i < NF; ++i) acc[j][i] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
-    auto multiply = [&](const u32x4 *xs, const bf16x8 (&af)[RT], int kbo) {
+    auto multiply = [&](const u32x4 *xs, const bf16x8 (&af)[RT], const bf16x8 (&af1)[RT], int kbo) {
 #pragma unroll
         for (int i = 0; i < NF; ++i) {
 #pragma unroll
@@ -250,7 +257,8 @@ __device__ __forceinline__ void tile_body(const TgArgs &a, const uint16_t *wa, c
                 bf16x8 b = __builtin_bit_cast(bf16x8, xs[((part * TG_FRAGS + i) * KBS + kbo) * 64 + lane]);
 #pragma unroll
                 for (int j = 0; j < RT; ++j)
-                    acc[j][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[j], b, acc[j][i], 0, 0, 0);
+                    acc[j][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16((FUSED && i >= NFH) ? af1[j] : af[j], b,
+                                                                         acc[j][i], 0, 0, 0);
             }
         }
     };
@@ -262,17 +270,20 @@ __device__ __forceinline__ void tile_body(const TgArgs &a, const uint16_t *wa, c
 #pragma unroll
         for (int kbo = 0; kbo < KBS; ++kbo) {
             wait_w(raw, kbo, false);
-            bf16x8 af[RT];
+            bf16x8 af[RT], af1[RT];
 #pragma unroll
-            for (int j = 0; j < RT; ++j) af[j] = tg_decode<POS, DENSE>(raw[kbo][j]);
+            for (int j = 0; j < RT; ++j) {
+                af[j] = tg_decode<FUSED ? 0 : POS, DENSE>(raw[kbo][j]);
+                af1[j] = FUSED ? tg_decode<1, DENSE>(raw[kbo][j]) : af[j];
+            }
             if (kbo > 0) {                 // a k-block past the end (odd count): multiply by zero
                 const bool valid = kb0 + step * KBS + kbo < kb1;
                 const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
-                for (int j = 0; j < RT; ++j) af[j] = valid ? af[j] : zero;
+                for (int j = 0; j < RT; ++j) { af[j] = valid ? af[j] : zero; af1[j] = valid ? af1[j] : zero; }
             }
             fetch_w(step + 2, raw, kbo);
-            multiply(cur, af, kbo);
+            multiply(cur, af, af1, kbo);
             // order of issue: a few fragment reads ahead, then one more read per pair of matrix
             // instructions, so that the LDS latency is covered by the products of earlier fragments
             __builtin_amdgcn_sched_group_barrier(0x100, TG_READ_AHEAD, 0);
@@ -331,9 +342,15 @@ __device__ __forceinline__ void tile_body(const TgArgs &a, const uint16_t *wa, c
     const int col = lane & 15, rsub = (lane >> 4) * 4;
 #pragma unroll
     for (int i = 0; i < NF; ++i) {
-        int within = i * 16 + col;
-        if (within >= n_tok) continue;
-        int slot = slot0 + within;
+        int within = i * 16 + col, slot;
+        if (FUSED && i >= NFH) {
+            within -= NFH * 16;
+            if (within >= n_tok1) continue;
+            slot = slot0 + n_tok + within;
+        } else {
+            if (within >= n_tok) continue;
+            slot = slot0 + within;
+        }
         if (STAGE == TSTAGE_GATEUP) {
             int grt = ntile * TG_WAVES + wave;
             if (grt >= row_tiles) continue;
@@ -359,7 +376,7 @@ __device__ __forceinline__ void tile_body(const TgArgs &a, const uint16_t *wa, c
 
 // One token tile x one block of weight rows, given its logical id (see tile_kernel for the order).
 // Returns whether the tile ran (and, if asked to, drew the workgroup's next id into *drawn).
-template <int STAGE, bool DENSE, bool ALLTOK>
+template <int STAGE, bool DENSE, bool ALLTOK, bool PERSIST>
 __device__ __forceinline__ bool tile_run(const TgArgs &a, int logical, int n_mt, int gm_count, int per_ks,
                                          u32x4 *ring, int32_t *rowidx, int32_t *draw_ctr, int32_t *drawn)
 {
@@ -370,7 +387,8 @@ __device__ __forceinline__ bool tile_run(const TgArgs &a, int logical, int n_mt,
     const int ntile = (blk / gm_count) * TG_BLOCK_N + r / TG_BLOCK_M;
     if (mt >= n_mt || ntile >= a.n_ntiles) return false;
 
-    int g, pos, slot0, n_tok;
+    int g, pos, slot0, n_tok, n_tok1 = 0;
+    bool fused = false;
     if (ALLTOK) {
         g = mt / ((a.dense_tokens + a.dense_tile_tokens - 1) / a.dense_tile_tokens);
         int t_in = mt % ((a.dense_tokens + a.dense_tile_tokens - 1) / a.dense_tile_tokens);
@@ -379,11 +397,14 @@ __device__ __forceinline__ bool tile_run(const TgArgs &a, int logical, int n_mt,
         n_tok = min(a.dense_tile_tokens, a.dense_tokens - t_in * a.dense_tile_tokens);
     } else {
         int q = a.tile_q[mt];
+        fused = (q & TILE_FUSED_FLAG) != 0;
+        q &= ~TILE_FUSED_FLAG;
         g = q >> 1; pos = q & 1;
         if (g < a.group_lo || g >= a.group_hi) return false;  // another launch's kind of expert
         g -= a.group_lo;
         slot0 = a.tile_slot0[mt];
         n_tok = a.tile_n[mt];
+        if (fused) { n_tok1 = n_tok >> 16; n_tok &= 0xFFFF; }
     }
     // these are the same for the whole workgroup; say so, or the per-fragment guards below become
     // exec-masked branches and the accumulators get shuffled between register files
@@ -391,10 +412,24 @@ __device__ __forceinline__ bool tile_run(const TgArgs &a, int logical, int n_mt,
     pos = __builtin_amdgcn_readfirstlane(pos);
     slot0 = __builtin_amdgcn_readfirstlane(slot0);
     n_tok = __builtin_amdgcn_readfirstlane(n_tok);
+    n_tok1 = __builtin_amdgcn_readfirstlane(n_tok1);
     const uint16_t *wa = a.w_a[g];
     const uint16_t *wb = (STAGE == TSTAGE_GATEUP) ? a.w_b[g] : wa;
     const int cnt = (((n_tok + 15) >> 4) + 1) >> 1;          // 1..9 pairs of token fragments
-#define PZL_TILE(P, C) tile_body<STAGE, DENSE, ALLTOK, P, C>(a, wa, wb, slot0, n_tok, ntile, ks, ring, rowidx, draw_ctr, drawn)
+#define PZL_TILE(P, C) tile_body<STAGE, DENSE, ALLTOK, P, C>(a, wa, wb, slot0, n_tok, n_tok1, ntile, ks, ring, rowidx, draw_ctr, drawn)
+    // tiles that cover a pair exist only in one-shot launches (the grouping kernel is told so): the
+    // persistent kernels, already the largest, measured 5 % slower on every tile with these
+    // instantiations compiled in
+    if constexpr (!DENSE && !ALLTOK && !PERSIST) {
+        if (__builtin_amdgcn_readfirstlane((int)fused)) {
+            const int c2 = (max(n_tok, n_tok1) + 31) >> 5;       // 1..4 pairs of fragments per expert
+            switch (c2) {
+                case 1: PZL_TILE(2, 1); break; case 2: PZL_TILE(2, 2); break;
+                case 3: PZL_TILE(2, 3); break; default: PZL_TILE(2, 4); break;
+            }
+            return true;
+        }
+    }
 #define PZL_TILE_CNT(P)                                                         \
     switch (cnt) {                                                              \
         case 1: PZL_TILE(P, 1); break; case 2: PZL_TILE(P, 2); break;           \
@@ -467,7 +502,7 @@ tile_kernel(TgArgs a)
         if (i >= per_xcd || xcd * per_xcd + i >= total) return;
         // the tile after this one is drawn by this one unless it is a fixed one
         const bool draw = persistent && round + 1 >= fixed_rounds;
-        have_draw = tile_run<STAGE, DENSE, ALLTOK>(a, xcd * per_xcd + i, n_mt, gm_count, per_ks, ring, rowidx,
+        have_draw = tile_run<STAGE, DENSE, ALLTOK, PERSIST>(a, xcd * per_xcd + i, n_mt, gm_count, per_ks, ring, rowidx,
                                                    draw ? ctr : nullptr, &drawn) && draw;
         if (persistent && !have_draw) __syncthreads();     // everyone has read `drawn` before it is written again
     }

@@ -241,6 +241,42 @@ def test_hybrid_path_mixed_pair_sizes(tiled_case, T):
     check(tiled_case, T, "hybrid", ids=ids, w=w, x=x)
 
 
+# wide and shallow: 88 row groups in the gate/up stage, so that a handful of token tiles fills the chip
+WIDE = synth.LayerConfig("wide", 8, 128, 11264, 2, (256,), seed=43)
+
+
+@pytest.fixture(scope="module")
+def wide_case(oracle, binding):
+    return Case(WIDE, oracle, binding, emap_mode="random")
+
+
+@pytest.mark.parametrize("counts", [(40, 50, 64, 1, 33, 33, 20, 7), (96, 96, 97, 5, 48, 2, 1, 60),
+                                    (33, 1, 30, 31, 0, 50, 10, 10), (100, 64, 0, 90, 64, 16, 17, 15)])
+def test_tiled_path_pair_tiles(wide_case, counts):
+    """A tiled pair both of whose experts have 1..96 tokens gets ONE token tile for both (the
+    packed words are loaded once and decoded for both positions) if that shortens the launch
+    enough; 97 tokens, or an empty partner, give ordinary tiles, and in the last case too few pairs
+    qualify, so none shares a tile.  Expert loads are set by hand: counts = (pair 0 pos 0, pair 0
+    pos 1, pair 1 pos 0, ...)."""
+    cfg, case = WIDE, wide_case
+    pair_of, pos_of = np.asarray(case.emap[0]), np.asarray(case.emap[1])
+    experts = [int(np.where((pair_of == p) & (pos_of == q))[0][0]) for p in range(4) for q in (0, 1)]
+    flat = np.concatenate([np.full(c, e, dtype=np.int32) for e, c in zip(experts, counts)])
+    if flat.size % 2:
+        flat = np.concatenate([flat, np.array([-1], dtype=np.int32)])       # an ignored id pads the last token
+    np.random.RandomState(sum(counts)).shuffle(flat)
+    T = flat.size // 2
+    ids = flat.reshape(T, 2)
+    x = synth.tokens(cfg, T)
+    _, w = synth.routing(cfg, T)
+    assert flat.size >= 20 * cfg.n_experts and max(counts) >= 33          # both paths launched, pairs tiled
+    y = case.gpu(x, ids, w)
+    y64, _ = case.ref(x, np.where(ids < 0, 0, ids).astype(np.int32), np.where(ids < 0, 0.0, w).astype(np.float32))
+    ok, worst = tolerance_ok(y, y64)
+    say("  pair tiles %s: worst err / bound = %.3f" % (counts, worst))
+    assert ok, worst
+
+
 def test_tiled_path_skewed_routing(tiled_case):
     """One hot expert (several full token tiles), one expert with a single token, one with none."""
     cfg = TILED

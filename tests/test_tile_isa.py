@@ -16,8 +16,8 @@ def test_tile_kernel_in_flight_registers(tmp_path):
     check_tile_isa.compile_to_asm(str(asm))
     n_loops, n_exits, problems = check_tile_isa.check(asm.read_text())
     assert not problems, problems[:5]
-    # 6 kernels x 2 positions (packed) or 1 (dense) x 8 tile sizes
-    assert n_loops == 126 and n_exits == 126, (n_loops, n_exits)
+    # 10 kernels (one-shot and persistent) x positions x tile sizes, plus the tiles that cover a pair
+    assert n_loops == 134 and n_exits == 134, (n_loops, n_exits)
 
 
 def test_checker_flags_a_planted_copy():
@@ -31,3 +31,24 @@ def test_checker_flags_a_planted_copy():
     assert n_loops == 1 and len(problems) == 1 and "v_mov_b32" in problems[0]
     clean = text.replace("v_mov_b32_e32 v30, v21", "v_mov_b32_e32 v30, v31")
     assert check_tile_isa.check(clean)[2] == []
+
+
+def test_checker_accepts_only_dead_lane_reads():
+    """A lane-0 read of an in-flight register into a scalar register is how the compiler
+    materialises an undefined value; it is accepted only if that scalar is overwritten before it is
+    read on every path (here: the loop continues and redefines it, or the exit path ends)."""
+    body = ["\tv_mfma_f32_16x16x32_bf16 v[0:3], v[4:7], v[8:11], v[0:3]"] * 8
+    def prog(after_exit):
+        return "\n".join([".LBB0_1:", "\ts_add_i32 s9, s8, 2"] + body + [
+            "\t;;#ASMSTART", "\tglobal_load_dwordx4 v[20:23], v1, s[2:3]", "\t;;#ASMEND",
+            "\ts_barrier", "\ts_barrier",
+            "\ts_mov_b64 s[4:5], -1", "\ts_cmp_ge_i32 s9, s10",
+            "\tv_readfirstlane_b32 s9, v20",
+            "\ts_cbranch_scc0 .LBB0_1",                    # continue: s9 is redefined at the top
+            "\ts_andn2_b64 vcc, exec, s[4:5]", "\ts_mov_b32 s8, s9",
+            "\ts_cbranch_vccnz .LBB0_1",                   # not taken: vcc is zero on this path
+            ".LBB0_2:"] + after_exit + ["\ts_endpgm"])
+    assert check_tile_isa.check(prog([]))[2] == []
+    bad = check_tile_isa.check(prog(["\ts_add_i32 s11, s9, 1"]))[2]          # the value is used
+    assert bad and all("v_readfirstlane" in b for b in bad)
+
