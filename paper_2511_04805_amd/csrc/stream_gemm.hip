@@ -103,22 +103,19 @@ __device__ __forceinline__ bf16x8 decode_frag(u32x4 w)
     return __builtin_bit_cast(bf16x8, o);
 }
 
-__device__ __forceinline__ uint32_t f32_to_bf16_rne_sg(float v)
-{
-    uint32_t u = __float_as_uint(v);
-    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return 0x7FC0u;
-    u += 0x7FFFu + ((u >> 16) & 1u);
-    return u >> 16;
-}
+typedef __bf16 sg_bf16x2 __attribute__((ext_vector_type(2)));
+typedef float sg_f32x2 __attribute__((ext_vector_type(2)));
 
-__device__ __forceinline__ float silu_f32(float g) { return g / (1.0f + __expf(-g)); }
-
-// h = silu(g) * u  ->  hi = bf16(h), lo = bf16(h - hi)
-__device__ __forceinline__ void swiglu_split(float g, float u, uint32_t &hi, uint32_t &lo)
+// h = silu(g) * u for two elements -> a bf16 pair of leading parts and a bf16 pair of remainders
+// (hi = bf16(h), lo = bf16(h - hi); low half = first element).  Reciprocal and exponential are the
+// hardware's approximations (1 ulp), the conversions its round-to-nearest-even.
+__device__ __forceinline__ void swiglu_split2(float g0, float u0, float g1, float u1, uint32_t &hi, uint32_t &lo)
 {
-    float h = silu_f32(g) * u;
-    hi = f32_to_bf16_rne_sg(h);
-    lo = f32_to_bf16_rne_sg(h - __uint_as_float(hi << 16));
+    float h0 = g0 * __builtin_amdgcn_rcpf(1.0f + __expf(-g0)) * u0;
+    float h1 = g1 * __builtin_amdgcn_rcpf(1.0f + __expf(-g1)) * u1;
+    hi = __builtin_bit_cast(uint32_t, __builtin_convertvector((sg_f32x2){h0, h1}, sg_bf16x2));
+    float r0 = h0 - __uint_as_float(hi << 16), r1 = h1 - __uint_as_float(hi & 0xFFFF0000u);
+    lo = __builtin_bit_cast(uint32_t, __builtin_convertvector((sg_f32x2){r0, r1}, sg_bf16x2));
 }
 
 
@@ -432,11 +429,10 @@ __device__ __forceinline__ void stream_pass(const SgArgs &a, const uint16_t *wa,
         if (STAGE == STAGE_GATEUP) {
             if (!active0) continue;
             f32x4 g = acc[0][n], u = acc[1][n];
-            uint32_t hi[4], lo[4];
-#pragma unroll
-            for (int r = 0; r < 4; ++r) swiglu_split(g[r], u[r], hi[r], lo[r]);
-            u32x2 ohi = {hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16)};
-            u32x2 olo = {lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16)};
+            uint32_t hi01, lo01, hi23, lo23;
+            swiglu_split2(g[0], u[0], g[1], u[1], hi01, lo01);
+            swiglu_split2(g[2], u[2], g[3], u[3], hi23, lo23);
+            u32x2 ohi = {hi01, hi23}, olo = {lo01, lo23};
             uint16_t *dst = a.h_out + (int64_t)(slot - a.h_slot_base) * a.rows + rt0 * 16 + (lane >> 4) * 4;
             *(u32x2 *)dst = ohi;
             *(u32x2 *)(dst + a.h_plane_stride) = olo;
