@@ -76,6 +76,26 @@ def test_mixtral_prefill(mixtral):
     assert counts.min() > 850 and counts.max() < 1200          # near-uniform expert load
 
 
+def test_mixtral_prefill_properties(mixtral):
+    """Properties that hold at any size, checked bit for bit on the full prefill batch: the result
+    of a token does not depend on where the token stands in the batch (nor, therefore, on which
+    token tile it lands in), and doubling the routing weights doubles every output."""
+    cfg = mixtral.cfg
+    T = 4096
+    x = synth.tokens(cfg, T)
+    ids, w = synth.routing(cfg, T)
+    y = mixtral.gpu(x, ids, w)
+    perm = np.random.RandomState(11).permutation(T)
+    yp = mixtral.gpu(x[perm], ids[perm], w[perm])
+    assert np.array_equal(yp, y[perm])
+    y2 = mixtral.gpu(x, ids, (2.0 * w).astype(np.float32))
+
+    def bf16_to_f32(bits):
+        return (bits.astype(np.uint32) << 16).view(np.float32)
+    a, b = bf16_to_f32(y), bf16_to_f32(y2)
+    assert np.array_equal(b, 2.0 * a)
+
+
 def test_mixtral_large_batch(mixtral):
     # four times the prefill batch: ~57 token tiles per expert, several rounds of workgroups
     check_rows(mixtral, 16384, 8, seed=3)
