@@ -107,6 +107,22 @@ def batch(cfg, T):
             torch.from_numpy(w).cuda())
 
 
+def time_plain(hip, layer, xt, idt, wt, steps, warmup):
+    """K calls of pzl_moe_ffn as a caller makes them (shared experts on the layer's second stream)."""
+    y = torch.empty(xt.shape[0], layer.d_model, dtype=torch.bfloat16, device="cuda")
+    stream = torch.cuda.current_stream().cuda_stream
+    for _ in range(warmup):
+        layer.pzl_moe_ffn(xt, idt, wt, y=y)
+    t0, t1 = hip.event(), hip.event()
+    torch.cuda.synchronize()
+    hip.record(t0, stream)
+    for _ in range(steps):
+        layer.pzl_moe_ffn(xt, idt, wt, y=y)
+    hip.record(t1, stream)
+    torch.cuda.synchronize()
+    return hip.elapsed_ms(t0, t1) / steps
+
+
 def touched_pairs(ids, emap):
     return len(set(int(emap[0][e]) for e in np.unique(ids)))
 
@@ -150,6 +166,7 @@ def main():
     ap.add_argument("--no-sweep", action="store_true")
     ap.add_argument("--no-prefill", action="store_true")
     ap.add_argument("--no-quant", action="store_true")
+    ap.add_argument("--no-other-shapes", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (--gpus must be 1)", file=sys.stderr)
@@ -253,6 +270,30 @@ def main():
                          "algorithmic_bytes": q_alg, "avg_launch_ms": ms_qgu},
             "weight_bytes_vs_16bit": q_pair_bytes_gateup / pair_bytes_gateup}
         del qlayer
+
+    if not args.no_other_shapes:
+        # The other two layer shapes at their batch sizes, whole step.  Both roofline fractions are
+        # given: bytes = the packed weights of the touched pairs and the shared experts' weights,
+        # read once; flops = 3 projections x 2*d*f per (token, choice) and per (token, shared expert).
+        del layer
+        torch.cuda.empty_cache()
+        out["other_shapes"] = {}
+        for name in ("qwen15_moe", "deepseek_moe"):
+            c2 = synth.CONFIGS[name]
+            T2 = c2.n_tokens[0]
+            l2, emap2 = build_layer(c2)
+            x2, ids2, w2, xt2, idt2, wt2 = batch(c2, T2)
+            ms2 = time_plain(hip, l2, xt2, idt2, wt2, 50, 10)
+            nt2 = touched_pairs(ids2, emap2)
+            w_bytes = nt2 * 3 * c2.d_ffn * c2.d_model * 2 + sum(3 * fs * c2.d_model * 2 for fs in c2.shared_d_ffn)
+            flops = 2.0 * 3 * c2.d_model * (T2 * c2.top_k * c2.d_ffn + T2 * sum(c2.shared_d_ffn))
+            out["other_shapes"][name] = {
+                "tokens": T2, "experts": c2.n_experts, "top_k": c2.top_k, "touched_pairs": nt2,
+                "ms_per_step": ms2, "tokens_per_s": T2 / (ms2 * 1e-3),
+                "hbm_frac": w_bytes / (ms2 * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                "useful_mfma_frac": flops / (ms2 * 1e-3) / 2.5e15}
+            del l2
+            torch.cuda.empty_cache()
 
     if want_cpu:
         import oracle
