@@ -151,11 +151,12 @@ typedef struct pzl_layer_desc {
 typedef struct pzl_layer pzl_layer;
 
 /* Validates the description and builds the layer's device tables (the only allocation the
- * library performs).  The device current at the call is the layer's device.  A layer with
- * shared experts also owns a second stream (default priority) and two events: pzl_moe_ffn runs
- * the shared experts there, next to the routed experts, forked from and joined back into the
- * caller's stream inside the call.  Calls on one layer must therefore not overlap in time on
- * different streams (calls queued on one stream are fine). */
+ * library performs).  The device current at the call is the layer's device.  The layer also
+ * owns up to two further streams (default priority) with two events each: pzl_moe_ffn runs the
+ * shared experts on one and, for batches that use both kinds of kernel, the tiled kernels of
+ * the routed experts on the other, next to the rest of the call, forked from and joined back
+ * into the caller's stream inside the call.  Calls on one layer must therefore not overlap in
+ * time on different streams (calls queued on one stream are fine). */
 int pzl_layer_create(const pzl_layer_desc *desc, pzl_layer **out);
 void pzl_layer_destroy(pzl_layer *layer);
 
@@ -183,9 +184,8 @@ size_t pzl_moe_ffn_workspace_bytes(const pzl_layer *layer, int32_t max_tokens, i
  * Size limits of one call (the kernels address activations with 32-bit byte offsets; larger
  * batches are to be split by the caller): T * d_model < 2^31, T * k * d_ffn < 2^30, and for the
  * shared experts n_shared * T * f_shared < 2^30; PZL_EINVAL beyond them.
- * T == 0 is a no-op.  Calls on one layer that overlap in time (different streams) are not
- * supported when the layer has shared experts (see pzl_layer_create); otherwise they must use
- * different workspaces.
+ * T == 0 is a no-op.  Calls on one layer must not overlap in time on different streams (see
+ * pzl_layer_create); calls queued on one stream are fine.
  */
 int pzl_moe_ffn(const pzl_layer *layer, const uint16_t *x, const int32_t *topk_ids,
                 const float *topk_w, int32_t T, int32_t k, uint16_t *y,
