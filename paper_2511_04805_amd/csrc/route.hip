@@ -37,12 +37,22 @@ route_kernel(const int32_t *__restrict__ ids, int32_t n_flat, int32_t k, int32_t
     const int lo = wave * chunk;
     const int hi = min(n_flat, lo + chunk);
 
-    for (int i = lo; i < hi; i += 64) {
-        int idx = i + lane;
-        if (idx < hi) {
-            int e = ids[idx];
-            if (e >= 0 && e < n_experts) atomicAdd(&hist[wave][q_of_expert[e]], 1);
+    // four ids per lane and trip (one 16-byte load when the range allows): the loop is bound by
+    // the latency of its loads, not by their number
+    const bool vec_ok = ((uintptr_t)ids & 15) == 0;      // lo is a multiple of 64 ids
+    for (int i = lo; i < hi; i += 256) {
+        const int idx = i + lane * 4;
+        int e4[4] = {-1, -1, -1, -1};
+        if (vec_ok && idx + 3 < hi) {
+            const int4 v = *(const int4 *)(ids + idx);
+            e4[0] = v.x; e4[1] = v.y; e4[2] = v.z; e4[3] = v.w;
+        } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) if (idx + j < hi) e4[j] = ids[idx + j];
         }
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            if (e4[j] >= 0 && e4[j] < n_experts) atomicAdd(&hist[wave][q_of_expert[e4[j]]], 1);
     }
     __syncthreads();
     // per-q totals, then turn hist[w][q] into the first slot of (q, wave w)
@@ -157,16 +167,25 @@ route_kernel(const int32_t *__restrict__ ids, int32_t n_flat, int32_t k, int32_t
     // up to the hardware, so the order of slots inside one expert is not fixed; nothing
     // downstream depends on it (every slot is computed on its own and the combine adds a
     // token's choices in choice order).
-    for (int i = lo; i < hi; i += 64) {
-        int idx = i + lane;
-        if (idx < hi) {
-            int e = ids[idx];
-            if (e >= 0 && e < n_experts) {
-                int slot = atomicAdd(&hist[wave][q_of_expert[e]], 1);
-                slot_tok[slot] = idx / k;
-                slot_of[idx] = slot;
+    for (int i = lo; i < hi; i += 256) {
+        const int idx = i + lane * 4;
+        int e4[4] = {-1, -1, -1, -1};
+        if (vec_ok && idx + 3 < hi) {
+            const int4 v = *(const int4 *)(ids + idx);
+            e4[0] = v.x; e4[1] = v.y; e4[2] = v.z; e4[3] = v.w;
+        } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) if (idx + j < hi) e4[j] = ids[idx + j];
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            if (idx + j >= hi) continue;
+            if (e4[j] >= 0 && e4[j] < n_experts) {
+                int slot = atomicAdd(&hist[wave][q_of_expert[e4[j]]], 1);
+                slot_tok[slot] = (idx + j) / k;
+                slot_of[idx + j] = slot;
             } else {
-                slot_of[idx] = -1;
+                slot_of[idx + j] = -1;
             }
         }
     }
