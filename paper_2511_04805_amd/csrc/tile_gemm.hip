@@ -32,6 +32,12 @@
 // limit is what registers and LDS allow, not a power of two: a tile with few tokens streams the
 // same weights as a full one and costs about half as much (measured), so an expert with 1030
 // tokens is far better served by 4 tiles of 272 than by 4 of 256 and one of 6, or by 5 of 208.
+// For the same reason a pair whose two experts both have few tokens can get one tile for both
+// (tile_body with POS = 2): its packed words are loaded once and decoded for both positions.
+//
+// Launch forms (tile_kernel): one workgroup per tile, or, where the host's bound on the number of
+// tiles is loose and tiles are uneven (many experts), 256 persistent workgroups that work through
+// the tile list, by fixed stride first and then drawing from a counter.
 #include "pzl_common.h"
 
 namespace pzl {
@@ -45,7 +51,7 @@ constexpr int TG_MAX_TOK = TILE_MAX_TOKENS;   // tokens per tile (18 fragments o
 constexpr int TG_FRAGS = TG_MAX_TOK / 16;
 constexpr int TG_ROW_TILES = 2 * TG_WAVES;    // 16-row weight tiles per workgroup
 constexpr int TG_XSTAGES = 4;
-constexpr int TG_XSTAGE_UNITS = TG_FRAGS * 2 * 64;   // 16-byte units per stage (16 fragments x 2 k-blocks or planes)
+constexpr int TG_XSTAGE_UNITS = TG_FRAGS * 2 * 64;   // 16-byte units per stage (18 fragments x 2 k-blocks or planes)
 constexpr int TSTAGE_GATEUP = 0, TSTAGE_DOWN = 1;
 constexpr int TG_PERSISTENT_WGS = 256;   // workgroups of a persistent launch: one per compute unit (8 XCDs x 32)
 #ifndef TG_READ_AHEAD
