@@ -47,7 +47,7 @@ namespace pzl {
 #define PZL_TILED_MIN_TPE 96
 #endif
 #ifndef PZL_TILED_MIN_SHARED
-#define PZL_TILED_MIN_SHARED 1024
+#define PZL_TILED_MIN_SHARED 384
 #endif
 constexpr int TILED_MIN_TOKENS_PER_EXPERT = PZL_TILED_MIN_TPE;   // average tokens per expert from which the K split is sized for the tiled kernels
 #ifndef PZL_HYBRID_MIN_TPE
@@ -62,7 +62,10 @@ constexpr int TILED_MIN_TOKENS_PER_EXPERT = PZL_TILED_MIN_TPE;   // average toke
 constexpr int HYBRID_MIN_TOKENS_PER_EXPERT = PZL_HYBRID_MIN_TPE;  // average from which both paths are launched
 constexpr int HYBRID_MIN_TOKENS_PER_EXPERT_MANY = PZL_HYBRID_MIN_TPE_MANY;   // ... in a layer with 32 experts or more
 constexpr int HYBRID_TILE_MIN_TOKENS = PZL_HYBRID_TILE_MIN;       // ... and a pair with an expert of this many tokens is tiled
-constexpr int TILED_MIN_TOKENS_SHARED = PZL_TILED_MIN_SHARED;     // a dense expert sees every token but has few row tiles: the tiled path needs >= 4 token tiles
+// a dense expert sees every token: beyond a few 64-token sweeps of its weights the tiled kernels win,
+// also because their few workgroups leave most compute units to the routed experts' kernels that run
+// next to them (measured: 60 experts + 1 shared, 384-768 tokens -8..-11 %; at 256 tokens +8 %)
+constexpr int TILED_MIN_TOKENS_SHARED = PZL_TILED_MIN_SHARED;
 constexpr int MAX_KSPLIT = 8;   // upper bound on the k-splits of the down stage (sizes the workspace)
 
 struct WorkspaceLayout {

@@ -215,7 +215,7 @@ def tiled_case(oracle, binding):
 @pytest.mark.parametrize("T", [192, 200, 333, 600, 1100])
 def test_tiled_path_token_counts(tiled_case, T):
     """>= 96 slots per expert: tiled kernels; ragged token tiles, several tiles per expert, and from
-    1024 tokens the dense shared expert on the tiled kernels too."""
+    384 tokens the dense shared expert on the tiled kernels too."""
     check(tiled_case, T, "tiled")
 
 
