@@ -320,6 +320,21 @@ def test_mixed_layer_unmerged_experts(mixed_case, T):
     check(mixed_case, T, "mixed")
 
 
+def test_many_experts_mixed_layer_persistent_launches(oracle, binding):
+    """40 routed experts, 8 of them kept unmerged: with 32 or more expert slots and about one tile
+    per expert the tiled launches are persistent (workgroups draw their tiles), for the packed pairs
+    and for the dense experts alike.  Zipf routing gives a few busy experts (tiled) and many idle
+    ones (streamed or empty); the tiled kernels run on the layer's tile stream."""
+    cfg = synth.LayerConfig("many_mixed", 40, 128, 384, 3, (300,), shared_d_ffn=(128,), routing="zipf",
+                            seed=71, n_unmerged=8)
+    case = Case(cfg, oracle, binding, emap_mode="random")
+    for T in (120, 300, 700):
+        ids, _ = synth.routing(cfg, T)
+        counts = np.bincount(ids.ravel(), minlength=cfg.n_experts)
+        assert T * cfg.top_k >= 8 * cfg.n_experts and counts.max() >= 33
+        check(case, T, "many-mixed")
+
+
 def test_all_experts_unmerged(oracle, binding):
     """No pair at all: every routed expert dense (the degenerate end of the compression range)."""
     cfg = synth.LayerConfig("unmerged", 3, 128, 192, 2, (40,), seed=67, n_unmerged=3)
