@@ -47,7 +47,13 @@ namespace pzl {
 #define PZL_TILED_MIN_TPE 96
 #endif
 #ifndef PZL_TILED_MIN_SHARED
-#define PZL_TILED_MIN_SHARED 384
+#define PZL_TILED_MIN_SHARED 96
+#endif
+#ifndef PZL_SHARED_TILE_WGS
+#define PZL_SHARED_TILE_WGS 168
+#endif
+#ifndef PZL_SHARED_TILE_MIN_TOKENS
+#define PZL_SHARED_TILE_MIN_TOKENS 48
 #endif
 constexpr int TILED_MIN_TOKENS_PER_EXPERT = PZL_TILED_MIN_TPE;   // average tokens per expert from which the K split is sized for the tiled kernels
 #ifndef PZL_HYBRID_MIN_TPE
@@ -62,9 +68,9 @@ constexpr int TILED_MIN_TOKENS_PER_EXPERT = PZL_TILED_MIN_TPE;   // average toke
 constexpr int HYBRID_MIN_TOKENS_PER_EXPERT = PZL_HYBRID_MIN_TPE;  // average from which both paths are launched
 constexpr int HYBRID_MIN_TOKENS_PER_EXPERT_MANY = PZL_HYBRID_MIN_TPE_MANY;   // ... in a layer with 32 experts or more
 constexpr int HYBRID_TILE_MIN_TOKENS = PZL_HYBRID_TILE_MIN;       // ... and a pair with an expert of this many tokens is tiled
-// a dense expert sees every token: beyond a few 64-token sweeps of its weights the tiled kernels win,
-// also because their few workgroups leave most compute units to the routed experts' kernels that run
-// next to them (measured: 60 experts + 1 shared, 384-768 tokens -8..-11 %; at 256 tokens +8 %)
+// a dense expert sees every token: beyond one 64-token sweep of its weights the tiled kernels win,
+// given token tiles of the right size (shared_token_parts).  Measured, 60 experts + 1 shared
+// expert of 5632: 64 tokens 120 us streamed / 135 tiled, 96 tokens 156 / 139, 256 tokens 192 / 166
 constexpr int TILED_MIN_TOKENS_SHARED = PZL_TILED_MIN_SHARED;
 constexpr int MAX_KSPLIT = 8;   // upper bound on the k-splits of the down stage (sizes the workspace)
 
@@ -130,6 +136,41 @@ static int choose_tile_ksplit(int64_t token_tiles, int64_t slots, int rows, int 
         if (ks == 1 || us < best_us) { best_us = us; best = ks; }
     }
     return best;
+}
+
+// Token tiles per shared expert in the tiled kernels (`n_same` experts of width f share a launch).
+// The largest tiles (288 tokens) do the least work per token, but a shared expert has few row
+// tiles, and a few large tiles are then the longest-running workgroups of the step while compute
+// units idle.  So the tokens are cut into more, smaller tiles (48 tokens at least) until the
+// gate/up launch has about `target_wgs` workgroups (the down launch splits K to match); the
+// caller sets the target by what runs next to the shared experts (shared_target_wgs).
+// Measured, 60 experts top-4 + 1 shared expert of 5632 (44 workgroups per token tile), whole step
+// in us by tokens per tile: 128 tokens: 128 -> 168, 64 -> 155; 256 tokens: 288 -> 207, 128 -> 174,
+// 64 -> 166; 512 tokens: 288 -> 271, 192 -> 252, 128 -> 237, 96 -> 267, 64 -> 254; 768 tokens:
+// 288 -> 291, 192 -> 273, 128 -> 303; from 1024 tokens 288 is best (176 workgroups or more).
+// 64 experts top-6 + 2 shared experts of 1408 (22 per token tile): within 2 % from 64 to 288.
+static int shared_token_parts(int32_t T, int n_same, int f, int target_wgs)
+{
+    int parts = (T + TILE_MAX_TOKENS - 1) / TILE_MAX_TOKENS;
+    const int per_part = n_same * ((f + 127) / 128);              // gate/up workgroups per token tile
+    int want = (target_wgs + per_part / 2) / per_part;
+    const int most = T / PZL_SHARED_TILE_MIN_TOKENS;
+    if (want > most) want = most;
+    return want > parts ? want : parts;
+}
+
+// Workgroups that the shared experts' gate/up launch should have.  Next to routed kernels that
+// leave compute units idle (streaming launches, short one-shot tile lists): two thirds of the
+// chip.  Next to persistent tiled launches, which occupy every compute unit: in proportion to the
+// shared experts' part of the step's matrix work, with the same allowance (a shared expert as
+// heavy as the routed top-k gets two thirds, two narrow ones next to top-6 get a third).
+static int shared_target_wgs(const pzl_layer *L, int32_t k, bool chip_busy)
+{
+    if (!chip_busy) return PZL_SHARED_TILE_WGS;
+    double fs = 0.0;
+    for (int s = 0; s < L->n_shared; ++s) fs += L->shared_f[s];
+    const double share = fs / (fs + (double)k * L->d_ffn);
+    return (int)(2.0 * PZL_SHARED_TILE_WGS * share);
 }
 
 static int choose_ksplit(int groups_touched_max, int rows)
@@ -476,11 +517,13 @@ int pzl_moe_ffn_staged(const pzl_layer *L, const uint16_t *x, const int32_t *top
     // one k-split count for all shared experts (the combine step sums that many partials); sized
     // for the usual case, all of them of one width and hence in one launch per stage
     const int ns = L->n_shared > 0 ? L->n_shared : 1;
+    const int shared_wgs = shared_target_wgs(L, k, tiled && persistent);
     int ksplit_shared = choose_ksplit(ns * ((T + 63) / 64), L->d_model);
     if (tiled_shared) {
         ksplit_shared = MAX_KSPLIT;
         for (int s = 0; s < L->n_shared; ++s) {
-            int ks = choose_tile_ksplit((int64_t)ns * ((T + TILE_MAX_TOKENS - 1) / TILE_MAX_TOKENS), (int64_t)ns * T, L->d_model, L->shared_f[s]);
+            int ks = choose_tile_ksplit((int64_t)ns * shared_token_parts(T, ns, L->shared_f[s], shared_wgs), (int64_t)ns * T,
+                                        L->d_model, L->shared_f[s]);
             if (ks < ksplit_shared) ksplit_shared = ks;
         }
     }
@@ -561,7 +604,7 @@ int pzl_moe_ffn_staged(const pzl_layer *L, const uint16_t *x, const int32_t *top
         const int64_t hs_plane = (int64_t)nb * T * L->shared_f[s];
         if (tiled_shared) {
             TileGemmArgs a = {};
-            const int parts = (T + TILE_MAX_TOKENS - 1) / TILE_MAX_TOKENS;
+            const int parts = shared_token_parts(T, nb, L->shared_f[s], shared_wgs);
             a.dense_tokens = T; a.dense_slot_base = slot_base;
             a.dense_tile_tokens = ((T + parts - 1) / parts + 15) & ~15;
             a.dense_tiles = nb * ((T + a.dense_tile_tokens - 1) / a.dense_tile_tokens);

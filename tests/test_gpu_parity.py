@@ -214,8 +214,9 @@ def tiled_case(oracle, binding):
 
 @pytest.mark.parametrize("T", [192, 200, 333, 600, 1100])
 def test_tiled_path_token_counts(tiled_case, T):
-    """>= 96 slots per expert: tiled kernels; ragged token tiles, several tiles per expert, and from
-    384 tokens the dense shared expert on the tiled kernels too."""
+    """>= 96 slots per expert: tiled kernels; ragged token tiles, several tiles per expert; the
+    dense shared expert runs on the tiled kernels too (from 96 tokens), its tokens cut into several
+    small tiles with a ragged last one."""
     check(tiled_case, T, "tiled")
 
 
