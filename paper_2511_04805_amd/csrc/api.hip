@@ -47,7 +47,7 @@ namespace pzl {
 #define PZL_TILED_MIN_TPE 96
 #endif
 #ifndef PZL_TILED_MIN_SHARED
-#define PZL_TILED_MIN_SHARED 96
+#define PZL_TILED_MIN_SHARED 65
 #endif
 #ifndef PZL_SHARED_TILE_WGS
 #define PZL_SHARED_TILE_WGS 168
@@ -171,6 +171,24 @@ static int shared_target_wgs(const pzl_layer *L, int32_t k, bool chip_busy)
     for (int s = 0; s < L->n_shared; ++s) fs += L->shared_f[s];
     const double share = fs / (fs + (double)k * L->d_ffn);
     return (int)(2.0 * PZL_SHARED_TILE_WGS * share);
+}
+
+// Workgroups per routed group and row block in the streaming kernels.  A sweep of a pair's
+// weights serves 32 tokens per expert (64 for an expert kept unmerged); an expert with more takes
+// further sweeps.  Where the tiled kernels are launched too, such pairs are theirs and one
+// workgroup is enough.  Otherwise (small batches) a router that favours some experts can still
+// hand one of them up to T tokens, and its pair's workgroups would run two or three sweeps in a
+// row while the rest of the chip has finished: give every group that many workgroups, each taking
+// every n-th sweep; those that find no sweep to do leave at once.
+#ifndef PZL_STREAM_PASS_WGS_MAX
+#define PZL_STREAM_PASS_WGS_MAX 3
+#endif
+static int stream_pass_wgs(int32_t T, int kind, bool tiled_too)
+{
+    if (tiled_too) return 1;
+    const int per_sweep = kind == KIND_UNMERGED ? 64 : 32;
+    const int n = (T + per_sweep - 1) / per_sweep;
+    return n < 1 ? 1 : n > PZL_STREAM_PASS_WGS_MAX ? PZL_STREAM_PASS_WGS_MAX : n;
 }
 
 static int choose_ksplit(int groups_touched_max, int rows)
@@ -570,6 +588,7 @@ int pzl_moe_ffn_staged(const pzl_layer *L, const uint16_t *x, const int32_t *top
                 a.n_groups = n_groups; a.group_base = group_base;
                 a.groups_touched_max = (int)((int64_t)N < n_groups ? N : n_groups);
                 a.cnt = rt.cnt; a.off = rt.off; a.slot_tok = rt.slot_tok;
+                a.pass_wgs = stream_pass_wgs(T, kind, hybrid);
                 if (stage == 0) {                        // gate/up + SwiGLU -> H
                     a.w_a = wg; a.w_b = wu;
                     if (kind == KIND_QUANT) { a.s_a = L->d_gscale; a.s_b = L->d_uscale; }

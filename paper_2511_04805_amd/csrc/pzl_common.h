@@ -103,6 +103,7 @@ struct StreamGroupArgs {
     float *o_out;                 // down stage: partial sums [ksplit][slots][rows] fp32
     int64_t o_ks_stride;          // elements between k-splits
     int32_t ksplit;
+    int32_t pass_wgs;             // routed groups: workgroups that share a group's token passes (0 = 1)
 };
 int stream_row_groups(int rows, bool down_stage);   // row groups (workgroup units) along the output rows
 #ifndef SG_WAVES_N

@@ -69,7 +69,7 @@ struct SgArgs {
     const int32_t *cnt, *off, *slot_tok;
     int32_t group_base;          // routed groups: first group index (q = 2 * (group_base + g) + pos)
     int32_t dense_tokens, dense_slot_base;
-    int32_t n_passes;            // ALLTOK groups: token passes, each taken by its own workgroup
+    int32_t n_passes;            // workgroups per (group, rows, K split): workgroup p takes the token passes p, p + n_passes, ...
     uint16_t *h_out;
     int64_t h_plane_stride;
     int32_t h_slot_base;
@@ -461,9 +461,16 @@ stream_kernel(SgArgs a)
     int b = blockIdx.x;
     // A shared expert has few row groups (few workgroups) but sees every token: its token passes
     // go to different workgroups (pass index fastest, so the workgroups that read the same
-    // weights run at the same time and share them through L2 / the memory-side cache).
-    const int my_pass = ALLTOK ? b % a.n_passes : 0;
-    if (ALLTOK) b /= a.n_passes;
+    // weights run at the same time and share them through L2 / the memory-side cache).  Routed
+    // groups get n_passes workgroups too where a router that favours some experts may give one
+    // more tokens than a pass holds: the busy group's passes then run side by side instead of
+    // making its workgroups the last to finish; workgroups with no pass to do leave at once.
+    // (The hardware deals consecutive workgroup ids to the XCDs in turn: a routed group's extra
+    // workgroups therefore take the ids after all the first ones, not every n-th id, which would
+    // leave the first workgroups, the ones that always have work, on a subset of the XCDs.)
+    const int per_pass = gridDim.x / a.n_passes;
+    const int my_pass = ALLTOK ? b % a.n_passes : b / per_pass;
+    b = ALLTOK ? b / a.n_passes : b % per_pass;
     const int ks = b % a.ksplit; b /= a.ksplit;
     const int rgb = b % rg_blocks;
     const int g = b / rg_blocks;
@@ -491,6 +498,7 @@ stream_kernel(SgArgs a)
     const uint16_t *sb = QUANT ? ((STAGE == STAGE_GATEUP) ? a.s_b[g] : sa) : nullptr;
     constexpr int PT = DENSE ? SG_MAX_TILES : SG_POS_TILES;   // a dense group has one position only
     const int tiles0 = (n0 + 15) >> 4, tiles1 = (n1 + 15) >> 4;
+    if (my_pass * PT >= max(tiles0, tiles1)) return;
 
     for (int rg = rgb * a.rg_per_wg; rg < min(row_groups, (rgb + 1) * a.rg_per_wg); ++rg) {
     int rt0 = (rg * SG_WAVES + wave) * RT_PER_WAVE;
@@ -498,7 +506,7 @@ stream_kernel(SgArgs a)
     const bool active0 = rt0 < row_tiles, active1 = rt1 < row_tiles;
     rt0 = min(rt0, row_tiles - 1);      // inactive streams re-read a valid tile and store nothing
     rt1 = min(rt1, row_tiles - 1);
-    for (int t0 = my_pass * PT, t1 = 0; t0 < tiles0 || t1 < tiles1; t0 += PT, t1 += PT) {
+    for (int t0 = my_pass * PT, t1 = t0; t0 < tiles0 || t1 < tiles1; t0 += a.n_passes * PT, t1 = t0) {
         int c0 = min(PT, max(tiles0 - t0, 0));
         int c1 = min(PT, max(tiles1 - t1, 0));
 #define PZL_PASS(A, B)                                                                              \
@@ -524,7 +532,6 @@ stream_kernel(SgArgs a)
             }
         }
 #undef PZL_PASS
-        if (ALLTOK) break;           // the other passes belong to other workgroups
     }
     }
 }
@@ -556,9 +563,11 @@ static int launch(const StreamGroupArgs &g, hipStream_t st)
     // groups instead keeps the launch to one round.
     const int row_groups = stream_row_groups(g.rows, STAGE == STAGE_DOWN);
     const int pass_tokens = SG_MAX_TILES * 16;
-    a.n_passes = ALLTOK ? (g.dense_tokens + pass_tokens - 1) / pass_tokens : 1;
+    a.n_passes = ALLTOK ? (g.dense_tokens + pass_tokens - 1) / pass_tokens : g.pass_wgs;
     if (a.n_passes < 1) a.n_passes = 1;
-    const int64_t units = (int64_t)(g.groups_touched_max > 0 ? g.groups_touched_max : g.n_groups) * row_groups * g.ksplit * a.n_passes;
+    // (a routed group's extra pass workgroups mostly find nothing to do: not counted as work)
+    const int64_t units = (int64_t)(g.groups_touched_max > 0 ? g.groups_touched_max : g.n_groups) * row_groups * g.ksplit *
+                          (ALLTOK ? a.n_passes : 1);
     int rg_per_wg = (int)((units + SG_RESIDENT_WGS - 1) / SG_RESIDENT_WGS);
     if (rg_per_wg < 1) rg_per_wg = 1;
     if (rg_per_wg > 4) rg_per_wg = 1;            // many rounds anyway: keep the units small
