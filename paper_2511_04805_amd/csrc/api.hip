@@ -183,11 +183,11 @@ static int shared_target_wgs(const pzl_layer *L, int32_t k, bool chip_busy)
 #ifndef PZL_STREAM_PASS_WGS_MAX
 #define PZL_STREAM_PASS_WGS_MAX 3
 #endif
-static int stream_pass_wgs(int32_t T, int kind, bool tiled_too)
+static int stream_pass_wgs(int32_t T, int kind, int tile_min)
 {
-    if (tiled_too) return 1;
+    const int most = T < tile_min - 1 ? T : tile_min - 1;      // tokens of one expert that can come to the streaming kernels
     const int per_sweep = kind == KIND_UNMERGED ? 64 : 32;
-    const int n = (T + per_sweep - 1) / per_sweep;
+    const int n = (most + per_sweep - 1) / per_sweep;
     return n < 1 ? 1 : n > PZL_STREAM_PASS_WGS_MAX ? PZL_STREAM_PASS_WGS_MAX : n;
 }
 
@@ -588,7 +588,7 @@ int pzl_moe_ffn_staged(const pzl_layer *L, const uint16_t *x, const int32_t *top
                 a.n_groups = n_groups; a.group_base = group_base;
                 a.groups_touched_max = (int)((int64_t)N < n_groups ? N : n_groups);
                 a.cnt = rt.cnt; a.off = rt.off; a.slot_tok = rt.slot_tok;
-                a.pass_wgs = stream_pass_wgs(T, kind, hybrid);
+                a.pass_wgs = stream_pass_wgs(T, kind, tile_min);
                 if (stage == 0) {                        // gate/up + SwiGLU -> H
                     a.w_a = wg; a.w_b = wu;
                     if (kind == KIND_QUANT) { a.s_a = L->d_gscale; a.s_b = L->d_uscale; }
