@@ -497,14 +497,89 @@ int pzl_moe_ffn_staged(const pzl_layer *L, const uint16_t *x, const int32_t *top
     const bool mostly_tiled = hybrid && (int64_t)N >= (int64_t)TILED_MIN_TOKENS_PER_EXPERT * E64;
     const bool tiled_shared = T >= TILED_MIN_TOKENS_SHARED;
 
-    int rc = mark(PZL_STAGE_ROUTE, 0);
-    if (rc) return rc;
     // Many experts with at most about one full tile each: the tile list is far shorter than its
     // bound and its tiles are uneven, so the tiled launches are persistent and draw their tiles
     // (counters zeroed by the grouping kernel).  Otherwise one workgroup per tile of the bound.
     // Measured (whole step, persistent vs not): 64 experts top-6 at 512-2048 tokens -9 %, at 4096
     // +4 %; 60 experts top-4 at 2048 -3 %, at 4096 +3 %; 8 experts top-2 at 2048-4096 +5-7 %.
     const bool persistent = L->n_q >= 32 && (int64_t)N <= (int64_t)256 * L->n_q;
+    // one k-split count for all shared experts (the combine step sums that many partials); sized
+    // for the usual case, all of them of one width and hence in one launch per stage
+    const int ns = L->n_shared > 0 ? L->n_shared : 1;
+    const int shared_wgs = shared_target_wgs(L, k, tiled && persistent);
+    int ksplit_shared = choose_ksplit(ns * ((T + 63) / 64), L->d_model);
+    if (tiled_shared) {
+        ksplit_shared = MAX_KSPLIT;
+        for (int s = 0; s < L->n_shared; ++s) {
+            int ks = choose_tile_ksplit((int64_t)ns * shared_token_parts(T, ns, L->shared_f[s], shared_wgs), (int64_t)ns * T,
+                                        L->d_model, L->shared_f[s]);
+            if (ks < ksplit_shared) ksplit_shared = ks;
+        }
+    }
+    // Shared experts of equal width go into one launch per stage (group index = expert), so that
+    // the launch has enough workgroups; their H rows sit back to back, slot = N + s*T + t.
+    auto launch_shared = [&]() -> int {
+        int rc;
+        size_t h_off = w.h_shared;
+        for (int s = 0; s < L->n_shared;) {
+            int nb = 1;
+            while (s + nb < L->n_shared && L->shared_f[s + nb] == L->shared_f[s]) ++nb;
+            uint16_t *h_s = (uint16_t *)(ws + h_off);
+            for (int j = 0; j < nb; ++j) h_off += w.h_shared_each(L, T, s + j);
+            const int32_t slot_base = N + s * T;
+            const int64_t hs_plane = (int64_t)nb * T * L->shared_f[s];
+            if (tiled_shared) {
+                TileGemmArgs a = {};
+                const int parts = shared_token_parts(T, nb, L->shared_f[s], shared_wgs);
+                a.dense_tokens = T; a.dense_slot_base = slot_base;
+                a.dense_tile_tokens = ((T + parts - 1) / parts + 15) & ~15;
+                a.dense_tiles = nb * ((T + a.dense_tile_tokens - 1) / a.dense_tile_tokens);
+                a.max_mtiles = a.dense_tiles;
+                a.w_a = L->d_sgate + s; a.w_b = L->d_sup + s;
+                a.rows = L->shared_f[s]; a.kdim = L->d_model;
+                a.act = x; a.act_is_x = 1;
+                a.h_out = h_s; a.h_slot_base = slot_base; a.h_plane_stride = hs_plane;
+                rc = launch_tile_gateup(a, KIND_SHARED, sst);
+                if (rc) return rc;
+                a.w_a = L->d_sdown + s; a.w_b = nullptr;
+                a.rows = L->d_model; a.kdim = L->shared_f[s];
+                a.act = h_s; a.act_is_x = 0; a.act_slot_base = slot_base; a.act_plane_stride = hs_plane;
+                a.h_out = nullptr; a.o_out = opart; a.o_ks_stride = w.o_ks_stride; a.ksplit = ksplit_shared;
+                rc = launch_tile_down(a, KIND_SHARED, sst);
+                if (rc) return rc;
+                s += nb;
+                continue;
+            }
+            StreamGroupArgs a = {};
+            a.n_groups = nb;
+            a.dense_tokens = T; a.dense_slot_base = slot_base;
+            a.w_a = L->d_sgate + s; a.w_b = L->d_sup + s;
+            a.rows = L->shared_f[s]; a.kdim = L->d_model; a.ksplit = 1;
+            a.act = x; a.act_is_x = 1; a.act_slot_base = 0;
+            a.h_out = h_s; a.h_slot_base = slot_base; a.h_plane_stride = hs_plane;
+            rc = launch_stream_gateup(a, KIND_SHARED, sst);
+            if (rc) return rc;
+            a.w_a = L->d_sdown + s; a.w_b = nullptr;
+            a.rows = L->d_model; a.kdim = L->shared_f[s]; a.ksplit = ksplit_shared;
+            a.act = h_s; a.act_is_x = 0; a.act_slot_base = slot_base; a.act_plane_stride = hs_plane;
+            a.h_out = nullptr; a.o_out = opart; a.o_ks_stride = w.o_ks_stride;
+            rc = launch_stream_down(a, KIND_SHARED, sst);
+            if (rc) return rc;
+            s += nb;
+        }
+        return PZL_OK;
+    };
+    // The shared experts do not depend on the routing: with a stream of their own they are
+    // enqueued first, so that they can start with the grouping kernel and not when the host gets
+    // to them after the routed launches (no difference in a loop of calls, where the host runs
+    // ahead of the device anyway; it matters to a caller that waits for each call).
+    if (overlap) {
+        int rc_shared = launch_shared();
+        if (rc_shared) return rc_shared;
+    }
+
+    int rc = mark(PZL_STAGE_ROUTE, 0);
+    if (rc) return rc;
     // one-shot launches may give both experts of a pair one tile (row groups of gate/up tell the
     // grouping kernel how long the launch is); persistent launches do not have those kernels
     rc = launch_route(topk_ids, N, k, L->n_experts, L->n_q, L->d_q_of_expert, rt, tile_min,
@@ -532,19 +607,6 @@ int pzl_moe_ffn_staged(const pzl_layer *L, const uint16_t *x, const int32_t *top
     int ksplit = mostly_tiled ? choose_tile_ksplit(N / TILE_MAX_TOKENS + L->n_experts / 2, N, L->d_model, L->d_ffn)
                            : choose_ksplit(groups_max > 0 ? groups_max : 1, L->d_model);
     if (L->pair_format == 1 && ksplit > L->d_ffn / 128) ksplit = L->d_ffn / 128;   // whole 128-column groups per split
-    // one k-split count for all shared experts (the combine step sums that many partials); sized
-    // for the usual case, all of them of one width and hence in one launch per stage
-    const int ns = L->n_shared > 0 ? L->n_shared : 1;
-    const int shared_wgs = shared_target_wgs(L, k, tiled && persistent);
-    int ksplit_shared = choose_ksplit(ns * ((T + 63) / 64), L->d_model);
-    if (tiled_shared) {
-        ksplit_shared = MAX_KSPLIT;
-        for (int s = 0; s < L->n_shared; ++s) {
-            int ks = choose_tile_ksplit((int64_t)ns * shared_token_parts(T, ns, L->shared_f[s], shared_wgs), (int64_t)ns * T,
-                                        L->d_model, L->shared_f[s]);
-            if (ks < ksplit_shared) ksplit_shared = ks;
-        }
-    }
     const int64_t h_plane = (int64_t)N * L->d_ffn;
     // Routed experts come in two kinds that differ only in the decode: packed pairs (groups
     // [0, P)) and experts kept unmerged (dense bf16, groups [P, P + D), position 0 only).  Both
@@ -611,55 +673,7 @@ int pzl_moe_ffn_staged(const pzl_layer *L, const uint16_t *x, const int32_t *top
     }
 
     if ((rc = mark(PZL_STAGE_SHARED, 0))) return rc;
-    // Shared experts of equal width go into one launch per stage (group index = expert), so that
-    // the launch has enough workgroups; their H rows sit back to back, slot = N + s*T + t.
-    size_t h_off = w.h_shared;
-    for (int s = 0; s < L->n_shared;) {
-        int nb = 1;
-        while (s + nb < L->n_shared && L->shared_f[s + nb] == L->shared_f[s]) ++nb;
-        uint16_t *h_s = (uint16_t *)(ws + h_off);
-        for (int j = 0; j < nb; ++j) h_off += w.h_shared_each(L, T, s + j);
-        const int32_t slot_base = N + s * T;
-        const int64_t hs_plane = (int64_t)nb * T * L->shared_f[s];
-        if (tiled_shared) {
-            TileGemmArgs a = {};
-            const int parts = shared_token_parts(T, nb, L->shared_f[s], shared_wgs);
-            a.dense_tokens = T; a.dense_slot_base = slot_base;
-            a.dense_tile_tokens = ((T + parts - 1) / parts + 15) & ~15;
-            a.dense_tiles = nb * ((T + a.dense_tile_tokens - 1) / a.dense_tile_tokens);
-            a.max_mtiles = a.dense_tiles;
-            a.w_a = L->d_sgate + s; a.w_b = L->d_sup + s;
-            a.rows = L->shared_f[s]; a.kdim = L->d_model;
-            a.act = x; a.act_is_x = 1;
-            a.h_out = h_s; a.h_slot_base = slot_base; a.h_plane_stride = hs_plane;
-            rc = launch_tile_gateup(a, KIND_SHARED, sst);
-            if (rc) return rc;
-            a.w_a = L->d_sdown + s; a.w_b = nullptr;
-            a.rows = L->d_model; a.kdim = L->shared_f[s];
-            a.act = h_s; a.act_is_x = 0; a.act_slot_base = slot_base; a.act_plane_stride = hs_plane;
-            a.h_out = nullptr; a.o_out = opart; a.o_ks_stride = w.o_ks_stride; a.ksplit = ksplit_shared;
-            rc = launch_tile_down(a, KIND_SHARED, sst);
-            if (rc) return rc;
-            s += nb;
-            continue;
-        }
-        StreamGroupArgs a = {};
-        a.n_groups = nb;
-        a.dense_tokens = T; a.dense_slot_base = slot_base;
-        a.w_a = L->d_sgate + s; a.w_b = L->d_sup + s;
-        a.rows = L->shared_f[s]; a.kdim = L->d_model; a.ksplit = 1;
-        a.act = x; a.act_is_x = 1; a.act_slot_base = 0;
-        a.h_out = h_s; a.h_slot_base = slot_base; a.h_plane_stride = hs_plane;
-        rc = launch_stream_gateup(a, KIND_SHARED, sst);
-        if (rc) return rc;
-        a.w_a = L->d_sdown + s; a.w_b = nullptr;
-        a.rows = L->d_model; a.kdim = L->shared_f[s]; a.ksplit = ksplit_shared;
-        a.act = h_s; a.act_is_x = 0; a.act_slot_base = slot_base; a.act_plane_stride = hs_plane;
-        a.h_out = nullptr; a.o_out = opart; a.o_ks_stride = w.o_ks_stride;
-        rc = launch_stream_down(a, KIND_SHARED, sst);
-        if (rc) return rc;
-        s += nb;
-    }
+    if (!overlap && (rc = launch_shared())) return rc;
 
     if (tile_overlap) {
         hipError_t e = hipEventRecord(L->ev_tjoin, L->tile_stream);
