@@ -186,6 +186,11 @@ size_t pzl_moe_ffn_workspace_bytes(const pzl_layer *layer, int32_t max_tokens, i
  * shared experts n_shared * T * f_shared < 2^30; PZL_EINVAL beyond them.
  * T == 0 is a no-op.  Calls on one layer must not overlap in time on different streams (see
  * pzl_layer_create); calls queued on one stream are fine.
+ * Graph capture: the call only enqueues kernels and event record / wait pairs (the fork to and the
+ * join from the layer's own streams), allocates nothing, synchronises nothing and clears its
+ * counters inside its kernels, so it may be made on a capturing stream; replays are bit-identical
+ * to eager calls.  Make one eager call with the same shapes first: the first launch of each kernel
+ * sets a function attribute, which is not a stream operation.
  */
 int pzl_moe_ffn(const pzl_layer *layer, const uint16_t *x, const int32_t *topk_ids,
                 const float *topk_w, int32_t T, int32_t k, uint16_t *y,
