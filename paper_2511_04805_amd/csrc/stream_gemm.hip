@@ -558,7 +558,7 @@ static int launch(const StreamGroupArgs &g, hipStream_t st)
     a.dense_tokens = g.dense_tokens; a.dense_slot_base = g.dense_slot_base;
     a.h_out = g.h_out; a.h_plane_stride = g.h_plane_stride; a.h_slot_base = g.h_slot_base;
     a.o_out = g.o_out; a.o_ks_stride = g.o_ks_stride;
-    // Two workgroups fit a compute unit (registers, LDS), 512 on the chip.  A launch a little
+    // One workgroup (8 waves, two per SIMD) fits a compute unit, 256 on the chip.  A launch a little
     // larger than that runs a second, partly empty round; giving each workgroup several row
     // groups instead keeps the launch to one round.
     const int row_groups = stream_row_groups(g.rows, STAGE == STAGE_DOWN);
