@@ -123,6 +123,23 @@ def time_plain(hip, layer, xt, idt, wt, steps, warmup):
     return hip.elapsed_ms(t0, t1) / steps
 
 
+def time_router(hip, cfg, xt, steps=50, warmup=5):
+    """The on-device router in front of the layer (random router weights), on its own: ms per call."""
+    g = torch.Generator(device="cuda"); g.manual_seed(7)
+    wr = (torch.randn(cfg.n_experts, cfg.d_model, generator=g, device="cuda") * 0.05).to(torch.bfloat16)
+    stream = torch.cuda.current_stream().cuda_stream
+    for _ in range(warmup):
+        binding.pzl_router_topk(xt, wr, cfg.top_k)
+    t0, t1 = hip.event(), hip.event()
+    torch.cuda.synchronize()
+    hip.record(t0, stream)
+    for _ in range(steps):
+        binding.pzl_router_topk(xt, wr, cfg.top_k)
+    hip.record(t1, stream)
+    torch.cuda.synchronize()
+    return hip.elapsed_ms(t0, t1) / steps
+
+
 def touched_pairs(ids, emap):
     return len(set(int(emap[0][e]) for e in np.unique(ids)))
 
@@ -289,7 +306,7 @@ def main():
             flops = 2.0 * 3 * c2.d_model * (T2 * c2.top_k * c2.d_ffn + T2 * sum(c2.shared_d_ffn))
             out["other_shapes"][name] = {
                 "tokens": T2, "experts": c2.n_experts, "top_k": c2.top_k, "touched_pairs": nt2,
-                "ms_per_step": ms2, "tokens_per_s": T2 / (ms2 * 1e-3),
+                "ms_per_step": ms2, "tokens_per_s": T2 / (ms2 * 1e-3), "router_ms": time_router(hip, c2, xt2),
                 "hbm_frac": w_bytes / (ms2 * 1e-3) / 1e9 / HBM_PEAK_GBS,
                 "useful_mfma_frac": flops / (ms2 * 1e-3) / 2.5e15}
             del l2

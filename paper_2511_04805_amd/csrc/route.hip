@@ -233,53 +233,151 @@ combine_kernel(const float *__restrict__ opart, int32_t ksplit, int32_t ksplit_s
 }
 
 // Router in front of the experts (not in the paper, which leaves the rest of the model unchanged,
-// Sec. 4.1): logits = x W_r^T, top-k, softmax over the selected logits.  One workgroup per token;
-// thread e owns expert e and accumulates its logit as ONE fused-multiply-add chain over the
-// channels in order, so the logits, and with them the chosen experts, are reproducible bit for bit
-// by a CPU that does the same.  Ties go to the lower expert index.
+// Sec. 4.1): logits = x W_r^T, top-k, softmax over the selected logits.  A lane owns one (token,
+// expert) logit and accumulates it as ONE fused-multiply-add chain over the channels in order,
+// so the logits, and with them the chosen experts, are reproducible bit for bit by a CPU that
+// does the same.  Ties go to the lower expert index.
+// The chain is the time: d dependent steps of three vector operations (two bf16 -> fp32
+// conversions and the fma), whatever the number of lanes in use, so nothing else may hold it up.
+// Thread = token * e_pad + expert (e_pad: the power of two >= E, at least 8), 256 / e_pad tokens
+// per workgroup.  The lanes of a wave want 16 bytes each of DIFFERENT rows of W_r, which as a
+// global load costs one cache line per lane and instruction; instead the workgroup copies W_r in
+// chunks of CH channels (contiguous pieces of each row) into LDS, one chunk ahead of the chains
+// (a chunk is long enough to cover the latency of the next one's loads), and every lane reads its
+// row from there (row pitch CH*2 + 16 bytes).  x is read directly (the lanes of a token share the
+// address), one chunk ahead as well.
 constexpr int ROUTER_MAX_E = 256;
 constexpr int ROUTER_MAX_K = 64;
+constexpr int ROUTER_THREADS = 256;
+constexpr int ROUTER_MAX_TPB = ROUTER_THREADS / 8; // tokens per workgroup at e_pad = 8
 
-__global__ void __launch_bounds__(ROUTER_MAX_E)
-router_topk_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ w_router, int32_t d,
-                   int32_t E, int32_t k, int32_t *__restrict__ ids_out, float *__restrict__ w_out)
+template <int CH, int EROWS>                        // channels per chunk, rows of W_r the buffers hold
+__global__ void __launch_bounds__(ROUTER_THREADS)
+router_topk_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ w_router, int32_t T, int32_t d,
+                   int32_t E, int32_t k, int32_t e_pad, int32_t *__restrict__ ids_out, float *__restrict__ w_out)
 {
-    __shared__ float logit[ROUTER_MAX_E];
-    __shared__ float sel[ROUTER_MAX_K];
-    const int t = blockIdx.x, e = threadIdx.x;
-    if (e < E) {
-        const u32x4 *xr = (const u32x4 *)(x + (int64_t)t * d);
-        const u32x4 *wr = (const u32x4 *)(w_router + (int64_t)e * d);
-        float acc = 0.0f;
-        for (int c = 0; c < d / 8; ++c) {
-            u32x4 xv = xr[c], wv = wr[c];
+    constexpr int PITCH = CH * 2 + 16;              // bytes per row of a chunk in LDS
+    constexpr int UNITS = CH / 8;                   // 16-byte units per row and chunk
+    constexpr int WLOADS = EROWS * UNITS / ROUTER_THREADS;
+    static_assert(EROWS * UNITS % ROUTER_THREADS == 0, "copy loop");
+    __shared__ __attribute__((aligned(16))) unsigned char wbuf[2][EROWS * PITCH];
+    __shared__ float logit[ROUTER_THREADS];
+    __shared__ float sel[ROUTER_MAX_TPB][ROUTER_MAX_K];
+    const int tid = threadIdx.x;
+    const int tpb = ROUTER_THREADS / e_pad;
+    const int e = tid % e_pad, ts = tid / e_pad;
+    const int t = blockIdx.x * tpb + ts;
+    {
+        // lanes beyond the batch or the expert count run the chain of a valid (token, expert) and drop it
+        const u32x4 *xr = (const u32x4 *)(x + (int64_t)min(t, T - 1) * d);
+        const unsigned char *my_row = &wbuf[0][0] + min(e, E - 1) * PITCH;
+        const int n8 = d / 8;                             // 16-byte units per row; the last chunk may hold fewer than UNITS
+        const int n_chunks = (d + CH - 1) / CH;
+        u32x4 wreg[WLOADS], xreg[UNITS];
+        // unit v of a chunk = (row v / UNITS, 16-byte part v % UNITS); thread tid copies units tid, tid + 256, ...
+        auto fetch_w = [&](int chunk) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                acc = __fmaf_rn(__uint_as_float(xv[i] << 16), __uint_as_float(wv[i] << 16), acc);
-                acc = __fmaf_rn(__uint_as_float(xv[i] & 0xFFFF0000u), __uint_as_float(wv[i] & 0xFFFF0000u), acc);
+            for (int i = 0; i < WLOADS; ++i) {
+                const int v = tid + i * ROUTER_THREADS;
+                if (v < E * UNITS && chunk * UNITS + v % UNITS < n8)
+                    wreg[i] = *(const u32x4 *)(w_router + (int64_t)(v / UNITS) * d + chunk * CH + (v % UNITS) * 8);
             }
+        };
+        auto store_w = [&](int buf) {
+#pragma unroll
+            for (int i = 0; i < WLOADS; ++i) {
+                const int v = tid + i * ROUTER_THREADS;
+                if (v < E * UNITS) *(u32x4 *)(&wbuf[buf][0] + (v / UNITS) * PITCH + (v % UNITS) * 16) = wreg[i];
+            }
+        };
+        auto fetch_x = [&](int chunk) {
+#pragma unroll
+            for (int u = 0; u < UNITS; ++u) xreg[u] = xr[min(chunk * UNITS + u, n8 - 1)];
+        };
+        float acc = 0.0f;
+        fetch_w(0);
+        fetch_x(0);
+        store_w(0);
+        __syncthreads();
+        for (int c = 0; c < n_chunks; ++c) {
+            const bool more = c + 1 < n_chunks;
+            u32x4 xv[UNITS];
+#pragma unroll
+            for (int u = 0; u < UNITS; ++u) xv[u] = xreg[u];
+            if (more) { fetch_w(c + 1); fetch_x(c + 1); }
+            const unsigned char *row = my_row + (c & 1) * (EROWS * PITCH);
+            // a whole chunk is straight-line code (the LDS reads can then run ahead of the chain);
+            // only the last chunk of a row that is not a multiple of CH long checks its units
+            auto unit = [&](int u) {
+                const u32x4 wv = *(const u32x4 *)(row + u * 16);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    acc = __fmaf_rn(__uint_as_float(xv[u][i] << 16), __uint_as_float(wv[i] << 16), acc);
+                    acc = __fmaf_rn(__uint_as_float(xv[u][i] & 0xFFFF0000u), __uint_as_float(wv[i] & 0xFFFF0000u), acc);
+                }
+            };
+            if ((c + 1) * UNITS <= n8) {
+#pragma unroll
+                for (int u = 0; u < UNITS; ++u) unit(u);
+            } else {
+#pragma unroll
+                for (int u = 0; u < UNITS; ++u) if (c * UNITS + u < n8) unit(u);
+            }
+            if (more) store_w((c + 1) & 1);               // last read two chunks ago, before the previous barrier
+            __syncthreads();
         }
-        logit[e] = acc;
+        logit[tid] = acc;
     }
     __syncthreads();
-    if (e == 0) {
-        // k selection passes; a taken expert is marked by clearing its slot to -inf after the
-        // pass has recorded it (a NaN logit never wins, as on the CPU side)
-        for (int j = 0; j < k; ++j) {
-            int best = -1;
-            float bv = 0.0f;
-            for (int i = 0; i < E; ++i) {
-                float v = logit[i];
-                bool free_slot = !(__float_as_uint(v) == 0xFF800001u);      // marker, see below
-                if (free_slot && (best < 0 || v > bv)) { best = i; bv = v; }
+    // k selection passes: the largest logit not yet taken, ties to the lower expert index.
+    // A token whose experts sit in one wave (e_pad <= 64) and whose logits are all numbers takes
+    // each pass as a butterfly over its e_pad lanes on (value, index); otherwise one thread scans
+    // the logits in LDS in index order, as the CPU side does (which also fixes what happens with
+    // a NaN logit: it is never larger than anything, and nothing is larger than it).
+    bool scan = e_pad > 64;
+    if (!scan) {
+        const float v = logit[tid];
+        float nanf_ = (e < E && v != v) ? 1.0f : 0.0f;
+        for (int off = e_pad / 2; off >= 1; off >>= 1) nanf_ = fmaxf(nanf_, __shfl_xor(nanf_, off, 64));
+        scan = nanf_ != 0.0f;                               // the same for all lanes of the token
+        if (!scan) {
+            bool taken = e >= E;
+            for (int j = 0; j < k; ++j) {
+                float bv = taken ? -INFINITY : v;
+                int bi = taken ? 0x7FFFFFFF : e;
+                for (int off = e_pad / 2; off >= 1; off >>= 1) {
+                    const float ov = __shfl_xor(bv, off, 64);
+                    const int oi = __shfl_xor(bi, off, 64);
+                    if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+                }
+                if (e == bi) taken = true;
+                if (e == 0 && t < T) {
+                    ids_out[(int64_t)t * k + j] = bi;
+                    sel[ts][j] = bv;
+                }
             }
-            ids_out[(int64_t)t * k + j] = best;
-            sel[j] = bv;
-            logit[best] = __uint_as_float(0xFF800001u);                     // a NaN pattern no fma chain of finite bf16 yields
         }
-        float mx = sel[0], sum = 0.0f;
-        for (int j = 0; j < k; ++j) sum += expf(sel[j] - mx);
-        for (int j = 0; j < k; ++j) w_out[(int64_t)t * k + j] = expf(sel[j] - mx) / sum;
+    }
+    if (e == 0 && t < T) {
+        if (scan) {
+            // a taken expert is marked by clearing its slot after the pass has recorded it
+            float *lg = logit + ts * e_pad;
+            for (int j = 0; j < k; ++j) {
+                int best = -1;
+                float bv = 0.0f;
+                for (int i = 0; i < E; ++i) {
+                    float v = lg[i];
+                    bool free_slot = !(__float_as_uint(v) == 0xFF800001u);  // marker, see below
+                    if (free_slot && (best < 0 || v > bv)) { best = i; bv = v; }
+                }
+                ids_out[(int64_t)t * k + j] = best;
+                sel[ts][j] = bv;
+                lg[best] = __uint_as_float(0xFF800001u);                    // a NaN pattern no fma chain of finite bf16 yields
+            }
+        }
+        float mx = sel[ts][0], sum = 0.0f;
+        for (int j = 0; j < k; ++j) sum += expf(sel[ts][j] - mx);
+        for (int j = 0; j < k; ++j) w_out[(int64_t)t * k + j] = expf(sel[ts][j] - mx) / sum;
     }
 }
 
@@ -289,8 +387,17 @@ int launch_router_topk(const uint16_t *x, const uint16_t *w_router, int32_t T, i
     if (T < 0 || d <= 0 || d % 8 || E < 1 || E > ROUTER_MAX_E || k < 1 || k > E || k > ROUTER_MAX_K) return PZL_EINVAL;
     if (T == 0) return PZL_OK;
     if (!x || !w_router || !ids_out || !w_out) return PZL_EINVAL;
-    hipLaunchKernelGGL(router_topk_kernel, dim3((unsigned)T), dim3(ROUTER_MAX_E), 0, st, x, w_router, d, E, k,
-                       ids_out, w_out);
+    int e_pad = 8;
+    while (e_pad < E) e_pad *= 2;
+    const int tpb = ROUTER_THREADS / e_pad;
+    const dim3 grid((unsigned)((T + tpb - 1) / tpb)), block(ROUTER_THREADS);
+    // chunks as long as two buffers of E rows allow (about 17-20 KiB each)
+    if (e_pad <= 64)
+        hipLaunchKernelGGL((router_topk_kernel<128, 64>), grid, block, 0, st, x, w_router, T, d, E, k, e_pad, ids_out, w_out);
+    else if (e_pad == 128)
+        hipLaunchKernelGGL((router_topk_kernel<64, 128>), grid, block, 0, st, x, w_router, T, d, E, k, e_pad, ids_out, w_out);
+    else
+        hipLaunchKernelGGL((router_topk_kernel<32, 256>), grid, block, 0, st, x, w_router, T, d, E, k, e_pad, ids_out, w_out);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) { set_hip_error(e); return PZL_EHIP; }
     return PZL_OK;

@@ -361,6 +361,31 @@ def test_many_experts_small_batch_hot_expert(oracle, binding):
         check(case, T, "many-hot", ids=ids, w=w, x=x)
 
 
+def test_router_topk_nonfinite_logits(oracle, binding):
+    """A token with a NaN logit and infinite ones, and a token with one infinite logit: the
+    chosen experts still equal the oracle's scan (nothing is larger than a NaN and a NaN is larger
+    than nothing); the other tokens are unaffected."""
+    T, d, E, k = 12, 256, 16, 3
+    g = torch.Generator().manual_seed(5)
+    x = torch.randn(T, d, generator=g).to(torch.bfloat16)
+    wr = (torch.randn(E, d, generator=g) * 0.05).to(torch.bfloat16)
+    # (a chain of finite inputs can overflow to +-inf but never yields a NaN: the product inside an
+    # fma is not rounded; so the NaN comes from an infinite input)
+    x[2, 0] = float("inf"); wr[0, 0] = 0.0               # token 2: expert 0 NaN (inf * 0), the others +-inf
+    bx, bw = 1.0e38, 1.0e36                              # bx * bw overflows fp32; N(0,1) * bw and bx * 0.05 do not
+    x[7, 3] = bx; wr[9, 3] = bw                          # token 7, expert 9: +inf; other tokens: large but finite
+    ids, w = binding.pzl_router_topk(x.cuda(), wr.cuda(), k)
+    torch.cuda.synchronize()
+    ids_ref, w_ref, logits = oracle.router_topk(x.view(torch.int16).numpy().view(np.uint16),
+                                                wr.view(torch.int16).numpy().view(np.uint16), k)
+    assert np.isnan(logits[2, 0]) and np.isinf(logits[2, 5]) and np.isinf(logits[7, 9]) and np.isfinite(logits[7, 0])
+    assert np.array_equal(ids.cpu().numpy(), ids_ref)
+    fin = np.isfinite(w_ref).all(axis=1)
+    assert fin.sum() >= T - 2
+    assert np.allclose(w.cpu().numpy()[fin], w_ref[fin], rtol=2e-6, atol=1e-9)
+    assert np.array_equal(np.isnan(w.cpu().numpy()), np.isnan(w_ref))
+
+
 def test_all_experts_unmerged(oracle, binding):
     """No pair at all: every routed expert dense (the degenerate end of the compression range)."""
     cfg = synth.LayerConfig("unmerged", 3, 128, 192, 2, (40,), seed=67, n_unmerged=3)
@@ -369,7 +394,8 @@ def test_all_experts_unmerged(oracle, binding):
         check(case, T, "all-unmerged")
 
 
-@pytest.mark.parametrize("T,d,E,k", [(1, 4096, 8, 2), (64, 4096, 8, 2), (300, 2048, 60, 4), (2048, 2048, 64, 6)])
+@pytest.mark.parametrize("T,d,E,k", [(1, 4096, 8, 2), (64, 4096, 8, 2), (300, 2048, 60, 4), (2048, 2048, 64, 6),
+                                     (5, 520, 3, 1), (37, 1032, 20, 5), (9, 264, 130, 7), (3, 136, 256, 64)])
 def test_router_topk(oracle, binding, T, d, E, k):
     """Router logits as one fp32 fma chain: expert ids must equal the oracle's exactly."""
     say("router T=%d d=%d E=%d k=%d" % (T, d, E, k))
