@@ -516,6 +516,8 @@ int pzl_moe_ffn_staged(const pzl_layer *L, const uint16_t *x, const int32_t *top
             if (ks < ksplit_shared) ksplit_shared = ks;
         }
     }
+    for (int s = 0; s < L->n_shared; ++s)                                          // no split without a k-block
+        if (ksplit_shared > L->shared_f[s] / TILE_COLS) ksplit_shared = L->shared_f[s] / TILE_COLS;
     // Shared experts of equal width go into one launch per stage (group index = expert), so that
     // the launch has enough workgroups; their H rows sit back to back, slot = N + s*T + t.
     auto launch_shared = [&]() -> int {
@@ -607,6 +609,7 @@ int pzl_moe_ffn_staged(const pzl_layer *L, const uint16_t *x, const int32_t *top
     int ksplit = mostly_tiled ? choose_tile_ksplit(N / TILE_MAX_TOKENS + L->n_experts / 2, N, L->d_model, L->d_ffn)
                            : choose_ksplit(groups_max > 0 ? groups_max : 1, L->d_model);
     if (L->pair_format == 1 && ksplit > L->d_ffn / 128) ksplit = L->d_ffn / 128;   // whole 128-column groups per split
+    if (ksplit > L->d_ffn / TILE_COLS) ksplit = L->d_ffn / TILE_COLS;              // no split without a k-block (tiny layers)
     const int64_t h_plane = (int64_t)N * L->d_ffn;
     // Routed experts come in two kinds that differ only in the decode: packed pairs (groups
     // [0, P)) and experts kept unmerged (dense bf16, groups [P, P + D), position 0 only).  Both

@@ -547,6 +547,9 @@ static int launch(const StreamGroupArgs &g, hipStream_t st)
 {
     if (g.n_groups <= 0) return PZL_OK;
     if (g.rows % TILE_ROWS || g.kdim % TILE_COLS || g.ksplit < 1) return PZL_EINVAL;
+    // every K split must hold at least one k-block: the kernel clamps its read-ahead to the last
+    // k-block of its share, which an empty share does not have
+    if (g.ksplit > g.kdim / TILE_COLS) return PZL_EINVAL;
     if (QUANT && (g.kdim % 128 || !g.s_a || (STAGE == STAGE_GATEUP && !g.s_b))) return PZL_EINVAL;
     SgArgs a;
     a.w_a = g.w_a; a.w_b = g.w_b; a.rows = g.rows; a.kdim = g.kdim; a.ksplit = g.ksplit;

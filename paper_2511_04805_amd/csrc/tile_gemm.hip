@@ -519,6 +519,9 @@ static int launch(const TileGemmArgs &t, hipStream_t st)
 {
     if (t.max_mtiles <= 0) return PZL_OK;
     if (t.rows % TILE_ROWS || t.kdim % TILE_COLS) return PZL_EINVAL;
+    // every K split must hold at least one k-block: the kernel clamps its read-ahead to the last
+    // k-block of its share, which an empty share does not have
+    if (STAGE == TSTAGE_DOWN && t.ksplit > t.kdim / TILE_COLS) return PZL_EINVAL;
     TgArgs a;
     a.w_a = t.w_a; a.w_b = t.w_b; a.rows = t.rows; a.kdim = t.kdim;
     a.act = t.act; a.act_plane_stride = t.act_plane_stride; a.act_is_x = t.act_is_x;
