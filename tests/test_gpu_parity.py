@@ -386,6 +386,16 @@ def test_router_topk_nonfinite_logits(oracle, binding):
     assert np.array_equal(np.isnan(w.cpu().numpy()), np.isnan(w_ref))
 
 
+@pytest.mark.parametrize("T", [33, 80, 333])
+def test_short_contraction_dims(oracle, binding, T):
+    """d_ffn = 32 and shared widths of 96: the down stage contracts over 1 to 3 k-blocks, fewer
+    than the K splits that a launch of so few workgroups would otherwise get (no split may be left
+    without a k-block); d_model = 96 gives the gate/up stage an odd number of k-blocks."""
+    cfg = synth.LayerConfig("short_k", 6, 96, 32, 4, (80,), shared_d_ffn=(96, 96), routing="zipf", seed=83)
+    case = Case(cfg, oracle, binding)
+    check(case, T, "short-k")
+
+
 def test_all_experts_unmerged(oracle, binding):
     """No pair at all: every routed expert dense (the degenerate end of the compression range)."""
     cfg = synth.LayerConfig("unmerged", 3, 128, 192, 2, (40,), seed=67, n_unmerged=3)
