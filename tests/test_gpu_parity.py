@@ -128,6 +128,13 @@ def test_edge_cases(small_case, binding):
     w3 = w.copy(); w3[::3, 1] = 0; w3[1::3, 1] = 0
     y64, _ = case.ref(x, np.where((ids3 < 0) | (ids3 >= cfg.n_experts), 0, ids3).astype(np.int32), w3)
     assert tolerance_ok(y, y64)[0]
+    # k = 0: no routed expert at all, y is the sum of the shared experts
+    ids4 = np.zeros((T, 0), dtype=np.int32); w4 = np.zeros((T, 0), dtype=np.float32)
+    y = case.layer.pzl_moe_ffn(torch.from_numpy(x.view(np.int16)).cuda(), torch.from_numpy(ids4).cuda(),
+                               torch.from_numpy(w4).cuda())
+    torch.cuda.synchronize()
+    y64, _ = case.ref(x, ids4, w4)
+    assert np.abs(y64).max() > 0 and tolerance_ok(y.view(torch.int16).cpu().numpy().view(np.uint16), y64)[0]
     # T = 0 is a no-op, and results are reproducible bit for bit
     empty = case.layer.pzl_moe_ffn(torch.empty(0, cfg.d_model, dtype=torch.bfloat16, device="cuda"),
                                    torch.empty(0, 2, dtype=torch.int32, device="cuda"),
