@@ -160,6 +160,41 @@ typedef struct pzl_layer pzl_layer;
 int pzl_layer_create(const pzl_layer_desc *desc, pzl_layer **out);
 void pzl_layer_destroy(pzl_layer *layer);
 
+/*
+ * moe_ffn_plan — what pzl_moe_ffn decides on the host for a layer of this shape and a batch of T
+ * tokens with k choices each (the decode-GEMM of Sec. 3.3.2 runs as weight-streaming kernels for
+ * small batches and as tiled matrix-core kernels for large ones; the host knows the batch shape,
+ * the device the routing).  Pure host arithmetic: no layer, no device and no stream is needed, so
+ * a caller can inspect, and a test can check, the launch plan of any shape.  Host pointers.
+ */
+typedef struct pzl_layer_shape {
+    int32_t n_experts;            /* routed experts, 1..256 */
+    int32_t n_unmerged;           /* of which kept unmerged (n_experts - n_unmerged is even) */
+    int32_t d_model, d_ffn;       /* multiples of 32 */
+    int32_t n_shared;             /* 0..16 */
+    const int32_t *shared_d_ffn;  /* [n_shared] multiples of 32 */
+    int32_t pair_format;          /* 0: 16-bit packed words, 1: quantised records */
+} pzl_layer_shape;
+
+typedef struct pzl_plan {
+    int32_t shared_stream;        /* shared experts run on the layer's second stream */
+    int32_t hybrid;               /* tiled kernels are launched next to the streaming ones */
+    int32_t tile_min;             /* hybrid: a pair with an expert of this many tokens is tiled; else 0 */
+    int32_t persistent;           /* the routed tiled launches draw their tiles (256 workgroups) */
+    int32_t tile_stream;          /* ... and run on the layer's third stream */
+    int32_t ksplit;               /* K splits of the routed down stage (partial sums per slot) */
+    int32_t ksplit_shared;        /* ... of the shared experts' down stage */
+    int32_t tiled_shared;         /* shared experts run on the tiled kernels */
+    int32_t sweep_wgs_packed;     /* streaming kernels: workgroups per (pair, row block) sharing its sweeps */
+    int32_t sweep_wgs_unmerged;   /* ... per unmerged expert */
+    int32_t shared_token_tiles[16];   /* tiled_shared: token tiles per shared expert ... */
+    int32_t shared_tile_tokens[16];   /* ... and tokens per tile (a multiple of 16, at most 288) */
+} pzl_plan;
+
+/* Returns PZL_OK, or PZL_EINVAL for a null pointer, a negative T or k, or a shape that
+ * pzl_layer_create would reject. */
+int pzl_moe_ffn_plan(const pzl_layer_shape *shape, int32_t T, int32_t k, pzl_plan *out);
+
 /* Bytes of workspace pzl_moe_ffn needs for any T <= max_tokens at this top_k (0 on bad
  * arguments).  The workspace must be 256-byte aligned device memory. */
 size_t pzl_moe_ffn_workspace_bytes(const pzl_layer *layer, int32_t max_tokens, int32_t top_k);

@@ -19,9 +19,22 @@ PZL_OK, PZL_EINVAL, PZL_ENOSPC, PZL_EHIP, PZL_ENOMEM = 0, -1, -2, -3, -4
 EXPORTS = ("pzl_abi_version", "pzl_strerror", "pzl_last_hip_error", "pzl_packed_bytes", "pzl_pack",
            "pzl_unpack", "pzl_tile_dense", "pzl_merge_pack", "pzl_router_topk",
            "pzl_q_record_bytes", "pzl_q_scale_bytes", "pzl_q_pack", "pzl_q_unpack", "pzl_layer_create", "pzl_layer_destroy",
-           "pzl_moe_ffn_workspace_bytes", "pzl_moe_ffn", "pzl_moe_ffn_staged")
+           "pzl_moe_ffn_plan", "pzl_moe_ffn_workspace_bytes", "pzl_moe_ffn", "pzl_moe_ffn_staged")
 
 STAGES = ("route", "gateup", "down", "shared", "combine")
+
+
+class _LayerShape(ctypes.Structure):
+    _fields_ = [("n_experts", ctypes.c_int32), ("n_unmerged", ctypes.c_int32), ("d_model", ctypes.c_int32),
+                ("d_ffn", ctypes.c_int32), ("n_shared", ctypes.c_int32),
+                ("shared_d_ffn", ctypes.POINTER(ctypes.c_int32)), ("pair_format", ctypes.c_int32)]
+
+
+class _Plan(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("shared_stream", "hybrid", "tile_min", "persistent", "tile_stream",
+                                              "ksplit", "ksplit_shared", "tiled_shared", "sweep_wgs_packed",
+                                              "sweep_wgs_unmerged")] + \
+               [("shared_token_tiles", ctypes.c_int32 * 16), ("shared_tile_tokens", ctypes.c_int32 * 16)]
 
 
 class PzlError(RuntimeError):
@@ -76,6 +89,8 @@ def load():
         lib.pzl_layer_create.argtypes = [ctypes.POINTER(_LayerDesc), ctypes.POINTER(vp)]
         lib.pzl_layer_destroy.restype = None
         lib.pzl_layer_destroy.argtypes = [vp]
+        lib.pzl_moe_ffn_plan.restype = ctypes.c_int
+        lib.pzl_moe_ffn_plan.argtypes = [ctypes.POINTER(_LayerShape), i32, i32, ctypes.POINTER(_Plan)]
         lib.pzl_moe_ffn_workspace_bytes.restype = ctypes.c_size_t
         lib.pzl_moe_ffn_workspace_bytes.argtypes = [vp, i32, i32]
         lib.pzl_moe_ffn.restype = ctypes.c_int
@@ -219,6 +234,19 @@ def pzl_merge_pack(w_i, w_j, norm_i, norm_j, tau_sim, out=None, n_similar=None, 
                                rows, cols, ctypes.c_float(tau_sim), _dev(out, _BITS16, "out"),
                                opt(n_similar, "n_similar"), opt(n_out_of_range, "n_out_of_range"), _stream())
     _check(rc, "pzl_merge_pack")
+    return out
+
+
+def pzl_moe_ffn_plan(n_experts, d_model, d_ffn, T, k, shared_d_ffn=(), n_unmerged=0, quantised=False):
+    """The host-side launch plan of pzl_moe_ffn for this layer and batch shape (no GPU needed) as a dict."""
+    sf = (ctypes.c_int32 * max(len(shared_d_ffn), 1))(*shared_d_ffn)
+    shape = _LayerShape(int(n_experts), int(n_unmerged), int(d_model), int(d_ffn), len(shared_d_ffn),
+                        ctypes.cast(sf, ctypes.POINTER(ctypes.c_int32)), 1 if quantised else 0)
+    plan = _Plan()
+    _check(load().pzl_moe_ffn_plan(ctypes.byref(shape), int(T), int(k), ctypes.byref(plan)), "pzl_moe_ffn_plan")
+    out = {n: int(getattr(plan, n)) for n, _ in _Plan._fields_[:10]}
+    out["shared_token_tiles"] = list(plan.shared_token_tiles)[:len(shared_d_ffn)]
+    out["shared_tile_tokens"] = list(plan.shared_tile_tokens)[:len(shared_d_ffn)]
     return out
 
 

@@ -202,6 +202,60 @@ static int choose_ksplit(int groups_touched_max, int rows)
     return ks;
 }
 
+// The host-side decisions of one pzl_moe_ffn call; they depend on the layer's shape and on the
+// batch shape only (the routing is known to the device alone).  The reasons and the measurements
+// behind each rule stand where pzl_moe_ffn uses it.
+struct Plan {
+    bool overlap;          // shared experts on the layer's second stream
+    bool hybrid;           // tiled kernels launched next to the streaming ones; the grouping kernel picks per pair
+    bool mostly_tiled;     // the K split of the routed down stage is sized for the tiled kernels
+    bool tiled_shared;     // shared experts on the tiled kernels
+    bool persistent;       // tiled launches of the routed experts draw their tiles
+    bool tile_overlap;     // ... and run on the layer's third stream
+    int tile_min;          // tokens of an expert from which its pair is tiled
+    int ksplit, ksplit_shared;
+    int shared_wgs;        // workgroups aimed at for the shared experts' tiled gate/up launch
+};
+
+static Plan make_plan(const pzl_layer *L, int32_t T, int32_t k, bool staged)
+{
+    Plan pl;
+    const int64_t N = (int64_t)T * k;
+    const int64_t E64 = L->n_experts;
+    pl.overlap = L->n_shared > 0 && !staged && N > 0;
+    pl.hybrid = L->pair_format == 0 &&
+        N >= (int64_t)(E64 >= 32 ? HYBRID_MIN_TOKENS_PER_EXPERT_MANY : HYBRID_MIN_TOKENS_PER_EXPERT) * E64;
+    pl.tile_min = pl.hybrid ? HYBRID_TILE_MIN_TOKENS : 0x7FFFFFFF;
+    pl.mostly_tiled = pl.hybrid && N >= (int64_t)TILED_MIN_TOKENS_PER_EXPERT * E64;
+    pl.tiled_shared = T >= TILED_MIN_TOKENS_SHARED;
+    pl.persistent = L->n_q >= 32 && N <= (int64_t)256 * L->n_q;
+    pl.tile_overlap = pl.hybrid && !staged && E64 >= 32 && N < 32 * E64;
+
+    const int ns = L->n_shared > 0 ? L->n_shared : 1;
+    pl.shared_wgs = shared_target_wgs(L, k, pl.hybrid && pl.persistent);
+    int ksplit_shared = choose_ksplit(ns * ((T + 63) / 64), L->d_model);
+    if (pl.tiled_shared) {
+        ksplit_shared = MAX_KSPLIT;
+        for (int s = 0; s < L->n_shared; ++s) {
+            int ks = choose_tile_ksplit((int64_t)ns * shared_token_parts(T, ns, L->shared_f[s], pl.shared_wgs), (int64_t)ns * T,
+                                        L->d_model, L->shared_f[s]);
+            if (ks < ksplit_shared) ksplit_shared = ks;
+        }
+    }
+    for (int s = 0; s < L->n_shared; ++s)                                          // no split without a k-block
+        if (ksplit_shared > L->shared_f[s] / TILE_COLS) ksplit_shared = L->shared_f[s] / TILE_COLS;
+    pl.ksplit_shared = ksplit_shared;
+
+    const int routed_groups = L->n_pairs + L->n_dense;
+    const int groups_max = (int)(N < routed_groups ? N : routed_groups);           // groups that can have tokens
+    int ksplit = pl.mostly_tiled ? choose_tile_ksplit(N / TILE_MAX_TOKENS + L->n_experts / 2, N, L->d_model, L->d_ffn)
+                                 : choose_ksplit(groups_max > 0 ? groups_max : 1, L->d_model);
+    if (L->pair_format == 1 && ksplit > L->d_ffn / 128) ksplit = L->d_ffn / 128;   // whole 128-column groups per split
+    if (ksplit > L->d_ffn / TILE_COLS) ksplit = L->d_ffn / TILE_COLS;              // no split without a k-block (tiny layers)
+    pl.ksplit = ksplit;
+    return pl;
+}
+
 }  // namespace pzl
 
 using namespace pzl;
@@ -417,6 +471,42 @@ static bool batch_fits(const pzl_layer *L, int64_t T, int64_t k)
     return true;
 }
 
+int pzl_moe_ffn_plan(const pzl_layer_shape *shape, int32_t T, int32_t k, pzl_plan *out)
+{
+    if (!shape || !out || T < 0 || k < 0) return PZL_EINVAL;
+    const int E = shape->n_experts, D = shape->n_unmerged, S = shape->n_shared;
+    if (E < 1 || E > 256 || D < 0 || D > E || ((E - D) & 1) || shape->d_model <= 0 || shape->d_ffn <= 0 ||
+        shape->d_model % TILE_COLS || shape->d_ffn % TILE_COLS || S < 0 || S > 16 || (S > 0 && !shape->shared_d_ffn) ||
+        (shape->pair_format != 0 && shape->pair_format != 1))
+        return PZL_EINVAL;
+    for (int s = 0; s < S; ++s)
+        if (shape->shared_d_ffn[s] <= 0 || shape->shared_d_ffn[s] % TILE_COLS) return PZL_EINVAL;
+    pzl_layer L = {};                                        // the host fields only: make_plan reads nothing else
+    L.n_experts = E; L.n_dense = D; L.n_pairs = (E - D) / 2; L.n_q = 2 * (L.n_pairs + D);
+    L.d_model = shape->d_model; L.d_ffn = shape->d_ffn; L.n_shared = S; L.pair_format = shape->pair_format;
+    L.shared_f.assign(shape->shared_d_ffn, shape->shared_d_ffn + S);
+    const Plan pl = make_plan(&L, T, k, false);
+    *out = pzl_plan{};
+    out->shared_stream = pl.overlap; out->hybrid = pl.hybrid; out->tile_min = pl.hybrid ? pl.tile_min : 0;
+    out->persistent = pl.hybrid && pl.persistent; out->tile_stream = pl.tile_overlap;
+    out->ksplit = pl.ksplit; out->ksplit_shared = S > 0 ? pl.ksplit_shared : 0; out->tiled_shared = S > 0 && pl.tiled_shared;
+    out->sweep_wgs_packed = stream_pass_wgs(T, L.pair_format == 1 ? KIND_QUANT : KIND_PACKED, pl.tile_min);
+    out->sweep_wgs_unmerged = stream_pass_wgs(T, KIND_UNMERGED, pl.tile_min);
+    for (int s = 0; s < S;) {                                // experts of equal width share a launch
+        int nb = 1;
+        while (s + nb < S && L.shared_f[s + nb] == L.shared_f[s]) ++nb;
+        int tiles = 0, tokens = 0;
+        if (pl.tiled_shared) {
+            const int parts = shared_token_parts(T, nb, L.shared_f[s], pl.shared_wgs);
+            tokens = ((T + parts - 1) / parts + 15) & ~15;
+            tiles = (T + tokens - 1) / tokens;
+        }
+        for (int j = 0; j < nb; ++j) { out->shared_token_tiles[s + j] = tiles; out->shared_tile_tokens[s + j] = tokens; }
+        s += nb;
+    }
+    return PZL_OK;
+}
+
 size_t pzl_moe_ffn_workspace_bytes(const pzl_layer *layer, int32_t max_tokens, int32_t top_k)
 {
     if (!layer || max_tokens < 0 || top_k < 0) return 0;
@@ -454,7 +544,8 @@ int pzl_moe_ffn_staged(const pzl_layer *L, const uint16_t *x, const int32_t *top
     const int32_t N = T * k;
     // Shared experts on the layer's second stream, unless the caller times stages (then every
     // stage runs alone on the caller's stream) or there is nothing to run next to.
-    const bool overlap = L->n_shared > 0 && !stage_events && N > 0;
+    const Plan pl = make_plan(L, T, k, stage_events != nullptr);
+    const bool overlap = pl.overlap;
     hipStream_t sst = overlap ? L->aux_stream : st;
     if (overlap) {
         hipError_t e = hipEventRecord(L->ev_fork, st);
@@ -489,35 +580,20 @@ int pzl_moe_ffn_staged(const pzl_layer *L, const uint16_t *x, const int32_t *top
     // 10-20 us (60 experts, top-4, even routing, 128-192 tokens: 155-171 -> 178-182 us).  With
     // few experts the counts stay near their average.
     // (quantised pairs have no tiled kernel: they always stream)
-    const int64_t E64 = L->n_experts;
-    const bool hybrid = L->pair_format == 0 &&
-        (int64_t)N >= (int64_t)(E64 >= 32 ? HYBRID_MIN_TOKENS_PER_EXPERT_MANY : HYBRID_MIN_TOKENS_PER_EXPERT) * E64;
-    const int tile_min = hybrid ? HYBRID_TILE_MIN_TOKENS : 0x7FFFFFFF;
-    const bool tiled = hybrid, streamed = true;
-    const bool mostly_tiled = hybrid && (int64_t)N >= (int64_t)TILED_MIN_TOKENS_PER_EXPERT * E64;
-    const bool tiled_shared = T >= TILED_MIN_TOKENS_SHARED;
+    const int tile_min = pl.tile_min;
+    const bool tiled = pl.hybrid, streamed = true;
+    const bool tiled_shared = pl.tiled_shared;
 
     // Many experts with at most about one full tile each: the tile list is far shorter than its
     // bound and its tiles are uneven, so the tiled launches are persistent and draw their tiles
     // (counters zeroed by the grouping kernel).  Otherwise one workgroup per tile of the bound.
     // Measured (whole step, persistent vs not): 64 experts top-6 at 512-2048 tokens -9 %, at 4096
     // +4 %; 60 experts top-4 at 2048 -3 %, at 4096 +3 %; 8 experts top-2 at 2048-4096 +5-7 %.
-    const bool persistent = L->n_q >= 32 && (int64_t)N <= (int64_t)256 * L->n_q;
+    const bool persistent = pl.persistent;
     // one k-split count for all shared experts (the combine step sums that many partials); sized
     // for the usual case, all of them of one width and hence in one launch per stage
-    const int ns = L->n_shared > 0 ? L->n_shared : 1;
-    const int shared_wgs = shared_target_wgs(L, k, tiled && persistent);
-    int ksplit_shared = choose_ksplit(ns * ((T + 63) / 64), L->d_model);
-    if (tiled_shared) {
-        ksplit_shared = MAX_KSPLIT;
-        for (int s = 0; s < L->n_shared; ++s) {
-            int ks = choose_tile_ksplit((int64_t)ns * shared_token_parts(T, ns, L->shared_f[s], shared_wgs), (int64_t)ns * T,
-                                        L->d_model, L->shared_f[s]);
-            if (ks < ksplit_shared) ksplit_shared = ks;
-        }
-    }
-    for (int s = 0; s < L->n_shared; ++s)                                          // no split without a k-block
-        if (ksplit_shared > L->shared_f[s] / TILE_COLS) ksplit_shared = L->shared_f[s] / TILE_COLS;
+    const int shared_wgs = pl.shared_wgs;
+    const int ksplit_shared = pl.ksplit_shared;
     // Shared experts of equal width go into one launch per stage (group index = expert), so that
     // the launch has enough workgroups; their H rows sit back to back, slot = N + s*T + t.
     auto launch_shared = [&]() -> int {
@@ -595,7 +671,7 @@ int pzl_moe_ffn_staged(const pzl_layer *L, const uint16_t *x, const int32_t *top
     // 128-256 tokens: -12..-15 %).  The two cross-stream waits cost 5-10 us, so only where a
     // mixture is likely: many experts and fewer than 32 tokens per expert on average (beyond
     // that nearly every pair is tiled); and not when the caller times stages.
-    const bool tile_overlap = tiled && !stage_events && E64 >= 32 && (int64_t)N < 32 * E64;
+    const bool tile_overlap = pl.tile_overlap;
     hipStream_t tst = tile_overlap ? L->tile_stream : st;
     if (tile_overlap) {
         hipError_t e = hipEventRecord(L->ev_tfork, st);
@@ -603,13 +679,8 @@ int pzl_moe_ffn_staged(const pzl_layer *L, const uint16_t *x, const int32_t *top
         if (e != hipSuccess) { set_hip_error(e); return PZL_EHIP; }
     }
 
-    const int routed_groups = L->n_pairs + L->n_dense;
-    const int groups_max = (int)((int64_t)N < routed_groups ? N : routed_groups);   // groups that can have tokens
     // one k-split count for all routed slots (the combine step sums that many partials)
-    int ksplit = mostly_tiled ? choose_tile_ksplit(N / TILE_MAX_TOKENS + L->n_experts / 2, N, L->d_model, L->d_ffn)
-                           : choose_ksplit(groups_max > 0 ? groups_max : 1, L->d_model);
-    if (L->pair_format == 1 && ksplit > L->d_ffn / 128) ksplit = L->d_ffn / 128;   // whole 128-column groups per split
-    if (ksplit > L->d_ffn / TILE_COLS) ksplit = L->d_ffn / TILE_COLS;              // no split without a k-block (tiny layers)
+    const int ksplit = pl.ksplit;
     const int64_t h_plane = (int64_t)N * L->d_ffn;
     // Routed experts come in two kinds that differ only in the decode: packed pairs (groups
     // [0, P)) and experts kept unmerged (dense bf16, groups [P, P + D), position 0 only).  Both
