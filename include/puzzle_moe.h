@@ -43,7 +43,7 @@
 extern "C" {
 #endif
 
-#define PZL_ABI_VERSION 3
+#define PZL_ABI_VERSION 4
 
 #define PZL_OK       0
 #define PZL_EINVAL  -1   /* null pointer, bad shape, position not 0/1, pair map not a 2-to-1 cover */
