@@ -18,3 +18,14 @@ def test_header_symbols_are_exported():
     assert lib.pzl_abi_version() == 4
     assert lib.pzl_packed_bytes(14336, 4096) == 14336 * 4096 * 2
     assert lib.pzl_strerror(0) == b"ok" and b"workspace" in lib.pzl_strerror(binding.PZL_ENOSPC)
+
+
+def test_missing_library_fails_loudly(monkeypatch, tmp_path):
+    """There is no CPU fallback: without the built library the binding raises, it never computes."""
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "LIB_PATH", str(tmp_path / "libpuzzle_moe.so"))
+    import pytest
+    with pytest.raises(RuntimeError, match="not built"):
+        binding.load()
+    with pytest.raises(RuntimeError, match="not built"):
+        binding.pzl_moe_ffn_plan(8, 128, 256, 4, 2)
