@@ -236,6 +236,9 @@ def main():
     }
     path_bytes = n_touched * 3 * f * d * 2
     out["path_hbm_frac"] = path_bytes / (ms_step * 1e-3) / 1e9 / HBM_PEAK_GBS
+    # the on-device router in front of the layer, on its own (not part of the timed step: ids and
+    # weights are inputs of the path)
+    out["router_ms"] = time_router(hip, cfg, xt)
 
     if not args.no_sweep:
         sweep = {}
