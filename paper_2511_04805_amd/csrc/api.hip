@@ -55,6 +55,9 @@ namespace pzl {
 #ifndef PZL_SHARED_TILE_MIN_TOKENS
 #define PZL_SHARED_TILE_MIN_TOKENS 48
 #endif
+#ifndef PZL_SHARED_TILE_MIN_TOKENS_IDLE
+#define PZL_SHARED_TILE_MIN_TOKENS_IDLE 40
+#endif
 constexpr int TILED_MIN_TOKENS_PER_EXPERT = PZL_TILED_MIN_TPE;   // average tokens per expert from which the K split is sized for the tiled kernels
 #ifndef PZL_HYBRID_MIN_TPE
 #define PZL_HYBRID_MIN_TPE 20
@@ -149,12 +152,15 @@ static int choose_tile_ksplit(int64_t token_tiles, int64_t slots, int rows, int 
 // 64 -> 166; 512 tokens: 288 -> 271, 192 -> 252, 128 -> 237, 96 -> 267, 64 -> 254; 768 tokens:
 // 288 -> 291, 192 -> 273, 128 -> 303; from 1024 tokens 288 is best (176 workgroups or more).
 // 64 experts top-6 + 2 shared experts of 1408 (22 per token tile): within 2 % from 64 to 288.
-static int shared_token_parts(int32_t T, int n_same, int f, int target_wgs)
+static int shared_token_parts(int32_t T, int n_same, int f, int target_wgs, bool chip_busy)
 {
     int parts = (T + TILE_MAX_TOKENS - 1) / TILE_MAX_TOKENS;
     const int per_part = n_same * ((f + 127) / 128);              // gate/up workgroups per token tile
     int want = (target_wgs + per_part / 2) / per_part;
-    const int most = T / PZL_SHARED_TILE_MIN_TOKENS;
+    // at least 48 tokens per tile; 40 (rounded up to 48 by the fragment size) next to routed
+    // kernels that leave compute units idle, which lets 80-95 tokens be two tiles (60 experts +
+    // 1 shared expert, 80 / 88 tokens: 149 / 153 -> 141 / 142 us)
+    const int most = T / (chip_busy ? PZL_SHARED_TILE_MIN_TOKENS : PZL_SHARED_TILE_MIN_TOKENS_IDLE);
     if (want > most) want = most;
     return want > parts ? want : parts;
 }
@@ -237,7 +243,7 @@ static Plan make_plan(const pzl_layer *L, int32_t T, int32_t k, bool staged)
     if (pl.tiled_shared) {
         ksplit_shared = MAX_KSPLIT;
         for (int s = 0; s < L->n_shared; ++s) {
-            int ks = choose_tile_ksplit((int64_t)ns * shared_token_parts(T, ns, L->shared_f[s], pl.shared_wgs), (int64_t)ns * T,
+            int ks = choose_tile_ksplit((int64_t)ns * shared_token_parts(T, ns, L->shared_f[s], pl.shared_wgs, pl.hybrid && pl.persistent), (int64_t)ns * T,
                                         L->d_model, L->shared_f[s]);
             if (ks < ksplit_shared) ksplit_shared = ks;
         }
@@ -497,7 +503,7 @@ int pzl_moe_ffn_plan(const pzl_layer_shape *shape, int32_t T, int32_t k, pzl_pla
         while (s + nb < S && L.shared_f[s + nb] == L.shared_f[s]) ++nb;
         int tiles = 0, tokens = 0;
         if (pl.tiled_shared) {
-            const int parts = shared_token_parts(T, nb, L.shared_f[s], pl.shared_wgs);
+            const int parts = shared_token_parts(T, nb, L.shared_f[s], pl.shared_wgs, pl.hybrid && pl.persistent);
             tokens = ((T + parts - 1) / parts + 15) & ~15;
             tiles = (T + tokens - 1) / tokens;
         }
@@ -608,7 +614,7 @@ int pzl_moe_ffn_staged(const pzl_layer *L, const uint16_t *x, const int32_t *top
             const int64_t hs_plane = (int64_t)nb * T * L->shared_f[s];
             if (tiled_shared) {
                 TileGemmArgs a = {};
-                const int parts = shared_token_parts(T, nb, L->shared_f[s], shared_wgs);
+                const int parts = shared_token_parts(T, nb, L->shared_f[s], shared_wgs, pl.hybrid && pl.persistent);
                 a.dense_tokens = T; a.dense_slot_base = slot_base;
                 a.dense_tile_tokens = ((T + parts - 1) / parts + 15) & ~15;
                 a.dense_tiles = nb * ((T + a.dense_tile_tokens - 1) / a.dense_tile_tokens);
