@@ -56,7 +56,7 @@ namespace pzl {
 #define PZL_SHARED_TILE_MIN_TOKENS 48
 #endif
 #ifndef PZL_SHARED_TILE_MIN_TOKENS_IDLE
-#define PZL_SHARED_TILE_MIN_TOKENS_IDLE 40
+#define PZL_SHARED_TILE_MIN_TOKENS_IDLE 36
 #endif
 constexpr int TILED_MIN_TOKENS_PER_EXPERT = PZL_TILED_MIN_TPE;   // average tokens per expert from which the K split is sized for the tiled kernels
 #ifndef PZL_HYBRID_MIN_TPE
@@ -157,9 +157,9 @@ static int shared_token_parts(int32_t T, int n_same, int f, int target_wgs, bool
     int parts = (T + TILE_MAX_TOKENS - 1) / TILE_MAX_TOKENS;
     const int per_part = n_same * ((f + 127) / 128);              // gate/up workgroups per token tile
     int want = (target_wgs + per_part / 2) / per_part;
-    // at least 48 tokens per tile; 40 (rounded up to 48 by the fragment size) next to routed
-    // kernels that leave compute units idle, which lets 80-95 tokens be two tiles (60 experts +
-    // 1 shared expert, 80 / 88 tokens: 149 / 153 -> 141 / 142 us)
+    // at least 48 tokens per tile; 36 (rounded up to 48 by the fragment size) next to routed
+    // kernels that leave compute units idle, which lets 72-95 tokens be two tiles (60 experts +
+    // 1 shared expert, 72 / 80 / 88 tokens: 147 / 149 / 153 -> 141 / 142 / 142 us)
     const int most = T / (chip_busy ? PZL_SHARED_TILE_MIN_TOKENS : PZL_SHARED_TILE_MIN_TOKENS_IDLE);
     if (want > most) want = most;
     return want > parts ? want : parts;
