@@ -63,7 +63,7 @@ constexpr int TILED_MIN_TOKENS_PER_EXPERT = PZL_TILED_MIN_TPE;   // average toke
 #define PZL_HYBRID_MIN_TPE 20
 #endif
 #ifndef PZL_HYBRID_MIN_TPE_MANY
-#define PZL_HYBRID_MIN_TPE_MANY 8
+#define PZL_HYBRID_MIN_TPE_MANY 6
 #endif
 #ifndef PZL_HYBRID_TILE_MIN
 #define PZL_HYBRID_TILE_MIN 33
@@ -584,7 +584,9 @@ int pzl_moe_ffn_staged(const pzl_layer *L, const uint16_t *x, const int32_t *top
     // long before the average says so (64 experts, top-6, skewed: 96-192 tokens 272-464 us
     // streamed, 201-246 us with the busy pairs tiled), while two launches that find no tile cost
     // 10-20 us (60 experts, top-4, even routing, 128-192 tokens: 155-171 -> 178-182 us).  With
-    // few experts the counts stay near their average.
+    // few experts the counts stay near their average.  (6 rather than 8 slots per expert: with
+    // the tiled launches on their own stream an even router pays 3-4 % between the two, 60 experts
+    // top-4 at 96-112 tokens, a skewed one gains 3-12 %, 64 experts top-6 at 64-80 tokens.)
     // (quantised pairs have no tiled kernel: they always stream)
     const int tile_min = pl.tile_min;
     const bool tiled = pl.hybrid, streamed = true;

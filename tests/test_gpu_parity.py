@@ -344,18 +344,18 @@ def test_many_experts_mixed_layer_persistent_launches(oracle, binding):
 
 
 def test_many_experts_small_batch_hot_expert(oracle, binding):
-    """Small batches of a 40-expert layer (fewer than 8 slots per expert on average: streaming
+    """Small batches of a 64-expert layer (fewer than 6 slots per expert on average: streaming
     kernels only) in which every token picks the same first expert: its pair needs 2 to 4 sweeps of
     32 tokens, which the launch spreads over 2 or 3 workgroups per row block (the first of them
     takes sweeps 0 and 3 at 100 tokens), next to pairs and unmerged experts with one sweep or none."""
-    cfg = synth.LayerConfig("many_hot", 40, 128, 384, 3, (100,), shared_d_ffn=(128,), routing="zipf",
+    cfg = synth.LayerConfig("many_hot", 64, 128, 384, 3, (100,), shared_d_ffn=(128,), routing="zipf",
                             seed=73, n_unmerged=8)
     case = Case(cfg, oracle, binding, emap_mode="random")
     pair = np.asarray(case.emap[0])
     hot_packed = int(np.where(pair >= 0)[0][0])
     hot_dense = int(np.where(pair < 0)[0][0])
     for T, hot in ((48, hot_packed), (100, hot_packed), (100, hot_dense)):
-        assert T * cfg.top_k < 8 * cfg.n_experts
+        assert T * cfg.top_k < 6 * cfg.n_experts
         x = synth.tokens(cfg, T)
         ids, w = synth.routing(cfg, T)
         for t in range(T):                              # the hot expert first, the others kept distinct from it

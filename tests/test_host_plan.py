@@ -40,8 +40,8 @@ def test_plan_invariants(shape):
             assert 1 <= p["ksplit_shared"] <= min(8, min(shared) // 32), (T, p)
         # quantised layers have no tiled kernels
         assert not (quant and p["hybrid"])
-        # both paths from 20 slots per expert on average (8 with 32 experts or more)
-        assert bool(p["hybrid"]) == (not quant and N >= (8 if E >= 32 else 20) * E), (T, p)
+        # both paths from 20 slots per expert on average (6 with 32 experts or more)
+        assert bool(p["hybrid"]) == (not quant and N >= (6 if E >= 32 else 20) * E), (T, p)
         assert p["tile_min"] == (33 if p["hybrid"] else 0)
         # persistent launches and the tile stream only where tiled kernels are launched
         assert not (p["persistent"] and not p["hybrid"]) and not (p["tile_stream"] and not p["hybrid"])
