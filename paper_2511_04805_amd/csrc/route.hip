@@ -464,8 +464,13 @@ int launch_router_topk(const uint16_t *x, const uint16_t *w_router, int32_t T, i
     }
     const int tpb = ROUTER_THREADS / e_pad;
     const dim3 grid((unsigned)((T + tpb - 1) / tpb)), block(ROUTER_THREADS);
-    // chunks as long as two buffers of E rows allow (about 17-20 KiB each)
-    if (e_pad <= 64)
+    // chunks as long as two buffers of E rows allow (about 17-20 KiB each); with more than two
+    // workgroups per compute unit shorter chunks, whose registers let four workgroups share one
+    // (64 experts, d = 2048: 2048 tokens 46 us with 128 channels per chunk / 47 with 64, 4096
+    // tokens 88 / 71)
+    if (e_pad <= 64 && grid.x > 512)
+        hipLaunchKernelGGL((router_topk_kernel<64, 64>), grid, block, 0, st, x, w_router, T, d, E, k, e_pad, ids_out, w_out);
+    else if (e_pad <= 64)
         hipLaunchKernelGGL((router_topk_kernel<128, 64>), grid, block, 0, st, x, w_router, T, d, E, k, e_pad, ids_out, w_out);
     else if (e_pad == 128)
         hipLaunchKernelGGL((router_topk_kernel<64, 128>), grid, block, 0, st, x, w_router, T, d, E, k, e_pad, ids_out, w_out);

@@ -412,7 +412,8 @@ def test_all_experts_unmerged(oracle, binding):
 
 
 @pytest.mark.parametrize("T,d,E,k", [(1, 4096, 8, 2), (64, 4096, 8, 2), (300, 2048, 60, 4), (2048, 2048, 64, 6),
-                                     (5, 520, 3, 1), (37, 1032, 20, 5), (9, 264, 130, 7), (3, 136, 256, 64)])
+                                     (5, 520, 3, 1), (37, 1032, 20, 5), (9, 264, 130, 7), (3, 136, 256, 64),
+                                     (2100, 264, 33, 3)])
 def test_router_topk(oracle, binding, T, d, E, k):
     """Router logits as one fp32 fma chain: expert ids must equal the oracle's exactly."""
     say("router T=%d d=%d E=%d k=%d" % (T, d, E, k))
