@@ -120,7 +120,7 @@ static WorkspaceLayout carve(const pzl_layer *L, int32_t T, int32_t k)
 // split lost 3-10 %).  Constants: 1.8 us per K step for a full 288-token tile, about half of
 // that for a nearly empty one, 10 us of prologue and epilogue, 5 TB/s for the partial sums; only
 // their ratios matter.
-static int choose_tile_ksplit(int64_t token_tiles, int64_t slots, int rows, int kdim)
+static int choose_tile_ksplit(int64_t token_tiles, int64_t slots, int rows, int kdim, int min_steps = 8)
 {
     if (token_tiles < 1) token_tiles = 1;
     const double wgs = (double)token_tiles * ((rows + 255) / 256);
@@ -132,7 +132,7 @@ static int choose_tile_ksplit(int64_t token_tiles, int64_t slots, int rows, int 
     int best = 1;
     double best_us = 0.0;
     for (int ks = 1; ks <= MAX_KSPLIT; ++ks) {
-        if (ks > 1 && steps / ks < 8.0) break;
+        if (ks > 1 && steps / ks < (double)min_steps) break;
         double rounds = wgs * ks / 256.0;          // workgroups are handed out as compute units free up:
         if (rounds < 1.0) rounds = 1.0;            // measured, whole rounds are not the right granularity
         const double us = rounds * (steps / ks * us_per_step + 10.0) + ks * us_partials;
@@ -244,7 +244,7 @@ static Plan make_plan(const pzl_layer *L, int32_t T, int32_t k, bool staged)
         ksplit_shared = MAX_KSPLIT;
         for (int s = 0; s < L->n_shared; ++s) {
             int ks = choose_tile_ksplit((int64_t)ns * shared_token_parts(T, ns, L->shared_f[s], pl.shared_wgs, pl.hybrid && pl.persistent), (int64_t)ns * T,
-                                        L->d_model, L->shared_f[s]);
+                                        L->d_model, L->shared_f[s], pl.overlap ? 32 : 8);
             if (ks < ksplit_shared) ksplit_shared = ks;
         }
     }
@@ -252,6 +252,8 @@ static Plan make_plan(const pzl_layer *L, int32_t T, int32_t k, bool staged)
     // themselves, and every split is another set of partial sums for the combine step: at most 3
     // (60 experts + 1 shared expert of 5632: 256 tokens 166 -> 164 us, 1024 tokens 318 -> 306;
     // 64 experts + 2 shared of 1408: within 1 %)
+    // and a split keeps at least 32 K steps (choose_tile_ksplit above): two narrow shared experts of
+    // 1408 stay unsplit (64 experts top-6, 1024 / 2048 tokens: 392 / 572 -> 379 / 559 us)
     if (pl.overlap && pl.tiled_shared && ksplit_shared > 3) ksplit_shared = 3;
     for (int s = 0; s < L->n_shared; ++s)                                          // no split without a k-block
         if (ksplit_shared > L->shared_f[s] / TILE_COLS) ksplit_shared = L->shared_f[s] / TILE_COLS;
