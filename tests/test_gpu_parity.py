@@ -170,6 +170,9 @@ def test_error_codes(small_case, binding):
                       [case.packed_gpu[p, synth.UP] for p in range(3)],
                       [case.packed_gpu[p, synth.DOWN] for p in range(3)])
     assert lib.pzl_moe_ffn_workspace_bytes(case.layer._h, -1, 2) == 0
+    # a workspace sized for max_tokens serves every smaller batch: the size never shrinks with T
+    sizes = [lib.pzl_moe_ffn_workspace_bytes(case.layer._h, T, 2) for T in range(0, 1200)]
+    assert all(b >= a for a, b in zip(sizes, sizes[1:])) and sizes[1] > 0
     # a batch beyond the documented size limits (T * k * d_ffn < 2^30) is refused, not mis-addressed
     too_many = (1 << 30) // (2 * cfg.d_ffn) + 1
     assert lib.pzl_moe_ffn_workspace_bytes(case.layer._h, too_many, 2) == 0
