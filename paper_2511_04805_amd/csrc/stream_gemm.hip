@@ -20,6 +20,7 @@
 // down stage multiplies both (the matrix cores idle in this kernel anyway).  One bf16 plane
 // alone would put the rounding of H (2^-9 relative per element) straight into y and leave no
 // margin under the 1e-2 output tolerance.
+#include <atomic>
 #include "pzl_common.h"
 
 namespace pzl {
@@ -579,12 +580,16 @@ static int launch(const StreamGroupArgs &g, hipStream_t st)
     const int64_t blocks = (int64_t)g.n_groups * ((row_groups + rg_per_wg - 1) / rg_per_wg) * g.ksplit * a.n_passes;
     if (blocks > 0x7FFFFFFFLL) return PZL_EINVAL;
     const size_t lds = SG_LDS_BYTES + SG_MAX_TILES * 16 * sizeof(int32_t) + (QUANT ? Q_LUT_BYTES : 0);
-    static bool attr_set = false;
-    if (!attr_set) {
+    // the dynamic LDS size beyond 64 KiB is a per-device attribute of the kernel: set it once per
+    // device (bit d of the mask; setting it twice from two threads is harmless)
+    static std::atomic<uint64_t> attr_devices{0};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev > 63) dev = 63;       // unknown device: set it every time
+    if (dev == 63 || !((attr_devices.load(std::memory_order_relaxed) >> dev) & 1)) {
         hipError_t e = hipFuncSetAttribute((const void *)stream_kernel<STAGE, DENSE, ALLTOK, QUANT>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) { set_hip_error(e); return PZL_EHIP; }
-        attr_set = true;
+        if (dev != 63) attr_devices.fetch_or(1ull << dev, std::memory_order_relaxed);
     }
     hipLaunchKernelGGL((stream_kernel<STAGE, DENSE, ALLTOK, QUANT>), dim3((unsigned)blocks), dim3(SG_THREADS), lds, st, a);
     hipError_t e = hipGetLastError();
