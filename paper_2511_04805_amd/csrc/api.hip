@@ -235,7 +235,7 @@ static Plan make_plan(const pzl_layer *L, int32_t T, int32_t k, bool staged)
     pl.mostly_tiled = pl.hybrid && N >= (int64_t)TILED_MIN_TOKENS_PER_EXPERT * E64;
     pl.tiled_shared = T >= TILED_MIN_TOKENS_SHARED;
     pl.persistent = L->n_q >= 32 && N <= (int64_t)256 * L->n_q;
-    pl.tile_overlap = pl.hybrid && !staged && E64 >= 32 && N < 32 * E64;
+    pl.tile_overlap = pl.hybrid && !staged && E64 >= 32 && N < 40 * E64;
 
     const int ns = L->n_shared > 0 ? L->n_shared : 1;
     pl.shared_wgs = shared_target_wgs(L, k, pl.hybrid && pl.persistent);
@@ -684,8 +684,10 @@ int pzl_moe_ffn_staged(const pzl_layer *L, const uint16_t *x, const int32_t *top
     // own, forked here and joined before the combine: a launch that finds no tile then costs
     // nothing, and where both have work they fill the chip together (64 experts, top-6, skewed,
     // 128-256 tokens: -12..-15 %).  The two cross-stream waits cost 5-10 us, so only where a
-    // mixture is likely: many experts and fewer than 32 tokens per expert on average (beyond
-    // that nearly every pair is tiled); and not when the caller times stages.
+    // mixture is likely: many experts and fewer than 40 tokens per expert on average (beyond
+    // that nearly every pair is tiled); and not when the caller times stages.  Between 32 and 40
+    // the routing decides: skewed (64 experts top-6, 384 tokens) 288 -> 238 us, even (60 experts
+    // top-4, 512 tokens, every pair tiled) 238 -> 250 us.
     const bool tile_overlap = pl.tile_overlap;
     hipStream_t tst = tile_overlap ? L->tile_stream : st;
     if (tile_overlap) {
