@@ -676,7 +676,7 @@ int pzl_moe_ffn_staged(const pzl_layer *L, const uint16_t *x, const int32_t *top
     // one-shot launches may give both experts of a pair one tile (row groups of gate/up tell the
     // grouping kernel how long the launch is); persistent launches do not have those kernels
     rc = launch_route(topk_ids, N, k, L->n_experts, L->n_q, L->d_q_of_expert, rt, tile_min,
-                      persistent ? 0 : (L->d_ffn + 127) / 128, st);
+                      persistent ? 0 : (L->d_ffn + 127) / 128, (L->d_ffn + 127) / 128, st);
     if (rc) return rc;
     if ((rc = mark(PZL_STAGE_ROUTE, 1))) return rc;
     // The tiled and the streaming kernels of the routed experts work on disjoint pairs (the

@@ -40,6 +40,7 @@ constexpr int TILE_FUSED_FLAG = 1 << 30;
 #define PZL_FUSED_MAX 96
 #endif
 constexpr int TILE_FUSED_MAX_TOKENS = PZL_FUSED_MAX;
+constexpr int TILE_HALF_TOKENS = TILE_MAX_TOKENS / 2;   // tile size of launches that would not fill the chip once
 inline int max_token_tiles(int64_t n_flat, int n_experts) { return (int)(n_flat / TILE_MAX_TOKENS) + n_experts; }
 
 void set_hip_error(hipError_t e);
@@ -70,7 +71,7 @@ int launch_q_unpack(const uint8_t *records, const uint16_t *scales, int pos, int
 // row_groups: workgroups per token tile in the gate/up stage (decides whether pairs share tiles;
 // 0: never)
 int launch_route(const int32_t *ids, int32_t n_flat, int32_t k, int32_t n_experts, int32_t n_slots_q, const int32_t *q_of_expert,
-                 RouteTables rt, int32_t tile_min, int32_t row_groups, hipStream_t st);
+                 RouteTables rt, int32_t tile_min, int32_t row_groups, int32_t launch_rows, hipStream_t st);
 int launch_router_topk(const uint16_t *x, const uint16_t *w_router, int32_t T, int32_t d, int32_t E, int32_t k,
                        int32_t *ids_out, float *w_out, hipStream_t st);
 int launch_combine(const float *opart, int32_t ksplit, int32_t ksplit_shared, int64_t ks_stride, const RouteTables &rt,

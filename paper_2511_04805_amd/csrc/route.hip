@@ -23,7 +23,7 @@ route_kernel(const int32_t *__restrict__ ids, int32_t n_flat, int32_t k, int32_t
              const int32_t *__restrict__ q_of_expert, int32_t Q, int32_t *__restrict__ cnt,
              int32_t *__restrict__ off, int32_t *__restrict__ slot_tok, int32_t *__restrict__ slot_of,
              int32_t *__restrict__ tile_q, int32_t *__restrict__ tile_slot0, int32_t *__restrict__ tile_n,
-             int32_t *__restrict__ n_tiles, int32_t tile_min, int32_t row_groups)
+             int32_t *__restrict__ n_tiles, int32_t tile_min, int32_t row_groups, int32_t launch_rows)
 {
     __shared__ int32_t hist[ROUTE_WAVES][ROUTE_QMAX];
     __shared__ int32_t total[ROUTE_QMAX];
@@ -82,17 +82,34 @@ route_kernel(const int32_t *__restrict__ ids, int32_t n_flat, int32_t k, int32_t
     // it pays when the launch (tiles x row_groups workgroups, 256 at a time) gets shorter by well
     // over a third, counting a launch that does not fill the chip as one that just does; it costs
     // when it only thins out a launch that was already short.
-    __shared__ int32_t tiles_plain, pairs_fusable;
-    if (tid == 0) { tiles_plain = 0; pairs_fusable = 0; }
+    __shared__ int32_t tiles_plain, tiles_half, pairs_fusable, tiled_max, tiled_sum, tiled_experts;
+    if (tid == 0) { tiles_plain = 0; tiles_half = 0; pairs_fusable = 0; tiled_max = 0; tiled_sum = 0; tiled_experts = 0; }
     __syncthreads();
     for (int g = tid; g < Q / 2; g += ROUTE_THREADS) {
         const int c0 = total[2 * g], c1 = total[2 * g + 1];
         if (all_tiled || max(c0, c1) >= tile_min) {
             atomicAdd(&tiles_plain, (c0 + TILE_MAX_TOKENS - 1) / TILE_MAX_TOKENS + (c1 + TILE_MAX_TOKENS - 1) / TILE_MAX_TOKENS);
+            atomicAdd(&tiles_half, (c0 + TILE_HALF_TOKENS - 1) / TILE_HALF_TOKENS + (c1 + TILE_HALF_TOKENS - 1) / TILE_HALF_TOKENS);
             if (pair_is_fused(c0, c1)) atomicAdd(&pairs_fusable, 1);
+            atomicMax(&tiled_max, max(c0, c1));
+            atomicAdd(&tiled_sum, c0 + c1);
+            atomicAdd(&tiled_experts, (c0 > 0) + (c1 > 0));
         }
     }
     __syncthreads();
+    // A launch of a few rounds of workgroups ends with its largest tiles: a busy expert's 281
+    // tokens as one tile keep 11 workgroups running twice as long as the tiles of the others.
+    // Such a launch, if its busiest expert has at least twice the tokens of the average tiled
+    // expert, cuts its tiles at half the size (the tile list's bound, sized for full tiles plus
+    // one per expert, must still hold them).  Measured (whole step): 64 experts top-6, skewed,
+    // 192-768 tokens -10..-24 %; with an even router the smaller tiles only cost (60 experts top-4,
+    // 2048 tokens: +6 % when cut regardless of the spread).
+#ifndef PZL_HALF_TILE_WGS
+#define PZL_HALF_TILE_WGS 768
+#endif
+    const bool spread = (int64_t)tiled_max * tiled_experts >= 2 * (int64_t)tiled_sum;
+    const int tile_cap = (spread && (int64_t)tiles_plain * launch_rows <= PZL_HALF_TILE_WGS && tiles_half <= n_flat / TILE_MAX_TOKENS + Q)
+                             ? TILE_HALF_TOKENS : TILE_MAX_TOKENS;
     const int64_t wgs_plain = max((int64_t)tiles_plain * row_groups, (int64_t)256);
     const int64_t wgs_fused = max((int64_t)(tiles_plain - pairs_fusable) * row_groups, (int64_t)256);
     const bool fuse = row_groups > 0 && pairs_fusable > 0 && 17 * wgs_fused < 10 * wgs_plain;
@@ -101,7 +118,7 @@ route_kernel(const int32_t *__restrict__ ids, int32_t n_flat, int32_t k, int32_t
     for (int q = tid; q < ROUTE_QMAX; q += ROUTE_THREADS) {
         int c = q < Q ? total[q] : 0;
         bool t = q < Q && (all_tiled || max(total[q & ~1], total[q | 1]) >= tile_min);   // Q is even: q | 1 < Q
-        int parts = (c + TILE_MAX_TOKENS - 1) / TILE_MAX_TOKENS;
+        int parts = (c + tile_cap - 1) / tile_cap;
         int size = parts ? (((c + parts - 1) / parts + 15) & ~15) : 0;
         scan_c[q] = c;
         scan_t[q] = t && c ? (c + size - 1) / size : 0;
@@ -146,7 +163,7 @@ route_kernel(const int32_t *__restrict__ ids, int32_t n_flat, int32_t k, int32_t
                 tile_q[nt] = q | TILE_FUSED_FLAG; tile_slot0[nt] = first; tile_n[nt] = c | (total[q | 1] << 16);
             }
         } else if (tiled_pair[q] && c > 0) {
-            int parts = (c + TILE_MAX_TOKENS - 1) / TILE_MAX_TOKENS;
+            int parts = (c + tile_cap - 1) / tile_cap;
             int size = ((c + parts - 1) / parts + 15) & ~15;
             int nt = scan_t[q];
             for (int s0 = 0; s0 < c; s0 += size, ++nt) {
@@ -482,13 +499,14 @@ int launch_router_topk(const uint16_t *x, const uint16_t *w_router, int32_t T, i
 }
 
 int launch_route(const int32_t *ids, int32_t n_flat, int32_t k, int32_t n_experts, int32_t n_slots_q,
-                 const int32_t *q_of_expert, RouteTables rt, int32_t tile_min, int32_t row_groups, hipStream_t st)
+                 const int32_t *q_of_expert, RouteTables rt, int32_t tile_min, int32_t row_groups, int32_t launch_rows,
+                 hipStream_t st)
 {
     int Q = n_slots_q;
     if (Q > ROUTE_QMAX) return PZL_EINVAL;
     hipLaunchKernelGGL(route_kernel, dim3(1), dim3(ROUTE_THREADS), 0, st, ids, n_flat, k, n_experts,
                        q_of_expert, Q, rt.cnt, rt.off, rt.slot_tok, rt.slot_of, rt.tile_q, rt.tile_slot0,
-                       rt.tile_n, rt.n_tiles, tile_min, row_groups);
+                       rt.tile_n, rt.n_tiles, tile_min, row_groups, launch_rows);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) { set_hip_error(e); return PZL_EHIP; }
     return PZL_OK;
