@@ -13,9 +13,10 @@ no instruction after an inline-asm `global_load_dwordx4` names one of its destin
 before the loop wraps around (one exception: a lane-0 read into a scalar register that is
 overwritten before it is read on every path, which is how the compiler materialises an undefined
 value), that every loop exit waits for all loads before any vector instruction, and that nothing
-spills.  Run it after any change to the kernel or the compiler:
+spills.  A developer tool that lives with its test (test_tile_isa.py), not in the product
+package.  Run it after any change to the kernel or the compiler:
 
-    python -m paper_2511_04805_amd.check_tile_isa
+    python tests/check_tile_isa.py
 """
 import os
 import re
@@ -23,14 +24,17 @@ import subprocess
 import sys
 import tempfile
 
-_HERE = os.path.dirname(os.path.abspath(__file__))
+_ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+if _ROOT not in sys.path:
+    sys.path.insert(0, _ROOT)
+_CSRC = os.path.join(_ROOT, "paper_2511_04805_amd", "csrc")
 _REG = re.compile(r"v\[(\d+):(\d+)\]|\bv(\d+)\b")
 
 
 def compile_to_asm(out_path):
-    from .build import FLAGS as HIPCC_FLAGS  # the flags the library is built with
+    from paper_2511_04805_amd.build import FLAGS as HIPCC_FLAGS  # the flags the library is built with
     cmd = ["hipcc"] + HIPCC_FLAGS + ["-S", "--cuda-device-only", "-o", out_path,
-                                     os.path.join(_HERE, "csrc", "tile_gemm.hip")]
+                                     os.path.join(_CSRC, "tile_gemm.hip")]
     subprocess.run(cmd, check=True, stdout=subprocess.PIPE, stderr=subprocess.PIPE)
 
 
@@ -141,20 +145,10 @@ def _known_ones(lines, i):
     return frozenset(ones)
 
 
-def check(asm_text):
-    """Returns (number of K loops checked, number of loop exits checked, list of problems)."""
-    lines = asm_text.split("\n")
-    problems = []
-    for l in lines:
-        m = re.search(r"\.vgpr_spill_count:\s+(\d+)", l)
-        if m and int(m.group(1)):
-            problems.append("register spills: %s" % l.strip())
-    labels = {}
-    for i, l in enumerate(lines):
-        m = re.match(r"^(\.LBB\d+_\d+):", l)
-        if m:
-            labels[m.group(1)] = i
-    n_loops = 0
+def _k_loops(lines, labels):
+    """(first line, line of the backward branch) of every K loop: a backward branch whose body holds
+    matrix instructions, inline-asm weight loads, exactly two barriers (two K steps per trip) and
+    no store."""
     for i, l in enumerate(lines):
         m = re.match(r"\s+s_cbranch_\w+\s+(\.LBB\d+_\d+)", l)
         if not m or labels.get(m.group(1), i) >= i:
@@ -163,7 +157,56 @@ def check(asm_text):
         body = lines[start:i]
         if (sum("v_mfma" in b for b in body) < 8 or not any("global_load_dwordx4" in b for b in body)
                 or sum("s_barrier" in b for b in body) != 2 or any("global_store" in b for b in body)):
-            continue                                          # not a K loop (two steps per trip)
+            continue
+        yield start, i
+
+
+def _labels(lines):
+    labels = {}
+    for i, l in enumerate(lines):
+        m = re.match(r"^(\.LBB\d+_\d+):", l)
+        if m:
+            labels[m.group(1)] = i
+    return labels
+
+
+def loops_by_kernel(asm_text):
+    """{mangled kernel name: number of K loops found in it}, for every tile_kernel in the text."""
+    lines = asm_text.split("\n")
+    starts = [(i, m.group(1)) for i, l in enumerate(lines) for m in [re.match(r"^(_Z\w*tile_kernel\w*):", l)] if m]
+    out = {name: 0 for _, name in starts}
+    for start, _ in _k_loops(lines, _labels(lines)):
+        owner = [name for i, name in starts if i <= start]
+        if owner:
+            out[owner[-1]] += 1
+    return out
+
+
+def expected_loops(mangled):
+    """K loops a tile_kernel<STAGE, DENSE, ALLTOK, PERSIST> instantiation must contain, from its
+    template arguments: one per (expert position, number of token-fragment pairs 1..9); dense
+    weights have one position only; one-shot kernels of packed pairs also hold the 4 sizes of the
+    tile that covers both experts of a pair."""
+    m = re.search(r"tile_kernelILi(\d)ELb(\d)ELb(\d)ELb(\d)E", mangled)
+    assert m, mangled
+    dense, persist = m.group(2) == "1", m.group(4) == "1"
+    if dense:
+        return 9
+    return 18 if persist else 18 + 4
+
+
+def check(asm_text):
+    """Returns (number of K loops checked, number of loop exits checked, list of problems)."""
+    lines = asm_text.split("\n")
+    problems = []
+    for l in lines:
+        m = re.search(r"\.vgpr_spill_count:\s+(\d+)", l)
+        if m and int(m.group(1)):
+            problems.append("register spills: %s" % l.strip())
+    labels = _labels(lines)
+    n_loops = 0
+    for start, i in _k_loops(lines, labels):
+        body = lines[start:i]
         n_loops += 1
         inflight = set()
         in_asm = False
