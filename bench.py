@@ -27,6 +27,8 @@ HBM_PEAK_GBS = 8000.0
 # copy below) summarised under profiles/.  Counters cannot be read inside this process.
 MEASURED_TRAFFIC_BYTES = {"mixtral_decode_T64": 954.9e6, "mixtral_decode_T64_quantised": 429.8e6,
                           "mixtral_prefill_T4096": 8.368e9}
+TRAFFIC_FROM = ("separate rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script, summarised under profiles/ "
+                "(stream_kernels_mixtral_decode_T64.md, tile_kernels_mixtral_prefill_T4096.md); not read in this process")
 W3 = (synth.GATE, synth.UP, synth.DOWN)
 
 
@@ -107,20 +109,52 @@ def batch(cfg, T):
             torch.from_numpy(w).cuda())
 
 
+WARM_SECONDS = 0.5      # floor of the warm-up, whatever --warmup says: clocks and caches settle in about that time
+REPEATS = 5             # timed regions of K steps each; the median is reported
+
+
+def _warm(call, warmup):
+    """At least `warmup` calls and WARM_SECONDS of them, then on until three batches of 20 calls in a
+    row agree within 2 % (at most 3 s in all): a run right after start-up, before the clocks have
+    settled, measures up to 20 % slow."""
+    for _ in range(warmup):
+        call()
+    torch.cuda.synchronize()
+    t_end = time.perf_counter() + WARM_SECONDS
+    while time.perf_counter() < t_end:
+        for _ in range(20):
+            call()
+        torch.cuda.synchronize()
+    last, t_stop = [], time.perf_counter() + 2.5
+    while time.perf_counter() < t_stop:
+        t0 = time.perf_counter()
+        for _ in range(20):
+            call()
+        torch.cuda.synchronize()
+        last = (last + [time.perf_counter() - t0])[-3:]
+        if len(last) == 3 and max(last) <= 1.02 * min(last):
+            break
+
+
 def time_plain(hip, layer, xt, idt, wt, steps, warmup):
-    """K calls of pzl_moe_ffn as a caller makes them (shared experts on the layer's second stream)."""
+    """pzl_moe_ffn as a caller makes it (shared experts on the layer's second stream): REPEATS timed
+    regions of exactly `steps` calls, each bracketed by synchronisation, HIP events on the stream the
+    calls are queued on.  Returns (median ms per step over the regions, all regions' ms per step, y)."""
     y = torch.empty(xt.shape[0], layer.d_model, dtype=torch.bfloat16, device="cuda")
     stream = torch.cuda.current_stream().cuda_stream
-    for _ in range(warmup):
-        layer.pzl_moe_ffn(xt, idt, wt, y=y)
+    call = lambda: layer.pzl_moe_ffn(xt, idt, wt, y=y)
+    _warm(call, warmup)
     t0, t1 = hip.event(), hip.event()
-    torch.cuda.synchronize()
-    hip.record(t0, stream)
-    for _ in range(steps):
-        layer.pzl_moe_ffn(xt, idt, wt, y=y)
-    hip.record(t1, stream)
-    torch.cuda.synchronize()
-    return hip.elapsed_ms(t0, t1) / steps
+    regions = []
+    for _ in range(REPEATS):
+        torch.cuda.synchronize()
+        hip.record(t0, stream)
+        for _ in range(steps):
+            call()
+        hip.record(t1, stream)
+        torch.cuda.synchronize()
+        regions.append(hip.elapsed_ms(t0, t1) / steps)
+    return float(np.median(regions)), regions, y
 
 
 def time_router(hip, cfg, xt, steps=50, warmup=5):
@@ -144,10 +178,11 @@ def touched_pairs(ids, emap):
     return len(set(int(emap[0][e]) for e in np.unique(ids)))
 
 
-def time_steps(hip, layer, xt, idt, wt, steps, warmup, stage="gateup"):
-    """K timed steps bracketed by synchronisation; events around one stage of every step."""
+def time_stage(hip, layer, xt, idt, wt, steps, warmup, stage="gateup"):
+    """Average duration of one stage's launch: HIP events recorded by the library around that stage
+    (pzl_moe_ffn_staged) on the stream it runs on, in every one of `steps` calls after the warm-up.
+    Returns (median, mean) in ms."""
     y = torch.empty(xt.shape[0], layer.d_model, dtype=torch.bfloat16, device="cuda")
-    stream = torch.cuda.current_stream().cuda_stream
     si = binding.STAGES.index(stage)
     evs = []
     for _ in range(steps):
@@ -155,22 +190,36 @@ def time_steps(hip, layer, xt, idt, wt, steps, warmup, stage="gateup"):
         a, b = hip.event(), hip.event()
         arr[2 * si], arr[2 * si + 1] = a, b
         evs.append((arr, a, b))
-    for _ in range(warmup):
-        layer.pzl_moe_ffn(xt, idt, wt, y=y)
-    t0, t1 = hip.event(), hip.event()
-    torch.cuda.synchronize()
-    wall0 = time.perf_counter()
-    hip.record(t0, stream)
+    _warm(lambda: layer.pzl_moe_ffn(xt, idt, wt, y=y), warmup)
     for arr, _, _ in evs:
         layer.pzl_moe_ffn(xt, idt, wt, y=y, stage_events=arr)
-    hip.record(t1, stream)
     torch.cuda.synchronize()
-    wall = time.perf_counter() - wall0
-    total_ms = hip.elapsed_ms(t0, t1)
     stage_ms = [hip.elapsed_ms(a, b) for _, a, b in evs]
     for _, a, b in evs:
         hip.lib.hipEventDestroy(a); hip.lib.hipEventDestroy(b)
-    return total_ms / steps, float(np.mean(stage_ms)), wall * 1e3 / steps, y
+    return float(np.median(stage_ms)), float(np.mean(stage_ms))
+
+
+def decode_point(hip, cfg, layer, emap, T, steps, warmup):
+    """One decode batch size: the whole step and its two weight-streaming kernels."""
+    x, ids, w, xt, idt, wt = batch(cfg, T)
+    ms_step, regions, y = time_plain(hip, layer, xt, idt, wt, steps, warmup)
+    gu_med, gu_mean = time_stage(hip, layer, xt, idt, wt, steps, 0, "gateup")
+    dn_med, dn_mean = time_stage(hip, layer, xt, idt, wt, steps, 0, "down")
+    nt = touched_pairs(ids, emap)
+    d, f, k = cfg.d_model, cfg.d_ffn, cfg.top_k
+    # packed gate+up once, x, H (one 16-bit plane) / packed down once, H, fp32 partial sums out
+    gu_bytes = nt * 2 * f * d * 2 + T * d * 2 + T * k * f * 2
+    dn_bytes = nt * f * d * 2 + T * k * f * 2
+    path_bytes = nt * 3 * f * d * 2
+    return {"tokens": T, "touched_pairs": nt, "ms_per_step": ms_step, "ms_per_step_regions": regions,
+            "tokens_per_s": T / (ms_step * 1e-3),
+            "gateup_ms": gu_mean, "gateup_ms_median": gu_med, "gateup_bytes": gu_bytes,
+            "gateup_GBs": gu_bytes / (gu_mean * 1e-3) / 1e9,
+            "down_ms": dn_mean, "down_ms_median": dn_med, "down_bytes": dn_bytes,
+            "down_GBs": dn_bytes / (dn_mean * 1e-3) / 1e9,
+            "path_GBs": path_bytes / (ms_step * 1e-3) / 1e9,
+            "path_hbm_frac": path_bytes / (ms_step * 1e-3) / 1e9 / HBM_PEAK_GBS}, (x, ids, w, xt, idt, wt, y)
 
 
 def main():
@@ -213,71 +262,74 @@ def main():
     torch.cuda.synchronize()
     del cal
 
-    x, ids, w, xt, idt, wt = batch(cfg, T)
-    ms_step, ms_gateup, ms_wall, y = time_steps(hip, layer, xt, idt, wt, args.steps, args.warmup)
-    n_touched = touched_pairs(ids, emap)
+    # The sweep first and the headline batch last, each after its own warm-up (time-based, see
+    # _warm): what is measured first would otherwise carry the start-up of the process.
+    sweep = {}
+    if not args.no_sweep:
+        for Ts in (1, 8, 32, 64):
+            if Ts != T:
+                sweep[str(Ts)], _ = decode_point(hip, cfg, layer, emap, Ts, args.steps, args.warmup)
+    head, (x, ids, w, xt, idt, wt, y) = decode_point(hip, cfg, layer, emap, T, args.steps, args.warmup)
+    sweep[str(T)] = head
+    n_touched = head["touched_pairs"]
     d, f, k = cfg.d_model, cfg.d_ffn, cfg.top_k
     pair_bytes_gateup = 2 * f * d * 2
-    alg_bytes = n_touched * pair_bytes_gateup + T * d * 2 + T * k * f * 2   # packed gate+up once, x, H
-    achieved = alg_bytes / (ms_gateup * 1e-3) / 1e9
+    ms_step = head["ms_per_step"]
 
     out = {
         "metric": "MoE-FFN tokens/sec at 1 MI355X; achieved HBM GB/s (decode)",
-        "value": T / (ms_step * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak",
+        "value": head["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_step, "ms_per_step_regions": head["ms_per_step_regions"], "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "mixtral_decode_T%d" % T, "layer": "Mixtral-8x7B-shaped, 8 experts -> 4 packed pairs",
                    "d_model": d, "d_ffn": f, "top_k": k, "tokens": T, "touched_pairs": n_touched},
-        "roofline": {"bound": "hbm", "kernel": "stream_kernel<gate/up + SwiGLU>", "achieved": achieved,
-                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+        "timing": "median of %d timed regions of --steps calls each, after --warmup calls plus a warm-up of at least "
+                  "%.1f s that runs until three batches of 20 calls agree within 2 %%" % (REPEATS, WARM_SECONDS),
+        "roofline": {"bound": "hbm", "kernel": "stream_kernel<gate/up + SwiGLU>", "achieved": head["gateup_GBs"],
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": head["gateup_GBs"] / HBM_PEAK_GBS,
                      "traffic": MEASURED_TRAFFIC_BYTES.get("mixtral_decode_T%d" % T),
-                     "algorithmic_bytes": alg_bytes, "avg_launch_ms": ms_gateup},
-        "ms_per_step_host_wall": ms_wall,
+                     "traffic_from": TRAFFIC_FROM if MEASURED_TRAFFIC_BYTES.get("mixtral_decode_T%d" % T) else None,
+                     "algorithmic_bytes": head["gateup_bytes"], "avg_launch_ms": head["gateup_ms"],
+                     "median_launch_ms": head["gateup_ms_median"]},
+        "down_kernel": {"kernel": "stream_kernel<down>", "achieved": head["down_GBs"], "unit": "GB/s",
+                        "frac": head["down_GBs"] / HBM_PEAK_GBS, "algorithmic_bytes": head["down_bytes"],
+                        "avg_launch_ms": head["down_ms"]},
+        "path_hbm_frac": head["path_hbm_frac"],
     }
-    path_bytes = n_touched * 3 * f * d * 2
-    out["path_hbm_frac"] = path_bytes / (ms_step * 1e-3) / 1e9 / HBM_PEAK_GBS
     # the on-device router in front of the layer, on its own (not part of the timed step: ids and
     # weights are inputs of the path)
     out["router_ms"] = time_router(hip, cfg, xt)
-
     if not args.no_sweep:
-        sweep = {}
-        for Ts in (1, 8, 32, 64):
-            if Ts == T:
-                sweep[str(Ts)] = {"tokens_per_s": out["value"], "ms_per_step": ms_step,
-                                  "gateup_GBs": achieved}
-                continue
-            xs, ids_s, ws, xts, idts, wts = batch(cfg, Ts)
-            ms, msg, _, _ = time_steps(hip, layer, xts, idts, wts, max(20, args.steps // 4), 5)
-            nt = touched_pairs(ids_s, emap)
-            sweep[str(Ts)] = {"tokens_per_s": Ts / (ms * 1e-3), "ms_per_step": ms, "touched_pairs": nt,
-                              "gateup_GBs": (nt * pair_bytes_gateup) / (msg * 1e-3) / 1e9}
-        out["sweep"] = sweep
+        out["sweep"] = {t: {kk: v[kk] for kk in ("tokens_per_s", "ms_per_step", "touched_pairs", "gateup_GBs",
+                                                  "down_GBs", "path_GBs", "path_hbm_frac")}
+                        for t, v in sorted(sweep.items(), key=lambda kv: int(kv[0]))}
 
     if not args.no_prefill:
         # Same layer, prefill-sized batch (4096 tokens): the tiled decode-GEMM path on the matrix
-        # cores.  Useful flops only: 3 projections x 2*d*f per (token, choice); the second MFMA
-        # pass over the lo plane of H is not counted.
+        # cores.  Useful flops only: 3 projections x 2*d*f per (token, choice).
         Tp = 4096
         xs, ids_p, ws, xtp, idtp, wtp = batch(cfg, Tp)
-        ms_p, ms_gu, _, _ = time_steps(hip, layer, xtp, idtp, wtp, 10, 3, stage="gateup")
-        _, ms_dn, _, _ = time_steps(hip, layer, xtp, idtp, wtp, 10, 3, stage="down")
+        ms_p, _, _ = time_plain(hip, layer, xtp, idtp, wtp, 10, 3)
+        _, ms_gu = time_stage(hip, layer, xtp, idtp, wtp, 20, 0, "gateup")
+        _, ms_dn = time_stage(hip, layer, xtp, idtp, wtp, 20, 0, "down")
         fl_proj = 2.0 * Tp * k * d * f
         out["prefill"] = {
             "workload": "mixtral_prefill_T4096", "tokens_per_s": Tp / (ms_p * 1e-3), "ms_per_step": ms_p,
             "roofline": {"bound": "mfma", "kernel": "tile_kernel<gate/up + SwiGLU>",
                          "achieved": 2 * fl_proj / (ms_gu * 1e-3) / 1e12, "peak": 2500.0, "unit": "TFLOP/s",
                          "frac": 2 * fl_proj / (ms_gu * 1e-3) / 2.5e15,
-                         "traffic": MEASURED_TRAFFIC_BYTES.get("mixtral_prefill_T%d" % Tp), "avg_launch_ms": ms_gu},
+                         "traffic": MEASURED_TRAFFIC_BYTES.get("mixtral_prefill_T%d" % Tp),
+                         "traffic_from": TRAFFIC_FROM, "avg_launch_ms": ms_gu},
             "down_kernel": {"avg_launch_ms": ms_dn, "useful_TFLOPs": fl_proj / (ms_dn * 1e-3) / 1e12,
-                            "executed_TFLOPs": 2 * fl_proj / (ms_dn * 1e-3) / 1e12},
+                            "frac": fl_proj / (ms_dn * 1e-3) / 2.5e15},
             "path_useful_mfma_frac": 3 * fl_proj / (ms_p * 1e-3) / 2.5e15}
 
     if not args.no_quant:
         # Same layer and batch with the pairs in the quantised format (the paper's appendix on
         # combining the method with quantisation): 424 bytes per 16x32 tile plus the group scales.
         qlayer = build_quantised_layer(cfg)
-        ms_q, ms_qgu, _, _ = time_steps(hip, qlayer, xt, idt, wt, max(20, args.steps // 2), 5)
+        ms_q, _, _ = time_plain(hip, qlayer, xt, idt, wt, max(20, args.steps // 2), 5)
+        _, ms_qgu = time_stage(hip, qlayer, xt, idt, wt, max(20, args.steps // 2), 0, "gateup")
         q_pair_bytes_gateup = 2 * (f * d // 512 * 424 + f * d // 128 * 2)
         q_alg = n_touched * q_pair_bytes_gateup + T * d * 2 + T * k * f * 2
         out["quantised"] = {
@@ -287,6 +339,7 @@ def main():
                          "achieved": q_alg / (ms_qgu * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                          "frac": q_alg / (ms_qgu * 1e-3) / 1e9 / HBM_PEAK_GBS,
                          "traffic": MEASURED_TRAFFIC_BYTES.get("mixtral_decode_T%d_quantised" % T),
+                         "traffic_from": TRAFFIC_FROM,
                          "algorithmic_bytes": q_alg, "avg_launch_ms": ms_qgu},
             "weight_bytes_vs_16bit": q_pair_bytes_gateup / pair_bytes_gateup}
         del qlayer
@@ -303,7 +356,7 @@ def main():
             T2 = c2.n_tokens[0]
             l2, emap2 = build_layer(c2)
             x2, ids2, w2, xt2, idt2, wt2 = batch(c2, T2)
-            ms2 = time_plain(hip, l2, xt2, idt2, wt2, 50, 10)
+            ms2, _, _ = time_plain(hip, l2, xt2, idt2, wt2, 50, 10)
             nt2 = touched_pairs(ids2, emap2)
             w_bytes = nt2 * 3 * c2.d_ffn * c2.d_model * 2 + sum(3 * fs * c2.d_model * 2 for fs in c2.shared_d_ffn)
             flops = 2.0 * 3 * c2.d_model * (T2 * c2.top_k * c2.d_ffn + T2 * sum(c2.shared_d_ffn))
@@ -335,9 +388,10 @@ def main():
                                "kind": "oracle",
                                "sample": "%d passes over the first %d tokens of the same batch, fp64 oracle, %.1f s"
                                          % (passes, n_sample, dt)}
+        # the same bound as the parity tests: every element within 1e-2 of max(|y_ref|, rms of its token's row)
         yg = y[:n_sample].float().cpu().numpy().astype(np.float64)
-        rms = float(np.sqrt(np.mean(y64 ** 2)))
-        out["parity_sample"] = {"worst_err_over_bound":
+        rms = np.sqrt(np.mean(y64 ** 2, axis=1, keepdims=True))
+        out["parity_sample"] = {"rows": n_sample, "worst_err_over_bound":
                                 float((np.abs(yg - y64) / (1e-2 * np.maximum(np.abs(y64), rms))).max())}
     print(json.dumps(out))
 

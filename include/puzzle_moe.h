@@ -43,7 +43,7 @@
 extern "C" {
 #endif
 
-#define PZL_ABI_VERSION 4
+#define PZL_ABI_VERSION 5
 
 #define PZL_OK       0
 #define PZL_EINVAL  -1   /* null pointer, bad shape, position not 0/1, pair map not a 2-to-1 cover */
@@ -85,6 +85,18 @@ int pzl_pack(const uint16_t *merged, const uint8_t *mask0, const uint8_t *mask1,
  */
 int pzl_unpack(const uint16_t *packed, int expert_pos, int64_t rows, int64_t cols,
                uint16_t *out, void *stream);
+
+/*
+ * The same decode in the second form the library's matmuls use: IEEE half precision, every weight
+ * multiplied by 2 (Algorithm 1's exponent field is half precision's own biased exponent; the factor
+ * makes field 0 a normal number), as the down projection of a layer with half-precision H runs it.
+ * Exact, i.e. out = 2 * pzl_unpack(...) as numbers, for every word whose exponent field is at most
+ * 29; words with field 30 or 31 (|w| >= 2^15) have no half-precision form and such tensors are
+ * never decoded this way (pzl_layer_create checks).  For inspection and tests.
+ *   out     [rows, cols] row-major half-precision bit patterns, caller-owned
+ */
+int pzl_unpack_half_x2(const uint16_t *packed, int expert_pos, int64_t rows, int64_t cols,
+                       uint16_t *out, void *stream);
 
 /*
  * Re-order a dense row-major bf16 matrix (an unmerged shared expert, "other modules
@@ -146,12 +158,19 @@ typedef struct pzl_layer_desc {
     const uint16_t *const *gate_scale;    /* host [n_pairs] of device ptrs, or NULL (format 0) */
     const uint16_t *const *up_scale;
     const uint16_t *const *down_scale;
+    int32_t h_precision;            /* form of the SwiGLU output H of the packed pairs (format 0):
+                                       0: automatic -- one plane of IEEE half precision if no used
+                                          element of any down matrix has an exponent field above 29
+                                          (|w| < 2^15; pzl_layer_create scans them), else as 1;
+                                       1: always two bf16 planes (hi + lo, about 16 significant bits,
+                                          bf16's range): twice the matrix work in the down stage   */
 } pzl_layer_desc;
 
 typedef struct pzl_layer pzl_layer;
 
 /* Validates the description and builds the layer's device tables (the only allocation the
- * library performs).  The device current at the call is the layer's device.  The layer also
+ * library performs; it also sets the kernels' launch attributes).  The device current at the call
+ * is the layer's device.  The layer also
  * owns up to two further streams (default priority) with two events each: pzl_moe_ffn runs the
  * shared experts on one and, for batches that use both kinds of kernel, the tiled kernels of
  * the routed experts on the other, next to the rest of the call, forked from and joined back
@@ -159,6 +178,11 @@ typedef struct pzl_layer pzl_layer;
  * time on different streams (calls queued on one stream are fine). */
 int pzl_layer_create(const pzl_layer_desc *desc, pzl_layer **out);
 void pzl_layer_destroy(pzl_layer *layer);
+/* Which form of H the layer's packed pairs use (*half_precision = 1: one half-precision plane) and
+ * how many wavefronts have saturated a value of H to +-65504 since the layer was created (a
+ * blocking copy from the device; 0 in any sane model: |silu(g) * u| would have to exceed 65504).
+ * Either pointer may be NULL.  Host pointers. */
+int pzl_layer_h_info(const pzl_layer *layer, int32_t *half_precision, int32_t *saturated);
 
 /*
  * moe_ffn_plan — what pzl_moe_ffn decides on the host for a layer of this shape and a batch of T
@@ -200,6 +224,29 @@ int pzl_moe_ffn_plan(const pzl_layer_shape *shape, int32_t T, int32_t k, pzl_pla
 size_t pzl_moe_ffn_workspace_bytes(const pzl_layer *layer, int32_t max_tokens, int32_t top_k);
 
 /*
+ * Where pzl_moe_ffn keeps its routing tables inside the workspace, for inspection after a call (a
+ * test that wants to know which token landed in which token tile; a debugger).  Byte offsets from
+ * the start of the workspace; every table is int32.  Routing keys: 2 * pair + position for a merged
+ * expert, 2 * (n_pairs + j) for unmerged expert j.  Slots are the (token, choice) entries grouped by
+ * key.  The layout depends on (layer, T, k) only.  Host pointers; no device work.
+ */
+typedef struct pzl_workspace_layout {
+    int32_t n_keys;             /* routing keys of the layer */
+    int32_t max_tiles;          /* capacity of the three tile tables */
+    size_t streamed_count;      /* [n_keys]   slots of the key handled by the streaming kernels (0 if its pair is tiled) */
+    size_t first_slot;          /* [n_keys+1] first slot of each key */
+    size_t slot_token;          /* [T*k]      token of each slot */
+    size_t slot_of;             /* [T*k]      slot of flat index t*k+j, -1 for an ignored id */
+    size_t tile_key;            /* [max_tiles] key of each token tile of the tiled kernels; bit 30 set:
+                                   the tile covers both experts of the pair */
+    size_t tile_first_slot;     /* [max_tiles] */
+    size_t tile_tokens;         /* [max_tiles] tokens in the tile (n0 | n1 << 16 for a tile that covers a pair) */
+    size_t n_tiles;             /* [1]        number of token tiles */
+    size_t total;               /* pzl_moe_ffn_workspace_bytes(layer, T, k) */
+} pzl_workspace_layout;
+int pzl_moe_ffn_workspace_layout(const pzl_layer *layer, int32_t T, int32_t k, pzl_workspace_layout *out);
+
+/*
  * moe_ffn — the routed expert FFN over Eq. 6-decoded weights:
  *   y[t,:] = sum_j topk_w[t,j] * FFN_{topk_ids[t,j]}(x[t,:])  +  sum_s FFN_shared_s(x[t,:])
  *   FFN_e(x) = Wdown_e ( silu(Wgate_e x) * (Wup_e x) ),   silu(g) = g / (1 + exp(-g))
@@ -207,9 +254,14 @@ size_t pzl_moe_ffn_workspace_bytes(const pzl_layer *layer, int32_t max_tokens, i
  * layer in the quantised format, reconstructed on the fly as (-1)^S * M * code * scale (the group
  * scale is applied to the fp32 partial sums of each 128-column group, so code * scale is never
  * rounded).  Quantised layers always take the weight-streaming kernels.
- * Products are bf16 x bf16 accumulated in fp32; the SwiGLU output is kept as two bf16 numbers
- * (hi = bf16(h), lo = bf16(h - hi)) and the down projection multiplies both; y is rounded to
- * bf16 once at the end.
+ * Products are accumulated in fp32 and y is rounded to bf16 once at the end.  Between the two
+ * contractions the SwiGLU output h needs more than bf16's 8 significant bits to keep y within 1e-2:
+ * packed pairs keep it as one IEEE half-precision number (11 bits; the down projection then decodes
+ * its weights to half precision, exactly, and runs on the f16 matrix instruction; |h| beyond 65504
+ * saturates and is counted, |h| below 6e-5 keeps an absolute precision of 3e-8), or, where a down
+ * matrix holds weights of 2^15 and more or the layer asks for it (h_precision), as two bf16 numbers
+ * (hi = bf16(h), lo = bf16(h - hi)) that the down projection both multiplies, as unmerged, shared
+ * and quantised experts always do.
  *   x         [T, d_model] bf16 bits, row-major
  *   topk_ids  [T, k] int32 expert ids in [0, E); duplicates within a token add up; ids
  *             outside the range are ignored (contribute nothing)

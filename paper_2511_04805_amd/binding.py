@@ -17,9 +17,10 @@ _lib = None
 PZL_OK, PZL_EINVAL, PZL_ENOSPC, PZL_EHIP, PZL_ENOMEM = 0, -1, -2, -3, -4
 
 EXPORTS = ("pzl_abi_version", "pzl_strerror", "pzl_last_hip_error", "pzl_packed_bytes", "pzl_pack",
-           "pzl_unpack", "pzl_tile_dense", "pzl_merge_pack", "pzl_router_topk",
+           "pzl_unpack", "pzl_unpack_half_x2", "pzl_tile_dense", "pzl_merge_pack", "pzl_router_topk",
            "pzl_q_record_bytes", "pzl_q_scale_bytes", "pzl_q_pack", "pzl_q_unpack", "pzl_layer_create", "pzl_layer_destroy",
-           "pzl_moe_ffn_plan", "pzl_moe_ffn_workspace_bytes", "pzl_moe_ffn", "pzl_moe_ffn_staged")
+           "pzl_moe_ffn_plan", "pzl_moe_ffn_workspace_bytes", "pzl_moe_ffn", "pzl_moe_ffn_staged",
+           "pzl_moe_ffn_workspace_layout", "pzl_layer_h_info")
 
 STAGES = ("route", "gateup", "down", "shared", "combine")
 
@@ -35,6 +36,12 @@ class _Plan(ctypes.Structure):
                                               "ksplit", "ksplit_shared", "tiled_shared", "sweep_wgs_packed",
                                               "sweep_wgs_unmerged")] + \
                [("shared_token_tiles", ctypes.c_int32 * 16), ("shared_tile_tokens", ctypes.c_int32 * 16)]
+
+
+class _WorkspaceLayout(ctypes.Structure):
+    _fields_ = [("n_keys", ctypes.c_int32), ("max_tiles", ctypes.c_int32)] + \
+               [(n, ctypes.c_size_t) for n in ("streamed_count", "first_slot", "slot_token", "slot_of", "tile_key",
+                                               "tile_first_slot", "tile_tokens", "n_tiles", "total")]
 
 
 class PzlError(RuntimeError):
@@ -57,7 +64,7 @@ class _LayerDesc(ctypes.Structure):
                 ("n_dense", ctypes.c_int32), ("dense_gate", ctypes.c_void_p),
                 ("dense_up", ctypes.c_void_p), ("dense_down", ctypes.c_void_p),
                 ("pair_format", ctypes.c_int32), ("gate_scale", ctypes.c_void_p),
-                ("up_scale", ctypes.c_void_p), ("down_scale", ctypes.c_void_p)]
+                ("up_scale", ctypes.c_void_p), ("down_scale", ctypes.c_void_p), ("h_precision", ctypes.c_int32)]
 
 
 def load():
@@ -79,6 +86,8 @@ def load():
         lib.pzl_pack.argtypes = [vp, vp, vp, vp, vp, i64, i64, vp, vp, vp]
         lib.pzl_unpack.restype = ctypes.c_int
         lib.pzl_unpack.argtypes = [vp, ctypes.c_int, i64, i64, vp, vp]
+        lib.pzl_unpack_half_x2.restype = ctypes.c_int
+        lib.pzl_unpack_half_x2.argtypes = [vp, ctypes.c_int, i64, i64, vp, vp]
         lib.pzl_tile_dense.restype = ctypes.c_int
         lib.pzl_tile_dense.argtypes = [vp, i64, i64, vp, vp]
         lib.pzl_merge_pack.restype = ctypes.c_int
@@ -97,6 +106,10 @@ def load():
         lib.pzl_moe_ffn.argtypes = [vp, vp, vp, vp, i32, i32, vp, vp, ctypes.c_size_t, vp]
         lib.pzl_moe_ffn_staged.restype = ctypes.c_int
         lib.pzl_moe_ffn_staged.argtypes = [vp, vp, vp, vp, i32, i32, vp, vp, ctypes.c_size_t, vp, vp]
+        lib.pzl_layer_h_info.restype = ctypes.c_int
+        lib.pzl_layer_h_info.argtypes = [vp, ctypes.POINTER(i32), ctypes.POINTER(i32)]
+        lib.pzl_moe_ffn_workspace_layout.restype = ctypes.c_int
+        lib.pzl_moe_ffn_workspace_layout.argtypes = [vp, i32, i32, ctypes.POINTER(_WorkspaceLayout)]
         _lib = lib
     return _lib
 
@@ -149,6 +162,17 @@ def pzl_unpack(packed, expert_pos, rows, cols, out=None):
     rc = load().pzl_unpack(_dev(packed, _BITS16, "packed"), int(expert_pos), rows, cols,
                            _dev(out, _BITS16, "out"), _stream())
     _check(rc, "pzl_unpack")
+    return out
+
+
+def pzl_unpack_half_x2(packed, expert_pos, rows, cols):
+    """The half-precision form of the decode (each weight times 2) -> float16 [rows, cols], row-major."""
+    if packed.numel() != rows * cols:
+        raise ValueError("packed tensor does not hold rows*cols elements")
+    out = torch.empty(rows, cols, dtype=torch.float16, device=packed.device)
+    rc = load().pzl_unpack_half_x2(_dev(packed, _BITS16, "packed"), int(expert_pos), rows, cols,
+                                   _dev(out, (torch.float16,), "out"), _stream())
+    _check(rc, "pzl_unpack_half_x2")
     return out
 
 
@@ -270,7 +294,7 @@ class Layer:
     """Owns a pzl_layer handle and keeps the weight tensors it references alive."""
 
     def __init__(self, d_model, d_ffn, expert_pair, expert_pos, gate, up, down, shared=(), dense=(),
-                 quantised=False):
+                 quantised=False, wide_h=False):
         """gate/up/down: one packed tensor per pair -- or, with quantised=True, one (records, scales)
         pair of tensors per pair as returned by pzl_q_pack; shared: (gate, up, down, f) tiled dense
         per shared expert; dense: (gate, up, down) tiled dense per routed expert kept unmerged."""
@@ -333,6 +357,7 @@ class Layer:
             self._scale_tables = tuple(_ptr_table(ws) for ws in scales)
             d.pair_format = 1
             d.gate_scale, d.up_scale, d.down_scale = (cast(t) for t in self._scale_tables)
+        d.h_precision = 1 if wide_h else 0
         self._h = ctypes.c_void_p()
         _check(load().pzl_layer_create(ctypes.byref(d), ctypes.byref(self._h)), "pzl_layer_create")
         self._ws = None
@@ -347,6 +372,31 @@ class Layer:
 
     def pzl_moe_ffn_workspace_bytes(self, max_tokens, top_k):
         return load().pzl_moe_ffn_workspace_bytes(self._h, int(max_tokens), int(top_k))
+
+    def h_info(self):
+        """(H of the packed pairs is one half-precision plane, wavefronts that saturated a value of H so far)."""
+        half, sat = ctypes.c_int32(), ctypes.c_int32()
+        _check(load().pzl_layer_h_info(self._h, ctypes.byref(half), ctypes.byref(sat)), "pzl_layer_h_info")
+        return bool(half.value), int(sat.value)
+
+    def routing_tables(self, T, k):
+        """The routing tables the last pzl_moe_ffn call with this (T, k) left in the layer's own
+        workspace, as numpy arrays (a read-back for inspection; synchronises)."""
+        lay = _WorkspaceLayout()
+        _check(load().pzl_moe_ffn_workspace_layout(self._h, int(T), int(k), ctypes.byref(lay)),
+               "pzl_moe_ffn_workspace_layout")
+        torch.cuda.synchronize()
+        ws = self._ws[:lay.total].cpu().numpy()
+        N = T * k
+
+        def tab(off, n):
+            return ws[off:off + 4 * n].view(np.int32).copy()
+        n_tiles = int(tab(lay.n_tiles, 1)[0])
+        return {"n_keys": lay.n_keys, "first_slot": tab(lay.first_slot, lay.n_keys + 1),
+                "streamed_count": tab(lay.streamed_count, lay.n_keys),
+                "slot_token": tab(lay.slot_token, N), "slot_of": tab(lay.slot_of, N).reshape(T, k),
+                "n_tiles": n_tiles, "tile_key": tab(lay.tile_key, n_tiles),
+                "tile_first_slot": tab(lay.tile_first_slot, n_tiles), "tile_tokens": tab(lay.tile_tokens, n_tiles)}
 
     def pzl_moe_ffn(self, x, topk_ids, topk_w, y=None, workspace=None, stage_events=None):
         """moe_ffn(x, router top-k ids/weights, packed experts) -> y (bfloat16 [T, d_model]).

@@ -39,6 +39,11 @@ struct pzl_layer {
     hipEvent_t ev_fork, ev_join;
     hipStream_t tile_stream;           // tiled kernels of the routed experts, next to the streaming ones
     hipEvent_t ev_tfork, ev_tjoin;
+    // Form of the SwiGLU output H of the packed pairs (stream_gemm.hip): one half-precision plane if
+    // no down matrix holds an exponent field above 29 (and the caller did not ask for the wide
+    // form), else two bf16 planes.  Unmerged, shared and quantised experts always use two planes.
+    bool half_h;
+    int32_t *d_counters;               // [0] largest exponent field of the down matrices, [1] waves that saturated a value of H
 };
 
 namespace pzl {
@@ -102,7 +107,9 @@ static WorkspaceLayout carve(const pzl_layer *L, int32_t T, int32_t k)
     w.tile_slot0 = p; p += align_up(mt * 4, 256);
     w.tile_n = p;     p += align_up(mt * 4, 256);
     w.n_tiles = p;    p += 256;
-    w.h_routed = p;  p += align_up(2 * N * L->d_ffn * 2, 256);
+    // routed H: two bf16 planes, or one half-precision plane if every routed expert is a packed pair in that form
+    const size_t h_planes = (L->half_h && L->n_dense == 0) ? 1 : 2;
+    w.h_routed = p;  p += align_up(h_planes * N * L->d_ffn * 2, 256);
     w.h_shared = p;
     for (int s = 0; s < L->n_shared; ++s) p += w.h_shared_each(L, T, s);
     w.o_ks_stride = (int64_t)slots * L->d_model;
@@ -308,7 +315,13 @@ int pzl_pack(const uint16_t *merged, const uint8_t *mask0, const uint8_t *mask1,
 int pzl_unpack(const uint16_t *packed, int expert_pos, int64_t rows, int64_t cols, uint16_t *out,
                void *stream)
 {
-    return launch_unpack(packed, expert_pos, rows, cols, out, (hipStream_t)stream);
+    return launch_unpack(packed, expert_pos, rows, cols, out, false, (hipStream_t)stream);
+}
+
+int pzl_unpack_half_x2(const uint16_t *packed, int expert_pos, int64_t rows, int64_t cols, uint16_t *out,
+                       void *stream)
+{
+    return launch_unpack(packed, expert_pos, rows, cols, out, true, (hipStream_t)stream);
 }
 
 size_t pzl_q_record_bytes(int64_t rows, int64_t cols) { return q_record_bytes(rows, cols); }
@@ -364,6 +377,7 @@ int pzl_layer_create(const pzl_layer_desc *desc, pzl_layer **out)
     if (fmt != 0 && fmt != 1) return PZL_EINVAL;
     if (fmt == 1 && P > 0 && (d % 128 || f % 128 || !desc->gate_scale || !desc->up_scale || !desc->down_scale))
         return PZL_EINVAL;
+    if (desc->h_precision != 0 && desc->h_precision != 1) return PZL_EINVAL;
     if (S < 0 || S > 16) return PZL_EINVAL;
     if (S > 0 && (!desc->shared_d_ffn || !desc->shared_gate || !desc->shared_up || !desc->shared_down))
         return PZL_EINVAL;
@@ -408,7 +422,8 @@ int pzl_layer_create(const pzl_layer_desc *desc, pzl_layer **out)
     const size_t sz_p = align_up((size_t)(P > 0 ? P : 1) * sizeof(void *), 256);
     const size_t sz_s = align_up((size_t)(S > 0 ? S : 1) * sizeof(void *), 256);
     const size_t sz_d = align_up((size_t)(D > 0 ? D : 1) * sizeof(void *), 256);
-    const size_t total = sz_q + 6 * sz_p + 3 * sz_s + 3 * sz_d;
+    const size_t sz_c = 256;                                   // counters (see pzl_layer.d_counters)
+    const size_t total = sz_q + 6 * sz_p + 3 * sz_s + 3 * sz_d + sz_c;
     std::vector<unsigned char> host(total, 0);
     size_t o = 0;
     memcpy(&host[o], q_of.data(), (size_t)E * 4);                     size_t o_q = o;  o += sz_q;
@@ -425,6 +440,7 @@ int pzl_layer_create(const pzl_layer_desc *desc, pzl_layer **out)
     size_t o_sg = o; if (S) memcpy(&host[o], desc->shared_gate, (size_t)S * sizeof(void *)); o += sz_s;
     size_t o_su = o; if (S) memcpy(&host[o], desc->shared_up, (size_t)S * sizeof(void *));   o += sz_s;
     size_t o_sd = o; if (S) memcpy(&host[o], desc->shared_down, (size_t)S * sizeof(void *)); o += sz_s;
+    const size_t o_c = o; o += sz_c;
 
     hipError_t e = hipMalloc(&L->d_block, total);
     if (e != hipSuccess) { set_hip_error(e); delete L; return PZL_ENOMEM; }
@@ -444,6 +460,21 @@ int pzl_layer_create(const pzl_layer_desc *desc, pzl_layer **out)
     L->d_sgate = (const uint16_t **)(base + o_sg);
     L->d_sup = (const uint16_t **)(base + o_su);
     L->d_sdown = (const uint16_t **)(base + o_sd);
+    L->d_counters = (int32_t *)(base + o_c);
+    // Half-precision H needs every used exponent field of the down matrices to be at most 29
+    // (weights below 2^15): scan them once (device work on the null stream, then one blocking copy).
+    L->half_h = false;
+    if (fmt == 0 && P > 0 && desc->h_precision == 0) {
+        int rc_scan = PZL_OK;
+        for (int p = 0; p < P && !rc_scan; ++p) rc_scan = launch_max_exp_field(desc->down[p], d, f, L->d_counters, nullptr);
+        int32_t mx = 31;
+        if (!rc_scan) {
+            e = hipMemcpy(&mx, L->d_counters, sizeof(mx), hipMemcpyDeviceToHost);
+            if (e != hipSuccess) { set_hip_error(e); rc_scan = PZL_EHIP; }
+        }
+        if (rc_scan) { pzl_layer_destroy(L); return rc_scan; }
+        L->half_h = mx <= 29;
+    }
     L->aux_stream = nullptr; L->ev_fork = nullptr; L->ev_join = nullptr;
     if (S > 0) {                                               // default priority, as every stream here
         e = hipStreamCreateWithFlags(&L->aux_stream, hipStreamNonBlocking);
@@ -451,6 +482,9 @@ int pzl_layer_create(const pzl_layer_desc *desc, pzl_layer **out)
         if (e == hipSuccess) e = hipEventCreateWithFlags(&L->ev_join, hipEventDisableTiming);
         if (e != hipSuccess) { set_hip_error(e); pzl_layer_destroy(L); return PZL_EHIP; }
     }
+    // set-up work that is not a stream operation, done here so that the FFN calls need none of it:
+    // the kernels' dynamic-LDS attribute
+    { int rc_prep = prepare_stream_kernels(); if (rc_prep) { pzl_layer_destroy(L); return rc_prep; } }
     L->tile_stream = nullptr; L->ev_tfork = nullptr; L->ev_tjoin = nullptr;
     if (L->pair_format == 0) {
         e = hipStreamCreateWithFlags(&L->tile_stream, hipStreamNonBlocking);
@@ -528,10 +562,35 @@ size_t pzl_moe_ffn_workspace_bytes(const pzl_layer *layer, int32_t max_tokens, i
     return carve(layer, max_tokens, top_k).total;
 }
 
+int pzl_moe_ffn_workspace_layout(const pzl_layer *layer, int32_t T, int32_t k, pzl_workspace_layout *out)
+{
+    if (!layer || !out || T < 0 || k < 0) return PZL_EINVAL;
+    if ((int64_t)T * k > 0x3FFFFFFF || !batch_fits(layer, T, k)) return PZL_EINVAL;
+    const WorkspaceLayout w = carve(layer, T, k);
+    *out = pzl_workspace_layout{};
+    out->n_keys = layer->n_q;
+    out->max_tiles = max_token_tiles((int64_t)T * k, layer->n_q);
+    out->streamed_count = w.cnt; out->first_slot = w.off; out->slot_token = w.slot_tok; out->slot_of = w.slot_of;
+    out->tile_key = w.tile_q; out->tile_first_slot = w.tile_slot0; out->tile_tokens = w.tile_n; out->n_tiles = w.n_tiles;
+    out->total = w.total;
+    return PZL_OK;
+}
+
 int pzl_moe_ffn(const pzl_layer *L, const uint16_t *x, const int32_t *topk_ids, const float *topk_w,
                 int32_t T, int32_t k, uint16_t *y, void *workspace, size_t workspace_bytes, void *stream)
 {
     return pzl_moe_ffn_staged(L, x, topk_ids, topk_w, T, k, y, workspace, workspace_bytes, stream, nullptr);
+}
+
+int pzl_layer_h_info(const pzl_layer *layer, int32_t *half_precision, int32_t *saturated)
+{
+    if (!layer) return PZL_EINVAL;
+    if (half_precision) *half_precision = layer->half_h ? 1 : 0;
+    if (saturated) {
+        hipError_t e = hipMemcpy(saturated, layer->d_counters + 1, sizeof(int32_t), hipMemcpyDeviceToHost);
+        if (e != hipSuccess) { set_hip_error(e); return PZL_EHIP; }
+    }
+    return PZL_OK;
 }
 
 int pzl_moe_ffn_staged(const pzl_layer *L, const uint16_t *x, const int32_t *topk_ids, const float *topk_w,
@@ -720,6 +779,7 @@ int pzl_moe_ffn_staged(const pzl_layer *L, const uint16_t *x, const int32_t *top
                 a.tile_q = rt.tile_q; a.tile_slot0 = rt.tile_slot0; a.tile_n = rt.tile_n; a.n_tiles = rt.n_tiles;
                 a.group_lo = group_base; a.group_hi = group_base + n_groups;
                 a.max_mtiles = max_token_tiles(N, L->n_q);
+                a.half_h = kind == KIND_PACKED && L->half_h; a.h_saturated = L->d_counters + 1;
                 a.tile_ctr = persistent ? rt.n_tiles + 8 + (pass * 2 + stage) * 8 : nullptr;
                 if (stage == 0) {
                     a.w_a = wg; a.w_b = wu;
@@ -742,6 +802,7 @@ int pzl_moe_ffn_staged(const pzl_layer *L, const uint16_t *x, const int32_t *top
                 a.groups_touched_max = (int)((int64_t)N < n_groups ? N : n_groups);
                 a.cnt = rt.cnt; a.off = rt.off; a.slot_tok = rt.slot_tok;
                 a.pass_wgs = stream_pass_wgs(T, kind, tile_min);
+                a.half_h = kind == KIND_PACKED && L->half_h; a.h_saturated = L->d_counters + 1;
                 if (stage == 0) {                        // gate/up + SwiGLU -> H
                     a.w_a = wg; a.w_b = wu;
                     if (kind == KIND_QUANT) { a.s_a = L->d_gscale; a.s_b = L->d_uscale; }

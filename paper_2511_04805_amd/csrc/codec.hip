@@ -1,6 +1,7 @@
 // pack / unpack / tile_dense: element-wise codec kernels (HBM-bound, offline or test use).
-// pack: Sec. 3.3.2 exponent clamp-and-shift + flag bits; unpack: Algorithm 1.
+// pack: Sec. 3.3.2 exponent clamp-and-shift + flag bits; unpack: Algorithm 1 (pzl_decode.h).
 #include "pzl_common.h"
+#include "pzl_decode.h"
 
 namespace pzl {
 
@@ -111,19 +112,12 @@ merge_pack_kernel(const uint16_t *__restrict__ wi, const uint16_t *__restrict__ 
     if (bad && n_bad) atomicAdd(n_bad, bad);
 }
 
-__device__ __forceinline__ uint32_t decode16(uint32_t W, int pos)
-{
-    // Algorithm 1, one element.
-    uint32_t mask_bit = (W >> (13 - pos)) & 1u;
-    if (mask_bit == 0u) return 0u;
-    uint32_t sign_bit = (W >> (15 - pos)) & 1u;
-    uint32_t exp_field = (W & 0x0F80u) + (112u << 7);
-    return (sign_bit << 15) | exp_field | (W & 0x007Fu);
-}
-
+// unpack: the library's one decode routine (pzl_decode.h), written out to memory.
+// HALFW: the half-precision form of the decode (each weight times 2), as the down stage of a
+// layer with half-precision H runs it.
+template <int POS, bool HALFW>
 __global__ void __launch_bounds__(256)
-unpack_kernel(const uint16_t *__restrict__ packed, int pos, int64_t rows, int64_t cols,
-              uint16_t *__restrict__ out)
+unpack_kernel(const uint16_t *__restrict__ packed, int64_t rows, int64_t cols, uint16_t *__restrict__ out)
 {
     int64_t n_chunks = rows * cols / 8;
     int64_t chunk = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -133,8 +127,7 @@ unpack_kernel(const uint16_t *__restrict__ packed, int pos, int64_t rows, int64_
     u32x4 w = *(const u32x4 *)(packed + chunk * 8);
     u32x4 o;
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
-        o[i] = decode16(w[i] & 0xFFFFu, pos) | (decode16(w[i] >> 16, pos) << 16);
+    for (int i = 0; i < 4; ++i) o[i] = decode_pair<POS>(w[i], HALFW ? decode_body_half_x2(w[i]) : decode_body(w[i]));
     *(u32x4 *)(out + row * cols + col) = o;
 }
 
@@ -147,6 +140,35 @@ tile_dense_kernel(const uint16_t *__restrict__ in, int64_t rows, int64_t cols, u
     int64_t row, col;
     chunk_coords(chunk, cols / TILE_COLS, row, col);
     *(u32x4 *)(out + chunk * 8) = *(const u32x4 *)(in + row * cols + col);
+}
+
+// Largest stored exponent field (0..31) among the words that at least one expert uses, added to
+// *max_out by atomicMax.  pzl_layer_create runs it over the down matrices: a tensor whose largest
+// field is at most 29 can be decoded to half precision (pzl_decode.h).
+__global__ void __launch_bounds__(256)
+max_exp_field_kernel(const uint16_t *__restrict__ packed, int64_t n_chunks, int32_t *__restrict__ max_out)
+{
+    uint32_t mx = 0;
+    for (int64_t chunk = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; chunk < n_chunks; chunk += (int64_t)gridDim.x * blockDim.x) {
+        u32x4 w = *(const u32x4 *)(packed + chunk * 8);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const uint32_t lo = w[i] & 0xFFFFu, hi = w[i] >> 16;
+            if (lo & 0x3000u) mx = max(mx, (lo >> 7) & 31u);
+            if (hi & 0x3000u) mx = max(mx, (hi >> 7) & 31u);
+        }
+    }
+    for (int off = 32; off > 0; off >>= 1) mx = max(mx, (uint32_t)__shfl_down((int)mx, off));
+    if ((threadIdx.x & 63) == 0 && mx) atomicMax(max_out, (int32_t)mx);
+}
+
+int launch_max_exp_field(const uint16_t *packed, int64_t rows, int64_t cols, int32_t *max_out, hipStream_t st)
+{
+    if (!packed || !max_out || rows <= 0 || cols <= 0 || (rows * cols) % 8) return PZL_EINVAL;
+    hipLaunchKernelGGL(max_exp_field_kernel, dim3(2048), dim3(256), 0, st, packed, rows * cols / 8, max_out);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) { set_hip_error(e); return PZL_EHIP; }
+    return PZL_OK;
 }
 
 static bool shape_ok(int64_t rows, int64_t cols)
@@ -173,12 +195,18 @@ int launch_pack(const uint16_t *merged, const uint8_t *m0, const uint8_t *m1, co
     return finish_launch();
 }
 
-int launch_unpack(const uint16_t *packed, int pos, int64_t rows, int64_t cols, uint16_t *out, hipStream_t st)
+int launch_unpack(const uint16_t *packed, int pos, int64_t rows, int64_t cols, uint16_t *out, bool half_x2, hipStream_t st)
 {
     if (!packed || !out || (pos != 0 && pos != 1) || !shape_ok(rows, cols)) return PZL_EINVAL;
     int64_t n_chunks = rows * cols / 8;
     unsigned blocks = (unsigned)((n_chunks + 255) / 256);
-    hipLaunchKernelGGL(unpack_kernel, dim3(blocks), dim3(256), 0, st, packed, pos, rows, cols, out);
+    if (half_x2) {
+        if (pos == 0) hipLaunchKernelGGL((unpack_kernel<0, true>), dim3(blocks), dim3(256), 0, st, packed, rows, cols, out);
+        else          hipLaunchKernelGGL((unpack_kernel<1, true>), dim3(blocks), dim3(256), 0, st, packed, rows, cols, out);
+    } else {
+        if (pos == 0) hipLaunchKernelGGL((unpack_kernel<0, false>), dim3(blocks), dim3(256), 0, st, packed, rows, cols, out);
+        else          hipLaunchKernelGGL((unpack_kernel<1, false>), dim3(blocks), dim3(256), 0, st, packed, rows, cols, out);
+    }
     return finish_launch();
 }
 

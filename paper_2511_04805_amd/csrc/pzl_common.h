@@ -49,12 +49,14 @@ void set_hip_error(hipError_t e);
 int launch_pack(const uint16_t *merged, const uint8_t *m0, const uint8_t *m1, const uint8_t *s0,
                 const uint8_t *s1, int64_t rows, int64_t cols, uint16_t *out, int32_t *n_bad,
                 hipStream_t st);
-int launch_unpack(const uint16_t *packed, int pos, int64_t rows, int64_t cols, uint16_t *out,
+int launch_unpack(const uint16_t *packed, int pos, int64_t rows, int64_t cols, uint16_t *out, bool half_x2,
                   hipStream_t st);
 int launch_tile_dense(const uint16_t *in, int64_t rows, int64_t cols, uint16_t *out, hipStream_t st);
 int launch_merge_pack(const uint16_t *wi, const uint16_t *wj, const float *norm_i, const float *norm_j,
                       int64_t rows, int64_t cols, float tau, uint16_t *out, int32_t *n_similar,
                       int32_t *n_bad, hipStream_t st);
+
+int launch_max_exp_field(const uint16_t *packed, int64_t rows, int64_t cols, int32_t *max_out, hipStream_t st);
 
 // quant_codec.hip
 size_t q_record_bytes(int64_t rows, int64_t cols);
@@ -105,6 +107,8 @@ struct StreamGroupArgs {
     int64_t o_ks_stride;          // elements between k-splits
     int32_t ksplit;
     int32_t pass_wgs;             // routed groups: workgroups that share a group's token passes (0 = 1)
+    int32_t half_h;               // packed pairs only: H is one half-precision plane (see stream_gemm.hip)
+    int32_t *h_saturated;         // ... and this device counter is bumped when a value of H saturates (may be null)
 };
 int stream_row_groups(int rows, bool down_stage);   // row groups (workgroup units) along the output rows
 #ifndef SG_WAVES_N
@@ -114,6 +118,9 @@ constexpr int STREAM_RESIDENT_WGS = 2048 / SG_WAVES_N;             // workgroups
 // kind: 0 packed pairs, 1 dense experts seeing every token (shared), 2 dense routed experts
 constexpr int KIND_PACKED = 0, KIND_SHARED = 1, KIND_UNMERGED = 2, KIND_QUANT = 3;
 int launch_stream_gateup(const StreamGroupArgs &a, int kind, hipStream_t st);
+// Sets the dynamic-LDS attribute of every streaming kernel for the current device (not a stream
+// operation; the launches would otherwise do it on their first call per device).
+int prepare_stream_kernels();
 int launch_stream_down(const StreamGroupArgs &a, int kind, hipStream_t st);
 
 // tile_gemm.hip: LDS-staged decode-GEMM on the matrix cores for large token counts per expert.
@@ -136,6 +143,8 @@ struct TileGemmArgs {
     int32_t ksplit;               // down stage only: workgroups sharing one output tile along K
     int32_t max_mtiles;           // upper bound on token tiles (grid size)
     int32_t *tile_ctr;            // routed groups: 8 zeroed counters (one per XCD) for a persistent launch that draws its tiles, or nullptr
+    int32_t half_h;               // packed pairs only: H is one half-precision plane
+    int32_t *h_saturated;         // ... and this device counter is bumped when a value of H saturates (may be null)
 };
 int launch_tile_gateup(const TileGemmArgs &a, int kind, hipStream_t st);
 int launch_tile_down(const TileGemmArgs &a, int kind, hipStream_t st);

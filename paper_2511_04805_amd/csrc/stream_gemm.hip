@@ -16,12 +16,19 @@
 // of position 0 first; longer token lists take further passes (re-streaming the weights) —
 // only a fallback, large batches belong to the tiled GEMM path.
 //
-// The SwiGLU output H is kept as two bf16 planes, hi = bf16(h) and lo = bf16(h - hi), and the
-// down stage multiplies both (the matrix cores idle in this kernel anyway).  One bf16 plane
-// alone would put the rounding of H (2^-9 relative per element) straight into y and leave no
-// margin under the 1e-2 output tolerance.
+// The SwiGLU output H needs more than bf16's 8 significant bits: one bf16 plane alone would put
+// its rounding (2^-9 relative per element) straight into y and leave no margin under the 1e-2
+// output tolerance.  Two forms (template parameter HALF):
+//   HALF   one plane of IEEE half precision (11 significant bits; values beyond +-65504 saturate and
+//          are counted).  The down stage then decodes the packed words to half precision too (the
+//          stored 5-bit exponent field is half precision's own, see pzl_decode.h; the weights come
+//          out multiplied by 2, the accumulators are halved at the end) and uses the f16 matrix
+//          instruction.  For packed pairs whose down matrices hold no exponent field above 29.
+//   !HALF  two bf16 planes, hi = bf16(h) and lo = bf16(h - hi), both multiplied by bf16 weights:
+//          twice the matrix instructions and LDS traffic in the down stage, any range.
 #include <atomic>
 #include "pzl_common.h"
+#include "pzl_decode.h"
 
 namespace pzl {
 
@@ -76,32 +83,30 @@ struct SgArgs {
     int32_t h_slot_base;
     float *o_out;
     int64_t o_ks_stride;
+    int32_t *h_saturated;        // gate/up stage, half-precision H: counts waves that saturated a value (may be null)
 };
 
-// ---- Algorithm 1 on two packed elements at a time -------------------------------------------
-// body = exponent+112 and mantissa of both halves (no carry can cross: 0x0FFF + 0x3800 < 0x8000).
-__device__ __forceinline__ uint32_t decode_body(uint32_t x) { return (x & 0x0FFF0FFFu) + 0x38003800u; }
-
-// mask bit (13-pos) of each half -> 0xFFFF / 0x0000 via a packed arithmetic shift;
-// sign bit (15-pos) of each half moved to bit 15.
-template <int POS>
-__device__ __forceinline__ uint32_t decode_pair(uint32_t x, uint32_t body)
+// One 16x32 tile (8 elements per lane) decoded for position POS: as bf16, or (HALFW) as half
+// precision times 2.  DENSE: the weights are plain bf16 already.
+template <int POS, bool DENSE, bool HALFW>
+__device__ __forceinline__ u32x4 decode_frag(u32x4 w)
 {
-    uint32_t xs = POS ? (x << 1) : x;
-    s16x2 t = __builtin_bit_cast(s16x2, x << (2 + POS));
-    t = t >> 15;
-    uint32_t m = __builtin_bit_cast(uint32_t, t);
-    return ((xs & 0x80008000u) | body) & m;
-}
-
-template <int POS, bool DENSE>
-__device__ __forceinline__ bf16x8 decode_frag(u32x4 w)
-{
-    if (DENSE) return __builtin_bit_cast(bf16x8, w);
+    if (DENSE) return w;
     u32x4 o;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) o[i] = decode_pair<POS>(w[i], decode_body(w[i]));
-    return __builtin_bit_cast(bf16x8, o);
+    for (int i = 0; i < 4; ++i) o[i] = decode_pair<POS>(w[i], HALFW ? decode_body_half_x2(w[i]) : decode_body(w[i]));
+    return o;
+}
+
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 sg_f16x2 __attribute__((ext_vector_type(2)));
+
+// acc += A (16 rows x 32 k) * B (32 k x 16 tokens); operands as raw bits, bf16 or (HALFW) half precision
+template <bool HALFW>
+__device__ __forceinline__ f32x4 mma16(u32x4 a, u32x4 b, f32x4 acc)
+{
+    if (HALFW) return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), acc, 0, 0, 0);
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), acc, 0, 0, 0);
 }
 
 typedef __bf16 sg_bf16x2 __attribute__((ext_vector_type(2)));
@@ -119,6 +124,20 @@ __device__ __forceinline__ void swiglu_split2(float g0, float u0, float g1, floa
     lo = __builtin_bit_cast(uint32_t, __builtin_convertvector((sg_f32x2){r0, r1}, sg_bf16x2));
 }
 
+// h = silu(g) * u for two elements as one pair of half-precision numbers (low half = first
+// element), rounded to nearest even; magnitudes beyond the largest half-precision number saturate
+// to it (sat is set), NaN stays NaN.
+constexpr float HALF_MAX = 65504.0f;
+__device__ __forceinline__ uint32_t swiglu_half2(float g0, float u0, float g1, float u1, bool &sat)
+{
+    float h0 = g0 * __builtin_amdgcn_rcpf(1.0f + __expf(-g0)) * u0;
+    float h1 = g1 * __builtin_amdgcn_rcpf(1.0f + __expf(-g1)) * u1;
+    const bool s0 = fabsf(h0) > HALF_MAX, s1 = fabsf(h1) > HALF_MAX;
+    h0 = s0 ? copysignf(HALF_MAX, h0) : h0;
+    h1 = s1 ? copysignf(HALF_MAX, h1) : h1;
+    sat |= s0 | s1;
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector((sg_f32x2){h0, h1}, sg_f16x2));
+}
 
 // ---- quantised pairs (3-bit codes, group scales, base-3 masks) --------------------------------
 // The appendix on combining the method with quantisation stores, per element, a 3-bit magnitude
@@ -201,7 +220,7 @@ __device__ __forceinline__ QRecord q_split(uint64_t raw, int shift, const QLuts 
 }
 
 template <int POS>
-__device__ __forceinline__ bf16x8 q_frag(const QRecord &q, const QLuts &l)
+__device__ __forceinline__ u32x4 q_frag(const QRecord &q, const QLuts &l)
 {
     const uint32_t sb = POS ? q.s1 : q.s0;
     const uint32_t mb = POS ? (q.mm >> 8) : q.mm;
@@ -212,14 +231,14 @@ __device__ __forceinline__ bf16x8 q_frag(const QRecord &q, const QLuts &l)
     o[1] = (q.mag[1] | sl[1]) & ml[1];
     o[2] = (q.mag[2] | sh[0]) & mh[0];
     o[3] = (q.mag[3] | sh[1]) & mh[1];
-    return __builtin_bit_cast(bf16x8, o);
+    return o;
 }
 
 // One pass: NT0 token tiles of position 0 followed by NT1 tiles of position 1.
 // DENSE: the weights are plain bf16 (identity decode).  ALLTOK: the group sees every token
 // (a shared expert) instead of a routed slot range.
 // QUANT: the weights are quantised records (see above) instead of 16-bit words.
-template <int STAGE, bool DENSE, bool ALLTOK, bool QUANT, int NT0, int NT1>
+template <int STAGE, bool DENSE, bool ALLTOK, bool QUANT, bool HALF, int NT0, int NT1>
 __device__ __forceinline__ void stream_pass(const SgArgs &a, const uint16_t *wa, const uint16_t *wb,
                                             const uint16_t *sa, const uint16_t *sb, const QLuts &luts,
                                             int rt0, int rt1, bool active0, bool active1,
@@ -228,9 +247,11 @@ __device__ __forceinline__ void stream_pass(const SgArgs &a, const uint16_t *wa,
                                             u32x4 *xs, int32_t *rowidx)
 {
     constexpr int NT = NT0 + NT1;
-    constexpr int PARTS = (STAGE == STAGE_DOWN) ? 2 : 1;    // activation planes (hi, lo)
+    static_assert(!HALF || (!DENSE && !QUANT), "half-precision H is for 16-bit packed pairs");
+    constexpr bool HALFW = HALF && STAGE == STAGE_DOWN;      // weights and activations of this stage in half precision
+    constexpr int PARTS = (STAGE == STAGE_DOWN && !HALF) ? 2 : 1;    // activation planes (hi, lo)
     constexpr int VT = NT * PARTS;                          // staged fragment columns per k-block
-    constexpr int KCB = (STAGE == STAGE_DOWN) ? 4 : 8;      // k-blocks per staged chunk
+    constexpr int KCB = (STAGE == STAGE_DOWN && !HALF) ? 4 : 8;      // k-blocks per staged chunk
     // (a depth of 8 for the 8-byte quantised records measured 7 % slower than 4)
     constexpr int DEPTH = (STAGE == STAGE_DOWN) ? SG_DEPTH : (QUANT ? SG_DEPTH_QUANT_GATEUP : SG_DEPTH_GATEUP);
     static_assert(VT * KCB <= SG_FRAGS, "staged chunk does not fit its LDS buffer");
@@ -355,30 +376,30 @@ __device__ __forceinline__ void stream_pass(const SgArgs &a, const uint16_t *wa,
             }
             const u32x4 *xf = xs + (buf * SG_FRAGS + s) * 64 + lane;
             if (NT0 > 0) {
-                bf16x8 wd[2];
+                u32x4 wd[2];
 #pragma unroll
-                for (int m = 0; m < 2; ++m) wd[m] = QUANT ? q_frag<0>(qr[m], luts) : decode_frag<0, DENSE>(wv[m]);
+                for (int m = 0; m < 2; ++m) wd[m] = QUANT ? q_frag<0>(qr[m], luts) : decode_frag<0, DENSE, HALFW>(wv[m]);
 #pragma unroll
                 for (int c = 0; c < NT0 * PARTS; ++c) {
-                    bf16x8 b = __builtin_bit_cast(bf16x8, xf[c * KCB * 64]);
+                    const u32x4 b = xf[c * KCB * 64];
 #pragma unroll
                     for (int m = 0; m < 2; ++m) {
                         f32x4 &dst = QUANT ? accg[m][QUANT ? c / PARTS : 0] : acc[m][c / PARTS];
-                        dst = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wd[m], b, dst, 0, 0, 0);
+                        dst = mma16<HALFW>(wd[m], b, dst);
                     }
                 }
             }
             if (NT1 > 0) {
-                bf16x8 wd[2];
+                u32x4 wd[2];
 #pragma unroll
-                for (int m = 0; m < 2; ++m) wd[m] = QUANT ? q_frag<1>(qr[m], luts) : decode_frag<1, DENSE>(wv[m]);
+                for (int m = 0; m < 2; ++m) wd[m] = QUANT ? q_frag<1>(qr[m], luts) : decode_frag<1, DENSE, HALFW>(wv[m]);
 #pragma unroll
                 for (int c = NT0 * PARTS; c < VT; ++c) {
-                    bf16x8 b = __builtin_bit_cast(bf16x8, xf[c * KCB * 64]);
+                    const u32x4 b = xf[c * KCB * 64];
 #pragma unroll
                     for (int m = 0; m < 2; ++m) {
                         f32x4 &dst = QUANT ? accg[m][QUANT ? c / PARTS : 0] : acc[m][c / PARTS];
-                        dst = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wd[m], b, dst, 0, 0, 0);
+                        dst = mma16<HALFW>(wd[m], b, dst);
                     }
                 }
             }
@@ -421,13 +442,19 @@ __device__ __forceinline__ void stream_pass(const SgArgs &a, const uint16_t *wa,
 
     // D layout of the 16x16 MFMA: lane holds rows 4*(lane/16)..+3 of column lane%16.
     const int j = lane & 15;
+    bool sat = false;
 #pragma unroll
     for (int n = 0; n < NT; ++n) {
         int within = (n < NT0) ? (tile0 + n) * 16 + j : (tile1 + n - NT0) * 16 + j;
         int cnt = (n < NT0) ? n0 : n1;
         if (within >= cnt) continue;
         int slot = ((n < NT0) ? base0 : base1) + within;
-        if (STAGE == STAGE_GATEUP) {
+        if (STAGE == STAGE_GATEUP && HALF) {
+            if (!active0) continue;
+            f32x4 g = acc[0][n], u = acc[1][n];
+            u32x2 oh = {swiglu_half2(g[0], u[0], g[1], u[1], sat), swiglu_half2(g[2], u[2], g[3], u[3], sat)};
+            *(u32x2 *)(a.h_out + (int64_t)(slot - a.h_slot_base) * a.rows + rt0 * 16 + (lane >> 4) * 4) = oh;
+        } else if (STAGE == STAGE_GATEUP) {
             if (!active0) continue;
             f32x4 g = acc[0][n], u = acc[1][n];
             uint32_t hi01, lo01, hi23, lo23;
@@ -438,14 +465,16 @@ __device__ __forceinline__ void stream_pass(const SgArgs &a, const uint16_t *wa,
             *(u32x2 *)dst = ohi;
             *(u32x2 *)(dst + a.h_plane_stride) = olo;
         } else {
+            // (half-precision weights were decoded as 2 w: halve the sums, which is exact)
             float *dst = a.o_out + (int64_t)ks * a.o_ks_stride + (int64_t)slot * a.rows + (lane >> 4) * 4;
-            if (active0) *(f32x4 *)(dst + rt0 * 16) = acc[0][n];
-            if (active1) *(f32x4 *)(dst + rt1 * 16) = acc[1][n];
+            if (active0) *(f32x4 *)(dst + rt0 * 16) = HALFW ? acc[0][n] * 0.5f : acc[0][n];
+            if (active1) *(f32x4 *)(dst + rt1 * 16) = HALFW ? acc[1][n] * 0.5f : acc[1][n];
         }
     }
+    if (STAGE == STAGE_GATEUP && HALF && a.h_saturated && __any(sat) && lane == 0) atomicAdd(a.h_saturated, 1);
 }
 
-template <int STAGE, bool DENSE, bool ALLTOK, bool QUANT>
+template <int STAGE, bool DENSE, bool ALLTOK, bool QUANT, bool HALF>
 __global__ void __launch_bounds__(SG_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2)))
 stream_kernel(SgArgs a)
 {
@@ -511,7 +540,7 @@ stream_kernel(SgArgs a)
         int c0 = min(PT, max(tiles0 - t0, 0));
         int c1 = min(PT, max(tiles1 - t1, 0));
 #define PZL_PASS(A, B)                                                                              \
-    stream_pass<STAGE, DENSE, ALLTOK, QUANT, A, B>(a, wa, wb, sa, sb, luts, rt0, rt1, active0, active1, kb0, kb1, ks, \
+    stream_pass<STAGE, DENSE, ALLTOK, QUANT, HALF, A, B>(a, wa, wb, sa, sb, luts, rt0, rt1, active0, active1, kb0, kb1, ks, \
                                                    base0, n0, t0, base1, n1, t1, xs, rowidx)
         if (DENSE) {
             switch (c0) {
@@ -543,7 +572,40 @@ int stream_row_groups(int rows, bool down_stage)
     return (rows / TILE_ROWS + per_wg - 1) / per_wg;
 }
 
-template <int STAGE, bool DENSE, bool ALLTOK, bool QUANT>
+template <bool QUANT>
+static constexpr size_t stream_lds_bytes() { return SG_LDS_BYTES + SG_MAX_TILES * 16 * sizeof(int32_t) + (QUANT ? Q_LUT_BYTES : 0); }
+
+// The dynamic LDS size beyond 64 KiB is a per-device attribute of the kernel: set once per device
+// (bit d of the mask; setting it twice from two threads is harmless).
+template <int STAGE, bool DENSE, bool ALLTOK, bool QUANT, bool HALF>
+static int set_lds_attribute()
+{
+    static std::atomic<uint64_t> attr_devices{0};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev > 63) dev = 63;       // unknown device: set it every time
+    if (dev == 63 || !((attr_devices.load(std::memory_order_relaxed) >> dev) & 1)) {
+        hipError_t e = hipFuncSetAttribute((const void *)stream_kernel<STAGE, DENSE, ALLTOK, QUANT, HALF>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)stream_lds_bytes<QUANT>());
+        if (e != hipSuccess) { set_hip_error(e); return PZL_EHIP; }
+        if (dev != 63) attr_devices.fetch_or(1ull << dev, std::memory_order_relaxed);
+    }
+    return PZL_OK;
+}
+
+int prepare_stream_kernels()
+{
+    int rc = PZL_OK;
+#define PZL_PREP(S, D, A, Q, H) if (!rc) rc = set_lds_attribute<S, D, A, Q, H>()
+    PZL_PREP(STAGE_GATEUP, false, false, false, false); PZL_PREP(STAGE_DOWN, false, false, false, false);
+    PZL_PREP(STAGE_GATEUP, false, false, false, true);  PZL_PREP(STAGE_DOWN, false, false, false, true);
+    PZL_PREP(STAGE_GATEUP, true, true, false, false);   PZL_PREP(STAGE_DOWN, true, true, false, false);
+    PZL_PREP(STAGE_GATEUP, true, false, false, false);  PZL_PREP(STAGE_DOWN, true, false, false, false);
+    PZL_PREP(STAGE_GATEUP, false, false, true, false);  PZL_PREP(STAGE_DOWN, false, false, true, false);
+#undef PZL_PREP
+    return rc;
+}
+
+template <int STAGE, bool DENSE, bool ALLTOK, bool QUANT, bool HALF = false>
 static int launch(const StreamGroupArgs &g, hipStream_t st)
 {
     if (g.n_groups <= 0) return PZL_OK;
@@ -562,6 +624,7 @@ static int launch(const StreamGroupArgs &g, hipStream_t st)
     a.dense_tokens = g.dense_tokens; a.dense_slot_base = g.dense_slot_base;
     a.h_out = g.h_out; a.h_plane_stride = g.h_plane_stride; a.h_slot_base = g.h_slot_base;
     a.o_out = g.o_out; a.o_ks_stride = g.o_ks_stride;
+    a.h_saturated = g.h_saturated;
     // One workgroup (8 waves, two per SIMD) fits a compute unit, 256 on the chip.  A launch a little
     // larger than that runs a second, partly empty round; giving each workgroup several row
     // groups instead keeps the launch to one round.
@@ -579,19 +642,10 @@ static int launch(const StreamGroupArgs &g, hipStream_t st)
     a.rg_per_wg = rg_per_wg;
     const int64_t blocks = (int64_t)g.n_groups * ((row_groups + rg_per_wg - 1) / rg_per_wg) * g.ksplit * a.n_passes;
     if (blocks > 0x7FFFFFFFLL) return PZL_EINVAL;
-    const size_t lds = SG_LDS_BYTES + SG_MAX_TILES * 16 * sizeof(int32_t) + (QUANT ? Q_LUT_BYTES : 0);
-    // the dynamic LDS size beyond 64 KiB is a per-device attribute of the kernel: set it once per
-    // device (bit d of the mask; setting it twice from two threads is harmless)
-    static std::atomic<uint64_t> attr_devices{0};
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev > 63) dev = 63;       // unknown device: set it every time
-    if (dev == 63 || !((attr_devices.load(std::memory_order_relaxed) >> dev) & 1)) {
-        hipError_t e = hipFuncSetAttribute((const void *)stream_kernel<STAGE, DENSE, ALLTOK, QUANT>,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) { set_hip_error(e); return PZL_EHIP; }
-        if (dev != 63) attr_devices.fetch_or(1ull << dev, std::memory_order_relaxed);
-    }
-    hipLaunchKernelGGL((stream_kernel<STAGE, DENSE, ALLTOK, QUANT>), dim3((unsigned)blocks), dim3(SG_THREADS), lds, st, a);
+    const size_t lds = stream_lds_bytes<QUANT>();
+    int rc_attr = set_lds_attribute<STAGE, DENSE, ALLTOK, QUANT, HALF>();
+    if (rc_attr) return rc_attr;
+    hipLaunchKernelGGL((stream_kernel<STAGE, DENSE, ALLTOK, QUANT, HALF>), dim3((unsigned)blocks), dim3(SG_THREADS), lds, st, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) { set_hip_error(e); return PZL_EHIP; }
     return PZL_OK;
@@ -601,6 +655,7 @@ static int launch(const StreamGroupArgs &g, hipStream_t st)
 //       2 = dense routed experts (kept unmerged), 3 = quantised pairs (routed)
 int launch_stream_gateup(const StreamGroupArgs &a, int kind, hipStream_t st)
 {
+    if (kind == 0 && a.half_h) return launch<STAGE_GATEUP, false, false, false, true>(a, st);
     if (kind == 0) return launch<STAGE_GATEUP, false, false, false>(a, st);
     if (kind == 1) return launch<STAGE_GATEUP, true, true, false>(a, st);
     if (kind == 3) return launch<STAGE_GATEUP, false, false, true>(a, st);
@@ -609,6 +664,7 @@ int launch_stream_gateup(const StreamGroupArgs &a, int kind, hipStream_t st)
 
 int launch_stream_down(const StreamGroupArgs &a, int kind, hipStream_t st)
 {
+    if (kind == 0 && a.half_h) return launch<STAGE_DOWN, false, false, false, true>(a, st);
     if (kind == 0) return launch<STAGE_DOWN, false, false, false>(a, st);
     if (kind == 1) return launch<STAGE_DOWN, true, true, false>(a, st);
     if (kind == 3) return launch<STAGE_DOWN, false, false, true>(a, st);

@@ -39,6 +39,7 @@
 // tiles is loose and tiles are uneven (many experts), 256 persistent workgroups that work through
 // the tile list, by fixed stride first and then drawing from a counter.
 #include "pzl_common.h"
+#include "pzl_decode.h"
 
 namespace pzl {
 
@@ -82,23 +83,13 @@ struct TgArgs {
     int64_t o_ks_stride;
     int32_t max_mtiles, n_ntiles, ksplit;
     int32_t *tile_ctr;
+    int32_t *h_saturated;
 };
 
-__device__ __forceinline__ uint32_t tg_decode_body(uint32_t x) { return (x & 0x0FFF0FFFu) + 0x38003800u; }
-
-template <int POS>
-__device__ __forceinline__ uint32_t tg_decode_pair(uint32_t x)
-{
-    uint32_t body = tg_decode_body(x);
-    uint32_t xs = POS ? (x << 1) : x;
-    s16x2 t = __builtin_bit_cast(s16x2, x << (2 + POS));
-    t = t >> 15;
-    uint32_t m = __builtin_bit_cast(uint32_t, t);
-    return ((xs & 0x80008000u) | body) & m;
-}
-
-template <int POS, bool DENSE>
-__device__ __forceinline__ bf16x8 tg_decode(u32x4 w)
+// One packed 16x32 tile decoded for position POS, as raw bits: bf16, or (HALFW) half precision
+// times 2 (pzl_decode.h).
+template <int POS, bool DENSE, bool HALFW>
+__device__ __forceinline__ u32x4 tg_decode(u32x4 w)
 {
     u32x4 o;
     if (DENSE) {
@@ -108,12 +99,21 @@ __device__ __forceinline__ bf16x8 tg_decode(u32x4 w)
         uint32_t o0, o1, o2, o3;
         asm("v_mov_b32 %0, %4\n\tv_mov_b32 %1, %5\n\tv_mov_b32 %2, %6\n\tv_mov_b32 %3, %7"
             : "=&v"(o0), "=&v"(o1), "=&v"(o2), "=&v"(o3) : "v"(w[0]), "v"(w[1]), "v"(w[2]), "v"(w[3]));
-        o = (u32x4){o0, o1, o2, o3};
-        return __builtin_bit_cast(bf16x8, o);
+        return (u32x4){o0, o1, o2, o3};
     }
 #pragma unroll
-    for (int i = 0; i < 4; ++i) o[i] = tg_decode_pair<POS>(w[i]);
-    return __builtin_bit_cast(bf16x8, o);
+    for (int i = 0; i < 4; ++i) o[i] = decode_pair<POS>(w[i], HALFW ? decode_body_half_x2(w[i]) : decode_body(w[i]));
+    return o;
+}
+
+typedef _Float16 tg_f16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 tg_f16x2 __attribute__((ext_vector_type(2)));
+
+template <bool HALFW>
+__device__ __forceinline__ f32x4 tg_mma(u32x4 a, u32x4 b, f32x4 acc)
+{
+    if (HALFW) return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(tg_f16x8, a), __builtin_bit_cast(tg_f16x8, b), acc, 0, 0, 0);
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), acc, 0, 0, 0);
 }
 
 typedef __bf16 tg_bf16x2 __attribute__((ext_vector_type(2)));
@@ -133,6 +133,20 @@ __device__ __forceinline__ void tg_swiglu_split2(float g0, float u0, float g1, f
     lo = __builtin_bit_cast(uint32_t, __builtin_convertvector((tg_f32x2){r0, r1}, tg_bf16x2));
 }
 
+// The same for the half-precision form of H: one pair of half-precision numbers, round to nearest
+// even; magnitudes beyond the largest half-precision number saturate to it (sat is set), NaN stays NaN.
+constexpr float TG_HALF_MAX = 65504.0f;
+__device__ __forceinline__ uint32_t tg_swiglu_half2(float g0, float u0, float g1, float u1, bool &sat)
+{
+    float h0 = g0 * __builtin_amdgcn_rcpf(1.0f + __expf(-g0)) * u0;
+    float h1 = g1 * __builtin_amdgcn_rcpf(1.0f + __expf(-g1)) * u1;
+    const bool s0 = fabsf(h0) > TG_HALF_MAX, s1 = fabsf(h1) > TG_HALF_MAX;
+    h0 = s0 ? copysignf(TG_HALF_MAX, h0) : h0;
+    h1 = s1 ? copysignf(TG_HALF_MAX, h1) : h1;
+    sat |= s0 | s1;
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector((tg_f32x2){h0, h1}, tg_f16x2));
+}
+
 typedef const u32x4 __attribute__((address_space(1))) *tg_gvec_ptr;
 typedef __attribute__((address_space(3))) void *tg_lds_ptr;
 
@@ -144,14 +158,19 @@ typedef __attribute__((address_space(3))) void *tg_lds_ptr;
 // POS = 2: a tile for BOTH experts of a pair (n_tok tokens of position 0 in the first half of the
 // fragments, n_tok1 tokens of position 1, whose slots follow, in the second half; CNT pairs of
 // fragments each): every packed word is loaded once and decoded for both positions.
-template <int STAGE, bool DENSE, bool ALLTOK, int POS, int CNT>
+// HALF: H is one plane of half precision (written by the gate/up stage with saturation; the down
+// stage then decodes its weights to half precision times 2, uses the f16 matrix instruction with
+// K steps of 64 like the gate/up stage, and halves its sums), instead of two bf16 planes.
+template <int STAGE, bool DENSE, bool ALLTOK, bool HALF, int POS, int CNT>
 __device__ __forceinline__ void tile_body(const TgArgs &a, const uint16_t *wa, const uint16_t *wb,
                                           int slot0, int n_tok, int n_tok1, int ntile, int ks,
                                           u32x4 *ring, int32_t *rowidx, int32_t *draw_ctr, int32_t *drawn)
 {
     constexpr bool FUSED = POS == 2;
-    constexpr int KBS = (STAGE == TSTAGE_DOWN) ? 1 : 2;      // k-blocks (of 32) per K step
-    constexpr int PARTS = (STAGE == TSTAGE_DOWN) ? 2 : 1;    // activation planes (hi, lo)
+    static_assert(!HALF || !DENSE, "half-precision H is for packed pairs");
+    constexpr bool HALFW = HALF && STAGE == TSTAGE_DOWN;     // this stage's operands are half precision
+    constexpr int KBS = (STAGE == TSTAGE_DOWN && !HALF) ? 1 : 2;      // k-blocks (of 32) per K step
+    constexpr int PARTS = (STAGE == TSTAGE_DOWN && !HALF) ? 2 : 1;    // activation planes (hi, lo)
     constexpr int NF = (FUSED ? 4 : 2) * CNT;                // token fragments in use
     constexpr int NFH = FUSED ? NF / 2 : NF;                 // ... of which the first expert's
     static_assert(NF <= TG_FRAGS, "fragments");
@@ -255,16 +274,15 @@ __device__ __forceinline__ void tile_body(const TgArgs &a, const uint16_t *wa, c
 #pragma unroll
         for (int i = 0; i < NF; ++i) acc[j][i] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
-    auto multiply = [&](const u32x4 *xs, const bf16x8 (&af)[RT], const bf16x8 (&af1)[RT], int kbo) {
+    auto multiply = [&](const u32x4 *xs, const u32x4 (&af)[RT], const u32x4 (&af1)[RT], int kbo) {
 #pragma unroll
         for (int i = 0; i < NF; ++i) {
 #pragma unroll
             for (int part = 0; part < PARTS; ++part) {
-                bf16x8 b = __builtin_bit_cast(bf16x8, xs[((part * TG_FRAGS + i) * KBS + kbo) * 64 + lane]);
+                const u32x4 b = xs[((part * TG_FRAGS + i) * KBS + kbo) * 64 + lane];
 #pragma unroll
                 for (int j = 0; j < RT; ++j)
-                    acc[j][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16((FUSED && i >= NFH) ? af1[j] : af[j], b,
-                                                                         acc[j][i], 0, 0, 0);
+                    acc[j][i] = tg_mma<HALFW>((FUSED && i >= NFH) ? af1[j] : af[j], b, acc[j][i]);
             }
         }
     };
@@ -276,15 +294,15 @@ __device__ __forceinline__ void tile_body(const TgArgs &a, const uint16_t *wa, c
 #pragma unroll
         for (int kbo = 0; kbo < KBS; ++kbo) {
             wait_w(raw, kbo, false);
-            bf16x8 af[RT], af1[RT];
+            u32x4 af[RT], af1[RT];
 #pragma unroll
             for (int j = 0; j < RT; ++j) {
-                af[j] = tg_decode<FUSED ? 0 : POS, DENSE>(raw[kbo][j]);
-                af1[j] = FUSED ? tg_decode<1, DENSE>(raw[kbo][j]) : af[j];
+                af[j] = tg_decode<FUSED ? 0 : POS, DENSE, HALFW>(raw[kbo][j]);
+                af1[j] = FUSED ? tg_decode<1, DENSE, HALFW>(raw[kbo][j]) : af[j];
             }
             if (kbo > 0) {                 // a k-block past the end (odd count): multiply by zero
                 const bool valid = kb0 + step * KBS + kbo < kb1;
-                const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
+                const u32x4 zero = {0u, 0u, 0u, 0u};
 #pragma unroll
                 for (int j = 0; j < RT; ++j) { af[j] = valid ? af[j] : zero; af1[j] = valid ? af1[j] : zero; }
             }
@@ -346,6 +364,7 @@ __device__ __forceinline__ void tile_body(const TgArgs &a, const uint16_t *wa, c
 
     // ---- epilogue: lane holds rows 4*(lane/16)..+3 of its row tile for token column lane%16 ----
     const int col = lane & 15, rsub = (lane >> 4) * 4;
+    bool sat = false;
 #pragma unroll
     for (int i = 0; i < NF; ++i) {
         int within = i * 16 + col, slot;
@@ -357,7 +376,13 @@ __device__ __forceinline__ void tile_body(const TgArgs &a, const uint16_t *wa, c
             if (within >= n_tok) continue;
             slot = slot0 + within;
         }
-        if (STAGE == TSTAGE_GATEUP) {
+        if (STAGE == TSTAGE_GATEUP && HALF) {
+            int grt = ntile * TG_WAVES + wave;
+            if (grt >= row_tiles) continue;
+            f32x4 g = acc[0][i], u = acc[1][i];
+            u32x2 oh = {tg_swiglu_half2(g[0], u[0], g[1], u[1], sat), tg_swiglu_half2(g[2], u[2], g[3], u[3], sat)};
+            *(u32x2 *)(a.h_out + (int64_t)(slot - a.h_slot_base) * a.rows + grt * 16 + rsub) = oh;
+        } else if (STAGE == TSTAGE_GATEUP) {
             int grt = ntile * TG_WAVES + wave;
             if (grt >= row_tiles) continue;
             f32x4 g = acc[0][i], u = acc[1][i];
@@ -373,16 +398,19 @@ __device__ __forceinline__ void tile_body(const TgArgs &a, const uint16_t *wa, c
             for (int j = 0; j < RT; ++j) {
                 int grt = ntile * TG_ROW_TILES + wave * RT + j;
                 if (grt >= row_tiles) continue;
-                *(f32x4 *)(a.o_out + (int64_t)ks * a.o_ks_stride + (int64_t)slot * a.rows + grt * 16 + rsub) = acc[j][i];
+                // (half-precision weights were decoded as 2 w: halve the sums, which is exact)
+                *(f32x4 *)(a.o_out + (int64_t)ks * a.o_ks_stride + (int64_t)slot * a.rows + grt * 16 + rsub) =
+                    HALFW ? acc[j][i] * 0.5f : acc[j][i];
             }
         }
     }
+    if (STAGE == TSTAGE_GATEUP && HALF && a.h_saturated && __any(sat) && lane == 0) atomicAdd(a.h_saturated, 1);
     if (draw_ctr && tid == 0) *drawn = next_draw;
 }
 
 // One token tile x one block of weight rows, given its logical id (see tile_kernel for the order).
 // Returns whether the tile ran (and, if asked to, drew the workgroup's next id into *drawn).
-template <int STAGE, bool DENSE, bool ALLTOK, bool PERSIST>
+template <int STAGE, bool DENSE, bool ALLTOK, bool PERSIST, bool HALF>
 __device__ __forceinline__ bool tile_run(const TgArgs &a, int logical, int n_mt, int gm_count, int per_ks,
                                          u32x4 *ring, int32_t *rowidx, int32_t *draw_ctr, int32_t *drawn)
 {
@@ -422,7 +450,7 @@ __device__ __forceinline__ bool tile_run(const TgArgs &a, int logical, int n_mt,
     const uint16_t *wa = a.w_a[g];
     const uint16_t *wb = (STAGE == TSTAGE_GATEUP) ? a.w_b[g] : wa;
     const int cnt = (((n_tok + 15) >> 4) + 1) >> 1;          // 1..9 pairs of token fragments
-#define PZL_TILE(P, C) tile_body<STAGE, DENSE, ALLTOK, P, C>(a, wa, wb, slot0, n_tok, n_tok1, ntile, ks, ring, rowidx, draw_ctr, drawn)
+#define PZL_TILE(P, C) tile_body<STAGE, DENSE, ALLTOK, HALF, P, C>(a, wa, wb, slot0, n_tok, n_tok1, ntile, ks, ring, rowidx, draw_ctr, drawn)
     // tiles that cover a pair exist only in one-shot launches (the grouping kernel is told so): the
     // persistent kernels, already the largest, measured 5 % slower on every tile with these
     // instantiations compiled in
@@ -450,7 +478,7 @@ __device__ __forceinline__ bool tile_run(const TgArgs &a, int logical, int n_mt,
     return true;
 }
 
-template <int STAGE, bool DENSE, bool ALLTOK, bool PERSIST>
+template <int STAGE, bool DENSE, bool ALLTOK, bool PERSIST, bool HALF>
 __global__ void __launch_bounds__(TG_THREADS) __attribute__((amdgpu_waves_per_eu(TG_WPE, TG_WPE)))
 tile_kernel(TgArgs a)
 {
@@ -508,13 +536,13 @@ tile_kernel(TgArgs a)
         if (i >= per_xcd || xcd * per_xcd + i >= total) return;
         // the tile after this one is drawn by this one unless it is a fixed one
         const bool draw = persistent && round + 1 >= fixed_rounds;
-        have_draw = tile_run<STAGE, DENSE, ALLTOK, PERSIST>(a, xcd * per_xcd + i, n_mt, gm_count, per_ks, ring, rowidx,
+        have_draw = tile_run<STAGE, DENSE, ALLTOK, PERSIST, HALF>(a, xcd * per_xcd + i, n_mt, gm_count, per_ks, ring, rowidx,
                                                    draw ? ctr : nullptr, &drawn) && draw;
         if (persistent && !have_draw) __syncthreads();     // everyone has read `drawn` before it is written again
     }
 }
 
-template <int STAGE, bool DENSE, bool ALLTOK>
+template <int STAGE, bool DENSE, bool ALLTOK, bool HALF = false>
 static int launch(const TileGemmArgs &t, hipStream_t st)
 {
     if (t.max_mtiles <= 0) return PZL_OK;
@@ -545,8 +573,9 @@ static int launch(const TileGemmArgs &t, hipStream_t st)
         a.tile_ctr = t.tile_ctr;
         if (blocks > TG_PERSISTENT_WGS) blocks = TG_PERSISTENT_WGS;
     }
-    if (a.tile_ctr) hipLaunchKernelGGL((tile_kernel<STAGE, DENSE, ALLTOK, !ALLTOK>), dim3((unsigned)blocks), dim3(TG_THREADS), 0, st, a);
-    else            hipLaunchKernelGGL((tile_kernel<STAGE, DENSE, ALLTOK, false>), dim3((unsigned)blocks), dim3(TG_THREADS), 0, st, a);
+    a.h_saturated = t.h_saturated;
+    if (a.tile_ctr) hipLaunchKernelGGL((tile_kernel<STAGE, DENSE, ALLTOK, !ALLTOK, HALF>), dim3((unsigned)blocks), dim3(TG_THREADS), 0, st, a);
+    else            hipLaunchKernelGGL((tile_kernel<STAGE, DENSE, ALLTOK, false, HALF>), dim3((unsigned)blocks), dim3(TG_THREADS), 0, st, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) { set_hip_error(e); return PZL_EHIP; }
     return PZL_OK;
@@ -556,6 +585,7 @@ static int launch(const TileGemmArgs &t, hipStream_t st)
 //       2 = dense routed experts (kept unmerged)
 int launch_tile_gateup(const TileGemmArgs &a, int kind, hipStream_t st)
 {
+    if (kind == 0 && a.half_h) return launch<TSTAGE_GATEUP, false, false, true>(a, st);
     if (kind == 0) return launch<TSTAGE_GATEUP, false, false>(a, st);
     if (kind == 1) return launch<TSTAGE_GATEUP, true, true>(a, st);
     return launch<TSTAGE_GATEUP, true, false>(a, st);
@@ -563,6 +593,7 @@ int launch_tile_gateup(const TileGemmArgs &a, int kind, hipStream_t st)
 
 int launch_tile_down(const TileGemmArgs &a, int kind, hipStream_t st)
 {
+    if (kind == 0 && a.half_h) return launch<TSTAGE_DOWN, false, false, true>(a, st);
     if (kind == 0) return launch<TSTAGE_DOWN, false, false>(a, st);
     if (kind == 1) return launch<TSTAGE_DOWN, true, true>(a, st);
     return launch<TSTAGE_DOWN, true, false>(a, st);

@@ -171,16 +171,19 @@ def test_q_layer_rejects_bad_shapes(binding):
 
 def test_q_ffn_mixtral_shaped_decode(oracle, binding):
     """The benchmark's layer shape and batch (Mixtral-8x7B-shaped, T = 64) in the quantised format,
-    in the launch configuration bench.py times; the oracle on sampled token rows (only the experts
-    those rows use are reconstructed in fp64: 0.47 GB per matrix)."""
+    in the launch configuration bench.py times.  The oracle runs on rows picked from the call's own
+    routing tables: of every expert its first, middle and last slot and the slots on either side
+    of its 16-token fragment borders (every expert is reconstructed in fp64: 0.47 GB per matrix)."""
+    from test_gpu_configs import rows_reaching_every_tile
     cfg = synth.CONFIGS["mixtral_decode"]
     T = 64
     x = synth.tokens(cfg, T)
     ids, w = synth.routing(cfg, T)
-    rows = np.array([0, 31, 63])
-    say("quantised FFN, %s T=%d, oracle on rows %s" % (cfg.name, T, rows.tolist()))
-    case = QCase(cfg, oracle, binding, needed_experts=np.unique(ids[rows]).tolist())
+    case = QCase(cfg, oracle, binding)
     y = case.gpu(x, ids, w)
+    rows, units, covered = rows_reaching_every_tile(case.layer.routing_tables(T, cfg.top_k), T)
+    say("quantised FFN, %s T=%d: %d streamed experts, all reached at their edges by %d rows" % (cfg.name, T, units, len(rows)))
+    assert units == cfg.n_experts and covered == units and len(rows) >= 12
     y64 = case.ref(x[rows], ids[rows], w[rows])
     ok, worst = tolerance_ok(y[rows], y64)
     say("  worst err / bound = %.3f" % worst)
