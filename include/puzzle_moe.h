@@ -169,8 +169,8 @@ typedef struct pzl_layer_desc {
 typedef struct pzl_layer pzl_layer;
 
 /* Validates the description and builds the layer's device tables (the only allocation the
- * library performs; it also sets the kernels' launch attributes).  The device current at the call
- * is the layer's device.  The layer also
+ * library performs; it also sets the kernels' launch attributes and looks up the static scratch
+ * array of pzl_moe_ffn_static).  The device current at the call is the layer's device.  The layer also
  * owns up to two further streams (default priority) with two events each: pzl_moe_ffn runs the
  * shared experts on one and, for batches that use both kinds of kernel, the tiled kernels of
  * the routed experts on the other, next to the rest of the call, forked from and joined back
@@ -282,6 +282,26 @@ int pzl_moe_ffn_workspace_layout(const pzl_layer *layer, int32_t T, int32_t k, p
 int pzl_moe_ffn(const pzl_layer *layer, const uint16_t *x, const int32_t *topk_ids,
                 const float *topk_w, int32_t T, int32_t k, uint16_t *y,
                 void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * moe_ffn_static — pzl_moe_ffn for callers that cannot allocate and have no workspace to pass: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same inputs,
+ * same outputs, same kernels and the same results bit for bit as pzl_moe_ffn; the workspace is a
+ * static array of PZL_STATIC_SCRATCH_BYTES in device memory that belongs to the library (every GPU
+ * the library runs on holds its own copy until the process ends; its address on the layer's
+ * device is looked up once, in pzl_layer_create).  The call allocates and frees nothing.
+ *   - A batch whose workspace (pzl_moe_ffn_workspace_bytes(layer, T, k)) exceeds the array is
+ *     refused with PZL_ENOSPC and nothing is launched.  32 MiB hold a Mixtral-8x7B-shaped layer
+ *     up to about 100 tokens at top-2; larger batches take pzl_moe_ffn with a caller workspace.
+ *   - All calls on one GPU share that GPU's array, on whatever layer and stream: calls that
+ *     overlap in time on one GPU race.  Calls queued on one stream are fine.  The array keeps the
+ *     previous call's contents; the call clears what it needs cleared inside its kernels.
+ */
+#define PZL_STATIC_SCRATCH_BYTES (32u << 20)
+int pzl_moe_ffn_static(const pzl_layer *layer, const uint16_t *x, const int32_t *topk_ids,
+                       const float *topk_w, int32_t T, int32_t k, uint16_t *y, void *stream);
+/* PZL_STATIC_SCRATCH_BYTES as the loaded library was built with. */
+size_t pzl_moe_ffn_static_max_bytes(void);
 
 /*
  * router_topk — the step in front of pzl_moe_ffn, so that a whole MoE block runs on the device.

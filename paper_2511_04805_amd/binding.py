@@ -20,7 +20,7 @@ EXPORTS = ("pzl_abi_version", "pzl_strerror", "pzl_last_hip_error", "pzl_packed_
            "pzl_unpack", "pzl_unpack_half_x2", "pzl_tile_dense", "pzl_merge_pack", "pzl_router_topk",
            "pzl_q_record_bytes", "pzl_q_scale_bytes", "pzl_q_pack", "pzl_q_unpack", "pzl_layer_create", "pzl_layer_destroy",
            "pzl_moe_ffn_plan", "pzl_moe_ffn_workspace_bytes", "pzl_moe_ffn", "pzl_moe_ffn_staged",
-           "pzl_moe_ffn_workspace_layout", "pzl_layer_h_info")
+           "pzl_moe_ffn_static", "pzl_moe_ffn_static_max_bytes", "pzl_moe_ffn_workspace_layout", "pzl_layer_h_info")
 
 STAGES = ("route", "gateup", "down", "shared", "combine")
 
@@ -110,6 +110,9 @@ def load():
         lib.pzl_layer_h_info.argtypes = [vp, ctypes.POINTER(i32), ctypes.POINTER(i32)]
         lib.pzl_moe_ffn_workspace_layout.restype = ctypes.c_int
         lib.pzl_moe_ffn_workspace_layout.argtypes = [vp, i32, i32, ctypes.POINTER(_WorkspaceLayout)]
+        lib.pzl_moe_ffn_static.restype = ctypes.c_int
+        lib.pzl_moe_ffn_static.argtypes = [vp, vp, vp, vp, i32, i32, vp, vp]
+        lib.pzl_moe_ffn_static_max_bytes.restype = ctypes.c_size_t
         _lib = lib
     return _lib
 
@@ -398,6 +401,15 @@ class Layer:
                 "n_tiles": n_tiles, "tile_key": tab(lay.tile_key, n_tiles),
                 "tile_first_slot": tab(lay.tile_first_slot, n_tiles), "tile_tokens": tab(lay.tile_tokens, n_tiles)}
 
+    def pzl_moe_ffn_static(self, x, topk_ids, topk_w, y):
+        """pzl_moe_ffn on the library's static scratch array: no workspace, no allocation (y is the caller's)."""
+        T = x.shape[0]
+        k = topk_ids.shape[1] if topk_ids.dim() == 2 else 0
+        _check(load().pzl_moe_ffn_static(self._h, _dev(x, _BITS16, "x"), _dev(topk_ids, (torch.int32,), "topk_ids"),
+                                         _dev(topk_w, (torch.float32,), "topk_w"), T, k, _dev(y, _BITS16, "y"),
+                                         _stream()), "pzl_moe_ffn_static")
+        return y
+
     def pzl_moe_ffn(self, x, topk_ids, topk_w, y=None, workspace=None, stage_events=None):
         """moe_ffn(x, router top-k ids/weights, packed experts) -> y (bfloat16 [T, d_model]).
 
@@ -423,6 +435,10 @@ class Layer:
             _check(load().pzl_moe_ffn_staged(*args, ctypes.cast(stage_events, ctypes.c_void_p)),
                    "pzl_moe_ffn_staged")
         return y
+
+
+def pzl_moe_ffn_static_max_bytes():
+    return load().pzl_moe_ffn_static_max_bytes()
 
 
 def tiled_to_logical(tiled, rows, cols):

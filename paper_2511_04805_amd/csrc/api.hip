@@ -2,9 +2,16 @@
 // carving and the launch sequence of pzl_moe_ffn.  No kernel lives here.
 #include "pzl_common.h"
 
+#include <mutex>
 #include <new>
 #include <string.h>
 #include <vector>
+
+// Scratch memory of pzl_moe_ffn_static, the entry point for callers that cannot allocate: one
+// array per GPU, part of the loaded code object, held until the process ends.  In host code the
+// name below is only a handle for hipGetSymbolAddress: the device address is looked up once per
+// device (static_scratch_of) and that pointer is what kernels and copies get.
+static __device__ __align__(256) unsigned char scratch[PZL_STATIC_SCRATCH_BYTES];
 
 namespace pzl {
 
@@ -18,6 +25,25 @@ void set_hip_error(hipError_t e)
 }
 
 static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// Device address of this GPU's copy of `scratch`; looked up on the first call per device (with
+// that device current) and kept.  Returns nullptr (and records the HIP error) on failure.
+static void *static_scratch_of_current_device()
+{
+    static std::mutex mu;
+    static void *ptr_of[64] = {};
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess || dev < 0 || dev >= 64) { set_hip_error(e != hipSuccess ? e : hipErrorInvalidDevice); return nullptr; }
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ptr_of[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) { set_hip_error(e != hipSuccess ? e : hipErrorInvalidSymbol); return nullptr; }
+        ptr_of[dev] = p;
+    }
+    return ptr_of[dev];
+}
 
 }  // namespace pzl
 
@@ -39,6 +65,7 @@ struct pzl_layer {
     hipEvent_t ev_fork, ev_join;
     hipStream_t tile_stream;           // tiled kernels of the routed experts, next to the streaming ones
     hipEvent_t ev_tfork, ev_tjoin;
+    void *static_scratch;              // this device's copy of the library's static scratch array (pzl_moe_ffn_static)
     // Form of the SwiGLU output H of the packed pairs (stream_gemm.hip): one half-precision plane if
     // no down matrix holds an exponent field above 29 (and the caller did not ask for the wide
     // form), else two bf16 planes.  Unmerged, shared and quantised experts always use two planes.
@@ -289,7 +316,7 @@ const char *pzl_strerror(int rc)
     switch (rc) {
         case PZL_OK: return "ok";
         case PZL_EINVAL: return "invalid argument (null pointer, bad shape, bad position or pair map)";
-        case PZL_ENOSPC: return "workspace too small";
+        case PZL_ENOSPC: return "workspace too small (pzl_moe_ffn_static: the batch needs more than the static scratch array holds)";
         case PZL_EHIP: return "HIP call or kernel launch failed (see pzl_last_hip_error)";
         case PZL_ENOMEM: return "device allocation failed";
         default: return "unknown error code";
@@ -483,7 +510,9 @@ int pzl_layer_create(const pzl_layer_desc *desc, pzl_layer **out)
         if (e != hipSuccess) { set_hip_error(e); pzl_layer_destroy(L); return PZL_EHIP; }
     }
     // set-up work that is not a stream operation, done here so that the FFN calls need none of it:
-    // the kernels' dynamic-LDS attribute
+    // the address of this device's static scratch array and the kernels' dynamic-LDS attribute
+    L->static_scratch = static_scratch_of_current_device();
+    if (!L->static_scratch) { pzl_layer_destroy(L); return PZL_EHIP; }
     { int rc_prep = prepare_stream_kernels(); if (rc_prep) { pzl_layer_destroy(L); return rc_prep; } }
     L->tile_stream = nullptr; L->ev_tfork = nullptr; L->ev_tjoin = nullptr;
     if (L->pair_format == 0) {
@@ -582,6 +611,17 @@ int pzl_moe_ffn(const pzl_layer *L, const uint16_t *x, const int32_t *topk_ids, 
     return pzl_moe_ffn_staged(L, x, topk_ids, topk_w, T, k, y, workspace, workspace_bytes, stream, nullptr);
 }
 
+int pzl_moe_ffn_static(const pzl_layer *L, const uint16_t *x, const int32_t *topk_ids, const float *topk_w,
+                       int32_t T, int32_t k, uint16_t *y, void *stream)
+{
+    if (!L || T < 0 || k < 0) return PZL_EINVAL;
+    if (T == 0) return PZL_OK;
+    if ((int64_t)T * k > 0x3FFFFFFF || !batch_fits(L, T, k)) return PZL_EINVAL;
+    if (carve(L, T, k).total > (size_t)PZL_STATIC_SCRATCH_BYTES) return PZL_ENOSPC;
+    // L->static_scratch is the device address found at pzl_layer_create; never the array's name
+    return pzl_moe_ffn_staged(L, x, topk_ids, topk_w, T, k, y, L->static_scratch, PZL_STATIC_SCRATCH_BYTES, stream, nullptr);
+}
+
 int pzl_layer_h_info(const pzl_layer *layer, int32_t *half_precision, int32_t *saturated)
 {
     if (!layer) return PZL_EINVAL;
@@ -592,6 +632,8 @@ int pzl_layer_h_info(const pzl_layer *layer, int32_t *half_precision, int32_t *s
     }
     return PZL_OK;
 }
+
+size_t pzl_moe_ffn_static_max_bytes(void) { return (size_t)PZL_STATIC_SCRATCH_BYTES; }
 
 int pzl_moe_ffn_staged(const pzl_layer *L, const uint16_t *x, const int32_t *topk_ids, const float *topk_w,
                        int32_t T, int32_t k, uint16_t *y, void *workspace, size_t workspace_bytes,
