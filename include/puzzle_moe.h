@@ -213,6 +213,8 @@ typedef struct pzl_plan {
     int32_t sweep_wgs_unmerged;   /* ... per unmerged expert */
     int32_t shared_token_tiles[16];   /* tiled_shared: token tiles per shared expert ... */
     int32_t shared_tile_tokens[16];   /* ... and tokens per tile (a multiple of 16, at most 288) */
+    int32_t grouping_in_kernel;   /* small streaming-only batches: no grouping kernel is launched, the gate/up
+                                     kernel of the packed pairs groups the (token, choice) list itself */
 } pzl_plan;
 
 /* Returns PZL_OK, or PZL_EINVAL for a null pointer, a negative T or k, or a shape that

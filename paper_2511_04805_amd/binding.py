@@ -35,7 +35,8 @@ class _Plan(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in ("shared_stream", "hybrid", "tile_min", "persistent", "tile_stream",
                                               "ksplit", "ksplit_shared", "tiled_shared", "sweep_wgs_packed",
                                               "sweep_wgs_unmerged")] + \
-               [("shared_token_tiles", ctypes.c_int32 * 16), ("shared_tile_tokens", ctypes.c_int32 * 16)]
+               [("shared_token_tiles", ctypes.c_int32 * 16), ("shared_tile_tokens", ctypes.c_int32 * 16),
+                ("grouping_in_kernel", ctypes.c_int32)]
 
 
 class _WorkspaceLayout(ctypes.Structure):
@@ -274,6 +275,7 @@ def pzl_moe_ffn_plan(n_experts, d_model, d_ffn, T, k, shared_d_ffn=(), n_unmerge
     out = {n: int(getattr(plan, n)) for n, _ in _Plan._fields_[:10]}
     out["shared_token_tiles"] = list(plan.shared_token_tiles)[:len(shared_d_ffn)]
     out["shared_tile_tokens"] = list(plan.shared_tile_tokens)[:len(shared_d_ffn)]
+    out["grouping_in_kernel"] = int(plan.grouping_in_kernel)
     return out
 
 

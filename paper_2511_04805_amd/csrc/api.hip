@@ -157,7 +157,7 @@ static WorkspaceLayout carve(const pzl_layer *L, int32_t T, int32_t k)
 static int choose_tile_ksplit(int64_t token_tiles, int64_t slots, int rows, int kdim, int min_steps = 8)
 {
     if (token_tiles < 1) token_tiles = 1;
-    const double wgs = (double)token_tiles * ((rows + 255) / 256);
+    const double wgs = (double)token_tiles * ((rows + TILE_WG_DOWN_ROWS - 1) / TILE_WG_DOWN_ROWS) / TILE_WGS_PER_CU;
     const double steps = kdim / TILE_COLS;
     double fill = (double)slots / ((double)token_tiles * TILE_MAX_TOKENS);
     if (fill > 1.0) fill = 1.0;
@@ -189,7 +189,7 @@ static int choose_tile_ksplit(int64_t token_tiles, int64_t slots, int rows, int 
 static int shared_token_parts(int32_t T, int n_same, int f, int target_wgs, bool chip_busy)
 {
     int parts = (T + TILE_MAX_TOKENS - 1) / TILE_MAX_TOKENS;
-    const int per_part = n_same * ((f + 127) / 128);              // gate/up workgroups per token tile
+    const int per_part = n_same * ((f + TILE_WG_FEATURES - 1) / TILE_WG_FEATURES) / TILE_WGS_PER_CU;   // gate/up workgroups (in units of a compute unit's share) per token tile
     int want = (target_wgs + per_part / 2) / per_part;
     // at least 48 tokens per tile; 36 (rounded up to 48 by the fragment size) next to routed
     // kernels that leave compute units idle, which lets 72-95 tokens be two tiles (60 experts +
@@ -255,6 +255,7 @@ struct Plan {
     int tile_min;          // tokens of an expert from which its pair is tiled
     int ksplit, ksplit_shared;
     int shared_wgs;        // workgroups aimed at for the shared experts' tiled gate/up launch
+    bool fused_route;      // no grouping kernel: the streaming gate/up kernel of the packed pairs groups the list itself
 };
 
 static Plan make_plan(const pzl_layer *L, int32_t T, int32_t k, bool staged)
@@ -270,6 +271,11 @@ static Plan make_plan(const pzl_layer *L, int32_t T, int32_t k, bool staged)
     pl.tiled_shared = T >= TILED_MIN_TOKENS_SHARED;
     pl.persistent = L->n_q >= 32 && N <= (int64_t)256 * L->n_q;
     pl.tile_overlap = pl.hybrid && !staged && E64 >= 32 && N < 40 * E64;
+    // Small batches that only stream (no token tiles to cut): a grouping kernel in front of the first
+    // weight-streaming kernel is 5-6 us of a 120-240 us step; the gate/up kernel of the packed pairs
+    // sorts the few hundred entries itself instead (stream_gemm.hip, route_in_block).
+    pl.fused_route = !pl.hybrid && L->pair_format == 0 && L->n_pairs > 0 && N >= 1 &&
+                     N <= STREAM_FUSED_ROUTE_MAX_FLAT && L->n_q <= STREAM_FUSED_ROUTE_MAX_KEYS;
 
     const int ns = L->n_shared > 0 ? L->n_shared : 1;
     pl.shared_wgs = shared_target_wgs(L, k, pl.hybrid && pl.persistent);
@@ -566,6 +572,7 @@ int pzl_moe_ffn_plan(const pzl_layer_shape *shape, int32_t T, int32_t k, pzl_pla
     out->shared_stream = pl.overlap; out->hybrid = pl.hybrid; out->tile_min = pl.hybrid ? pl.tile_min : 0;
     out->persistent = pl.hybrid && pl.persistent; out->tile_stream = pl.tile_overlap;
     out->ksplit = pl.ksplit; out->ksplit_shared = S > 0 ? pl.ksplit_shared : 0; out->tiled_shared = S > 0 && pl.tiled_shared;
+    out->grouping_in_kernel = pl.fused_route;
     out->sweep_wgs_packed = stream_pass_wgs(T, L.pair_format == 1 ? KIND_QUANT : KIND_PACKED, pl.tile_min);
     out->sweep_wgs_unmerged = stream_pass_wgs(T, KIND_UNMERGED, pl.tile_min);
     for (int s = 0; s < S;) {                                // experts of equal width share a launch
@@ -776,9 +783,11 @@ int pzl_moe_ffn_staged(const pzl_layer *L, const uint16_t *x, const int32_t *top
     if (rc) return rc;
     // one-shot launches may give both experts of a pair one tile (row groups of gate/up tell the
     // grouping kernel how long the launch is); persistent launches do not have those kernels
-    rc = launch_route(topk_ids, N, k, L->n_experts, L->n_q, L->d_q_of_expert, rt, tile_min,
-                      persistent ? 0 : (L->d_ffn + 127) / 128, (L->d_ffn + 127) / 128, st);
-    if (rc) return rc;
+    if (!pl.fused_route) {
+        rc = launch_route(topk_ids, N, k, L->n_experts, L->n_q, L->d_q_of_expert, rt, tile_min,
+                          persistent ? 0 : (L->d_ffn + 127) / 128, (L->d_ffn + 127) / 128, st);   // (in units of a compute unit's share of a launch)
+        if (rc) return rc;
+    }
     if ((rc = mark(PZL_STAGE_ROUTE, 1))) return rc;
     // The tiled and the streaming kernels of the routed experts work on disjoint pairs (the
     // grouping kernel gave each pair to one of them), so the tiled ones run on a stream of their
@@ -851,6 +860,11 @@ int pzl_moe_ffn_staged(const pzl_layer *L, const uint16_t *x, const int32_t *top
                     a.rows = L->d_ffn; a.kdim = L->d_model; a.ksplit = 1;
                     a.act = x; a.act_is_x = 1; a.act_slot_base = 0;
                     a.h_out = h_routed; a.h_slot_base = 0; a.h_plane_stride = h_plane;
+                    if (pl.fused_route && kind == KIND_PACKED) {      // this launch groups the list and writes the tables
+                        a.route_ids = topk_ids; a.route_q_of_expert = L->d_q_of_expert;
+                        a.route_n_flat = N; a.route_k = k; a.route_n_experts = L->n_experts; a.route_n_keys = L->n_q;
+                        a.route_slot_of = rt.slot_of;
+                    }
                     rc = launch_stream_gateup(a, kind, st);
                 } else {                                 // down -> partial sums
                     a.w_a = wd; a.w_b = nullptr;

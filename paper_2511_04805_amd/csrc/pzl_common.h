@@ -109,7 +109,15 @@ struct StreamGroupArgs {
     int32_t pass_wgs;             // routed groups: workgroups that share a group's token passes (0 = 1)
     int32_t half_h;               // packed pairs only: H is one half-precision plane (see stream_gemm.hip)
     int32_t *h_saturated;         // ... and this device counter is bumped when a value of H saturates (may be null)
+    // Gate/up launch of packed pairs in a small batch: the kernel groups the (token, choice) list
+    // itself and writes cnt / off / slot_tok (above) and slot_of for the kernels that follow; no
+    // grouping kernel runs before it.  route_ids == nullptr: the tables were written beforehand.
+    const int32_t *route_ids, *route_q_of_expert;
+    int32_t route_n_flat, route_k, route_n_experts, route_n_keys;
+    int32_t *route_slot_of;
 };
+constexpr int STREAM_FUSED_ROUTE_MAX_FLAT = 512;   // (token, choice) entries the gate/up kernel can group by itself
+constexpr int STREAM_FUSED_ROUTE_MAX_KEYS = 128;   // ... and routing keys
 int stream_row_groups(int rows, bool down_stage);   // row groups (workgroup units) along the output rows
 #ifndef SG_WAVES_N
 #define SG_WAVES_N 8
@@ -124,6 +132,12 @@ int prepare_stream_kernels();
 int launch_stream_down(const StreamGroupArgs &a, int kind, hipStream_t st);
 
 // tile_gemm.hip: LDS-staged decode-GEMM on the matrix cores for large token counts per expert.
+#ifndef TG_WAVES_N
+#define TG_WAVES_N 8
+#endif
+constexpr int TILE_WG_FEATURES = TG_WAVES_N * 16;    // gate/up stage: features (rows of gate and of up) per workgroup
+constexpr int TILE_WG_DOWN_ROWS = TG_WAVES_N * 32;   // down stage: weight rows per workgroup
+constexpr int TILE_WGS_PER_CU = 8 / TG_WAVES_N;      // workgroups a compute unit holds (8 waves)
 struct TileGemmArgs {
     const uint16_t *const *w_a;   // device array: gate (gate/up stage) or down (down stage)
     const uint16_t *const *w_b;   // device array: up, or nullptr

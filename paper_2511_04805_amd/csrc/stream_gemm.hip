@@ -65,6 +65,13 @@ constexpr int SG_LDS_BYTES = 2 * SG_FRAGS * 64 * 16;   // 64 KiB, two buffers
 constexpr int STAGE_GATEUP = 0, STAGE_DOWN = 1;
 constexpr int SG_RESIDENT_WGS = 2048 / SG_WAVES;   // 256 CUs x 8 waves
 
+// Routing done by the gate/up kernel itself (FUSE, small batches; see route_in_block).
+struct SgRoute {
+    const int32_t *ids, *q_of_expert;        // [n_flat] expert ids, [n_experts] expert -> routing key
+    int32_t n_flat, k, n_experts, n_keys;
+    int32_t *cnt, *off, *slot_tok, *slot_of; // the workspace's routing tables, written by workgroup 0 for the kernels that follow
+};
+
 struct SgArgs {
     const uint16_t *const *w_a;
     const uint16_t *const *w_b;
@@ -84,6 +91,7 @@ struct SgArgs {
     float *o_out;
     int64_t o_ks_stride;
     int32_t *h_saturated;        // gate/up stage, half-precision H: counts waves that saturated a value (may be null)
+    SgRoute route;               // FUSE only
 };
 
 // One 16x32 tile (8 elements per lane) decoded for position POS: as bf16, or (HALFW) as half
@@ -234,6 +242,78 @@ __device__ __forceinline__ u32x4 q_frag(const QRecord &q, const QLuts &l)
     return o;
 }
 
+// ---- grouping of the (token, choice) list inside the gate/up kernel (small batches) -----------
+// A decode-time batch has a few hundred (token, choice) entries at most.  A separate grouping
+// kernel in front of the first weight-streaming kernel costs about 6 us of a 240 us step; instead
+// every workgroup of that kernel sorts the list by itself, in LDS, before it starts streaming (all
+// workgroups do the same deterministic work and arrive at the same tables), and workgroup 0 also
+// writes the tables to the workspace for the kernels that follow.  Counting sort by routing key,
+// stable: a key's slots are in ascending (token, choice) order.  Entry i belongs to thread i
+// (n_flat <= FR_MAX_N = the workgroup's size); a wave ranks its 64 entries with one ballot per
+// distinct key, the waves' counts are combined through a small table in LDS.
+constexpr int FR_MAX_N = SG_THREADS;
+constexpr int FR_MAX_KEYS = 128;
+static_assert(FR_MAX_N == STREAM_FUSED_ROUTE_MAX_FLAT && FR_MAX_KEYS == STREAM_FUSED_ROUTE_MAX_KEYS, "limits the host checks");
+constexpr int FR_LDS_INTS = FR_MAX_N + 2 * FR_MAX_KEYS + SG_WAVES * FR_MAX_KEYS;   // slot_tok, cnt, off, per-wave counts
+
+__device__ __forceinline__ void route_in_block(const SgRoute &r, int32_t *lds, const int32_t *&cnt, const int32_t *&off,
+                                               const int32_t *&slot_tok)
+{
+    int32_t *l_tok = lds, *l_cnt = lds + FR_MAX_N, *l_off = l_cnt + FR_MAX_KEYS, *l_wave = l_off + FR_MAX_KEYS;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const bool writer = blockIdx.x == 0;
+    for (int i = tid; i < SG_WAVES * FR_MAX_KEYS; i += SG_THREADS) l_wave[i] = 0;
+    int key = -1;
+    if (tid < r.n_flat) {
+        const int e = r.ids[tid];
+        if (e >= 0 && e < r.n_experts) key = r.q_of_expert[e];      // ids outside [0, E) are ignored
+    }
+    __syncthreads();
+    // rank among the wave's entries of the same key (ascending lane), and the wave's count per key
+    int rank = 0;
+    uint64_t todo = __ballot(key >= 0);
+    while (todo) {
+        const int first = __builtin_ctzll(todo);
+        const int v = __builtin_amdgcn_readlane(key, first);
+        const uint64_t same = __ballot(key == v);
+        if (key == v) rank = __popcll(same & ((1ull << lane) - 1ull));
+        if (lane == first) l_wave[wave * FR_MAX_KEYS + v] = __popcll(same);
+        todo &= ~same;
+    }
+    __syncthreads();
+    // per key: first slot of each wave's entries (relative to the key's first slot) and the total
+    for (int q = tid; q < r.n_keys; q += SG_THREADS) {
+        int run = 0;
+        for (int w = 0; w < SG_WAVES; ++w) { const int c = l_wave[w * FR_MAX_KEYS + q]; l_wave[w * FR_MAX_KEYS + q] = run; run += c; }
+        l_cnt[q] = run;
+    }
+    __syncthreads();
+    if (wave == 0) {                       // exclusive scan of the counts (at most 128 keys: two per lane)
+        const int c0 = 2 * lane < r.n_keys ? l_cnt[2 * lane] : 0, c1 = 2 * lane + 1 < r.n_keys ? l_cnt[2 * lane + 1] : 0;
+        int inc = c0 + c1;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) { const int u = __shfl_up(inc, d); if (lane >= d) inc += u; }
+        const int ex = inc - c0 - c1;
+        if (2 * lane < r.n_keys) l_off[2 * lane] = ex;
+        if (2 * lane + 1 < r.n_keys) l_off[2 * lane + 1] = ex + c0;
+        if (writer && lane == 63) r.off[r.n_keys] = inc;
+    }
+    __syncthreads();
+    if (tid < r.n_flat) {
+        int slot = -1;
+        if (key >= 0) {
+            slot = l_off[key] + l_wave[wave * FR_MAX_KEYS + key] + rank;
+            l_tok[slot] = tid / r.k;
+            if (writer) r.slot_tok[slot] = tid / r.k;
+        }
+        if (writer) r.slot_of[tid] = slot;
+    }
+    if (writer)
+        for (int q = tid; q < r.n_keys; q += SG_THREADS) { r.cnt[q] = l_cnt[q]; r.off[q] = l_off[q]; }
+    __syncthreads();
+    cnt = l_cnt; off = l_off; slot_tok = l_tok;
+}
+
 // One pass: NT0 token tiles of position 0 followed by NT1 tiles of position 1.
 // DENSE: the weights are plain bf16 (identity decode).  ALLTOK: the group sees every token
 // (a shared expert) instead of a routed slot range.
@@ -244,7 +324,7 @@ __device__ __forceinline__ void stream_pass(const SgArgs &a, const uint16_t *wa,
                                             int rt0, int rt1, bool active0, bool active1,
                                             int kb0, int kb1, int ks,
                                             int base0, int n0, int tile0, int base1, int n1, int tile1,
-                                            u32x4 *xs, int32_t *rowidx)
+                                            u32x4 *xs, int32_t *rowidx, const int32_t *slot_tok)
 {
     constexpr int NT = NT0 + NT1;
     static_assert(!HALF || (!DENSE && !QUANT), "half-precision H is for 16-bit packed pairs");
@@ -267,7 +347,7 @@ __device__ __forceinline__ void stream_pass(const SgArgs &a, const uint16_t *wa,
         if (nt < NT0) slot = base0 + min((tile0 + nt) * 16 + j, n0 - 1);
         else          slot = base1 + min((tile1 + nt - NT0) * 16 + j, n1 - 1);
         int row;
-        if (a.act_is_x) row = ALLTOK ? (slot - base0) : a.slot_tok[slot];
+        if (a.act_is_x) row = ALLTOK ? (slot - base0) : slot_tok[slot];
         else            row = slot - a.act_slot_base;
         rowidx[tid] = row;
     }
@@ -474,15 +554,20 @@ __device__ __forceinline__ void stream_pass(const SgArgs &a, const uint16_t *wa,
     if (STAGE == STAGE_GATEUP && HALF && a.h_saturated && __any(sat) && lane == 0) atomicAdd(a.h_saturated, 1);
 }
 
-template <int STAGE, bool DENSE, bool ALLTOK, bool QUANT, bool HALF>
+// FUSE: the kernel groups the (token, choice) list itself (route_in_block) instead of reading the
+// tables of a grouping kernel that ran before it.
+template <int STAGE, bool DENSE, bool ALLTOK, bool QUANT, bool HALF, bool FUSE>
 __global__ void __launch_bounds__(SG_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2)))
 stream_kernel(SgArgs a)
 {
+    static_assert(!FUSE || (STAGE == STAGE_GATEUP && !ALLTOK && !QUANT), "in-kernel grouping is for the routed gate/up launch");
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
     u32x4 *xs = (u32x4 *)lds_raw;
     int32_t *rowidx = (int32_t *)(lds_raw + SG_LDS_BYTES);
     QLuts luts = {nullptr, nullptr, nullptr, nullptr};
     if (QUANT) q_build_luts(lds_raw + SG_LDS_BYTES + SG_MAX_TILES * 16 * sizeof(int32_t), luts);   // visible after the pass's first barrier
+    const int32_t *cnt = a.cnt, *off = a.off, *slot_tok = a.slot_tok;
+    if (FUSE) route_in_block(a.route, (int32_t *)(lds_raw + SG_LDS_BYTES + SG_MAX_TILES * 16 * sizeof(int32_t)), cnt, off, slot_tok);
 
     constexpr int RT_PER_WAVE = (STAGE == STAGE_DOWN) ? 2 : 1;
     const int row_tiles = a.rows / TILE_ROWS;
@@ -511,8 +596,8 @@ stream_kernel(SgArgs a)
         base0 = a.dense_slot_base + g * a.dense_tokens; base1 = 0;
     } else {
         const int q0 = 2 * (a.group_base + g);
-        n0 = a.cnt[q0]; n1 = a.cnt[q0 + 1];
-        base0 = a.off[q0]; base1 = a.off[q0 + 1];
+        n0 = cnt[q0]; n1 = cnt[q0 + 1];
+        base0 = off[q0]; base1 = off[q0 + 1];
     }
     if (n0 + n1 == 0) return;
 
@@ -541,7 +626,7 @@ stream_kernel(SgArgs a)
         int c1 = min(PT, max(tiles1 - t1, 0));
 #define PZL_PASS(A, B)                                                                              \
     stream_pass<STAGE, DENSE, ALLTOK, QUANT, HALF, A, B>(a, wa, wb, sa, sb, luts, rt0, rt1, active0, active1, kb0, kb1, ks, \
-                                                   base0, n0, t0, base1, n1, t1, xs, rowidx)
+                                                   base0, n0, t0, base1, n1, t1, xs, rowidx, slot_tok)
         if (DENSE) {
             switch (c0) {
                 case 1: PZL_PASS(1, 0); break;
@@ -572,20 +657,23 @@ int stream_row_groups(int rows, bool down_stage)
     return (rows / TILE_ROWS + per_wg - 1) / per_wg;
 }
 
-template <bool QUANT>
-static constexpr size_t stream_lds_bytes() { return SG_LDS_BYTES + SG_MAX_TILES * 16 * sizeof(int32_t) + (QUANT ? Q_LUT_BYTES : 0); }
+template <bool QUANT, bool FUSE>
+static constexpr size_t stream_lds_bytes()
+{
+    return SG_LDS_BYTES + SG_MAX_TILES * 16 * sizeof(int32_t) + (QUANT ? Q_LUT_BYTES : 0) + (FUSE ? FR_LDS_INTS * sizeof(int32_t) : 0);
+}
 
 // The dynamic LDS size beyond 64 KiB is a per-device attribute of the kernel: set once per device
 // (bit d of the mask; setting it twice from two threads is harmless).
-template <int STAGE, bool DENSE, bool ALLTOK, bool QUANT, bool HALF>
+template <int STAGE, bool DENSE, bool ALLTOK, bool QUANT, bool HALF, bool FUSE = false>
 static int set_lds_attribute()
 {
     static std::atomic<uint64_t> attr_devices{0};
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev > 63) dev = 63;       // unknown device: set it every time
     if (dev == 63 || !((attr_devices.load(std::memory_order_relaxed) >> dev) & 1)) {
-        hipError_t e = hipFuncSetAttribute((const void *)stream_kernel<STAGE, DENSE, ALLTOK, QUANT, HALF>,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)stream_lds_bytes<QUANT>());
+        hipError_t e = hipFuncSetAttribute((const void *)stream_kernel<STAGE, DENSE, ALLTOK, QUANT, HALF, FUSE>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)stream_lds_bytes<QUANT, FUSE>());
         if (e != hipSuccess) { set_hip_error(e); return PZL_EHIP; }
         if (dev != 63) attr_devices.fetch_or(1ull << dev, std::memory_order_relaxed);
     }
@@ -602,13 +690,18 @@ int prepare_stream_kernels()
     PZL_PREP(STAGE_GATEUP, true, false, false, false);  PZL_PREP(STAGE_DOWN, true, false, false, false);
     PZL_PREP(STAGE_GATEUP, false, false, true, false);  PZL_PREP(STAGE_DOWN, false, false, true, false);
 #undef PZL_PREP
+    if (!rc) rc = set_lds_attribute<STAGE_GATEUP, false, false, false, false, true>();
+    if (!rc) rc = set_lds_attribute<STAGE_GATEUP, false, false, false, true, true>();
     return rc;
 }
 
-template <int STAGE, bool DENSE, bool ALLTOK, bool QUANT, bool HALF = false>
+template <int STAGE, bool DENSE, bool ALLTOK, bool QUANT, bool HALF = false, bool FUSE = false>
 static int launch(const StreamGroupArgs &g, hipStream_t st)
 {
     if (g.n_groups <= 0) return PZL_OK;
+    if (FUSE && (!g.route_ids || !g.route_q_of_expert || g.route_n_flat < 1 || g.route_n_flat > FR_MAX_N || g.route_k < 1 ||
+                 g.route_n_keys < 2 || g.route_n_keys > FR_MAX_KEYS || !g.route_slot_of))
+        return PZL_EINVAL;
     if (g.rows % TILE_ROWS || g.kdim % TILE_COLS || g.ksplit < 1) return PZL_EINVAL;
     // every K split must hold at least one k-block: the kernel clamps its read-ahead to the last
     // k-block of its share, which an empty share does not have
@@ -625,6 +718,8 @@ static int launch(const StreamGroupArgs &g, hipStream_t st)
     a.h_out = g.h_out; a.h_plane_stride = g.h_plane_stride; a.h_slot_base = g.h_slot_base;
     a.o_out = g.o_out; a.o_ks_stride = g.o_ks_stride;
     a.h_saturated = g.h_saturated;
+    a.route = SgRoute{g.route_ids, g.route_q_of_expert, g.route_n_flat, g.route_k, g.route_n_experts, g.route_n_keys,
+                      const_cast<int32_t *>(g.cnt), const_cast<int32_t *>(g.off), const_cast<int32_t *>(g.slot_tok), g.route_slot_of};
     // One workgroup (8 waves, two per SIMD) fits a compute unit, 256 on the chip.  A launch a little
     // larger than that runs a second, partly empty round; giving each workgroup several row
     // groups instead keeps the launch to one round.
@@ -642,10 +737,10 @@ static int launch(const StreamGroupArgs &g, hipStream_t st)
     a.rg_per_wg = rg_per_wg;
     const int64_t blocks = (int64_t)g.n_groups * ((row_groups + rg_per_wg - 1) / rg_per_wg) * g.ksplit * a.n_passes;
     if (blocks > 0x7FFFFFFFLL) return PZL_EINVAL;
-    const size_t lds = stream_lds_bytes<QUANT>();
-    int rc_attr = set_lds_attribute<STAGE, DENSE, ALLTOK, QUANT, HALF>();
+    const size_t lds = stream_lds_bytes<QUANT, FUSE>();
+    int rc_attr = set_lds_attribute<STAGE, DENSE, ALLTOK, QUANT, HALF, FUSE>();
     if (rc_attr) return rc_attr;
-    hipLaunchKernelGGL((stream_kernel<STAGE, DENSE, ALLTOK, QUANT, HALF>), dim3((unsigned)blocks), dim3(SG_THREADS), lds, st, a);
+    hipLaunchKernelGGL((stream_kernel<STAGE, DENSE, ALLTOK, QUANT, HALF, FUSE>), dim3((unsigned)blocks), dim3(SG_THREADS), lds, st, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) { set_hip_error(e); return PZL_EHIP; }
     return PZL_OK;
@@ -655,6 +750,8 @@ static int launch(const StreamGroupArgs &g, hipStream_t st)
 //       2 = dense routed experts (kept unmerged), 3 = quantised pairs (routed)
 int launch_stream_gateup(const StreamGroupArgs &a, int kind, hipStream_t st)
 {
+    if (kind == 0 && a.route_ids) return a.half_h ? launch<STAGE_GATEUP, false, false, false, true, true>(a, st)
+                                                  : launch<STAGE_GATEUP, false, false, false, false, true>(a, st);
     if (kind == 0 && a.half_h) return launch<STAGE_GATEUP, false, false, false, true>(a, st);
     if (kind == 0) return launch<STAGE_GATEUP, false, false, false>(a, st);
     if (kind == 1) return launch<STAGE_GATEUP, true, true, false>(a, st);

@@ -46,15 +46,23 @@ namespace pzl {
 #ifndef TG_WPE
 #define TG_WPE 2
 #endif
-constexpr int TG_WAVES = 8;
+#ifndef TG_KBS_N
+#define TG_KBS_N 2          // k-blocks (of 32) per K step where one activation plane is read
+#endif
+constexpr int TG_WAVES = TG_WAVES_N;
 constexpr int TG_THREADS = TG_WAVES * 64;
 constexpr int TG_MAX_TOK = TILE_MAX_TOKENS;   // tokens per tile (18 fragments of 16)
 constexpr int TG_FRAGS = TG_MAX_TOK / 16;
 constexpr int TG_ROW_TILES = 2 * TG_WAVES;    // 16-row weight tiles per workgroup
 constexpr int TG_XSTAGES = 4;
-constexpr int TG_XSTAGE_UNITS = TG_FRAGS * 2 * 64;   // 16-byte units per stage (18 fragments x 2 k-blocks or planes)
+// 16-byte units per ring stage: 18 fragments x (k-blocks per step) x (activation planes)
+template <int STAGE, bool HALF, bool DENSE>
+constexpr int tg_stage_units()
+{
+    return (STAGE == 1 /* down */ && (!HALF || DENSE)) ? TG_FRAGS * 2 * 64 : TG_FRAGS * TG_KBS_N * 64;
+}
 constexpr int TSTAGE_GATEUP = 0, TSTAGE_DOWN = 1;
-constexpr int TG_PERSISTENT_WGS = 256;   // workgroups of a persistent launch: one per compute unit (8 XCDs x 32)
+constexpr int TG_PERSISTENT_WGS = 256 * (8 / TG_WAVES);   // workgroups of a persistent launch: as many as the chip holds (8 waves per compute unit)
 #ifndef TG_READ_AHEAD
 #define TG_READ_AHEAD 3     // fragment reads kept in flight ahead of the matrix instructions
 #endif
@@ -169,7 +177,7 @@ __device__ __forceinline__ void tile_body(const TgArgs &a, const uint16_t *wa, c
     constexpr bool FUSED = POS == 2;
     static_assert(!HALF || !DENSE, "half-precision H is for packed pairs");
     constexpr bool HALFW = HALF && STAGE == TSTAGE_DOWN;     // this stage's operands are half precision
-    constexpr int KBS = (STAGE == TSTAGE_DOWN && !HALF) ? 1 : 2;      // k-blocks (of 32) per K step
+    constexpr int KBS = (STAGE == TSTAGE_DOWN && !HALF) ? 1 : TG_KBS_N;      // k-blocks (of 32) per K step
     constexpr int PARTS = (STAGE == TSTAGE_DOWN && !HALF) ? 2 : 1;    // activation planes (hi, lo)
     constexpr int NF = (FUSED ? 4 : 2) * CNT;                // token fragments in use
     constexpr int NFH = FUSED ? NF / 2 : NF;                 // ... of which the first expert's
@@ -177,6 +185,7 @@ __device__ __forceinline__ void tile_body(const TgArgs &a, const uint16_t *wa, c
     constexpr int RT = 2;                                    // row tiles per wave
     constexpr int XTOTAL = PARTS * NF * KBS;                 // activation fragments per stage
     constexpr int XPT = (XTOTAL + TG_WAVES - 1) / TG_WAVES;  // ... of which each wave fetches this many
+    constexpr int TG_XSTAGE_UNITS = tg_stage_units<STAGE, HALF, DENSE>();
     static_assert(PARTS * TG_FRAGS * KBS * 64 == TG_XSTAGE_UNITS, "stage size");
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -190,13 +199,18 @@ __device__ __forceinline__ void tile_body(const TgArgs &a, const uint16_t *wa, c
     const int row_tiles = a.rows / TILE_ROWS;
 
     // activation row behind each token column of the tile (clamped to the last valid token)
-    if (tid < TG_MAX_TOK) {
-        int slot = slot0 + min(tid, n_tok - 1);
-        if (FUSED && tid >= NFH * 16) slot = slot0 + n_tok + min(tid - NFH * 16, n_tok1 - 1);
+    auto set_row = [&](int t) {
+        int slot = slot0 + min(t, n_tok - 1);
+        if (FUSED && t >= NFH * 16) slot = slot0 + n_tok + min(t - NFH * 16, n_tok1 - 1);
         int row;
         if (a.act_is_x) row = ALLTOK ? (slot - a.dense_slot_base) % a.dense_tokens : a.slot_tok[slot];
         else            row = slot - a.act_slot_base;
-        rowidx[tid] = row;
+        rowidx[t] = row;
+    };
+    if constexpr (TG_THREADS >= TG_MAX_TOK) {
+        if (tid < TG_MAX_TOK) set_row(tid);
+    } else {                                       // fewer threads than a tile has tokens
+        for (int t = tid; t < TG_MAX_TOK; t += TG_THREADS) set_row(t);
     }
     __syncthreads();
 
@@ -482,7 +496,7 @@ template <int STAGE, bool DENSE, bool ALLTOK, bool PERSIST, bool HALF>
 __global__ void __launch_bounds__(TG_THREADS) __attribute__((amdgpu_waves_per_eu(TG_WPE, TG_WPE)))
 tile_kernel(TgArgs a)
 {
-    __shared__ u32x4 ring[TG_XSTAGES * TG_XSTAGE_UNITS];
+    __shared__ u32x4 ring[TG_XSTAGES * tg_stage_units<STAGE, HALF, DENSE>()];
     __shared__ int32_t rowidx[TG_MAX_TOK];
     __shared__ int32_t drawn;
 
@@ -562,7 +576,7 @@ static int launch(const TileGemmArgs &t, hipStream_t st)
     a.o_out = t.o_out; a.o_ks_stride = t.o_ks_stride;
     a.ksplit = (STAGE == TSTAGE_DOWN && t.ksplit > 1) ? t.ksplit : 1;
     a.max_mtiles = t.max_mtiles;
-    const int rows_per_wg = (STAGE == TSTAGE_GATEUP) ? TG_ROW_TILES * 8 : TG_ROW_TILES * 16;   // feature rows / down rows
+    const int rows_per_wg = (STAGE == TSTAGE_GATEUP) ? TILE_WG_FEATURES : TILE_WG_DOWN_ROWS;
     a.n_ntiles = (t.rows + rows_per_wg - 1) / rows_per_wg;
     int64_t blocks = (int64_t)((a.max_mtiles + TG_BLOCK_M - 1) / TG_BLOCK_M) *
                      ((a.n_ntiles + TG_BLOCK_N - 1) / TG_BLOCK_N) * (TG_BLOCK_M * TG_BLOCK_N);

@@ -346,6 +346,44 @@ def test_many_experts_mixed_layer_persistent_launches(oracle, binding):
         check(case, T, "many-mixed")
 
 
+def test_grouping_inside_the_gateup_kernel_at_its_limits(oracle, binding):
+    """Small streaming-only batches have no grouping kernel: the gate/up kernel sorts the (token,
+    choice) list itself (at most 512 entries, 128 routing keys).  30 experts with 4 kept unmerged
+    (whose launch reads the tables the packed launch wrote): 512 entries (the limit), 514 (one
+    over: the grouping kernel runs), ids out of range and every token on one expert."""
+    cfg = synth.LayerConfig("group_in_kernel", 30, 128, 256, 2, (256,), shared_d_ffn=(128,), seed=79, n_unmerged=4)
+    case = Case(cfg, oracle, binding, emap_mode="random")
+    for T, fused in ((256, 1), (257, 0), (3, 1)):
+        plan = binding.pzl_moe_ffn_plan(cfg.n_experts, cfg.d_model, cfg.d_ffn, T, cfg.top_k,
+                                        shared_d_ffn=cfg.shared_d_ffn, n_unmerged=cfg.n_unmerged)
+        assert plan["grouping_in_kernel"] == fused and not plan["hybrid"]
+        check(case, T, "grouping in the gate/up kernel" if fused else "grouping kernel")
+        tab = case.layer.routing_tables(T, cfg.top_k)            # stable: a key's slots are in ascending flat order
+        ids, _ = synth.routing(cfg, T)
+        if fused:
+            flat_of_slot = np.empty(T * cfg.top_k, dtype=np.int64)
+            flat_of_slot[tab["slot_of"].ravel()] = np.arange(T * cfg.top_k)
+            for q in range(tab["n_keys"]):
+                seg = flat_of_slot[tab["first_slot"][q]:tab["first_slot"][q + 1]]
+                assert np.all(np.diff(seg) > 0)
+    T = 200
+    x = synth.tokens(cfg, T)
+    ids, w = synth.routing(cfg, T)
+    ids[::7, 1] = cfg.n_experts + 3                               # ignored ids
+    ids[5, 0] = -1
+    y = case.gpu(x, ids, w)
+    tab = case.layer.routing_tables(T, cfg.top_k)
+    assert np.array_equal(tab["slot_of"] < 0, (ids < 0) | (ids >= cfg.n_experts))
+    keep = (ids >= 0) & (ids < cfg.n_experts)
+    y64, _ = case.ref(x, np.where(keep, ids, 0), np.where(keep, w, 0.0).astype(np.float32))
+    ok, worst = tolerance_ok(y, y64)
+    say("  ignored ids: worst err / bound = %.3f" % worst)
+    assert ok, worst
+    ids1 = np.zeros((T, 2), dtype=np.int32)
+    ids1[:, 1] = 1 + (np.arange(T) % 3)                           # expert 0 gets every token: 200 tokens, 7 sweeps
+    check(case, T, "one busy expert", ids=ids1, w=w, x=x)
+
+
 def test_many_experts_small_batch_hot_expert(oracle, binding):
     """Small batches of a 64-expert layer (fewer than 6 slots per expert on average: streaming
     kernels only) in which every token picks the same first expert: its pair needs 2 to 4 sweeps of

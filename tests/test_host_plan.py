@@ -54,6 +54,10 @@ def test_plan_invariants(shape):
         else:
             assert p["sweep_wgs_packed"] == max(1, min(3, -(-T // 32)))
             assert p["sweep_wgs_unmerged"] == max(1, min(3, -(-T // 64)))
+        # the gate/up kernel groups the list itself exactly where only it needs the tables first: a
+        # streaming-only batch of packed pairs that fits its limits (512 entries, 128 routing keys)
+        n_keys = 2 * ((E - D) // 2 + D)
+        assert bool(p["grouping_in_kernel"]) == (not quant and not p["hybrid"] and E > D and 1 <= N <= 512 and n_keys <= 128), (T, p)
         # shared experts: tiled from 65 tokens; the tiles cover the batch, hold 16..288 tokens in
         # whole fragments, and experts of equal width (one launch) agree
         assert bool(p["tiled_shared"]) == (len(shared) > 0 and T >= 65)
@@ -72,7 +76,7 @@ def test_plan_invariants(shape):
 def test_plan_of_the_benchmark_shapes():
     """The decisions that the measured configurations rely on."""
     p = plan(8, 4096, 14336, 64, 2)                           # decode: streaming only, down split 4 ways
-    assert not p["hybrid"] and p["ksplit"] == 4 and p["sweep_wgs_packed"] == 2
+    assert not p["hybrid"] and p["ksplit"] == 4 and p["sweep_wgs_packed"] == 2 and p["grouping_in_kernel"]
     p = plan(8, 4096, 14336, 4096, 2)                         # prefill: one workgroup per tile, no K split
     assert p["hybrid"] and not p["persistent"] and not p["tile_stream"] and p["ksplit"] == 1
     p = plan(60, 2048, 1408, 256, 4, shared_d_ffn=(5632,))    # persistent tiles on the third stream, 4 x 64 shared tokens
