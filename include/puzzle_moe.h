@@ -255,7 +255,10 @@ int pzl_moe_ffn_workspace_layout(const pzl_layer *layer, int32_t T, int32_t k, p
  * with every routed W_e decoded on the fly from its pair's packed tensor (Algorithm 1), or, for a
  * layer in the quantised format, reconstructed on the fly as (-1)^S * M * code * scale (the group
  * scale is applied to the fp32 partial sums of each 128-column group, so code * scale is never
- * rounded).  Quantised layers always take the weight-streaming kernels.
+ * rounded).  Quantised layers always take the weight-streaming kernels, which serve 32 tokens of an
+ * expert per sweep of its pair's weights: a call with more than 64 (token, choice) entries per
+ * expert on average (T * k > 64 * n_experts) is refused with PZL_EINVAL (split the batch, or keep
+ * layers that see prefill-sized batches in the 16-bit format).
  * Products are accumulated in fp32 and y is rounded to bf16 once at the end.  Between the two
  * contractions the SwiGLU output h needs more than bf16's 8 significant bits to keep y within 1e-2:
  * packed pairs keep it as one IEEE half-precision number (11 bits; the down projection then decodes

@@ -107,6 +107,7 @@ constexpr int HYBRID_TILE_MIN_TOKENS = PZL_HYBRID_TILE_MIN;       // ... and a p
 // given token tiles of the right size (shared_token_parts).  Measured, 60 experts + 1 shared
 // expert of 5632: 64 tokens 120 us streamed / 135 tiled, 96 tokens 156 / 139, 256 tokens 192 / 166
 constexpr int TILED_MIN_TOKENS_SHARED = PZL_TILED_MIN_SHARED;
+constexpr int QUANT_MAX_SLOTS_PER_EXPERT = 64;   // quantised layers: largest average of (token, choice) entries per expert that a call accepts
 constexpr int MAX_KSPLIT = 8;   // upper bound on the k-splits of the down stage (sizes the workspace)
 
 struct WorkspaceLayout {
@@ -658,6 +659,11 @@ int pzl_moe_ffn_staged(const pzl_layer *L, const uint16_t *x, const int32_t *top
     if (!x || !y || (k > 0 && (!topk_ids || !topk_w)) || !workspace) return PZL_EINVAL;
     if ((int64_t)T * k > 0x3FFFFFFF || ((uintptr_t)workspace & 255)) return PZL_EINVAL;
     if (!batch_fits(L, T, k)) return PZL_EINVAL;
+    // Quantised pairs have no tiled kernel: the streaming kernels serve 32 tokens of an expert per
+    // sweep of its pair's weights and sweep again for every 32 more.  Batches that would, on
+    // average, sweep more than twice are refused rather than served at a fraction of the speed
+    // (the caller splits them, or keeps such layers in the 16-bit format).
+    if (L->pair_format == 1 && (int64_t)T * k > (int64_t)QUANT_MAX_SLOTS_PER_EXPERT * L->n_experts) return PZL_EINVAL;
     const WorkspaceLayout w = carve(L, T, k);
     if (workspace_bytes < w.total) return PZL_ENOSPC;
     hipStream_t st = (hipStream_t)stream;

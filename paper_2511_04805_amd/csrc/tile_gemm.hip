@@ -47,7 +47,7 @@ namespace pzl {
 #define TG_WPE 2
 #endif
 #ifndef TG_KBS_N
-#define TG_KBS_N 2          // k-blocks (of 32) per K step where one activation plane is read
+#define TG_KBS_N 1          // k-blocks (of 32) per K step where one activation plane is read (measured: 1 is 5 % faster than 2 where K is 2048, equal at 4096)
 #endif
 constexpr int TG_WAVES = TG_WAVES_N;
 constexpr int TG_THREADS = TG_WAVES * 64;
@@ -63,6 +63,9 @@ constexpr int tg_stage_units()
 }
 constexpr int TSTAGE_GATEUP = 0, TSTAGE_DOWN = 1;
 constexpr int TG_PERSISTENT_WGS = 256 * (8 / TG_WAVES);   // workgroups of a persistent launch: as many as the chip holds (8 waves per compute unit)
+#ifndef TG_PIPE_DECODE
+#define TG_PIPE_DECODE 1    // decode a step ahead, between the matrix instructions of the current step
+#endif
 #ifndef TG_READ_AHEAD
 #define TG_READ_AHEAD 3     // fragment reads kept in flight ahead of the matrix instructions
 #endif
@@ -300,6 +303,123 @@ __device__ __forceinline__ void tile_body(const TgArgs &a, const uint16_t *wa, c
             }
         }
     };
+#if TG_PIPE_DECODE
+    // One K step, decode one step ahead.  The vector ALU and the matrix pipes only run side by side
+    // when their instructions alternate in the instruction stream (measured: with the decode of a
+    // step in one piece in front of its matrix instructions the two co-execute 3 % of the time and
+    // their times add up).  So step s multiplies operands that step s-1 decoded, and decodes the
+    // operands of step s+1 between its own matrix instructions.
+    //   cur      activations of this step          fill   the stage read three steps ago
+    //   raw_n    packed weights of step s+1 (loaded at the end of step s-2): waited for, decoded
+    //            into dn, then refilled with the weights of step s+3
+    //   dc / dn  decoded operands of this step / of the next
+    // Loads complete in issue order; a step issues [activation stage s+3 ... weights s+3].  Younger
+    // than the weights of s+1 are: activation stage s+2, weights s+2, activation stage s+3, i.e.
+    // 2*XPT + KBS*RT loads; waiting until only that many are outstanding makes the weights usable
+    // and, being older, the activation stage s+1 complete, which the barrier then publishes.
+    struct Dec { u32x4 a[KBS][RT]; u32x4 a1[KBS][RT]; };
+    auto wait_step = [&](u32x4 (&raw)[KBS][RT], bool all) {
+        // the asm takes the registers as in/out operands so that nothing that uses them can be scheduled above the wait
+        if (KBS == 1) {
+            if (all) asm volatile("s_waitcnt vmcnt(0)" : "+v"(raw[0][0]), "+v"(raw[0][1]));
+            else     asm volatile("s_waitcnt vmcnt(%2)" : "+v"(raw[0][0]), "+v"(raw[0][1]) : "n"(2 * XPT + KBS * RT));
+        } else {
+            if (all) asm volatile("s_waitcnt vmcnt(0)" : "+v"(raw[0][0]), "+v"(raw[0][1]), "+v"(raw[KBS - 1][0]), "+v"(raw[KBS - 1][1]));
+            else     asm volatile("s_waitcnt vmcnt(%4)" : "+v"(raw[0][0]), "+v"(raw[0][1]), "+v"(raw[KBS - 1][0]), "+v"(raw[KBS - 1][1])
+                                  : "n"(2 * XPT + KBS * RT));
+        }
+    };
+    static_assert(KBS <= 2, "wait_step names the registers of at most two k-blocks");
+    // The step's matrix instructions come in groups: one token fragment read from LDS (TG_READ_AHEAD
+    // groups ahead), its RT products, and a share of the next step's decode, in that order, group
+    // after group (a scheduling fence after each keeps the order in the machine code).  Decode
+    // units: one 32-bit word (two elements) of a packed tile, or one whole register quad of a dense one.
+    constexpr int GROUPS = NF * PARTS * KBS;
+    constexpr int RA = TG_READ_AHEAD < GROUPS ? TG_READ_AHEAD : GROUPS - 1;
+    constexpr int UNITS = DENSE ? KBS * RT : KBS * RT * 4;
+    auto decode_unit = [&](u32x4 (&raw)[KBS][RT], Dec &d, int u, int step) {
+        if (DENSE) {
+            const int kbo = u / RT, j = u % RT;
+            d.a[kbo][j] = tg_decode<0, true, false>(raw[kbo][j]);
+            if (kbo > 0 && !(kb0 + step * KBS + kbo < kb1)) d.a[kbo][j] = (u32x4){0u, 0u, 0u, 0u};
+            d.a1[kbo][j] = d.a[kbo][j];
+        } else {
+            const int kbo = u / (RT * 4), j = (u / 4) % RT, i = u % 4;
+            const uint32_t w = raw[kbo][j][i];
+            const uint32_t body = HALFW ? decode_body_half_x2(w) : decode_body(w);
+            uint32_t v0 = decode_pair<FUSED ? 0 : POS>(w, body);
+            uint32_t v1 = FUSED ? decode_pair<1>(w, body) : v0;
+            if (kbo > 0 && !(kb0 + step * KBS + kbo < kb1)) { v0 = 0u; v1 = 0u; }   // a k-block past the end: multiply by zero
+            // pin the result to this place in the instruction stream (an empty volatile asm that
+            // "uses" it): the compiler otherwise sinks the whole decode to its first use, at the
+            // top of the next step, in one piece
+            if (FUSED) asm volatile("" : "+v"(v0), "+v"(v1)); else asm volatile("" : "+v"(v0));
+            d.a[kbo][j][i] = v0;
+            d.a1[kbo][j][i] = FUSED ? v1 : v0;
+        }
+    };
+    auto full_step = [&](const u32x4 *cur, u32x4 *fill, u32x4 (&raw_n)[KBS][RT], const Dec &dc, Dec &dn, int step) {
+        fetch_x(step + 3, fill);
+        wait_step(raw_n, false);
+        __builtin_amdgcn_sched_barrier(0);
+        u32x4 bq[RA + 1];
+#pragma unroll
+        for (int f = 0; f < GROUPS + RA; ++f) {
+            if (f < GROUPS) {
+                const int kbo = f / (NF * PARTS), i = (f % (NF * PARTS)) / PARTS, part = f % PARTS;
+                bq[f % (RA + 1)] = cur[((part * TG_FRAGS + i) * KBS + kbo) * 64 + lane];
+            }
+            if (f >= RA) {
+                const int g = f - RA;
+                const int kbo = g / (NF * PARTS), i = (g % (NF * PARTS)) / PARTS;
+#pragma unroll
+                for (int j = 0; j < RT; ++j)
+                    acc[j][i] = tg_mma<HALFW>((FUSED && i >= NFH) ? dc.a1[kbo][j] : dc.a[kbo][j], bq[g % (RA + 1)], acc[j][i]);
+#pragma unroll
+                for (int u = g * UNITS / GROUPS; u < (g + 1) * UNITS / GROUPS; ++u) decode_unit(raw_n, dn, u, step + 1);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        // refill the registers just decoded with the weights of step s+3 (in/out operands: the
+        // loads cannot be scheduled above the decode that reads the registers)
+#pragma unroll
+        for (int kbo = 0; kbo < KBS; ++kbo) fetch_w(step + 3, raw_n, kbo);
+        // A bare barrier (no fence): the only LDS writes are the direct loads, whose completion
+        // the wait above covers.  Nothing may be scheduled across it.
+        __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    // stage of step s: ring + (s % 4) * TG_XSTAGE_UNITS
+    auto stage = [&](int step) { return ring + (step & (TG_XSTAGES - 1)) * TG_XSTAGE_UNITS; };
+    u32x4 raw0[KBS][RT] = {}, raw1[KBS][RT] = {};      // packed weights of the even / of the odd steps
+    Dec dec0, dec1;                                    // decoded operands of the even / of the odd steps
+    fetch_x(0, stage(0));
+    fetch_x(1, stage(1));
+    fetch_x(2, stage(2));
+#pragma unroll
+    for (int kbo = 0; kbo < KBS; ++kbo) fetch_w(0, raw0, kbo);
+#pragma unroll
+    for (int kbo = 0; kbo < KBS; ++kbo) fetch_w(1, raw1, kbo);
+    wait_step(raw0, true);                 // everything landed (this wave's share of the stages too)
+    wait_step(raw1, true);
+#pragma unroll
+    for (int u = 0; u < UNITS; ++u) decode_unit(raw0, dec0, u, 0);
+#pragma unroll
+    for (int kbo = 0; kbo < KBS; ++kbo) fetch_w(2, raw0, kbo);
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+
+    // Every step is the same code, the last ones included: their refills are clamped re-reads
+    // and their decodes operands that nobody uses, their barrier is harmless.
+    for (int step = 0;; step += 2) {
+        full_step(stage(step), stage(step + 3), raw1, dec0, dec1, step);
+        if (step + 1 >= n_steps) break;
+        full_step(stage(step + 1), stage(step + 4), raw0, dec1, dec0, step + 1);
+        if (step + 2 >= n_steps) break;
+    }
+#else
     // One K step.  `cur` holds the activations of this step, `fill` is the stage read three steps
     // ago (free since the last barrier); `raw` holds this step's packed weights and is refilled
     // with those of step + 2 once they are decoded.
@@ -364,6 +484,7 @@ __device__ __forceinline__ void tile_body(const TgArgs &a, const uint16_t *wa, c
         full_step(stage(step + 1), stage(step + 4), raw1, step + 1);
         if (step + 2 >= n_steps) break;
     }
+#endif
     // No load of this wave is in flight past this point: the refills of the last steps still
     // write the (now dead) weight registers, so nothing may be scheduled above this wait that
     // could be given one of them.

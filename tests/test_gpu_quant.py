@@ -162,6 +162,24 @@ def test_q_ffn_skewed_and_empty(small_q):
     assert y0.shape == (0, cfg.d_model)
 
 
+def test_q_ffn_refuses_batches_beyond_two_sweeps(small_q, binding):
+    """No tiled kernel for the quantised format: a batch of more than 64 (token, choice) entries per
+    expert on average is refused (PZL_EINVAL) instead of re-streaming the weights many times."""
+    cfg = small_q.cfg                                   # 8 experts, top-2: the limit is 256 tokens
+    for T, ok in ((256, True), (257, False), (4096, False)):
+        x = torch.zeros(T, cfg.d_model, dtype=torch.bfloat16, device="cuda")
+        ids = torch.zeros(T, 2, dtype=torch.int32, device="cuda")
+        ids[:, 1] = 1
+        w = torch.full((T, 2), 0.5, dtype=torch.float32, device="cuda")
+        if ok:
+            small_q.layer.pzl_moe_ffn(x, ids, w)
+            torch.cuda.synchronize()
+        else:
+            with pytest.raises(binding.PzlError) as e:
+                small_q.layer.pzl_moe_ffn(x, ids, w)
+            assert e.value.rc == binding.PZL_EINVAL
+
+
 def test_q_layer_rejects_bad_shapes(binding):
     """d_model / d_ffn must be multiples of 128 for the quantised format."""
     dummy = (torch.zeros(8, dtype=torch.uint8, device="cuda"), torch.zeros(8, dtype=torch.int16, device="cuda"))
