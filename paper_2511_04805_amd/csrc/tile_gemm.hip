@@ -38,6 +38,7 @@
 // Launch forms (tile_kernel): one workgroup per tile, or, where the host's bound on the number of
 // tiles is loose and tiles are uneven (many experts), 256 persistent workgroups that work through
 // the tile list, by fixed stride first and then drawing from a counter.
+#include <type_traits>
 #include "pzl_common.h"
 #include "pzl_decode.h"
 
@@ -54,7 +55,6 @@ constexpr int TG_THREADS = TG_WAVES * 64;
 constexpr int TG_MAX_TOK = TILE_MAX_TOKENS;   // tokens per tile (18 fragments of 16)
 constexpr int TG_FRAGS = TG_MAX_TOK / 16;
 constexpr int TG_ROW_TILES = 2 * TG_WAVES;    // 16-row weight tiles per workgroup
-constexpr int TG_XSTAGES = 4;
 // 16-byte units per ring stage: 18 fragments x (k-blocks per step) x (activation planes)
 template <int STAGE, bool HALF, bool DENSE>
 constexpr int tg_stage_units()
@@ -63,12 +63,10 @@ constexpr int tg_stage_units()
 }
 constexpr int TSTAGE_GATEUP = 0, TSTAGE_DOWN = 1;
 constexpr int TG_PERSISTENT_WGS = 256 * (8 / TG_WAVES);   // workgroups of a persistent launch: as many as the chip holds (8 waves per compute unit)
-#ifndef TG_PIPE_DECODE
-#define TG_PIPE_DECODE 1    // decode a step ahead, between the matrix instructions of the current step
-#endif
-#ifndef TG_READ_AHEAD
-#define TG_READ_AHEAD 3     // fragment reads kept in flight ahead of the matrix instructions
-#endif
+// Stages of the activation ring: 8 where a stage is 18 KiB (one activation plane, K step 32), which
+// lets a step read the first fragments of the next stage before its closing barrier; else 4.
+template <int STAGE, bool HALF, bool DENSE>
+constexpr int tg_ring_stages() { return tg_stage_units<STAGE, HALF, DENSE>() * 16 * 8 <= 147456 ? 8 : 4; }
 #ifndef TG_BLOCK_M
 #define TG_BLOCK_M 8
 #endif
@@ -252,15 +250,16 @@ __device__ __forceinline__ void tile_body(const TgArgs &a, const uint16_t *wa, c
     // the compiler, seeing a direct-to-LDS load, waits for ALL outstanding loads before the next
     // LDS read, which would undo the prefetch.
     const uint64_t act_base = (uint64_t)(uintptr_t)a.act;
+    auto fetch_x_one = [&](int step, u32x4 *stage, int i) {
+        int kb = min(kb0 + step * KBS + xkbo[i], kb1 - 1);
+        uint32_t voff = xoff[i] + (uint32_t)(kb * TILE_COLS * 2);
+        uint32_t lds_addr = (uint32_t)(uintptr_t)(tg_lds_ptr)(stage + xunit[i]);
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                     :: "s"(lds_addr), "v"(voff), "s"(act_base) : "memory");
+    };
     auto fetch_x = [&](int step, u32x4 *stage) {
 #pragma unroll
-        for (int i = 0; i < XPT; ++i) {
-            int kb = min(kb0 + step * KBS + xkbo[i], kb1 - 1);
-            uint32_t voff = xoff[i] + (uint32_t)(kb * TILE_COLS * 2);
-            uint32_t lds_addr = (uint32_t)(uintptr_t)(tg_lds_ptr)(stage + xunit[i]);
-            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                         :: "s"(lds_addr), "v"(voff), "s"(act_base) : "memory");
-        }
+        for (int i = 0; i < XPT; ++i) fetch_x_one(step, stage, i);
     };
     auto fetch_w = [&](int step, u32x4 (&raw)[KBS][RT], int kbo) {
         int kb = min(kb0 + step * KBS + kbo, kb1 - 1);
@@ -273,69 +272,62 @@ __device__ __forceinline__ void tile_body(const TgArgs &a, const uint16_t *wa, c
             asm volatile("global_load_dwordx4 %0, %1, %2" : "+v"(raw[kbo][j]) : "v"(lane16), "s"(base));
         }
     };
-    // Loads complete in issue order.  A step issues: activation stage s+3, then per k-block
-    // [wait for its weights, decode, refill the registers with the weights of step s+2].  Younger
-    // than the weights of (s, k-block) are then: the remaining k-blocks of s, activation stage
-    // s+2, the weights of s+1, activation stage s+3 and the refills already issued in this step:
-    // 2*XPT + (2*KBS-1)*RT loads in all.  Waiting until only that many are outstanding makes the
-    // weights usable and, being older, the activation stage s+1 complete.  The asm takes the
-    // registers as in/out operands so that nothing that uses them can be scheduled above the wait.
-    auto wait_w = [&](u32x4 (&raw)[KBS][RT], int kbo, bool all) {
-        if (all) asm volatile("s_waitcnt vmcnt(0)" : "+v"(raw[kbo][0]), "+v"(raw[kbo][1]));
-        else     asm volatile("s_waitcnt vmcnt(%2)" : "+v"(raw[kbo][0]), "+v"(raw[kbo][1]) : "n"(2 * XPT + (2 * KBS - 1) * RT));
-    };
-
     f32x4 acc[RT][NF];
 #pragma unroll
     for (int j = 0; j < RT; ++j)
 #pragma unroll
         for (int i = 0; i < NF; ++i) acc[j][i] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
-    auto multiply = [&](const u32x4 *xs, const u32x4 (&af)[RT], const u32x4 (&af1)[RT], int kbo) {
-#pragma unroll
-        for (int i = 0; i < NF; ++i) {
-#pragma unroll
-            for (int part = 0; part < PARTS; ++part) {
-                const u32x4 b = xs[((part * TG_FRAGS + i) * KBS + kbo) * 64 + lane];
-#pragma unroll
-                for (int j = 0; j < RT; ++j)
-                    acc[j][i] = tg_mma<HALFW>((FUSED && i >= NFH) ? af1[j] : af[j], b, acc[j][i]);
-            }
-        }
-    };
-#if TG_PIPE_DECODE
     // One K step, decode one step ahead.  The vector ALU and the matrix pipes only run side by side
     // when their instructions alternate in the instruction stream (measured: with the decode of a
     // step in one piece in front of its matrix instructions the two co-execute 3 % of the time and
     // their times add up).  So step s multiplies operands that step s-1 decoded, and decodes the
     // operands of step s+1 between its own matrix instructions.
-    //   cur      activations of this step          fill   the stage read three steps ago
     //   raw_n    packed weights of step s+1 (loaded at the end of step s-2): waited for, decoded
     //            into dn, then refilled with the weights of step s+3
     //   dc / dn  decoded operands of this step / of the next
-    // Loads complete in issue order; a step issues [activation stage s+3 ... weights s+3].  Younger
-    // than the weights of s+1 are: activation stage s+2, weights s+2, activation stage s+3, i.e.
-    // 2*XPT + KBS*RT loads; waiting until only that many are outstanding makes the weights usable
-    // and, being older, the activation stage s+1 complete, which the barrier then publishes.
+    // Loads complete in issue order, so waiting for the weights of step s+1 also completes every
+    // older load, the activation stages among them, which the step's closing barrier publishes.
+    // Two schedules of the activation ring:
+    //   DEEP (8 stages)  a step issues [activation stage s+4, weights s+3]; younger than the weights
+    //     of s+1 at the step's start: stage s+3, weights s+2 = XPT + KBS*RT loads; older and hence
+    //     complete: stage s+2, which the closing barrier of step s publishes -- one step before it is
+    //     read, so that step s can read the first fragments of stage s+1 before its own closing
+    //     barrier and the matrix pipes do not drain at every step boundary.  The stage's loads are
+    //     spread over the step's first groups.  Slot reuse: stage s+4 overwrites stage s-4, which
+    //     every wave left before the barrier of step s-1.
+    //   else (4 stages)  a step issues [stage s+3 at its start, weights s+3 at its end]; younger than
+    //     the weights of s+1: stage s+2, weights s+2, stage s+3 = 2*XPT + KBS*RT; the closing barrier
+    //     publishes stage s+1; slot reuse: stage s+3 overwrites stage s-1.
+    constexpr int RING = tg_ring_stages<STAGE, HALF, DENSE>();
+    constexpr bool DEEP = RING == 8;
+    constexpr int LEAD = DEEP ? 4 : 3;
     struct Dec { u32x4 a[KBS][RT]; u32x4 a1[KBS][RT]; };
     auto wait_step = [&](u32x4 (&raw)[KBS][RT], bool all) {
         // the asm takes the registers as in/out operands so that nothing that uses them can be scheduled above the wait
+        constexpr int YOUNGER = (DEEP ? XPT : 2 * XPT) + KBS * RT;
         if (KBS == 1) {
             if (all) asm volatile("s_waitcnt vmcnt(0)" : "+v"(raw[0][0]), "+v"(raw[0][1]));
-            else     asm volatile("s_waitcnt vmcnt(%2)" : "+v"(raw[0][0]), "+v"(raw[0][1]) : "n"(2 * XPT + KBS * RT));
+            else     asm volatile("s_waitcnt vmcnt(%2)" : "+v"(raw[0][0]), "+v"(raw[0][1]) : "n"(YOUNGER));
         } else {
             if (all) asm volatile("s_waitcnt vmcnt(0)" : "+v"(raw[0][0]), "+v"(raw[0][1]), "+v"(raw[KBS - 1][0]), "+v"(raw[KBS - 1][1]));
             else     asm volatile("s_waitcnt vmcnt(%4)" : "+v"(raw[0][0]), "+v"(raw[0][1]), "+v"(raw[KBS - 1][0]), "+v"(raw[KBS - 1][1])
-                                  : "n"(2 * XPT + KBS * RT));
+                                  : "n"(YOUNGER));
         }
     };
     static_assert(KBS <= 2, "wait_step names the registers of at most two k-blocks");
-    // The step's matrix instructions come in groups: one token fragment read from LDS (TG_READ_AHEAD
-    // groups ahead), its RT products, and a share of the next step's decode, in that order, group
-    // after group (a scheduling fence after each keeps the order in the machine code).  Decode
-    // units: one 32-bit word (two elements) of a packed tile, or one whole register quad of a dense one.
+    // The step's matrix instructions come in groups: one token fragment read from LDS (RA groups
+    // ahead), its RT products, and a share of the next step's decode (and, DEEP, of the activation
+    // loads), in that order, group after group (a scheduling fence after each keeps the order in
+    // the machine code).  Decode units: one 32-bit word (two elements) of a packed tile, or one
+    // whole register quad of a dense one.
     constexpr int GROUPS = NF * PARTS * KBS;
-    constexpr int RA = TG_READ_AHEAD < GROUPS ? TG_READ_AHEAD : GROUPS - 1;
+    // fragments read ahead: 3, or 1 for the smallest tiles (the read-ahead may reach into the next
+    // stage but not beyond it; the ring of RA+1 fragment registers must divide two steps' groups)
+    // (the largest tiles, whose accumulators leave the fewest registers, read 2 ahead)
+    constexpr int RA = GROUPS < 4 ? 1 : (NF == TG_FRAGS ? 2 : 3);
+    static_assert(GROUPS % 2 == 0 && (2 * GROUPS) % (RA + 1) == 0 && RA <= GROUPS, "fragment register ring");
+    static_assert(!DEEP || XPT <= GROUPS, "activation loads are spread over the groups");
     constexpr int UNITS = DENSE ? KBS * RT : KBS * RT * 4;
     auto decode_unit = [&](u32x4 (&raw)[KBS][RT], Dec &d, int u, int step) {
         if (DENSE) {
@@ -358,26 +350,38 @@ __device__ __forceinline__ void tile_body(const TgArgs &a, const uint16_t *wa, c
             d.a1[kbo][j][i] = FUSED ? v1 : v0;
         }
     };
-    auto full_step = [&](const u32x4 *cur, u32x4 *fill, u32x4 (&raw_n)[KBS][RT], const Dec &dc, Dec &dn, int step) {
-        fetch_x(step + 3, fill);
+    // stage of step s
+    auto stage = [&](int step) { return ring + (step & (RING - 1)) * TG_XSTAGE_UNITS; };
+    auto frag_of = [&](const u32x4 *st, int g) {                 // B fragment of group g of a stage
+        const int kbo = g / (NF * PARTS), i = (g % (NF * PARTS)) / PARTS, part = g % PARTS;
+        return st[((part * TG_FRAGS + i) * KBS + kbo) * 64 + lane];
+    };
+    u32x4 bq[RA + 1];                                            // fragments in flight; DEEP: carried across steps
+    // PH: the step's parity (two steps per loop trip), which fixes where in the fragment ring it starts
+    auto full_step = [&](auto ph, u32x4 (&raw_n)[KBS][RT], const Dec &dc, Dec &dn, int step) {
+        constexpr int PH = decltype(ph)::value;
+        const u32x4 *cur = stage(step), *nxt = stage(step + 1);
+        u32x4 *fill = stage(step + LEAD);
+        if (!DEEP) fetch_x(step + LEAD, fill);
         wait_step(raw_n, false);
         __builtin_amdgcn_sched_barrier(0);
-        u32x4 bq[RA + 1];
+        if (!DEEP) {
 #pragma unroll
-        for (int f = 0; f < GROUPS + RA; ++f) {
-            if (f < GROUPS) {
-                const int kbo = f / (NF * PARTS), i = (f % (NF * PARTS)) / PARTS, part = f % PARTS;
-                bq[f % (RA + 1)] = cur[((part * TG_FRAGS + i) * KBS + kbo) * 64 + lane];
-            }
-            if (f >= RA) {
-                const int g = f - RA;
-                const int kbo = g / (NF * PARTS), i = (g % (NF * PARTS)) / PARTS;
+            for (int f = 0; f < RA; ++f) bq[f % (RA + 1)] = frag_of(cur, f);
+            __builtin_amdgcn_sched_barrier(0);
+        }
 #pragma unroll
-                for (int j = 0; j < RT; ++j)
-                    acc[j][i] = tg_mma<HALFW>((FUSED && i >= NFH) ? dc.a1[kbo][j] : dc.a[kbo][j], bq[g % (RA + 1)], acc[j][i]);
+        for (int g = 0; g < GROUPS; ++g) {
+            constexpr int BASE = DEEP ? PH * GROUPS : 0;
+            if (g + RA < GROUPS) bq[(BASE + g + RA) % (RA + 1)] = frag_of(cur, g + RA);
+            else if (DEEP)       bq[(BASE + g + RA) % (RA + 1)] = frag_of(nxt, g + RA - GROUPS);
+            const int kbo = g / (NF * PARTS), i = (g % (NF * PARTS)) / PARTS;
 #pragma unroll
-                for (int u = g * UNITS / GROUPS; u < (g + 1) * UNITS / GROUPS; ++u) decode_unit(raw_n, dn, u, step + 1);
-            }
+            for (int j = 0; j < RT; ++j)
+                acc[j][i] = tg_mma<HALFW>((FUSED && i >= NFH) ? dc.a1[kbo][j] : dc.a[kbo][j], bq[(BASE + g) % (RA + 1)], acc[j][i]);
+#pragma unroll
+            for (int u = g * UNITS / GROUPS; u < (g + 1) * UNITS / GROUPS; ++u) decode_unit(raw_n, dn, u, step + 1);
+            if (DEEP && g < XPT) fetch_x_one(step + LEAD, fill, g);
             __builtin_amdgcn_sched_barrier(0);
         }
         // refill the registers just decoded with the weights of step s+3 (in/out operands: the
@@ -390,13 +394,10 @@ __device__ __forceinline__ void tile_body(const TgArgs &a, const uint16_t *wa, c
         __builtin_amdgcn_s_barrier();
         __builtin_amdgcn_sched_barrier(0);
     };
-    // stage of step s: ring + (s % 4) * TG_XSTAGE_UNITS
-    auto stage = [&](int step) { return ring + (step & (TG_XSTAGES - 1)) * TG_XSTAGE_UNITS; };
     u32x4 raw0[KBS][RT] = {}, raw1[KBS][RT] = {};      // packed weights of the even / of the odd steps
     Dec dec0, dec1;                                    // decoded operands of the even / of the odd steps
-    fetch_x(0, stage(0));
-    fetch_x(1, stage(1));
-    fetch_x(2, stage(2));
+#pragma unroll
+    for (int st = 0; st < LEAD; ++st) fetch_x(st, stage(st));
 #pragma unroll
     for (int kbo = 0; kbo < KBS; ++kbo) fetch_w(0, raw0, kbo);
 #pragma unroll
@@ -410,81 +411,19 @@ __device__ __forceinline__ void tile_body(const TgArgs &a, const uint16_t *wa, c
     __builtin_amdgcn_sched_barrier(0);
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_sched_barrier(0);
+    if (DEEP) {                            // the first fragments of stage 0
+#pragma unroll
+        for (int f = 0; f < RA; ++f) bq[f % (RA + 1)] = frag_of(stage(0), f);
+    }
 
     // Every step is the same code, the last ones included: their refills are clamped re-reads
     // and their decodes operands that nobody uses, their barrier is harmless.
     for (int step = 0;; step += 2) {
-        full_step(stage(step), stage(step + 3), raw1, dec0, dec1, step);
+        full_step(std::integral_constant<int, 0>{}, raw1, dec0, dec1, step);
         if (step + 1 >= n_steps) break;
-        full_step(stage(step + 1), stage(step + 4), raw0, dec1, dec0, step + 1);
+        full_step(std::integral_constant<int, 1>{}, raw0, dec1, dec0, step + 1);
         if (step + 2 >= n_steps) break;
     }
-#else
-    // One K step.  `cur` holds the activations of this step, `fill` is the stage read three steps
-    // ago (free since the last barrier); `raw` holds this step's packed weights and is refilled
-    // with those of step + 2 once they are decoded.
-    auto full_step = [&](const u32x4 *cur, u32x4 *fill, u32x4 (&raw)[KBS][RT], int step) {
-        fetch_x(step + 3, fill);
-#pragma unroll
-        for (int kbo = 0; kbo < KBS; ++kbo) {
-            wait_w(raw, kbo, false);
-            u32x4 af[RT], af1[RT];
-#pragma unroll
-            for (int j = 0; j < RT; ++j) {
-                af[j] = tg_decode<FUSED ? 0 : POS, DENSE, HALFW>(raw[kbo][j]);
-                af1[j] = FUSED ? tg_decode<1, DENSE, HALFW>(raw[kbo][j]) : af[j];
-            }
-            if (kbo > 0) {                 // a k-block past the end (odd count): multiply by zero
-                const bool valid = kb0 + step * KBS + kbo < kb1;
-                const u32x4 zero = {0u, 0u, 0u, 0u};
-#pragma unroll
-                for (int j = 0; j < RT; ++j) { af[j] = valid ? af[j] : zero; af1[j] = valid ? af1[j] : zero; }
-            }
-            fetch_w(step + 2, raw, kbo);
-            multiply(cur, af, af1, kbo);
-            // order of issue: a few fragment reads ahead, then one more read per pair of matrix
-            // instructions, so that the LDS latency is covered by the products of earlier fragments
-            __builtin_amdgcn_sched_group_barrier(0x100, TG_READ_AHEAD, 0);
-#pragma unroll
-            for (int f = 0; f < NF * PARTS; ++f) {
-                __builtin_amdgcn_sched_group_barrier(0x008, RT, 0);
-                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-            }
-        }
-        // A bare barrier (no fence): the only LDS writes are the direct loads, whose completion
-        // the wait above covers.  Nothing may be scheduled across it.
-        __builtin_amdgcn_sched_barrier(0);
-        __builtin_amdgcn_s_barrier();
-        __builtin_amdgcn_sched_barrier(0);
-    };
-    // stage of step s: ring + (s % 4) * TG_XSTAGE_UNITS
-    auto stage = [&](int step) { return ring + (step & (TG_XSTAGES - 1)) * TG_XSTAGE_UNITS; };
-    u32x4 raw0[KBS][RT] = {}, raw1[KBS][RT] = {};      // weights of the even / of the odd steps
-    fetch_x(0, stage(0));
-    fetch_x(1, stage(1));
-    fetch_x(2, stage(2));
-#pragma unroll
-    for (int kbo = 0; kbo < KBS; ++kbo) fetch_w(0, raw0, kbo);
-#pragma unroll
-    for (int kbo = 0; kbo < KBS; ++kbo) fetch_w(1, raw1, kbo);
-#pragma unroll
-    for (int kbo = 0; kbo < KBS; ++kbo) {  // everything landed (this wave's share of the stages too)
-        wait_w(raw0, kbo, true);
-        wait_w(raw1, kbo, true);
-    }
-    __builtin_amdgcn_sched_barrier(0);
-    __builtin_amdgcn_s_barrier();
-    __builtin_amdgcn_sched_barrier(0);
-
-    // Every step is the same code, the last ones included: their refills are clamped re-reads
-    // that nobody uses, their barrier is harmless.
-    for (int step = 0;; step += 2) {
-        full_step(stage(step), stage(step + 3), raw0, step);
-        if (step + 1 >= n_steps) break;
-        full_step(stage(step + 1), stage(step + 4), raw1, step + 1);
-        if (step + 2 >= n_steps) break;
-    }
-#endif
     // No load of this wave is in flight past this point: the refills of the last steps still
     // write the (now dead) weight registers, so nothing may be scheduled above this wait that
     // could be given one of them.
@@ -617,7 +556,7 @@ template <int STAGE, bool DENSE, bool ALLTOK, bool PERSIST, bool HALF>
 __global__ void __launch_bounds__(TG_THREADS) __attribute__((amdgpu_waves_per_eu(TG_WPE, TG_WPE)))
 tile_kernel(TgArgs a)
 {
-    __shared__ u32x4 ring[TG_XSTAGES * tg_stage_units<STAGE, HALF, DENSE>()];
+    __shared__ u32x4 ring[tg_ring_stages<STAGE, HALF, DENSE>() * tg_stage_units<STAGE, HALF, DENSE>()];
     __shared__ int32_t rowidx[TG_MAX_TOK];
     __shared__ int32_t drawn;
 
