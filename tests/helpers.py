@@ -31,7 +31,7 @@ class Case:
     """One layer: oracle-side packed tensors (numpy, logical order) + the library's Layer."""
 
     def __init__(self, cfg, oracle, binding, device="cuda", emap_mode="adjacent", gen_device=None,
-                 check_pack=True, from_merge=None):
+                 check_pack=True, from_merge=None, wide_h=False):
         self.cfg, self.oracle, self.binding = cfg, oracle, binding
         gen_device = gen_device or device
         self.emap = synth.expert_map(cfg, emap_mode)
@@ -90,7 +90,7 @@ class Case:
                                    [self.packed_gpu[p, synth.GATE] for p in range(P)],
                                    [self.packed_gpu[p, synth.UP] for p in range(P)],
                                    [self.packed_gpu[p, synth.DOWN] for p in range(P)], shared=shared_gpu,
-                                   dense=dense_gpu)
+                                   dense=dense_gpu, wide_h=wide_h)
         assert int(self.n_bad.item()) == 0
         self.device = device
 
