@@ -520,7 +520,7 @@ int pzl_layer_create(const pzl_layer_desc *desc, pzl_layer **out)
     // the address of this device's static scratch array and the kernels' dynamic-LDS attribute
     L->static_scratch = static_scratch_of_current_device();
     if (!L->static_scratch) { pzl_layer_destroy(L); return PZL_EHIP; }
-    { int rc_prep = prepare_stream_kernels(); if (rc_prep) { pzl_layer_destroy(L); return rc_prep; } }
+    { int rc_prep = prepare_stream_kernels(); if (!rc_prep) rc_prep = prepare_route_kernel(); if (rc_prep) { pzl_layer_destroy(L); return rc_prep; } }
     L->tile_stream = nullptr; L->ev_tfork = nullptr; L->ev_tjoin = nullptr;
     if (L->pair_format == 0) {
         e = hipStreamCreateWithFlags(&L->tile_stream, hipStreamNonBlocking);

@@ -74,6 +74,7 @@ int launch_q_unpack(const uint8_t *records, const uint16_t *scales, int pos, int
 // 0: never)
 int launch_route(const int32_t *ids, int32_t n_flat, int32_t k, int32_t n_experts, int32_t n_slots_q, const int32_t *q_of_expert,
                  RouteTables rt, int32_t tile_min, int32_t row_groups, int32_t launch_rows, hipStream_t st);
+int prepare_route_kernel();   // per-device kernel attribute; called at layer creation and (cheaply) by launch_route
 int launch_router_topk(const uint16_t *x, const uint16_t *w_router, int32_t T, int32_t d, int32_t E, int32_t k,
                        int32_t *ids_out, float *w_out, hipStream_t st);
 int launch_combine(const float *opart, int32_t ksplit, int32_t ksplit_shared, int64_t ks_stride, const RouteTables &rt,

@@ -3,12 +3,15 @@
 // unchanged"); they are the glue that lets one packed-pair read serve both experts'
 // token blocks, as the decode-GEMM of Sec. 3.3.2 requires.
 #include "pzl_common.h"
+#include <atomic>
 
 namespace pzl {
 
 constexpr int ROUTE_THREADS = 1024;
 constexpr int ROUTE_WAVES = ROUTE_THREADS / 64;
 constexpr int ROUTE_QMAX = 512;
+constexpr int ROUTE_EMAX = 256;                     // routed experts of a layer (pzl_layer_create's bound)
+constexpr int ROUTE_KEEP = 4;                       // trips of 256 ids that a wave keeps in registers
 
 __device__ __forceinline__ bool pair_is_fused(int c0, int c1)
 {
@@ -23,26 +26,29 @@ route_kernel(const int32_t *__restrict__ ids, int32_t n_flat, int32_t k, int32_t
              const int32_t *__restrict__ q_of_expert, int32_t Q, int32_t *__restrict__ cnt,
              int32_t *__restrict__ off, int32_t *__restrict__ slot_tok, int32_t *__restrict__ slot_of,
              int32_t *__restrict__ tile_q, int32_t *__restrict__ tile_slot0, int32_t *__restrict__ tile_n,
-             int32_t *__restrict__ n_tiles, int32_t tile_min, int32_t row_groups, int32_t launch_rows)
+             int32_t *__restrict__ n_tiles, int32_t tile_min, int32_t row_groups, int32_t launch_rows,
+             int32_t sorted_cap)
 {
     __shared__ int32_t hist[ROUTE_WAVES][ROUTE_QMAX];
     __shared__ int32_t total[ROUTE_QMAX];
     __shared__ bool tiled_pair[ROUTE_QMAX];
+    __shared__ int16_t q_of[ROUTE_EMAX];              // expert -> routing key, staged: the lookups below are LDS reads
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     for (int i = tid; i < ROUTE_WAVES * ROUTE_QMAX; i += ROUTE_THREADS) (&hist[0][0])[i] = 0;
-    __syncthreads();
+    for (int e = tid; e < n_experts; e += ROUTE_THREADS) q_of[e] = (int16_t)q_of_expert[e];
 
     int chunk = (n_flat + ROUTE_WAVES - 1) / ROUTE_WAVES;
     chunk = (chunk + 63) & ~63;
     const int lo = wave * chunk;
     const int hi = min(n_flat, lo + chunk);
 
-    // four ids per lane and trip (one 16-byte load when the range allows): the loop is bound by
-    // the latency of its loads, not by their number
+    // Four ids per lane and trip (one 16-byte load when the range allows).  The kernel is bound by
+    // the latency of its loads, not by their number: the first ROUTE_KEEP trips of a wave (1024
+    // ids; all of them up to 16384 entries) are loaded at once, before anything waits for them,
+    // and stay in registers for the scatter pass.
     const bool vec_ok = ((uintptr_t)ids & 15) == 0;      // lo is a multiple of 64 ids
-    for (int i = lo; i < hi; i += 256) {
-        const int idx = i + lane * 4;
-        int e4[4] = {-1, -1, -1, -1};
+    auto load4 = [&](int idx, int (&e4)[4]) {
+        e4[0] = e4[1] = e4[2] = e4[3] = -1;
         if (vec_ok && idx + 3 < hi) {
             const int4 v = *(const int4 *)(ids + idx);
             e4[0] = v.x; e4[1] = v.y; e4[2] = v.z; e4[3] = v.w;
@@ -50,9 +56,23 @@ route_kernel(const int32_t *__restrict__ ids, int32_t n_flat, int32_t k, int32_t
 #pragma unroll
             for (int j = 0; j < 4; ++j) if (idx + j < hi) e4[j] = ids[idx + j];
         }
+    };
+    int kept[ROUTE_KEEP][4];
+#pragma unroll
+    for (int r = 0; r < ROUTE_KEEP; ++r) load4(lo + r * 256 + lane * 4, kept[r]);
+    __syncthreads();                                     // hist is zero, q_of is there
+
+#pragma unroll
+    for (int r = 0; r < ROUTE_KEEP; ++r)
 #pragma unroll
         for (int j = 0; j < 4; ++j)
-            if (e4[j] >= 0 && e4[j] < n_experts) atomicAdd(&hist[wave][q_of_expert[e4[j]]], 1);
+            if (kept[r][j] >= 0 && kept[r][j] < n_experts) atomicAdd(&hist[wave][q_of[kept[r][j]]], 1);
+    for (int i = lo + ROUTE_KEEP * 256; i < hi; i += 256) {
+        int e4[4];
+        load4(i + lane * 4, e4);
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            if (e4[j] >= 0 && e4[j] < n_experts) atomicAdd(&hist[wave][q_of[e4[j]]], 1);
     }
     __syncthreads();
     // per-q totals, then turn hist[w][q] into the first slot of (q, wave w)
@@ -67,36 +87,55 @@ route_kernel(const int32_t *__restrict__ ids, int32_t n_flat, int32_t k, int32_t
     // pair's weights are swept by one path only.  If at least half of the pairs that have tokens
     // are such pairs, all of them go to the tiled kernels: two half-empty launches one after the
     // other are slower than either path alone.
-    __shared__ int32_t n_active, n_big, scan_c[ROUTE_QMAX], scan_t[ROUTE_QMAX];
-    if (tid == 0) { n_active = 0; n_big = 0; }
-    __syncthreads();
-    for (int g = tid; g < Q / 2; g += ROUTE_THREADS) {
-        int m = max(total[2 * g], total[2 * g + 1]);
-        if (m > 0) atomicAdd(&n_active, 1);
-        if (m >= tile_min) atomicAdd(&n_big, 1);
-    }
-    __syncthreads();
-    const bool all_tiled = n_big > 0 && 2 * n_big >= n_active;
+    //
     // One tile for both experts of a pair (see pair_is_fused) saves a second pass over the pair's
     // weights but does the work of two tiles in one workgroup.  Measured on the three layer shapes
     // it pays when the launch (tiles x row_groups workgroups, 256 at a time) gets shorter by well
     // over a third, counting a launch that does not fill the chip as one that just does; it costs
     // when it only thins out a launch that was already short.
-    __shared__ int32_t tiles_plain, tiles_half, pairs_fusable, tiled_max, tiled_sum, tiled_experts;
-    if (tid == 0) { tiles_plain = 0; tiles_half = 0; pairs_fusable = 0; tiled_max = 0; tiled_sum = 0; tiled_experts = 0; }
-    __syncthreads();
-    for (int g = tid; g < Q / 2; g += ROUTE_THREADS) {
-        const int c0 = total[2 * g], c1 = total[2 * g + 1];
-        if (all_tiled || max(c0, c1) >= tile_min) {
-            atomicAdd(&tiles_plain, (c0 + TILE_MAX_TOKENS - 1) / TILE_MAX_TOKENS + (c1 + TILE_MAX_TOKENS - 1) / TILE_MAX_TOKENS);
-            atomicAdd(&tiles_half, (c0 + TILE_HALF_TOKENS - 1) / TILE_HALF_TOKENS + (c1 + TILE_HALF_TOKENS - 1) / TILE_HALF_TOKENS);
-            if (pair_is_fused(c0, c1)) atomicAdd(&pairs_fusable, 1);
-            atomicMax(&tiled_max, max(c0, c1));
-            atomicAdd(&tiled_sum, c0 + c1);
-            atomicAdd(&tiled_experts, (c0 > 0) + (c1 > 0));
+    //
+    // The sums over the pairs behind these decisions are taken by wave 0 with shuffles (every thread
+    // adding to one LDS word took 60 cycles per pair and sum, 12 000 cycles with 32 pairs).
+    __shared__ int32_t scan_c[ROUTE_QMAX], scan_t[ROUTE_QMAX], n_slots_sh;
+    __shared__ int32_t all_tiled_sh, tiles_plain, tiles_half, pairs_fusable, tiled_max, tiled_sum, tiled_experts;
+    if (wave == 0) {
+        auto wave_sum = [](int v) {
+#pragma unroll
+            for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d);
+            return v;
+        };
+        auto wave_max = [](int v) {
+#pragma unroll
+            for (int d = 32; d >= 1; d >>= 1) v = max(v, __shfl_xor(v, d));
+            return v;
+        };
+        int act = 0, big = 0;
+        for (int g = lane; g < Q / 2; g += 64) {
+            const int m = max(total[2 * g], total[2 * g + 1]);
+            act += m > 0; big += m >= tile_min;
+        }
+        act = wave_sum(act); big = wave_sum(big);
+        const bool all = big > 0 && 2 * big >= act;
+        int tp = 0, th = 0, pf = 0, tm = 0, ts = 0, te = 0;
+        for (int g = lane; g < Q / 2; g += 64) {
+            const int c0 = total[2 * g], c1 = total[2 * g + 1];
+            if (all || max(c0, c1) >= tile_min) {
+                tp += (c0 + TILE_MAX_TOKENS - 1) / TILE_MAX_TOKENS + (c1 + TILE_MAX_TOKENS - 1) / TILE_MAX_TOKENS;
+                th += (c0 + TILE_HALF_TOKENS - 1) / TILE_HALF_TOKENS + (c1 + TILE_HALF_TOKENS - 1) / TILE_HALF_TOKENS;
+                pf += pair_is_fused(c0, c1);
+                tm = max(tm, max(c0, c1));
+                ts += c0 + c1;
+                te += (c0 > 0) + (c1 > 0);
+            }
+        }
+        tp = wave_sum(tp); th = wave_sum(th); pf = wave_sum(pf); tm = wave_max(tm); ts = wave_sum(ts); te = wave_sum(te);
+        if (lane == 0) {
+            all_tiled_sh = all; tiles_plain = tp; tiles_half = th; pairs_fusable = pf;
+            tiled_max = tm; tiled_sum = ts; tiled_experts = te;
         }
     }
     __syncthreads();
+    const bool all_tiled = all_tiled_sh != 0;
     // A launch of a few rounds of workgroups ends with its largest tiles: a busy expert's 281
     // tokens as one tile keep 11 workgroups running twice as long as the tiles of the others.
     // Such a launch, if its busiest expert has at least twice the tokens of the average tiled
@@ -150,7 +189,7 @@ route_kernel(const int32_t *__restrict__ ids, int32_t n_flat, int32_t k, int32_t
             scan_c[q] = run_c; scan_t[q] = run_t;
             run_c += c; run_t += t;
         }
-        if (lane == 63) { off[Q] = run_c; *n_tiles = run_t; }
+        if (lane == 63) { off[Q] = run_c; *n_tiles = run_t; n_slots_sh = run_c; }
         if (lane >= 8 && lane < 40) n_tiles[lane] = 0;               // work counters of the tiled launches
     }
     __syncthreads();
@@ -184,27 +223,40 @@ route_kernel(const int32_t *__restrict__ ids, int32_t n_flat, int32_t k, int32_t
     // up to the hardware, so the order of slots inside one expert is not fixed; nothing
     // downstream depends on it (every slot is computed on its own and the combine adds a
     // token's choices in choice order).
-    for (int i = lo; i < hi; i += 256) {
-        const int idx = i + lane * 4;
-        int e4[4] = {-1, -1, -1, -1};
-        if (vec_ok && idx + 3 < hi) {
-            const int4 v = *(const int4 *)(ids + idx);
-            e4[0] = v.x; e4[1] = v.y; e4[2] = v.z; e4[3] = v.w;
-        } else {
-#pragma unroll
-            for (int j = 0; j < 4; ++j) if (idx + j < hi) e4[j] = ids[idx + j];
-        }
+    // slot -> token goes through LDS where the list fits (sorted_cap entries of dynamic LDS): written
+    // straight to memory it is one scattered 4-byte store per entry, a cache line each, from a single
+    // compute unit (14 000 cycles for 12 288 entries); from LDS it leaves as whole lines.
+    extern __shared__ int32_t sorted_tok[];
+    const bool via_lds = n_flat <= sorted_cap;
+    auto scatter4 = [&](int idx, const int (&e4)[4]) {
+        int slot4[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            if (idx + j >= hi) continue;
-            if (e4[j] >= 0 && e4[j] < n_experts) {
-                int slot = atomicAdd(&hist[wave][q_of_expert[e4[j]]], 1);
-                slot_tok[slot] = (idx + j) / k;
-                slot_of[idx + j] = slot;
-            } else {
-                slot_of[idx + j] = -1;
+            slot4[j] = -1;
+            if (idx + j < hi && e4[j] >= 0 && e4[j] < n_experts) {
+                const int slot = atomicAdd(&hist[wave][q_of[e4[j]]], 1);
+                if (via_lds) sorted_tok[slot] = (idx + j) / k;
+                else         slot_tok[slot] = (idx + j) / k;
+                slot4[j] = slot;
             }
         }
+        if ((((uintptr_t)slot_of) & 15) == 0 && idx + 3 < hi) {
+            *(int4 *)(slot_of + idx) = make_int4(slot4[0], slot4[1], slot4[2], slot4[3]);
+        } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) if (idx + j < hi) slot_of[idx + j] = slot4[j];
+        }
+    };
+#pragma unroll
+    for (int r = 0; r < ROUTE_KEEP; ++r) scatter4(lo + r * 256 + lane * 4, kept[r]);
+    for (int i = lo + ROUTE_KEEP * 256; i < hi; i += 256) {
+        int e4[4];
+        load4(i + lane * 4, e4);
+        scatter4(i + lane * 4, e4);
+    }
+    if (via_lds) {
+        __syncthreads();
+        for (int i = tid; i < n_slots_sh; i += ROUTE_THREADS) slot_tok[i] = sorted_tok[i];
     }
 }
 
@@ -498,15 +550,37 @@ int launch_router_topk(const uint16_t *x, const uint16_t *w_router, int32_t T, i
     return PZL_OK;
 }
 
+// Dynamic LDS of the grouping kernel: the slot -> token list of batches up to this many entries
+constexpr int ROUTE_SORTED_CAP = 16384;
+
+// more than 64 KiB of LDS in all: a per-device attribute of the kernel, set once per device (layer
+// creation does it, so that no call under stream capture has to)
+int prepare_route_kernel()
+{
+    static std::atomic<uint64_t> attr_devices{0};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev > 63) dev = 63;       // unknown device: set it every time
+    if (dev == 63 || !((attr_devices.load(std::memory_order_relaxed) >> dev) & 1)) {
+        hipError_t e = hipFuncSetAttribute((const void *)route_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           ROUTE_SORTED_CAP * (int)sizeof(int32_t));
+        if (e != hipSuccess) { set_hip_error(e); return PZL_EHIP; }
+        if (dev != 63) attr_devices.fetch_or(1ull << dev, std::memory_order_relaxed);
+    }
+    return PZL_OK;
+}
+
 int launch_route(const int32_t *ids, int32_t n_flat, int32_t k, int32_t n_experts, int32_t n_slots_q,
                  const int32_t *q_of_expert, RouteTables rt, int32_t tile_min, int32_t row_groups, int32_t launch_rows,
                  hipStream_t st)
 {
     int Q = n_slots_q;
-    if (Q > ROUTE_QMAX) return PZL_EINVAL;
-    hipLaunchKernelGGL(route_kernel, dim3(1), dim3(ROUTE_THREADS), 0, st, ids, n_flat, k, n_experts,
+    if (Q > ROUTE_QMAX || n_experts > ROUTE_EMAX) return PZL_EINVAL;
+    int rc = prepare_route_kernel();
+    if (rc) return rc;
+    const int sorted_cap = n_flat <= ROUTE_SORTED_CAP ? ((n_flat + 63) & ~63) : 0;
+    hipLaunchKernelGGL(route_kernel, dim3(1), dim3(ROUTE_THREADS), sorted_cap * sizeof(int32_t), st, ids, n_flat, k, n_experts,
                        q_of_expert, Q, rt.cnt, rt.off, rt.slot_tok, rt.slot_of, rt.tile_q, rt.tile_slot0,
-                       rt.tile_n, rt.n_tiles, tile_min, row_groups, launch_rows);
+                       rt.tile_n, rt.n_tiles, tile_min, row_groups, launch_rows, sorted_cap);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) { set_hip_error(e); return PZL_EHIP; }
     return PZL_OK;
