@@ -158,10 +158,11 @@ typedef struct pzl_layer_desc {
     const uint16_t *const *gate_scale;    /* host [n_pairs] of device ptrs, or NULL (format 0) */
     const uint16_t *const *up_scale;
     const uint16_t *const *down_scale;
-    int32_t h_precision;            /* form of the SwiGLU output H of the packed pairs (format 0):
+    int32_t h_precision;            /* form of the SwiGLU output H of the packed pairs (format 0) and of the shared experts:
                                        0: automatic -- one plane of IEEE half precision if no used
                                           element of any down matrix has an exponent field above 29
-                                          (|w| < 2^15; pzl_layer_create scans them), else as 1;
+                                          (|w| < 2^15; pzl_layer_create scans them), else as 1
+                                          (shared experts: see pzl_moe_ffn);
                                        1: always two bf16 planes (hi + lo, about 16 significant bits,
                                           bf16's range): twice the matrix work in the down stage   */
 } pzl_layer_desc;
@@ -265,8 +266,12 @@ int pzl_moe_ffn_workspace_layout(const pzl_layer *layer, int32_t T, int32_t k, p
  * its weights to half precision, exactly, and runs on the f16 matrix instruction; |h| beyond 65504
  * saturates and is counted, |h| below 6e-5 keeps an absolute precision of 3e-8), or, where a down
  * matrix holds weights of 2^15 and more or the layer asks for it (h_precision), as two bf16 numbers
- * (hi = bf16(h), lo = bf16(h - hi)) that the down projection both multiplies, as unmerged, shared
- * and quantised experts always do.
+ * (hi = bf16(h), lo = bf16(h - hi)) that the down projection both multiplies, as unmerged and
+ * quantised experts always do.  Shared experts keep h in half precision too where they run on the
+ * tiled kernels (65 tokens and more) unless h_precision asks otherwise or a shared down matrix holds
+ * an infinity or a NaN: their bf16 down weights are then decoded to half precision times a power of
+ * two chosen from the largest weight of the launch's matrices (weights more than 2^30 below it
+ * count as zero), and the sums are scaled back.
  *   x         [T, d_model] bf16 bits, row-major
  *   topk_ids  [T, k] int32 expert ids in [0, E); duplicates within a token add up; ids
  *             outside the range are ignored (contribute nothing)

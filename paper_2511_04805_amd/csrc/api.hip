@@ -2,6 +2,7 @@
 // carving and the launch sequence of pzl_moe_ffn.  No kernel lives here.
 #include "pzl_common.h"
 
+#include <algorithm>
 #include <mutex>
 #include <new>
 #include <string.h>
@@ -70,6 +71,7 @@ struct pzl_layer {
     // no down matrix holds an exponent field above 29 (and the caller did not ask for the wide
     // form), else two bf16 planes.  Unmerged, shared and quantised experts always use two planes.
     bool half_h;
+    std::vector<int> shared_max_exp;   // per shared expert: largest bf16 exponent field of its down matrix, or -1 (keep H wide)
     int32_t *d_counters;               // [0] largest exponent field of the down matrices, [1] waves that saturated a value of H
 };
 
@@ -509,6 +511,22 @@ int pzl_layer_create(const pzl_layer_desc *desc, pzl_layer **out)
         if (rc_scan) { pzl_layer_destroy(L); return rc_scan; }
         L->half_h = mx <= 29;
     }
+    // The shared experts' down matrices likewise: with their largest exponent field known, the tiled
+    // kernels decode them to half precision times a power of two that puts the largest weights at
+    // the top of its range, and H can be one half-precision plane for them too.  Not with an
+    // infinity or a NaN among them (field 255), and not if the caller asked for wide H.
+    L->shared_max_exp.assign(S, -1);
+    if (S > 0 && desc->h_precision == 0) {
+        for (int sdx = 0; sdx < S; ++sdx) {
+            int32_t mx = 255;
+            e = hipMemset(L->d_counters, 0, sizeof(int32_t));
+            int rc_scan = e == hipSuccess ? launch_max_exp_bf16(desc->shared_down[sdx], (int64_t)d * desc->shared_d_ffn[sdx], L->d_counters, nullptr) : PZL_EHIP;
+            if (e == hipSuccess && !rc_scan) e = hipMemcpy(&mx, L->d_counters, sizeof(mx), hipMemcpyDeviceToHost);
+            if (e != hipSuccess) { set_hip_error(e); rc_scan = PZL_EHIP; }
+            if (rc_scan) { pzl_layer_destroy(L); return rc_scan; }
+            L->shared_max_exp[sdx] = mx <= 254 ? mx : -1;
+        }
+    }
     L->aux_stream = nullptr; L->ev_fork = nullptr; L->ev_join = nullptr;
     if (S > 0) {                                               // default priority, as every stream here
         e = hipStreamCreateWithFlags(&L->aux_stream, hipStreamNonBlocking);
@@ -746,6 +764,11 @@ int pzl_moe_ffn_staged(const pzl_layer *L, const uint16_t *x, const int32_t *top
                 a.rows = L->shared_f[s]; a.kdim = L->d_model;
                 a.act = x; a.act_is_x = 1;
                 a.h_out = h_s; a.h_slot_base = slot_base; a.h_plane_stride = hs_plane;
+                // half-precision H if every expert of the launch allows it, with their common scale
+                int mx = 0;
+                bool half_ok = true;
+                for (int j = 0; j < nb; ++j) { half_ok = half_ok && L->shared_max_exp[s + j] >= 0; mx = std::max(mx, L->shared_max_exp[s + j]); }
+                a.half_h = half_ok; a.dense_half_bias = std::max(mx - 30, 0); a.h_saturated = L->d_counters + 1;
                 rc = launch_tile_gateup(a, KIND_SHARED, sst);
                 if (rc) return rc;
                 a.w_a = L->d_sdown + s; a.w_b = nullptr;

@@ -162,6 +162,30 @@ max_exp_field_kernel(const uint16_t *__restrict__ packed, int64_t n_chunks, int3
     if ((threadIdx.x & 63) == 0 && mx) atomicMax(max_out, (int32_t)mx);
 }
 
+// Largest bf16 exponent field among the non-zero elements of a dense matrix (any element order):
+// what decides whether, and with which scale, its weights can be decoded to half precision.
+__global__ void __launch_bounds__(256)
+max_exp_bf16_kernel(const uint16_t *__restrict__ w, int64_t n_chunks, int32_t *__restrict__ max_out)
+{
+    uint32_t mx = 0;
+    for (int64_t chunk = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; chunk < n_chunks; chunk += (int64_t)gridDim.x * blockDim.x) {
+        u32x4 v = *(const u32x4 *)(w + chunk * 8);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) mx = max(mx, max((v[i] >> 7) & 255u, (v[i] >> 23) & 255u));
+    }
+    for (int off = 32; off > 0; off >>= 1) mx = max(mx, (uint32_t)__shfl_down((int)mx, off));
+    if ((threadIdx.x & 63) == 0 && mx) atomicMax(max_out, (int32_t)mx);
+}
+
+int launch_max_exp_bf16(const uint16_t *w, int64_t n_elems, int32_t *max_out, hipStream_t st)
+{
+    if (!w || !max_out || n_elems <= 0 || n_elems % 8) return PZL_EINVAL;
+    hipLaunchKernelGGL(max_exp_bf16_kernel, dim3(1024), dim3(256), 0, st, w, n_elems / 8, max_out);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) { set_hip_error(e); return PZL_EHIP; }
+    return PZL_OK;
+}
+
 int launch_max_exp_field(const uint16_t *packed, int64_t rows, int64_t cols, int32_t *max_out, hipStream_t st)
 {
     if (!packed || !max_out || rows <= 0 || cols <= 0 || (rows * cols) % 8) return PZL_EINVAL;

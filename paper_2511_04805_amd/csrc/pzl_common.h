@@ -56,6 +56,7 @@ int launch_merge_pack(const uint16_t *wi, const uint16_t *wj, const float *norm_
                       int64_t rows, int64_t cols, float tau, uint16_t *out, int32_t *n_similar,
                       int32_t *n_bad, hipStream_t st);
 
+int launch_max_exp_bf16(const uint16_t *w, int64_t n_elems, int32_t *max_out, hipStream_t st);   // atomicMax of the bf16 exponent fields of the non-zero elements
 int launch_max_exp_field(const uint16_t *packed, int64_t rows, int64_t cols, int32_t *max_out, hipStream_t st);
 
 // quant_codec.hip
@@ -158,7 +159,8 @@ struct TileGemmArgs {
     int32_t ksplit;               // down stage only: workgroups sharing one output tile along K
     int32_t max_mtiles;           // upper bound on token tiles (grid size)
     int32_t *tile_ctr;            // routed groups: 8 zeroed counters (one per XCD) for a persistent launch that draws its tiles, or nullptr
-    int32_t half_h;               // packed pairs only: H is one half-precision plane
+    int32_t half_h;               // H is one half-precision plane (packed pairs; shared experts with dense_half_bias >= 0)
+    int32_t dense_half_bias;      // dense weights of a half_h launch: largest exponent field of the down matrices - 30, at least 0
     int32_t *h_saturated;         // ... and this device counter is bumped when a value of H saturates (may be null)
 };
 int launch_tile_gateup(const TileGemmArgs &a, int kind, hipStream_t st);

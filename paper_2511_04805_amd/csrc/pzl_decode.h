@@ -39,4 +39,23 @@ __device__ __forceinline__ uint32_t decode_pair(uint32_t x, uint32_t body)
     return ((xs & 0x80008000u) | body) & m;
 }
 
+typedef unsigned short dec_u16x2 __attribute__((ext_vector_type(2)));
+
+// Two plain bf16 weights (a dense expert) as IEEE half precision times 2^(112 - B), B = `bias`:
+// the tensor's largest exponent field minus 30 (at least 0), so that its largest weights land on
+// half precision's largest exponent and everything down to 2^-30 of them stays a normal number.
+// Per half: exponent field clamped from below to B (smaller weights, and zeros, become zero or a
+// subnormal of no weight in a sum), the 15 bits moved up by three (the exponent's top bits fall
+// off the half), B subtracted from what is now the exponent's place modulo 64 -- exact, since the
+// true difference is within 0..30 -- and the sign put back.  clamp2 = B << 7 and bias2 =
+// (B << 10) mod 2^16, each in both halves.  Tensors with an infinity or a NaN are not decoded
+// this way.
+__device__ __forceinline__ uint32_t dense_pair_to_half_scaled(uint32_t x, uint32_t clamp2, uint32_t bias2)
+{
+    dec_u16x2 t = __builtin_bit_cast(dec_u16x2, x & 0x7FFF7FFFu);
+    t = __builtin_elementwise_max(t, __builtin_bit_cast(dec_u16x2, clamp2));
+    t = (t << 3) - __builtin_bit_cast(dec_u16x2, bias2);
+    return (x & 0x80008000u) | (__builtin_bit_cast(uint32_t, t) & 0x7FFF7FFFu);
+}
+
 }  // namespace pzl

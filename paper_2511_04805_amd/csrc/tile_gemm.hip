@@ -59,7 +59,7 @@ constexpr int TG_ROW_TILES = 2 * TG_WAVES;    // 16-row weight tiles per workgro
 template <int STAGE, bool HALF, bool DENSE>
 constexpr int tg_stage_units()
 {
-    return (STAGE == 1 /* down */ && (!HALF || DENSE)) ? TG_FRAGS * 2 * 64 : TG_FRAGS * TG_KBS_N * 64;
+    return (STAGE == 1 /* down */ && !HALF) ? TG_FRAGS * 2 * 64 : TG_FRAGS * TG_KBS_N * 64;
 }
 constexpr int TSTAGE_GATEUP = 0, TSTAGE_DOWN = 1;
 constexpr int TG_PERSISTENT_WGS = 256 * (8 / TG_WAVES);   // workgroups of a persistent launch: as many as the chip holds (8 waves per compute unit)
@@ -93,6 +93,8 @@ struct TgArgs {
     int32_t max_mtiles, n_ntiles, ksplit;
     int32_t *tile_ctr;
     int32_t *h_saturated;
+    float out_scale;              // half-precision down stage: what its sums are multiplied by (the weights' scale undone)
+    uint32_t dense_clamp2, dense_bias2;   // ... of dense weights: the constants of dense_pair_to_half_scaled
 };
 
 // One packed 16x32 tile decoded for position POS, as raw bits: bf16, or (HALFW) half precision
@@ -176,7 +178,7 @@ __device__ __forceinline__ void tile_body(const TgArgs &a, const uint16_t *wa, c
                                           u32x4 *ring, int32_t *rowidx, int32_t *draw_ctr, int32_t *drawn)
 {
     constexpr bool FUSED = POS == 2;
-    static_assert(!HALF || !DENSE, "half-precision H is for packed pairs");
+    static_assert(!HALF || !DENSE || ALLTOK, "half-precision H: packed pairs and shared experts");
     constexpr bool HALFW = HALF && STAGE == TSTAGE_DOWN;     // this stage's operands are half precision
     constexpr int KBS = (STAGE == TSTAGE_DOWN && !HALF) ? 1 : TG_KBS_N;      // k-blocks (of 32) per K step
     constexpr int PARTS = (STAGE == TSTAGE_DOWN && !HALF) ? 2 : 1;    // activation planes (hi, lo)
@@ -332,7 +334,16 @@ __device__ __forceinline__ void tile_body(const TgArgs &a, const uint16_t *wa, c
     auto decode_unit = [&](u32x4 (&raw)[KBS][RT], Dec &d, int u, int step) {
         if (DENSE) {
             const int kbo = u / RT, j = u % RT;
-            d.a[kbo][j] = tg_decode<0, true, false>(raw[kbo][j]);
+            if (HALFW) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    uint32_t v = dense_pair_to_half_scaled(raw[kbo][j][i], a.dense_clamp2, a.dense_bias2);
+                    asm volatile("" : "+v"(v));               // stays between this step's matrix instructions (see below)
+                    d.a[kbo][j][i] = v;
+                }
+            } else {
+                d.a[kbo][j] = tg_decode<0, true, false>(raw[kbo][j]);
+            }
             if (kbo > 0 && !(kb0 + step * KBS + kbo < kb1)) d.a[kbo][j] = (u32x4){0u, 0u, 0u, 0u};
             d.a1[kbo][j] = d.a[kbo][j];
         } else {
@@ -472,9 +483,9 @@ __device__ __forceinline__ void tile_body(const TgArgs &a, const uint16_t *wa, c
             for (int j = 0; j < RT; ++j) {
                 int grt = ntile * TG_ROW_TILES + wave * RT + j;
                 if (grt >= row_tiles) continue;
-                // (half-precision weights were decoded as 2 w: halve the sums, which is exact)
+                // (half-precision weights were decoded times a power of two: undo it, which is exact)
                 *(f32x4 *)(a.o_out + (int64_t)ks * a.o_ks_stride + (int64_t)slot * a.rows + grt * 16 + rsub) =
-                    HALFW ? acc[j][i] * 0.5f : acc[j][i];
+                    HALFW ? acc[j][i] * a.out_scale : acc[j][i];
             }
         }
     }
@@ -648,6 +659,14 @@ static int launch(const TileGemmArgs &t, hipStream_t st)
         if (blocks > TG_PERSISTENT_WGS) blocks = TG_PERSISTENT_WGS;
     }
     a.h_saturated = t.h_saturated;
+    a.out_scale = 0.5f; a.dense_clamp2 = 0; a.dense_bias2 = 0;
+    if (DENSE && HALF) {
+        const int B = t.dense_half_bias;
+        if (B < 0 || B > 224) return PZL_EINVAL;
+        a.out_scale = ldexpf(1.0f, B - 112);
+        a.dense_clamp2 = ((uint32_t)B << 7) * 0x00010001u;
+        a.dense_bias2 = (((uint32_t)B << 10) & 0xFFFFu) * 0x00010001u;
+    }
     if (a.tile_ctr) hipLaunchKernelGGL((tile_kernel<STAGE, DENSE, ALLTOK, !ALLTOK, HALF>), dim3((unsigned)blocks), dim3(TG_THREADS), 0, st, a);
     else            hipLaunchKernelGGL((tile_kernel<STAGE, DENSE, ALLTOK, false, HALF>), dim3((unsigned)blocks), dim3(TG_THREADS), 0, st, a);
     hipError_t e = hipGetLastError();
@@ -661,6 +680,7 @@ int launch_tile_gateup(const TileGemmArgs &a, int kind, hipStream_t st)
 {
     if (kind == 0 && a.half_h) return launch<TSTAGE_GATEUP, false, false, true>(a, st);
     if (kind == 0) return launch<TSTAGE_GATEUP, false, false>(a, st);
+    if (kind == 1 && a.half_h) return launch<TSTAGE_GATEUP, true, true, true>(a, st);
     if (kind == 1) return launch<TSTAGE_GATEUP, true, true>(a, st);
     return launch<TSTAGE_GATEUP, true, false>(a, st);
 }
@@ -669,6 +689,7 @@ int launch_tile_down(const TileGemmArgs &a, int kind, hipStream_t st)
 {
     if (kind == 0 && a.half_h) return launch<TSTAGE_DOWN, false, false, true>(a, st);
     if (kind == 0) return launch<TSTAGE_DOWN, false, false>(a, st);
+    if (kind == 1 && a.half_h) return launch<TSTAGE_DOWN, true, true, true>(a, st);
     if (kind == 1) return launch<TSTAGE_DOWN, true, true>(a, st);
     return launch<TSTAGE_DOWN, true, false>(a, st);
 }

@@ -8,7 +8,11 @@ wide form (two bf16 planes).  Checked here against the CPU oracle, which knows n
     clamped and zero words, in the wide form, and whose down matrices span 112..141 in the
     half-precision form;
   - activations scaled down until H sits in half precision's subnormal range, and scaled up until
-    it saturates (counted, finite; the wide form of the same layer stays within the bound).
+    it saturates (counted, finite; the wide form of the same layer stays within the bound);
+  - shared (dense bf16) experts on the tiled kernels, whose H is one half-precision plane too and
+    whose down matrices are decoded to half precision times a power of two taken from their
+    largest exponent: ordinary weights, weights over 30 and over 80 binades, huge and tiny ones,
+    two experts of one launch with different ranges, saturation, and the wide form on request.
 """
 import numpy as np
 import pytest
@@ -57,8 +61,12 @@ def test_half_decode_all_words(oracle, binding):
 class PlaneCase:
     """A layer built from explicit pack inputs: planes[p][which] = dict(merged, mask0, mask1, sign0, sign1)."""
 
-    def __init__(self, oracle, binding, d, f, planes, wide_h=False):
+    def __init__(self, oracle, binding, d, f, planes, wide_h=False, shared=()):
+        """shared: (gate [fs, d], up [fs, d], down [d, fs]) bf16 bit patterns (uint16) per shared expert."""
         self.oracle, self.d, self.f = oracle, d, f
+        self.shared_cpu = [tuple(np.ascontiguousarray(m) for m in mats) for mats in shared]
+        shared_gpu = [tuple(binding.pzl_tile_dense(torch.from_numpy(m.view(np.int16)).cuda()) for m in mats) + (mats[0].shape[0],)
+                      for mats in self.shared_cpu]
         P = len(planes)
         self.cpu, gpu = {}, {}
         n_bad = torch.zeros(1, dtype=torch.int32, device="cuda")
@@ -79,7 +87,7 @@ class PlaneCase:
         self.P = P
         self.layer = binding.Layer(d, f, self.pair, self.pos, [gpu[p, synth.GATE] for p in range(P)],
                                    [gpu[p, synth.UP] for p in range(P)], [gpu[p, synth.DOWN] for p in range(P)],
-                                   wide_h=wide_h)
+                                   shared=shared_gpu, wide_h=wide_h)
 
     def gpu(self, x, ids, w):
         y = self.layer.pzl_moe_ffn(torch.from_numpy(x.view(np.int16)).cuda(), torch.from_numpy(ids).cuda(),
@@ -90,7 +98,7 @@ class PlaneCase:
     def ref(self, x, ids, w):
         return self.oracle.moe_ffn(x, ids, w, self.pair, self.pos, [self.cpu[p, synth.GATE] for p in range(self.P)],
                                    [self.cpu[p, synth.UP] for p in range(self.P)],
-                                   [self.cpu[p, synth.DOWN] for p in range(self.P)])[0]
+                                   [self.cpu[p, synth.DOWN] for p in range(self.P)], shared=self.shared_cpu)[0]
 
 
 def draw_planes(rng, shape, exp_lo, exp_hi, sigma=None):
@@ -188,3 +196,75 @@ def test_small_and_large_activations(oracle, binding, T):
     ok, worst = tolerance_ok(wide.gpu(x, ids, w), case.ref(x, ids, w))
     say("wide H, T=%d, x scaled by 2^10: worst err / bound = %.3f" % (T, worst))
     assert ok, worst
+
+
+def dense_bits(rng, shape, exp_lo=None, exp_hi=None, sigma=None):
+    """bf16 bit patterns: exponents uniform over [exp_lo, exp_hi] with random mantissas, or N(0, sigma); random
+    signs, a sprinkle of exact zeros."""
+    n = shape[0] * shape[1]
+    if sigma is None:
+        bits = ((rng.randint(exp_lo, exp_hi + 1, size=n) << 7) | rng.randint(0, 128, size=n)).astype(np.uint16)
+    else:
+        v = np.abs(rng.randn(n) * sigma).astype(np.float32)
+        bits = ((v.view(np.uint32) + 0x8000) >> 16).astype(np.uint16)
+    bits[rng.rand(n) < 0.01] = 0
+    bits |= (rng.randint(0, 2, size=n).astype(np.uint16) << 15)
+    return bits.reshape(shape)
+
+
+@pytest.mark.parametrize("T", [80, 300])
+def test_shared_experts_half_form_weight_ranges(oracle, binding, T):
+    """Three shared experts on the tiled kernels (65 tokens and more).  The two of width 256 share a
+    launch and hence a scale: one has ordinary down weights, the other's span 30 binades up to 2^73
+    (everything of the first then sits far below the common top and is flushed -- the oracle's sum
+    is dominated by the second in the same way).  The third, of width 128, spans 80 binades."""
+    rng = np.random.RandomState(504)
+    d, f, P = 256, 128, 1
+    cfg = synth.LayerConfig("r", 2, d, f, 1, (1,))
+    planes = [{which: draw_planes(rng, synth.matrix_shape(cfg, which), 0, 0, sigma=0.05) for which in W3}]
+    for spans in (((None, None, 0.05), (None, None, 0.04), (None, None, 0.06)),     # ordinary weights, three experts
+                  ((None, None, 0.05), (170, 200, None), (40, 120, None)),            # huge next to ordinary; 80 binades
+                  ((20, 50, None), (20, 50, None), (1, 29, None))):                   # tiny: below half precision's own range
+        shared = []
+        for (lo, hi, sg), fs in zip(spans, (256, 256, 128)):
+            shared.append((dense_bits(rng, (fs, d), sigma=0.05), dense_bits(rng, (fs, d), sigma=0.05),
+                           dense_bits(rng, (d, fs), lo, hi, sg)))
+        x, ids, w = batch(rng, T, d, 2, 1)
+        ref = None
+        for wide in (False, True):
+            case = PlaneCase(oracle, binding, d, f, planes, wide_h=wide, shared=shared)
+            ref = case.ref(x, ids, w) if ref is None else ref
+            assert np.isfinite(ref).all()
+            ok, worst = tolerance_ok(case.gpu(x, ids, w), ref)
+            say("shared experts, down spans %s, %s H, T=%d: worst err / bound = %.3f" % (
+                [sp[:2] if sp[2] is None else "N(0,%g)" % sp[2] for sp in spans], "wide" if wide else "half-precision", T, worst))
+            assert ok, worst
+            assert case.layer.h_info()[1] == 0
+
+
+def test_shared_expert_saturation_is_counted(oracle, binding):
+    """Packed pairs with small gate/up weights (their H stays small) and a shared expert with large
+    ones: with activations scaled up, only the shared expert's H passes 65504.  The half-precision
+    form saturates and counts it; the wide form of the same layer is within the bound.  Below 65
+    tokens the shared experts run on the streaming kernels, which keep H wide: no saturation."""
+    rng = np.random.RandomState(505)
+    d, f, P = 256, 128, 1
+    cfg = synth.LayerConfig("r", 2, d, f, 1, (1,))
+    planes = [{which: draw_planes(rng, synth.matrix_shape(cfg, which), 0, 0, sigma=0.01) for which in W3}]
+    shared = [(dense_bits(rng, (256, d), sigma=2.0), dense_bits(rng, (256, d), sigma=2.0), dense_bits(rng, (d, 256), sigma=0.05))]
+    case = PlaneCase(oracle, binding, d, f, planes, shared=shared)
+    x, ids, w = batch(rng, 100, d, 2, 1, scale=64.0)
+    y = case.gpu(x, ids, w)
+    assert np.isfinite(bits_to_f64(y)).all()
+    assert case.layer.h_info()[1] > 0
+    wide = PlaneCase(oracle, binding, d, f, planes, wide_h=True, shared=shared)
+    ref = case.ref(x, ids, w)
+    ok, worst = tolerance_ok(wide.gpu(x, ids, w), ref)
+    say("shared expert, |H| beyond 65504, wide H: worst err / bound = %.3f" % worst)
+    assert ok, worst
+    assert wide.layer.h_info()[1] == 0
+    small = PlaneCase(oracle, binding, d, f, planes, shared=shared)
+    ok, worst = tolerance_ok(small.gpu(x[:40], ids[:40], w[:40]), ref[:40])
+    say("shared expert, |H| beyond 65504, 40 tokens (streaming kernels): worst err / bound = %.3f" % worst)
+    assert ok, worst
+    assert small.layer.h_info()[1] == 0
