@@ -9,8 +9,8 @@ copy, a spill or a re-use of such a register would read stale data or, worse, le
 overwrite an unrelated value such as an address.
 
 This module compiles `csrc/tile_gemm.hip` to gfx950 assembly and verifies, for every K loop, that
-no instruction after an inline-asm `global_load_dwordx4` names one of its destination registers
-before the loop wraps around (one exception: a lane-0 read into a scalar register that is
+no instruction names a destination register of an inline-asm `global_load_dwordx4` between the
+load and the hand-written wait that covers it, across the loop's back edge too (one exception: a lane-0 read into a scalar register that is
 overwritten before it is read on every path, which is how the compiler materialises an undefined
 value), that every loop exit waits for all loads before any vector instruction, and that nothing
 spills.  A developer tool that lives with its test (test_tile_isa.py), not in the product
@@ -149,19 +149,45 @@ def _known_ones(lines, i):
 
 
 def _k_loops(lines, labels):
-    """(first line, line of the backward branch) of every K loop: a backward branch whose body holds
-    matrix instructions, inline-asm weight loads, exactly two barriers (two K steps per trip) and
-    no store."""
+    """(first line, line of the last backward branch) of every K loop.  A loop is a header label (the
+    compiler marks it) with the blocks it notes as belonging to that header; its extent in the text
+    runs from the first of these that a backward branch names to the last such branch (the
+    compiler may rotate a loop, or place its exit blocks in front of the header).  K loops are those
+    whose extent holds matrix instructions, inline-asm weight loads, two or four barriers (two or
+    four K steps per trip) and no store."""
+    header_of = {}
+    for name, at in labels.items():
+        if _is_loop_header(lines, at):
+            header_of[name] = name
+        else:
+            m = re.search(r"in Loop: Header=(BB\d+_\d+)", lines[at])
+            if m:
+                header_of[name] = ".L" + m.group(1)
+    extent = {}
     for i, l in enumerate(lines):
         m = re.match(r"\s+s_cbranch_\w+\s+(\.LBB\d+_\d+)", l)
-        if not m or labels.get(m.group(1), i) >= i:
+        if not m or labels.get(m.group(1), i) >= i or m.group(1) not in header_of:
             continue
-        start = labels[m.group(1)]
+        h = header_of[m.group(1)]
+        lo, hi = extent.get(h, (labels[m.group(1)], i))
+        extent[h] = (min(lo, labels[m.group(1)]), max(hi, i))
+    for start, i in sorted(extent.values()):
         body = lines[start:i]
-        if (sum("v_mfma" in b for b in body) < 8 or not any("global_load_dwordx4" in b for b in body)
-                or sum("s_barrier" in b for b in body) != 2 or any("global_store" in b for b in body)):
+        if (sum("v_mfma" in b for b in body) < 2 or not any("global_load_dwordx4" in b for b in body)
+                or sum("s_barrier" in b for b in body) not in (2, 4) or any("global_store" in b for b in body)):
             continue
         yield start, i
+
+
+def _is_loop_header(lines, at):
+    """The compiler's own note on a label: a loop header (the note may follow on the next comment
+    line, after the parent loop's), as opposed to a block that merely belongs to a loop."""
+    j = at
+    while j < len(lines) and (j == at or lines[j].strip().startswith(";")):
+        if re.search(r"=>\s*This (Inner )?Loop Header", lines[j]):
+            return True
+        j += 1
+    return False
 
 
 def _labels(lines):
@@ -211,32 +237,46 @@ def check(asm_text):
     for start, i in _k_loops(lines, labels):
         body = lines[start:i]
         n_loops += 1
-        inflight = set()
-        in_asm = False
-        for k, b in enumerate(body):
-            if "ASMSTART" in b:
-                in_asm = True
-                continue
-            if "ASMEND" in b:
-                in_asm = False
-                continue
-            t = b.split(";")[0]
-            if not t.strip() or t.strip().startswith("."):
-                continue
-            is_load = in_asm and "global_load_dwordx4" in t
-            hit = _regs(t) & inflight
-            if hit and not is_load:
-                # The compiler materialises an undefined scalar (a loop-carried value on an exit
-                # path) by reading lane 0 of any vector register.  Reading an in-flight register
-                # does not disturb the load; it is accepted only if the scalar is provably dead.
-                mrf = re.match(r"\s*v_readfirstlane_b32\s+s(\d+),\s*v\d+\s*$", t)
-                if mrf and _scalar_dead(lines, labels, start + k + 1, int(mrf.group(1)), set(), [60000],
-                                        _known_ones(lines, start + k)):
+        # Loads complete in issue order and the waits name how many of the youngest may still be
+        # out: keep the queue of outstanding loads (destination registers of the inline-asm weight
+        # loads; nothing for a load into LDS) and drop from its old end at every wait.  Three trips
+        # through the body (which may be rotated), so that what the end of a trip leaves in flight
+        # meets the start of the next in the steady state.
+        outstanding = []
+        seen = set()
+        for trip in range(3):
+            in_asm = False
+            for k, b in enumerate(body):
+                if "ASMSTART" in b:
+                    in_asm = True
                     continue
-                problems.append("line %d touches in-flight v%s: %s" % (start + k + 1, sorted(hit)[:4], t.strip()))
-            if is_load:
-                m2 = re.search(r"global_load_dwordx4\s+v\[(\d+):(\d+)\]", t)
-                inflight.update(range(int(m2.group(1)), int(m2.group(2)) + 1))
+                if "ASMEND" in b:
+                    in_asm = False
+                    continue
+                t = b.split(";")[0]
+                if not t.strip() or t.strip().startswith("."):
+                    continue
+                mw = re.search(r"s_waitcnt.*vmcnt\((\d+)\)", t)
+                if mw:
+                    del outstanding[:max(0, len(outstanding) - int(mw.group(1)))]
+                    continue
+                is_load = in_asm and re.search(r"global_load_dwordx4\s+v", t) is not None
+                inflight = set().union(*outstanding) if outstanding else set()
+                hit = _regs(t) & inflight
+                if hit and not is_load and (k, tuple(sorted(hit))) not in seen:
+                    seen.add((k, tuple(sorted(hit))))
+                    # The compiler materialises an undefined scalar (a loop-carried value on an exit
+                    # path) by reading lane 0 of any vector register.  Reading an in-flight register
+                    # does not disturb the load; it is accepted only if the scalar is provably dead.
+                    mrf = re.match(r"\s*v_readfirstlane_b32\s+s(\d+),\s*v\d+\s*$", t)
+                    if not (mrf and _scalar_dead(lines, labels, start + k + 1, int(mrf.group(1)), set(), [60000],
+                                                 _known_ones(lines, start + k))):
+                        problems.append("line %d touches in-flight v%s: %s" % (start + k + 1, sorted(hit)[:4], t.strip()))
+                if is_load:
+                    m2 = re.search(r"global_load_dwordx4\s+v\[(\d+):(\d+)\]", t)
+                    outstanding.append(set(range(int(m2.group(1)), int(m2.group(2)) + 1)))
+                elif re.search(r"\b(global|buffer|flat|scratch)_load", t):
+                    outstanding.append(set())                 # into LDS, or the compiler's own: counted, not tracked
     # loop exits: the hand-written "wait for everything" must be the first thing in its block
     n_exits = 0
     for i, l in enumerate(lines):

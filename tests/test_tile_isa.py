@@ -29,7 +29,7 @@ def test_tile_kernel_in_flight_registers(tmp_path):
 def test_checker_flags_a_planted_copy():
     """The checker itself: a copy of a register that an asm load has just written is reported."""
     body = ["\tv_mfma_f32_16x16x32_bf16 v[0:3], v[4:7], v[8:11], v[0:3]"] * 8
-    text = "\n".join([".LBB0_1:"] + body + [
+    text = "\n".join([".LBB0_1:                                ; =>This Inner Loop Header: Depth=1"] + body + [
         "\t;;#ASMSTART", "\tglobal_load_dwordx4 v[20:23], v1, s[2:3]", "\t;;#ASMEND",
         "\ts_barrier", "\tv_mov_b32_e32 v30, v21", "\ts_barrier",
         "\ts_cbranch_scc1 .LBB0_1"])
@@ -39,13 +39,35 @@ def test_checker_flags_a_planted_copy():
     assert check_tile_isa.check(clean)[2] == []
 
 
+def test_checker_follows_the_waits():
+    """A register is in flight from its load to the wait that covers it: a read after `vmcnt(0)` is
+    fine, a read after a wait that still allows the load to be out is reported, and so is a read at
+    the top of the loop of what the previous trip left in flight."""
+    hdr = ".LBB0_1:                                ; =>This Inner Loop Header: Depth=1"
+    mfma = ["\tv_mfma_f32_16x16x32_bf16 v[0:3], v[4:7], v[8:11], v[0:3]"] * 4
+    load = ["\t;;#ASMSTART", "\tglobal_load_dwordx4 v[20:23], v1, s[2:3]", "\t;;#ASMEND"]
+    lds_load = ["\t;;#ASMSTART", "\tglobal_load_lds_dwordx4 v1, s[2:3]", "\t;;#ASMEND"]
+    def prog(wait, use_at_top=False):
+        top = ["\tv_mov_b32_e32 v30, v21"] if use_at_top else []
+        return "\n".join([hdr] + top + mfma + load + lds_load + ["\ts_barrier"] +
+                         ["\t;;#ASMSTART", "\ts_waitcnt vmcnt(%d)" % wait, "\t;;#ASMEND"] +
+                         ([] if use_at_top else ["\tv_mov_b32_e32 v30, v21"]) + mfma + ["\ts_barrier", "\ts_cbranch_scc1 .LBB0_1"])
+    assert check_tile_isa.check(prog(1))[2] == []            # one load may be out: the younger one, into LDS
+    bad = check_tile_isa.check(prog(2))[2]                    # two may be out: v[20:23] may still be in flight
+    assert len(bad) == 1 and "v_mov_b32" in bad[0]
+    assert check_tile_isa.check(prog(0))[2] == []
+    bad = check_tile_isa.check(prog(2, use_at_top=True))[2]   # left in flight by the previous trip
+    assert len(bad) == 1 and "v_mov_b32" in bad[0]
+    assert check_tile_isa.check(prog(1, use_at_top=True))[2] == []
+
+
 def test_checker_accepts_only_dead_lane_reads():
     """A lane-0 read of an in-flight register into a scalar register is how the compiler
     materialises an undefined value; it is accepted only if that scalar is overwritten before it is
     read on every path (here: the loop continues and redefines it, or the exit path ends)."""
     body = ["\tv_mfma_f32_16x16x32_bf16 v[0:3], v[4:7], v[8:11], v[0:3]"] * 8
     def prog(after_exit):
-        return "\n".join([".LBB0_1:", "\ts_add_i32 s9, s8, 2"] + body + [
+        return "\n".join([".LBB0_1:                                ; =>This Inner Loop Header: Depth=1", "\ts_add_i32 s9, s8, 2"] + body + [
             "\t;;#ASMSTART", "\tglobal_load_dwordx4 v[20:23], v1, s[2:3]", "\t;;#ASMEND",
             "\ts_barrier", "\ts_barrier",
             "\ts_mov_b64 s[4:5], -1", "\ts_cmp_ge_i32 s9, s10",
