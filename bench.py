@@ -8,9 +8,11 @@ and weights are resident in HBM before the timed region.  Prints one JSON line.
 """
 import argparse
 import ctypes
+import glob
 import json
 import os
 import sys
+import threading
 import time
 
 import numpy as np
@@ -200,6 +202,104 @@ def time_stage(hip, layer, xt, idt, wt, steps, warmup, stage="gateup"):
     return float(np.median(stage_ms)), float(np.mean(stage_ms))
 
 
+class PowerSampler:
+    """Board power while a loop runs: the driver's hwmon reading (microwatts), sampled every 20 ms by
+    a host thread; None where the files cannot be read.  The reading is the driver's own running
+    average, so only loops of a second or more say anything."""
+
+    def __init__(self):
+        self.files = sorted(glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_input") +
+                            glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_average"))[:1]
+        caps = sorted(glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_cap"))[:1]
+        self.cap_w = None
+        try:
+            self.cap_w = int(open(caps[0]).read()) / 1e6 if caps else None
+        except (OSError, ValueError):
+            pass
+
+    def _read(self):
+        try:
+            return int(open(self.files[0]).read()) / 1e6
+        except (OSError, ValueError, IndexError):
+            return None
+
+    def measure(self, call, seconds=2.0):
+        """Runs `call` in batches for `seconds`; returns the mean reading over the second half."""
+        if self._read() is None:
+            return None
+        samples, stop = [], [False]
+
+        def loop():
+            while not stop[0]:
+                samples.append(self._read())
+                time.sleep(0.02)
+        th = threading.Thread(target=loop)
+        th.start()
+        t_end = time.perf_counter() + seconds
+        while time.perf_counter() < t_end:
+            for _ in range(10):
+                call()
+            torch.cuda.synchronize()
+        stop[0] = True
+        th.join()
+        tail = [v for v in samples[len(samples) // 2:] if v is not None]
+        return float(np.mean(tail)) if tail else None
+
+
+def vendor_gemm_tflops(m, k, n, masked):
+    """Context only: the vendor library's plain bf16 GEMM (torch.matmul) of the gate/up contraction's
+    shape on operands of the same distribution (x ~ N(0,1), w ~ N(0,0.02), half of w zero if
+    `masked`), weights already decoded in memory.  What the matrix cores deliver on this board at
+    its power limit when nothing is decoded or gathered."""
+    g = torch.Generator(device="cuda"); g.manual_seed(11)
+    a = torch.randn(m, k, generator=g, device="cuda").to(torch.bfloat16)
+    b = torch.randn(n, k, generator=g, device="cuda") * 0.02
+    if masked:
+        b = b * (torch.rand(n, k, generator=g, device="cuda") < 0.5)
+    b = b.to(torch.bfloat16)
+    c = torch.empty(m, n, dtype=torch.bfloat16, device="cuda")
+    t_end = time.perf_counter() + 1.0
+    while time.perf_counter() < t_end:
+        for _ in range(10):
+            torch.matmul(a, b.t(), out=c)
+        torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ms = []
+    for _ in range(REPEATS):
+        e0.record()
+        for _ in range(20):
+            torch.matmul(a, b.t(), out=c)
+        e1.record()
+        torch.cuda.synchronize()
+        ms.append(e0.elapsed_time(e1) / 20)
+    return 2.0 * m * k * n / (float(np.median(ms)) * 1e-3) / 1e12
+
+
+def uniform_routing(T):
+    """Top-2 ids over 8 experts that give every expert exactly T/4 tokens (T a multiple of 8)."""
+    t = np.arange(T)
+    return np.stack([t % 8, (t % 8 + 1 + (t // 8) % 7) % 8], axis=1).astype(np.int32)
+
+
+def tile_curve(hip, cfg, layer, sizes):
+    """Duration of the tiled launches against the tile size: every expert of the Mixtral-shaped layer
+    gets exactly n tokens (one tile of n up to 288, else equal tiles), for each n in `sizes`."""
+    out = []
+    for n in sizes:
+        T = 4 * n
+        ids = uniform_routing(T)
+        x = synth.tokens(cfg, T)
+        xt, idt = torch.from_numpy(x.view(np.int16)).cuda(), torch.from_numpy(ids).cuda()
+        wt = torch.full((T, 2), 0.5, dtype=torch.float32, device="cuda")
+        gu, _ = time_stage(hip, layer, xt, idt, wt, 20, 3, "gateup")
+        dn, _ = time_stage(hip, layer, xt, idt, wt, 20, 0, "down")
+        tiles = -(-n // 288)
+        out.append({"tokens_per_expert": n, "tiles_per_expert": tiles, "fragments_per_tile": -(-(-(-n // tiles)) // 16),
+                    "gateup_ms": gu, "down_ms": dn,
+                    "gateup_mfma_frac": 2 * 2.0 * T * cfg.top_k * cfg.d_model * cfg.d_ffn / (gu * 1e-3) / 2.5e15})
+    return out
+
+
 def decode_point(hip, cfg, layer, emap, T, steps, warmup):
     """One decode batch size: the whole step and its two weight-streaming kernels."""
     x, ids, w, xt, idt, wt = batch(cfg, T)
@@ -233,6 +333,9 @@ def main():
     ap.add_argument("--no-prefill", action="store_true")
     ap.add_argument("--no-quant", action="store_true")
     ap.add_argument("--no-other-shapes", action="store_true")
+    ap.add_argument("--no-context", action="store_true", help="skip the board-power readings and the vendor GEMM of the prefill shape")
+    ap.add_argument("--tile-curve", type=str, default="", metavar="N,N,...",
+                    help="only time the tiled launches with exactly N tokens per expert (Mixtral-shaped layer) and print that")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (--gpus must be 1)", file=sys.stderr)
@@ -254,6 +357,10 @@ def main():
             cpu_packed[p, which] = oracle.pack(planes["merged"], planes["mask0"], planes["mask1"],
                                                planes["sign0"], planes["sign1"])[0]
     layer, emap = build_layer(cfg, keep if want_cpu else None)
+
+    if args.tile_curve:
+        print(json.dumps({"tile_curve": tile_curve(hip, cfg, layer, [int(v) for v in args.tile_curve.split(",")])}))
+        return
 
     # A plain copy of known size (256 MiB in, 256 MiB out), outside the timed region: under
     # `rocprofv3 --pmc FETCH_SIZE|WRITE_SIZE` its reading calibrates the HBM byte counters.
@@ -296,6 +403,10 @@ def main():
                         "avg_launch_ms": head["down_ms"]},
         "path_hbm_frac": head["path_hbm_frac"],
     }
+    power = PowerSampler()
+    if not args.no_context:
+        out["board_power_W"] = power.measure(lambda: layer.pzl_moe_ffn(xt, idt, wt, y=y), seconds=1.5)
+        out["board_power_cap_W"] = power.cap_w
     # the on-device router in front of the layer, on its own (not part of the timed step: ids and
     # weights are inputs of the path)
     out["router_ms"] = time_router(hip, cfg, xt)
@@ -323,6 +434,19 @@ def main():
             "down_kernel": {"avg_launch_ms": ms_dn, "useful_TFLOPs": fl_proj / (ms_dn * 1e-3) / 1e12,
                             "frac": fl_proj / (ms_dn * 1e-3) / 2.5e15},
             "path_useful_mfma_frac": 3 * fl_proj / (ms_p * 1e-3) / 2.5e15}
+        if not args.no_context:
+            # What bounds this path on the board: the power drawn while it loops, against the cap
+            # (at the cap the core clock drops well below the 2.4 GHz that the peak assumes), and
+            # what the vendor's plain bf16 GEMM of the same shape reaches under the same cap.
+            yp = torch.empty(Tp, d, dtype=torch.bfloat16, device="cuda")
+            watts = power.measure(lambda: layer.pzl_moe_ffn(xtp, idtp, wtp, y=yp))
+            vend = vendor_gemm_tflops(Tp * k, d, 2 * f, masked=True)
+            out["prefill"]["context"] = {
+                "board_power_W": watts, "board_power_cap_W": power.cap_w,
+                "vendor_bf16_gemm_TFLOPs": vend, "vendor_bf16_gemm_frac_of_peak": vend / 2500.0,
+                "gateup_vs_vendor_gemm": out["prefill"]["roofline"]["achieved"] / vend,
+                "note": "vendor GEMM = torch.matmul on decoded weights of the same distribution resident in HBM, "
+                        "shape [T*k, d] x [d, 2f]; context, not part of the path"}
 
     if not args.no_quant:
         # Same layer and batch with the pairs in the quantised format (the paper's appendix on
