@@ -67,6 +67,9 @@ constexpr int TG_PERSISTENT_WGS = 256 * (8 / TG_WAVES);   // workgroups of a per
 // lets a step read the first fragments of the next stage before its closing barrier; else 4.
 template <int STAGE, bool HALF, bool DENSE>
 constexpr int tg_ring_stages() { return tg_stage_units<STAGE, HALF, DENSE>() * 16 * 8 <= 147456 ? 8 : 4; }
+#ifndef TG_QUARTER_LOADS
+#define TG_QUARTER_LOADS 1
+#endif
 #ifndef TG_BLOCK_M
 #define TG_BLOCK_M 8
 #endif
@@ -187,7 +190,18 @@ __device__ __forceinline__ void tile_body(const TgArgs &a, const uint16_t *wa, c
     static_assert(NF <= TG_FRAGS, "fragments");
     constexpr int RT = 2;                                    // row tiles per wave
     constexpr int XTOTAL = PARTS * NF * KBS;                 // activation fragments per stage
-    constexpr int XPT = (XTOTAL + TG_WAVES - 1) / TG_WAVES;  // ... of which each wave fetches this many
+    // ... fetched by the 8 waves with the same number of loads each (the hand-written waits count
+    // loads): whole fragments, 16 bytes per lane, as far as they divide by the number of waves;
+    // 2 or 4 fragments left over are fetched as quarters (the 16 rows of one 8-element column
+    // group: 256 bytes, 4 bytes per lane), one or two per wave.  (A whole-fragment load for every
+    // wave, most of them fetching the last fragment again, cost a tile of 18 fragments 24 loads
+    // per K step for 18 KiB: the loads of a step, not its matrix instructions, are what a
+    // step's length grows with beyond 16 fragments.)
+    constexpr int XLEFT = XTOTAL % TG_WAVES;
+    constexpr bool XQUART = TG_QUARTER_LOADS && PARTS == 1 && TG_WAVES == 8 && (XLEFT == 2 || XLEFT == 4);
+    constexpr int XFULL = XQUART ? XTOTAL / TG_WAVES : (XTOTAL + TG_WAVES - 1) / TG_WAVES;   // whole-fragment loads per wave
+    constexpr int XQ = XQUART ? XLEFT / 2 : 0;                                               // quarter loads per wave
+    constexpr int XPT = XFULL + XQ;                          // loads per wave and stage
     constexpr int TG_XSTAGE_UNITS = tg_stage_units<STAGE, HALF, DENSE>();
     static_assert(PARTS * TG_FRAGS * KBS * 64 == TG_XSTAGE_UNITS, "stage size");
 
@@ -239,12 +253,23 @@ __device__ __forceinline__ void tile_body(const TgArgs &a, const uint16_t *wa, c
     int xunit[XPT], xkbo[XPT];
 #pragma unroll
     for (int i = 0; i < XPT; ++i) {
-        int c = min(wave * XPT + i, XTOTAL - 1);
-        int kbo = c % KBS, fr = (c / KBS) % NF, part = c / (KBS * NF);
-        xkbo[i] = kbo;
-        xunit[i] = ((part * TG_FRAGS + fr) * KBS + kbo) * 64;
-        xoff[i] = 2u * ((uint32_t)(part * a.act_plane_stride) +
-                        (uint32_t)rowidx[fr * 16 + (lane & 15)] * (uint32_t)a.kdim + (lane >> 4) * 8);
+        if (i < XFULL) {
+            int c = min(wave * XFULL + i, XTOTAL - 1);
+            int kbo = c % KBS, fr = (c / KBS) % NF, part = c / (KBS * NF);
+            xkbo[i] = kbo;
+            xunit[i] = ((part * TG_FRAGS + fr) * KBS + kbo) * 64;
+            xoff[i] = 2u * ((uint32_t)(part * a.act_plane_stride) +
+                            (uint32_t)rowidx[fr * 16 + (lane & 15)] * (uint32_t)a.kdim + (lane >> 4) * 8);
+        } else {
+            // quarter qq of the left-over fragments: lane l fetches 4 bytes, the (l % 4)-th of the
+            // 16 that lane 16 * quarter + l / 4 of the fragment holds (row l / 4, column group `quarter`)
+            const int qq = wave * XQ + (i - XFULL);
+            const int c = TG_WAVES * XFULL + qq / 4, quarter = qq % 4;
+            const int kbo = c % KBS, fr = (c / KBS) % NF;
+            xkbo[i] = kbo;
+            xunit[i] = (fr * KBS + kbo) * 64 + quarter * 16;
+            xoff[i] = 2u * ((uint32_t)rowidx[fr * 16 + (lane >> 2)] * (uint32_t)a.kdim + quarter * 8) + (lane & 3) * 4u;
+        }
     }
 
     // a k-block past the end re-reads the last valid one; the last step skips its products
@@ -256,8 +281,12 @@ __device__ __forceinline__ void tile_body(const TgArgs &a, const uint16_t *wa, c
         int kb = min(kb0 + step * KBS + xkbo[i], kb1 - 1);
         uint32_t voff = xoff[i] + (uint32_t)(kb * TILE_COLS * 2);
         uint32_t lds_addr = (uint32_t)(uintptr_t)(tg_lds_ptr)(stage + xunit[i]);
-        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                     :: "s"(lds_addr), "v"(voff), "s"(act_base) : "memory");
+        if (i < XFULL)
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                         :: "s"(lds_addr), "v"(voff), "s"(act_base) : "memory");
+        else
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2"
+                         :: "s"(lds_addr), "v"(voff), "s"(act_base) : "memory");
     };
     auto fetch_x = [&](int step, u32x4 *stage) {
 #pragma unroll
