@@ -300,6 +300,40 @@ def tile_curve(hip, cfg, layer, sizes):
     return out
 
 
+PLAN_ALTERNATIVES = (("auto", (-1, -1, -1)), ("stream_only", (0, -1, -1)), ("tiled_one_shot", (1, 0, 0)),
+                     ("tiled_one_shot_own_stream", (1, 0, 1)), ("tiled_persistent", (1, 1, 0)),
+                     ("tiled_persistent_own_stream", (1, 1, 1)))
+
+
+def plan_study(hip, names, token_counts):
+    """The library's launch plan against the alternatives it could have chosen (pzl_layer_force_plan),
+    whole step, on layer shapes that its rules were not fitted on: ms per step for each alternative,
+    and how far the library's own choice is from the best of them."""
+    out = {}
+    for name in names:
+        cfg = synth.CONFIGS[name]
+        layer, _ = build_layer(cfg)
+        rows = {}
+        for T in token_counts:
+            _, _, _, xt, idt, wt = batch(cfg, T)
+            per_expert = T * cfg.top_k / cfg.n_experts
+            ms = {}
+            for label, force in PLAN_ALTERNATIVES:
+                if label == "stream_only" and per_expert > 128:
+                    continue                                  # dozens of sweeps over the weights: not a candidate
+                layer.pzl_layer_force_plan(*force)
+                ms[label], _, _ = time_plain(hip, layer, xt, idt, wt, 20, 3)
+            layer.pzl_layer_force_plan(-1, -1, -1)
+            pl = binding.pzl_moe_ffn_plan(cfg.n_experts, cfg.d_model, cfg.d_ffn, T, cfg.top_k, shared_d_ffn=cfg.shared_d_ffn)
+            best = min(ms, key=ms.get)
+            rows[str(T)] = {"ms": ms, "library_plan": {k: pl[k] for k in ("hybrid", "persistent", "tile_stream")},
+                            "best": best, "library_over_best": ms["auto"] / ms[best]}
+        out[name] = rows
+        del layer
+        torch.cuda.empty_cache()
+    return out
+
+
 def decode_point(hip, cfg, layer, emap, T, steps, warmup):
     """One decode batch size: the whole step and its two weight-streaming kernels."""
     x, ids, w, xt, idt, wt = batch(cfg, T)
@@ -334,6 +368,9 @@ def main():
     ap.add_argument("--no-quant", action="store_true")
     ap.add_argument("--no-other-shapes", action="store_true")
     ap.add_argument("--no-context", action="store_true", help="skip the board-power readings and the vendor GEMM of the prefill shape")
+    ap.add_argument("--plan-study", type=str, default="", metavar="SHAPE,SHAPE,...",
+                    help="only time the library's launch plan against forced alternatives on these synth.CONFIGS shapes")
+    ap.add_argument("--plan-tokens", type=str, default="16,64,128,256,512,1024,2048,4096")
     ap.add_argument("--tile-curve", type=str, default="", metavar="N,N,...",
                     help="only time the tiled launches with exactly N tokens per expert (Mixtral-shaped layer) and print that")
     args = ap.parse_args()
@@ -345,6 +382,9 @@ def main():
         sys.exit(2)
     binding.load()
     hip = Hip()
+    if args.plan_study:
+        print(json.dumps({"plan_study": plan_study(hip, args.plan_study.split(","), [int(v) for v in args.plan_tokens.split(",")])}))
+        return
     cfg = synth.CONFIGS["mixtral_decode"]
     T = args.tokens
 

@@ -43,7 +43,7 @@
 extern "C" {
 #endif
 
-#define PZL_ABI_VERSION 5
+#define PZL_ABI_VERSION 6
 
 #define PZL_OK       0
 #define PZL_EINVAL  -1   /* null pointer, bad shape, position not 0/1, pair map not a 2-to-1 cover */
@@ -221,6 +221,16 @@ typedef struct pzl_plan {
 /* Returns PZL_OK, or PZL_EINVAL for a null pointer, a negative T or k, or a shape that
  * pzl_layer_create would reject. */
 int pzl_moe_ffn_plan(const pzl_layer_shape *shape, int32_t T, int32_t k, pzl_plan *out);
+
+/* For measurement: overrides, for every later call on this layer, three of the decisions that
+ * pzl_moe_ffn_plan reports (hybrid, persistent, tile_stream): 1 or 0 forces the decision, -1 leaves
+ * it to the library (the state of a new layer).  Every combination computes the same y; what
+ * changes is which kernels run (Sec. 3.3.2's decode-GEMM as streaming or as tiled kernels) and how
+ * they are launched, so a benchmark can time the library's choice against the alternatives on any
+ * layer shape.  Call it before pzl_moe_ffn_workspace_bytes: the workspace size follows the plan.
+ * hybrid is ignored for quantised layers (they have no tiled kernel).  Not for use while calls on
+ * the layer are in flight.  PZL_EINVAL for a null layer or a value outside -1..1. */
+int pzl_layer_force_plan(pzl_layer *layer, int32_t hybrid, int32_t persistent, int32_t tile_stream);
 
 /* Bytes of workspace pzl_moe_ffn needs for any T <= max_tokens at this top_k (0 on bad
  * arguments).  The workspace must be 256-byte aligned device memory. */

@@ -20,7 +20,8 @@ EXPORTS = ("pzl_abi_version", "pzl_strerror", "pzl_last_hip_error", "pzl_packed_
            "pzl_unpack", "pzl_unpack_half_x2", "pzl_tile_dense", "pzl_merge_pack", "pzl_router_topk",
            "pzl_q_record_bytes", "pzl_q_scale_bytes", "pzl_q_pack", "pzl_q_unpack", "pzl_layer_create", "pzl_layer_destroy",
            "pzl_moe_ffn_plan", "pzl_moe_ffn_workspace_bytes", "pzl_moe_ffn", "pzl_moe_ffn_staged",
-           "pzl_moe_ffn_static", "pzl_moe_ffn_static_max_bytes", "pzl_moe_ffn_workspace_layout", "pzl_layer_h_info")
+           "pzl_moe_ffn_static", "pzl_moe_ffn_static_max_bytes", "pzl_moe_ffn_workspace_layout", "pzl_layer_h_info",
+           "pzl_layer_force_plan")
 
 STAGES = ("route", "gateup", "down", "shared", "combine")
 
@@ -107,6 +108,8 @@ def load():
         lib.pzl_moe_ffn.argtypes = [vp, vp, vp, vp, i32, i32, vp, vp, ctypes.c_size_t, vp]
         lib.pzl_moe_ffn_staged.restype = ctypes.c_int
         lib.pzl_moe_ffn_staged.argtypes = [vp, vp, vp, vp, i32, i32, vp, vp, ctypes.c_size_t, vp, vp]
+        lib.pzl_layer_force_plan.restype = ctypes.c_int
+        lib.pzl_layer_force_plan.argtypes = [vp, i32, i32, i32]
         lib.pzl_layer_h_info.restype = ctypes.c_int
         lib.pzl_layer_h_info.argtypes = [vp, ctypes.POINTER(i32), ctypes.POINTER(i32)]
         lib.pzl_moe_ffn_workspace_layout.restype = ctypes.c_int
@@ -377,6 +380,10 @@ class Layer:
 
     def pzl_moe_ffn_workspace_bytes(self, max_tokens, top_k):
         return load().pzl_moe_ffn_workspace_bytes(self._h, int(max_tokens), int(top_k))
+
+    def pzl_layer_force_plan(self, hybrid=-1, persistent=-1, tile_stream=-1):
+        """Override (1 / 0) or release (-1) the library's choice of kernels and launch form for later calls."""
+        _check(load().pzl_layer_force_plan(self._h, int(hybrid), int(persistent), int(tile_stream)), "pzl_layer_force_plan")
 
     def h_info(self):
         """(H of the packed pairs is one half-precision plane, wavefronts that saturated a value of H so far)."""

@@ -73,6 +73,8 @@ struct pzl_layer {
     bool half_h;
     std::vector<int> shared_max_exp;   // per shared expert: largest bf16 exponent field of its down matrix, or -1 (keep H wide)
     int32_t *d_counters;               // [0] largest exponent field of the down matrices, [1] waves that saturated a value of H
+    // pzl_layer_force_plan: -1 leaves the decision to make_plan, 0 / 1 overrides it (measurement only)
+    int32_t force_hybrid = -1, force_persistent = -1, force_tile_stream = -1;
 };
 
 namespace pzl {
@@ -269,11 +271,14 @@ static Plan make_plan(const pzl_layer *L, int32_t T, int32_t k, bool staged)
     pl.overlap = L->n_shared > 0 && !staged && N > 0;
     pl.hybrid = L->pair_format == 0 &&
         N >= (int64_t)(E64 >= 32 ? HYBRID_MIN_TOKENS_PER_EXPERT_MANY : HYBRID_MIN_TOKENS_PER_EXPERT) * E64;
+    if (L->force_hybrid >= 0 && L->pair_format == 0) pl.hybrid = L->force_hybrid != 0;
     pl.tile_min = pl.hybrid ? HYBRID_TILE_MIN_TOKENS : 0x7FFFFFFF;
     pl.mostly_tiled = pl.hybrid && N >= (int64_t)TILED_MIN_TOKENS_PER_EXPERT * E64;
     pl.tiled_shared = T >= TILED_MIN_TOKENS_SHARED;
     pl.persistent = L->n_q >= 32 && N <= (int64_t)256 * L->n_q;
+    if (L->force_persistent >= 0) pl.persistent = L->force_persistent != 0;
     pl.tile_overlap = pl.hybrid && !staged && E64 >= 32 && N < 40 * E64;
+    if (L->force_tile_stream >= 0) pl.tile_overlap = pl.hybrid && !staged && L->force_tile_stream != 0;
     // Small batches that only stream (no token tiles to cut): a grouping kernel in front of the first
     // weight-streaming kernel is 5-6 us of a 120-240 us step; the gate/up kernel of the packed pairs
     // sorts the few hundred entries itself instead (stream_gemm.hip, route_in_block).
@@ -659,6 +664,14 @@ int pzl_layer_h_info(const pzl_layer *layer, int32_t *half_precision, int32_t *s
     return PZL_OK;
 }
 
+int pzl_layer_force_plan(pzl_layer *layer, int32_t hybrid, int32_t persistent, int32_t tile_stream)
+{
+    if (!layer || hybrid < -1 || hybrid > 1 || persistent < -1 || persistent > 1 || tile_stream < -1 || tile_stream > 1)
+        return PZL_EINVAL;
+    layer->force_hybrid = hybrid; layer->force_persistent = persistent; layer->force_tile_stream = tile_stream;
+    return PZL_OK;
+}
+
 size_t pzl_moe_ffn_static_max_bytes(void) { return (size_t)PZL_STATIC_SCRATCH_BYTES; }
 
 int pzl_moe_ffn_staged(const pzl_layer *L, const uint16_t *x, const int32_t *topk_ids, const float *topk_w,
@@ -810,11 +823,11 @@ int pzl_moe_ffn_staged(const pzl_layer *L, const uint16_t *x, const int32_t *top
 
     int rc = mark(PZL_STAGE_ROUTE, 0);
     if (rc) return rc;
-    // one-shot launches may give both experts of a pair one tile (row groups of gate/up tell the
-    // grouping kernel how long the launch is); persistent launches do not have those kernels
+    // both experts of a pair may get one tile (the row groups of gate/up tell the grouping kernel
+    // how long the launch is)
     if (!pl.fused_route) {
         rc = launch_route(topk_ids, N, k, L->n_experts, L->n_q, L->d_q_of_expert, rt, tile_min,
-                          persistent ? 0 : (L->d_ffn + 127) / 128, (L->d_ffn + 127) / 128, st);   // (in units of a compute unit's share of a launch)
+                          (L->d_ffn + 127) / 128, (L->d_ffn + 127) / 128, st);   // (in units of a compute unit's share of a launch)
         if (rc) return rc;
     }
     if ((rc = mark(PZL_STAGE_ROUTE, 1))) return rc;

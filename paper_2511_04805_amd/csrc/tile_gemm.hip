@@ -205,7 +205,12 @@ __device__ __forceinline__ void tile_body(const TgArgs &a, const uint16_t *wa, c
     constexpr int TG_XSTAGE_UNITS = tg_stage_units<STAGE, HALF, DENSE>();
     static_assert(PARTS * TG_FRAGS * KBS * 64 == TG_XSTAGE_UNITS, "stage size");
 
-    const int tid = threadIdx.x, lane = tid & 63;
+    // (the thread index passes through an empty asm: what is derived from it is then computed per
+    // tile, not once per kernel and kept in registers across the tiles of a persistent workgroup,
+    // where the largest tiles have none to spare)
+    int tid = threadIdx.x;
+    asm volatile("" : "+v"(tid));
+    const int lane = tid & 63;
     const uint32_t lane16 = lane * 16u;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int kb_total = a.kdim / TILE_COLS;
@@ -565,15 +570,15 @@ __device__ __forceinline__ bool tile_run(const TgArgs &a, int logical, int n_mt,
     const uint16_t *wb = (STAGE == TSTAGE_GATEUP) ? a.w_b[g] : wa;
     const int cnt = (((n_tok + 15) >> 4) + 1) >> 1;          // 1..9 pairs of token fragments
 #define PZL_TILE(P, C) tile_body<STAGE, DENSE, ALLTOK, HALF, P, C>(a, wa, wb, slot0, n_tok, n_tok1, ntile, ks, ring, rowidx, draw_ctr, drawn)
-    // tiles that cover a pair exist only in one-shot launches (the grouping kernel is told so): the
-    // persistent kernels, already the largest, measured 5 % slower on every tile with these
-    // instantiations compiled in
-    if constexpr (!DENSE && !ALLTOK && !PERSIST) {
+    // tiles that cover a pair, in either launch form (60 experts top-4, even router, 1024 tokens,
+    // persistent launches: 282 -> 261 us; a skewed router has few such pairs and loses nothing)
+    if constexpr (!DENSE && !ALLTOK) {
         if (__builtin_amdgcn_readfirstlane((int)fused)) {
-            const int c2 = (max(n_tok, n_tok1) + 31) >> 5;       // 1..4 pairs of fragments per expert
+            static_assert(TILE_FUSED_MAX_TOKENS <= 96, "a tile for both experts holds at most 3 pairs of fragments per expert");
+            const int c2 = (max(n_tok, n_tok1) + 31) >> 5;       // 1..3 pairs of fragments per expert
             switch (c2) {
                 case 1: PZL_TILE(2, 1); break; case 2: PZL_TILE(2, 2); break;
-                case 3: PZL_TILE(2, 3); break; default: PZL_TILE(2, 4); break;
+                default: PZL_TILE(2, 3); break;
             }
             return true;
         }

@@ -46,6 +46,12 @@ CONFIGS = {
                               seed=1003),
     "deepseek_moe": LayerConfig("deepseek_moe", 64, 2048, 1408, 6, (2048,),
                                 shared_d_ffn=(1408, 1408), routing="zipf", seed=1004),
+    # Two further layer shapes, not among the paper's models: the library's launch rules were fitted
+    # on the three shapes above, and the benchmark's plan study times them on these (16 wide experts
+    # top-2; 128 narrow experts top-8, with an even and with a skewed router).
+    "wide16": LayerConfig("wide16", 16, 4096, 6400, 2, (256,), seed=1005),
+    "narrow128": LayerConfig("narrow128", 128, 2048, 768, 8, (256,), seed=1006),
+    "narrow128_zipf": LayerConfig("narrow128_zipf", 128, 2048, 768, 8, (256,), routing="zipf", seed=1006),
 }
 
 _GATE, _UP, _DOWN = 0, 1, 2

@@ -214,14 +214,12 @@ def loops_by_kernel(asm_text):
 def expected_loops(mangled):
     """K loops a tile_kernel<STAGE, DENSE, ALLTOK, PERSIST, HALF> instantiation must contain, from its
     template arguments: one per (expert position, number of token-fragment pairs 1..9); dense
-    weights have one position only; one-shot kernels of packed pairs also hold the 4 sizes of the
-    tile that covers both experts of a pair."""
+    weights have one position only; kernels of packed pairs also hold the 3 sizes of the tile that
+    covers both experts of a pair."""
     m = re.search(r"tile_kernelILi(\d)ELb(\d)ELb(\d)ELb(\d)ELb(\d)E", mangled)
     assert m, mangled
-    dense, persist = m.group(2) == "1", m.group(4) == "1"
-    if dense:
-        return 9
-    return 18 if persist else 18 + 4
+    dense = m.group(2) == "1"
+    return 9 if dense else 18 + 3
 
 
 def check(asm_text):

@@ -15,7 +15,7 @@ def test_header_symbols_are_exported():
     lib = binding.load()
     for name in declared:
         assert hasattr(lib, name), name
-    assert lib.pzl_abi_version() == 5
+    assert lib.pzl_abi_version() == 6
     assert lib.pzl_moe_ffn_static_max_bytes() == 32 << 20
     assert lib.pzl_packed_bytes(14336, 4096) == 14336 * 4096 * 2
     assert lib.pzl_strerror(0) == b"ok" and b"workspace" in lib.pzl_strerror(binding.PZL_ENOSPC)

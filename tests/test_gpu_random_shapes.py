@@ -54,3 +54,32 @@ def test_random_layer(oracle, ci):
         ok, worst = tolerance_ok(y, y64)
         print("   T=%d worst err / bound = %.3f" % (T, worst), flush=True)
         assert ok, (T, worst)
+
+
+FORCED = [(-1, -1, -1), (0, -1, -1), (1, 0, 0), (1, 0, 1), (1, 1, 0), (1, 1, 1)]
+
+
+@pytest.mark.parametrize("shape", [(8, 0, 128, 256, 2, (), "gaussian"), (40, 2, 96, 160, 4, (64,), "zipf"),
+                                   (64, 0, 64, 96, 6, (96, 96), "zipf")])
+def test_forced_plans(oracle, shape):
+    """pzl_layer_force_plan: every launch plan the library could choose (streaming kernels only; tiled
+    kernels as one workgroup per tile or as a persistent launch, on the caller's stream or on the
+    layer's own) gives the same y within the bound, at batch sizes on both sides of the library's own
+    thresholds; releasing the override gives the library's choice back."""
+    from paper_2511_04805_amd import binding
+    binding.load()
+    E, D, d, f, k, shared, routing = shape
+    cfg = synth.LayerConfig("forced", E, d, f, k, (1,), shared_d_ffn=shared, routing=routing, seed=9100 + E, n_unmerged=D)
+    case = Case(cfg, oracle, binding, emap_mode="random")
+    with pytest.raises(binding.PzlError):
+        case.layer.pzl_layer_force_plan(2, 0, 0)
+    for T in (5, 70, 300):
+        x = synth.tokens(cfg, T)
+        ids, w = synth.routing(cfg, T)
+        y64, _ = case.ref(x, ids, w)
+        for force in FORCED:
+            case.layer.pzl_layer_force_plan(*force)
+            print("   E=%d T=%d forced %s" % (E, T, force), flush=True)
+            ok, worst = tolerance_ok(case.gpu(x, ids, w), y64)
+            assert ok, (T, force, worst)
+    case.layer.pzl_layer_force_plan(-1, -1, -1)
