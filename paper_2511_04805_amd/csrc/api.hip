@@ -261,6 +261,7 @@ struct Plan {
     int ksplit, ksplit_shared;
     int shared_wgs;        // workgroups aimed at for the shared experts' tiled gate/up launch
     bool fused_route;      // no grouping kernel: the streaming gate/up kernel of the packed pairs groups the list itself
+    int tiles_per_expert;  // token tiles of an expert with the average number of tokens
 };
 
 static Plan make_plan(const pzl_layer *L, int32_t T, int32_t k, bool staged)
@@ -273,6 +274,7 @@ static Plan make_plan(const pzl_layer *L, int32_t T, int32_t k, bool staged)
         N >= (int64_t)(E64 >= 32 ? HYBRID_MIN_TOKENS_PER_EXPERT_MANY : HYBRID_MIN_TOKENS_PER_EXPERT) * E64;
     if (L->force_hybrid >= 0 && L->pair_format == 0) pl.hybrid = L->force_hybrid != 0;
     pl.tile_min = pl.hybrid ? HYBRID_TILE_MIN_TOKENS : 0x7FFFFFFF;
+    pl.tiles_per_expert = (int)((N / E64 + TILE_MAX_TOKENS - 1) / TILE_MAX_TOKENS);
     pl.mostly_tiled = pl.hybrid && N >= (int64_t)TILED_MIN_TOKENS_PER_EXPERT * E64;
     pl.tiled_shared = T >= TILED_MIN_TOKENS_SHARED;
     pl.persistent = L->n_q >= 32 && N <= (int64_t)256 * L->n_q;
@@ -872,6 +874,7 @@ int pzl_moe_ffn_staged(const pzl_layer *L, const uint16_t *x, const int32_t *top
                 a.tile_q = rt.tile_q; a.tile_slot0 = rt.tile_slot0; a.tile_n = rt.tile_n; a.n_tiles = rt.n_tiles;
                 a.group_lo = group_base; a.group_hi = group_base + n_groups;
                 a.max_mtiles = max_token_tiles(N, L->n_q);
+                a.block_m = pl.tiles_per_expert <= 4 ? 4 : 0;
                 a.half_h = kind == KIND_PACKED && L->half_h; a.h_saturated = L->d_counters + 1;
                 a.tile_ctr = persistent ? rt.n_tiles + 8 + (pass * 2 + stage) * 8 : nullptr;
                 if (stage == 0) {

@@ -158,6 +158,7 @@ struct TileGemmArgs {
     int64_t o_ks_stride;
     int32_t ksplit;               // down stage only: workgroups sharing one output tile along K
     int32_t max_mtiles;           // upper bound on token tiles (grid size)
+    int32_t block_m;              // 4: about four token tiles per expert are expected (see launch() in tile_gemm.hip); else 0
     int32_t *tile_ctr;            // routed groups: 8 zeroed counters (one per XCD) for a persistent launch that draws its tiles, or nullptr
     int32_t half_h;               // H is one half-precision plane (packed pairs; shared experts with dense_half_bias >= 0)
     int32_t dense_half_bias;      // dense weights of a half_h launch: largest exponent field of the down matrices - 30, at least 0
