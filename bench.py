@@ -27,8 +27,8 @@ HBM_PEAK_GBS = 8000.0
 # Bytes between L2 and memory per launch of the gate/up kernels (streaming at T = 64, tiled at
 # T = 4096), from rocprofv3 --pmc runs (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, calibrated on the
 # copy below) summarised under profiles/.  Counters cannot be read inside this process.
-MEASURED_TRAFFIC_BYTES = {"mixtral_decode_T64": 950.9e6, "mixtral_decode_T64_quantised": 430.2e6,
-                          "mixtral_prefill_T4096": 6.969e9}
+MEASURED_TRAFFIC_BYTES = {"mixtral_decode_T64": 950.9e6, "mixtral_decode_T64_quantised": 429.7e6,
+                          "mixtral_prefill_T4096": 3.209e9}
 TRAFFIC_FROM = ("separate rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script, summarised under profiles/ "
                 "(stream_kernels_mixtral_decode_T64.md, tile_kernels_mixtral_prefill_T4096.md); not read in this process")
 W3 = (synth.GATE, synth.UP, synth.DOWN)
