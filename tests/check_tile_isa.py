@@ -12,8 +12,9 @@ This module compiles `csrc/tile_gemm.hip` to gfx950 assembly and verifies, for e
 no instruction names a destination register of an inline-asm `global_load_dwordx4` between the
 load and the hand-written wait that covers it, across the loop's back edge too (one exception: a lane-0 read into a scalar register that is
 overwritten before it is read on every path, which is how the compiler materialises an undefined
-value), that every loop exit waits for all loads before any vector instruction, and that nothing
-spills.  A developer tool that lives with its test (test_tile_isa.py), not in the product
+value), that every loop exit waits for all loads before any vector instruction, that nothing
+spills, and that no K loop touches scratch memory (a reload there would be a load the waits do not
+count).  A developer tool that lives with its test (test_tile_isa.py), not in the product
 package.  Run it after any change to the kernel or the compiler:
 
     python tests/check_tile_isa.py
@@ -235,6 +236,11 @@ def check(asm_text):
     for start, i in _k_loops(lines, labels):
         body = lines[start:i]
         n_loops += 1
+        # A spill inside a K loop would not only be slow: its reload is a load that the hand-written
+        # waits do not count, so every wait after it would let one more weight load stay out.
+        for k, b in enumerate(body):
+            if re.match(r"\s*scratch_", b):
+                problems.append("line %d: scratch access inside a K loop: %s" % (start + k + 1, b.strip()))
         # Loads complete in issue order and the waits name how many of the youngest may still be
         # out: keep the queue of outstanding loads (destination registers of the inline-asm weight
         # loads; nothing for a load into LDS) and drop from its old end at every wait.  Three trips

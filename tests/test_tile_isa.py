@@ -39,6 +39,17 @@ def test_checker_flags_a_planted_copy():
     assert check_tile_isa.check(clean)[2] == []
 
 
+def test_checker_flags_scratch_in_a_loop():
+    """A spill reload inside a K loop is a load that the hand-written waits do not count."""
+    body = ["\tv_mfma_f32_16x16x32_bf16 v[0:3], v[4:7], v[8:11], v[0:3]"] * 8
+    text = "\n".join([".LBB0_1:                                ; =>This Inner Loop Header: Depth=1"] + body + [
+        "\t;;#ASMSTART", "\tglobal_load_dwordx4 v[20:23], v1, s[2:3]", "\t;;#ASMEND",
+        "\ts_barrier", "\tscratch_load_dword v30, off, off", "\ts_barrier",
+        "\ts_cbranch_scc1 .LBB0_1"])
+    problems = check_tile_isa.check(text)[2]
+    assert len(problems) == 1 and "scratch" in problems[0]
+
+
 def test_checker_follows_the_waits():
     """A register is in flight from its load to the wait that covers it: a read after `vmcnt(0)` is
     fine, a read after a wait that still allows the load to be out is reported, and so is a read at
