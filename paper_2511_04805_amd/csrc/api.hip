@@ -112,10 +112,12 @@ constexpr int HYBRID_TILE_MIN_TOKENS = PZL_HYBRID_TILE_MIN;       // ... and a p
 // expert of 5632: 64 tokens 120 us streamed / 135 tiled, 96 tokens 156 / 139, 256 tokens 192 / 166
 constexpr int TILED_MIN_TOKENS_SHARED = PZL_TILED_MIN_SHARED;
 constexpr int QUANT_MAX_SLOTS_PER_EXPERT = 64;   // quantised layers: largest average of (token, choice) entries per expert that a call accepts
+constexpr int FRAG_X_MIN_FFN = 8192;   // expert width from which x is gathered into fragment order for the tiled gate/up stage
 constexpr int MAX_KSPLIT = 8;   // upper bound on the k-splits of the down stage (sizes the workspace)
 
 struct WorkspaceLayout {
-    size_t cnt, off, slot_tok, slot_of, tile_q, tile_slot0, tile_n, n_tiles, h_routed, h_shared, opart, total;
+    size_t cnt, off, slot_tok, slot_of, tile_q, tile_slot0, tile_n, n_tiles, h_routed, h_frag, x_frag, h_shared, opart, total;
+    bool has_h_frag, has_x_frag;   // fragment-ordered copies of H and of x for the tiled kernels (tile_gemm.hip, tg_frag_row)
     int64_t o_ks_stride;      // elements between k-splits of the partial-sum buffer
     // H is held as two bf16 planes (hi, lo), the lo plane right after the hi plane
     size_t h_shared_each(const pzl_layer *L, int32_t T, int s) const
@@ -123,32 +125,6 @@ struct WorkspaceLayout {
         return align_up((size_t)2 * T * L->shared_f[s] * 2, 256);
     }
 };
-
-static WorkspaceLayout carve(const pzl_layer *L, int32_t T, int32_t k)
-{
-    WorkspaceLayout w;
-    const size_t N = (size_t)T * k;
-    const size_t slots = N + (size_t)L->n_shared * T;
-    size_t p = 0;
-    w.cnt = p;       p += align_up((size_t)L->n_q * 4, 256);
-    w.off = p;       p += align_up(((size_t)L->n_q + 1) * 4, 256);
-    w.slot_tok = p;  p += align_up(N * 4, 256);
-    w.slot_of = p;   p += align_up(N * 4, 256);
-    const size_t mt = (size_t)max_token_tiles((int64_t)N, L->n_q);
-    w.tile_q = p;     p += align_up(mt * 4, 256);
-    w.tile_slot0 = p; p += align_up(mt * 4, 256);
-    w.tile_n = p;     p += align_up(mt * 4, 256);
-    w.n_tiles = p;    p += 256;
-    // routed H: two bf16 planes, or one half-precision plane if every routed expert is a packed pair in that form
-    const size_t h_planes = (L->half_h && L->n_dense == 0) ? 1 : 2;
-    w.h_routed = p;  p += align_up(h_planes * N * L->d_ffn * 2, 256);
-    w.h_shared = p;
-    for (int s = 0; s < L->n_shared; ++s) p += w.h_shared_each(L, T, s);
-    w.o_ks_stride = (int64_t)slots * L->d_model;
-    w.opart = p;     p += align_up((size_t)MAX_KSPLIT * slots * L->d_model * 4, 256);
-    w.total = p;
-    return w;
-}
 
 // Tiled down stage: workgroups = token tiles x rows/256, one per compute unit at a time.  Splitting
 // K over `ks` workgroups fills idle compute units when there are few tiles, but every split writes
@@ -262,6 +238,7 @@ struct Plan {
     int shared_wgs;        // workgroups aimed at for the shared experts' tiled gate/up launch
     bool fused_route;      // no grouping kernel: the streaming gate/up kernel of the packed pairs groups the list itself
     int tiles_per_expert;  // token tiles of an expert with the average number of tokens
+    bool frag_h, frag_x;   // the tiled kernels of the packed pairs keep H / read x in fragment order
 };
 
 static Plan make_plan(const pzl_layer *L, int32_t T, int32_t k, bool staged)
@@ -275,6 +252,13 @@ static Plan make_plan(const pzl_layer *L, int32_t T, int32_t k, bool staged)
     if (L->force_hybrid >= 0 && L->pair_format == 0) pl.hybrid = L->force_hybrid != 0;
     pl.tile_min = pl.hybrid ? HYBRID_TILE_MIN_TOKENS : 0x7FFFFFFF;
     pl.tiles_per_expert = (int)((N / E64 + TILE_MAX_TOKENS - 1) / TILE_MAX_TOKENS);
+    // Fragment-ordered H costs nothing (the gate/up stage stores it there instead); fragment-ordered
+    // x costs a pass that reads and writes N x d elements in front of a gate/up stage that gets
+    // about 3 % shorter: by the two kernels' rates that pays from f of about 7000 on, in batches
+    // where the tiled kernels do most of the work.
+    const int64_t frag_cells = (int64_t)tile_frag_rows(N, L->n_q) * (L->d_ffn > L->d_model ? L->d_ffn : L->d_model);
+    pl.frag_h = pl.hybrid && L->half_h && L->pair_format == 0 && L->n_pairs > 0 && frag_cells < (1LL << 31);
+    pl.frag_x = pl.frag_h && L->d_ffn >= FRAG_X_MIN_FFN && N >= (int64_t)TILED_MIN_TOKENS_PER_EXPERT * E64;
     pl.mostly_tiled = pl.hybrid && N >= (int64_t)TILED_MIN_TOKENS_PER_EXPERT * E64;
     pl.tiled_shared = T >= TILED_MIN_TOKENS_SHARED;
     pl.persistent = L->n_q >= 32 && N <= (int64_t)256 * L->n_q;
@@ -317,6 +301,38 @@ static Plan make_plan(const pzl_layer *L, int32_t T, int32_t k, bool staged)
     if (ksplit > L->d_ffn / TILE_COLS) ksplit = L->d_ffn / TILE_COLS;              // no split without a k-block (tiny layers)
     pl.ksplit = ksplit;
     return pl;
+}
+
+static WorkspaceLayout carve(const pzl_layer *L, int32_t T, int32_t k)
+{
+    WorkspaceLayout w;
+    const size_t N = (size_t)T * k;
+    const size_t slots = N + (size_t)L->n_shared * T;
+    size_t p = 0;
+    w.cnt = p;       p += align_up((size_t)L->n_q * 4, 256);
+    w.off = p;       p += align_up(((size_t)L->n_q + 1) * 4, 256);
+    w.slot_tok = p;  p += align_up(N * 4, 256);
+    w.slot_of = p;   p += align_up(N * 4, 256);
+    const size_t mt = (size_t)max_token_tiles((int64_t)N, L->n_q);
+    w.tile_q = p;     p += align_up(mt * 4, 256);
+    w.tile_slot0 = p; p += align_up(mt * 4, 256);
+    w.tile_n = p;     p += align_up(mt * 4, 256);
+    w.n_tiles = p;    p += 256;
+    // routed H: two bf16 planes, or one half-precision plane if every routed expert is a packed pair in that form
+    const size_t h_planes = (L->half_h && L->n_dense == 0) ? 1 : 2;
+    w.h_routed = p;  p += align_up(h_planes * N * L->d_ffn * 2, 256);
+    // fragment-ordered H (written by the tiled gate/up stage for the tiled down stage) and x (gathered)
+    const Plan pl = make_plan(L, T, k, false);
+    const size_t frag_rows = tile_frag_rows((int64_t)N, L->n_q);
+    w.has_h_frag = pl.frag_h; w.has_x_frag = pl.frag_x;
+    w.h_frag = p;    if (w.has_h_frag) p += align_up(frag_rows * L->d_ffn * 2, 256);
+    w.x_frag = p;    if (w.has_x_frag) p += align_up(frag_rows * L->d_model * 2, 256);
+    w.h_shared = p;
+    for (int s = 0; s < L->n_shared; ++s) p += w.h_shared_each(L, T, s);
+    w.o_ks_stride = (int64_t)slots * L->d_model;
+    w.opart = p;     p += align_up((size_t)MAX_KSPLIT * slots * L->d_model * 4, 256);
+    w.total = p;
+    return w;
 }
 
 }  // namespace pzl
@@ -723,6 +739,8 @@ int pzl_moe_ffn_staged(const pzl_layer *L, const uint16_t *x, const int32_t *top
     rt.tile_n = (int32_t *)(ws + w.tile_n);
     rt.n_tiles = (int32_t *)(ws + w.n_tiles);
     uint16_t *h_routed = (uint16_t *)(ws + w.h_routed);
+    uint16_t *h_frag = w.has_h_frag ? (uint16_t *)(ws + w.h_frag) : nullptr;
+    uint16_t *x_frag = w.has_x_frag ? (uint16_t *)(ws + w.x_frag) : nullptr;
     float *opart = (float *)(ws + w.opart);
 
     // Path choice.  With few tokens per expert the layer is bound by streaming the packed weights
@@ -877,16 +895,25 @@ int pzl_moe_ffn_staged(const pzl_layer *L, const uint16_t *x, const int32_t *top
                 a.block_m = pl.tiles_per_expert <= 4 ? 4 : 0;
                 a.half_h = kind == KIND_PACKED && L->half_h; a.h_saturated = L->d_counters + 1;
                 a.tile_ctr = persistent ? rt.n_tiles + 8 + (pass * 2 + stage) * 8 : nullptr;
+                const bool frag = kind == KIND_PACKED && L->half_h;    // fragment-ordered copies, where the workspace has them
                 if (stage == 0) {
                     a.w_a = wg; a.w_b = wu;
                     a.rows = L->d_ffn; a.kdim = L->d_model;
                     a.act = x; a.act_is_x = 1;
                     a.h_out = h_routed; a.h_slot_base = 0; a.h_plane_stride = h_plane;
+                    if (frag && x_frag) {
+                        rc = launch_gather_x(x, L->d_model, rt.slot_tok, rt.tile_q, rt.tile_slot0, rt.tile_n, rt.n_tiles,
+                                             a.max_mtiles, x_frag, tst);
+                        if (rc) return rc;
+                        a.act_frag = x_frag;
+                    }
+                    a.h_frag = frag ? h_frag : nullptr;
                     rc = launch_tile_gateup(a, kind, tst);
                 } else {
                     a.w_a = wd; a.w_b = nullptr;
                     a.rows = L->d_model; a.kdim = L->d_ffn;
                     a.act = h_routed; a.act_is_x = 0; a.act_slot_base = 0; a.act_plane_stride = h_plane;
+                    a.act_frag = frag ? h_frag : nullptr;
                     a.o_out = opart; a.o_ks_stride = w.o_ks_stride; a.ksplit = ksplit;
                     rc = launch_tile_down(a, kind, tst);
                 }

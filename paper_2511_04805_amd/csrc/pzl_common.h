@@ -159,11 +159,20 @@ struct TileGemmArgs {
     int32_t ksplit;               // down stage only: workgroups sharing one output tile along K
     int32_t max_mtiles;           // upper bound on token tiles (grid size)
     int32_t block_m;              // 4: about four token tiles per expert are expected (see launch() in tile_gemm.hip); else 0
+    // packed pairs with half-precision H only: fragment-ordered buffers (tile_gemm.hip, tg_frag_row), or null
+    const uint16_t *act_frag;     // this stage's token operand in fragment order (x gathered by launch_gather_x; H written by the gate/up stage)
+    uint16_t *h_frag;             // gate/up stage: where H goes in fragment order
     int32_t *tile_ctr;            // routed groups: 8 zeroed counters (one per XCD) for a persistent launch that draws its tiles, or nullptr
     int32_t half_h;               // H is one half-precision plane (packed pairs; shared experts with dense_half_bias >= 0)
     int32_t dense_half_bias;      // dense weights of a half_h launch: largest exponent field of the down matrices - 30, at least 0
     int32_t *h_saturated;         // ... and this device counter is bumped when a value of H saturates (may be null)
 };
+// rows that a fragment-ordered buffer holds per tile of the tile list's bound, beyond the slots
+constexpr int TILE_FRAG_PAD_ROWS = 32;
+inline size_t tile_frag_rows(int64_t n_flat, int n_keys) { return (size_t)n_flat + (size_t)TILE_FRAG_PAD_ROWS * ((size_t)max_token_tiles(n_flat, n_keys) + 1); }
+// x in fragment order for the token tiles of the list (tiles that cover a pair are left out)
+int launch_gather_x(const uint16_t *x, int32_t d, const int32_t *slot_tok, const int32_t *tile_q, const int32_t *tile_slot0,
+                    const int32_t *tile_n, const int32_t *n_tiles, int32_t max_mtiles, uint16_t *x_frag, hipStream_t st);
 int launch_tile_gateup(const TileGemmArgs &a, int kind, hipStream_t st);
 int launch_tile_down(const TileGemmArgs &a, int kind, hipStream_t st);
 

@@ -72,6 +72,20 @@ constexpr int tg_ring_stages() { return tg_stage_units<STAGE, HALF, DENSE>() * 1
 #endif
 constexpr int TG_BLOCK_WGS = 32;            // workgroups an XCD runs side by side (32 compute units): one block of token tiles x row blocks
 
+// Activations in fragment order.  A tile's token operand is what its K loop reads most often from
+// L2: 16 rows x 32 columns per fragment and K step, 64 bytes from each of 16 rows that lie
+// wherever the router put them (x) or f elements apart (H) -- half of every 128-byte line fetched
+// for nothing.  In a fragment-ordered buffer the 1 KiB that one load instruction moves is
+// contiguous: 16 token rows form a block of 16 * K elements, inside it k-block after k-block, each
+// as the 64 lanes x 8 elements of the matrix instruction's B operand.  Tile number mt of the
+// tile list owns the blocks from row slot0 + 32 * mt on (its slots are contiguous from slot0; a
+// tile has at most 31 rows of padding, so the blocks of successive tiles never overlap; the
+// buffers hold TILE_FRAG_PAD_ROWS rows per tile of the list's bound beyond the slots).  The gate/up
+// stage writes H that way for the down stage at no cost (same 8-byte stores, other addresses); x
+// needs a gathering pass in front (gather_x_kernel), which pays for wide experts only.
+// Measured on the Mixtral-shaped prefill with both: gate/up -3 %, down -5 %.
+__device__ __forceinline__ int tg_frag_row(int slot0, int mt) { return slot0 + TILE_FRAG_PAD_ROWS * mt; }
+
 struct TgArgs {
     const uint16_t *const *w_a;
     const uint16_t *const *w_b;
@@ -86,6 +100,11 @@ struct TgArgs {
     uint16_t *h_out;
     int64_t h_plane_stride;
     int32_t h_slot_base;
+    // Activations in fragment order (see tg_frag_row): the stage's input, if it has such a copy, and
+    // (gate/up stage) where H goes in that order.  Tiles that cover both experts of a pair keep the
+    // row-major buffers.
+    const uint16_t *act_frag;
+    uint16_t *h_frag;
     float *o_out;
     int64_t o_ks_stride;
     int32_t max_mtiles, n_ntiles, ksplit;
@@ -173,7 +192,7 @@ typedef __attribute__((address_space(3))) void *tg_lds_ptr;
 // K steps of 64 like the gate/up stage, and halves its sums), instead of two bf16 planes.
 template <int STAGE, bool DENSE, bool ALLTOK, bool HALF, int POS, int CNT>
 __device__ __forceinline__ void tile_body(const TgArgs &a, const uint16_t *wa, const uint16_t *wb,
-                                          int slot0, int n_tok, int n_tok1, int ntile, int ks,
+                                          int slot0, int n_tok, int n_tok1, int ntile, int ks, int mt,
                                           u32x4 *ring, int32_t *rowidx, int32_t *draw_ctr, int32_t *drawn)
 {
     constexpr bool FUSED = POS == 2;
@@ -250,6 +269,11 @@ __device__ __forceinline__ void tile_body(const TgArgs &a, const uint16_t *wa, c
     // last one repeated if the count does not divide) -> (plane, token fragment, k-block);
     // 32-bit byte offsets from the activation base (every activation buffer is < 2^31 elements):
     // uniform base + 32-bit lane offset is the addressing form that needs no 64-bit vector math
+    // (frag_in: this tile reads its token operand from the fragment-ordered copy: a k-block is then
+    // 1 KiB further on, not 64 bytes, and the lane's place inside it is the lane itself)
+    const bool frag_in = !FUSED && PARTS == 1 && a.act_frag != nullptr;
+    const uint32_t frag_base = (uint32_t)tg_frag_row(slot0, mt) * (uint32_t)a.kdim;   // elements
+    const uint32_t xkstride = frag_in ? 1024u : (uint32_t)(TILE_COLS * 2);           // bytes per k-block
     uint32_t xoff[XPT];
     int xunit[XPT], xkbo[XPT];
 #pragma unroll
@@ -261,6 +285,7 @@ __device__ __forceinline__ void tile_body(const TgArgs &a, const uint16_t *wa, c
             xunit[i] = ((part * TG_FRAGS + fr) * KBS + kbo) * 64;
             xoff[i] = 2u * ((uint32_t)(part * a.act_plane_stride) +
                             (uint32_t)rowidx[fr * 16 + (lane & 15)] * (uint32_t)a.kdim + (lane >> 4) * 8);
+            if (frag_in) xoff[i] = 2u * (frag_base + (uint32_t)fr * 16u * (uint32_t)a.kdim) + lane16;
         } else {
             // quarter qq of the left-over fragments: lane l fetches 4 bytes, the (l % 4)-th of the
             // 16 that lane 16 * quarter + l / 4 of the fragment holds (row l / 4, column group `quarter`)
@@ -270,6 +295,7 @@ __device__ __forceinline__ void tile_body(const TgArgs &a, const uint16_t *wa, c
             xkbo[i] = kbo;
             xunit[i] = (fr * KBS + kbo) * 64 + quarter * 16;
             xoff[i] = 2u * ((uint32_t)rowidx[fr * 16 + (lane >> 2)] * (uint32_t)a.kdim + quarter * 8) + (lane & 3) * 4u;
+            if (frag_in) xoff[i] = 2u * (frag_base + (uint32_t)fr * 16u * (uint32_t)a.kdim) + quarter * 256u + lane * 4u;
         }
     }
 
@@ -277,10 +303,10 @@ __device__ __forceinline__ void tile_body(const TgArgs &a, const uint16_t *wa, c
     // Both kinds of load are issued from inline assembly, and waited for by hand (wait_w below):
     // the compiler, seeing a direct-to-LDS load, waits for ALL outstanding loads before the next
     // LDS read, which would undo the prefetch.
-    const uint64_t act_base = (uint64_t)(uintptr_t)a.act;
+    const uint64_t act_base = (uint64_t)(uintptr_t)(frag_in ? a.act_frag : a.act);
     auto fetch_x_one = [&](int step, u32x4 *stage, int i) {
         int kb = min(kb0 + step * KBS + xkbo[i], kb1 - 1);
-        uint32_t voff = xoff[i] + (uint32_t)(kb * TILE_COLS * 2);
+        uint32_t voff = xoff[i] + (uint32_t)kb * xkstride;
         uint32_t lds_addr = (uint32_t)(uintptr_t)(tg_lds_ptr)(stage + xunit[i]);
         if (i < XFULL)
             asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
@@ -469,7 +495,7 @@ __device__ __forceinline__ void tile_body(const TgArgs &a, const uint16_t *wa, c
     // write the (now dead) weight registers, so nothing may be scheduled above this wait that
     // could be given one of them.
     __builtin_amdgcn_sched_barrier(0);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    asm volatile("s_waitcnt vmcnt(0) ; end of K loop" ::: "memory");     // (the comment is what the machine-code check looks for)
     __builtin_amdgcn_sched_barrier(0);
 
     // Draw this workgroup's next tile now (see tile_kernel): the counter's answer travels while
@@ -496,7 +522,16 @@ __device__ __forceinline__ void tile_body(const TgArgs &a, const uint16_t *wa, c
             if (grt >= row_tiles) continue;
             f32x4 g = acc[0][i], u = acc[1][i];
             u32x2 oh = {tg_swiglu_half2(g[0], u[0], g[1], u[1], sat), tg_swiglu_half2(g[2], u[2], g[3], u[3], sat)};
-            *(u32x2 *)(a.h_out + (int64_t)(slot - a.h_slot_base) * a.rows + grt * 16 + rsub) = oh;
+            if (!FUSED && a.h_frag) {
+                // fragment order for the down stage: features grt*16 + rsub .. +3 of token `col` of
+                // fragment i are elements rsub % 8 .. +3 of lane ((feature % 32) / 8) * 16 + col of
+                // k-block feature / 32
+                const int feat = grt * 16 + rsub;
+                *(u32x2 *)(a.h_frag + ((int64_t)tg_frag_row(slot0, mt) + 16 * i) * a.rows + (feat >> 5) * 512 +
+                           ((((feat & 31) >> 3) * 16 + col) * 8) + (feat & 7)) = oh;
+            } else {
+                *(u32x2 *)(a.h_out + (int64_t)(slot - a.h_slot_base) * a.rows + grt * 16 + rsub) = oh;
+            }
         } else if (STAGE == TSTAGE_GATEUP) {
             int grt = ntile * TG_WAVES + wave;
             if (grt >= row_tiles) continue;
@@ -566,7 +601,7 @@ __device__ __forceinline__ bool tile_run(const TgArgs &a, int logical, int n_mt,
     const uint16_t *wa = a.w_a[g];
     const uint16_t *wb = (STAGE == TSTAGE_GATEUP) ? a.w_b[g] : wa;
     const int cnt = (((n_tok + 15) >> 4) + 1) >> 1;          // 1..9 pairs of token fragments
-#define PZL_TILE(P, C) tile_body<STAGE, DENSE, ALLTOK, HALF, P, C>(a, wa, wb, slot0, n_tok, n_tok1, ntile, ks, ring, rowidx, draw_ctr, drawn)
+#define PZL_TILE(P, C) tile_body<STAGE, DENSE, ALLTOK, HALF, P, C>(a, wa, wb, slot0, n_tok, n_tok1, ntile, ks, mt, ring, rowidx, draw_ctr, drawn)
     // tiles that cover a pair, in either launch form (60 experts top-4, even router, 1024 tokens,
     // persistent launches: 282 -> 261 us; a skewed router has few such pairs and loses nothing)
     if constexpr (!DENSE && !ALLTOK) {
@@ -676,6 +711,8 @@ static int launch(const TileGemmArgs &t, hipStream_t st)
     a.dense_tokens = t.dense_tokens; a.dense_slot_base = t.dense_slot_base;
     a.dense_tiles = t.dense_tiles; a.dense_tile_tokens = t.dense_tile_tokens;
     a.h_out = t.h_out; a.h_plane_stride = t.h_plane_stride; a.h_slot_base = t.h_slot_base;
+    a.act_frag = (!DENSE && HALF) ? t.act_frag : nullptr;
+    a.h_frag = (!DENSE && HALF && STAGE == TSTAGE_GATEUP) ? t.h_frag : nullptr;
     a.o_out = t.o_out; a.o_ks_stride = t.o_ks_stride;
     a.ksplit = (STAGE == TSTAGE_DOWN && t.ksplit > 1) ? t.ksplit : 1;
     a.max_mtiles = t.max_mtiles;
@@ -707,6 +744,39 @@ static int launch(const TileGemmArgs &t, hipStream_t st)
     }
     if (a.tile_ctr) hipLaunchKernelGGL((tile_kernel<STAGE, DENSE, ALLTOK, !ALLTOK, HALF>), dim3((unsigned)blocks), dim3(TG_THREADS), 0, st, a);
     else            hipLaunchKernelGGL((tile_kernel<STAGE, DENSE, ALLTOK, false, HALF>), dim3((unsigned)blocks), dim3(TG_THREADS), 0, st, a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) { set_hip_error(e); return PZL_EHIP; }
+    return PZL_OK;
+}
+
+// x in fragment order for the tiles of the list: one workgroup per (tile, token fragment), a wave
+// per k-block in turn; every lane moves the 16 bytes that the tile's gate/up stage will want in
+// its place (columns past the tile's last token repeat that token, as the kernel's own gather does).
+__global__ void __launch_bounds__(256)
+gather_x_kernel(const uint16_t *__restrict__ x, int32_t d, const int32_t *__restrict__ slot_tok,
+                const int32_t *__restrict__ tile_q, const int32_t *__restrict__ tile_slot0,
+                const int32_t *__restrict__ tile_n, const int32_t *__restrict__ n_tiles, uint16_t *__restrict__ x_frag)
+{
+    const int mt = blockIdx.x / TG_FRAGS, fr = blockIdx.x % TG_FRAGS;
+    if (mt >= *n_tiles) return;
+    if (tile_q[mt] & TILE_FUSED_FLAG) return;                  // such tiles read x itself
+    const int n = tile_n[mt], slot0 = tile_slot0[mt];
+    const int nfrag = 2 * ((((n + 15) >> 4) + 1) >> 1);        // fragments come in pairs
+    if (fr >= nfrag) return;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int row = slot_tok[slot0 + min(fr * 16 + (lane & 15), n - 1)];
+    const u32x4 *src = (const u32x4 *)(x + (int64_t)row * d + (lane >> 4) * 8);
+    u32x4 *dst = (u32x4 *)(x_frag + ((int64_t)tg_frag_row(slot0, mt) + 16 * fr) * d) + lane;
+    for (int kb = wave; kb < d / TILE_COLS; kb += 4) dst[kb * 64] = src[kb * (TILE_COLS / 8)];
+}
+
+int launch_gather_x(const uint16_t *x, int32_t d, const int32_t *slot_tok, const int32_t *tile_q, const int32_t *tile_slot0,
+                    const int32_t *tile_n, const int32_t *n_tiles, int32_t max_mtiles, uint16_t *x_frag, hipStream_t st)
+{
+    if (max_mtiles <= 0) return PZL_OK;
+    if (d % TILE_COLS) return PZL_EINVAL;
+    hipLaunchKernelGGL(gather_x_kernel, dim3((unsigned)max_mtiles * TG_FRAGS), dim3(256), 0, st, x, d, slot_tok, tile_q, tile_slot0,
+                       tile_n, n_tiles, x_frag);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) { set_hip_error(e); return PZL_EHIP; }
     return PZL_OK;

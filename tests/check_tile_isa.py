@@ -284,7 +284,7 @@ def check(asm_text):
     # loop exits: the hand-written "wait for everything" must be the first thing in its block
     n_exits = 0
     for i, l in enumerate(lines):
-        if "s_waitcnt vmcnt(0)" in l and "ASMSTART" in lines[i - 1]:
+        if "s_waitcnt vmcnt(0)" in l and "end of K loop" in l and "ASMSTART" in lines[i - 1]:   # the kernel marks this wait with a comment
             j = i - 2
             seg = []
             while j > 0 and not lines[j].startswith(".LBB") and not re.search(r"s_c?branch|s_barrier", lines[j]):
@@ -292,8 +292,6 @@ def check(asm_text):
                 if t and not t.startswith(";"):
                     seg.append(t)
                 j -= 1
-            if "s_barrier" in lines[j]:
-                continue                                      # the prologue's waits, not a loop exit
             n_exits += 1
             vec = [x for x in seg if re.match(r"(v_|global_|ds_|scratch_|buffer_|flat_)", x)]
             if vec:

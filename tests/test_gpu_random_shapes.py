@@ -83,3 +83,20 @@ def test_forced_plans(oracle, shape):
             ok, worst = tolerance_ok(case.gpu(x, ids, w), y64)
             assert ok, (T, force, worst)
     case.layer.pzl_layer_force_plan(-1, -1, -1)
+
+
+@pytest.mark.parametrize("T", [420, 1100])
+def test_wide_experts_gathered_x(oracle, T):
+    """Experts of 8192 features or more, in a batch that the tiled kernels take: x is gathered into
+    fragment order in front of the gate/up stage (and H is kept in it), tiles of one to four token
+    fragments short of full included; same bar."""
+    from paper_2511_04805_amd import binding
+    binding.load()
+    cfg = synth.LayerConfig("wide8192", 4, 64, 8192, 2, (T,), seed=9200)
+    case = Case(cfg, oracle, binding, emap_mode="random")
+    x = synth.tokens(cfg, T)
+    ids, w = synth.routing(cfg, T)
+    y64, _ = case.ref(x, ids, w)
+    ok, worst = tolerance_ok(case.gpu(x, ids, w), y64)
+    print("   T=%d worst err / bound = %.3f" % (T, worst), flush=True)
+    assert ok, (T, worst)
