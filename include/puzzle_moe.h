@@ -312,7 +312,8 @@ int pzl_moe_ffn(const pzl_layer *layer, const uint16_t *x, const int32_t *topk_i
  * device is looked up once, in pzl_layer_create).  The call allocates and frees nothing.
  *   - A batch whose workspace (pzl_moe_ffn_workspace_bytes(layer, T, k)) exceeds the array is
  *     refused with PZL_ENOSPC and nothing is launched.  32 MiB hold a Mixtral-8x7B-shaped layer
- *     up to about 100 tokens at top-2; larger batches take pzl_moe_ffn with a caller workspace.
+ *     up to 76 tokens at top-2 (the batches that the streaming kernels serve alone); larger
+ *     batches take pzl_moe_ffn with a caller workspace.
  *   - All calls on one GPU share that GPU's array, on whatever layer and stream: calls that
  *     overlap in time on one GPU race.  Calls queued on one stream are fine.  The array keeps the
  *     previous call's contents; the call clears what it needs cleared inside its kernels.

@@ -757,7 +757,7 @@ gather_x_kernel(const uint16_t *__restrict__ x, int32_t d, const int32_t *__rest
                 const int32_t *__restrict__ tile_q, const int32_t *__restrict__ tile_slot0,
                 const int32_t *__restrict__ tile_n, const int32_t *__restrict__ n_tiles, uint16_t *__restrict__ x_frag)
 {
-    const int mt = blockIdx.x / TG_FRAGS, fr = blockIdx.x % TG_FRAGS;
+    const int mt = blockIdx.x / TG_FRAGS, fr = blockIdx.x % TG_FRAGS;   // blockIdx.y: a quarter of the k-blocks (more loads in flight per compute unit)
     if (mt >= *n_tiles) return;
     if (tile_q[mt] & TILE_FUSED_FLAG) return;                  // such tiles read x itself
     const int n = tile_n[mt], slot0 = tile_slot0[mt];
@@ -767,7 +767,9 @@ gather_x_kernel(const uint16_t *__restrict__ x, int32_t d, const int32_t *__rest
     const int row = slot_tok[slot0 + min(fr * 16 + (lane & 15), n - 1)];
     const u32x4 *src = (const u32x4 *)(x + (int64_t)row * d + (lane >> 4) * 8);
     u32x4 *dst = (u32x4 *)(x_frag + ((int64_t)tg_frag_row(slot0, mt) + 16 * fr) * d) + lane;
-    for (int kb = wave; kb < d / TILE_COLS; kb += 4) dst[kb * 64] = src[kb * (TILE_COLS / 8)];
+    const int kbs = d / TILE_COLS, per = (kbs + (int)gridDim.y - 1) / (int)gridDim.y;
+    const int kb_end = min(kbs, ((int)blockIdx.y + 1) * per);
+    for (int kb = (int)blockIdx.y * per + wave; kb < kb_end; kb += 4) dst[kb * 64] = src[kb * (TILE_COLS / 8)];
 }
 
 int launch_gather_x(const uint16_t *x, int32_t d, const int32_t *slot_tok, const int32_t *tile_q, const int32_t *tile_slot0,
@@ -775,7 +777,7 @@ int launch_gather_x(const uint16_t *x, int32_t d, const int32_t *slot_tok, const
 {
     if (max_mtiles <= 0) return PZL_OK;
     if (d % TILE_COLS) return PZL_EINVAL;
-    hipLaunchKernelGGL(gather_x_kernel, dim3((unsigned)max_mtiles * TG_FRAGS), dim3(256), 0, st, x, d, slot_tok, tile_q, tile_slot0,
+    hipLaunchKernelGGL(gather_x_kernel, dim3((unsigned)max_mtiles * TG_FRAGS, 4), dim3(256), 0, st, x, d, slot_tok, tile_q, tile_slot0,
                        tile_n, n_tiles, x_frag);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) { set_hip_error(e); return PZL_EHIP; }
