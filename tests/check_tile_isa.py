@@ -166,7 +166,7 @@ def _k_loops(lines, labels):
                 header_of[name] = ".L" + m.group(1)
     extent = {}
     for i, l in enumerate(lines):
-        m = re.match(r"\s+s_cbranch_\w+\s+(\.LBB\d+_\d+)", l)
+        m = re.match(r"\s+s_(?:cbranch_\w+|branch)\s+(\.LBB\d+_\d+)", l)   # (the back edge may be an unconditional branch to a latch block placed in front of the header)
         if not m or labels.get(m.group(1), i) >= i or m.group(1) not in header_of:
             continue
         h = header_of[m.group(1)]
