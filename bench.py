@@ -367,6 +367,8 @@ def main():
     ap.add_argument("--no-prefill", action="store_true")
     ap.add_argument("--no-quant", action="store_true")
     ap.add_argument("--no-other-shapes", action="store_true")
+    ap.add_argument("--shapes", type=str, default="qwen15_moe,deepseek_moe", metavar="NAME,NAME",
+                    help="the other layer shapes to time (a profiler run may want one alone)")
     ap.add_argument("--no-context", action="store_true", help="skip the board-power readings and the vendor GEMM of the prefill shape")
     ap.add_argument("--plan-study", type=str, default="", metavar="SHAPE,SHAPE,...",
                     help="only time the library's launch plan against forced alternatives on these synth.CONFIGS shapes")
@@ -515,7 +517,7 @@ def main():
         del layer
         torch.cuda.empty_cache()
         out["other_shapes"] = {}
-        for name in ("qwen15_moe", "deepseek_moe"):
+        for name in [n for n in args.shapes.split(",") if n]:
             c2 = synth.CONFIGS[name]
             T2 = c2.n_tokens[0]
             l2, emap2 = build_layer(c2)
