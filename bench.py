@@ -27,8 +27,8 @@ HBM_PEAK_GBS = 8000.0
 # Bytes between L2 and memory per launch of the gate/up kernels (streaming at T = 64, tiled at
 # T = 4096), from rocprofv3 --pmc runs (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, calibrated on the
 # copy below) summarised under profiles/.  Counters cannot be read inside this process.
-MEASURED_TRAFFIC_BYTES = {"mixtral_decode_T64": 950.9e6, "mixtral_decode_T64_quantised": 429.7e6,
-                          "mixtral_prefill_T4096": 3.209e9}
+MEASURED_TRAFFIC_BYTES = {"mixtral_decode_T64": 951.0e6, "mixtral_decode_T64_quantised": 429.2e6,
+                          "mixtral_prefill_T4096": 3.339e9}
 TRAFFIC_FROM = ("separate rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script, summarised under profiles/ "
                 "(stream_kernels_mixtral_decode_T64.md, tile_kernels_mixtral_prefill_T4096.md); not read in this process")
 W3 = (synth.GATE, synth.UP, synth.DOWN)
@@ -157,6 +157,26 @@ def time_plain(hip, layer, xt, idt, wt, steps, warmup):
         torch.cuda.synchronize()
         regions.append(hip.elapsed_ms(t0, t1) / steps)
     return float(np.median(regions)), regions, y
+
+
+def time_cold(hip, layer, xt, idt, wt, calls=15):
+    """One call at a time with the caches flushed in front of it: a 1 GiB fill (four times the
+    memory-side cache, far more than the L2s) goes through the same stream before every timed
+    call, the events bracket the call alone.  Returns the median ms of `calls` such calls."""
+    y = torch.empty(xt.shape[0], layer.d_model, dtype=torch.bfloat16, device="cuda")
+    flush = torch.empty(1 << 28, dtype=torch.int32, device="cuda")
+    stream = torch.cuda.current_stream().cuda_stream
+    t0, t1 = hip.event(), hip.event()
+    ms = []
+    for i in range(calls):
+        flush.fill_(i)
+        hip.record(t0, stream)
+        layer.pzl_moe_ffn(xt, idt, wt, y=y)
+        hip.record(t1, stream)
+        torch.cuda.synchronize()
+        ms.append(hip.elapsed_ms(t0, t1))
+    del flush
+    return float(np.median(ms))
 
 
 def time_router(hip, cfg, xt, steps=50, warmup=5):
@@ -452,6 +472,12 @@ def main():
     # the on-device router in front of the layer, on its own (not part of the timed step: ids and
     # weights are inputs of the path)
     out["router_ms"] = time_router(hip, cfg, xt)
+    if not args.no_context:
+        # the same step with the caches flushed in front of every call (context: the timed loop
+        # above does not flush, and the layer's 1.4 GB of packed words do not fit any cache anyway)
+        cold_ms = time_cold(hip, layer, xt, idt, wt)
+        out["cold_cache"] = {"ms_per_step": cold_ms, "tokens_per_s": T / (cold_ms * 1e-3),
+                             "flush": "1 GiB fill on the same stream before each timed call; median of 15 calls"}
     if not args.no_sweep:
         out["sweep"] = {t: {kk: v[kk] for kk in ("tokens_per_s", "ms_per_step", "touched_pairs", "gateup_GBs",
                                                   "down_GBs", "path_GBs", "path_hbm_frac")}
