@@ -70,6 +70,7 @@ constexpr int tg_ring_stages() { return tg_stage_units<STAGE, HALF, DENSE>() * 1
 #ifndef TG_QUARTER_LOADS
 #define TG_QUARTER_LOADS 1
 #endif
+constexpr int TG_ODD_MIN_CNT = 5;           // pairs of fragments from which a tile with an odd number of fragments has its own loop
 constexpr int TG_BLOCK_WGS = 32;            // workgroups an XCD runs side by side (32 compute units): one block of token tiles x row blocks
 
 // Activations in fragment order.  A tile's token operand is what its K loop reads most often from
@@ -190,7 +191,12 @@ typedef __attribute__((address_space(3))) void *tg_lds_ptr;
 // HALF: H is one plane of half precision (written by the gate/up stage with saturation; the down
 // stage then decodes its weights to half precision times 2, uses the f16 matrix instruction with
 // K steps of 64 like the gate/up stage, and halves its sums), instead of two bf16 planes.
-template <int STAGE, bool DENSE, bool ALLTOK, bool HALF, int POS, int CNT>
+// ODD: the tile's last fragment is padding (an odd number of fragments in use): it keeps its place
+// in the step's groups (LDS read, share of the decode and of the loads), so that the fragment
+// ring and the load counts are those of the even tile, but its matrix instructions are left out
+// and it has no accumulators: at the power cap a matrix instruction not issued is time won
+// (tiles of 17 fragments, Mixtral-shaped prefill: -3 % per launch).
+template <int STAGE, bool DENSE, bool ALLTOK, bool HALF, int POS, int CNT, bool ODD = false>
 __device__ __forceinline__ void tile_body(const TgArgs &a, const uint16_t *wa, const uint16_t *wb,
                                           int slot0, int n_tok, int n_tok1, int ntile, int ks, int mt,
                                           u32x4 *ring, int32_t *rowidx, int32_t *draw_ctr, int32_t *drawn)
@@ -202,6 +208,8 @@ __device__ __forceinline__ void tile_body(const TgArgs &a, const uint16_t *wa, c
     constexpr int PARTS = (STAGE == TSTAGE_DOWN && !HALF) ? 2 : 1;    // activation planes (hi, lo)
     constexpr int NF = (FUSED ? 4 : 2) * CNT;                // token fragments in use
     constexpr int NFH = FUSED ? NF / 2 : NF;                 // ... of which the first expert's
+    constexpr int NFR = NF - (ODD ? 1 : 0);                  // ... that hold tokens
+    static_assert(!ODD || !FUSED, "tiles that cover a pair come in whole pairs of fragments");
     static_assert(NF <= TG_FRAGS, "fragments");
     constexpr int RT = 2;                                    // row tiles per wave
     constexpr int XTOTAL = PARTS * NF * KBS;                 // activation fragments per stage
@@ -443,9 +451,11 @@ __device__ __forceinline__ void tile_body(const TgArgs &a, const uint16_t *wa, c
             if (g + RA < GROUPS) bq[(BASE + g + RA) % (RA + 1)] = frag_of(cur, g + RA);
             else if (DEEP)       bq[(BASE + g + RA) % (RA + 1)] = frag_of(nxt, g + RA - GROUPS);
             const int kbo = g / (NF * PARTS), i = (g % (NF * PARTS)) / PARTS;
+            if (i < NFR) {
 #pragma unroll
-            for (int j = 0; j < RT; ++j)
-                acc[j][i] = tg_mma<HALFW>((FUSED && i >= NFH) ? dc.a1[kbo][j] : dc.a[kbo][j], bq[(BASE + g) % (RA + 1)], acc[j][i]);
+                for (int j = 0; j < RT; ++j)
+                    acc[j][i] = tg_mma<HALFW>((FUSED && i >= NFH) ? dc.a1[kbo][j] : dc.a[kbo][j], bq[(BASE + g) % (RA + 1)], acc[j][i]);
+            }
 #pragma unroll
             for (int u = g * UNITS / GROUPS; u < (g + 1) * UNITS / GROUPS; ++u) decode_unit(raw_n, dn, u, step + 1);
             if (DEEP && g < XPT) fetch_x_one(step + LEAD, fill, g);
@@ -507,7 +517,7 @@ __device__ __forceinline__ void tile_body(const TgArgs &a, const uint16_t *wa, c
     const int col = lane & 15, rsub = (lane >> 4) * 4;
     bool sat = false;
 #pragma unroll
-    for (int i = 0; i < NF; ++i) {
+    for (int i = 0; i < NFR; ++i) {
         int within = i * 16 + col, slot;
         if (FUSED && i >= NFH) {
             within -= NFH * 16;
@@ -600,8 +610,13 @@ __device__ __forceinline__ bool tile_run(const TgArgs &a, int logical, int n_mt,
     n_tok1 = __builtin_amdgcn_readfirstlane(n_tok1);
     const uint16_t *wa = a.w_a[g];
     const uint16_t *wb = (STAGE == TSTAGE_GATEUP) ? a.w_b[g] : wa;
-    const int cnt = (((n_tok + 15) >> 4) + 1) >> 1;          // 1..9 pairs of token fragments
+    const int frags = (n_tok + 15) >> 4;
+    const int cnt = (frags + 1) >> 1;                        // 1..9 pairs of token fragments
+    // (an odd number of fragments has its own loop from TG_ODD_MIN_CNT pairs on: smaller tiles are
+    // not bound by their matrix instructions)
+    const bool odd = (frags & 1) && cnt >= TG_ODD_MIN_CNT;
 #define PZL_TILE(P, C) tile_body<STAGE, DENSE, ALLTOK, HALF, P, C>(a, wa, wb, slot0, n_tok, n_tok1, ntile, ks, mt, ring, rowidx, draw_ctr, drawn)
+#define PZL_TILE_ODD(P, C) tile_body<STAGE, DENSE, ALLTOK, HALF, P, C, true>(a, wa, wb, slot0, n_tok, n_tok1, ntile, ks, mt, ring, rowidx, draw_ctr, drawn)
     // tiles that cover a pair, in either launch form (60 experts top-4, even router, 1024 tokens,
     // persistent launches: 282 -> 261 us; a skewed router has few such pairs and loses nothing)
     if constexpr (!DENSE && !ALLTOK) {
@@ -623,8 +638,21 @@ __device__ __forceinline__ bool tile_run(const TgArgs &a, int logical, int n_mt,
         case 7: PZL_TILE(P, 7); break; case 8: PZL_TILE(P, 8); break;           \
         default: PZL_TILE(P, 9); break;                                         \
     }
-    if (DENSE || pos == 0) { PZL_TILE_CNT(0) } else { PZL_TILE_CNT(1) }
+#define PZL_TILE_CNT_ODD(P)                                                     \
+    switch (cnt) {                                                              \
+        case 5: PZL_TILE_ODD(P, 5); break; case 6: PZL_TILE_ODD(P, 6); break;   \
+        case 7: PZL_TILE_ODD(P, 7); break; case 8: PZL_TILE_ODD(P, 8); break;   \
+        default: PZL_TILE_ODD(P, 9); break;                                     \
+    }
+    static_assert(TG_ODD_MIN_CNT == 5, "the switch above lists the odd tiles from 5 pairs of fragments on");
+    if (odd) {
+        if (DENSE || pos == 0) { PZL_TILE_CNT_ODD(0) } else { PZL_TILE_CNT_ODD(1) }
+    } else {
+        if (DENSE || pos == 0) { PZL_TILE_CNT(0) } else { PZL_TILE_CNT(1) }
+    }
+#undef PZL_TILE_CNT_ODD
 #undef PZL_TILE_CNT
+#undef PZL_TILE_ODD
 #undef PZL_TILE
     return true;
 }

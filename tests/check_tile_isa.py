@@ -214,13 +214,14 @@ def loops_by_kernel(asm_text):
 
 def expected_loops(mangled):
     """K loops a tile_kernel<STAGE, DENSE, ALLTOK, PERSIST, HALF> instantiation must contain, from its
-    template arguments: one per (expert position, number of token-fragment pairs 1..9); dense
-    weights have one position only; kernels of packed pairs also hold the 3 sizes of the tile that
-    covers both experts of a pair."""
+    template arguments: one per (expert position, number of token-fragment pairs 1..9) and one more
+    per (position, 5..9 pairs the last fragment of which is padding); dense weights have one
+    position only; kernels of packed pairs also hold the 3 sizes of the tile that covers both
+    experts of a pair."""
     m = re.search(r"tile_kernelILi(\d)ELb(\d)ELb(\d)ELb(\d)ELb(\d)E", mangled)
     assert m, mangled
     dense = m.group(2) == "1"
-    return 9 if dense else 18 + 3
+    return 9 + 5 if dense else 2 * (9 + 5) + 3
 
 
 def check(asm_text):
