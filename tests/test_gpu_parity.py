@@ -288,6 +288,53 @@ def test_tiled_path_pair_tiles(wide_case, counts):
     assert ok, worst
 
 
+def _ids_with_counts(cfg, counts, seed):
+    """A (T, 2) id table in which expert e appears exactly counts[e] times (a token may name an
+    expert twice; an ignored id pads an odd total)."""
+    flat = np.concatenate([np.full(c, e, dtype=np.int32) for e, c in enumerate(counts)])
+    if flat.size % 2:
+        flat = np.concatenate([flat, np.array([-1], dtype=np.int32)])
+    np.random.RandomState(seed).shuffle(flat)
+    return flat.reshape(flat.size // 2, 2)
+
+
+def _check_counts(case, counts, label):
+    cfg = case.cfg
+    ids = _ids_with_counts(cfg, counts, sum(counts))
+    T = ids.shape[0]
+    x = synth.tokens(cfg, T)
+    _, w = synth.routing(cfg, T)
+    y = case.gpu(x, ids, w)
+    y64, _ = case.ref(x, np.where(ids < 0, 0, ids).astype(np.int32), np.where(ids < 0, 0.0, w).astype(np.float32))
+    ok, worst = tolerance_ok(y, y64)
+    say("  %s %s: worst err / bound = %.3f" % (label, counts, worst))
+    assert ok, worst
+
+
+@pytest.mark.parametrize("counts", [(140, 170, 200, 270), (272, 129, 233, 144), (257, 161, 193, 225), (280, 150, 190, 0)])
+def test_tiled_path_odd_fragment_counts(tiled_case, counts):
+    """Tiles of 9, 11, 13, 15 and 17 token fragments have loops of their own that leave out the
+    matrix instructions of the padding fragment: expert loads set by hand so that every one of them
+    (and, last case, their even neighbours 18, 10, 12) runs in both stages, first and last token of
+    the last fragment included."""
+    frags = sorted((c + 15) // 16 for c in counts if c)
+    assert counts[3] == 0 or all(f % 2 == 1 and f >= 9 for f in frags), frags
+    _check_counts(tiled_case, counts, "odd tiles")
+
+
+def test_persistent_launches_odd_fragment_counts(oracle, binding):
+    """The same loops in the persistent launch form (32 routing keys or more, about one tile per
+    expert): a few experts with 129-272 tokens among many small ones."""
+    cfg = synth.LayerConfig("many_odd", 32, 128, 256, 2, (64,), seed=73)
+    case = Case(cfg, oracle, binding, emap_mode="random")
+    counts = [3] * 32
+    for e, c in ((1, 136), (6, 175), (7, 201), (12, 239), (20, 262), (21, 272), (30, 130), (31, 96)):
+        counts[e] = c
+    plan = binding.pzl_moe_ffn_plan(cfg.n_experts, cfg.d_model, cfg.d_ffn, (sum(counts) + 1) // 2, 2)
+    assert plan["hybrid"] and plan["persistent"], plan
+    _check_counts(case, tuple(counts), "persistent odd tiles")
+
+
 def test_tiled_path_skewed_routing(tiled_case):
     """One hot expert (several full token tiles), one expert with a single token, one with none."""
     cfg = TILED
