@@ -322,6 +322,14 @@ def test_tiled_path_odd_fragment_counts(tiled_case, counts):
     _check_counts(tiled_case, counts, "odd tiles")
 
 
+def test_odd_fragment_counts_two_plane_h_and_unmerged_experts(oracle, binding):
+    """The same for the two-plane form of H (two groups per fragment and K step in the down stage)
+    and for routed experts kept unmerged (dense weights, identity decode)."""
+    cfg = synth.LayerConfig("odd_wide", 6, 256, 384, 2, (600,), shared_d_ffn=(128,), seed=77, n_unmerged=2)
+    case = Case(cfg, oracle, binding, emap_mode="random", wide_h=True)
+    _check_counts(case, (140, 170, 200, 270, 233, 129), "odd tiles, wide H, unmerged")
+
+
 def test_persistent_launches_odd_fragment_counts(oracle, binding):
     """The same loops in the persistent launch form (32 routing keys or more, about one tile per
     expert): a few experts with 129-272 tokens among many small ones."""
