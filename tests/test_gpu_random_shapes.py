@@ -85,11 +85,11 @@ def test_forced_plans(oracle, shape):
     case.layer.pzl_layer_force_plan(-1, -1, -1)
 
 
-@pytest.mark.parametrize("T", [420, 1100])
+@pytest.mark.parametrize("T", [420, 1040, 1100])
 def test_wide_experts_gathered_x(oracle, T):
     """Experts of 8192 features or more, in a batch that the tiled kernels take: x is gathered into
     fragment order in front of the gate/up stage (and H is kept in it), tiles of one to four token
-    fragments short of full included; same bar."""
+    fragments short of full included, tiles of 17 fragments among them (1040 tokens); same bar."""
     from paper_2511_04805_amd import binding
     binding.load()
     cfg = synth.LayerConfig("wide8192", 4, 64, 8192, 2, (T,), seed=9200)
